@@ -1,0 +1,158 @@
+"""Seeded synthetic workloads: layer tables and input generators.
+
+This module holds none of the method's arithmetic.  It names the layer shapes
+(the thirteen depthwise layers of MobileNet-v1 as listed in the paper's Table III,
+and Xception-style stride-1 layers), and draws x, w and dy from a seeded
+generator.  Both the GPU tests and the CPU oracle consume the arrays it returns.
+
+Recipe: x, dy ~ N(0,1); w ~ N(0, variance 1/K^2) (sigma = 1/K, so outputs have
+about unit variance); float32; drawn in NCHW logical order and permuted for NHWC
+so both layouts see the same values; for the bf16 workloads every array is then
+rounded to the nearest bf16 (ties to even) and kept as float32 holding exactly
+that value.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, replace
+from typing import Dict, List, Tuple
+
+import numpy as np
+
+NCHW = 0
+NHWC = 1
+F32 = 0
+BF16 = 1
+
+
+@dataclass(frozen=True)
+class Layer:
+    name: str
+    C: int
+    H: int
+    W: int
+    K: int = 3
+    stride: int = 1
+    pad: int = 1
+    mult: int = 1
+
+    @property
+    def O(self) -> int:
+        return self.C * self.mult
+
+    @property
+    def Ho(self) -> int:
+        return (self.H + 2 * self.pad - self.K) // self.stride + 1
+
+    @property
+    def Wo(self) -> int:
+        return (self.W + 2 * self.pad - self.K) // self.stride + 1
+
+    def x_elems(self, N: int) -> int:
+        return N * self.C * self.H * self.W
+
+    def y_elems(self, N: int) -> int:
+        return N * self.O * self.Ho * self.Wo
+
+    def pass_bytes(self, N: int, elem_bytes: int) -> int:
+        """Algorithmic bytes one pass must move: every input element and every output element once."""
+        return (self.x_elems(N) + self.y_elems(N)) * elem_bytes
+
+    def pass_flops(self, N: int) -> int:
+        return 2 * self.K * self.K * self.y_elems(N)
+
+
+def _mb(i, C, H, s):
+    return Layer("mobilenet_dw%02d_c%d_h%d_s%d" % (i, C, H, s), C, H, H, 3, s, 1, 1)
+
+
+# The thirteen depthwise layers of MobileNet-v1 (224 input, width 1.0): Table III's shapes.
+MOBILENET_V1: Tuple[Layer, ...] = (
+    _mb(1, 32, 112, 1), _mb(2, 64, 112, 2), _mb(3, 128, 56, 1), _mb(4, 128, 56, 2),
+    _mb(5, 256, 28, 1), _mb(6, 256, 28, 2),
+    _mb(7, 512, 14, 1), _mb(8, 512, 14, 1), _mb(9, 512, 14, 1), _mb(10, 512, 14, 1), _mb(11, 512, 14, 1),
+    _mb(12, 512, 14, 2), _mb(13, 1024, 7, 1),
+)
+
+
+def _xc(name, C, H, mult=1):
+    return Layer("xception_%s_c%d_h%d_m%d" % (name, C, H, mult), C, H, H, 3, 1, 1, mult)
+
+
+# Xception-style stride-1 layers; `repeat` says how often the layer occurs in the stack.
+XCEPTION: Tuple[Tuple[Layer, int], ...] = (
+    (_xc("entry1", 128, 147), 1), (_xc("entry2", 256, 74), 1), (_xc("entry3", 728, 37), 1),
+    (_xc("middle", 728, 19), 24),
+    (_xc("exit1", 1024, 19), 1), (_xc("exit2", 1536, 10), 1), (_xc("exit3", 2048, 10), 1),
+    (_xc("mult2", 256, 56, 2), 1),
+)
+
+
+def mobilenet_5x5() -> Tuple[Layer, ...]:
+    """The nine stride-1 MobileNet layers with a 5x5 pad-2 filter."""
+    return tuple(replace(l, name=l.name + "_k5", K=5, pad=2) for l in MOBILENET_V1 if l.stride == 1)
+
+
+def config(index: int) -> Dict:
+    """The five benchmark configurations, as dicts: N, layouts, dtype, layers [(Layer, repeat)]."""
+    if index == 0:
+        return dict(name="single_3x3_n8_c32_h112_f32_nchw", N=8, layouts=(NCHW,), dtype=F32,
+                    layers=[(Layer("single_c32_h112", 32, 112, 112), 1)])
+    if index == 1:
+        return dict(name="mobilenet_v1_dw_b64_f32_nhwc", N=64, layouts=(NHWC,), dtype=F32,
+                    layers=[(l, 1) for l in MOBILENET_V1])
+    if index == 2:
+        return dict(name="mobilenet_v1_dw_b128_f32_nchw_nhwc", N=128, layouts=(NCHW, NHWC), dtype=F32,
+                    layers=[(l, 1) for l in MOBILENET_V1])
+    if index == 3:
+        return dict(name="xception_dw_b32_f32_nhwc", N=32, layouts=(NHWC,), dtype=F32,
+                    layers=list(XCEPTION))
+    if index == 4:
+        return dict(name="mobilenet_v1_dw_b256_bf16", N=256, layouts=(NHWC, NCHW), dtype=BF16,
+                    layers=[(l, 1) for l in MOBILENET_V1] + [(l, 1) for l in mobilenet_5x5()])
+    raise ValueError("config index must be 0..4")
+
+
+def round_to_bf16(a: np.ndarray) -> np.ndarray:
+    """Round float32 values to the nearest bf16 (ties to even); result is float32 holding that value."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    bits = a.view(np.uint32).astype(np.uint64)
+    lsb = (bits >> 16) & 1
+    rounded = ((bits + 0x7FFF + lsb) >> 16) << 16
+    return rounded.astype(np.uint32).view(np.float32).reshape(a.shape)
+
+
+def bf16_bits(a: np.ndarray) -> np.ndarray:
+    """The upper 16 bits of float32 values that already hold exact bf16 values."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return (a.view(np.uint32) >> 16).astype(np.uint16).reshape(a.shape)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    b = np.ascontiguousarray(b, dtype=np.uint16)
+    return (b.astype(np.uint32) << 16).view(np.float32).reshape(b.shape)
+
+
+def make_inputs(layer: Layer, N: int, layout: int, dtype: int, seed: int):
+    """Return (x, w, dy) as float32 numpy arrays in `layout`.
+
+    x  [N,C,H,W] / [N,H,W,C];  dy [N,O,Ho,Wo] / [N,Ho,Wo,O];  w [O,K,K] / [K,K,O].
+    """
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((N, layer.C, layer.H, layer.W), dtype=np.float32)
+    w = rng.standard_normal((layer.O, layer.K, layer.K), dtype=np.float32) / np.float32(layer.K)
+    dy = rng.standard_normal((N, layer.O, layer.Ho, layer.Wo), dtype=np.float32)
+    if dtype == BF16:
+        x, w, dy = round_to_bf16(x), round_to_bf16(w), round_to_bf16(dy)
+    if layout == NHWC:
+        x = np.ascontiguousarray(x.transpose(0, 2, 3, 1))
+        dy = np.ascontiguousarray(dy.transpose(0, 2, 3, 1))
+        w = np.ascontiguousarray(w.transpose(1, 2, 0))
+    return x, w, dy
+
+
+def to_layout(a_nchw: np.ndarray, layout: int) -> np.ndarray:
+    return a_nchw if layout == NCHW else np.ascontiguousarray(a_nchw.transpose(0, 2, 3, 1))
+
+
+def w_to_layout(w_okk: np.ndarray, layout: int) -> np.ndarray:
+    return w_okk if layout == NCHW else np.ascontiguousarray(w_okk.transpose(1, 2, 0))
