@@ -1,0 +1,197 @@
+#!/usr/bin/env python3
+"""Benchmark: fwd + bwd_data + bwd_filter of the MobileNet-v1 depthwise stack (Table III's thirteen
+layers), batch 128, fp32, once in NCHW and once in NHWC, on one MI355X.
+
+A step is one pass of the whole hot path over the whole workload: for each layout, for each of
+the 13 layers, dwconv_fwd, dwconv_bwd_data, dwconv_bwd_filter (stage 1 + stage 2) through the
+C ABI.  Every layer has its own device buffers (about 10 GB in all, far beyond the caches), so
+each launch reads its operands from HBM.  Inputs are synthetic (seeded normal draws) and already
+resident in HBM when the timed region starts.
+
+Prints ONE JSON line.  `value` is algorithmic HBM bytes per second: for every pass
+(|x| + |y|) * 4 bytes, divided by the wall time of the timed steps.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+PEAK_HBM_GBS = 8000.0
+METRIC = "ms and HBM GB/s (% of peak) per fwd+bwd of MobileNet-v1 dw stack, batch 128"
+PASS_NAMES = ("fwd", "bwd_data", "bwd_filter")
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="workload index 0..4 (default 2: the headline one)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true", help="skip the per-launch HIP-event pass")
+    ap.add_argument("--report", action="store_true", help="print a per-layer table to stderr")
+    return ap.parse_args()
+
+
+def build_ops(dw, wl, cfg, torch):
+    """Allocate per-layer buffers and return the list of launches that make one step."""
+    ops = []
+    esz = 4 if cfg["dtype"] == wl.F32 else 2
+    for layout in cfg["layouts"]:
+        for li, (layer, repeat) in enumerate(cfg["layers"]):
+            x, w, dy = wl.make_inputs_device(layer, cfg["N"], layout, cfg["dtype"], seed=1000 * 7 + li)
+            d = dw.desc(cfg["N"], layer.C, layer.H, layer.W, layer.K, layer.stride, layer.pad, layer.mult,
+                        layout, cfg["dtype"])
+            y = torch.empty_like(dy); dx = torch.empty_like(x)
+            dwt = torch.empty(w.shape, device="cuda", dtype=torch.float32)
+            ws = torch.empty(max(dw.bwd_filter_workspace_bytes(d), 16), device="cuda", dtype=torch.uint8)
+            nbytes = layer.pass_bytes(cfg["N"], esz)
+            common = dict(layer=layer.name, li=li, layout="NCHW" if layout == wl.NCHW else "NHWC",
+                          bytes=nbytes, repeat=repeat, stride=layer.stride, H=layer.H)
+            ops.append(dict(common, which=0, variant=dw.variant_name(d, 0),
+                            run=(lambda d=d, x=x, w=w, y=y: dw.fwd(d, x, w, y))))
+            ops.append(dict(common, which=1, variant=dw.variant_name(d, 1),
+                            run=(lambda d=d, dy=dy, w=w, dx=dx: dw.bwd_data(d, dy, w, dx))))
+            ops.append(dict(common, which=2, variant=dw.variant_name(d, 2),
+                            run=(lambda d=d, x=x, dy=dy, dwt=dwt, ws=ws: dw.bwd_filter(d, x, dy, dwt, ws))))
+    return ops
+
+
+def run_step(ops):
+    for op in ops:
+        for _ in range(op["repeat"]):
+            op["run"]()
+
+
+def time_kernels(ops, steps, torch):
+    """Per-launch durations with HIP events on the launch stream, in the same cold-cache order as
+    the timed steps.  Returns ms per op (average over steps)."""
+    acc = [0.0] * len(ops)
+    for _ in range(steps):
+        evs = []
+        for op in ops:
+            a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
+            a.record(); op["run"](); b.record()
+            evs.append((a, b))
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(evs):
+            acc[i] += a.elapsed_time(b)
+    return [t / steps for t in acc]
+
+
+def cpu_baseline(wl, cfg):
+    """The CPU oracle, as it stands, on a batch-reduced sample of the same workload."""
+    import numpy as np
+    import oracle
+    cores = min(oracle.threads_available(), os.cpu_count() or 1)
+    Ns = 16
+    layout = cfg["layouts"][-1]
+    total_bytes, total_s = 0, 0.0
+    esz = 4 if cfg["dtype"] == wl.F32 else 2
+    for li, (layer, repeat) in enumerate(cfg["layers"]):
+        x, w, dy = wl.make_inputs(layer, Ns, layout, cfg["dtype"], seed=li)
+        x64, w64, dy64 = x.astype(np.float64), w.astype(np.float64), dy.astype(np.float64)
+        kw = dict(K=layer.K, stride=layer.stride, pad=layer.pad, mult=layer.mult, layout=layout, nthreads=cores)
+        t0 = time.perf_counter()
+        oracle.fwd(x64, w64, **kw)
+        oracle.bwd_data(dy64, w64, x_shape=x64.shape, **kw)
+        oracle.bwd_filter(x64, dy64, **kw)
+        total_s += (time.perf_counter() - t0) * repeat
+        total_bytes += 3 * layer.pass_bytes(Ns, esz) * repeat
+    return dict(value=total_bytes / total_s / 1e9, unit="GB/s", cores=cores, kind="oracle",
+                sample="all layers of the workload, all three passes, batch reduced to %d, %s, fp64 loop nests, "
+                       "%d OpenMP threads; algorithmic bytes counted at the workload's element size" %
+                       (Ns, "NCHW" if layout == wl.NCHW else "NHWC", cores),
+                seconds=total_s)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus %d is not supported (no collectives, no "
+              "sharding code exists here). Run with --gpus 1." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_1803_09926_amd as dw
+    from paper_1803_09926_amd import workloads as wl
+    dw.load()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    cfg = wl.config(args.config)
+    ops = build_ops(dw, wl, cfg, torch)
+    step_bytes = sum(op["bytes"] * op["repeat"] for op in ops)
+
+    for _ in range(args.warmup):
+        run_step(ops)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run_step(ops)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    gbs = step_bytes / (dt / args.steps) / 1e9
+
+    out = {
+        "metric": METRIC, "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32" if cfg["dtype"] == wl.F32 else "bf16", "data": "synthetic",
+        "config": {"workload": cfg["name"], "batch": cfg["N"],
+                   "layouts": ["NCHW" if l == wl.NCHW else "NHWC" for l in cfg["layouts"]],
+                   "layers": len(cfg["layers"]), "passes": "fwd+bwd_data+bwd_filter",
+                   "step": "one fwd+bwd of the stack in every listed layout"},
+        "pct_of_peak_hbm": round(100.0 * gbs / PEAK_HBM_GBS, 2),
+        "algorithmic_GB_per_step": round(step_bytes / 1e9, 4),
+    }
+
+    if not args.no_kernel_timing:
+        kms = time_kernels(ops, max(3, min(args.steps, 10)), torch)
+        per_layout = {}
+        by_variant = {}
+        for op, ms in zip(ops, kms):
+            per_layout.setdefault(op["layout"], {"ms": 0.0, "bytes": 0, "tail_ms": 0.0, "stride2_ms": 0.0,
+                                                 "fwd_ms": 0.0, "bwd_data_ms": 0.0, "bwd_filter_ms": 0.0})
+            pl = per_layout[op["layout"]]
+            pl["ms"] += ms * op["repeat"]; pl["bytes"] += op["bytes"] * op["repeat"]
+            pl[PASS_NAMES[op["which"]] + "_ms"] += ms * op["repeat"]
+            if op["H"] <= 14: pl["tail_ms"] += ms * op["repeat"]
+            if op["stride"] == 2: pl["stride2_ms"] += ms * op["repeat"]
+            key = PASS_NAMES[op["which"]] + ":" + op["variant"]
+            v = by_variant.setdefault(key, {"ms": 0.0, "bytes": 0, "launches": 0})
+            v["ms"] += ms * op["repeat"]; v["bytes"] += op["bytes"] * op["repeat"]; v["launches"] += op["repeat"]
+        out["kernel_ms_per_stack"] = {k: {kk: round(vv, 4) for kk, vv in v.items() if kk != "bytes"} |
+                                      {"GBps": round(v["bytes"] / v["ms"] / 1e6, 1)} for k, v in per_layout.items()}
+        dom_key = max(by_variant, key=lambda k: by_variant[k]["ms"])
+        dom = by_variant[dom_key]
+        achieved = dom["bytes"] / dom["ms"] / 1e6   # GB/s
+        out["roofline"] = {"bound": "hbm", "kernel": dom_key, "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
+                           "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None,
+                           "launches_per_step": dom["launches"],
+                           "avg_launch_ms": round(dom["ms"] / dom["launches"], 5),
+                           "algorithmic_bytes_per_launch": int(dom["bytes"] / dom["launches"])}
+        if args.report:
+            print("%-34s %-5s %-10s %-28s %9s %9s %7s" % ("layer", "lay", "pass", "variant", "ms", "GB/s", "%peak"),
+                  file=sys.stderr)
+            for op, ms in zip(ops, kms):
+                g = op["bytes"] / ms / 1e6
+                print("%-34s %-5s %-10s %-28s %9.4f %9.1f %7.2f" % (op["layer"], op["layout"], PASS_NAMES[op["which"]],
+                      op["variant"], ms, g, 100 * g / PEAK_HBM_GBS), file=sys.stderr)
+            for k, v in sorted(by_variant.items(), key=lambda kv: -kv[1]["ms"]):
+                print("variant %-44s launches %3d  ms %9.4f  GB/s %9.1f" % (k, v["launches"], v["ms"],
+                      v["bytes"] / v["ms"] / 1e6), file=sys.stderr)
+            out["per_op"] = [[op["layer"], op["layout"], PASS_NAMES[op["which"]], op["variant"], round(ms, 4)]
+                             for op, ms in zip(ops, kms)]
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, cfg)
+        out["cpu_baseline"]["value"] = round(out["cpu_baseline"]["value"], 3)
+        out["cpu_baseline"]["seconds"] = round(out["cpu_baseline"]["seconds"], 2)
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,143 @@
+// Shared device-side helpers for the gfx950 depthwise-convolution kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dwc {
+
+// Problem geometry handed to every kernel by value.
+struct Geom {
+    int N, C, H, W;   // input dims
+    int K, s, p, m;   // filter size, stride, pad, channel multiplier
+    int O, Ho, Wo;    // O = C*m, output spatial dims
+};
+
+typedef uint16_t bf16_t;  // raw bf16 bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// Round to nearest, ties to even; NaN stays NaN (quiet bit forced).
+__device__ __forceinline__ bf16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float ldf(const float *p) { return *p; }
+__device__ __forceinline__ float ldf(const bf16_t *p) { return bf16_to_f32(*p); }
+__device__ __forceinline__ void stf(float *p, float v) { *p = v; }
+__device__ __forceinline__ void stf(bf16_t *p, float v) { *p = f32_to_bf16(v); }
+
+// ---- vector access: V consecutive elements of T as float[V] -----------------------------
+template <typename T, int V> struct Vec;
+
+template <> struct Vec<float, 4> {
+    static __device__ __forceinline__ void load(const float *p, float (&r)[4])
+    {
+        float4 v = *reinterpret_cast<const float4 *>(p);
+        r[0] = v.x; r[1] = v.y; r[2] = v.z; r[3] = v.w;
+    }
+    static __device__ __forceinline__ void store(float *p, const float (&r)[4])
+    {
+        *reinterpret_cast<float4 *>(p) = make_float4(r[0], r[1], r[2], r[3]);
+    }
+};
+template <> struct Vec<float, 2> {
+    static __device__ __forceinline__ void load(const float *p, float (&r)[2])
+    {
+        float2 v = *reinterpret_cast<const float2 *>(p);
+        r[0] = v.x; r[1] = v.y;
+    }
+    static __device__ __forceinline__ void store(float *p, const float (&r)[2])
+    {
+        *reinterpret_cast<float2 *>(p) = make_float2(r[0], r[1]);
+    }
+};
+template <> struct Vec<float, 1> {
+    static __device__ __forceinline__ void load(const float *p, float (&r)[1]) { r[0] = *p; }
+    static __device__ __forceinline__ void store(float *p, const float (&r)[1]) { *p = r[0]; }
+};
+template <> struct Vec<bf16_t, 8> {
+    static __device__ __forceinline__ void load(const bf16_t *p, float (&r)[8])
+    {
+        uint4 v = *reinterpret_cast<const uint4 *>(p);
+        r[0] = __uint_as_float(v.x << 16); r[1] = __uint_as_float(v.x & 0xffff0000u);
+        r[2] = __uint_as_float(v.y << 16); r[3] = __uint_as_float(v.y & 0xffff0000u);
+        r[4] = __uint_as_float(v.z << 16); r[5] = __uint_as_float(v.z & 0xffff0000u);
+        r[6] = __uint_as_float(v.w << 16); r[7] = __uint_as_float(v.w & 0xffff0000u);
+    }
+    static __device__ __forceinline__ void store(bf16_t *p, const float (&r)[8])
+    {
+        uint4 v;
+        v.x = (uint32_t)f32_to_bf16(r[0]) | ((uint32_t)f32_to_bf16(r[1]) << 16);
+        v.y = (uint32_t)f32_to_bf16(r[2]) | ((uint32_t)f32_to_bf16(r[3]) << 16);
+        v.z = (uint32_t)f32_to_bf16(r[4]) | ((uint32_t)f32_to_bf16(r[5]) << 16);
+        v.w = (uint32_t)f32_to_bf16(r[6]) | ((uint32_t)f32_to_bf16(r[7]) << 16);
+        *reinterpret_cast<uint4 *>(p) = v;
+    }
+};
+template <> struct Vec<bf16_t, 4> {
+    static __device__ __forceinline__ void load(const bf16_t *p, float (&r)[4])
+    {
+        uint2 v = *reinterpret_cast<const uint2 *>(p);
+        r[0] = __uint_as_float(v.x << 16); r[1] = __uint_as_float(v.x & 0xffff0000u);
+        r[2] = __uint_as_float(v.y << 16); r[3] = __uint_as_float(v.y & 0xffff0000u);
+    }
+    static __device__ __forceinline__ void store(bf16_t *p, const float (&r)[4])
+    {
+        uint2 v;
+        v.x = (uint32_t)f32_to_bf16(r[0]) | ((uint32_t)f32_to_bf16(r[1]) << 16);
+        v.y = (uint32_t)f32_to_bf16(r[2]) | ((uint32_t)f32_to_bf16(r[3]) << 16);
+        *reinterpret_cast<uint2 *>(p) = v;
+    }
+};
+template <> struct Vec<bf16_t, 2> {
+    static __device__ __forceinline__ void load(const bf16_t *p, float (&r)[2])
+    {
+        uint32_t v = *reinterpret_cast<const uint32_t *>(p);
+        r[0] = __uint_as_float(v << 16); r[1] = __uint_as_float(v & 0xffff0000u);
+    }
+    static __device__ __forceinline__ void store(bf16_t *p, const float (&r)[2])
+    {
+        *reinterpret_cast<uint32_t *>(p) = (uint32_t)f32_to_bf16(r[0]) | ((uint32_t)f32_to_bf16(r[1]) << 16);
+    }
+};
+template <> struct Vec<bf16_t, 1> {
+    static __device__ __forceinline__ void load(const bf16_t *p, float (&r)[1]) { r[0] = bf16_to_f32(*p); }
+    static __device__ __forceinline__ void store(bf16_t *p, const float (&r)[1]) { *p = f32_to_bf16(r[0]); }
+};
+
+// ---- fixed-order reductions -----------------------------------------------------------------
+// Butterfly sum over the 64 lanes of a wavefront; every lane ends with the same total and the
+// order of additions is fixed by the lane numbers, so the result is reproducible.
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// Butterfly over lanes whose numbers differ only in the bits at or above `lo_stride`
+// (lo_stride a power of two): sums lanes l, l^lo_stride, l^(2*lo_stride), ... up to 32.
+__device__ __forceinline__ float wave_sum_strided(float v, int lo_stride)
+{
+    for (int off = 32; off >= lo_stride; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// The dispatcher launches workgroups round-robin over the 8 XCDs (each with its own L2).
+// This maps the hardware block id to a logical one so that each XCD walks a contiguous range
+// of logical ids: blocks that share halo rows then share an L2 and run close in time.
+__device__ __forceinline__ unsigned xcd_remap(unsigned bid, unsigned nblocks)
+{
+    const unsigned X = 8;
+    unsigned per = nblocks / X, rem = nblocks % X;
+    unsigned xcd = bid % X, slot = bid / X;
+    // XCDs 0..rem-1 own per+1 logical ids, the rest own per.
+    unsigned base = xcd * per + (xcd < rem ? xcd : rem);
+    return base + slot;
+}
+
+}  // namespace dwc

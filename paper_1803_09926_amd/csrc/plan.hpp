@@ -1,0 +1,30 @@
+// Kernel-variant selection.  A Plan is computed on the host from the geometry alone, so the
+// workspace query and the launch always agree.
+#pragma once
+#include "kernels.hpp"
+
+namespace dwc {
+
+enum Variant {
+    V_GENERIC = 0,
+};
+
+struct Plan {
+    int variant;
+    int parts;         // bwd_filter: number of partial sums per dw element in the workspace
+    int a, b, c;       // variant-specific launch parameters
+    const char *name;
+};
+
+Plan plan_fwd(const Geom &g, int layout, int dtype);
+Plan plan_bwd_data(const Geom &g, int layout, int dtype);
+Plan plan_bwd_filter(const Geom &g, int layout, int dtype);
+
+hipError_t launch_fwd(const Plan &pl, const Geom &g, int layout, int dtype, const void *x, const void *w, void *y,
+                      hipStream_t st);
+hipError_t launch_bwd_data(const Plan &pl, const Geom &g, int layout, int dtype, const void *dy, const void *w,
+                           void *dx, hipStream_t st);
+hipError_t launch_bwd_filter(const Plan &pl, const Geom &g, int layout, int dtype, const void *x, const void *dy,
+                             float *ws, hipStream_t st);
+
+}  // namespace dwc

@@ -156,3 +156,22 @@ def to_layout(a_nchw: np.ndarray, layout: int) -> np.ndarray:
 
 def w_to_layout(w_okk: np.ndarray, layout: int) -> np.ndarray:
     return w_okk if layout == NCHW else np.ascontiguousarray(w_okk.transpose(1, 2, 0))
+
+
+def make_inputs_device(layer: Layer, N: int, layout: int, dtype: int, seed: int, device="cuda"):
+    """Same recipe as make_inputs, drawn on the device with torch's seeded generator (for the
+    full-size workloads, where host generation and the PCIe copy would dominate).  Returns torch
+    tensors x, w, dy in `layout`, float32 or bfloat16 storage.  The values differ from
+    make_inputs' (another generator); tests that use this copy what they sample back to the host."""
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(int(seed))
+    tdt = torch.float32 if dtype == F32 else torch.bfloat16
+    if layout == NCHW:
+        xs, ys, ws = (N, layer.C, layer.H, layer.W), (N, layer.O, layer.Ho, layer.Wo), (layer.O, layer.K, layer.K)
+    else:
+        xs, ys, ws = (N, layer.H, layer.W, layer.C), (N, layer.Ho, layer.Wo, layer.O), (layer.K, layer.K, layer.O)
+    x = torch.randn(xs, generator=gen, device=device, dtype=torch.float32).to(tdt)
+    w = (torch.randn(ws, generator=gen, device=device, dtype=torch.float32) / layer.K).to(tdt)
+    dy = torch.randn(ys, generator=gen, device=device, dtype=torch.float32).to(tdt)
+    return x, w, dy

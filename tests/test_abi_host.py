@@ -1,0 +1,112 @@
+"""Host-side checks of the C ABI: the library loads, exports every symbol the header declares,
+and every validation error is reported before any HIP call (so this runs with no GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_1803_09926_amd as dw
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "dwconv.h")
+
+OK, E_NULL, E_DIM, E_ENUM, E_WS, E_ALIGN, E_UNSUP, E_LAUNCH, E_LARGE = 0, -1, -2, -3, -4, -5, -6, -7, -8
+A, B, Cp, Dp = 0x1000, 0x2000, 0x3000, 0x4000   # fake aligned "device" addresses: never dereferenced on error paths
+
+
+def test_library_exports_every_declared_symbol():
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    declared = set(re.findall(r"\b(dwconv_[a-z_]+)\s*\(", text))
+    assert declared == set(dw.EXPORTS), declared ^ set(dw.EXPORTS)
+    lib = dw.load()
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_desc_struct_matches_header_field_order():
+    text = open(HEADER).read()
+    body = re.search(r"typedef struct dwconv_desc \{(.*?)\} dwconv_desc;", text, re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = []
+    for decl in re.findall(r"int32_t\s+([^;]+);", body):
+        fields += [f.strip() for f in decl.split(",")]
+    assert fields == [f[0] for f in dw.Desc._fields_]
+    assert ctypes.sizeof(dw.Desc) == 4 * len(fields)
+
+
+def test_out_dims_follow_the_floor_formula():
+    # MobileNet stride-2 chain of Table III: 112 -> 56 -> 28 -> 14 -> 7
+    for H, Ho in [(112, 56), (56, 28), (28, 14), (14, 7)]:
+        assert dw.out_dims(dw.desc(1, 8, H, H, 3, 2, 1)) == (Ho, Ho)
+    assert dw.out_dims(dw.desc(1, 8, 7, 9, 3, 2, 1)) == (4, 5)
+    assert dw.out_dims(dw.desc(1, 8, 2, 2, 3, 1, 1)) == (2, 2)       # map smaller than the filter, enough pad
+    assert dw.out_dims(dw.desc(1, 8, 5, 5, 5, 1, 0)) == (1, 1)
+
+
+@pytest.mark.parametrize("field,value,code", [
+    ("N", 0, E_DIM), ("C", 0, E_DIM), ("H", -1, E_DIM), ("W", 0, E_DIM), ("K", 0, E_DIM), ("stride", 0, E_DIM),
+    ("pad", -1, E_DIM), ("mult", 0, E_DIM), ("layout", 2, E_ENUM), ("layout", -1, E_ENUM), ("dtype", 2, E_ENUM),
+    ("K", 16, E_UNSUP), ("N", 1 << 20, E_LARGE),
+])
+def test_bad_descriptors(field, value, code):
+    d = dw.desc(2, 8, 16, 16)
+    setattr(d, field, value)
+    lib = dw.load()
+    assert lib.dwconv_out_dims(ctypes.byref(d), None, None) == code
+    assert lib.dwconv_fwd(ctypes.byref(d), A, B, Cp, None) == code
+    assert lib.dwconv_bwd_data(ctypes.byref(d), A, B, Cp, None) == code
+    assert lib.dwconv_bwd_filter(ctypes.byref(d), A, B, Cp, Dp, 1 << 30, None) == code
+    assert dw.bwd_filter_workspace_bytes(d) == 0
+    assert dw.variant_name(d, 0) == "invalid"
+
+
+def test_empty_output_is_a_bad_dim():
+    d = dw.desc(1, 4, 2, 2, 5, 1, 0)     # 2 + 0 - 5 < 0
+    assert dw.load().dwconv_out_dims(ctypes.byref(d), None, None) == E_DIM
+
+
+def test_null_misaligned_and_workspace_errors():
+    lib = dw.load()
+    d = dw.desc(2, 8, 16, 16)
+    ref = ctypes.byref(d)
+    assert lib.dwconv_out_dims(None, None, None) == E_NULL
+    assert lib.dwconv_fwd(None, A, B, Cp, None) == E_NULL
+    for args in [(None, B, Cp), (A, None, Cp), (A, B, None)]:
+        assert lib.dwconv_fwd(ref, *args, None) == E_NULL
+        assert lib.dwconv_bwd_data(ref, *args, None) == E_NULL
+        assert lib.dwconv_bwd_filter(ref, *args, Dp, 1 << 30, None) == E_NULL
+    for args in [(A + 4, B, Cp), (A, B + 8, Cp), (A, B, Cp + 2)]:
+        assert lib.dwconv_fwd(ref, *args, None) == E_ALIGN
+        assert lib.dwconv_bwd_data(ref, *args, None) == E_ALIGN
+        assert lib.dwconv_bwd_filter(ref, *args, Dp, 1 << 30, None) == E_ALIGN
+    need = dw.bwd_filter_workspace_bytes(d)
+    assert need > 0 and need <= (64 << 20)
+    assert lib.dwconv_bwd_filter(ref, A, B, Cp, None, need, None) == E_WS
+    assert lib.dwconv_bwd_filter(ref, A, B, Cp, Dp, need - 1, None) == E_WS
+    assert lib.dwconv_bwd_filter(ref, A, B, Cp, Dp + 4, need, None) == E_ALIGN
+
+
+def test_status_strings():
+    seen = set()
+    for code in range(0, -9, -1):
+        s = dw.status_string(code)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 9
+    assert dw.status_string(-99) == "unknown status"
+
+
+def test_workspace_is_bounded_for_every_benchmark_layer():
+    from paper_1803_09926_amd import workloads as wl
+    for ci in range(5):
+        cfg = wl.config(ci)
+        for layer, _ in cfg["layers"]:
+            for layout in cfg["layouts"]:
+                d = dw.desc(cfg["N"], layer.C, layer.H, layer.W, layer.K, layer.stride, layer.pad, layer.mult,
+                            layout, cfg["dtype"])
+                assert dw.out_dims(d) == (layer.Ho, layer.Wo)
+                need = dw.bwd_filter_workspace_bytes(d)
+                assert 0 < need <= (64 << 20), (layer.name, need)
+                for which in range(3):
+                    assert dw.variant_name(d, which) not in ("", "invalid")

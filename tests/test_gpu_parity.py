@@ -1,0 +1,192 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle, element by element,
+on seeded inputs.  Small and awkward shapes are compared in full; the benchmark workloads at
+their full sizes are compared on sampled images (fwd, bwd_data: images are independent) and
+sampled channels over the whole batch (bwd_filter: channels are independent)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_1803_09926_amd as dw
+from paper_1803_09926_amd import workloads as wl
+from paper_1803_09926_amd.workloads import Layer
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+LAYOUTS = [wl.NCHW, wl.NHWC]
+DTYPES = [wl.F32, wl.BF16]
+
+# name, C, H, W, K, stride, pad, mult ; batch chosen per case below
+AWKWARD = [
+    (3, Layer("odd_hw", 8, 13, 11)),
+    (2, Layer("w_lt_k", 4, 5, 2)),
+    (2, Layer("h_lt_k", 4, 2, 9)),
+    (2, Layer("c_not_mult4", 6, 9, 9)),
+    (2, Layer("c_prime", 37, 10, 12)),
+    (2, Layer("c1", 1, 17, 19)),
+    (3, Layer("s2_even", 16, 16, 16, 3, 2, 1)),
+    (3, Layer("s2_odd", 12, 15, 13, 3, 2, 1)),
+    (2, Layer("s2_pad0", 8, 12, 14, 3, 2, 0)),
+    (2, Layer("k5", 16, 14, 14, 5, 1, 2)),
+    (2, Layer("k5_s2", 8, 15, 16, 5, 2, 2)),
+    (2, Layer("k5_pad1", 8, 9, 10, 5, 1, 1)),
+    (2, Layer("k1", 8, 6, 7, 1, 1, 0)),
+    (2, Layer("k2", 8, 8, 8, 2, 2, 0)),
+    (2, Layer("k7", 4, 12, 12, 7, 1, 3)),
+    (2, Layer("m2", 16, 12, 12, 3, 1, 1, 2)),
+    (2, Layer("m3_s2", 8, 11, 12, 3, 2, 1, 3)),
+    (1, Layer("s3", 8, 17, 17, 3, 3, 1)),
+    (1, Layer("s_gt_k", 4, 16, 16, 3, 4, 1)),
+    (1, Layer("pad_ge_k", 4, 6, 6, 3, 1, 3)),
+    (5, Layer("mn_tail7", 64, 7, 7)),
+    (5, Layer("mn_tail14", 32, 14, 14)),
+    (3, Layer("mn_tail14_s2", 32, 14, 14, 3, 2, 1)),
+    (3, Layer("mn28", 24, 28, 28)),
+    (2, Layer("mn28_s2", 16, 28, 28, 3, 2, 1)),
+    (2, Layer("mn56", 8, 56, 56)),
+    (2, Layer("mn56_s2", 8, 56, 56, 3, 2, 1)),
+    (2, Layer("mn112", 4, 112, 112)),
+    (2, Layer("mn112_s2", 4, 112, 112, 3, 2, 1)),
+    (2, Layer("xc19", 40, 19, 19)),
+    (2, Layer("xc10", 72, 10, 10)),
+    (1, Layer("xc37", 24, 37, 37)),
+    (1, Layer("xc147", 8, 147, 147)),
+    (1, Layer("xc74", 8, 74, 74)),
+    (2, Layer("c728_like", 182 * 4, 5, 6)),
+    (2, Layer("k5_tail7", 32, 7, 7, 5, 1, 2)),
+    (2, Layer("k5_56", 8, 56, 56, 5, 1, 2)),
+    (2, Layer("m2_56", 8, 56, 56, 3, 1, 1, 2)),
+    (3, Layer("tall", 8, 70, 12)),
+    (3, Layer("wide", 8, 6, 300)),
+]
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("N,layer", AWKWARD, ids=[l.name for _, l in AWKWARD])
+def test_awkward_shapes_match_oracle(gpu_lib, N, layer, layout, dtype):
+    print("case", layer, N, layout, dtype, flush=True)
+    gu.check_layer_full(layer, N, layout, dtype, seed=7000 + 31 * layout + 17 * dtype + layer.C)
+
+
+def test_config0_single_layer_full(gpu_lib):
+    cfg = wl.config(0)
+    layer = cfg["layers"][0][0]
+    gu.check_layer_full(layer, cfg["N"], wl.NCHW, wl.F32, seed=1000)
+    gu.check_layer_full(layer, cfg["N"], wl.NHWC, wl.F32, seed=1001)
+
+
+def _distinct_layers(cfg):
+    seen, out = set(), []
+    for layer, _ in cfg["layers"]:
+        key = (layer.C, layer.H, layer.W, layer.K, layer.stride, layer.pad, layer.mult)
+        if key not in seen:
+            seen.add(key)
+            out.append(layer)
+    return out
+
+
+def _sampled_check(layer, N, layout, dtype, seed):
+    """Full-size problem in the launch configuration the benchmark times; oracle on samples."""
+    x, w, dy = wl.make_inputs_device(layer, N, layout, dtype, seed)
+    y, dx, dwt = gu.gpu_passes(layer, N, layout, dtype, x, w, dy)
+    kw = dict(K=layer.K, stride=layer.stride, pad=layer.pad, mult=layer.mult, layout=layout, nthreads=8)
+    tol = gu.TOL_F32 if dtype == wl.F32 else gu.TOL_BF16
+    tag = "%s N=%d layout=%d dtype=%d" % (layer.name, N, layout, dtype)
+    wh = gu.to_host(w)
+    # fwd / bwd_data: first, a middle and the last image
+    imgs = sorted({0, N // 2 - 1, N - 1})
+    xh = gu.to_host(x[imgs]); dyh = gu.to_host(dy[imgs])
+    gu.assert_close(gu.to_host(y[imgs]), oracle.fwd(xh, wh, **kw), tol, "fwd " + tag)
+    gu.assert_close(gu.to_host(dx[imgs]), oracle.bwd_data(dyh, wh, x_shape=xh.shape, **kw), tol, "bwd_data " + tag)
+    # bwd_filter: a few input channels (first, one in the middle, last) over the whole batch
+    m = layer.mult
+    for c in sorted({0, layer.C // 2 + 1 if layer.C > 2 else 0, layer.C - 1}):
+        if layout == wl.NCHW:
+            xc = gu.to_host(x[:, c:c + 1]); dyc = gu.to_host(dy[:, c * m:(c + 1) * m]); got = gu.to_host(dwt[c * m:(c + 1) * m])
+        else:
+            xc = gu.to_host(x[..., c:c + 1]); dyc = gu.to_host(dy[..., c * m:(c + 1) * m]); got = gu.to_host(dwt[..., c * m:(c + 1) * m])
+        ref = oracle.bwd_filter(xc, dyc, **kw)
+        gu.assert_close(got, ref, gu.TOL_F32_FILTER, "bwd_filter ch %d %s" % (c, tag))
+    del x, w, dy, y, dx, dwt
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("ci", [1, 2, 3, 4])
+def test_benchmark_configs_full_size_sampled(gpu_lib, ci):
+    cfg = wl.config(ci)
+    for li, layer in enumerate(_distinct_layers(cfg)):
+        for layout in cfg["layouts"]:
+            print("config", ci, layer.name, "layout", layout, flush=True)
+            _sampled_check(layer, cfg["N"], layout, cfg["dtype"], seed=1000 * ci + li)
+
+
+def test_bwd_filter_is_bit_reproducible(gpu_lib):
+    for layout in LAYOUTS:
+        for layer, N in [(wl.MOBILENET_V1[0], 16), (wl.MOBILENET_V1[5], 16), (wl.MOBILENET_V1[12], 32)]:
+            x, w, dy = wl.make_inputs_device(layer, N, layout, wl.F32, 99)
+            outs = []
+            for _ in range(3):
+                _, _, dwt = gu.gpu_passes(layer, N, layout, wl.F32, x, w, dy)
+                outs.append(dwt.cpu().numpy().view(np.uint32))
+            assert (outs[0] == outs[1]).all() and (outs[0] == outs[2]).all()
+
+
+def test_no_write_outside_the_output_buffers(gpu_lib):
+    """Outputs sit inside larger poisoned buffers; the guard bands must be untouched."""
+    G = 256  # guard elements on each side (keeps 16-byte alignment)
+    for dtype in DTYPES:
+        tdt = torch.float32 if dtype == wl.F32 else torch.bfloat16
+        for layout in LAYOUTS:
+            for layer, N in [(Layer("g1", 12, 13, 11), 2), (Layer("g2", 16, 14, 14, 3, 2, 1), 3),
+                             (Layer("g3", 32, 7, 7), 5), (Layer("g4", 8, 56, 56), 2), (Layer("g5", 8, 28, 28, 5, 1, 2), 2)]:
+                x, w, dy = wl.make_inputs(layer, N, layout, dtype, 5)
+                xt, wt, dyt = gu.to_dev(x, dtype), gu.to_dev(w, dtype), gu.to_dev(dy, dtype)
+                d = gu.desc_for(layer, N, layout, dtype)
+                xs, ys, ws = gu.shapes(layer, N, layout)
+                def guarded(n, dt):
+                    n_pad = (n + 7) // 8 * 8
+                    buf = torch.full((n_pad + 2 * G,), 12345.0, device="cuda", dtype=dt)
+                    return buf, buf[G:G + n]
+                ybuf, yv = guarded(int(np.prod(ys)), tdt)
+                dxbuf, dxv = guarded(int(np.prod(xs)), tdt)
+                dwbuf, dwv = guarded(int(np.prod(ws)), torch.float32)
+                wsb = torch.zeros(max(dw.bwd_filter_workspace_bytes(d), 16), device="cuda", dtype=torch.uint8)
+                dw.fwd(d, xt, wt, yv); dw.bwd_data(d, dyt, wt, dxv); dw.bwd_filter(d, xt, dyt, dwv, wsb)
+                torch.cuda.synchronize()
+                for buf, v in [(ybuf, yv), (dxbuf, dxv), (dwbuf, dwv)]:
+                    n = v.numel()
+                    assert (buf[:G] == 12345.0).all() and (buf[G + n:] == 12345.0).all(), (layer.name, layout, dtype)
+
+
+def test_non_default_stream_and_input_preservation(gpu_lib):
+    layer, N = Layer("st", 16, 28, 28), 4
+    for layout in LAYOUTS:
+        x, w, dy = wl.make_inputs(layer, N, layout, wl.F32, 11)
+        xt, wt, dyt = gu.to_dev(x, wl.F32), gu.to_dev(w, wl.F32), gu.to_dev(dy, wl.F32)
+        ref = gu.gpu_passes(layer, N, layout, wl.F32, xt, wt, dyt)
+        s = torch.cuda.Stream()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(s):
+            got = gu.gpu_passes(layer, N, layout, wl.F32, xt, wt, dyt, stream=s)
+        for a, b in zip(ref, got):
+            assert torch.equal(a, b)
+        assert np.array_equal(gu.to_host(xt), x) and np.array_equal(gu.to_host(wt), w) and np.array_equal(gu.to_host(dyt), dy)
+
+
+def test_binding_rejects_wrong_tensors(gpu_lib):
+    d = dw.desc(2, 8, 8, 8)
+    x = torch.zeros(2, 8, 8, 8, device="cuda"); w = torch.zeros(8, 3, 3, device="cuda"); y = torch.zeros(2, 8, 8, 8, device="cuda")
+    with pytest.raises(ValueError):
+        dw.fwd(d, x.cpu(), w, y)
+    with pytest.raises(ValueError):
+        dw.fwd(d, x.to(torch.bfloat16), w, y)
+    with pytest.raises(ValueError):
+        dw.fwd(d, x[:, :4], w, y)
+    dwt = torch.zeros(8, 3, 3, device="cuda")
+    small = torch.zeros(16, device="cuda", dtype=torch.uint8)
+    if dw.bwd_filter_workspace_bytes(d) > 16:
+        with pytest.raises(dw.DwconvError):
+            dw.bwd_filter(d, x, y, dwt, small)
