@@ -21,4 +21,18 @@ hipError_t generic_bwd_filter(const Geom &g, int layout, int dtype, const void *
 // dw[j] = sum_{p < parts} ws[p*J + j], j < J, added in a fixed order.
 hipError_t reduce_partials(const float *ws, int parts, int J, float *dw, hipStream_t st);
 
+// ---- NHWC row-walk kernels, multiplier 1 (nhwc.hip) ------------------------------------------
+// V = channels per lane (4 for fp32; 8 or 4 for bf16), TH = rows per strip.
+// stride 1, K in {3,5}, pad (K-1)/2; flip = true gives backward-data.
+hipError_t nhwc_s1(const Geom &g, int dtype, int V, const void *x, const void *w, void *y, bool flip, int TH,
+                   hipStream_t st);
+// 3x3 stride 2 pad 1; bwd = false: forward (in = x, out = y); bwd = true: backward-data (in = dy, out = dx).
+hipError_t nhwc_k3s2(const Geom &g, int dtype, int V, const void *in, const void *w, void *out, bool bwd, int TH,
+                     hipStream_t st);
+// filter gradient stage 1; NI = images per block.
+void nhwc_bwd_filter_tiling(const Geom &g, int V, int TH, int NI, int *CT, int *nctiles, int *nowtiles, int *nstrips,
+                            int *ngroups);
+hipError_t nhwc_bwd_filter(const Geom &g, int dtype, int V, const void *x, const void *dy, float *ws, int TH, int NI,
+                           hipStream_t st);
+
 }  // namespace dwc

@@ -1,23 +1,105 @@
 // Variant selection and launch dispatch.
 #include "plan.hpp"
+#include <stdlib.h>
 
 namespace dwc {
+
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Optional overrides for tuning runs (unset in normal use): DWCONV_TUNE_TH, DWCONV_TUNE_NI.
+static int tune(const char *name, int dflt)
+{
+    const char *e = getenv(name);
+    if (!e || !*e) return dflt;
+    int v = atoi(e);
+    return v > 0 ? v : dflt;
+}
+
+static bool same_pad_s1(const Geom &g) { return g.s == 1 && (g.K == 3 || g.K == 5) && g.p == (g.K - 1) / 2; }
+static bool k3s2p1(const Geom &g) { return g.s == 2 && g.K == 3 && g.p == 1; }
+
+// channels per lane for the NHWC kernels, 0 if the fast path does not apply
+static int nhwc_vec(const Geom &g, int dtype)
+{
+    if (g.m != 1) return 0;
+    if (dtype == DT_F32) return g.C % 4 == 0 ? 4 : 0;
+    if (g.K == 5) return g.C % 4 == 0 ? 4 : 0;   // 25 taps x 8 channels would not fit in registers
+    return g.C % 8 == 0 ? 8 : (g.C % 4 == 0 ? 4 : 0);
+}
+
+// Rows per strip: enough strips that the launch has at least ~12 wavefronts per CU, but strips of
+// at least 7 rows so that the K-1 halo rows re-read per strip stay a small fraction.
+static int pick_th(int rows, long long lanes_per_row_all_images)
+{
+    const long long want = 256ll * 12 * 64;
+    int th = rows;
+    while (th > 7 && lanes_per_row_all_images * ceil_div(rows, th) < want) th = (th + 1) / 2;
+    return tune("DWCONV_TUNE_TH", th);
+}
 
 Plan plan_fwd(const Geom &g, int layout, int dtype)
 {
     Plan pl = {V_GENERIC, 0, 0, 0, 0, "generic"};
+    if (layout == LAYOUT_NHWC) {
+        const int V = nhwc_vec(g, dtype);
+        if (V && same_pad_s1(g)) {
+            pl.variant = V_NHWC_S1; pl.a = V; pl.b = pick_th(g.H, (long long)g.N * g.W * (g.C / V));
+            pl.name = g.K == 3 ? "nhwc_rowwalk_k3s1" : "nhwc_rowwalk_k5s1";
+        } else if (V && k3s2p1(g)) {
+            pl.variant = V_NHWC_K3S2; pl.a = V; pl.b = pick_th(g.Ho, (long long)g.N * g.Wo * (g.C / V));
+            pl.name = "nhwc_rowwalk_fwd_k3s2";
+        }
+    }
     return pl;
 }
 
 Plan plan_bwd_data(const Geom &g, int layout, int dtype)
 {
     Plan pl = {V_GENERIC, 0, 0, 0, 0, "generic"};
+    if (layout == LAYOUT_NHWC) {
+        const int V = nhwc_vec(g, dtype);
+        if (V && same_pad_s1(g)) {
+            pl.variant = V_NHWC_S1; pl.a = V; pl.b = pick_th(g.H, (long long)g.N * g.W * (g.C / V));
+            pl.name = g.K == 3 ? "nhwc_rowwalk_k3s1_flip" : "nhwc_rowwalk_k5s1_flip";
+        } else if (V && k3s2p1(g)) {
+            pl.variant = V_NHWC_K3S2; pl.a = V; pl.b = pick_th(g.Ho, (long long)g.N * g.Wo * (g.C / V));
+            pl.name = "nhwc_rowwalk_bwd_data_k3s2";
+        }
+    }
     return pl;
 }
 
 Plan plan_bwd_filter(const Geom &g, int layout, int dtype)
 {
     Plan pl = {V_GENERIC, generic_bwd_filter_parts(g), 0, 0, 0, "generic"};
+    if (layout == LAYOUT_NHWC) {
+        const int V = nhwc_vec(g, dtype);
+        if (V && (same_pad_s1(g) || k3s2p1(g))) {
+            // lanes per (row, image) after tiling: columns x channel-vectors, rounded up to the block tiling
+            int CT, nct, nowt, nst, ngr;
+            nhwc_bwd_filter_tiling(g, V, g.Ho, 1, &CT, &nct, &nowt, &nst, &ngr);
+            const long long lanes = 256ll * nct * nowt;
+            // images per block: aim for ~12 wavefronts per CU over the whole launch
+            int TH = g.Ho, NI = 1;
+            const long long want = 256ll * 12 * 64;
+            long long blocks_lanes = lanes * g.N;       // with NI = 1, one strip
+            if (blocks_lanes >= 2 * want) {
+                while (NI < g.N && lanes * ceil_div(g.N, NI * 2) >= want) NI *= 2;
+            } else {
+                while (TH > 7 && lanes * g.N * ceil_div(g.Ho, TH) < want) TH = (TH + 1) / 2;
+            }
+            TH = tune("DWCONV_TUNE_TH", TH); NI = tune("DWCONV_TUNE_NI", NI);
+            nhwc_bwd_filter_tiling(g, V, TH, NI, &CT, &nct, &nowt, &nst, &ngr);
+            // keep the partials within the 64 MiB the header promises
+            while ((long long)nowt * nst * ngr * g.O * g.K * g.K * 4 > (64ll << 20)) {
+                if (NI < g.N) NI *= 2; else TH *= 2;
+                nhwc_bwd_filter_tiling(g, V, TH, NI, &CT, &nct, &nowt, &nst, &ngr);
+            }
+            pl.variant = V_NHWC_BWD_FILTER; pl.a = V; pl.b = TH; pl.c = NI;
+            pl.parts = nowt * nst * ngr;
+            pl.name = g.s == 2 ? "nhwc_bwd_filter_k3s2" : (g.K == 3 ? "nhwc_bwd_filter_k3s1" : "nhwc_bwd_filter_k5s1");
+        }
+    }
     return pl;
 }
 
@@ -25,6 +107,8 @@ hipError_t launch_fwd(const Plan &pl, const Geom &g, int layout, int dtype, cons
                       hipStream_t st)
 {
     switch (pl.variant) {
+    case V_NHWC_S1: return nhwc_s1(g, dtype, pl.a, x, w, y, false, pl.b, st);
+    case V_NHWC_K3S2: return nhwc_k3s2(g, dtype, pl.a, x, w, y, false, pl.b, st);
     default: return generic_fwd(g, layout, dtype, x, w, y, st);
     }
 }
@@ -33,6 +117,8 @@ hipError_t launch_bwd_data(const Plan &pl, const Geom &g, int layout, int dtype,
                            void *dx, hipStream_t st)
 {
     switch (pl.variant) {
+    case V_NHWC_S1: return nhwc_s1(g, dtype, pl.a, dy, w, dx, true, pl.b, st);
+    case V_NHWC_K3S2: return nhwc_k3s2(g, dtype, pl.a, dy, w, dx, true, pl.b, st);
     default: return generic_bwd_data(g, layout, dtype, dy, w, dx, st);
     }
 }
@@ -41,6 +127,7 @@ hipError_t launch_bwd_filter(const Plan &pl, const Geom &g, int layout, int dtyp
                              float *ws, hipStream_t st)
 {
     switch (pl.variant) {
+    case V_NHWC_BWD_FILTER: return nhwc_bwd_filter(g, dtype, pl.a, x, dy, ws, pl.b, pl.c, st);
     default: return generic_bwd_filter(g, layout, dtype, x, dy, ws, pl.parts, st);
     }
 }

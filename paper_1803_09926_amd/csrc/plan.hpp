@@ -7,6 +7,9 @@ namespace dwc {
 
 enum Variant {
     V_GENERIC = 0,
+    V_NHWC_S1,          // a = V, b = TH
+    V_NHWC_K3S2,        // a = V, b = TH
+    V_NHWC_BWD_FILTER,  // a = V, b = TH, c = NI
 };
 
 struct Plan {
