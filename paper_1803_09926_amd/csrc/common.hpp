@@ -1,5 +1,8 @@
 // Shared device-side helpers for the gfx950 depthwise-convolution kernels.
 #pragma once
+#ifndef DWC_EXP
+#define DWC_EXP 0
+#endif
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -36,12 +39,23 @@ template <typename T, int V> struct Vec;
 template <> struct Vec<float, 4> {
     static __device__ __forceinline__ void load(const float *p, float (&r)[4])
     {
+#if DWC_EXP == 3
+        typedef float f4v __attribute__((ext_vector_type(4)));
+        f4v v = __builtin_nontemporal_load(reinterpret_cast<const f4v *>(p));
+#else
         float4 v = *reinterpret_cast<const float4 *>(p);
+#endif
         r[0] = v.x; r[1] = v.y; r[2] = v.z; r[3] = v.w;
     }
     static __device__ __forceinline__ void store(float *p, const float (&r)[4])
     {
+#if DWC_EXP == 2 || DWC_EXP == 3
+        typedef float f4v __attribute__((ext_vector_type(4)));
+        f4v v = {r[0], r[1], r[2], r[3]};
+        __builtin_nontemporal_store(v, reinterpret_cast<f4v *>(p));
+#else
         *reinterpret_cast<float4 *>(p) = make_float4(r[0], r[1], r[2], r[3]);
+#endif
     }
 };
 template <> struct Vec<float, 2> {

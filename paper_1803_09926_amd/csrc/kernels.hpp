@@ -24,8 +24,9 @@ hipError_t reduce_partials(const float *ws, int parts, int J, float *dw, hipStre
 // ---- NHWC row-walk kernels, multiplier 1 (nhwc.hip) ------------------------------------------
 // V = channels per lane (4 for fp32; 8 or 4 for bf16), TH = rows per strip.
 // stride 1, K in {3,5}, pad (K-1)/2; flip = true gives backward-data.
-hipError_t nhwc_s1(const Geom &g, int dtype, int V, const void *x, const void *w, void *y, bool flip, int TH,
-                   hipStream_t st);
+// TW = adjacent output columns per lane, PF = rows loaded ahead.
+hipError_t nhwc_s1(const Geom &g, int dtype, int V, const void *x, const void *w, void *y, bool flip, int TH, int TW,
+                   int PF, hipStream_t st);
 // 3x3 stride 2 pad 1; bwd = false: forward (in = x, out = y); bwd = true: backward-data (in = dy, out = dx).
 hipError_t nhwc_k3s2(const Geom &g, int dtype, int V, const void *in, const void *w, void *out, bool bwd, int TH,
                      hipStream_t st);
@@ -33,6 +34,17 @@ hipError_t nhwc_k3s2(const Geom &g, int dtype, int V, const void *in, const void
 void nhwc_bwd_filter_tiling(const Geom &g, int V, int TH, int NI, int *CT, int *nctiles, int *nowtiles, int *nstrips,
                             int *ngroups);
 hipError_t nhwc_bwd_filter(const Geom &g, int dtype, int V, const void *x, const void *dy, float *ws, int TH, int NI,
+                           hipStream_t st);
+
+// ---- NCHW LDS-tile kernels (nchw.hip) ----------------------------------------------------------
+// TR = rows per unit.  K in {3,5}, stride in {1,2}, any pad, any multiplier for forward and the
+// filter gradient; flip = true gives backward-data for stride 1, "same" padding, multiplier 1.
+bool nchw_fwd_supported(const Geom &g, int TR);
+hipError_t nchw_fwd(const Geom &g, int dtype, const void *x, const void *w, void *y, bool flip, int TR, hipStream_t st);
+bool nchw_bwd_data_k3s2_supported(const Geom &g, int TR);
+hipError_t nchw_bwd_data_k3s2(const Geom &g, int dtype, const void *dy, const void *w, void *dx, int TR, hipStream_t st);
+int nchw_bwd_filter_parts(const Geom &g, int TR, int NI);   // 0 = unsupported
+hipError_t nchw_bwd_filter(const Geom &g, int dtype, const void *x, const void *dy, float *ws, int TR, int NI,
                            hipStream_t st);
 
 }  // namespace dwc

@@ -18,21 +18,36 @@ __device__ __forceinline__ Tile tile_of(unsigned nblocks, int nchunks, int nstri
     return t;
 }
 
+// Register budget of the stride-1 kernel as wavefronts per SIMD (512 VGPRs / budget): filter taps,
+// the row ring, the rotating accumulators and one row of outputs, plus addressing.
+template <int V, int K, int TW, int PF> constexpr int S1_WAVES()
+{
+    const int regs = K * K * V + (PF + 1) * (TW + K - 1) * V + (K - 1) * TW * V + TW * V + 24;
+    return regs <= 64 ? 8 : regs <= 72 ? 7 : regs <= 84 ? 6 : regs <= 100 ? 5 : regs <= 128 ? 4 : regs <= 168 ? 3 : 2;
+}
+
 // ---------------------------------------------------------------------------------------------
 // Forward, stride 1, "same" padding (K odd, pad = (K-1)/2, so Wo = W and Ho = H), multiplier 1.
+// A lane owns V channels of TW adjacent output columns and walks down the rows of its strip.
+// Per input row it loads the TW + K - 1 columns it needs (each element of the row is loaded
+// (TW+K-1)/TW times over all lanes; the L1 serves the repeats), PF rows ahead of the row being
+// consumed, so that PF * (TW+K-1) loads are in flight per lane.
 // FLIP = true reads the filter rotated by 180 degrees, which makes this the backward-data pass
 // of the same layer (input = dy, output = dx).
 // ---------------------------------------------------------------------------------------------
-template <typename T, int V, int K, bool FLIP>
-__global__ __launch_bounds__(256) void k_nhwc_s1(Geom g, const T *__restrict__ x, const T *__restrict__ w,
+template <typename T, int V, int K, int TW, int PF, bool FLIP>
+__global__ __launch_bounds__(256, (S1_WAVES<V, K, TW, PF>())) void k_nhwc_s1(Geom g, const T *__restrict__ x, const T *__restrict__ w,
                                                  T *__restrict__ y, int TH, int nstrips, int nchunks, unsigned nblocks)
 {
     constexpr int P = (K - 1) / 2;
+    constexpr int NC = TW + K - 1;        // input columns per lane
+    constexpr int R = PF + 1;             // ring of rows: PF in flight + the one being consumed
     const Tile tl = tile_of(nblocks, nchunks, nstrips);
-    const int Q = g.C / V, WQ = g.W * Q;
+    const int Q = g.C / V;
+    const int nowg = (g.W + TW - 1) / TW;
     const int f = tl.chunk * blockDim.x + threadIdx.x;
-    if (f >= WQ) return;
-    const int cq = f % Q;
+    if (f >= nowg * Q) return;
+    const int cq = f % Q, ow0 = (f / Q) * TW;
 
     float wr[K][K][V];
 #pragma unroll
@@ -42,66 +57,89 @@ __global__ __launch_bounds__(256) void k_nhwc_s1(Geom g, const T *__restrict__ x
             const int sh = FLIP ? K - 1 - kh : kh, sw = FLIP ? K - 1 - kw : kw;
             Vec<T, V>::load(w + (sh * K + sw) * g.C + cq * V, wr[kh][kw]);
         }
-    bool colok[K];
+    // Out-of-image taps read a valid address (clamped row, the lane's own column) and are zeroed
+    // with a select, so the loads are unconditional and can all be issued ahead.
+    bool colok[NC];
+    int coloff[NC];
 #pragma unroll
-    for (int kw = 0; kw < K; ++kw) {
-        const int ff = f + (kw - P) * Q;
-        colok[kw] = ff >= 0 && ff < WQ;
+    for (int c = 0; c < NC; ++c) {
+        const int iw = ow0 - P + c;
+        colok[c] = iw >= 0 && iw < g.W;
+        coloff[c] = (colok[c] ? c : P) * g.C;
     }
 
     const int oh0 = tl.strip * TH, oh1 = min(g.H, oh0 + TH);
-    const size_t img = (size_t)tl.n * g.H * WQ * V;
-    const T *xin = x + img + (size_t)f * V;
-    T *yout = y + img + (size_t)f * V;
-    const int rowstride = WQ * V;
+    const int rowstride = g.W * g.C;
+    const size_t img = (size_t)tl.n * g.H * rowstride;
+    const T *xin = x + img + (ptrdiff_t)(ow0 - P) * g.C + cq * V;
+    T *yout = y + img + (size_t)ow0 * g.C + cq * V;
 
-    float acc[K - 1 > 0 ? K - 1 : 1][V];
+    float acc[K - 1 > 0 ? K - 1 : 1][TW][V];
 #pragma unroll
     for (int j = 0; j < K - 1; ++j)
 #pragma unroll
-        for (int v = 0; v < V; ++v) acc[j][v] = 0.f;
+        for (int t = 0; t < TW; ++t)
+#pragma unroll
+            for (int v = 0; v < V; ++v) acc[j][t][v] = 0.f;
 
-    float cur[K][V], nxt[K][V];
-    auto load_row = [&](int r, float (&dst)[K][V]) {
-        const bool rowok = r >= 0 && r < g.H;
+    float ring[R][NC][V];
+    auto load_row = [&](int r, float (&dst)[NC][V]) {
+        const int rr = min(max(r, 0), g.H - 1);
+        const bool rowok = rr == r;
+        const T *rp = xin + (size_t)rr * rowstride;
 #pragma unroll
-        for (int kw = 0; kw < K; ++kw) {
-            if (rowok && colok[kw]) Vec<T, V>::load(xin + (ptrdiff_t)r * rowstride + (kw - P) * Q * V, dst[kw]);
-            else {
+        for (int c = 0; c < NC; ++c) {
+            Vec<T, V>::load(rp + coloff[c], dst[c]);
+            const bool ok = rowok && colok[c];
 #pragma unroll
-                for (int v = 0; v < V; ++v) dst[kw][v] = 0.f;
+            for (int v = 0; v < V; ++v) dst[c][v] = ok ? dst[c][v] : 0.f;
+        }
+    };
+    auto consume = [&](int r, const float (&cur)[NC][V]) {
+        // input row r is tap row kh of output row r + P - kh
+        float out[TW][V];
+#pragma unroll
+        for (int t = 0; t < TW; ++t)
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                float s = (K > 1) ? acc[0][t][v] : 0.f;
+#pragma unroll
+                for (int kw = 0; kw < K; ++kw) s = fmaf(wr[K - 1][kw][v], cur[t + kw][v], s);
+                out[t][v] = s;
             }
+#pragma unroll
+        for (int j = 0; j < K - 1; ++j)
+#pragma unroll
+            for (int t = 0; t < TW; ++t)
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    float s = (j + 1 < K - 1) ? acc[j + 1][t][v] : 0.f;
+#pragma unroll
+                    for (int kw = 0; kw < K; ++kw) s = fmaf(wr[K - 2 - j][kw][v], cur[t + kw][v], s);
+                    acc[j][t][v] = s;
+                }
+        const int oh = r - P;
+        if (oh >= oh0) {
+#pragma unroll
+            for (int t = 0; t < TW; ++t)
+                if (TW == 1 || ow0 + t < g.W) Vec<T, V>::store(yout + (size_t)oh * rowstride + t * g.C, out[t]);
         }
     };
 
     const int r0 = oh0 - P, r1 = oh1 + P;   // input rows [r0, r1)
-    load_row(r0, cur);
-    for (int r = r0; r < r1; ++r) {
-        if (r + 1 < r1) load_row(r + 1, nxt);
-        // input row r is tap row kh of output row r + P - kh
-        float out[V];
 #pragma unroll
-        for (int v = 0; v < V; ++v) {
-            float s = (K > 1) ? acc[0][v] : 0.f;
+    for (int j = 0; j < PF; ++j)
+        if (r0 + j < r1) load_row(r0 + j, ring[j]);
+#pragma unroll 1
+    for (int base = r0; base < r1; base += R) {
 #pragma unroll
-            for (int kw = 0; kw < K; ++kw) s = fmaf(wr[K - 1][kw][v], cur[kw][v], s);
-            out[v] = s;
-        }
-#pragma unroll
-        for (int j = 0; j < K - 1; ++j)
-#pragma unroll
-            for (int v = 0; v < V; ++v) {
-                float s = (j + 1 < K - 1) ? acc[j + 1][v] : 0.f;
-#pragma unroll
-                for (int kw = 0; kw < K; ++kw) s = fmaf(wr[K - 2 - j][kw][v], cur[kw][v], s);
-                acc[j][v] = s;
+        for (int j = 0; j < R; ++j) {
+            const int r = base + j;
+            if (r < r1) {
+                if (r + PF < r1) load_row(r + PF, ring[(j + PF) % R]);
+                consume(r, ring[j]);
             }
-        const int oh = r - P;
-        if (oh >= oh0) Vec<T, V>::store(yout + (size_t)oh * rowstride, out);
-#pragma unroll
-        for (int kw = 0; kw < K; ++kw)
-#pragma unroll
-            for (int v = 0; v < V; ++v) cur[kw][v] = nxt[kw][v];
+        }
     }
 }
 
@@ -394,33 +432,38 @@ static inline int flat_block(int WQ)
     return waste128 < waste256 ? 128 : 256;
 }
 
-template <typename T, int V, int K>
+template <typename T, int V, int K, int TW, int PF>
 static hipError_t launch_s1(const Geom &g, const void *x, const void *w, void *y, bool flip, int TH, hipStream_t st)
 {
-    const int WQ = g.W * (g.C / V);
-    const int bs = flat_block(WQ);
-    const int nchunks = ceil_div(WQ, bs), nstrips = ceil_div(g.H, TH);
+    const int lanes = ceil_div(g.W, TW) * (g.C / V);
+    const int bs = flat_block(lanes);
+    const int nchunks = ceil_div(lanes, bs), nstrips = ceil_div(g.H, TH);
     const unsigned nblocks = (unsigned)g.N * nchunks * nstrips;
     if (flip)
-        hipLaunchKernelGGL((k_nhwc_s1<T, V, K, true>), dim3(nblocks), dim3(bs), 0, st, g, (const T *)x, (const T *)w,
-                           (T *)y, TH, nstrips, nchunks, nblocks);
+        hipLaunchKernelGGL((k_nhwc_s1<T, V, K, TW, PF, true>), dim3(nblocks), dim3(bs), 0, st, g, (const T *)x,
+                           (const T *)w, (T *)y, TH, nstrips, nchunks, nblocks);
     else
-        hipLaunchKernelGGL((k_nhwc_s1<T, V, K, false>), dim3(nblocks), dim3(bs), 0, st, g, (const T *)x, (const T *)w,
-                           (T *)y, TH, nstrips, nchunks, nblocks);
+        hipLaunchKernelGGL((k_nhwc_s1<T, V, K, TW, PF, false>), dim3(nblocks), dim3(bs), 0, st, g, (const T *)x,
+                           (const T *)w, (T *)y, TH, nstrips, nchunks, nblocks);
     return hipGetLastError();
 }
 
-hipError_t nhwc_s1(const Geom &g, int dtype, int V, const void *x, const void *w, void *y, bool flip, int TH,
-                   hipStream_t st)
+hipError_t nhwc_s1(const Geom &g, int dtype, int V, const void *x, const void *w, void *y, bool flip, int TH, int TW,
+                   int PF, hipStream_t st)
 {
+#define TRY(T, VV, KK, TTW, PPF) if (g.K == KK && V == VV && TW == TTW && PF == PPF) return launch_s1<T, VV, KK, TTW, PPF>(g, x, w, y, flip, TH, st)
     if (dtype == DT_F32) {
-        if (g.K == 3) return launch_s1<float, 4, 3>(g, x, w, y, flip, TH, st);
-        if (g.K == 5) return launch_s1<float, 4, 5>(g, x, w, y, flip, TH, st);
+        TRY(float, 4, 3, 1, 1); TRY(float, 4, 3, 1, 2); TRY(float, 4, 3, 1, 3);
+        TRY(float, 4, 3, 2, 1); TRY(float, 4, 3, 2, 2); TRY(float, 4, 3, 2, 3);
+        TRY(float, 4, 3, 4, 1); TRY(float, 4, 3, 4, 2);
+        TRY(float, 4, 3, 7, 1); TRY(float, 4, 3, 7, 2);
+        TRY(float, 4, 5, 1, 1); TRY(float, 4, 5, 2, 1);
     } else {
-        if (g.K == 3 && V == 8) return launch_s1<bf16_t, 8, 3>(g, x, w, y, flip, TH, st);
-        if (g.K == 3 && V == 4) return launch_s1<bf16_t, 4, 3>(g, x, w, y, flip, TH, st);
-        if (g.K == 5) return launch_s1<bf16_t, 4, 5>(g, x, w, y, flip, TH, st);
+        TRY(bf16_t, 8, 3, 1, 1); TRY(bf16_t, 8, 3, 2, 1); TRY(bf16_t, 8, 3, 2, 2);
+        TRY(bf16_t, 4, 3, 1, 1); TRY(bf16_t, 4, 3, 2, 1);
+        TRY(bf16_t, 4, 5, 1, 1); TRY(bf16_t, 4, 5, 2, 1);
     }
+#undef TRY
     return hipErrorInvalidValue;
 }
 

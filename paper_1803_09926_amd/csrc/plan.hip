@@ -37,9 +37,26 @@ static int pick_th(int rows, long long lanes_per_row_all_images)
     return tune("DWCONV_TUNE_TH", th);
 }
 
+// NCHW: rows per unit.  Small planes are taken whole; larger ones in strips of 8 output rows
+// (halo rows come from L2), shrunk until the tile fits in LDS.
+static int nchw_pick_tr(const Geom &g, bool (*fits)(const Geom &, int))
+{
+    int tr = g.Ho <= 16 ? g.Ho : 8;
+    tr = tune("DWCONV_TUNE_TH", tr);
+    if (tr > g.Ho) tr = g.Ho;
+    while (tr > 1 && !fits(g, tr)) tr = (tr + 1) / 2;
+    return fits(g, tr) ? tr : 0;
+}
+static bool fits_bwd_filter(const Geom &g, int tr) { return nchw_bwd_filter_parts(g, tr, 1) > 0; }
+
 Plan plan_fwd(const Geom &g, int layout, int dtype)
 {
     Plan pl = {V_GENERIC, 0, 0, 0, 0, "generic"};
+    if (layout == LAYOUT_NCHW) {
+        const int tr = nchw_pick_tr(g, nchw_fwd_supported);
+        if (tr) { pl.variant = V_NCHW_FWD; pl.b = tr; pl.name = "nchw_tile_fwd"; }
+        return pl;
+    }
     if (layout == LAYOUT_NHWC) {
         const int V = nhwc_vec(g, dtype);
         if (V && same_pad_s1(g)) {
@@ -56,6 +73,16 @@ Plan plan_fwd(const Geom &g, int layout, int dtype)
 Plan plan_bwd_data(const Geom &g, int layout, int dtype)
 {
     Plan pl = {V_GENERIC, 0, 0, 0, 0, "generic"};
+    if (layout == LAYOUT_NCHW) {
+        if (g.m == 1 && same_pad_s1(g)) {
+            const int tr = nchw_pick_tr(g, nchw_fwd_supported);
+            if (tr) { pl.variant = V_NCHW_FWD; pl.b = tr; pl.name = "nchw_tile_fwd_flip"; }
+        } else if (g.m == 1 && k3s2p1(g)) {
+            const int tr = nchw_pick_tr(g, nchw_bwd_data_k3s2_supported);
+            if (tr) { pl.variant = V_NCHW_BWD_DATA_K3S2; pl.b = tr; pl.name = "nchw_tile_bwd_data_k3s2"; }
+        }
+        return pl;
+    }
     if (layout == LAYOUT_NHWC) {
         const int V = nhwc_vec(g, dtype);
         if (V && same_pad_s1(g)) {
@@ -72,6 +99,27 @@ Plan plan_bwd_data(const Geom &g, int layout, int dtype)
 Plan plan_bwd_filter(const Geom &g, int layout, int dtype)
 {
     Plan pl = {V_GENERIC, generic_bwd_filter_parts(g), 0, 0, 0, "generic"};
+    if (layout == LAYOUT_NCHW) {
+        const int tr = nchw_pick_tr(g, fits_bwd_filter);
+        if (tr) {
+            // images per block: keep about 4096 blocks in the launch
+            const int wpl = g.Wo <= 8 ? 8 : g.Wo <= 16 ? 16 : g.Wo <= 32 ? 32 : g.Wo <= 64 ? 64 : g.Wo <= 128 ? 128 : 256;
+            const long long ublocks = ((long long)g.O * ceil_div(g.Ho, tr) + (256 / wpl) - 1) / (256 / wpl);
+            int NI = (int)((ublocks * g.N) / 4096);
+            if (NI < 1) NI = 1;
+            if (NI > g.N) NI = g.N;
+            NI = tune("DWCONV_TUNE_NI", NI);
+            int parts = nchw_bwd_filter_parts(g, tr, NI);
+            while ((long long)parts * g.O * g.K * g.K * 4 > (64ll << 20) && NI < g.N) {
+                NI *= 2;
+                parts = nchw_bwd_filter_parts(g, tr, NI);
+            }
+            if ((long long)parts * g.O * g.K * g.K * 4 <= (64ll << 20)) {
+                pl.variant = V_NCHW_BWD_FILTER; pl.b = tr; pl.c = NI; pl.parts = parts; pl.name = "nchw_tile_bwd_filter";
+            }
+        }
+        return pl;
+    }
     if (layout == LAYOUT_NHWC) {
         const int V = nhwc_vec(g, dtype);
         if (V && (same_pad_s1(g) || k3s2p1(g))) {
@@ -107,8 +155,9 @@ hipError_t launch_fwd(const Plan &pl, const Geom &g, int layout, int dtype, cons
                       hipStream_t st)
 {
     switch (pl.variant) {
-    case V_NHWC_S1: return nhwc_s1(g, dtype, pl.a, x, w, y, false, pl.b, st);
+    case V_NHWC_S1: return nhwc_s1(g, dtype, pl.a, x, w, y, false, pl.b, tune("DWCONV_TUNE_TW", 1), tune("DWCONV_TUNE_PF", 1), st);
     case V_NHWC_K3S2: return nhwc_k3s2(g, dtype, pl.a, x, w, y, false, pl.b, st);
+    case V_NCHW_FWD: return nchw_fwd(g, dtype, x, w, y, false, pl.b, st);
     default: return generic_fwd(g, layout, dtype, x, w, y, st);
     }
 }
@@ -117,8 +166,10 @@ hipError_t launch_bwd_data(const Plan &pl, const Geom &g, int layout, int dtype,
                            void *dx, hipStream_t st)
 {
     switch (pl.variant) {
-    case V_NHWC_S1: return nhwc_s1(g, dtype, pl.a, dy, w, dx, true, pl.b, st);
+    case V_NHWC_S1: return nhwc_s1(g, dtype, pl.a, dy, w, dx, true, pl.b, tune("DWCONV_TUNE_TW", 1), tune("DWCONV_TUNE_PF", 1), st);
     case V_NHWC_K3S2: return nhwc_k3s2(g, dtype, pl.a, dy, w, dx, true, pl.b, st);
+    case V_NCHW_FWD: return nchw_fwd(g, dtype, dy, w, dx, true, pl.b, st);
+    case V_NCHW_BWD_DATA_K3S2: return nchw_bwd_data_k3s2(g, dtype, dy, w, dx, pl.b, st);
     default: return generic_bwd_data(g, layout, dtype, dy, w, dx, st);
     }
 }
@@ -128,6 +179,7 @@ hipError_t launch_bwd_filter(const Plan &pl, const Geom &g, int layout, int dtyp
 {
     switch (pl.variant) {
     case V_NHWC_BWD_FILTER: return nhwc_bwd_filter(g, dtype, pl.a, x, dy, ws, pl.b, pl.c, st);
+    case V_NCHW_BWD_FILTER: return nchw_bwd_filter(g, dtype, x, dy, ws, pl.b, pl.c, st);
     default: return generic_bwd_filter(g, layout, dtype, x, dy, ws, pl.parts, st);
     }
 }

@@ -10,6 +10,9 @@ enum Variant {
     V_NHWC_S1,          // a = V, b = TH
     V_NHWC_K3S2,        // a = V, b = TH
     V_NHWC_BWD_FILTER,  // a = V, b = TH, c = NI
+    V_NCHW_FWD,         // b = TR (forward, or backward-data with the filter rotated)
+    V_NCHW_BWD_DATA_K3S2,  // b = TR
+    V_NCHW_BWD_FILTER,  // b = TR, c = NI
 };
 
 struct Plan {
