@@ -136,29 +136,37 @@ __global__ __launch_bounds__(256) void k_generic_bwd_filter_nhwc(Geom g, const T
         ws[(size_t)part * (g.O * g.K * g.K) + tap * g.O + o] = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
 }
 
-// Stage 2: dw[j] = sum_p ws[p*J + j].  A block owns 16 consecutive j; 16 threads per j take the
-// partials p = r, r+16, r+32, ... in order, then the 16 sub-sums are added in a fixed tree.
+// Stage 2: dw[j] = sum_p ws[p*J + j].  A block owns JT consecutive j; PT = 256/JT threads per j
+// take the partials p = r, r+PT, r+2PT, ... eight at a time (eight independent loads in flight,
+// added in a fixed tree), then the PT sub-sums are added in a fixed tree through LDS.
+template <int JT>
 __global__ __launch_bounds__(256) void k_reduce_partials(const float *__restrict__ ws, int parts, int J,
                                                          float *__restrict__ dw)
 {
-    __shared__ float red[16][17];
-    const int jj = threadIdx.x & 15, r = threadIdx.x >> 4;
-    const int j = blockIdx.x * 16 + jj;
+    constexpr int PT = 256 / JT;
+    __shared__ float red[PT][JT + 1];
+    const int jj = threadIdx.x % JT, r = threadIdx.x / JT;
+    const int j = blockIdx.x * JT + jj;
     float acc = 0.f;
-    if (j < J)
-        for (int p = r; p < parts; p += 16) acc += ws[(size_t)p * J + j];
+    if (j < J) {
+        const float *p0 = ws + j;
+        int p = r;
+        for (; p + 7 * PT < parts; p += 8 * PT) {
+            float v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = p0[(size_t)(p + i * PT) * J];
+            acc += ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
+        }
+        for (; p < parts; p += PT) acc += p0[(size_t)p * J];
+    }
     red[r][jj] = acc;
     __syncthreads();
-    if (r == 0 && j < J) {
-        float s[16];
-#pragma unroll
-        for (int i = 0; i < 16; ++i) s[i] = red[i][jj];
-#pragma unroll
-        for (int w = 8; w >= 1; w >>= 1)
-#pragma unroll
-            for (int i = 0; i < w; ++i) s[i] += s[i + w];
-        dw[j] = s[0];
+    // tree over the PT sub-sums: thread (r, jj) adds red[r + half]
+    for (int half = PT / 2; half >= 1; half >>= 1) {
+        if (r < half) red[r][jj] += red[r + half][jj];
+        __syncthreads();
     }
+    if (r == 0 && j < J) dw[j] = red[0][jj];
 }
 
 // ---- host side --------------------------------------------------------------------------------
@@ -220,8 +228,10 @@ hipError_t generic_bwd_filter(const Geom &g, int layout, int dtype, const void *
 
 hipError_t reduce_partials(const float *ws, int parts, int J, float *dw, hipStream_t st)
 {
-    dim3 grid((J + 15) / 16), block(256);
-    hipLaunchKernelGGL(k_reduce_partials, grid, block, 0, st, ws, parts, J, dw);
+    // small J: fewer j per block so that enough blocks exist to pull the partials in parallel
+    if (J >= 8192) hipLaunchKernelGGL(k_reduce_partials<16>, dim3((J + 15) / 16), dim3(256), 0, st, ws, parts, J, dw);
+    else if (J >= 2048) hipLaunchKernelGGL(k_reduce_partials<8>, dim3((J + 7) / 8), dim3(256), 0, st, ws, parts, J, dw);
+    else hipLaunchKernelGGL(k_reduce_partials<4>, dim3((J + 3) / 4), dim3(256), 0, st, ws, parts, J, dw);
     return hipGetLastError();
 }
 

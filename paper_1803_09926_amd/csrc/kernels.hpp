@@ -47,4 +47,15 @@ int nchw_bwd_filter_parts(const Geom &g, int TR, int NI);   // 0 = unsupported
 hipError_t nchw_bwd_filter(const Geom &g, int dtype, const void *x, const void *dy, float *ws, int TR, int NI,
                            hipStream_t st);
 
+// ---- NCHW row-walk kernels for rows that are whole 16-byte vectors (nchw_direct.hip) -----------
+// pass: 0 fwd, 1 bwd_data, 2 bwd_filter.  Returns the columns per lane, 0 if not applicable.
+int nchwd_vec(const Geom &g, int dtype, int pass);
+hipError_t nchwd_s1(const Geom &g, int dtype, int V, const void *x, const void *w, void *y, bool flip, int TH,
+                    hipStream_t st);
+hipError_t nchwd_k3s2(const Geom &g, int dtype, int V, const void *in, const void *w, void *out, bool bwd, int TH,
+                      hipStream_t st);
+void nchwd_bwd_filter_tiling(const Geom &g, int V, int TH, int *sg_log2, int *nstrips, int *rounds, int *parts);
+hipError_t nchwd_bwd_filter(const Geom &g, int dtype, int V, const void *x, const void *dy, float *ws, int TH,
+                            hipStream_t st);
+
 }  // namespace dwc

@@ -32,22 +32,8 @@ struct Unit {
     int go0, golen;      // second range: output (or dy for the filter gradient)
 };
 
-// Global range [g0, g0+len) -> LDS, element e at lds_unit[e - a0] with a0 = g0 rounded down to 16
-// bytes.  `a` is the vector's first element.  The tensor's last partial vector uses scalar loads.
-template <typename T>
-__device__ __forceinline__ void load_vec_to_lds(const T *__restrict__ src, int total, int a, float *lds)
-{
-    constexpr int VE = Elems<T>::VE;
-    float v[VE];
-    if (a + VE <= total) {
-        Vec<T, VE>::load(src + a, v);
-    } else {
-#pragma unroll
-        for (int j = 0; j < VE; ++j) v[j] = (a + j < total) ? ldf(src + a + j) : 0.f;
-    }
-#pragma unroll
-    for (int j = 0; j < VE; j += 4) *reinterpret_cast<float4 *>(lds + j) = make_float4(v[j], v[j + 1], v[j + 2], v[j + 3]);
-}
+// A unit's global range [g0, g0+len) sits in LDS with element e at area[e - a0], a0 = g0 rounded down to
+// 16 bytes, so that aligned 16-byte global vectors map to aligned LDS vectors.
 
 // LDS -> global: elements of the vector outside [g0, g1) belong to another unit and are skipped.
 template <typename T>
@@ -101,17 +87,44 @@ __device__ __forceinline__ Unit unit_of(const Geom &g, const TileGeom &tg, int u
     return u;
 }
 
+// Cooperative copy of every unit's input range into its LDS area.  Each lane first issues all of
+// its (up to BATCH) 16-byte loads, then writes them to LDS, so the loads overlap each other.
 template <typename T>
 __device__ __forceinline__ void tile_load(const T *__restrict__ src, int total, const Unit *units, int nu, int LA,
                                           float inv_lv, bool second, float *area)
 {
     constexpr int VE = Elems<T>::VE;
+    constexpr int BATCH = 16 / VE * 2;      // 8 vectors of fp32, 4 of bf16: 32 registers either way
     const int lv = LA / VE;
-    for (int idx = threadIdx.x; idx < nu * lv; idx += 256) {
-        const int u = __float2int_rd((idx + 0.5f) * inv_lv), i = idx - u * lv;
-        const int g0 = second ? units[u].go0 : units[u].gi0, len = second ? units[u].golen : units[u].gilen;
-        const int a = (g0 & ~(VE - 1)) + i * VE;
-        if (a < g0 + len) load_vec_to_lds<T>(src, total, a, area + u * LA + i * VE);
+    const int nvec = nu * lv;
+    for (int base = 0; base < nvec; base += BATCH * 256) {
+        float v[BATCH][VE];
+        int dst[BATCH];
+#pragma unroll
+        for (int it = 0; it < BATCH; ++it) {
+            const int idx = base + it * 256 + (int)threadIdx.x;
+            dst[it] = -1;
+            if (idx < nvec) {
+                const int u = __float2int_rd((idx + 0.5f) * inv_lv), i = idx - u * lv;
+                const int g0 = second ? units[u].go0 : units[u].gi0, len = second ? units[u].golen : units[u].gilen;
+                const int a = (g0 & ~(VE - 1)) + i * VE;
+                if (a < g0 + len) {
+                    dst[it] = u * LA + i * VE;
+                    if (a + VE <= total) Vec<T, VE>::load(src + a, v[it]);
+                    else {
+#pragma unroll
+                        for (int j = 0; j < VE; ++j) v[it][j] = (a + j < total) ? ldf(src + a + j) : 0.f;
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < BATCH; ++it)
+            if (dst[it] >= 0) {
+#pragma unroll
+                for (int j = 0; j < VE; j += 4)
+                    *reinterpret_cast<float4 *>(area + dst[it] + j) = make_float4(v[it][j], v[it][j + 1], v[it][j + 2], v[it][j + 3]);
+            }
     }
 }
 
@@ -164,22 +177,61 @@ __global__ __launch_bounds__(256) void k_nchw_fwd(Geom g, TileGeom tg, const T *
             const float *base = lin + u * tg.LIN + (un.gi0 & (VE - 1));     // element (r_lo, 0)
             float *obase = lout + u * tg.LOUT + (un.go0 & (VE - 1));         // element (oh0, 0)
             const int iw0 = c * S - g.p;
+            // out-of-image taps read a clamped (valid) LDS address and are zeroed with a select
             bool colok[K];
+            int coff[K];
 #pragma unroll
-            for (int kw = 0; kw < K; ++kw) colok[kw] = iw0 + kw >= 0 && iw0 + kw < g.W;
-            for (int oh = un.oh0; oh < un.oh1; ++oh) {
-                float acc = 0.f;
+            for (int kw = 0; kw < K; ++kw) {
+                colok[kw] = iw0 + kw >= 0 && iw0 + kw < g.W;
+                coff[kw] = colok[kw] ? iw0 + kw : 0;
+            }
+            const int r_hi = un.r_lo + un.gilen / g.W - 1;   // last input row held in LDS
+            auto read_row = [&](int r, float (&row)[K]) {
+                const int rr = min(max(r, un.r_lo), r_hi);
+                const bool rowok = rr == r && r_hi >= un.r_lo;
+                const float *rp = base + (rowok ? rr - un.r_lo : 0) * g.W;
 #pragma unroll
-                for (int kh = 0; kh < K; ++kh) {
-                    const int ih = oh * S - g.p + kh;
-                    if (ih >= 0 && ih < g.H) {
-                        const float *rp = base + (ih - un.r_lo) * g.W + iw0;
-#pragma unroll
-                        for (int kw = 0; kw < K; ++kw)
-                            if (colok[kw]) acc = fmaf(wr[kh][kw], rp[kw], acc);
-                    }
+                for (int kw = 0; kw < K; ++kw) {
+                    const float t = rp[coff[kw]];
+                    row[kw] = (rowok && colok[kw]) ? t : 0.f;
                 }
-                obase[(oh - un.oh0) * g.Wo + c] = acc;
+            };
+            if constexpr (S == 1) {
+                // input row r is tap row kh of output row r + p - kh: K-1 rotating partial sums
+                float acc[K - 1 > 0 ? K - 1 : 1];
+#pragma unroll
+                for (int j = 0; j < K - 1; ++j) acc[j] = 0.f;
+                const int r0 = un.oh0 - g.p, r1 = un.oh1 - g.p + K - 1;     // rows [r0, r1)
+#pragma unroll 4
+                for (int r = r0; r < r1; ++r) {
+                    float row[K];
+                    read_row(r, row);
+                    float out = (K > 1) ? acc[0] : 0.f;
+#pragma unroll
+                    for (int kw = 0; kw < K; ++kw) out = fmaf(wr[K - 1][kw], row[kw], out);
+#pragma unroll
+                    for (int j = 0; j < K - 1; ++j) {
+                        float t = (j + 1 < K - 1) ? acc[j + 1] : 0.f;
+#pragma unroll
+                        for (int kw = 0; kw < K; ++kw) t = fmaf(wr[K - 2 - j][kw], row[kw], t);
+                        acc[j] = t;
+                    }
+                    const int oh = r + g.p - (K - 1);
+                    if (oh >= un.oh0) obase[(oh - un.oh0) * g.Wo + c] = out;
+                }
+            } else {
+#pragma unroll 2
+                for (int oh = un.oh0; oh < un.oh1; ++oh) {
+                    float rows[K][K];
+#pragma unroll
+                    for (int kh = 0; kh < K; ++kh) read_row(oh * S - g.p + kh, rows[kh]);
+                    float acc = 0.f;
+#pragma unroll
+                    for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+                        for (int kw = 0; kw < K; ++kw) acc = fmaf(wr[kh][kw], rows[kh][kw], acc);
+                    obase[(oh - un.oh0) * g.Wo + c] = acc;
+                }
             }
         }
     }

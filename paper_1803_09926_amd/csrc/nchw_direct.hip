@@ -1,0 +1,506 @@
+// NCHW "row-walk" kernels for planes whose rows are a whole number of 16-byte vectors.
+// A lane owns V adjacent columns of one plane and walks down the rows of its strip.  Per input
+// row it loads one aligned V-wide vector plus the few neighbour elements left and right of it
+// (the L1 serves those), rows ahead of the row being consumed.  The vector ALU budget is what
+// shapes these kernels: at full HBM rate a CU retires about one output element per clock and can
+// issue 64 lane-operations per clock, so everything besides the K*K multiply-adds per element
+// (addressing, edge handling) is amortised over the V outputs of a lane.
+#include "kernels.hpp"
+
+namespace dwc {
+
+static inline int ceil_div_h(int a, int b) { return (a + b - 1) / b; }
+
+// flat lane index -> (plane, strip, vector column)
+struct Lane { int plane, strip, c4; bool valid; };
+__device__ __forceinline__ Lane lane_of(unsigned nblocks, int ncols, int nstrips, int nplanes)
+{
+    const unsigned lb = xcd_remap(blockIdx.x, nblocks);
+    const unsigned f = lb * 256u + threadIdx.x;
+    Lane l;
+    const unsigned ps = f / (unsigned)ncols;
+    l.c4 = f - ps * ncols;
+    l.plane = ps / (unsigned)nstrips;
+    l.strip = ps - l.plane * nstrips;
+    l.valid = l.plane < nplanes;
+    return l;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Forward, stride 1, "same" padding (K odd, pad (K-1)/2), any multiplier; FLIP = filter rotated
+// by 180 degrees = backward-data of the same layer (multiplier 1).
+// ---------------------------------------------------------------------------------------------
+template <typename T, int V, int K, int PF, bool FLIP>
+__global__ __launch_bounds__(256) void k_nchwd_s1(Geom g, const T *__restrict__ x, const T *__restrict__ w,
+                                                  T *__restrict__ y, int TH, int nstrips, unsigned nblocks)
+{
+    constexpr int P = (K - 1) / 2;
+    constexpr int NW = V + 2 * P;       // window: P left neighbours, V own columns, P right neighbours
+    constexpr int R = PF + 1;
+    const int W4 = g.W / V;
+    const Lane ln = lane_of(nblocks, W4, nstrips, g.N * g.O);
+    if (!ln.valid) return;
+    const int n = ln.plane / g.O, o = ln.plane - n * g.O;
+    const int plane_in = n * g.C + o / g.m;
+
+    float wr[K][K];
+#pragma unroll
+    for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < K; ++kw) wr[kh][kw] = ldf(w + (o * K + (FLIP ? K - 1 - kh : kh)) * K + (FLIP ? K - 1 - kw : kw));
+
+    const bool has_left = ln.c4 > 0, has_right = ln.c4 < W4 - 1;
+    const T *xin = x + (size_t)plane_in * g.H * g.W + ln.c4 * V;
+    T *yout = y + (size_t)ln.plane * g.H * g.W + ln.c4 * V;
+    const int oh0 = ln.strip * TH, oh1 = min(g.H, oh0 + TH);
+
+    // neighbour offsets, clamped into the lane's own vector when they fall outside the row
+    int loff[P > 0 ? P : 1], roff[P > 0 ? P : 1];
+#pragma unroll
+    for (int i = 0; i < P; ++i) { loff[i] = has_left ? -(P - i) : 0; roff[i] = has_right ? V + i : V - 1; }
+
+    float ring[R][NW];
+    auto load_row = [&](int r, float (&dst)[NW]) {
+        const int rr = min(max(r, 0), g.H - 1);
+        const bool rowok = rr == r;
+        const T *rp = xin + (size_t)rr * g.W;
+        float mid[V];
+        Vec<T, V>::load(rp, mid);
+#pragma unroll
+        for (int i = 0; i < P; ++i) {
+            const float a = ldf(rp + loff[i]), b = ldf(rp + roff[i]);
+            dst[i] = (rowok && has_left) ? a : 0.f;
+            dst[P + V + i] = (rowok && has_right) ? b : 0.f;
+        }
+#pragma unroll
+        for (int v = 0; v < V; ++v) dst[P + v] = rowok ? mid[v] : 0.f;
+    };
+
+    float acc[K - 1 > 0 ? K - 1 : 1][V];
+#pragma unroll
+    for (int j = 0; j < K - 1; ++j)
+#pragma unroll
+        for (int v = 0; v < V; ++v) acc[j][v] = 0.f;
+
+    const int r0 = oh0 - P, r1 = oh1 + P;
+#pragma unroll
+    for (int j = 0; j < PF; ++j)
+        if (r0 + j < r1) load_row(r0 + j, ring[j]);
+#pragma unroll 1
+    for (int base = r0; base < r1; base += R) {
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            const int r = base + j;
+            if (r < r1) {
+                if (r + PF < r1) load_row(r + PF, ring[(j + PF) % R]);
+                const float (&cur)[NW] = ring[j];
+                float out[V];
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    float s = (K > 1) ? acc[0][v] : 0.f;
+#pragma unroll
+                    for (int kw = 0; kw < K; ++kw) s = fmaf(wr[K - 1][kw], cur[v + kw], s);
+                    out[v] = s;
+                }
+#pragma unroll
+                for (int jj = 0; jj < K - 1; ++jj)
+#pragma unroll
+                    for (int v = 0; v < V; ++v) {
+                        float s = (jj + 1 < K - 1) ? acc[jj + 1][v] : 0.f;
+#pragma unroll
+                        for (int kw = 0; kw < K; ++kw) s = fmaf(wr[K - 2 - jj][kw], cur[v + kw], s);
+                        acc[jj][v] = s;
+                    }
+                const int oh = r - P;
+                if (oh >= oh0) Vec<T, V>::store(yout + (size_t)oh * g.W, out);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Forward, 3x3, stride 2, pad 1, W even.  A lane owns V adjacent output columns and walks down
+// the output rows: it needs input columns 2*V*c4 - 1 .. 2*V*c4 + 2V - 1 of rows 2oh-1, 2oh, 2oh+1
+// (row 2oh+1 is reused as the top row of output row oh+1).
+// ---------------------------------------------------------------------------------------------
+template <typename T, int V>
+__global__ __launch_bounds__(256) void k_nchwd_fwd_k3s2(Geom g, const T *__restrict__ x, const T *__restrict__ w,
+                                                        T *__restrict__ y, int TH, int nstrips, unsigned nblocks)
+{
+    constexpr int NW = 2 * V + 1;
+    const int Wo4 = g.Wo / V;
+    const Lane ln = lane_of(nblocks, Wo4, nstrips, g.N * g.O);
+    if (!ln.valid) return;
+    const int n = ln.plane / g.O, o = ln.plane - n * g.O;
+    const int plane_in = n * g.C + o / g.m;
+    float wr[3][3];
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) wr[kh][kw] = ldf(w + (o * 3 + kh) * 3 + kw);
+    const bool has_left = ln.c4 > 0;
+    const T *xin = x + (size_t)plane_in * g.H * g.W + ln.c4 * 2 * V;
+    T *yout = y + (size_t)ln.plane * g.Ho * g.Wo + ln.c4 * V;
+    const int oh0 = ln.strip * TH, oh1 = min(g.Ho, oh0 + TH);
+    const int loff = has_left ? -1 : 0;
+
+    auto load_row = [&](int r, float (&dst)[NW]) {
+        const int rr = min(max(r, 0), g.H - 1);
+        const bool rowok = rr == r;
+        const T *rp = xin + (size_t)rr * g.W;
+        float a[V], b[V];
+        Vec<T, V>::load(rp, a);
+        Vec<T, V>::load(rp + V, b);
+        const float l = ldf(rp + loff);
+        dst[0] = (rowok && has_left) ? l : 0.f;
+#pragma unroll
+        for (int v = 0; v < V; ++v) { dst[1 + v] = rowok ? a[v] : 0.f; dst[1 + V + v] = rowok ? b[v] : 0.f; }
+    };
+
+    float carry[V], re[2][NW], ro[2][NW];
+    {
+        float top[NW];
+        load_row(2 * oh0 - 1, top);
+#pragma unroll
+        for (int v = 0; v < V; ++v) carry[v] = fmaf(wr[0][0], top[2 * v], fmaf(wr[0][1], top[2 * v + 1], wr[0][2] * top[2 * v + 2]));
+    }
+    load_row(2 * oh0, re[0]);
+    load_row(2 * oh0 + 1, ro[0]);
+#pragma unroll 1
+    for (int base = oh0; base < oh1; base += 2) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int oh = base + j;
+            if (oh < oh1) {
+                if (oh + 1 < oh1) { load_row(2 * oh + 2, re[j ^ 1]); load_row(2 * oh + 3, ro[j ^ 1]); }
+                float out[V];
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    float s = carry[v];
+                    s = fmaf(wr[1][0], re[j][2 * v], s); s = fmaf(wr[1][1], re[j][2 * v + 1], s); s = fmaf(wr[1][2], re[j][2 * v + 2], s);
+                    s = fmaf(wr[2][0], ro[j][2 * v], s); s = fmaf(wr[2][1], ro[j][2 * v + 1], s); s = fmaf(wr[2][2], ro[j][2 * v + 2], s);
+                    out[v] = s;
+                    carry[v] = fmaf(wr[0][0], ro[j][2 * v], fmaf(wr[0][1], ro[j][2 * v + 1], wr[0][2] * ro[j][2 * v + 2]));
+                }
+                Vec<T, V>::store(yout + (size_t)oh * g.Wo, out);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Backward-data, 3x3, stride 2, pad 1, multiplier 1, W = 2*Wo, H = 2*Ho.  A lane owns V adjacent
+// dy columns b and walks down dy rows a; it writes dx columns 2*V*c4 .. 2*V*c4 + 2V - 1 of rows
+// 2a and 2a+1 as one 16-byte vector per row (the pass is write-dominated, so the stores are the
+// ones kept contiguous across lanes):
+//   dx[2a  ][2b  ] = w11 dy[a][b]
+//   dx[2a  ][2b+1] = w10 dy[a][b+1] + w12 dy[a][b]
+//   dx[2a+1][2b  ] = w01 dy[a+1][b] + w21 dy[a][b]
+//   dx[2a+1][2b+1] = w00 dy[a+1][b+1] + w02 dy[a+1][b] + w20 dy[a][b+1] + w22 dy[a][b]
+// ---------------------------------------------------------------------------------------------
+template <typename T, int V>
+__global__ __launch_bounds__(256) void k_nchwd_bwd_data_k3s2(Geom g, const T *__restrict__ dy, const T *__restrict__ w,
+                                                             T *__restrict__ dx, int TH, int nstrips, unsigned nblocks)
+{
+    const int Wo4 = g.Wo / V;
+    const Lane ln = lane_of(nblocks, Wo4, nstrips, g.N * g.C);
+    if (!ln.valid) return;
+    const int o = ln.plane % g.C;
+    float wr[3][3];
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) wr[kh][kw] = ldf(w + (o * 3 + kh) * 3 + kw);
+    const bool has_right = ln.c4 < Wo4 - 1;
+    const T *dyin = dy + (size_t)ln.plane * g.Ho * g.Wo + ln.c4 * V;
+    T *dxout = dx + (size_t)ln.plane * g.H * g.W + ln.c4 * 2 * V;
+    const int a0 = ln.strip * TH, a1 = min(g.Ho, a0 + TH);
+    const int roff = has_right ? V : V - 1;
+
+    auto load_row = [&](int a, float (&dst)[V + 1]) {
+        const int rr = min(a, g.Ho - 1);
+        const bool rowok = rr == a;
+        const T *rp = dyin + (size_t)rr * g.Wo;
+        float m[V];
+        Vec<T, V>::load(rp, m);
+        const float r = ldf(rp + roff);
+#pragma unroll
+        for (int v = 0; v < V; ++v) dst[v] = rowok ? m[v] : 0.f;
+        dst[V] = (rowok && has_right) ? r : 0.f;
+    };
+
+    float rowA[2][V + 1];
+    load_row(a0, rowA[0]);
+#pragma unroll 1
+    for (int base = a0; base < a1; base += 2) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int a = base + j;
+            if (a < a1) {
+                load_row(a + 1, rowA[j ^ 1]);
+                const float (&A)[V + 1] = rowA[j];
+                const float (&B)[V + 1] = rowA[j ^ 1];
+                float ev[2 * V], od[2 * V];   // dx rows 2a and 2a+1, the lane's 2V columns
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    ev[2 * v] = wr[1][1] * A[v];
+                    ev[2 * v + 1] = fmaf(wr[1][0], A[v + 1], wr[1][2] * A[v]);
+                    od[2 * v] = fmaf(wr[0][1], B[v], wr[2][1] * A[v]);
+                    od[2 * v + 1] = fmaf(wr[0][0], B[v + 1], fmaf(wr[0][2], B[v], fmaf(wr[2][0], A[v + 1], wr[2][2] * A[v])));
+                }
+                T *rp = dxout + (size_t)(2 * a) * g.W;
+                Vec<T, 2 * V>::store(rp, ev);
+                Vec<T, 2 * V>::store(rp + g.W, od);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Backward-filter stage 1, 3x3, stride S in {1 ("same" pad), 2 (pad 1, W even)}.
+// grid = (parts, O).  A block works on ONE output channel: its 256 lanes are 256/SG sub-groups of
+// SG lanes (SG = power of two >= vectors per row); a sub-group takes one (image, strip) work
+// item per round and the block walks `rounds` rounds, so partial sums stay in registers.  At the
+// end all 256 lanes hold sums for the same channel: wavefront butterfly, LDS across the four
+// wavefronts, one partial per block at ws[part][o][kh][kw].  Fixed order throughout.
+// ---------------------------------------------------------------------------------------------
+template <typename T, int V, int S>
+__global__ __launch_bounds__(256) void k_nchwd_bwd_filter_k3(Geom g, const T *__restrict__ x, const T *__restrict__ dy,
+                                                             float *__restrict__ ws, int TH, int nstrips, int sg_log2,
+                                                             int rounds)
+{
+    __shared__ float red[4][9];
+    constexpr int NW = (S == 1) ? V + 2 : 2 * V + 1;
+    const int o = blockIdx.y, part = blockIdx.x;
+    const int SG = 1 << sg_log2, nsg = 256 >> sg_log2;
+    const int sg = threadIdx.x >> sg_log2, c4 = threadIdx.x & (SG - 1);
+    const int ncols = g.Wo / V;                         // vectors per dy row
+    const int nitems = g.N * nstrips;
+    const int c_in = o / g.m;
+    const bool has_left = c4 > 0, has_right = c4 < ncols - 1;
+
+    float acc[3][3];
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) acc[kh][kw] = 0.f;
+
+    if (c4 < ncols) {
+        for (int rd = 0; rd < rounds; ++rd) {
+            const int item = (part * rounds + rd) * nsg + sg;
+            if (item >= nitems) break;
+            const int n = item / nstrips, strip = item - n * nstrips;
+            const int oh0 = strip * TH, oh1 = min(g.Ho, oh0 + TH);
+            const T *xin = x + ((size_t)n * g.C + c_in) * g.H * g.W + c4 * V * S;
+            const T *dyin = dy + ((size_t)n * g.O + o) * g.Ho * g.Wo + c4 * V;
+            const int loff = has_left ? -1 : 0, roff = has_right ? V : V - 1;
+            auto load_x = [&](int r, float (&dst)[NW]) {
+                const int rr = min(max(r, 0), g.H - 1);
+                const bool rowok = rr == r;
+                const T *rp = xin + (size_t)rr * g.W;
+                if constexpr (S == 1) {
+                    float m[V];
+                    Vec<T, V>::load(rp, m);
+                    const float l = ldf(rp + loff), rt = ldf(rp + roff);
+                    dst[0] = (rowok && has_left) ? l : 0.f;
+                    dst[V + 1] = (rowok && has_right) ? rt : 0.f;
+#pragma unroll
+                    for (int v = 0; v < V; ++v) dst[1 + v] = rowok ? m[v] : 0.f;
+                } else {
+                    float a[V], b[V];
+                    Vec<T, V>::load(rp, a);
+                    Vec<T, V>::load(rp + V, b);
+                    const float l = ldf(rp + loff);
+                    dst[0] = (rowok && has_left) ? l : 0.f;
+#pragma unroll
+                    for (int v = 0; v < V; ++v) { dst[1 + v] = rowok ? a[v] : 0.f; dst[1 + V + v] = rowok ? b[v] : 0.f; }
+                }
+            };
+            auto load_dy = [&](int oh, float (&dst)[V]) {
+                const int rr = min(oh, oh1 - 1);
+                Vec<T, V>::load(dyin + (size_t)rr * g.Wo, dst);
+                const bool ok = rr == oh;
+#pragma unroll
+                for (int v = 0; v < V; ++v) dst[v] = ok ? dst[v] : 0.f;
+            };
+            // x rows oh*S-1, oh*S, oh*S+1 meet dy row oh at tap rows 0, 1, 2.
+            float xa[NW], xb[NW], xc[2][NW], d[2][V], xs[2][NW];
+            load_x(oh0 * S - 1, xa);
+            if constexpr (S == 1) {
+                load_x(oh0, xb);
+                load_x(oh0 + 1, xc[0]); load_dy(oh0, d[0]);
+#pragma unroll 1
+                for (int base = oh0; base < oh1; base += 2) {
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        const int oh = base + j;
+                        if (oh < oh1) {
+                            if (oh + 1 < oh1) { load_x(oh + 2, xc[j ^ 1]); load_dy(oh + 1, d[j ^ 1]); }
+#pragma unroll
+                            for (int v = 0; v < V; ++v)
+#pragma unroll
+                                for (int kw = 0; kw < 3; ++kw) {
+                                    acc[0][kw] = fmaf(d[j][v], xa[v + kw], acc[0][kw]);
+                                    acc[1][kw] = fmaf(d[j][v], xb[v + kw], acc[1][kw]);
+                                    acc[2][kw] = fmaf(d[j][v], xc[j][v + kw], acc[2][kw]);
+                                }
+#pragma unroll
+                            for (int i = 0; i < NW; ++i) { xa[i] = xb[i]; xb[i] = xc[j][i]; }
+                        }
+                    }
+                }
+            } else {
+                load_x(2 * oh0, xs[0]); load_x(2 * oh0 + 1, xc[0]); load_dy(oh0, d[0]);
+#pragma unroll 1
+                for (int base = oh0; base < oh1; base += 2) {
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        const int oh = base + j;
+                        if (oh < oh1) {
+                            if (oh + 1 < oh1) { load_x(2 * oh + 2, xs[j ^ 1]); load_x(2 * oh + 3, xc[j ^ 1]); load_dy(oh + 1, d[j ^ 1]); }
+#pragma unroll
+                            for (int v = 0; v < V; ++v)
+#pragma unroll
+                                for (int kw = 0; kw < 3; ++kw) {
+                                    acc[0][kw] = fmaf(d[j][v], xa[2 * v + kw], acc[0][kw]);
+                                    acc[1][kw] = fmaf(d[j][v], xs[j][2 * v + kw], acc[1][kw]);
+                                    acc[2][kw] = fmaf(d[j][v], xc[j][2 * v + kw], acc[2][kw]);
+                                }
+#pragma unroll
+                            for (int i = 0; i < NW; ++i) xa[i] = xc[j][i];
+                        }
+                    }
+                }
+            }
+        }
+    }
+
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) {
+            const float s = wave_sum(acc[kh][kw]);
+            if (lane == 0) red[wv][kh * 3 + kw] = s;
+        }
+    __syncthreads();
+    if (threadIdx.x < 9) {
+        const int t = threadIdx.x;
+        ws[((size_t)part * g.O + o) * 9 + t] = (red[0][t] + red[1][t]) + (red[2][t] + red[3][t]);
+    }
+}
+
+// ---- host side --------------------------------------------------------------------------------
+
+// vector width for the direct kernels (0 = not applicable): rows must be whole 16-byte vectors;
+// bf16 rows that are only a multiple of 4 use 8-byte vectors.
+int nchwd_vec(const Geom &g, int dtype, int pass)
+{
+    const bool s1 = g.s == 1 && (g.K == 3 || g.K == 5) && g.p == (g.K - 1) / 2;
+    const bool s2 = g.s == 2 && g.K == 3 && g.p == 1 && g.W % 2 == 0 && g.H % 2 == 0;
+    if (!s1 && !s2) return 0;
+    if (pass == 1 && g.m != 1) return 0;
+    if (pass == 2 && g.K != 3) return 0;
+    if (g.H < 16) return 0;                      // small planes go to the LDS-tile kernels
+    const int wv = s1 ? g.W : g.Wo;              // the dimension that lanes split into vectors
+    if (s2 && pass == 1) {                       // dy columns per lane; dx is stored 2V wide
+        if (dtype == DT_F32) return wv % 2 == 0 ? 2 : 0;
+        return wv % 4 == 0 ? 4 : 0;
+    }
+    if (dtype == DT_F32) return wv % 4 == 0 ? 4 : (s2 && wv % 2 == 0 ? 2 : 0);
+    return wv % 8 == 0 ? 8 : (wv % 4 == 0 ? 4 : 0);
+}
+
+template <typename T, int V, int K>
+static hipError_t go_s1(const Geom &g, const void *x, const void *w, void *y, bool flip, int TH, hipStream_t st)
+{
+    const int nstrips = ceil_div_h(g.H, TH);
+    const long long lanes = (long long)g.N * g.O * nstrips * (g.W / V);
+    const unsigned nblocks = (unsigned)((lanes + 255) / 256);
+    if (flip)
+        hipLaunchKernelGGL((k_nchwd_s1<T, V, K, 2, true>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, (const T *)w,
+                           (T *)y, TH, nstrips, nblocks);
+    else
+        hipLaunchKernelGGL((k_nchwd_s1<T, V, K, 2, false>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, (const T *)w,
+                           (T *)y, TH, nstrips, nblocks);
+    return hipGetLastError();
+}
+
+hipError_t nchwd_s1(const Geom &g, int dtype, int V, const void *x, const void *w, void *y, bool flip, int TH,
+                    hipStream_t st)
+{
+    if (dtype == DT_F32 && V == 4) return g.K == 3 ? go_s1<float, 4, 3>(g, x, w, y, flip, TH, st) : go_s1<float, 4, 5>(g, x, w, y, flip, TH, st);
+    if (dtype == DT_BF16 && V == 8) return g.K == 3 ? go_s1<bf16_t, 8, 3>(g, x, w, y, flip, TH, st) : go_s1<bf16_t, 8, 5>(g, x, w, y, flip, TH, st);
+    if (dtype == DT_BF16 && V == 4) return g.K == 3 ? go_s1<bf16_t, 4, 3>(g, x, w, y, flip, TH, st) : go_s1<bf16_t, 4, 5>(g, x, w, y, flip, TH, st);
+    return hipErrorInvalidValue;
+}
+
+hipError_t nchwd_k3s2(const Geom &g, int dtype, int V, const void *in, const void *w, void *out, bool bwd, int TH,
+                      hipStream_t st)
+{
+    const int nstrips = ceil_div_h(g.Ho, TH);
+    const long long lanes = (long long)g.N * g.O * nstrips * (g.Wo / V);
+    const unsigned nblocks = (unsigned)((lanes + 255) / 256);
+#define GO(KERNEL, T, VV) hipLaunchKernelGGL((KERNEL<T, VV>), dim3(nblocks), dim3(256), 0, st, g, (const T *)in, \
+                                             (const T *)w, (T *)out, TH, nstrips, nblocks)
+    if (!bwd) {
+        if (dtype == DT_F32 && V == 4) GO(k_nchwd_fwd_k3s2, float, 4);
+        else if (dtype == DT_F32 && V == 2) GO(k_nchwd_fwd_k3s2, float, 2);
+        else if (dtype == DT_BF16 && V == 8) GO(k_nchwd_fwd_k3s2, bf16_t, 8);
+        else if (dtype == DT_BF16 && V == 4) GO(k_nchwd_fwd_k3s2, bf16_t, 4);
+        else return hipErrorInvalidValue;
+    } else {
+        // V = dy columns per lane; the lane stores 2V dx columns as one 16-byte vector per row
+        if (dtype == DT_F32 && V == 2) GO(k_nchwd_bwd_data_k3s2, float, 2);
+        else if (dtype == DT_BF16 && V == 4) GO(k_nchwd_bwd_data_k3s2, bf16_t, 4);
+        else return hipErrorInvalidValue;
+    }
+#undef GO
+    return hipGetLastError();
+}
+
+// Filter gradient tiling: sub-group width, rounds per block and number of partials.
+void nchwd_bwd_filter_tiling(const Geom &g, int V, int TH, int *sg_log2, int *nstrips, int *rounds, int *parts)
+{
+    const int ncols = g.Wo / V;
+    int lg = 0;
+    while ((1 << lg) < ncols) ++lg;
+    *sg_log2 = lg;
+    *nstrips = ceil_div_h(g.Ho, TH);
+    const int nsg = 256 >> lg;
+    const int nitems = g.N * *nstrips;
+    // enough blocks for ~8 per CU over the O channels, but at least 2 rounds per block
+    int want_parts = (2048 + g.O - 1) / g.O;
+    if (want_parts < 1) want_parts = 1;
+    int r = nitems / (nsg * want_parts);
+    if (r < 1) r = 1;
+    *rounds = r;
+    *parts = ceil_div_h(nitems, nsg * r);
+}
+
+hipError_t nchwd_bwd_filter(const Geom &g, int dtype, int V, const void *x, const void *dy, float *ws, int TH,
+                            hipStream_t st)
+{
+    int lg, nstrips, rounds, parts;
+    nchwd_bwd_filter_tiling(g, V, TH, &lg, &nstrips, &rounds, &parts);
+    if (lg > 8) return hipErrorInvalidValue;
+    dim3 grid(parts, g.O);
+#define GO(T, VV, SS) hipLaunchKernelGGL((k_nchwd_bwd_filter_k3<T, VV, SS>), grid, dim3(256), 0, st, g, (const T *)x, \
+                                         (const T *)dy, ws, TH, nstrips, lg, rounds)
+    if (g.s == 1) {
+        if (dtype == DT_F32 && V == 4) GO(float, 4, 1);
+        else if (dtype == DT_BF16 && V == 8) GO(bf16_t, 8, 1);
+        else if (dtype == DT_BF16 && V == 4) GO(bf16_t, 4, 1);
+        else return hipErrorInvalidValue;
+    } else {
+        if (dtype == DT_F32 && V == 4) GO(float, 4, 2);
+        else if (dtype == DT_F32 && V == 2) GO(float, 2, 2);
+        else if (dtype == DT_BF16 && V == 8) GO(bf16_t, 8, 2);
+        else if (dtype == DT_BF16 && V == 4) GO(bf16_t, 4, 2);
+        else return hipErrorInvalidValue;
+    }
+#undef GO
+    return hipGetLastError();
+}
+
+}  // namespace dwc

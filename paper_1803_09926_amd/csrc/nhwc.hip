@@ -295,7 +295,7 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_data_k3s2(Geom g, const T *__r
 // workspace at [part][kh][kw][o].
 // S = 1: "same" padding, K odd.  S = 2: K = 3, pad = 1.
 // ---------------------------------------------------------------------------------------------
-template <typename T, int V, int K, int S>
+template <typename T, int V, int K, int S, int PF>
 __global__ __launch_bounds__(256) void k_nhwc_bwd_filter(Geom g, const T *__restrict__ x, const T *__restrict__ dy,
                                                          float *__restrict__ ws, int CT, int nctiles, int nowtiles,
                                                          int TH, int nstrips, int NI, unsigned nblocks)
@@ -322,73 +322,103 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_filter(Geom g, const T *__rest
             for (int v = 0; v < V; ++v) acc[kh][kw][v] = 0.f;
 
     if (active) {
+        // Out-of-image taps read a valid address (clamped row, the lane's own column) and are
+        // zeroed with a select, so every load is unconditional and can be issued rows ahead.
         bool colok[K];
+        int coloff[K];
 #pragma unroll
         for (int kw = 0; kw < K; ++kw) {
             const int iw = ow * S - P + kw;
             colok[kw] = iw >= 0 && iw < g.W;
+            coloff[kw] = (colok[kw] ? iw : ow * S) * g.C;
         }
         const int xrow = g.W * g.C, dyrow = g.Wo * g.C;
         const int oh0 = strip * TH, oh1 = min(g.Ho, oh0 + TH);
         const int n0 = ngroup * NI, n1 = min(g.N, n0 + NI);
         for (int n = n0; n < n1; ++n) {
-            const T *xin = x + (size_t)n * g.H * xrow + (ptrdiff_t)(ow * S - P) * g.C + cq * V;
+            const T *xin = x + (size_t)n * g.H * xrow + cq * V;
             const T *dyin = dy + ((size_t)n * g.Ho * g.Wo + ow) * g.C + cq * V;
             auto load_x = [&](int r, float (&dst)[K][V]) {
-                const bool rowok = r >= 0 && r < g.H;
+                const int rr = min(max(r, 0), g.H - 1);
+                const bool rowok = rr == r;
+                const T *rp = xin + (size_t)rr * xrow;
 #pragma unroll
                 for (int kw = 0; kw < K; ++kw) {
-                    if (rowok && colok[kw]) Vec<T, V>::load(xin + (ptrdiff_t)r * xrow + kw * g.C, dst[kw]);
-                    else {
+                    Vec<T, V>::load(rp + coloff[kw], dst[kw]);
+                    const bool ok = rowok && colok[kw];
 #pragma unroll
-                        for (int v = 0; v < V; ++v) dst[kw][v] = 0.f;
-                    }
+                    for (int v = 0; v < V; ++v) dst[kw][v] = ok ? dst[kw][v] : 0.f;
                 }
             };
+            auto load_dy = [&](int oh, float (&dst)[V]) {
+                const int rr = min(max(oh, oh0), oh1 - 1);
+                Vec<T, V>::load(dyin + (size_t)rr * dyrow, dst);
+                const bool ok = rr == oh;
+#pragma unroll
+                for (int v = 0; v < V; ++v) dst[v] = ok ? dst[v] : 0.f;
+            };
             if constexpr (S == 1) {
-                // input row r meets dy row r + P - kh at tap row kh; keep the K live dy rows
+                // input row r meets dy row r + P - kh at tap row kh; dyw holds the K live dy rows
+                constexpr int R = PF + 1;
                 float dyw[K][V];
 #pragma unroll
                 for (int kh = 0; kh < K; ++kh)
 #pragma unroll
                     for (int v = 0; v < V; ++v) dyw[kh][v] = 0.f;
-                for (int r = oh0 - P; r < oh1 + P; ++r) {
+                float xr[R][K][V], dr[R][V];
+                const int r0 = oh0 - P, r1 = oh1 + P;
 #pragma unroll
-                    for (int kh = K - 1; kh > 0; --kh)
+                for (int j = 0; j < PF; ++j)
+                    if (r0 + j < r1) { load_x(r0 + j, xr[j]); load_dy(r0 + j + P, dr[j]); }
+#pragma unroll 1
+                for (int base = r0; base < r1; base += R) {
 #pragma unroll
-                        for (int v = 0; v < V; ++v) dyw[kh][v] = dyw[kh - 1][v];
-                    const int oh = r + P;
-                    if (oh >= oh0 && oh < oh1) Vec<T, V>::load(dyin + (size_t)oh * dyrow, dyw[0]);
-                    else {
+                    for (int j = 0; j < R; ++j) {
+                        const int r = base + j;
+                        if (r < r1) {
+                            if (r + PF < r1) { load_x(r + PF, xr[(j + PF) % R]); load_dy(r + PF + P, dr[(j + PF) % R]); }
 #pragma unroll
-                        for (int v = 0; v < V; ++v) dyw[0][v] = 0.f;
+                            for (int kh = K - 1; kh > 0; --kh)
+#pragma unroll
+                                for (int v = 0; v < V; ++v) dyw[kh][v] = dyw[kh - 1][v];
+#pragma unroll
+                            for (int v = 0; v < V; ++v) dyw[0][v] = dr[j][v];
+#pragma unroll
+                            for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+                                for (int kw = 0; kw < K; ++kw)
+#pragma unroll
+                                    for (int v = 0; v < V; ++v)
+                                        acc[kh][kw][v] = fmaf(dyw[kh][v], xr[j][kw][v], acc[kh][kw][v]);
+                        }
                     }
-                    float xr[K][V];
-                    load_x(r, xr);
-#pragma unroll
-                    for (int kh = 0; kh < K; ++kh)
-#pragma unroll
-                        for (int kw = 0; kw < K; ++kw)
-#pragma unroll
-                            for (int v = 0; v < V; ++v) acc[kh][kw][v] = fmaf(dyw[kh][v], xr[kw][v], acc[kh][kw][v]);
                 }
             } else {
-                // output row oh meets input rows 2oh-1, 2oh, 2oh+1; row 2oh+1 is reused by oh+1
-                float xa[K][V], xb[K][V], xc[K][V], d[V];
+                // output row oh meets input rows 2oh-1, 2oh, 2oh+1; row 2oh+1 is reused by oh+1.
+                // The two new rows and the dy row of the next output row are loaded one step ahead.
+                float xa[K][V], xb[2][K][V], xc[2][K][V], d[2][V];
                 load_x(2 * oh0 - 1, xa);
-                for (int oh = oh0; oh < oh1; ++oh) {
-                    Vec<T, V>::load(dyin + (size_t)oh * dyrow, d);
-                    load_x(2 * oh, xb);
-                    load_x(2 * oh + 1, xc);
+                load_x(2 * oh0, xb[0]); load_x(2 * oh0 + 1, xc[0]); load_dy(oh0, d[0]);
+#pragma unroll 1
+                for (int base = oh0; base < oh1; base += 2) {
 #pragma unroll
-                    for (int kw = 0; kw < K; ++kw)
+                    for (int j = 0; j < 2; ++j) {
+                        const int oh = base + j;
+                        if (oh < oh1) {
+                            if (oh + 1 < oh1) {
+                                load_x(2 * oh + 2, xb[j ^ 1]); load_x(2 * oh + 3, xc[j ^ 1]); load_dy(oh + 1, d[j ^ 1]);
+                            }
 #pragma unroll
-                        for (int v = 0; v < V; ++v) {
-                            acc[0][kw][v] = fmaf(d[v], xa[kw][v], acc[0][kw][v]);
-                            acc[1][kw][v] = fmaf(d[v], xb[kw][v], acc[1][kw][v]);
-                            acc[2][kw][v] = fmaf(d[v], xc[kw][v], acc[2][kw][v]);
-                            xa[kw][v] = xc[kw][v];
+                            for (int kw = 0; kw < K; ++kw)
+#pragma unroll
+                                for (int v = 0; v < V; ++v) {
+                                    acc[0][kw][v] = fmaf(d[j][v], xa[kw][v], acc[0][kw][v]);
+                                    acc[1][kw][v] = fmaf(d[j][v], xb[j][kw][v], acc[1][kw][v]);
+                                    acc[2][kw][v] = fmaf(d[j][v], xc[j][kw][v], acc[2][kw][v]);
+                                    xa[kw][v] = xc[j][kw][v];
+                                }
                         }
+                    }
                 }
             }
         }
@@ -509,7 +539,7 @@ hipError_t nhwc_bwd_filter(const Geom &g, int dtype, int V, const void *x, const
     int CT, nctiles, nowtiles, nstrips, ngroups;
     nhwc_bwd_filter_tiling(g, V, TH, NI, &CT, &nctiles, &nowtiles, &nstrips, &ngroups);
     const unsigned nblocks = (unsigned)nctiles * nowtiles * nstrips * ngroups;
-#define GO(T, VV, KK, SS) hipLaunchKernelGGL((k_nhwc_bwd_filter<T, VV, KK, SS>), dim3(nblocks), dim3(256), 0, st, g, \
+#define GO(T, VV, KK, SS) hipLaunchKernelGGL((k_nhwc_bwd_filter<T, VV, KK, SS, 2>), dim3(nblocks), dim3(256), 0, st, g, \
                                              (const T *)x, (const T *)dy, ws, CT, nctiles, nowtiles, TH, nstrips, NI, nblocks)
     if (dtype == DT_F32) {
         if (g.K == 3 && g.s == 1) GO(float, 4, 3, 1);

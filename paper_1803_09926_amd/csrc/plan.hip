@@ -53,6 +53,13 @@ Plan plan_fwd(const Geom &g, int layout, int dtype)
 {
     Plan pl = {V_GENERIC, 0, 0, 0, 0, "generic"};
     if (layout == LAYOUT_NCHW) {
+        const int V = nchwd_vec(g, dtype, 0);
+        if (V) {
+            pl.a = V;
+            if (g.s == 1) { pl.variant = V_NCHWD_S1; pl.b = pick_th(g.H, (long long)g.N * g.O * (g.W / V)); pl.name = g.K == 3 ? "nchw_rowwalk_k3s1" : "nchw_rowwalk_k5s1"; }
+            else { pl.variant = V_NCHWD_K3S2; pl.b = pick_th(g.Ho, (long long)g.N * g.O * (g.Wo / V)); pl.name = "nchw_rowwalk_fwd_k3s2"; }
+            return pl;
+        }
         const int tr = nchw_pick_tr(g, nchw_fwd_supported);
         if (tr) { pl.variant = V_NCHW_FWD; pl.b = tr; pl.name = "nchw_tile_fwd"; }
         return pl;
@@ -74,6 +81,13 @@ Plan plan_bwd_data(const Geom &g, int layout, int dtype)
 {
     Plan pl = {V_GENERIC, 0, 0, 0, 0, "generic"};
     if (layout == LAYOUT_NCHW) {
+        const int V = nchwd_vec(g, dtype, 1);
+        if (V) {
+            pl.a = V;
+            if (g.s == 1) { pl.variant = V_NCHWD_S1; pl.b = pick_th(g.H, (long long)g.N * g.O * (g.W / V)); pl.name = g.K == 3 ? "nchw_rowwalk_k3s1_flip" : "nchw_rowwalk_k5s1_flip"; }
+            else { pl.variant = V_NCHWD_K3S2; pl.b = pick_th(g.Ho, (long long)g.N * g.O * (g.Wo / V)); pl.name = "nchw_rowwalk_bwd_data_k3s2"; }
+            return pl;
+        }
         if (g.m == 1 && same_pad_s1(g)) {
             const int tr = nchw_pick_tr(g, nchw_fwd_supported);
             if (tr) { pl.variant = V_NCHW_FWD; pl.b = tr; pl.name = "nchw_tile_fwd_flip"; }
@@ -100,6 +114,17 @@ Plan plan_bwd_filter(const Geom &g, int layout, int dtype)
 {
     Plan pl = {V_GENERIC, generic_bwd_filter_parts(g), 0, 0, 0, "generic"};
     if (layout == LAYOUT_NCHW) {
+        const int V = nchwd_vec(g, dtype, 2);
+        if (V) {
+            int TH = tune("DWCONV_TUNE_TH", g.Ho <= 28 ? g.Ho : 14);
+            int lg, nst, rounds, parts;
+            nchwd_bwd_filter_tiling(g, V, TH, &lg, &nst, &rounds, &parts);
+            if (lg <= 8 && (long long)parts * g.O * 9 * 4 <= (64ll << 20)) {
+                pl.variant = V_NCHWD_BWD_FILTER; pl.a = V; pl.b = TH; pl.parts = parts;
+                pl.name = g.s == 1 ? "nchw_rowwalk_bwd_filter_k3s1" : "nchw_rowwalk_bwd_filter_k3s2";
+                return pl;
+            }
+        }
         const int tr = nchw_pick_tr(g, fits_bwd_filter);
         if (tr) {
             // images per block: keep about 4096 blocks in the launch
@@ -158,6 +183,8 @@ hipError_t launch_fwd(const Plan &pl, const Geom &g, int layout, int dtype, cons
     case V_NHWC_S1: return nhwc_s1(g, dtype, pl.a, x, w, y, false, pl.b, tune("DWCONV_TUNE_TW", 1), tune("DWCONV_TUNE_PF", 1), st);
     case V_NHWC_K3S2: return nhwc_k3s2(g, dtype, pl.a, x, w, y, false, pl.b, st);
     case V_NCHW_FWD: return nchw_fwd(g, dtype, x, w, y, false, pl.b, st);
+    case V_NCHWD_S1: return nchwd_s1(g, dtype, pl.a, x, w, y, false, pl.b, st);
+    case V_NCHWD_K3S2: return nchwd_k3s2(g, dtype, pl.a, x, w, y, false, pl.b, st);
     default: return generic_fwd(g, layout, dtype, x, w, y, st);
     }
 }
@@ -169,6 +196,8 @@ hipError_t launch_bwd_data(const Plan &pl, const Geom &g, int layout, int dtype,
     case V_NHWC_S1: return nhwc_s1(g, dtype, pl.a, dy, w, dx, true, pl.b, tune("DWCONV_TUNE_TW", 1), tune("DWCONV_TUNE_PF", 1), st);
     case V_NHWC_K3S2: return nhwc_k3s2(g, dtype, pl.a, dy, w, dx, true, pl.b, st);
     case V_NCHW_FWD: return nchw_fwd(g, dtype, dy, w, dx, true, pl.b, st);
+    case V_NCHWD_S1: return nchwd_s1(g, dtype, pl.a, dy, w, dx, true, pl.b, st);
+    case V_NCHWD_K3S2: return nchwd_k3s2(g, dtype, pl.a, dy, w, dx, true, pl.b, st);
     case V_NCHW_BWD_DATA_K3S2: return nchw_bwd_data_k3s2(g, dtype, dy, w, dx, pl.b, st);
     default: return generic_bwd_data(g, layout, dtype, dy, w, dx, st);
     }
@@ -180,6 +209,7 @@ hipError_t launch_bwd_filter(const Plan &pl, const Geom &g, int layout, int dtyp
     switch (pl.variant) {
     case V_NHWC_BWD_FILTER: return nhwc_bwd_filter(g, dtype, pl.a, x, dy, ws, pl.b, pl.c, st);
     case V_NCHW_BWD_FILTER: return nchw_bwd_filter(g, dtype, x, dy, ws, pl.b, pl.c, st);
+    case V_NCHWD_BWD_FILTER: return nchwd_bwd_filter(g, dtype, pl.a, x, dy, ws, pl.b, st);
     default: return generic_bwd_filter(g, layout, dtype, x, dy, ws, pl.parts, st);
     }
 }

@@ -13,6 +13,9 @@ enum Variant {
     V_NCHW_FWD,         // b = TR (forward, or backward-data with the filter rotated)
     V_NCHW_BWD_DATA_K3S2,  // b = TR
     V_NCHW_BWD_FILTER,  // b = TR, c = NI
+    V_NCHWD_S1,         // a = V, b = TH
+    V_NCHWD_K3S2,       // a = V, b = TH
+    V_NCHWD_BWD_FILTER, // a = V, b = TH
 };
 
 struct Plan {
