@@ -58,4 +58,12 @@ void nchwd_bwd_filter_tiling(const Geom &g, int V, int TH, int *sg_log2, int *ns
 hipError_t nchwd_bwd_filter(const Geom &g, int dtype, int V, const void *x, const void *dy, float *ws, int TH,
                             hipStream_t st);
 
+// ---- NCHW small-plane kernels: rows of 7, 14 or 28 elements, 3x3 pad 1, multiplier 1 (nchw_small.hip)
+bool nchws_supported(const Geom &g, int pass);
+hipError_t nchws_fwd(const Geom &g, int dtype, const void *x, const void *w, void *y, bool flip, hipStream_t st);
+hipError_t nchws_bwd_data_s2(const Geom &g, int dtype, const void *dy, const void *w, void *dx, hipStream_t st);
+void nchws_bwd_filter_tiling(const Geom &g, int dtype, int *U, int *NI, int *parts);
+hipError_t nchws_bwd_filter(const Geom &g, int dtype, const void *x, const void *dy, float *ws, int U, int NI,
+                            hipStream_t st);
+
 }  // namespace dwc

@@ -1,0 +1,387 @@
+// NCHW kernels for small planes (rows of 7, 14 or 28 elements; 3x3 filters; multiplier 1).
+// Rows this short are not whole 16-byte vectors, but consecutive planes are contiguous, so a block
+// takes a run of whole planes as ONE flat range: aligned 16-byte loads into LDS (all of a lane's
+// loads issued before its first wait), then one lane per (plane, output row) computes the whole
+// row from LDS with the row width known at compile time (every tap is a multiply-add with a
+// fixed LDS offset, nothing else), stages it in LDS, and the block writes the flat output range
+// back with aligned 16-byte stores.
+#include "kernels.hpp"
+
+namespace dwc {
+
+template <typename T> struct ElemsS { static constexpr int VE = 16 / sizeof(T); };
+
+// Flat range [g0, g1) of `src` -> lds[e - a0], a0 = g0 rounded down to a 16-byte boundary.
+template <typename T>
+__device__ __forceinline__ void flat_load(const T *__restrict__ src, int total, int g0, int g1, float *lds)
+{
+    constexpr int VE = ElemsS<T>::VE;
+    constexpr int BATCH = 16 / VE * 2;
+    const int a0 = g0 & ~(VE - 1);
+    const int nvec = (g1 - a0 + VE - 1) / VE;
+    for (int base = 0; base < nvec; base += BATCH * 256) {
+        float v[BATCH][VE];
+#pragma unroll
+        for (int it = 0; it < BATCH; ++it) {
+            const int idx = base + it * 256 + (int)threadIdx.x;
+            if (idx < nvec) {
+                const int a = a0 + idx * VE;
+                if (a + VE <= total) Vec<T, VE>::load(src + a, v[it]);
+                else {
+#pragma unroll
+                    for (int j = 0; j < VE; ++j) v[it][j] = (a + j < total) ? ldf(src + a + j) : 0.f;
+                }
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < BATCH; ++it) {
+            const int idx = base + it * 256 + (int)threadIdx.x;
+            if (idx < nvec) {
+#pragma unroll
+                for (int j = 0; j < VE; j += 4)
+                    *reinterpret_cast<float4 *>(lds + idx * VE + j) = make_float4(v[it][j], v[it][j + 1], v[it][j + 2], v[it][j + 3]);
+            }
+        }
+    }
+}
+
+// lds[e - a0] -> flat range [g0, g1) of dst; the first and last vector may be partial.
+template <typename T>
+__device__ __forceinline__ void flat_store(T *__restrict__ dst, int g0, int g1, const float *lds)
+{
+    constexpr int VE = ElemsS<T>::VE;
+    const int a0 = g0 & ~(VE - 1);
+    const int nvec = (g1 - a0 + VE - 1) / VE;
+    for (int idx = threadIdx.x; idx < nvec; idx += 256) {
+        const int a = a0 + idx * VE;
+        float v[VE];
+#pragma unroll
+        for (int j = 0; j < VE; j += 4) {
+            const float4 q = *reinterpret_cast<const float4 *>(lds + idx * VE + j);
+            v[j] = q.x; v[j + 1] = q.y; v[j + 2] = q.z; v[j + 3] = q.w;
+        }
+        if (a >= g0 && a + VE <= g1) Vec<T, VE>::store(dst + a, v);
+        else {
+#pragma unroll
+            for (int j = 0; j < VE; ++j)
+                if (a + j >= g0 && a + j < g1) stf(dst + a + j, v[j]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Forward 3x3, pad 1, stride S, row width W (template).  FLIP: filter rotated by 180 degrees
+// (backward-data of the stride-1 layer).  U planes per block, one lane per (plane, output row).
+// ---------------------------------------------------------------------------------------------
+template <typename T, int S, int W, bool FLIP>
+__global__ __launch_bounds__(256) void k_nchws_fwd(Geom g, const T *__restrict__ x, const T *__restrict__ w,
+                                                   T *__restrict__ y, int U, int nplanes, unsigned nblocks)
+{
+    extern __shared__ float4 smem4[];
+    constexpr int VE = ElemsS<T>::VE;
+    constexpr int WO = (W + 2 - 3) / S + 1;
+    const int HW = g.H * W, HoWo = g.Ho * WO;
+    const unsigned lb = xcd_remap(blockIdx.x, nblocks);
+    const int p0 = lb * U, np = min(U, nplanes - p0);
+    float *lin = reinterpret_cast<float *>(smem4);
+    float *lout = lin + ((U * HW + 2 * VE + 3) & ~3);
+    const int gi0 = p0 * HW, go0 = p0 * HoWo;
+
+    flat_load<T>(x, g.N * g.C * HW, gi0, gi0 + np * HW, lin);
+    __syncthreads();
+
+    const int p = threadIdx.x / g.Ho, oh = threadIdx.x - p * g.Ho;
+    if (p < np) {
+        const int c = (p0 + p) % g.C;
+        float wr[3][3];
+        // taps on rows outside the image are dropped by zeroing their weights (the row address is clamped)
+#pragma unroll
+        for (int kh = 0; kh < 3; ++kh) {
+            const int ih = oh * S - 1 + kh;
+            const bool ok = ih >= 0 && ih < g.H;
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw) {
+                const float t = ldf(w + (c * 3 + (FLIP ? 2 - kh : kh)) * 3 + (FLIP ? 2 - kw : kw));
+                wr[kh][kw] = ok ? t : 0.f;
+            }
+        }
+        const float *pl = lin + (gi0 & (VE - 1)) + p * HW;
+        float out[WO];
+#pragma unroll
+        for (int j = 0; j < WO; ++j) out[j] = 0.f;
+#pragma unroll
+        for (int kh = 0; kh < 3; ++kh) {
+            const int ih = min(max(oh * S - 1 + kh, 0), g.H - 1);
+            const float *rp = pl + ih * W;
+            float row[W];
+#pragma unroll
+            for (int i = 0; i < W; ++i) row[i] = rp[i];
+#pragma unroll
+            for (int j = 0; j < WO; ++j)
+#pragma unroll
+                for (int kw = 0; kw < 3; ++kw) {
+                    const int iw = j * S - 1 + kw;
+                    if (iw >= 0 && iw < W) out[j] = fmaf(wr[kh][kw], row[iw], out[j]);
+                }
+        }
+        float *op = lout + (go0 & (VE - 1)) + p * HoWo + oh * WO;
+#pragma unroll
+        for (int j = 0; j < WO; ++j) op[j] = out[j];
+    }
+    __syncthreads();
+
+    flat_store<T>(y, go0, go0 + np * HoWo, lout);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Backward-data 3x3, stride 2, pad 1, dx row width W (template, even), dy row width W/2.
+// One lane per (plane, dy row a): writes dx rows 2a and 2a+1.
+// ---------------------------------------------------------------------------------------------
+template <typename T, int W>
+__global__ __launch_bounds__(256) void k_nchws_bwd_data_s2(Geom g, const T *__restrict__ dy, const T *__restrict__ w,
+                                                           T *__restrict__ dx, int U, int nplanes, unsigned nblocks)
+{
+    extern __shared__ float4 smem4[];
+    constexpr int VE = ElemsS<T>::VE;
+    constexpr int WO = W / 2;
+    const int HW = g.H * W, HoWo = g.Ho * WO;
+    const unsigned lb = xcd_remap(blockIdx.x, nblocks);
+    const int p0 = lb * U, np = min(U, nplanes - p0);
+    float *lin = reinterpret_cast<float *>(smem4);
+    float *lout = lin + ((U * HoWo + 2 * VE + 3) & ~3);
+    const int gi0 = p0 * HoWo, go0 = p0 * HW;
+
+    flat_load<T>(dy, g.N * g.O * HoWo, gi0, gi0 + np * HoWo, lin);
+    __syncthreads();
+
+    const int p = threadIdx.x / g.Ho, a = threadIdx.x - p * g.Ho;
+    if (p < np) {
+        const int c = (p0 + p) % g.C;
+        float wr[3][3];
+#pragma unroll
+        for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw) wr[kh][kw] = ldf(w + (c * 3 + kh) * 3 + kw);
+        const float *pl = lin + (gi0 & (VE - 1)) + p * HoWo;
+        const bool has_b = a + 1 < g.Ho;
+        const float *ra = pl + a * WO, *rb = pl + (has_b ? a + 1 : a) * WO;
+        float A[WO + 1], B[WO + 1];
+#pragma unroll
+        for (int i = 0; i < WO; ++i) { A[i] = ra[i]; const float t = rb[i]; B[i] = has_b ? t : 0.f; }
+        A[WO] = 0.f; B[WO] = 0.f;
+        float *op = lout + (go0 & (VE - 1)) + p * HW + (2 * a) * W;
+#pragma unroll
+        for (int b = 0; b < WO; ++b) {
+            op[2 * b] = wr[1][1] * A[b];
+            op[2 * b + 1] = fmaf(wr[1][0], A[b + 1], wr[1][2] * A[b]);
+            op[W + 2 * b] = fmaf(wr[0][1], B[b], wr[2][1] * A[b]);
+            op[W + 2 * b + 1] = fmaf(wr[0][0], B[b + 1], fmaf(wr[0][2], B[b], fmaf(wr[2][0], A[b + 1], wr[2][2] * A[b])));
+        }
+    }
+    __syncthreads();
+
+    flat_store<T>(dx, go0, go0 + np * HW, lout);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Backward-filter stage 1, 3x3, pad 1, stride S, x row width W (template).  A block owns U
+// consecutive channels and walks NI images; a lane owns (channel, output row) and keeps its nine
+// partial sums in registers across the images.  At the end the rows of a channel are added in
+// row order through LDS and one partial per block is written at ws[part][c][kh][kw].
+// ---------------------------------------------------------------------------------------------
+template <typename T, int S, int W>
+__global__ __launch_bounds__(256) void k_nchws_bwd_filter(Geom g, const T *__restrict__ x, const T *__restrict__ dy,
+                                                          float *__restrict__ ws, int U, int NI, int ncblocks,
+                                                          unsigned nblocks)
+{
+    extern __shared__ float4 smem4[];
+    constexpr int VE = ElemsS<T>::VE;
+    constexpr int WO = (W + 2 - 3) / S + 1;
+    const int HW = g.H * W, HoWo = g.Ho * WO;
+    const unsigned lb = xcd_remap(blockIdx.x, nblocks);
+    const int cblk = lb % ncblocks, part = lb / ncblocks;
+    const int c0 = cblk * U, nc = min(U, g.C - c0);
+    const int n0 = part * NI, n1 = min(g.N, n0 + NI);
+    float *lx = reinterpret_cast<float *>(smem4);
+    float *ld = lx + ((U * HW + 2 * VE + 3) & ~3);
+
+    const int p = threadIdx.x / g.Ho, oh = threadIdx.x - p * g.Ho;
+    float acc[3][3];
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) acc[kh][kw] = 0.f;
+    bool rowok[3];
+    int rowi[3];
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh) {
+        const int ih = oh * S - 1 + kh;
+        rowok[kh] = ih >= 0 && ih < g.H;
+        rowi[kh] = min(max(ih, 0), g.H - 1);
+    }
+
+    for (int n = n0; n < n1; ++n) {
+        const int gx0 = (n * g.C + c0) * HW, gd0 = (n * g.O + c0) * HoWo;
+        __syncthreads();
+        flat_load<T>(x, g.N * g.C * HW, gx0, gx0 + nc * HW, lx);
+        flat_load<T>(dy, g.N * g.O * HoWo, gd0, gd0 + nc * HoWo, ld);
+        __syncthreads();
+        if (p < nc) {
+            const float *xp = lx + (gx0 & (VE - 1)) + p * HW;
+            const float *dp = ld + (gd0 & (VE - 1)) + p * HoWo + oh * WO;
+            float d[WO];
+#pragma unroll
+            for (int j = 0; j < WO; ++j) d[j] = dp[j];
+#pragma unroll
+            for (int kh = 0; kh < 3; ++kh) {
+                const float *rp = xp + rowi[kh] * W;
+                float row[W];
+#pragma unroll
+                for (int i = 0; i < W; ++i) { const float t = rp[i]; row[i] = rowok[kh] ? t : 0.f; }
+#pragma unroll
+                for (int kw = 0; kw < 3; ++kw) {
+                    float s = acc[kh][kw];
+#pragma unroll
+                    for (int j = 0; j < WO; ++j) {
+                        const int iw = j * S - 1 + kw;
+                        if (iw >= 0 && iw < W) s = fmaf(d[j], row[iw], s);
+                    }
+                    acc[kh][kw] = s;
+                }
+            }
+        }
+    }
+
+    // rows of a channel are added in row order (fixed), through LDS
+    __syncthreads();
+    float *red = lx;     // 256 * 9 floats, reusing the x area (U*HW >= 9*U*Ho since W >= 7... checked on the host)
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) red[threadIdx.x * 9 + kh * 3 + kw] = (p < nc) ? acc[kh][kw] : 0.f;
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < nc * 9; idx += 256) {
+        const int pc = idx / 9, t = idx - pc * 9;
+        float s = 0.f;
+        for (int r = 0; r < g.Ho; ++r) s += red[(pc * g.Ho + r) * 9 + t];
+        ws[((size_t)part * g.O + c0 + pc) * 9 + t] = s;
+    }
+}
+
+// ---- host side --------------------------------------------------------------------------------
+
+static inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+// Row widths with a compiled instance; the pass needs 3x3, pad 1, multiplier 1 and H small enough
+// that one lane per output row fills a block with at least 8 planes.
+bool nchws_supported(const Geom &g, int pass)
+{
+    if (g.K != 3 || g.p != 1 || g.m != 1 || (g.s != 1 && g.s != 2)) return false;
+    if (!(g.W == 7 || g.W == 14 || g.W == 28)) return false;
+    if (g.s == 2 && (g.W % 2 != 0 || g.H % 2 != 0)) return false;
+    if (g.Ho > 32 || g.H > 32) return false;
+    (void)pass;
+    return true;
+}
+
+static int planes_per_block(const Geom &g) { return 256 / g.Ho; }
+
+static size_t lds_bytes_for(int U, int in_plane, int out_plane, int ve)
+{
+    return (size_t)(((U * in_plane + 2 * ve + 3) & ~3) + U * out_plane + 2 * ve + 4) * sizeof(float);
+}
+
+template <typename T>
+static hipError_t go_fwd(const Geom &g, const void *x, const void *w, void *y, bool flip, hipStream_t st)
+{
+    constexpr int VE = ElemsS<T>::VE;
+    int U = planes_per_block(g);
+    const int HW = g.H * g.W, HoWo = g.Ho * g.Wo;
+    while (U > 1 && lds_bytes_for(U, HW, HoWo, VE) > 60 * 1024) --U;
+    const size_t lds = lds_bytes_for(U, HW, HoWo, VE);
+    const int nplanes = g.N * g.C;
+    const unsigned nblocks = (unsigned)cdiv(nplanes, U);
+#define GO(SS, WW, FL) hipLaunchKernelGGL((k_nchws_fwd<T, SS, WW, FL>), dim3(nblocks), dim3(256), lds, st, g, (const T *)x, \
+                                          (const T *)w, (T *)y, U, nplanes, nblocks)
+#define PICK(SS, WW) if (g.s == SS && g.W == WW) { if (flip) GO(SS, WW, true); else GO(SS, WW, false); return hipGetLastError(); }
+    PICK(1, 7) PICK(1, 14) PICK(1, 28) PICK(2, 14) PICK(2, 28)
+#undef PICK
+#undef GO
+    return hipErrorInvalidValue;
+}
+
+hipError_t nchws_fwd(const Geom &g, int dtype, const void *x, const void *w, void *y, bool flip, hipStream_t st)
+{
+    return dtype == DT_F32 ? go_fwd<float>(g, x, w, y, flip, st) : go_fwd<bf16_t>(g, x, w, y, flip, st);
+}
+
+template <typename T>
+static hipError_t go_bwd_data_s2(const Geom &g, const void *dy, const void *w, void *dx, hipStream_t st)
+{
+    constexpr int VE = ElemsS<T>::VE;
+    int U = planes_per_block(g);
+    const int HW = g.H * g.W, HoWo = g.Ho * g.Wo;
+    while (U > 1 && lds_bytes_for(U, HoWo, HW, VE) > 60 * 1024) --U;
+    const size_t lds = lds_bytes_for(U, HoWo, HW, VE);
+    const int nplanes = g.N * g.C;
+    const unsigned nblocks = (unsigned)cdiv(nplanes, U);
+#define GO(WW) hipLaunchKernelGGL((k_nchws_bwd_data_s2<T, WW>), dim3(nblocks), dim3(256), lds, st, g, (const T *)dy, \
+                                  (const T *)w, (T *)dx, U, nplanes, nblocks)
+    if (g.W == 14) GO(14);
+    else if (g.W == 28) GO(28);
+    else return hipErrorInvalidValue;
+#undef GO
+    return hipGetLastError();
+}
+
+hipError_t nchws_bwd_data_s2(const Geom &g, int dtype, const void *dy, const void *w, void *dx, hipStream_t st)
+{
+    return dtype == DT_F32 ? go_bwd_data_s2<float>(g, dy, w, dx, st) : go_bwd_data_s2<bf16_t>(g, dy, w, dx, st);
+}
+
+// planes (channels) per block and images per block for the filter gradient
+void nchws_bwd_filter_tiling(const Geom &g, int dtype, int *U, int *NI, int *parts)
+{
+    const int ve = dtype == DT_F32 ? 4 : 8;
+    int u = planes_per_block(g);
+    if (u > g.C) u = g.C;
+    const int HW = g.H * g.W, HoWo = g.Ho * g.Wo;
+    while (u > 1 && lds_bytes_for(u, HW, HoWo, ve) > 60 * 1024) --u;
+    *U = u;
+    // about 2048 blocks in the launch
+    const int ncb = cdiv(g.C, u);
+    int ni = (int)(((long long)g.N * ncb) / 2048);
+    if (ni < 1) ni = 1;
+    if (ni > g.N) ni = g.N;
+    *NI = ni;
+    *parts = cdiv(g.N, ni);
+}
+
+template <typename T>
+static hipError_t go_bwd_filter(const Geom &g, const void *x, const void *dy, float *ws, int U, int NI, hipStream_t st)
+{
+    constexpr int VE = ElemsS<T>::VE;
+    const int HW = g.H * g.W, HoWo = g.Ho * g.Wo;
+    size_t lds = lds_bytes_for(U, HW, HoWo, VE);
+    if (lds < 256 * 9 * sizeof(float)) lds = 256 * 9 * sizeof(float);
+    const int ncb = cdiv(g.C, U);
+    const unsigned nblocks = (unsigned)ncb * cdiv(g.N, NI);
+#define GO(SS, WW) hipLaunchKernelGGL((k_nchws_bwd_filter<T, SS, WW>), dim3(nblocks), dim3(256), lds, st, g, (const T *)x, \
+                                      (const T *)dy, ws, U, NI, ncb, nblocks)
+    if (g.s == 1 && g.W == 7) GO(1, 7);
+    else if (g.s == 1 && g.W == 14) GO(1, 14);
+    else if (g.s == 1 && g.W == 28) GO(1, 28);
+    else if (g.s == 2 && g.W == 14) GO(2, 14);
+    else if (g.s == 2 && g.W == 28) GO(2, 28);
+    else return hipErrorInvalidValue;
+#undef GO
+    return hipGetLastError();
+}
+
+hipError_t nchws_bwd_filter(const Geom &g, int dtype, const void *x, const void *dy, float *ws, int U, int NI,
+                            hipStream_t st)
+{
+    return dtype == DT_F32 ? go_bwd_filter<float>(g, x, dy, ws, U, NI, st) : go_bwd_filter<bf16_t>(g, x, dy, ws, U, NI, st);
+}
+
+}  // namespace dwc

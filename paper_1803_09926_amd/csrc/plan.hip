@@ -49,10 +49,18 @@ static int nchw_pick_tr(const Geom &g, bool (*fits)(const Geom &, int))
 }
 static bool fits_bwd_filter(const Geom &g, int tr) { return nchw_bwd_filter_parts(g, tr, 1) > 0; }
 
+// Small-plane NCHW kernels: rows of 7 or 14 always; rows of 28 when asked for (tuning switch).
+static bool use_small(const Geom &g, int pass)
+{
+    if (!nchws_supported(g, pass)) return false;
+    return g.W <= 14 || tune("DWCONV_TUNE_S28", 0) == 1;
+}
+
 Plan plan_fwd(const Geom &g, int layout, int dtype)
 {
     Plan pl = {V_GENERIC, 0, 0, 0, 0, "generic"};
     if (layout == LAYOUT_NCHW) {
+        if (use_small(g, 0)) { pl.variant = V_NCHWS_FWD; pl.name = g.s == 1 ? "nchw_smallplane_k3s1" : "nchw_smallplane_fwd_k3s2"; return pl; }
         const int V = nchwd_vec(g, dtype, 0);
         if (V) {
             pl.a = V;
@@ -81,6 +89,11 @@ Plan plan_bwd_data(const Geom &g, int layout, int dtype)
 {
     Plan pl = {V_GENERIC, 0, 0, 0, 0, "generic"};
     if (layout == LAYOUT_NCHW) {
+        if (use_small(g, 1)) {
+            if (g.s == 1) { pl.variant = V_NCHWS_FWD; pl.name = "nchw_smallplane_k3s1_flip"; }
+            else { pl.variant = V_NCHWS_BWD_DATA_S2; pl.name = "nchw_smallplane_bwd_data_k3s2"; }
+            return pl;
+        }
         const int V = nchwd_vec(g, dtype, 1);
         if (V) {
             pl.a = V;
@@ -114,6 +127,18 @@ Plan plan_bwd_filter(const Geom &g, int layout, int dtype)
 {
     Plan pl = {V_GENERIC, generic_bwd_filter_parts(g), 0, 0, 0, "generic"};
     if (layout == LAYOUT_NCHW) {
+        if (use_small(g, 2)) {
+            int U, NI, parts;
+            nchws_bwd_filter_tiling(g, dtype, &U, &NI, &parts);
+            NI = tune("DWCONV_TUNE_NI", NI);
+            if (NI > g.N) NI = g.N;
+            parts = ceil_div(g.N, NI);
+            if ((long long)parts * g.O * 9 * 4 <= (64ll << 20)) {
+                pl.variant = V_NCHWS_BWD_FILTER; pl.a = U; pl.c = NI; pl.parts = parts;
+                pl.name = g.s == 1 ? "nchw_smallplane_bwd_filter_k3s1" : "nchw_smallplane_bwd_filter_k3s2";
+                return pl;
+            }
+        }
         const int V = nchwd_vec(g, dtype, 2);
         if (V) {
             int TH = tune("DWCONV_TUNE_TH", g.Ho <= 28 ? g.Ho : 14);
@@ -184,6 +209,7 @@ hipError_t launch_fwd(const Plan &pl, const Geom &g, int layout, int dtype, cons
     case V_NHWC_K3S2: return nhwc_k3s2(g, dtype, pl.a, x, w, y, false, pl.b, st);
     case V_NCHW_FWD: return nchw_fwd(g, dtype, x, w, y, false, pl.b, st);
     case V_NCHWD_S1: return nchwd_s1(g, dtype, pl.a, x, w, y, false, pl.b, st);
+    case V_NCHWS_FWD: return nchws_fwd(g, dtype, x, w, y, false, st);
     case V_NCHWD_K3S2: return nchwd_k3s2(g, dtype, pl.a, x, w, y, false, pl.b, st);
     default: return generic_fwd(g, layout, dtype, x, w, y, st);
     }
@@ -197,6 +223,8 @@ hipError_t launch_bwd_data(const Plan &pl, const Geom &g, int layout, int dtype,
     case V_NHWC_K3S2: return nhwc_k3s2(g, dtype, pl.a, dy, w, dx, true, pl.b, st);
     case V_NCHW_FWD: return nchw_fwd(g, dtype, dy, w, dx, true, pl.b, st);
     case V_NCHWD_S1: return nchwd_s1(g, dtype, pl.a, dy, w, dx, true, pl.b, st);
+    case V_NCHWS_FWD: return nchws_fwd(g, dtype, dy, w, dx, true, st);
+    case V_NCHWS_BWD_DATA_S2: return nchws_bwd_data_s2(g, dtype, dy, w, dx, st);
     case V_NCHWD_K3S2: return nchwd_k3s2(g, dtype, pl.a, dy, w, dx, true, pl.b, st);
     case V_NCHW_BWD_DATA_K3S2: return nchw_bwd_data_k3s2(g, dtype, dy, w, dx, pl.b, st);
     default: return generic_bwd_data(g, layout, dtype, dy, w, dx, st);
@@ -210,6 +238,7 @@ hipError_t launch_bwd_filter(const Plan &pl, const Geom &g, int layout, int dtyp
     case V_NHWC_BWD_FILTER: return nhwc_bwd_filter(g, dtype, pl.a, x, dy, ws, pl.b, pl.c, st);
     case V_NCHW_BWD_FILTER: return nchw_bwd_filter(g, dtype, x, dy, ws, pl.b, pl.c, st);
     case V_NCHWD_BWD_FILTER: return nchwd_bwd_filter(g, dtype, pl.a, x, dy, ws, pl.b, st);
+    case V_NCHWS_BWD_FILTER: return nchws_bwd_filter(g, dtype, x, dy, ws, pl.a, pl.c, st);
     default: return generic_bwd_filter(g, layout, dtype, x, dy, ws, pl.parts, st);
     }
 }

@@ -16,6 +16,9 @@ enum Variant {
     V_NCHWD_S1,         // a = V, b = TH
     V_NCHWD_K3S2,       // a = V, b = TH
     V_NCHWD_BWD_FILTER, // a = V, b = TH
+    V_NCHWS_FWD,        // small planes: forward / backward-data stride 1 (rotated filter)
+    V_NCHWS_BWD_DATA_S2,
+    V_NCHWS_BWD_FILTER, // a = U, c = NI
 };
 
 struct Plan {
