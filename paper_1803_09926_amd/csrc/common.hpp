@@ -1,8 +1,5 @@
 // Shared device-side helpers for the gfx950 depthwise-convolution kernels.
 #pragma once
-#ifndef DWC_EXP
-#define DWC_EXP 0
-#endif
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -39,23 +36,12 @@ template <typename T, int V> struct Vec;
 template <> struct Vec<float, 4> {
     static __device__ __forceinline__ void load(const float *p, float (&r)[4])
     {
-#if DWC_EXP == 3
-        typedef float f4v __attribute__((ext_vector_type(4)));
-        f4v v = __builtin_nontemporal_load(reinterpret_cast<const f4v *>(p));
-#else
         float4 v = *reinterpret_cast<const float4 *>(p);
-#endif
         r[0] = v.x; r[1] = v.y; r[2] = v.z; r[3] = v.w;
     }
     static __device__ __forceinline__ void store(float *p, const float (&r)[4])
     {
-#if DWC_EXP == 2 || DWC_EXP == 3
-        typedef float f4v __attribute__((ext_vector_type(4)));
-        f4v v = {r[0], r[1], r[2], r[3]};
-        __builtin_nontemporal_store(v, reinterpret_cast<f4v *>(p));
-#else
         *reinterpret_cast<float4 *>(p) = make_float4(r[0], r[1], r[2], r[3]);
-#endif
     }
 };
 template <> struct Vec<float, 2> {
@@ -122,6 +108,35 @@ template <> struct Vec<bf16_t, 1> {
     static __device__ __forceinline__ void load(const bf16_t *p, float (&r)[1]) { r[0] = bf16_to_f32(*p); }
     static __device__ __forceinline__ void store(bf16_t *p, const float (&r)[1]) { *p = f32_to_bf16(r[0]); }
 };
+
+// Store V elements; `stream` = true marks the store non-temporal (the output of a large layer is
+// not read again by these kernels, so it should not displace the halo rows that are).
+typedef float f4v_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u4v_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u2v_t __attribute__((ext_vector_type(2)));
+template <typename T, int V>
+__device__ __forceinline__ void store_vec(T *p, const float (&r)[V], bool stream)
+{
+    if (!stream) { Vec<T, V>::store(p, r); return; }
+    if constexpr (sizeof(T) == 4 && V == 4) {
+        f4v_t v = {r[0], r[1], r[2], r[3]};
+        __builtin_nontemporal_store(v, reinterpret_cast<f4v_t *>(p));
+    } else if constexpr (sizeof(T) == 2 && V == 8) {
+        u4v_t v;
+        v.x = (uint32_t)f32_to_bf16(r[0]) | ((uint32_t)f32_to_bf16(r[1]) << 16);
+        v.y = (uint32_t)f32_to_bf16(r[2]) | ((uint32_t)f32_to_bf16(r[3]) << 16);
+        v.z = (uint32_t)f32_to_bf16(r[4]) | ((uint32_t)f32_to_bf16(r[5]) << 16);
+        v.w = (uint32_t)f32_to_bf16(r[6]) | ((uint32_t)f32_to_bf16(r[7]) << 16);
+        __builtin_nontemporal_store(v, reinterpret_cast<u4v_t *>(p));
+    } else if constexpr (sizeof(T) == 2 && V == 4) {
+        u2v_t v;
+        v.x = (uint32_t)f32_to_bf16(r[0]) | ((uint32_t)f32_to_bf16(r[1]) << 16);
+        v.y = (uint32_t)f32_to_bf16(r[2]) | ((uint32_t)f32_to_bf16(r[3]) << 16);
+        __builtin_nontemporal_store(v, reinterpret_cast<u2v_t *>(p));
+    } else {
+        Vec<T, V>::store(p, r);
+    }
+}
 
 // ---- fixed-order reductions -----------------------------------------------------------------
 // Butterfly sum over the 64 lanes of a wavefront; every lane ends with the same total and the

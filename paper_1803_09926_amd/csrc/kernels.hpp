@@ -2,10 +2,20 @@
 // the launch.  All pointers are device pointers; T-typed tensors are passed as void*.
 #pragma once
 #include "common.hpp"
+#include <stdlib.h>
 
 namespace dwc {
 
 enum { LAYOUT_NCHW = 0, LAYOUT_NHWC = 1 };
+
+// Outputs at least this large are written with non-temporal stores (DWCONV_TUNE_NT=0/1 overrides,
+// for tuning runs only).
+inline int stream_stores(long long out_bytes)
+{
+    const char *e = getenv("DWCONV_TUNE_NT");
+    if (e && *e) return atoi(e) != 0;
+    return out_bytes >= (64ll << 20);
+}
 enum { DT_F32 = 0, DT_BF16 = 1 };
 
 // ---- generic fallback: any K, stride, pad, multiplier (generic.hip) -------------------------

@@ -32,7 +32,7 @@ __device__ __forceinline__ Lane lane_of(unsigned nblocks, int ncols, int nstrips
 // ---------------------------------------------------------------------------------------------
 template <typename T, int V, int K, int PF, bool FLIP>
 __global__ __launch_bounds__(256) void k_nchwd_s1(Geom g, const T *__restrict__ x, const T *__restrict__ w,
-                                                  T *__restrict__ y, int TH, int nstrips, unsigned nblocks)
+                                                  T *__restrict__ y, int TH, int nstrips, unsigned nblocks, int nt)
 {
     constexpr int P = (K - 1) / 2;
     constexpr int NW = V + 2 * P;       // window: P left neighbours, V own columns, P right neighbours
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(256) void k_nchwd_s1(Geom g, const T *__restrict__ 
                         acc[jj][v] = s;
                     }
                 const int oh = r - P;
-                if (oh >= oh0) Vec<T, V>::store(yout + (size_t)oh * g.W, out);
+                if (oh >= oh0) store_vec<T, V>(yout + (size_t)oh * g.W, out, nt != 0);
             }
         }
     }
@@ -125,7 +125,7 @@ __global__ __launch_bounds__(256) void k_nchwd_s1(Geom g, const T *__restrict__ 
 // ---------------------------------------------------------------------------------------------
 template <typename T, int V>
 __global__ __launch_bounds__(256) void k_nchwd_fwd_k3s2(Geom g, const T *__restrict__ x, const T *__restrict__ w,
-                                                        T *__restrict__ y, int TH, int nstrips, unsigned nblocks)
+                                                        T *__restrict__ y, int TH, int nstrips, unsigned nblocks, int nt)
 {
     constexpr int NW = 2 * V + 1;
     const int Wo4 = g.Wo / V;
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(256) void k_nchwd_fwd_k3s2(Geom g, const T *__restr
                     out[v] = s;
                     carry[v] = fmaf(wr[0][0], ro[j][2 * v], fmaf(wr[0][1], ro[j][2 * v + 1], wr[0][2] * ro[j][2 * v + 2]));
                 }
-                Vec<T, V>::store(yout + (size_t)oh * g.Wo, out);
+                store_vec<T, V>(yout + (size_t)oh * g.Wo, out, nt != 0);
             }
         }
     }
@@ -200,7 +200,7 @@ __global__ __launch_bounds__(256) void k_nchwd_fwd_k3s2(Geom g, const T *__restr
 // ---------------------------------------------------------------------------------------------
 template <typename T, int V>
 __global__ __launch_bounds__(256) void k_nchwd_bwd_data_k3s2(Geom g, const T *__restrict__ dy, const T *__restrict__ w,
-                                                             T *__restrict__ dx, int TH, int nstrips, unsigned nblocks)
+                                                             T *__restrict__ dx, int TH, int nstrips, unsigned nblocks, int nt)
 {
     const int Wo4 = g.Wo / V;
     const Lane ln = lane_of(nblocks, Wo4, nstrips, g.N * g.C);
@@ -249,8 +249,8 @@ __global__ __launch_bounds__(256) void k_nchwd_bwd_data_k3s2(Geom g, const T *__
                     od[2 * v + 1] = fmaf(wr[0][0], B[v + 1], fmaf(wr[0][2], B[v], fmaf(wr[2][0], A[v + 1], wr[2][2] * A[v])));
                 }
                 T *rp = dxout + (size_t)(2 * a) * g.W;
-                Vec<T, 2 * V>::store(rp, ev);
-                Vec<T, 2 * V>::store(rp + g.W, od);
+                store_vec<T, 2 * V>(rp, ev, nt != 0);
+                store_vec<T, 2 * V>(rp + g.W, od, nt != 0);
             }
         }
     }
@@ -417,12 +417,13 @@ static hipError_t go_s1(const Geom &g, const void *x, const void *w, void *y, bo
     const int nstrips = ceil_div_h(g.H, TH);
     const long long lanes = (long long)g.N * g.O * nstrips * (g.W / V);
     const unsigned nblocks = (unsigned)((lanes + 255) / 256);
+    const int nt = 0;   // a wave's store covers pieces of several rows (partial lines): keep it cached
     if (flip)
         hipLaunchKernelGGL((k_nchwd_s1<T, V, K, 2, true>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, (const T *)w,
-                           (T *)y, TH, nstrips, nblocks);
+                           (T *)y, TH, nstrips, nblocks, nt);
     else
         hipLaunchKernelGGL((k_nchwd_s1<T, V, K, 2, false>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, (const T *)w,
-                           (T *)y, TH, nstrips, nblocks);
+                           (T *)y, TH, nstrips, nblocks, nt);
     return hipGetLastError();
 }
 
@@ -441,8 +442,9 @@ hipError_t nchwd_k3s2(const Geom &g, int dtype, int V, const void *in, const voi
     const int nstrips = ceil_div_h(g.Ho, TH);
     const long long lanes = (long long)g.N * g.O * nstrips * (g.Wo / V);
     const unsigned nblocks = (unsigned)((lanes + 255) / 256);
+    const int nt = bwd ? 0 : stream_stores((long long)g.N * g.O * g.Ho * g.Wo * (dtype == DT_F32 ? 4 : 2));
 #define GO(KERNEL, T, VV) hipLaunchKernelGGL((KERNEL<T, VV>), dim3(nblocks), dim3(256), 0, st, g, (const T *)in, \
-                                             (const T *)w, (T *)out, TH, nstrips, nblocks)
+                                             (const T *)w, (T *)out, TH, nstrips, nblocks, nt)
     if (!bwd) {
         if (dtype == DT_F32 && V == 4) GO(k_nchwd_fwd_k3s2, float, 4);
         else if (dtype == DT_F32 && V == 2) GO(k_nchwd_fwd_k3s2, float, 2);

@@ -37,7 +37,7 @@ template <int V, int K, int TW, int PF> constexpr int S1_WAVES()
 // ---------------------------------------------------------------------------------------------
 template <typename T, int V, int K, int TW, int PF, bool FLIP>
 __global__ __launch_bounds__(256, (S1_WAVES<V, K, TW, PF>())) void k_nhwc_s1(Geom g, const T *__restrict__ x, const T *__restrict__ w,
-                                                 T *__restrict__ y, int TH, int nstrips, int nchunks, unsigned nblocks)
+                                                 T *__restrict__ y, int TH, int nstrips, int nchunks, unsigned nblocks, int nt)
 {
     constexpr int P = (K - 1) / 2;
     constexpr int NC = TW + K - 1;        // input columns per lane
@@ -122,7 +122,7 @@ __global__ __launch_bounds__(256, (S1_WAVES<V, K, TW, PF>())) void k_nhwc_s1(Geo
         if (oh >= oh0) {
 #pragma unroll
             for (int t = 0; t < TW; ++t)
-                if (TW == 1 || ow0 + t < g.W) Vec<T, V>::store(yout + (size_t)oh * rowstride + t * g.C, out[t]);
+                if (TW == 1 || ow0 + t < g.W) store_vec<T, V>(yout + (size_t)oh * rowstride + t * g.C, out[t], nt != 0);
         }
     };
 
@@ -150,7 +150,7 @@ __global__ __launch_bounds__(256, (S1_WAVES<V, K, TW, PF>())) void k_nhwc_s1(Geo
 template <typename T, int V>
 __global__ __launch_bounds__(256) void k_nhwc_fwd_k3s2(Geom g, const T *__restrict__ x, const T *__restrict__ w,
                                                        T *__restrict__ y, int TH, int nstrips, int nchunks,
-                                                       unsigned nblocks)
+                                                       unsigned nblocks, int nt)
 {
     const Tile tl = tile_of(nblocks, nchunks, nstrips);
     const int Q = g.C / V, WoQ = g.Wo * Q;
@@ -211,7 +211,7 @@ __global__ __launch_bounds__(256) void k_nhwc_fwd_k3s2(Geom g, const T *__restri
             }
             out[v] = s; carry[v] = c;
         }
-        Vec<T, V>::store(yout + (size_t)oh * g.Wo * g.C, out);
+        store_vec<T, V>(yout + (size_t)oh * g.Wo * g.C, out, nt != 0);
     }
 }
 
@@ -227,7 +227,7 @@ __global__ __launch_bounds__(256) void k_nhwc_fwd_k3s2(Geom g, const T *__restri
 template <typename T, int V>
 __global__ __launch_bounds__(256) void k_nhwc_bwd_data_k3s2(Geom g, const T *__restrict__ dy, const T *__restrict__ w,
                                                             T *__restrict__ dx, int TH, int nstrips, int nchunks,
-                                                            unsigned nblocks)
+                                                            unsigned nblocks, int nt)
 {
     const Tile tl = tile_of(nblocks, nchunks, nstrips);
     const int Q = g.C / V, WoQ = g.Wo * Q;
@@ -275,11 +275,11 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_data_k3s2(Geom g, const T *__r
             o11[v] = fmaf(wr[0][0][v], B1[v], fmaf(wr[0][2][v], B0[v], fmaf(wr[2][0][v], A1[v], wr[2][2][v] * A0[v])));
         }
         T *r0p = dxout + (size_t)(2 * a) * dxrow;
-        Vec<T, V>::store(r0p, o00);
-        if (col1) Vec<T, V>::store(r0p + g.C, o01);
+        store_vec<T, V>(r0p, o00, nt != 0);
+        if (col1) store_vec<T, V>(r0p + g.C, o01, nt != 0);
         if (2 * a + 1 < g.H) {
-            Vec<T, V>::store(r0p + dxrow, o10);
-            if (col1) Vec<T, V>::store(r0p + dxrow + g.C, o11);
+            store_vec<T, V>(r0p + dxrow, o10, nt != 0);
+            if (col1) store_vec<T, V>(r0p + dxrow + g.C, o11, nt != 0);
         }
 #pragma unroll
         for (int v = 0; v < V; ++v) { A0[v] = B0[v]; A1[v] = B1[v]; }
@@ -469,12 +469,13 @@ static hipError_t launch_s1(const Geom &g, const void *x, const void *w, void *y
     const int bs = flat_block(lanes);
     const int nchunks = ceil_div(lanes, bs), nstrips = ceil_div(g.H, TH);
     const unsigned nblocks = (unsigned)g.N * nchunks * nstrips;
+    const int nt = stream_stores((long long)g.N * g.H * g.W * g.C * sizeof(T));
     if (flip)
         hipLaunchKernelGGL((k_nhwc_s1<T, V, K, TW, PF, true>), dim3(nblocks), dim3(bs), 0, st, g, (const T *)x,
-                           (const T *)w, (T *)y, TH, nstrips, nchunks, nblocks);
+                           (const T *)w, (T *)y, TH, nstrips, nchunks, nblocks, nt);
     else
         hipLaunchKernelGGL((k_nhwc_s1<T, V, K, TW, PF, false>), dim3(nblocks), dim3(bs), 0, st, g, (const T *)x,
-                           (const T *)w, (T *)y, TH, nstrips, nchunks, nblocks);
+                           (const T *)w, (T *)y, TH, nstrips, nchunks, nblocks, nt);
     return hipGetLastError();
 }
 
@@ -504,8 +505,11 @@ hipError_t nhwc_k3s2(const Geom &g, int dtype, int V, const void *in, const void
     const int bs = flat_block(WoQ);
     const int nchunks = ceil_div(WoQ, bs), nstrips = ceil_div(g.Ho, TH);
     const unsigned nblocks = (unsigned)g.N * nchunks * nstrips;
+    // forward: a wave's store is one contiguous run, and the pass is read-dominated: stream the output.
+    // backward-data writes alternate pixel columns per instruction (partial lines): keep those cached.
+    const int nt = bwd ? 0 : stream_stores((long long)g.N * g.Ho * g.Wo * g.C * (dtype == DT_F32 ? 4 : 2));
 #define GO(KERNEL, T, VV) hipLaunchKernelGGL((KERNEL<T, VV>), dim3(nblocks), dim3(bs), 0, st, g, (const T *)in, \
-                                             (const T *)w, (T *)out, TH, nstrips, nchunks, nblocks)
+                                             (const T *)w, (T *)out, TH, nstrips, nchunks, nblocks, nt)
     if (!bwd) {
         if (dtype == DT_F32) GO(k_nhwc_fwd_k3s2, float, 4);
         else if (V == 8) GO(k_nhwc_fwd_k3s2, bf16_t, 8);
