@@ -1,0 +1,105 @@
+"""Turn rocprofv3 CSV output of `bench.py` into the short text summaries kept under profiles/.
+
+Usage:
+  python -m paper_1803_09926_amd.rocprof_summary stats   <dir with *_kernel_stats.csv>
+  python -m paper_1803_09926_amd.rocprof_summary traffic <FETCH_SIZE dir> <WRITE_SIZE dir>
+
+`traffic` expects both runs to contain bench.py's --calibrate-copy dispatches (a plain device copy
+of 2^30 bytes): each counter is scaled so that the copy reads (writes) exactly 2^30 bytes.
+Output goes to stdout.
+"""
+import csv
+import glob
+import os
+import re
+import sys
+
+# bench.py's "<pass>:<variant>" keys -> the kernel(s) that implement them (regex on the demangled name)
+VARIANT_KERNELS = {
+    "fwd:nhwc_rowwalk_k3s1": [r"k_nhwc_s1<.*, 3, \d+, \d+, false>"],
+    "bwd_data:nhwc_rowwalk_k3s1_flip": [r"k_nhwc_s1<.*, 3, \d+, \d+, true>"],
+    "fwd:nhwc_rowwalk_fwd_k3s2": [r"k_nhwc_fwd_k3s2<"],
+    "bwd_data:nhwc_rowwalk_bwd_data_k3s2": [r"k_nhwc_bwd_data_k3s2<"],
+    "bwd_filter:nhwc_bwd_filter_k3s1": [r"k_nhwc_bwd_filter<.*, 3, 1, \d+>"],
+    "bwd_filter:nhwc_bwd_filter_k3s2": [r"k_nhwc_bwd_filter<.*, 3, 2, \d+>"],
+    "fwd:nchw_rowwalk_k3s1": [r"k_nchwd_s1<.*, 3, \d+, false>"],
+    "bwd_data:nchw_rowwalk_k3s1_flip": [r"k_nchwd_s1<.*, 3, \d+, true>"],
+    "fwd:nchw_rowwalk_fwd_k3s2": [r"k_nchwd_fwd_k3s2<"],
+    "bwd_data:nchw_rowwalk_bwd_data_k3s2": [r"k_nchwd_bwd_data_k3s2<"],
+    "bwd_filter:nchw_rowwalk_bwd_filter_k3s1": [r"k_nchwd_bwd_filter_k3<.*, 1>"],
+    "bwd_filter:nchw_rowwalk_bwd_filter_k3s2": [r"k_nchwd_bwd_filter_k3<.*, 2>"],
+    "fwd:nchw_smallplane_k3s1": [r"k_nchws_fwd<.*, 1, \d+, false>"],
+    "bwd_data:nchw_smallplane_k3s1_flip": [r"k_nchws_fwd<.*, 1, \d+, true>"],
+    "fwd:nchw_smallplane_fwd_k3s2": [r"k_nchws_fwd<.*, 2, \d+, false>"],
+    "bwd_data:nchw_smallplane_bwd_data_k3s2": [r"k_nchws_bwd_data_s2<"],
+    "bwd_filter:nchw_smallplane_bwd_filter_k3s1": [r"k_nchws_bwd_filter<.*, 1, \d+>"],
+    "bwd_filter:nchw_smallplane_bwd_filter_k3s2": [r"k_nchws_bwd_filter<.*, 2, \d+>"],
+}
+
+
+def _one(pattern):
+    files = glob.glob(pattern)
+    if not files:
+        sys.exit("no file matches " + pattern)
+    return files[0]
+
+
+def short(name):
+    name = re.sub(r"\(.*$", "", name)
+    return name.replace("void dwc::", "").replace("dwc::", "")
+
+
+def stats(d):
+    rows = list(csv.DictReader(open(_one(os.path.join(d, "*kernel_stats.csv")))))
+    rows = [r for r in rows if "dwc::" in r["Name"]]
+    total = sum(int(r["TotalDurationNs"]) for r in rows)
+    print("%-64s %7s %12s %12s %10s %10s %6s" % ("kernel", "calls", "total_us", "avg_us", "min_us", "max_us", "%"))
+    for r in sorted(rows, key=lambda r: -int(r["TotalDurationNs"])):
+        print("%-64s %7d %12.1f %12.2f %10.2f %10.2f %6.2f" % (
+            short(r["Name"])[:64], int(r["Calls"]), int(r["TotalDurationNs"]) / 1e3, float(r["AverageNs"]) / 1e3,
+            int(r["MinNs"]) / 1e3, int(r["MaxNs"]) / 1e3, 100.0 * int(r["TotalDurationNs"]) / total))
+    print("sum over the library's kernels: %.1f us" % (total / 1e3))
+
+
+def _counter(d, cname):
+    rows = [r for r in csv.DictReader(open(_one(os.path.join(d, "*counter_collection.csv")))) if r["Counter_Name"] == cname]
+    cal = [float(r["Counter_Value"]) for r in rows if "copyBuffer" in r["Kernel_Name"]]
+    if not cal:
+        sys.exit("no calibration copy in " + d + " (run bench.py with --calibrate-copy)")
+    unit = float(1 << 30) / (sum(cal) / len(cal))
+    per = {}
+    for r in rows:
+        if "dwc::" not in r["Kernel_Name"]:
+            continue
+        per.setdefault(short(r["Kernel_Name"]), []).append(float(r["Counter_Value"]) * unit)
+    return unit, cal, per
+
+
+def traffic(dfetch, dwrite):
+    fu, fcal, fper = _counter(dfetch, "FETCH_SIZE")
+    wu, wcal, wper = _counter(dwrite, "WRITE_SIZE")
+    print("# calibration: a device copy of 2^30 bytes reads FETCH_SIZE = %s and writes WRITE_SIZE = %s" % (fcal, wcal))
+    print("# scale: %.1f bytes per FETCH_SIZE unit, %.1f bytes per WRITE_SIZE unit" % (fu, wu))
+    print("# per kernel: mean HBM bytes per dispatch (fetch, write, sum) over all its dispatches")
+    print("%-64s %7s %14s %14s %14s" % ("kernel", "calls", "fetch_B", "write_B", "total_B"))
+    for k in sorted(fper):
+        f = sum(fper[k]) / len(fper[k]); w = sum(wper.get(k, [0.0])) / max(1, len(wper.get(k, [])))
+        print("%-64s %7d %14.0f %14.0f %14.0f" % (k[:64], len(fper[k]), f, w, f + w))
+    print("# bench.py keys: mean HBM bytes per launch over every dispatch of the kernel(s) behind the key")
+    print("# (for bwd_filter: stage 1 only; the stage-2 kernel k_reduce_partials is listed above)")
+    for key, pats in VARIANT_KERNELS.items():
+        ks = [k for k in fper if any(re.search(p, k) for p in pats)]
+        if not ks:
+            continue
+        calls = sum(len(fper[k]) for k in ks)
+        val = (sum(sum(fper[k]) for k in ks) + sum(sum(wper.get(k, [])) for k in ks)) / calls
+        print("traffic %s %.0f" % (key, val))
+
+
+if __name__ == "__main__":
+    if len(sys.argv) >= 3 and sys.argv[1] == "stats":
+        stats(sys.argv[2])
+    elif len(sys.argv) >= 4 and sys.argv[1] == "traffic":
+        traffic(sys.argv[2], sys.argv[3])
+    else:
+        sys.exit(__doc__)
