@@ -34,9 +34,9 @@ hipError_t reduce_partials(const float *ws, int parts, int J, float *dw, hipStre
 // ---- NHWC row-walk kernels, multiplier 1 (nhwc.hip) ------------------------------------------
 // V = channels per lane (4 for fp32; 8 or 4 for bf16), TH = rows per strip.
 // stride 1, K in {3,5}, pad (K-1)/2; flip = true gives backward-data.
-// TW = adjacent output columns per lane, PF = rows loaded ahead.
-hipError_t nhwc_s1(const Geom &g, int dtype, int V, const void *x, const void *w, void *y, bool flip, int TH, int TW,
-                   int PF, hipStream_t st);
+// PF = rows loaded ahead of the row being consumed.
+hipError_t nhwc_s1(const Geom &g, int dtype, int V, const void *x, const void *w, void *y, bool flip, int TH, int PF,
+                   hipStream_t st);
 // 3x3 stride 2 pad 1; bwd = false: forward (in = x, out = y); bwd = true: backward-data (in = dy, out = dx).
 hipError_t nhwc_k3s2(const Geom &g, int dtype, int V, const void *in, const void *w, void *out, bool bwd, int TH,
                      hipStream_t st);

@@ -27,6 +27,16 @@ static int nhwc_vec(const Geom &g, int dtype)
     return g.C % 8 == 0 ? 8 : (g.C % 4 == 0 ? 4 : 0);
 }
 
+// Rows loaded ahead in the NHWC stride-1 kernel (5x5 keeps 25 taps x V in registers: one row less).
+static int nhwc_pf(const Geom &g, int dtype)
+{
+    int pf = tune("DWCONV_TUNE_PF", 2);
+    if (g.K == 5 && pf > 2) pf = 2;
+    if (pf > 3 && !(dtype == DT_F32 && g.K == 3)) pf = 3;
+    if (pf > 4) pf = 4;
+    return pf;
+}
+
 // Rows per strip: enough strips that the launch has at least ~12 wavefronts per CU, but strips of
 // at least 7 rows so that the K-1 halo rows re-read per strip stay a small fraction.
 static int pick_th(int rows, long long lanes_per_row_all_images)
@@ -141,7 +151,7 @@ Plan plan_bwd_filter(const Geom &g, int layout, int dtype)
         }
         const int V = nchwd_vec(g, dtype, 2);
         if (V) {
-            int TH = tune("DWCONV_TUNE_TH", g.Ho <= 28 ? g.Ho : 14);
+            int TH = tune("DWCONV_TUNE_THW", tune("DWCONV_TUNE_TH", g.Ho > 56 ? (g.Ho + 1) / 2 : (g.s == 2 && g.Ho >= 28 ? (g.Ho + 1) / 2 : g.Ho)));
             int lg, nst, rounds, parts;
             nchwd_bwd_filter_tiling(g, V, TH, &lg, &nst, &rounds, &parts);
             if (lg <= 8 && (long long)parts * g.O * 9 * 4 <= (64ll << 20)) {
@@ -173,20 +183,18 @@ Plan plan_bwd_filter(const Geom &g, int layout, int dtype)
     if (layout == LAYOUT_NHWC) {
         const int V = nhwc_vec(g, dtype);
         if (V && (same_pad_s1(g) || k3s2p1(g))) {
-            // lanes per (row, image) after tiling: columns x channel-vectors, rounded up to the block tiling
+            // One block = 256 lanes over (columns x channel-vectors) x one strip x NI images.  Long
+            // walks win (fewer partials, less stage-2 work): start from whole columns and one image
+            // per block, and only split rows when the launch would have too few blocks to keep the
+            // memory system busy (stride 1 issues fewer loads per row, so it wants more blocks).
             int CT, nct, nowt, nst, ngr;
             nhwc_bwd_filter_tiling(g, V, g.Ho, 1, &CT, &nct, &nowt, &nst, &ngr);
-            const long long lanes = 256ll * nct * nowt;
-            // images per block: aim for ~12 wavefronts per CU over the whole launch
+            const long long per_strip = (long long)nct * nowt * g.N;   // blocks with NI = 1 and one strip
+            const long long want = g.s == 1 ? 1024 : 512;
             int TH = g.Ho, NI = 1;
-            const long long want = 256ll * 12 * 64;
-            long long blocks_lanes = lanes * g.N;       // with NI = 1, one strip
-            if (blocks_lanes >= 2 * want) {
-                while (NI < g.N && lanes * ceil_div(g.N, NI * 2) >= want) NI *= 2;
-            } else {
-                while (TH > 7 && lanes * g.N * ceil_div(g.Ho, TH) < want) TH = (TH + 1) / 2;
-            }
-            TH = tune("DWCONV_TUNE_TH", TH); NI = tune("DWCONV_TUNE_NI", NI);
+            while (TH > 7 && per_strip * ceil_div(g.Ho, TH) * 4 < want * 3) TH = (TH + 1) / 2;
+            while (NI < g.N && per_strip * ceil_div(g.Ho, TH) / (NI * 2) >= want) NI *= 2;
+            TH = tune("DWCONV_TUNE_THW", tune("DWCONV_TUNE_TH", TH)); NI = tune("DWCONV_TUNE_NI", NI);
             nhwc_bwd_filter_tiling(g, V, TH, NI, &CT, &nct, &nowt, &nst, &ngr);
             // keep the partials within the 64 MiB the header promises
             while ((long long)nowt * nst * ngr * g.O * g.K * g.K * 4 > (64ll << 20)) {
@@ -205,7 +213,7 @@ hipError_t launch_fwd(const Plan &pl, const Geom &g, int layout, int dtype, cons
                       hipStream_t st)
 {
     switch (pl.variant) {
-    case V_NHWC_S1: return nhwc_s1(g, dtype, pl.a, x, w, y, false, pl.b, tune("DWCONV_TUNE_TW", 1), tune("DWCONV_TUNE_PF", 1), st);
+    case V_NHWC_S1: return nhwc_s1(g, dtype, pl.a, x, w, y, false, pl.b, nhwc_pf(g, dtype), st);
     case V_NHWC_K3S2: return nhwc_k3s2(g, dtype, pl.a, x, w, y, false, pl.b, st);
     case V_NCHW_FWD: return nchw_fwd(g, dtype, x, w, y, false, pl.b, st);
     case V_NCHWD_S1: return nchwd_s1(g, dtype, pl.a, x, w, y, false, pl.b, st);
@@ -219,7 +227,7 @@ hipError_t launch_bwd_data(const Plan &pl, const Geom &g, int layout, int dtype,
                            void *dx, hipStream_t st)
 {
     switch (pl.variant) {
-    case V_NHWC_S1: return nhwc_s1(g, dtype, pl.a, dy, w, dx, true, pl.b, tune("DWCONV_TUNE_TW", 1), tune("DWCONV_TUNE_PF", 1), st);
+    case V_NHWC_S1: return nhwc_s1(g, dtype, pl.a, dy, w, dx, true, pl.b, nhwc_pf(g, dtype), st);
     case V_NHWC_K3S2: return nhwc_k3s2(g, dtype, pl.a, dy, w, dx, true, pl.b, st);
     case V_NCHW_FWD: return nchw_fwd(g, dtype, dy, w, dx, true, pl.b, st);
     case V_NCHWD_S1: return nchwd_s1(g, dtype, pl.a, dy, w, dx, true, pl.b, st);
