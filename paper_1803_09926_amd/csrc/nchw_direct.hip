@@ -59,21 +59,18 @@ __global__ __launch_bounds__(256) void k_nchwd_s1(Geom g, const T *__restrict__ 
 #pragma unroll
     for (int i = 0; i < P; ++i) { loff[i] = has_left ? -(P - i) : 0; roff[i] = has_right ? V + i : V - 1; }
 
+    // The ring holds raw loads (clamped addresses); padding is applied when a row is consumed, so
+    // nothing waits on a load until then.  Every lane walks the same number of rows (TH + 2P):
+    // lanes of the image's last, shorter strip run past it with their stores masked.
     float ring[R][NW];
     auto load_row = [&](int r, float (&dst)[NW]) {
-        const int rr = min(max(r, 0), g.H - 1);
-        const bool rowok = rr == r;
-        const T *rp = xin + (size_t)rr * g.W;
+        const T *rp = xin + (size_t)min(max(r, 0), g.H - 1) * g.W;
         float mid[V];
         Vec<T, V>::load(rp, mid);
 #pragma unroll
-        for (int i = 0; i < P; ++i) {
-            const float a = ldf(rp + loff[i]), b = ldf(rp + roff[i]);
-            dst[i] = (rowok && has_left) ? a : 0.f;
-            dst[P + V + i] = (rowok && has_right) ? b : 0.f;
-        }
+        for (int i = 0; i < P; ++i) { dst[i] = ldf(rp + loff[i]); dst[P + V + i] = ldf(rp + roff[i]); }
 #pragma unroll
-        for (int v = 0; v < V; ++v) dst[P + v] = rowok ? mid[v] : 0.f;
+        for (int v = 0; v < V; ++v) dst[P + v] = mid[v];
     };
 
     float acc[K - 1 > 0 ? K - 1 : 1][V];
@@ -82,40 +79,50 @@ __global__ __launch_bounds__(256) void k_nchwd_s1(Geom g, const T *__restrict__ 
 #pragma unroll
         for (int v = 0; v < V; ++v) acc[j][v] = 0.f;
 
-    const int r0 = oh0 - P, r1 = oh1 + P;
+    auto consume = [&](int r, const float (&raw)[NW]) {
+        const bool rowok = r >= 0 && r < g.H;
+        float cur[NW];
 #pragma unroll
-    for (int j = 0; j < PF; ++j)
-        if (r0 + j < r1) load_row(r0 + j, ring[j]);
+        for (int i = 0; i < NW; ++i) {
+            const bool ok = rowok && (i < P ? has_left : (i >= P + V ? has_right : true));
+            cur[i] = ok ? raw[i] : 0.f;
+        }
+        float out[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            float s = (K > 1) ? acc[0][v] : 0.f;
+#pragma unroll
+            for (int kw = 0; kw < K; ++kw) s = fmaf(wr[K - 1][kw], cur[v + kw], s);
+            out[v] = s;
+        }
+#pragma unroll
+        for (int jj = 0; jj < K - 1; ++jj)
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                float s = (jj + 1 < K - 1) ? acc[jj + 1][v] : 0.f;
+#pragma unroll
+                for (int kw = 0; kw < K; ++kw) s = fmaf(wr[K - 2 - jj][kw], cur[v + kw], s);
+                acc[jj][v] = s;
+            }
+        const int oh = r - P;
+        if (oh >= oh0 && oh < oh1) store_vec<T, V>(yout + (size_t)oh * g.W, out, nt != 0);
+    };
+
+    const int r0 = oh0 - P, nrows = TH + 2 * P;
+#pragma unroll
+    for (int j = 0; j < PF; ++j) load_row(r0 + j, ring[j]);
+    int i = 0;
 #pragma unroll 1
-    for (int base = r0; base < r1; base += R) {
+    for (; i + R <= nrows; i += R) {
 #pragma unroll
         for (int j = 0; j < R; ++j) {
-            const int r = base + j;
-            if (r < r1) {
-                if (r + PF < r1) load_row(r + PF, ring[(j + PF) % R]);
-                const float (&cur)[NW] = ring[j];
-                float out[V];
-#pragma unroll
-                for (int v = 0; v < V; ++v) {
-                    float s = (K > 1) ? acc[0][v] : 0.f;
-#pragma unroll
-                    for (int kw = 0; kw < K; ++kw) s = fmaf(wr[K - 1][kw], cur[v + kw], s);
-                    out[v] = s;
-                }
-#pragma unroll
-                for (int jj = 0; jj < K - 1; ++jj)
-#pragma unroll
-                    for (int v = 0; v < V; ++v) {
-                        float s = (jj + 1 < K - 1) ? acc[jj + 1][v] : 0.f;
-#pragma unroll
-                        for (int kw = 0; kw < K; ++kw) s = fmaf(wr[K - 2 - jj][kw], cur[v + kw], s);
-                        acc[jj][v] = s;
-                    }
-                const int oh = r - P;
-                if (oh >= oh0) store_vec<T, V>(yout + (size_t)oh * g.W, out, nt != 0);
-            }
+            load_row(r0 + i + j + PF, ring[(j + PF) % R]);
+            consume(r0 + i + j, ring[j]);
         }
     }
+#pragma unroll
+    for (int j = 0; j < R - 1; ++j)
+        if (i + j < nrows) consume(r0 + i + j, ring[j]);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -144,48 +151,56 @@ __global__ __launch_bounds__(256) void k_nchwd_fwd_k3s2(Geom g, const T *__restr
     const int oh0 = ln.strip * TH, oh1 = min(g.Ho, oh0 + TH);
     const int loff = has_left ? -1 : 0;
 
+    // Raw loads (clamped row), masks applied at use: with H = 2*Ho every row 2oh, 2oh+1 of a valid
+    // output row is inside the image, so only the left neighbour (first vector of a row) and the
+    // row above the image need a select.  Every lane walks TH output rows; lanes past the end of
+    // a shorter last strip keep going with their stores masked.
     auto load_row = [&](int r, float (&dst)[NW]) {
-        const int rr = min(max(r, 0), g.H - 1);
-        const bool rowok = rr == r;
-        const T *rp = xin + (size_t)rr * g.W;
+        const T *rp = xin + (size_t)min(max(r, 0), g.H - 1) * g.W;
         float a[V], b[V];
         Vec<T, V>::load(rp, a);
         Vec<T, V>::load(rp + V, b);
-        const float l = ldf(rp + loff);
-        dst[0] = (rowok && has_left) ? l : 0.f;
+        dst[0] = ldf(rp + loff);
 #pragma unroll
-        for (int v = 0; v < V; ++v) { dst[1 + v] = rowok ? a[v] : 0.f; dst[1 + V + v] = rowok ? b[v] : 0.f; }
+        for (int v = 0; v < V; ++v) { dst[1 + v] = a[v]; dst[1 + V + v] = b[v]; }
     };
 
     float carry[V], re[2][NW], ro[2][NW];
     {
         float top[NW];
         load_row(2 * oh0 - 1, top);
+        const bool topok = oh0 > 0;
+        const float l = has_left ? top[0] : 0.f;
 #pragma unroll
-        for (int v = 0; v < V; ++v) carry[v] = fmaf(wr[0][0], top[2 * v], fmaf(wr[0][1], top[2 * v + 1], wr[0][2] * top[2 * v + 2]));
+        for (int v = 0; v < V; ++v) {
+            const float t = fmaf(wr[0][0], v == 0 ? l : top[2 * v], fmaf(wr[0][1], top[2 * v + 1], wr[0][2] * top[2 * v + 2]));
+            carry[v] = topok ? t : 0.f;
+        }
     }
     load_row(2 * oh0, re[0]);
     load_row(2 * oh0 + 1, ro[0]);
-#pragma unroll 1
-    for (int base = oh0; base < oh1; base += 2) {
+    auto step = [&](int oh, int j) {
+        const float le = has_left ? re[j][0] : 0.f, lo = has_left ? ro[j][0] : 0.f;
+        float out[V];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int oh = base + j;
-            if (oh < oh1) {
-                if (oh + 1 < oh1) { load_row(2 * oh + 2, re[j ^ 1]); load_row(2 * oh + 3, ro[j ^ 1]); }
-                float out[V];
-#pragma unroll
-                for (int v = 0; v < V; ++v) {
-                    float s = carry[v];
-                    s = fmaf(wr[1][0], re[j][2 * v], s); s = fmaf(wr[1][1], re[j][2 * v + 1], s); s = fmaf(wr[1][2], re[j][2 * v + 2], s);
-                    s = fmaf(wr[2][0], ro[j][2 * v], s); s = fmaf(wr[2][1], ro[j][2 * v + 1], s); s = fmaf(wr[2][2], ro[j][2 * v + 2], s);
-                    out[v] = s;
-                    carry[v] = fmaf(wr[0][0], ro[j][2 * v], fmaf(wr[0][1], ro[j][2 * v + 1], wr[0][2] * ro[j][2 * v + 2]));
-                }
-                store_vec<T, V>(yout + (size_t)oh * g.Wo, out, nt != 0);
-            }
+        for (int v = 0; v < V; ++v) {
+            float s = carry[v];
+            s = fmaf(wr[1][0], v == 0 ? le : re[j][2 * v], s); s = fmaf(wr[1][1], re[j][2 * v + 1], s); s = fmaf(wr[1][2], re[j][2 * v + 2], s);
+            s = fmaf(wr[2][0], v == 0 ? lo : ro[j][2 * v], s); s = fmaf(wr[2][1], ro[j][2 * v + 1], s); s = fmaf(wr[2][2], ro[j][2 * v + 2], s);
+            out[v] = s;
+            carry[v] = fmaf(wr[0][0], v == 0 ? lo : ro[j][2 * v], fmaf(wr[0][1], ro[j][2 * v + 1], wr[0][2] * ro[j][2 * v + 2]));
         }
+        if (oh < oh1) store_vec<T, V>(yout + (size_t)oh * g.Wo, out, nt != 0);
+    };
+    int i = 0;
+#pragma unroll 1
+    for (; i + 2 <= TH; i += 2) {
+        load_row(2 * (oh0 + i) + 2, re[1]); load_row(2 * (oh0 + i) + 3, ro[1]);
+        step(oh0 + i, 0);
+        load_row(2 * (oh0 + i) + 4, re[0]); load_row(2 * (oh0 + i) + 5, ro[0]);
+        step(oh0 + i + 1, 1);
     }
+    if (i < TH) step(oh0 + i, 0);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -217,41 +232,56 @@ __global__ __launch_bounds__(256) void k_nchwd_bwd_data_k3s2(Geom g, const T *__
     const int a0 = ln.strip * TH, a1 = min(g.Ho, a0 + TH);
     const int roff = has_right ? V : V - 1;
 
+    // Raw loads (clamped row); the row below the image's last dy row and the column right of a
+    // row's last vector are masked at use.  Every lane walks TH dy rows, stores masked past the
+    // end of a shorter last strip.
     auto load_row = [&](int a, float (&dst)[V + 1]) {
-        const int rr = min(a, g.Ho - 1);
-        const bool rowok = rr == a;
-        const T *rp = dyin + (size_t)rr * g.Wo;
+        const T *rp = dyin + (size_t)min(a, g.Ho - 1) * g.Wo;
         float m[V];
         Vec<T, V>::load(rp, m);
-        const float r = ldf(rp + roff);
+        dst[V] = ldf(rp + roff);
 #pragma unroll
-        for (int v = 0; v < V; ++v) dst[v] = rowok ? m[v] : 0.f;
-        dst[V] = (rowok && has_right) ? r : 0.f;
+        for (int v = 0; v < V; ++v) dst[v] = m[v];
     };
 
-    float rowA[2][V + 1];
-    load_row(a0, rowA[0]);
+    float rows[3][V + 1];
+    load_row(a0, rows[0]);
+    load_row(a0 + 1, rows[1]);
+    auto emit = [&](int a, const float (&Ar)[V + 1], const float (&Br)[V + 1]) {
+        const bool below = a + 1 < g.Ho;
+        float A[V + 1], B[V + 1];
+#pragma unroll
+        for (int v = 0; v < V; ++v) { A[v] = Ar[v]; B[v] = below ? Br[v] : 0.f; }
+        A[V] = has_right ? Ar[V] : 0.f;
+        B[V] = (has_right && below) ? Br[V] : 0.f;
+        float ev[2 * V], od[2 * V];   // dx rows 2a and 2a+1, the lane's 2V columns
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            ev[2 * v] = wr[1][1] * A[v];
+            ev[2 * v + 1] = fmaf(wr[1][0], A[v + 1], wr[1][2] * A[v]);
+            od[2 * v] = fmaf(wr[0][1], B[v], wr[2][1] * A[v]);
+            od[2 * v + 1] = fmaf(wr[0][0], B[v + 1], fmaf(wr[0][2], B[v], fmaf(wr[2][0], A[v + 1], wr[2][2] * A[v])));
+        }
+        if (a < a1) {
+            T *rp = dxout + (size_t)(2 * a) * g.W;
+            store_vec<T, 2 * V>(rp, ev, nt != 0);
+            store_vec<T, 2 * V>(rp + g.W, od, nt != 0);
+        }
+    };
+    int i = 0;
 #pragma unroll 1
-    for (int base = a0; base < a1; base += 2) {
+    for (; i + 3 <= TH; i += 3) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int a = base + j;
-            if (a < a1) {
-                load_row(a + 1, rowA[j ^ 1]);
-                const float (&A)[V + 1] = rowA[j];
-                const float (&B)[V + 1] = rowA[j ^ 1];
-                float ev[2 * V], od[2 * V];   // dx rows 2a and 2a+1, the lane's 2V columns
+        for (int j = 0; j < 3; ++j) {
+            load_row(a0 + i + j + 2, rows[(j + 2) % 3]);
+            emit(a0 + i + j, rows[j], rows[(j + 1) % 3]);
+        }
+    }
 #pragma unroll
-                for (int v = 0; v < V; ++v) {
-                    ev[2 * v] = wr[1][1] * A[v];
-                    ev[2 * v + 1] = fmaf(wr[1][0], A[v + 1], wr[1][2] * A[v]);
-                    od[2 * v] = fmaf(wr[0][1], B[v], wr[2][1] * A[v]);
-                    od[2 * v + 1] = fmaf(wr[0][0], B[v + 1], fmaf(wr[0][2], B[v], fmaf(wr[2][0], A[v + 1], wr[2][2] * A[v])));
-                }
-                T *rp = dxout + (size_t)(2 * a) * g.W;
-                store_vec<T, 2 * V>(rp, ev, nt != 0);
-                store_vec<T, 2 * V>(rp + g.W, od, nt != 0);
-            }
+    for (int j = 0; j < 2; ++j) {
+        if (i + j < TH) {
+            load_row(a0 + i + j + 2, rows[(j + 2) % 3]);
+            emit(a0 + i + j, rows[j], rows[(j + 1) % 3]);
         }
     }
 }
@@ -294,83 +324,100 @@ __global__ __launch_bounds__(256) void k_nchwd_bwd_filter_k3(Geom g, const T *__
             const T *xin = x + ((size_t)n * g.C + c_in) * g.H * g.W + c4 * V * S;
             const T *dyin = dy + ((size_t)n * g.O + o) * g.Ho * g.Wo + c4 * V;
             const int loff = has_left ? -1 : 0, roff = has_right ? V : V - 1;
+            // Raw loads with clamped rows; padding (rows outside the image, neighbours outside the
+            // row, dy rows past the strip) is applied when the values are used, so the loads of the
+            // next row stay in flight while this one is accumulated.  Every lane walks TH rows.
             auto load_x = [&](int r, float (&dst)[NW]) {
-                const int rr = min(max(r, 0), g.H - 1);
-                const bool rowok = rr == r;
-                const T *rp = xin + (size_t)rr * g.W;
+                const T *rp = xin + (size_t)min(max(r, 0), g.H - 1) * g.W;
                 if constexpr (S == 1) {
                     float m[V];
                     Vec<T, V>::load(rp, m);
-                    const float l = ldf(rp + loff), rt = ldf(rp + roff);
-                    dst[0] = (rowok && has_left) ? l : 0.f;
-                    dst[V + 1] = (rowok && has_right) ? rt : 0.f;
+                    dst[0] = ldf(rp + loff);
+                    dst[V + 1] = ldf(rp + roff);
 #pragma unroll
-                    for (int v = 0; v < V; ++v) dst[1 + v] = rowok ? m[v] : 0.f;
+                    for (int v = 0; v < V; ++v) dst[1 + v] = m[v];
                 } else {
                     float a[V], b[V];
                     Vec<T, V>::load(rp, a);
                     Vec<T, V>::load(rp + V, b);
-                    const float l = ldf(rp + loff);
-                    dst[0] = (rowok && has_left) ? l : 0.f;
+                    dst[0] = ldf(rp + loff);
 #pragma unroll
-                    for (int v = 0; v < V; ++v) { dst[1 + v] = rowok ? a[v] : 0.f; dst[1 + V + v] = rowok ? b[v] : 0.f; }
+                    for (int v = 0; v < V; ++v) { dst[1 + v] = a[v]; dst[1 + V + v] = b[v]; }
+                }
+            };
+            auto mask_x = [&](int r, float (&row)[NW]) {
+                const bool rowok = r >= 0 && r < g.H;
+#pragma unroll
+                for (int i = 0; i < NW; ++i) {
+                    const bool ok = rowok && (i == 0 ? has_left : ((S == 1 && i == V + 1) ? has_right : true));
+                    row[i] = ok ? row[i] : 0.f;
                 }
             };
             auto load_dy = [&](int oh, float (&dst)[V]) {
-                const int rr = min(oh, oh1 - 1);
-                Vec<T, V>::load(dyin + (size_t)rr * g.Wo, dst);
-                const bool ok = rr == oh;
-#pragma unroll
-                for (int v = 0; v < V; ++v) dst[v] = ok ? dst[v] : 0.f;
+                Vec<T, V>::load(dyin + (size_t)min(oh, g.Ho - 1) * g.Wo, dst);
             };
             // x rows oh*S-1, oh*S, oh*S+1 meet dy row oh at tap rows 0, 1, 2.
             float xa[NW], xb[NW], xc[2][NW], d[2][V], xs[2][NW];
             load_x(oh0 * S - 1, xa);
+            mask_x(oh0 * S - 1, xa);
             if constexpr (S == 1) {
                 load_x(oh0, xb);
+                mask_x(oh0, xb);
                 load_x(oh0 + 1, xc[0]); load_dy(oh0, d[0]);
-#pragma unroll 1
-                for (int base = oh0; base < oh1; base += 2) {
+                auto step = [&](int oh, int j) {
+                    mask_x(oh + 1, xc[j]);
+                    const bool dok = oh < oh1;
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        const int oh = base + j;
-                        if (oh < oh1) {
-                            if (oh + 1 < oh1) { load_x(oh + 2, xc[j ^ 1]); load_dy(oh + 1, d[j ^ 1]); }
+                    for (int v = 0; v < V; ++v) {
+                        const float dv = dok ? d[j][v] : 0.f;
 #pragma unroll
-                            for (int v = 0; v < V; ++v)
-#pragma unroll
-                                for (int kw = 0; kw < 3; ++kw) {
-                                    acc[0][kw] = fmaf(d[j][v], xa[v + kw], acc[0][kw]);
-                                    acc[1][kw] = fmaf(d[j][v], xb[v + kw], acc[1][kw]);
-                                    acc[2][kw] = fmaf(d[j][v], xc[j][v + kw], acc[2][kw]);
-                                }
-#pragma unroll
-                            for (int i = 0; i < NW; ++i) { xa[i] = xb[i]; xb[i] = xc[j][i]; }
+                        for (int kw = 0; kw < 3; ++kw) {
+                            acc[0][kw] = fmaf(dv, xa[v + kw], acc[0][kw]);
+                            acc[1][kw] = fmaf(dv, xb[v + kw], acc[1][kw]);
+                            acc[2][kw] = fmaf(dv, xc[j][v + kw], acc[2][kw]);
                         }
                     }
+#pragma unroll
+                    for (int i = 0; i < NW; ++i) { xa[i] = xb[i]; xb[i] = xc[j][i]; }
+                };
+                int i = 0;
+#pragma unroll 1
+                for (; i + 2 <= TH; i += 2) {
+                    load_x(oh0 + i + 2, xc[1]); load_dy(oh0 + i + 1, d[1]);
+                    step(oh0 + i, 0);
+                    load_x(oh0 + i + 3, xc[0]); load_dy(oh0 + i + 2, d[0]);
+                    step(oh0 + i + 1, 1);
                 }
+                if (i < TH) step(oh0 + i, 0);
             } else {
                 load_x(2 * oh0, xs[0]); load_x(2 * oh0 + 1, xc[0]); load_dy(oh0, d[0]);
-#pragma unroll 1
-                for (int base = oh0; base < oh1; base += 2) {
+                auto step = [&](int oh, int j) {
+                    // rows 2oh and 2oh+1 are inside the image for every valid oh (H = 2*Ho)
+                    const float ls = has_left ? xs[j][0] : 0.f, lc = has_left ? xc[j][0] : 0.f;
+                    xs[j][0] = ls; xc[j][0] = lc;
+                    const bool dok = oh < oh1;
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        const int oh = base + j;
-                        if (oh < oh1) {
-                            if (oh + 1 < oh1) { load_x(2 * oh + 2, xs[j ^ 1]); load_x(2 * oh + 3, xc[j ^ 1]); load_dy(oh + 1, d[j ^ 1]); }
+                    for (int v = 0; v < V; ++v) {
+                        const float dv = dok ? d[j][v] : 0.f;
 #pragma unroll
-                            for (int v = 0; v < V; ++v)
-#pragma unroll
-                                for (int kw = 0; kw < 3; ++kw) {
-                                    acc[0][kw] = fmaf(d[j][v], xa[2 * v + kw], acc[0][kw]);
-                                    acc[1][kw] = fmaf(d[j][v], xs[j][2 * v + kw], acc[1][kw]);
-                                    acc[2][kw] = fmaf(d[j][v], xc[j][2 * v + kw], acc[2][kw]);
-                                }
-#pragma unroll
-                            for (int i = 0; i < NW; ++i) xa[i] = xc[j][i];
+                        for (int kw = 0; kw < 3; ++kw) {
+                            acc[0][kw] = fmaf(dv, xa[2 * v + kw], acc[0][kw]);
+                            acc[1][kw] = fmaf(dv, xs[j][2 * v + kw], acc[1][kw]);
+                            acc[2][kw] = fmaf(dv, xc[j][2 * v + kw], acc[2][kw]);
                         }
                     }
+#pragma unroll
+                    for (int i = 0; i < NW; ++i) xa[i] = xc[j][i];
+                };
+                int i = 0;
+#pragma unroll 1
+                for (; i + 2 <= TH; i += 2) {
+                    load_x(2 * (oh0 + i) + 2, xs[1]); load_x(2 * (oh0 + i) + 3, xc[1]); load_dy(oh0 + i + 1, d[1]);
+                    step(oh0 + i, 0);
+                    load_x(2 * (oh0 + i) + 4, xs[0]); load_x(2 * (oh0 + i) + 5, xc[0]); load_dy(oh0 + i + 2, d[0]);
+                    step(oh0 + i + 1, 1);
                 }
+                if (i < TH) step(oh0 + i, 0);
             }
         }
     }
