@@ -437,6 +437,115 @@ __global__ __launch_bounds__(256) void k_nchwd_bwd_filter_k3(Geom g, const T *__
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Backward-filter stage 1, K x K (K odd), stride 1, "same" padding: same block organisation as the
+// 3x3 kernel above (one channel per block, sub-groups take (image, strip) items, one partial per
+// block), written input-row-major: x row r meets dy row r + P - kh at tap row kh, so a lane keeps
+// the K live dy rows in a shifting window and K*K partial sums.
+// ---------------------------------------------------------------------------------------------
+template <typename T, int V, int K>
+__global__ __launch_bounds__(256) void k_nchwd_bwd_filter_s1(Geom g, const T *__restrict__ x, const T *__restrict__ dy,
+                                                             float *__restrict__ ws, int TH, int nstrips, int sg_log2,
+                                                             int rounds)
+{
+    __shared__ float red[4][K * K];
+    constexpr int P = (K - 1) / 2;
+    constexpr int NW = V + 2 * P;
+    const int o = blockIdx.y, part = blockIdx.x;
+    const int SG = 1 << sg_log2, nsg = 256 >> sg_log2;
+    const int sg = threadIdx.x >> sg_log2, c4 = threadIdx.x & (SG - 1);
+    const int ncols = g.W / V;
+    const int nitems = g.N * nstrips;
+    const int c_in = o / g.m;
+    const bool has_left = c4 > 0, has_right = c4 < ncols - 1;
+
+    float acc[K][K];
+#pragma unroll
+    for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < K; ++kw) acc[kh][kw] = 0.f;
+
+    if (c4 < ncols) {
+        int loff[P], roff[P];
+#pragma unroll
+        for (int i = 0; i < P; ++i) { loff[i] = has_left ? -(P - i) : 0; roff[i] = has_right ? V + i : V - 1; }
+        for (int rd = 0; rd < rounds; ++rd) {
+            const int item = (part * rounds + rd) * nsg + sg;
+            if (item >= nitems) break;
+            const int n = item / nstrips, strip = item - n * nstrips;
+            const int oh0 = strip * TH, oh1 = min(g.H, oh0 + TH);
+            const T *xin = x + ((size_t)n * g.C + c_in) * g.H * g.W + c4 * V;
+            const T *dyin = dy + ((size_t)n * g.O + o) * g.H * g.W + c4 * V;
+            auto load_row = [&](int r, float (&xd)[NW], float (&dd)[V]) {
+                const T *rp = xin + (size_t)min(max(r, 0), g.H - 1) * g.W;
+                float m[V];
+                Vec<T, V>::load(rp, m);
+#pragma unroll
+                for (int i = 0; i < P; ++i) { xd[i] = ldf(rp + loff[i]); xd[P + V + i] = ldf(rp + roff[i]); }
+#pragma unroll
+                for (int v = 0; v < V; ++v) xd[P + v] = m[v];
+                Vec<T, V>::load(dyin + (size_t)min(max(r + P, 0), g.H - 1) * g.W, dd);
+            };
+            float dyw[K][V];
+#pragma unroll
+            for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+                for (int v = 0; v < V; ++v) dyw[kh][v] = 0.f;
+            float xr[2][NW], dr[2][V];
+            auto step = [&](int r, int j) {
+                const bool rowok = r >= 0 && r < g.H;
+                const bool dok = r + P >= oh0 && r + P < oh1;
+                float xv[NW];
+#pragma unroll
+                for (int i = 0; i < NW; ++i) {
+                    const bool ok = rowok && (i < P ? has_left : (i >= P + V ? has_right : true));
+                    xv[i] = ok ? xr[j][i] : 0.f;
+                }
+#pragma unroll
+                for (int kh = K - 1; kh > 0; --kh)
+#pragma unroll
+                    for (int v = 0; v < V; ++v) dyw[kh][v] = dyw[kh - 1][v];
+#pragma unroll
+                for (int v = 0; v < V; ++v) dyw[0][v] = dok ? dr[j][v] : 0.f;
+#pragma unroll
+                for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+                    for (int kw = 0; kw < K; ++kw) {
+                        float sacc = acc[kh][kw];
+#pragma unroll
+                        for (int v = 0; v < V; ++v) sacc = fmaf(dyw[kh][v], xv[v + kw], sacc);
+                        acc[kh][kw] = sacc;
+                    }
+            };
+            const int r0 = oh0 - P, nrows = TH + 2 * P;
+            load_row(r0, xr[0], dr[0]);
+            int i = 0;
+#pragma unroll 1
+            for (; i + 2 <= nrows; i += 2) {
+                load_row(r0 + i + 1, xr[1], dr[1]);
+                step(r0 + i, 0);
+                load_row(r0 + i + 2, xr[0], dr[0]);
+                step(r0 + i + 1, 1);
+            }
+            if (i < nrows) step(r0 + i, 0);
+        }
+    }
+
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+#pragma unroll
+    for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < K; ++kw) {
+            const float s = wave_sum(acc[kh][kw]);
+            if (lane == 0) red[wv][kh * K + kw] = s;
+        }
+    __syncthreads();
+    if (threadIdx.x < K * K) {
+        const int t = threadIdx.x;
+        ws[((size_t)part * g.O + o) * (K * K) + t] = (red[0][t] + red[1][t]) + (red[2][t] + red[3][t]);
+    }
+}
+
 // ---- host side --------------------------------------------------------------------------------
 
 // vector width for the direct kernels (0 = not applicable): rows must be whole 16-byte vectors;
@@ -447,7 +556,7 @@ int nchwd_vec(const Geom &g, int dtype, int pass)
     const bool s2 = g.s == 2 && g.K == 3 && g.p == 1 && g.W % 2 == 0 && g.H % 2 == 0;
     if (!s1 && !s2) return 0;
     if (pass == 1 && g.m != 1) return 0;
-    if (pass == 2 && g.K != 3) return 0;
+    if (pass == 2 && g.K != 3 && !(g.K == 5 && s1)) return 0;
     if (g.H < 16) return 0;                      // small planes go to the LDS-tile kernels
     const int wv = s1 ? g.W : g.Wo;              // the dimension that lanes split into vectors
     if (s2 && pass == 1) {                       // dy columns per lane; dx is stored 2V wide
@@ -536,7 +645,15 @@ hipError_t nchwd_bwd_filter(const Geom &g, int dtype, int V, const void *x, cons
     dim3 grid(parts, g.O);
 #define GO(T, VV, SS) hipLaunchKernelGGL((k_nchwd_bwd_filter_k3<T, VV, SS>), grid, dim3(256), 0, st, g, (const T *)x, \
                                          (const T *)dy, ws, TH, nstrips, lg, rounds)
-    if (g.s == 1) {
+    if (g.s == 1 && g.K == 5) {
+#define GO5(T, VV) hipLaunchKernelGGL((k_nchwd_bwd_filter_s1<T, VV, 5>), grid, dim3(256), 0, st, g, (const T *)x, \
+                                      (const T *)dy, ws, TH, nstrips, lg, rounds)
+        if (dtype == DT_F32 && V == 4) GO5(float, 4);
+        else if (dtype == DT_BF16 && V == 8) GO5(bf16_t, 8);
+        else if (dtype == DT_BF16 && V == 4) GO5(bf16_t, 4);
+        else return hipErrorInvalidValue;
+#undef GO5
+    } else if (g.s == 1) {
         if (dtype == DT_F32 && V == 4) GO(float, 4, 1);
         else if (dtype == DT_BF16 && V == 8) GO(bf16_t, 8, 1);
         else if (dtype == DT_BF16 && V == 4) GO(bf16_t, 4, 1);

@@ -1,4 +1,5 @@
-// NCHW kernels for small planes (rows of 7, 14 or 28 elements; 3x3 filters; multiplier 1).
+// NCHW kernels for small planes (rows of 7, 14 or 28 elements; 3x3 filters, 5x5 at stride 1;
+// multiplier 1).
 // Rows this short are not whole 16-byte vectors, but consecutive planes are contiguous, so a block
 // takes a run of whole planes as ONE flat range: aligned 16-byte loads into LDS (all of a lane's
 // loads issued before its first wait), then one lane per (plane, output row) computes the whole
@@ -70,16 +71,17 @@ __device__ __forceinline__ void flat_store(T *__restrict__ dst, int g0, int g1, 
 }
 
 // ---------------------------------------------------------------------------------------------
-// Forward 3x3, pad 1, stride S, row width W (template).  FLIP: filter rotated by 180 degrees
+// Forward K x K (K odd), pad (K-1)/2, stride S, row width W (template).  FLIP: filter rotated by 180 degrees
 // (backward-data of the stride-1 layer).  U planes per block, one lane per (plane, output row).
 // ---------------------------------------------------------------------------------------------
-template <typename T, int S, int W, bool FLIP>
+template <typename T, int K, int S, int W, bool FLIP>
 __global__ __launch_bounds__(256) void k_nchws_fwd(Geom g, const T *__restrict__ x, const T *__restrict__ w,
                                                    T *__restrict__ y, int U, int nplanes, unsigned nblocks)
 {
     extern __shared__ float4 smem4[];
     constexpr int VE = ElemsS<T>::VE;
-    constexpr int WO = (W + 2 - 3) / S + 1;
+    constexpr int P = (K - 1) / 2;
+    constexpr int WO = (W + 2 * P - K) / S + 1;
     const int HW = g.H * W, HoWo = g.Ho * WO;
     const unsigned lb = xcd_remap(blockIdx.x, nblocks);
     const int p0 = lb * U, np = min(U, nplanes - p0);
@@ -93,15 +95,15 @@ __global__ __launch_bounds__(256) void k_nchws_fwd(Geom g, const T *__restrict__
     const int p = threadIdx.x / g.Ho, oh = threadIdx.x - p * g.Ho;
     if (p < np) {
         const int c = (p0 + p) % g.C;
-        float wr[3][3];
+        float wr[K][K];
         // taps on rows outside the image are dropped by zeroing their weights (the row address is clamped)
 #pragma unroll
-        for (int kh = 0; kh < 3; ++kh) {
-            const int ih = oh * S - 1 + kh;
+        for (int kh = 0; kh < K; ++kh) {
+            const int ih = oh * S - P + kh;
             const bool ok = ih >= 0 && ih < g.H;
 #pragma unroll
-            for (int kw = 0; kw < 3; ++kw) {
-                const float t = ldf(w + (c * 3 + (FLIP ? 2 - kh : kh)) * 3 + (FLIP ? 2 - kw : kw));
+            for (int kw = 0; kw < K; ++kw) {
+                const float t = ldf(w + (c * K + (FLIP ? K - 1 - kh : kh)) * K + (FLIP ? K - 1 - kw : kw));
                 wr[kh][kw] = ok ? t : 0.f;
             }
         }
@@ -110,8 +112,8 @@ __global__ __launch_bounds__(256) void k_nchws_fwd(Geom g, const T *__restrict__
 #pragma unroll
         for (int j = 0; j < WO; ++j) out[j] = 0.f;
 #pragma unroll
-        for (int kh = 0; kh < 3; ++kh) {
-            const int ih = min(max(oh * S - 1 + kh, 0), g.H - 1);
+        for (int kh = 0; kh < K; ++kh) {
+            const int ih = min(max(oh * S - P + kh, 0), g.H - 1);
             const float *rp = pl + ih * W;
             float row[W];
 #pragma unroll
@@ -119,8 +121,8 @@ __global__ __launch_bounds__(256) void k_nchws_fwd(Geom g, const T *__restrict__
 #pragma unroll
             for (int j = 0; j < WO; ++j)
 #pragma unroll
-                for (int kw = 0; kw < 3; ++kw) {
-                    const int iw = j * S - 1 + kw;
+                for (int kw = 0; kw < K; ++kw) {
+                    const int iw = j * S - P + kw;
                     if (iw >= 0 && iw < W) out[j] = fmaf(wr[kh][kw], row[iw], out[j]);
                 }
         }
@@ -184,19 +186,20 @@ __global__ __launch_bounds__(256) void k_nchws_bwd_data_s2(Geom g, const T *__re
 }
 
 // ---------------------------------------------------------------------------------------------
-// Backward-filter stage 1, 3x3, pad 1, stride S, x row width W (template).  A block owns U
-// consecutive channels and walks NI images; a lane owns (channel, output row) and keeps its nine
+// Backward-filter stage 1, K x K (K odd), pad (K-1)/2, stride S, x row width W (template).  A block owns U
+// consecutive channels and walks NI images; a lane owns (channel, output row) and keeps its K*K
 // partial sums in registers across the images.  At the end the rows of a channel are added in
 // row order through LDS and one partial per block is written at ws[part][c][kh][kw].
 // ---------------------------------------------------------------------------------------------
-template <typename T, int S, int W>
+template <typename T, int K, int S, int W>
 __global__ __launch_bounds__(256) void k_nchws_bwd_filter(Geom g, const T *__restrict__ x, const T *__restrict__ dy,
                                                           float *__restrict__ ws, int U, int NI, int ncblocks,
                                                           unsigned nblocks)
 {
     extern __shared__ float4 smem4[];
     constexpr int VE = ElemsS<T>::VE;
-    constexpr int WO = (W + 2 - 3) / S + 1;
+    constexpr int P = (K - 1) / 2;
+    constexpr int WO = (W + 2 * P - K) / S + 1;
     const int HW = g.H * W, HoWo = g.Ho * WO;
     const unsigned lb = xcd_remap(blockIdx.x, nblocks);
     const int cblk = lb % ncblocks, part = lb / ncblocks;
@@ -206,16 +209,16 @@ __global__ __launch_bounds__(256) void k_nchws_bwd_filter(Geom g, const T *__res
     float *ld = lx + ((U * HW + 2 * VE + 3) & ~3);
 
     const int p = threadIdx.x / g.Ho, oh = threadIdx.x - p * g.Ho;
-    float acc[3][3];
+    float acc[K][K];
 #pragma unroll
-    for (int kh = 0; kh < 3; ++kh)
+    for (int kh = 0; kh < K; ++kh)
 #pragma unroll
-        for (int kw = 0; kw < 3; ++kw) acc[kh][kw] = 0.f;
-    bool rowok[3];
-    int rowi[3];
+        for (int kw = 0; kw < K; ++kw) acc[kh][kw] = 0.f;
+    bool rowok[K];
+    int rowi[K];
 #pragma unroll
-    for (int kh = 0; kh < 3; ++kh) {
-        const int ih = oh * S - 1 + kh;
+    for (int kh = 0; kh < K; ++kh) {
+        const int ih = oh * S - P + kh;
         rowok[kh] = ih >= 0 && ih < g.H;
         rowi[kh] = min(max(ih, 0), g.H - 1);
     }
@@ -233,17 +236,17 @@ __global__ __launch_bounds__(256) void k_nchws_bwd_filter(Geom g, const T *__res
 #pragma unroll
             for (int j = 0; j < WO; ++j) d[j] = dp[j];
 #pragma unroll
-            for (int kh = 0; kh < 3; ++kh) {
+            for (int kh = 0; kh < K; ++kh) {
                 const float *rp = xp + rowi[kh] * W;
                 float row[W];
 #pragma unroll
                 for (int i = 0; i < W; ++i) { const float t = rp[i]; row[i] = rowok[kh] ? t : 0.f; }
 #pragma unroll
-                for (int kw = 0; kw < 3; ++kw) {
+                for (int kw = 0; kw < K; ++kw) {
                     float s = acc[kh][kw];
 #pragma unroll
                     for (int j = 0; j < WO; ++j) {
-                        const int iw = j * S - 1 + kw;
+                        const int iw = j * S - P + kw;
                         if (iw >= 0 && iw < W) s = fmaf(d[j], row[iw], s);
                     }
                     acc[kh][kw] = s;
@@ -254,17 +257,17 @@ __global__ __launch_bounds__(256) void k_nchws_bwd_filter(Geom g, const T *__res
 
     // rows of a channel are added in row order (fixed), through LDS
     __syncthreads();
-    float *red = lx;     // 256 * 9 floats, reusing the x area (U*HW >= 9*U*Ho since W >= 7... checked on the host)
+    float *red = lx;     // 256 * K*K floats, reusing the staging areas (the host sizes the LDS for it)
 #pragma unroll
-    for (int kh = 0; kh < 3; ++kh)
+    for (int kh = 0; kh < K; ++kh)
 #pragma unroll
-        for (int kw = 0; kw < 3; ++kw) red[threadIdx.x * 9 + kh * 3 + kw] = (p < nc) ? acc[kh][kw] : 0.f;
+        for (int kw = 0; kw < K; ++kw) red[threadIdx.x * (K * K) + kh * K + kw] = (p < nc) ? acc[kh][kw] : 0.f;
     __syncthreads();
-    for (int idx = threadIdx.x; idx < nc * 9; idx += 256) {
-        const int pc = idx / 9, t = idx - pc * 9;
+    for (int idx = threadIdx.x; idx < nc * K * K; idx += 256) {
+        const int pc = idx / (K * K), t = idx - pc * (K * K);
         float s = 0.f;
-        for (int r = 0; r < g.Ho; ++r) s += red[(pc * g.Ho + r) * 9 + t];
-        ws[((size_t)part * g.O + c0 + pc) * 9 + t] = s;
+        for (int r = 0; r < g.Ho; ++r) s += red[(pc * g.Ho + r) * (K * K) + t];
+        ws[((size_t)part * g.O + c0 + pc) * (K * K) + t] = s;
     }
 }
 
@@ -276,7 +279,11 @@ static inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 // that one lane per output row fills a block with at least 8 planes.
 bool nchws_supported(const Geom &g, int pass)
 {
-    if (g.K != 3 || g.p != 1 || g.m != 1 || (g.s != 1 && g.s != 2)) return false;
+    if (g.m != 1) return false;
+    const bool k3 = g.K == 3 && g.p == 1 && (g.s == 1 || g.s == 2);
+    const bool k5 = g.K == 5 && g.p == 2 && g.s == 1;   // 5x5 stride 1 (backward-data runs the forward kernel with the rotated filter)
+    if (!k3 && !k5) return false;
+    if (g.K == 5 && g.W == 28) return false;     // 28-wide rows with 25 taps: too many registers per lane
     if (!(g.W == 7 || g.W == 14 || g.W == 28)) return false;
     if (g.s == 2 && (g.W % 2 != 0 || g.H % 2 != 0)) return false;
     if (g.Ho > 32 || g.H > 32) return false;
@@ -301,10 +308,10 @@ static hipError_t go_fwd(const Geom &g, const void *x, const void *w, void *y, b
     const size_t lds = lds_bytes_for(U, HW, HoWo, VE);
     const int nplanes = g.N * g.C;
     const unsigned nblocks = (unsigned)cdiv(nplanes, U);
-#define GO(SS, WW, FL) hipLaunchKernelGGL((k_nchws_fwd<T, SS, WW, FL>), dim3(nblocks), dim3(256), lds, st, g, (const T *)x, \
-                                          (const T *)w, (T *)y, U, nplanes, nblocks)
-#define PICK(SS, WW) if (g.s == SS && g.W == WW) { if (flip) GO(SS, WW, true); else GO(SS, WW, false); return hipGetLastError(); }
-    PICK(1, 7) PICK(1, 14) PICK(1, 28) PICK(2, 14) PICK(2, 28)
+#define GO(KK, SS, WW, FL) hipLaunchKernelGGL((k_nchws_fwd<T, KK, SS, WW, FL>), dim3(nblocks), dim3(256), lds, st, g, \
+                                              (const T *)x, (const T *)w, (T *)y, U, nplanes, nblocks)
+#define PICK(KK, SS, WW) if (g.K == KK && g.s == SS && g.W == WW) { if (flip) GO(KK, SS, WW, true); else GO(KK, SS, WW, false); return hipGetLastError(); }
+    PICK(3, 1, 7) PICK(3, 1, 14) PICK(3, 1, 28) PICK(3, 2, 14) PICK(3, 2, 28) PICK(5, 1, 7) PICK(5, 1, 14)
 #undef PICK
 #undef GO
     return hipErrorInvalidValue;
@@ -363,16 +370,18 @@ static hipError_t go_bwd_filter(const Geom &g, const void *x, const void *dy, fl
     constexpr int VE = ElemsS<T>::VE;
     const int HW = g.H * g.W, HoWo = g.Ho * g.Wo;
     size_t lds = lds_bytes_for(U, HW, HoWo, VE);
-    if (lds < 256 * 9 * sizeof(float)) lds = 256 * 9 * sizeof(float);
+    if (lds < 256 * (size_t)(g.K * g.K) * sizeof(float)) lds = 256 * (size_t)(g.K * g.K) * sizeof(float);
     const int ncb = cdiv(g.C, U);
     const unsigned nblocks = (unsigned)ncb * cdiv(g.N, NI);
-#define GO(SS, WW) hipLaunchKernelGGL((k_nchws_bwd_filter<T, SS, WW>), dim3(nblocks), dim3(256), lds, st, g, (const T *)x, \
-                                      (const T *)dy, ws, U, NI, ncb, nblocks)
-    if (g.s == 1 && g.W == 7) GO(1, 7);
-    else if (g.s == 1 && g.W == 14) GO(1, 14);
-    else if (g.s == 1 && g.W == 28) GO(1, 28);
-    else if (g.s == 2 && g.W == 14) GO(2, 14);
-    else if (g.s == 2 && g.W == 28) GO(2, 28);
+#define GO(KK, SS, WW) hipLaunchKernelGGL((k_nchws_bwd_filter<T, KK, SS, WW>), dim3(nblocks), dim3(256), lds, st, g, \
+                                          (const T *)x, (const T *)dy, ws, U, NI, ncb, nblocks)
+    if (g.K == 3 && g.s == 1 && g.W == 7) GO(3, 1, 7);
+    else if (g.K == 3 && g.s == 1 && g.W == 14) GO(3, 1, 14);
+    else if (g.K == 3 && g.s == 1 && g.W == 28) GO(3, 1, 28);
+    else if (g.K == 3 && g.s == 2 && g.W == 14) GO(3, 2, 14);
+    else if (g.K == 3 && g.s == 2 && g.W == 28) GO(3, 2, 28);
+    else if (g.K == 5 && g.s == 1 && g.W == 7) GO(5, 1, 7);
+    else if (g.K == 5 && g.s == 1 && g.W == 14) GO(5, 1, 14);
     else return hipErrorInvalidValue;
 #undef GO
     return hipGetLastError();

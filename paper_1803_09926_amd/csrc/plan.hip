@@ -70,7 +70,7 @@ Plan plan_fwd(const Geom &g, int layout, int dtype)
 {
     Plan pl = {V_GENERIC, 0, 0, 0, 0, "generic"};
     if (layout == LAYOUT_NCHW) {
-        if (use_small(g, 0)) { pl.variant = V_NCHWS_FWD; pl.name = g.s == 1 ? "nchw_smallplane_k3s1" : "nchw_smallplane_fwd_k3s2"; return pl; }
+        if (use_small(g, 0)) { pl.variant = V_NCHWS_FWD; pl.name = g.K == 5 ? "nchw_smallplane_k5s1" : (g.s == 1 ? "nchw_smallplane_k3s1" : "nchw_smallplane_fwd_k3s2"); return pl; }
         const int V = nchwd_vec(g, dtype, 0);
         if (V) {
             pl.a = V;
@@ -100,7 +100,7 @@ Plan plan_bwd_data(const Geom &g, int layout, int dtype)
     Plan pl = {V_GENERIC, 0, 0, 0, 0, "generic"};
     if (layout == LAYOUT_NCHW) {
         if (use_small(g, 1)) {
-            if (g.s == 1) { pl.variant = V_NCHWS_FWD; pl.name = "nchw_smallplane_k3s1_flip"; }
+            if (g.s == 1) { pl.variant = V_NCHWS_FWD; pl.name = g.K == 5 ? "nchw_smallplane_k5s1_flip" : "nchw_smallplane_k3s1_flip"; }
             else { pl.variant = V_NCHWS_BWD_DATA_S2; pl.name = "nchw_smallplane_bwd_data_k3s2"; }
             return pl;
         }
@@ -143,9 +143,10 @@ Plan plan_bwd_filter(const Geom &g, int layout, int dtype)
             NI = tune("DWCONV_TUNE_NI", NI);
             if (NI > g.N) NI = g.N;
             parts = ceil_div(g.N, NI);
-            if ((long long)parts * g.O * 9 * 4 <= (64ll << 20)) {
+            if ((long long)parts * g.O * g.K * g.K * 4 <= (64ll << 20)) {
                 pl.variant = V_NCHWS_BWD_FILTER; pl.a = U; pl.c = NI; pl.parts = parts;
-                pl.name = g.s == 1 ? "nchw_smallplane_bwd_filter_k3s1" : "nchw_smallplane_bwd_filter_k3s2";
+                pl.name = g.K == 5 ? "nchw_smallplane_bwd_filter_k5s1"
+                                   : (g.s == 1 ? "nchw_smallplane_bwd_filter_k3s1" : "nchw_smallplane_bwd_filter_k3s2");
                 return pl;
             }
         }
@@ -154,9 +155,10 @@ Plan plan_bwd_filter(const Geom &g, int layout, int dtype)
             int TH = tune("DWCONV_TUNE_THW", tune("DWCONV_TUNE_TH", g.Ho > 56 ? (g.Ho + 1) / 2 : (g.s == 2 && g.Ho >= 28 ? (g.Ho + 1) / 2 : g.Ho)));
             int lg, nst, rounds, parts;
             nchwd_bwd_filter_tiling(g, V, TH, &lg, &nst, &rounds, &parts);
-            if (lg <= 8 && (long long)parts * g.O * 9 * 4 <= (64ll << 20)) {
+            if (lg <= 8 && (long long)parts * g.O * g.K * g.K * 4 <= (64ll << 20)) {
                 pl.variant = V_NCHWD_BWD_FILTER; pl.a = V; pl.b = TH; pl.parts = parts;
-                pl.name = g.s == 1 ? "nchw_rowwalk_bwd_filter_k3s1" : "nchw_rowwalk_bwd_filter_k3s2";
+                pl.name = g.K == 5 ? "nchw_rowwalk_bwd_filter_k5s1"
+                                   : (g.s == 1 ? "nchw_rowwalk_bwd_filter_k3s1" : "nchw_rowwalk_bwd_filter_k3s2");
                 return pl;
             }
         }
@@ -181,7 +183,10 @@ Plan plan_bwd_filter(const Geom &g, int layout, int dtype)
         return pl;
     }
     if (layout == LAYOUT_NHWC) {
-        const int V = nhwc_vec(g, dtype);
+        int V = nhwc_vec(g, dtype);
+        // bf16 stride 2: 8 channels per lane need more than 256 registers (three input rows per output
+        // row in flight); 4 channels per lane measured 1.5x faster
+        if (V == 8 && g.s == 2) V = 4;
         if (V && (same_pad_s1(g) || k3s2p1(g))) {
             // One block = 256 lanes over (columns x channel-vectors) x one strip x NI images.  Long
             // walks win (fewer partials, less stage-2 work): start from whole columns and one image
