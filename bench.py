@@ -194,7 +194,8 @@ def main():
     gbs = step_bytes / (dt / args.steps) / 1e9
 
     out = {
-        "metric": METRIC, "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "metric": METRIC if args.config == 2 else "ms and HBM GB/s (% of peak) per fwd+bwd of " + cfg["name"],
+        "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32" if cfg["dtype"] == wl.F32 else "bf16", "data": "synthetic",
         "config": {"workload": cfg["name"], "batch": cfg["N"],

@@ -37,7 +37,7 @@ template <int V, int K, int PF> constexpr int S1_WAVES()
 // FLIP = true reads the filter rotated by 180 degrees, which makes this the backward-data pass
 // of the same layer (input = dy, output = dx).
 // ---------------------------------------------------------------------------------------------
-template <typename T, int V, int K, int PF, bool FLIP>
+template <typename T, int V, int K, int PF, bool FLIP, int M>
 __global__ __launch_bounds__(256, (S1_WAVES<V, K, PF>())) void k_nhwc_s1(
     Geom g, const T *__restrict__ x, const T *__restrict__ w, T *__restrict__ y, int TH, int nstrips, int nchunks,
     unsigned nblocks, int nt)
@@ -45,10 +45,16 @@ __global__ __launch_bounds__(256, (S1_WAVES<V, K, PF>())) void k_nhwc_s1(
     constexpr int P = (K - 1) / 2;
     constexpr int R = PF + 1;             // ring of rows: PF in flight + the one being consumed
     const Tile tl = tile_of(nblocks, nchunks, nstrips);
-    const int Q = g.C / V;
+    // A lane owns V consecutive OUTPUT channels of the layer (o = cq*V ...), which read V/M input
+    // channels.  Forward: load V/M channels of x, store V channels of y.  Backward-data: load V
+    // channels of dy, add the M outputs that share an input channel, store V/M channels of dx.
+    constexpr int VI = FLIP ? V : V / M;      // channels per lane in the tensor that is read
+    constexpr int VO = FLIP ? V / M : V;      // channels per lane in the tensor that is written
+    const int Q = g.O / V;
     const int f = tl.chunk * blockDim.x + threadIdx.x;
     if (f >= g.W * Q) return;
     const int cq = f % Q, ow = f / Q;
+    const int CI = FLIP ? g.O : g.C, CO = FLIP ? g.C : g.O;   // channels per pixel, read / written
 
     int coloff[K];
     float wr[K][K][V];
@@ -56,21 +62,20 @@ __global__ __launch_bounds__(256, (S1_WAVES<V, K, PF>())) void k_nhwc_s1(
     for (int kw = 0; kw < K; ++kw) {
         const int iw = ow - P + kw;
         const bool ok = iw >= 0 && iw < g.W;
-        coloff[kw] = (ok ? iw - ow : 0) * g.C;
+        coloff[kw] = (ok ? iw - ow : 0) * CI;
 #pragma unroll
         for (int kh = 0; kh < K; ++kh) {
             const int sh = FLIP ? K - 1 - kh : kh, sw = FLIP ? K - 1 - kw : kw;
-            Vec<T, V>::load(w + (sh * K + sw) * g.C + cq * V, wr[kh][kw]);
+            Vec<T, V>::load(w + (sh * K + sw) * g.O + cq * V, wr[kh][kw]);
 #pragma unroll
             for (int v = 0; v < V; ++v) wr[kh][kw][v] = ok ? wr[kh][kw][v] : 0.f;
         }
     }
 
     const int oh0 = tl.strip * TH, oh1 = min(g.H, oh0 + TH);
-    const int rowstride = g.W * g.C;
-    const size_t img = (size_t)tl.n * g.H * rowstride;
-    const T *xin = x + img + (size_t)ow * g.C + cq * V;
-    T *yout = y + img + (size_t)ow * g.C + cq * V;
+    const int rowstride = g.W * CI, orowstride = g.W * CO;
+    const T *xin = x + (size_t)tl.n * g.H * rowstride + (size_t)ow * CI + cq * VI;
+    T *yout = y + (size_t)tl.n * g.H * orowstride + (size_t)ow * CO + cq * VO;
 
     float acc[K - 1 > 0 ? K - 1 : 1][V];
 #pragma unroll
@@ -84,20 +89,35 @@ __global__ __launch_bounds__(256, (S1_WAVES<V, K, PF>())) void k_nhwc_s1(
     // (a few redundant re-loads of the last row at the end of a strip).
     const int r0 = oh0 - P, r1 = oh1 + P;
     const int ra = max(r0, 0), rb = min(r1, g.H);
-    float ring[R][K][V];
-    auto load_row = [&](int r, float (&dst)[K][V]) {
+    float ring[R][K][VI];
+    auto load_row = [&](int r, float (&dst)[K][VI]) {
         const T *rp = xin + (size_t)min(r, rb - 1) * rowstride;
 #pragma unroll
-        for (int kw = 0; kw < K; ++kw) Vec<T, V>::load(rp + coloff[kw], dst[kw]);
+        for (int kw = 0; kw < K; ++kw) Vec<T, VI>::load(rp + coloff[kw], dst[kw]);
     };
-    auto consume = [&](int r, const float (&cur)[K][V]) {
+    auto emit = [&](int oh, const float (&out)[V]) {
+        if constexpr (VO == V) {
+            store_vec<T, V>(yout + (size_t)oh * orowstride, out, nt != 0);
+        } else {
+            float red[VO];
+#pragma unroll
+            for (int c = 0; c < VO; ++c) {
+                float t = out[c * M];
+#pragma unroll
+                for (int q = 1; q < M; ++q) t += out[c * M + q];
+                red[c] = t;
+            }
+            store_vec<T, VO>(yout + (size_t)oh * orowstride, red, nt != 0);
+        }
+    };
+    auto consume = [&](int r, const float (&cur)[K][VI]) {
         // input row r is tap row kh of output row r + P - kh
         float out[V];
 #pragma unroll
         for (int v = 0; v < V; ++v) {
             float s = (K > 1) ? acc[0][v] : 0.f;
 #pragma unroll
-            for (int kw = 0; kw < K; ++kw) s = fmaf(wr[K - 1][kw][v], cur[kw][v], s);
+            for (int kw = 0; kw < K; ++kw) s = fmaf(wr[K - 1][kw][v], cur[kw][FLIP ? v : v / M], s);
             out[v] = s;
         }
 #pragma unroll
@@ -106,11 +126,11 @@ __global__ __launch_bounds__(256, (S1_WAVES<V, K, PF>())) void k_nhwc_s1(
             for (int v = 0; v < V; ++v) {
                 float s = (j + 1 < K - 1) ? acc[j + 1][v] : 0.f;
 #pragma unroll
-                for (int kw = 0; kw < K; ++kw) s = fmaf(wr[K - 2 - j][kw][v], cur[kw][v], s);
+                for (int kw = 0; kw < K; ++kw) s = fmaf(wr[K - 2 - j][kw][v], cur[kw][FLIP ? v : v / M], s);
                 acc[j][v] = s;
             }
         const int oh = r - P;
-        if (oh >= oh0) store_vec<T, V>(yout + (size_t)oh * rowstride, out, nt != 0);
+        if (oh >= oh0) emit(oh, out);
     };
 
 #pragma unroll
@@ -137,7 +157,7 @@ __global__ __launch_bounds__(256, (S1_WAVES<V, K, PF>())) void k_nhwc_s1(
             for (int j = 0; j < K - 1; ++j) acc[j][v] = (j + 1 < K - 1) ? acc[j + 1][v] : 0.f;
         }
         const int oh = r - P;
-        if (oh >= oh0) store_vec<T, V>(yout + (size_t)oh * rowstride, out, nt != 0);
+        if (oh >= oh0) emit(oh, out);
     }
 }
 
@@ -345,7 +365,7 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_data_k3s2(Geom g, const T *__r
 // workspace at [part][kh][kw][o].
 // S = 1: "same" padding, K odd.  S = 2: K = 3, pad = 1.
 // ---------------------------------------------------------------------------------------------
-template <typename T, int V, int K, int S, int PF>
+template <typename T, int V, int K, int S, int PF, int M>
 __global__ __launch_bounds__(256) void k_nhwc_bwd_filter(Geom g, const T *__restrict__ x, const T *__restrict__ dy,
                                                          float *__restrict__ ws, int CT, int nctiles, int nowtiles,
                                                          int TH, int nstrips, int NI, unsigned nblocks)
@@ -359,7 +379,8 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_filter(Geom g, const T *__rest
 
     const int OWT = 256 / CT;
     const int tx = threadIdx.x % CT, ty = threadIdx.x / CT;
-    const int Q = g.C / V;
+    constexpr int VX = V / M;      // input channels behind the lane's V output channels
+    const int Q = g.O / V;
     const int cq = ctile * CT + tx, ow = owtile * OWT + ty;
     const bool active = cq < Q && ow < g.Wo;
 
@@ -385,16 +406,16 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_filter(Geom g, const T *__rest
             colok[kw] = iw >= 0 && iw < g.W;
             coloff[kw] = (colok[kw] ? iw : ow * S) * g.C;
         }
-        const int xrow = g.W * g.C, dyrow = g.Wo * g.C;
+        const int xrow = g.W * g.C, dyrow = g.Wo * g.O;
         const int oh0 = strip * TH, oh1 = min(g.Ho, oh0 + TH);
         const int n0 = ngroup * NI, n1 = min(g.N, n0 + NI);
         for (int n = n0; n < n1; ++n) {
-            const T *xin = x + (size_t)n * g.H * xrow + cq * V;
-            const T *dyin = dy + ((size_t)n * g.Ho * g.Wo + ow) * g.C + cq * V;
-            auto load_x = [&](int r, float (&dst)[K][V]) {
+            const T *xin = x + (size_t)n * g.H * xrow + cq * VX;
+            const T *dyin = dy + ((size_t)n * g.Ho * g.Wo + ow) * g.O + cq * V;
+            auto load_x = [&](int r, float (&dst)[K][VX]) {
                 const T *rp = xin + (size_t)min(max(r, 0), g.H - 1) * xrow;
 #pragma unroll
-                for (int kw = 0; kw < K; ++kw) Vec<T, V>::load(rp + coloff[kw], dst[kw]);
+                for (int kw = 0; kw < K; ++kw) Vec<T, VX>::load(rp + coloff[kw], dst[kw]);
             };
             auto load_dy = [&](int oh, float (&dst)[V]) {
                 Vec<T, V>::load(dyin + (size_t)min(max(oh, oh0), oh1 - 1) * dyrow, dst);
@@ -415,13 +436,13 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_filter(Geom g, const T *__rest
 #pragma unroll
                     for (int v = 0; v < V; ++v) dyw[0][v] = d[v];
                 };
-                auto accumulate = [&](const float (&xr)[K][V]) {
+                auto accumulate = [&](const float (&xr)[K][VX]) {
 #pragma unroll
                     for (int kh = 0; kh < K; ++kh)
 #pragma unroll
                         for (int kw = 0; kw < K; ++kw)
 #pragma unroll
-                            for (int v = 0; v < V; ++v) acc[kh][kw][v] = fmaf(dyw[kh][v], xr[kw][v], acc[kh][kw][v]);
+                            for (int v = 0; v < V; ++v) acc[kh][kw][v] = fmaf(dyw[kh][v], xr[kw][v / M], acc[kh][kw][v]);
                 };
                 const int r0 = oh0 - P, r1 = oh1 + P;
                 const int ra = max(r0, 0), rb = min(r1, g.H);       // x rows inside the image
@@ -436,7 +457,7 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_filter(Geom g, const T *__rest
                     }
                     push_dy(d);
                 }
-                float xr[R][K][V], dr[R][V];
+                float xr[R][K][VX], dr[R][V];
 #pragma unroll
                 for (int j = 0; j < PF; ++j) { load_x(ra + j, xr[j]); load_dy(ra + j + P, dr[j]); }
                 int base = ra;
@@ -464,7 +485,7 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_filter(Geom g, const T *__rest
 #pragma unroll
                     for (int v = 0; v < V; ++v) zero[v] = 0.f;
                     for (int r = max(rm, ra); r < rb; ++r) {
-                        float xt[K][V];
+                        float xt[K][VX];
                         load_x(r, xt);
                         push_dy(zero);
                         accumulate(xt);
@@ -475,13 +496,13 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_filter(Geom g, const T *__rest
                 // Rows [oh0, ohb) have all of 2oh, 2oh+1 inside the image; an odd H leaves one last
                 // row without its bottom tap row.  The next output row's loads are issued ahead.
                 const int ohb = min(oh1, g.H / 2);
-                float xa[K][V], xb[2][K][V], xc[2][K][V], d[2][V];
+                float xa[K][VX], xb[2][K][VX], xc[2][K][VX], d[2][V];
                 if (2 * oh0 - 1 >= 0) load_x(2 * oh0 - 1, xa);
                 else {
 #pragma unroll
                     for (int kw = 0; kw < K; ++kw)
 #pragma unroll
-                        for (int v = 0; v < V; ++v) xa[kw][v] = 0.f;
+                        for (int v = 0; v < VX; ++v) xa[kw][v] = 0.f;
                 }
                 load_x(2 * oh0, xb[0]); load_x(2 * oh0 + 1, xc[0]); load_dy(oh0, d[0]);
                 auto step = [&](int j) {
@@ -489,11 +510,14 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_filter(Geom g, const T *__rest
                     for (int kw = 0; kw < K; ++kw)
 #pragma unroll
                         for (int v = 0; v < V; ++v) {
-                            acc[0][kw][v] = fmaf(d[j][v], xa[kw][v], acc[0][kw][v]);
-                            acc[1][kw][v] = fmaf(d[j][v], xb[j][kw][v], acc[1][kw][v]);
-                            acc[2][kw][v] = fmaf(d[j][v], xc[j][kw][v], acc[2][kw][v]);
-                            xa[kw][v] = xc[j][kw][v];
+                            acc[0][kw][v] = fmaf(d[j][v], xa[kw][v / M], acc[0][kw][v]);
+                            acc[1][kw][v] = fmaf(d[j][v], xb[j][kw][v / M], acc[1][kw][v]);
+                            acc[2][kw][v] = fmaf(d[j][v], xc[j][kw][v / M], acc[2][kw][v]);
                         }
+#pragma unroll
+                    for (int kw = 0; kw < K; ++kw)
+#pragma unroll
+                        for (int v = 0; v < VX; ++v) xa[kw][v] = xc[j][kw][v];
                 };
                 int oh = oh0;
 #pragma unroll 1
@@ -510,7 +534,7 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_filter(Geom g, const T *__rest
 #pragma unroll
                     for (int kw = 0; kw < K; ++kw)
 #pragma unroll
-                        for (int v = 0; v < V; ++v) xb[0][kw][v] = xb[1][kw][v];
+                        for (int v = 0; v < VX; ++v) xb[0][kw][v] = xb[1][kw][v];
 #pragma unroll
                     for (int v = 0; v < V; ++v) d[0][v] = d[1][v];
                 }
@@ -520,8 +544,8 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_filter(Geom g, const T *__rest
                     for (int kw = 0; kw < K; ++kw)
 #pragma unroll
                         for (int v = 0; v < V; ++v) {
-                            acc[0][kw][v] = fmaf(d[0][v], xa[kw][v], acc[0][kw][v]);
-                            acc[1][kw][v] = fmaf(d[0][v], xb[0][kw][v], acc[1][kw][v]);
+                            acc[0][kw][v] = fmaf(d[0][v], xa[kw][v / M], acc[0][kw][v]);
+                            acc[1][kw][v] = fmaf(d[0][v], xb[0][kw][v / M], acc[1][kw][v]);
                         }
                 }
             }
@@ -540,7 +564,7 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_filter(Geom g, const T *__rest
     // ---- fixed-order block reduction, one tap at a time ----
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int part = (ngroup * nstrips + strip) * nowtiles + owtile;
-    float *wsp = ws + (size_t)part * (K * K * g.C);
+    float *wsp = ws + (size_t)part * (K * K * g.O);
 #pragma unroll
     for (int kh = 0; kh < K; ++kh)
 #pragma unroll
@@ -557,7 +581,7 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_filter(Geom g, const T *__rest
                 for (int v = 0; v < V; ++v)
                     o[v] = (red[0][v][lane] + red[1][v][lane]) + (red[2][v][lane] + red[3][v][lane]);
 #pragma unroll
-                for (int v = 0; v < V; ++v) wsp[(kh * K + kw) * g.C + cq * V + v] = o[v];
+                for (int v = 0; v < V; ++v) wsp[(kh * K + kw) * g.O + cq * V + v] = o[v];
             }
             __syncthreads();
         }
@@ -575,19 +599,19 @@ static inline int flat_block(int WQ)
     return waste128 < waste256 ? 128 : 256;
 }
 
-template <typename T, int V, int K, int PF>
+template <typename T, int V, int K, int PF, int M>
 static hipError_t launch_s1(const Geom &g, const void *x, const void *w, void *y, bool flip, int TH, hipStream_t st)
 {
-    const int lanes = g.W * (g.C / V);
+    const int lanes = g.W * (g.O / V);
     const int bs = flat_block(lanes);
     const int nchunks = ceil_div(lanes, bs), nstrips = ceil_div(g.H, TH);
     const unsigned nblocks = (unsigned)g.N * nchunks * nstrips;
-    const int nt = stream_stores((long long)g.N * g.H * g.W * g.C * sizeof(T));
+    const int nt = stream_stores((long long)g.N * g.H * g.W * (flip ? g.C : g.O) * sizeof(T));
     if (flip)
-        hipLaunchKernelGGL((k_nhwc_s1<T, V, K, PF, true>), dim3(nblocks), dim3(bs), 0, st, g, (const T *)x,
+        hipLaunchKernelGGL((k_nhwc_s1<T, V, K, PF, true, M>), dim3(nblocks), dim3(bs), 0, st, g, (const T *)x,
                            (const T *)w, (T *)y, TH, nstrips, nchunks, nblocks, nt);
     else
-        hipLaunchKernelGGL((k_nhwc_s1<T, V, K, PF, false>), dim3(nblocks), dim3(bs), 0, st, g, (const T *)x,
+        hipLaunchKernelGGL((k_nhwc_s1<T, V, K, PF, false, M>), dim3(nblocks), dim3(bs), 0, st, g, (const T *)x,
                            (const T *)w, (T *)y, TH, nstrips, nchunks, nblocks, nt);
     return hipGetLastError();
 }
@@ -595,7 +619,14 @@ static hipError_t launch_s1(const Geom &g, const void *x, const void *w, void *y
 hipError_t nhwc_s1(const Geom &g, int dtype, int V, const void *x, const void *w, void *y, bool flip, int TH, int PF,
                    hipStream_t st)
 {
-#define TRY(T, VV, KK, PPF) if (g.K == KK && V == VV && PF == PPF) return launch_s1<T, VV, KK, PPF>(g, x, w, y, flip, TH, st)
+#define TRY(T, VV, KK, PPF) if (g.m == 1 && g.K == KK && V == VV && PF == PPF) return launch_s1<T, VV, KK, PPF, 1>(g, x, w, y, flip, TH, st)
+    // channel multiplier 2: 3x3, two rows ahead
+    if (g.m == 2 && g.K == 3) {
+        if (dtype == DT_F32 && V == 4) return launch_s1<float, 4, 3, 2, 2>(g, x, w, y, flip, TH, st);
+        if (dtype == DT_BF16 && V == 8) return launch_s1<bf16_t, 8, 3, 2, 2>(g, x, w, y, flip, TH, st);
+        if (dtype == DT_BF16 && V == 4) return launch_s1<bf16_t, 4, 3, 2, 2>(g, x, w, y, flip, TH, st);
+        return hipErrorInvalidValue;
+    }
     if (dtype == DT_F32) {
         TRY(float, 4, 3, 1); TRY(float, 4, 3, 2); TRY(float, 4, 3, 3); TRY(float, 4, 3, 4);
         TRY(float, 4, 5, 1); TRY(float, 4, 5, 2);
@@ -637,7 +668,7 @@ hipError_t nhwc_k3s2(const Geom &g, int dtype, int V, const void *in, const void
 void nhwc_bwd_filter_tiling(const Geom &g, int V, int TH, int NI, int *CT, int *nctiles, int *nowtiles, int *nstrips,
                             int *ngroups)
 {
-    const int Q = g.C / V;
+    const int Q = g.O / V;
     int ct = 1;
     while (ct < Q && ct < 64) ct <<= 1;
     *CT = ct;
@@ -653,8 +684,19 @@ hipError_t nhwc_bwd_filter(const Geom &g, int dtype, int V, const void *x, const
     int CT, nctiles, nowtiles, nstrips, ngroups;
     nhwc_bwd_filter_tiling(g, V, TH, NI, &CT, &nctiles, &nowtiles, &nstrips, &ngroups);
     const unsigned nblocks = (unsigned)nctiles * nowtiles * nstrips * ngroups;
-#define GO(T, VV, KK, SS) hipLaunchKernelGGL((k_nhwc_bwd_filter<T, VV, KK, SS, 2>), dim3(nblocks), dim3(256), 0, st, g, \
+#define GO(T, VV, KK, SS) hipLaunchKernelGGL((k_nhwc_bwd_filter<T, VV, KK, SS, 2, 1>), dim3(nblocks), dim3(256), 0, st, g, \
                                              (const T *)x, (const T *)dy, ws, CT, nctiles, nowtiles, TH, nstrips, NI, nblocks)
+#define GOM2(T, VV) hipLaunchKernelGGL((k_nhwc_bwd_filter<T, VV, 3, 1, 2, 2>), dim3(nblocks), dim3(256), 0, st, g, \
+                                       (const T *)x, (const T *)dy, ws, CT, nctiles, nowtiles, TH, nstrips, NI, nblocks)
+    if (g.m == 2) {
+        if (!(g.K == 3 && g.s == 1)) return hipErrorInvalidValue;
+        if (dtype == DT_F32 && V == 4) GOM2(float, 4);
+        else if (dtype == DT_BF16 && V == 8) GOM2(bf16_t, 8);
+        else if (dtype == DT_BF16 && V == 4) GOM2(bf16_t, 4);
+        else return hipErrorInvalidValue;
+        return hipGetLastError();
+    }
+#undef GOM2
     if (dtype == DT_F32) {
         if (g.K == 3 && g.s == 1) GO(float, 4, 3, 1);
         else if (g.K == 3 && g.s == 2) GO(float, 4, 3, 2);

@@ -21,10 +21,12 @@ static bool k3s2p1(const Geom &g) { return g.s == 2 && g.K == 3 && g.p == 1; }
 // channels per lane for the NHWC kernels, 0 if the fast path does not apply
 static int nhwc_vec(const Geom &g, int dtype)
 {
-    if (g.m != 1) return 0;
-    if (dtype == DT_F32) return g.C % 4 == 0 ? 4 : 0;
-    if (g.K == 5) return g.C % 4 == 0 ? 4 : 0;   // 25 taps x 8 channels would not fit in registers
-    return g.C % 8 == 0 ? 8 : (g.C % 4 == 0 ? 4 : 0);
+    // multiplier 2 has a fast path for 3x3 stride 1 only; the vector counts OUTPUT channels
+    if (g.m == 2) { if (!(g.K == 3 && g.s == 1 && g.p == 1)) return 0; }
+    else if (g.m != 1) return 0;
+    if (dtype == DT_F32) return g.O % 4 == 0 ? 4 : 0;
+    if (g.K == 5) return g.O % 4 == 0 ? 4 : 0;   // 25 taps x 8 channels would not fit in registers
+    return g.O % 8 == 0 ? 8 : (g.O % 4 == 0 ? 4 : 0);
 }
 
 // Rows loaded ahead in the NHWC stride-1 kernel (5x5 keeps 25 taps x V in registers: one row less).
@@ -85,8 +87,8 @@ Plan plan_fwd(const Geom &g, int layout, int dtype)
     if (layout == LAYOUT_NHWC) {
         const int V = nhwc_vec(g, dtype);
         if (V && same_pad_s1(g)) {
-            pl.variant = V_NHWC_S1; pl.a = V; pl.b = pick_th(g.H, (long long)g.N * g.W * (g.C / V));
-            pl.name = g.K == 3 ? "nhwc_rowwalk_k3s1" : "nhwc_rowwalk_k5s1";
+            pl.variant = V_NHWC_S1; pl.a = V; pl.b = pick_th(g.H, (long long)g.N * g.W * (g.O / V));
+            pl.name = g.m == 2 ? "nhwc_rowwalk_k3s1_m2" : (g.K == 3 ? "nhwc_rowwalk_k3s1" : "nhwc_rowwalk_k5s1");
         } else if (V && k3s2p1(g)) {
             pl.variant = V_NHWC_K3S2; pl.a = V; pl.b = pick_th(g.Ho, (long long)g.N * g.Wo * (g.C / V));
             pl.name = "nhwc_rowwalk_fwd_k3s2";
@@ -123,8 +125,8 @@ Plan plan_bwd_data(const Geom &g, int layout, int dtype)
     if (layout == LAYOUT_NHWC) {
         const int V = nhwc_vec(g, dtype);
         if (V && same_pad_s1(g)) {
-            pl.variant = V_NHWC_S1; pl.a = V; pl.b = pick_th(g.H, (long long)g.N * g.W * (g.C / V));
-            pl.name = g.K == 3 ? "nhwc_rowwalk_k3s1_flip" : "nhwc_rowwalk_k5s1_flip";
+            pl.variant = V_NHWC_S1; pl.a = V; pl.b = pick_th(g.H, (long long)g.N * g.W * (g.O / V));
+            pl.name = g.m == 2 ? "nhwc_rowwalk_k3s1_flip_m2" : (g.K == 3 ? "nhwc_rowwalk_k3s1_flip" : "nhwc_rowwalk_k5s1_flip");
         } else if (V && k3s2p1(g)) {
             pl.variant = V_NHWC_K3S2; pl.a = V; pl.b = pick_th(g.Ho, (long long)g.N * g.Wo * (g.C / V));
             pl.name = "nhwc_rowwalk_bwd_data_k3s2";
@@ -208,7 +210,8 @@ Plan plan_bwd_filter(const Geom &g, int layout, int dtype)
             }
             pl.variant = V_NHWC_BWD_FILTER; pl.a = V; pl.b = TH; pl.c = NI;
             pl.parts = nowt * nst * ngr;
-            pl.name = g.s == 2 ? "nhwc_bwd_filter_k3s2" : (g.K == 3 ? "nhwc_bwd_filter_k3s1" : "nhwc_bwd_filter_k5s1");
+            pl.name = g.m == 2 ? "nhwc_bwd_filter_k3s1_m2"
+                               : (g.s == 2 ? "nhwc_bwd_filter_k3s2" : (g.K == 3 ? "nhwc_bwd_filter_k3s1" : "nhwc_bwd_filter_k5s1"));
         }
     }
     return pl;

@@ -110,3 +110,22 @@ def test_workspace_is_bounded_for_every_benchmark_layer():
                 assert 0 < need <= (64 << 20), (layer.name, need)
                 for which in range(3):
                     assert dw.variant_name(d, which) not in ("", "invalid")
+
+
+def test_benchmark_layers_get_tuned_variants():
+    """No layer of the five benchmark configurations may fall back to the generic kernels."""
+    from paper_1803_09926_amd import workloads as wl
+    for ci in range(5):
+        cfg = wl.config(ci)
+        for layer, _ in cfg["layers"]:
+            for layout in cfg["layouts"]:
+                d = dw.desc(cfg["N"], layer.C, layer.H, layer.W, layer.K, layer.stride, layer.pad, layer.mult,
+                            layout, cfg["dtype"])
+                for which in range(3):
+                    assert dw.variant_name(d, which) != "generic", (ci, layer.name, layout, which)
+
+
+def test_generic_fallback_is_selected_for_untuned_shapes():
+    assert dw.variant_name(dw.desc(2, 6, 9, 9, 3, 1, 1, 1, dw.NHWC), 0) == "generic"       # C not a multiple of 4
+    assert dw.variant_name(dw.desc(2, 8, 9, 9, 7, 1, 3, 1, dw.NCHW), 0) == "generic"       # 7x7
+    assert dw.variant_name(dw.desc(2, 8, 9, 9, 3, 3, 1, 1, dw.NHWC), 2) == "generic"       # stride 3
