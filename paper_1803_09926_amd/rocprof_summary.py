@@ -16,24 +16,40 @@ import sys
 
 # bench.py's "<pass>:<variant>" keys -> the kernel(s) that implement them (regex on the demangled name)
 VARIANT_KERNELS = {
-    "fwd:nhwc_rowwalk_k3s1": [r"k_nhwc_s1<.*, 3, \d+, \d+, false>"],
-    "bwd_data:nhwc_rowwalk_k3s1_flip": [r"k_nhwc_s1<.*, 3, \d+, \d+, true>"],
+    # k_nhwc_s1<T, V, K, PF, FLIP, M>
+    "fwd:nhwc_rowwalk_k3s1": [r"k_nhwc_s1<\w+, \d+, 3, \d+, false, 1>"],
+    "bwd_data:nhwc_rowwalk_k3s1_flip": [r"k_nhwc_s1<\w+, \d+, 3, \d+, true, 1>"],
+    "fwd:nhwc_rowwalk_k5s1": [r"k_nhwc_s1<\w+, \d+, 5, \d+, false, 1>"],
+    "bwd_data:nhwc_rowwalk_k5s1_flip": [r"k_nhwc_s1<\w+, \d+, 5, \d+, true, 1>"],
+    "fwd:nhwc_rowwalk_k3s1_m2": [r"k_nhwc_s1<\w+, \d+, 3, \d+, false, 2>"],
+    "bwd_data:nhwc_rowwalk_k3s1_flip_m2": [r"k_nhwc_s1<\w+, \d+, 3, \d+, true, 2>"],
     "fwd:nhwc_rowwalk_fwd_k3s2": [r"k_nhwc_fwd_k3s2<"],
     "bwd_data:nhwc_rowwalk_bwd_data_k3s2": [r"k_nhwc_bwd_data_k3s2<"],
-    "bwd_filter:nhwc_bwd_filter_k3s1": [r"k_nhwc_bwd_filter<.*, 3, 1, \d+>"],
-    "bwd_filter:nhwc_bwd_filter_k3s2": [r"k_nhwc_bwd_filter<.*, 3, 2, \d+>"],
-    "fwd:nchw_rowwalk_k3s1": [r"k_nchwd_s1<.*, 3, \d+, false>"],
-    "bwd_data:nchw_rowwalk_k3s1_flip": [r"k_nchwd_s1<.*, 3, \d+, true>"],
+    # k_nhwc_bwd_filter<T, V, K, S, PF, M>
+    "bwd_filter:nhwc_bwd_filter_k3s1": [r"k_nhwc_bwd_filter<\w+, \d+, 3, 1, \d+, 1>"],
+    "bwd_filter:nhwc_bwd_filter_k3s2": [r"k_nhwc_bwd_filter<\w+, \d+, 3, 2, \d+, 1>"],
+    "bwd_filter:nhwc_bwd_filter_k5s1": [r"k_nhwc_bwd_filter<\w+, \d+, 5, 1, \d+, 1>"],
+    "bwd_filter:nhwc_bwd_filter_k3s1_m2": [r"k_nhwc_bwd_filter<\w+, \d+, 3, 1, \d+, 2>"],
+    # k_nchwd_s1<T, V, K, PF, FLIP>
+    "fwd:nchw_rowwalk_k3s1": [r"k_nchwd_s1<\w+, \d+, 3, \d+, false>"],
+    "bwd_data:nchw_rowwalk_k3s1_flip": [r"k_nchwd_s1<\w+, \d+, 3, \d+, true>"],
+    "fwd:nchw_rowwalk_k5s1": [r"k_nchwd_s1<\w+, \d+, 5, \d+, false>"],
+    "bwd_data:nchw_rowwalk_k5s1_flip": [r"k_nchwd_s1<\w+, \d+, 5, \d+, true>"],
     "fwd:nchw_rowwalk_fwd_k3s2": [r"k_nchwd_fwd_k3s2<"],
     "bwd_data:nchw_rowwalk_bwd_data_k3s2": [r"k_nchwd_bwd_data_k3s2<"],
-    "bwd_filter:nchw_rowwalk_bwd_filter_k3s1": [r"k_nchwd_bwd_filter_k3<.*, 1>"],
-    "bwd_filter:nchw_rowwalk_bwd_filter_k3s2": [r"k_nchwd_bwd_filter_k3<.*, 2>"],
-    "fwd:nchw_smallplane_k3s1": [r"k_nchws_fwd<.*, 1, \d+, false>"],
-    "bwd_data:nchw_smallplane_k3s1_flip": [r"k_nchws_fwd<.*, 1, \d+, true>"],
-    "fwd:nchw_smallplane_fwd_k3s2": [r"k_nchws_fwd<.*, 2, \d+, false>"],
+    "bwd_filter:nchw_rowwalk_bwd_filter_k3s1": [r"k_nchwd_bwd_filter_k3<\w+, \d+, 1>"],
+    "bwd_filter:nchw_rowwalk_bwd_filter_k3s2": [r"k_nchwd_bwd_filter_k3<\w+, \d+, 2>"],
+    "bwd_filter:nchw_rowwalk_bwd_filter_k5s1": [r"k_nchwd_bwd_filter_s1<\w+, \d+, 5>"],
+    # k_nchws_fwd<T, K, S, W, FLIP>, k_nchws_bwd_filter<T, K, S, W>
+    "fwd:nchw_smallplane_k3s1": [r"k_nchws_fwd<\w+, 3, 1, \d+, false>"],
+    "bwd_data:nchw_smallplane_k3s1_flip": [r"k_nchws_fwd<\w+, 3, 1, \d+, true>"],
+    "fwd:nchw_smallplane_fwd_k3s2": [r"k_nchws_fwd<\w+, 3, 2, \d+, false>"],
     "bwd_data:nchw_smallplane_bwd_data_k3s2": [r"k_nchws_bwd_data_s2<"],
-    "bwd_filter:nchw_smallplane_bwd_filter_k3s1": [r"k_nchws_bwd_filter<.*, 1, \d+>"],
-    "bwd_filter:nchw_smallplane_bwd_filter_k3s2": [r"k_nchws_bwd_filter<.*, 2, \d+>"],
+    "bwd_filter:nchw_smallplane_bwd_filter_k3s1": [r"k_nchws_bwd_filter<\w+, 3, 1, \d+>"],
+    "bwd_filter:nchw_smallplane_bwd_filter_k3s2": [r"k_nchws_bwd_filter<\w+, 3, 2, \d+>"],
+    "fwd:nchw_smallplane_k5s1": [r"k_nchws_fwd<\w+, 5, 1, \d+, false>"],
+    "bwd_data:nchw_smallplane_k5s1_flip": [r"k_nchws_fwd<\w+, 5, 1, \d+, true>"],
+    "bwd_filter:nchw_smallplane_bwd_filter_k5s1": [r"k_nchws_bwd_filter<\w+, 5, 1, \d+>"],
 }
 
 
