@@ -3,7 +3,7 @@
 layers), batch 128, fp32, once in NCHW and once in NHWC, on one MI355X.
 
 A step is one pass of the whole hot path over the whole workload: for each layout, for each of
-the 13 layers, dwconv_fwd, dwconv_bwd_data, dwconv_bwd_filter (stage 1 + stage 2) through the
+the 13 layers, dwconv_fwd, dwconv_bwd_filter (stage 1 + stage 2), dwconv_bwd_data through the
 C ABI.  Every layer has its own device buffers (about 10 GB in all, far beyond the caches), so
 each launch reads its operands from HBM.  Inputs are synthetic (seeded normal draws) and already
 resident in HBM when the timed region starts.
@@ -73,9 +73,11 @@ def build_ops(dw, wl, cfg, torch):
                 rc = lib.dwconv_bwd_filter(dref, px, pdy, pdw, pws, nws, stream)
                 if rc: raise dw.DwconvError(rc, "dwconv_bwd_filter")
 
+            # order within a layer: forward, filter gradient, input gradient.  The two backward passes
+            # both read dy; run back to back, the second finds much of it in the 256 MB Infinity Cache.
             ops.append(dict(common, which=0, variant=dw.variant_name(d, 0), run=run_fwd))
-            ops.append(dict(common, which=1, variant=dw.variant_name(d, 1), run=run_bwd_data))
             ops.append(dict(common, which=2, variant=dw.variant_name(d, 2), run=run_bwd_filter))
+            ops.append(dict(common, which=1, variant=dw.variant_name(d, 1), run=run_bwd_data))
     return ops
 
 

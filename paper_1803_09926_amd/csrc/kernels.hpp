@@ -64,7 +64,7 @@ hipError_t nchwd_s1(const Geom &g, int dtype, int V, const void *x, const void *
                     hipStream_t st);
 hipError_t nchwd_k3s2(const Geom &g, int dtype, int V, const void *in, const void *w, void *out, bool bwd, int TH,
                       hipStream_t st);
-void nchwd_bwd_filter_tiling(const Geom &g, int V, int TH, int *sg_log2, int *nstrips, int *rounds, int *parts);
+void nchwd_bwd_filter_tiling(const Geom &g, int V, int TH, int *items_per_round, int *nstrips, int *rounds, int *parts);
 hipError_t nchwd_bwd_filter(const Geom &g, int dtype, int V, const void *x, const void *dy, float *ws, int TH,
                             hipStream_t st);
 

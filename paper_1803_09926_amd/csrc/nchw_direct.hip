@@ -288,23 +288,23 @@ __global__ __launch_bounds__(256) void k_nchwd_bwd_data_k3s2(Geom g, const T *__
 
 // ---------------------------------------------------------------------------------------------
 // Backward-filter stage 1, 3x3, stride S in {1 ("same" pad), 2 (pad 1, W even)}.
-// grid = (parts, O).  A block works on ONE output channel: its 256 lanes are 256/SG sub-groups of
-// SG lanes (SG = power of two >= vectors per row); a sub-group takes one (image, strip) work
-// item per round and the block walks `rounds` rounds, so partial sums stay in registers.  At the
+// grid = (parts, O).  A block works on ONE output channel: its 256 lanes are laid flat over
+// (item, vector column) with nsg = 256 / (vectors per row) (image, strip) work items per round,
+// and the block walks `rounds` rounds, so partial sums stay in registers.  At the
 // end all 256 lanes hold sums for the same channel: wavefront butterfly, LDS across the four
 // wavefronts, one partial per block at ws[part][o][kh][kw].  Fixed order throughout.
 // ---------------------------------------------------------------------------------------------
 template <typename T, int V, int S>
 __global__ __launch_bounds__(256) void k_nchwd_bwd_filter_k3(Geom g, const T *__restrict__ x, const T *__restrict__ dy,
-                                                             float *__restrict__ ws, int TH, int nstrips, int sg_log2,
+                                                             float *__restrict__ ws, int TH, int nstrips, int nsg,
                                                              int rounds)
 {
     __shared__ float red[4][9];
     constexpr int NW = (S == 1) ? V + 2 : 2 * V + 1;
     const int o = blockIdx.y, part = blockIdx.x;
-    const int SG = 1 << sg_log2, nsg = 256 >> sg_log2;
-    const int sg = threadIdx.x >> sg_log2, c4 = threadIdx.x & (SG - 1);
     const int ncols = g.Wo / V;                         // vectors per dy row
+    // lanes are laid flat over (item, vector column): nsg = 256 / ncols items per round, no padding
+    const int sg = threadIdx.x / ncols, c4 = threadIdx.x - sg * ncols;
     const int nitems = g.N * nstrips;
     const int c_in = o / g.m;
     const bool has_left = c4 > 0, has_right = c4 < ncols - 1;
@@ -315,7 +315,7 @@ __global__ __launch_bounds__(256) void k_nchwd_bwd_filter_k3(Geom g, const T *__
 #pragma unroll
         for (int kw = 0; kw < 3; ++kw) acc[kh][kw] = 0.f;
 
-    if (c4 < ncols) {
+    if (sg < nsg) {
         for (int rd = 0; rd < rounds; ++rd) {
             const int item = (part * rounds + rd) * nsg + sg;
             if (item >= nitems) break;
@@ -357,13 +357,15 @@ __global__ __launch_bounds__(256) void k_nchwd_bwd_filter_k3(Geom g, const T *__
                 Vec<T, V>::load(dyin + (size_t)min(oh, g.Ho - 1) * g.Wo, dst);
             };
             // x rows oh*S-1, oh*S, oh*S+1 meet dy row oh at tap rows 0, 1, 2.
-            float xa[NW], xb[NW], xc[2][NW], d[2][V], xs[2][NW];
+            float xa[NW], xb[NW], xc[3][NW], d[3][V], xs[2][NW];
             load_x(oh0 * S - 1, xa);
             mask_x(oh0 * S - 1, xa);
             if constexpr (S == 1) {
                 load_x(oh0, xb);
                 mask_x(oh0, xb);
+                // two rows ahead: while row oh is accumulated, rows oh+2 and oh+3 are in flight
                 load_x(oh0 + 1, xc[0]); load_dy(oh0, d[0]);
+                load_x(oh0 + 2, xc[1]); load_dy(oh0 + 1, d[1]);
                 auto step = [&](int oh, int j) {
                     mask_x(oh + 1, xc[j]);
                     const bool dok = oh < oh1;
@@ -382,13 +384,16 @@ __global__ __launch_bounds__(256) void k_nchwd_bwd_filter_k3(Geom g, const T *__
                 };
                 int i = 0;
 #pragma unroll 1
-                for (; i + 2 <= TH; i += 2) {
-                    load_x(oh0 + i + 2, xc[1]); load_dy(oh0 + i + 1, d[1]);
-                    step(oh0 + i, 0);
-                    load_x(oh0 + i + 3, xc[0]); load_dy(oh0 + i + 2, d[0]);
-                    step(oh0 + i + 1, 1);
+                for (; i + 3 <= TH; i += 3) {
+#pragma unroll
+                    for (int j = 0; j < 3; ++j) {
+                        load_x(oh0 + i + j + 3, xc[(j + 2) % 3]); load_dy(oh0 + i + j + 2, d[(j + 2) % 3]);
+                        step(oh0 + i + j, j);
+                    }
                 }
-                if (i < TH) step(oh0 + i, 0);
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    if (i + j < TH) step(oh0 + i + j, j);
             } else {
                 load_x(2 * oh0, xs[0]); load_x(2 * oh0 + 1, xc[0]); load_dy(oh0, d[0]);
                 auto step = [&](int oh, int j) {
@@ -445,16 +450,15 @@ __global__ __launch_bounds__(256) void k_nchwd_bwd_filter_k3(Geom g, const T *__
 // ---------------------------------------------------------------------------------------------
 template <typename T, int V, int K>
 __global__ __launch_bounds__(256) void k_nchwd_bwd_filter_s1(Geom g, const T *__restrict__ x, const T *__restrict__ dy,
-                                                             float *__restrict__ ws, int TH, int nstrips, int sg_log2,
+                                                             float *__restrict__ ws, int TH, int nstrips, int nsg,
                                                              int rounds)
 {
     __shared__ float red[4][K * K];
     constexpr int P = (K - 1) / 2;
     constexpr int NW = V + 2 * P;
     const int o = blockIdx.y, part = blockIdx.x;
-    const int SG = 1 << sg_log2, nsg = 256 >> sg_log2;
-    const int sg = threadIdx.x >> sg_log2, c4 = threadIdx.x & (SG - 1);
     const int ncols = g.W / V;
+    const int sg = threadIdx.x / ncols, c4 = threadIdx.x - sg * ncols;
     const int nitems = g.N * nstrips;
     const int c_in = o / g.m;
     const bool has_left = c4 > 0, has_right = c4 < ncols - 1;
@@ -465,7 +469,7 @@ __global__ __launch_bounds__(256) void k_nchwd_bwd_filter_s1(Geom g, const T *__
 #pragma unroll
         for (int kw = 0; kw < K; ++kw) acc[kh][kw] = 0.f;
 
-    if (c4 < ncols) {
+    if (sg < nsg) {
         int loff[P], roff[P];
 #pragma unroll
         for (int i = 0; i < P; ++i) { loff[i] = has_left ? -(P - i) : 0; roff[i] = has_right ? V + i : V - 1; }
@@ -618,16 +622,15 @@ hipError_t nchwd_k3s2(const Geom &g, int dtype, int V, const void *in, const voi
 }
 
 // Filter gradient tiling: sub-group width, rounds per block and number of partials.
-void nchwd_bwd_filter_tiling(const Geom &g, int V, int TH, int *sg_log2, int *nstrips, int *rounds, int *parts)
+void nchwd_bwd_filter_tiling(const Geom &g, int V, int TH, int *nsg_out, int *nstrips, int *rounds, int *parts)
 {
     const int ncols = g.Wo / V;
-    int lg = 0;
-    while ((1 << lg) < ncols) ++lg;
-    *sg_log2 = lg;
+    const int nsg = ncols <= 256 ? 256 / ncols : 0;      // (image, strip) items a block works on per round
+    *nsg_out = nsg;
     *nstrips = ceil_div_h(g.Ho, TH);
-    const int nsg = 256 >> lg;
+    if (nsg == 0) { *rounds = 1; *parts = 0; return; }
     const int nitems = g.N * *nstrips;
-    // enough blocks for ~8 per CU over the O channels, but at least 2 rounds per block
+    // enough blocks for ~8 per CU over the O channels
     int want_parts = (2048 + g.O - 1) / g.O;
     if (want_parts < 1) want_parts = 1;
     int r = nitems / (nsg * want_parts);
@@ -639,9 +642,9 @@ void nchwd_bwd_filter_tiling(const Geom &g, int V, int TH, int *sg_log2, int *ns
 hipError_t nchwd_bwd_filter(const Geom &g, int dtype, int V, const void *x, const void *dy, float *ws, int TH,
                             hipStream_t st)
 {
-    int lg, nstrips, rounds, parts;
+    int lg, nstrips, rounds, parts;     // lg = items per round
     nchwd_bwd_filter_tiling(g, V, TH, &lg, &nstrips, &rounds, &parts);
-    if (lg > 8) return hipErrorInvalidValue;
+    if (lg < 1 || parts < 1) return hipErrorInvalidValue;
     dim3 grid(parts, g.O);
 #define GO(T, VV, SS) hipLaunchKernelGGL((k_nchwd_bwd_filter_k3<T, VV, SS>), grid, dim3(256), 0, st, g, (const T *)x, \
                                          (const T *)dy, ws, TH, nstrips, lg, rounds)
