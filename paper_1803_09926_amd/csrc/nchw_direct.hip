@@ -6,6 +6,7 @@
 // issue 64 lane-operations per clock, so everything besides the K*K multiply-adds per element
 // (addressing, edge handling) is amortised over the V outputs of a lane.
 #include "kernels.hpp"
+#include <stdlib.h>
 
 namespace dwc {
 
@@ -157,12 +158,21 @@ __global__ __launch_bounds__(256) void k_nchwd_fwd_k3s2(Geom g, const T *__restr
     // a shorter last strip keep going with their stores masked.
     auto load_row = [&](int r, float (&dst)[NW]) {
         const T *rp = xin + (size_t)min(max(r, 0), g.H - 1) * g.W;
-        float a[V], b[V];
-        Vec<T, V>::load(rp, a);
-        Vec<T, V>::load(rp + V, b);
-        dst[0] = ldf(rp + loff);
+        if constexpr (2 * V * sizeof(T) <= 16) {
+            // the lane's 2V input columns are one 16-byte vector: consecutive lanes read consecutive vectors
+            float ab[2 * V];
+            Vec<T, 2 * V>::load(rp, ab);
+            dst[0] = ldf(rp + loff);
 #pragma unroll
-        for (int v = 0; v < V; ++v) { dst[1 + v] = a[v]; dst[1 + V + v] = b[v]; }
+            for (int v = 0; v < 2 * V; ++v) dst[1 + v] = ab[v];
+        } else {
+            float a[V], b[V];
+            Vec<T, V>::load(rp, a);
+            Vec<T, V>::load(rp + V, b);
+            dst[0] = ldf(rp + loff);
+#pragma unroll
+            for (int v = 0; v < V; ++v) { dst[1 + v] = a[v]; dst[1 + V + v] = b[v]; }
+        }
     };
 
     float carry[V], re[2][NW], ro[2][NW];
@@ -567,6 +577,10 @@ int nchwd_vec(const Geom &g, int dtype, int pass)
         if (dtype == DT_F32) return wv % 2 == 0 ? 2 : 0;
         return wv % 4 == 0 ? 4 : 0;
     }
+    if (s2 && pass == 0 && !getenv("DWCONV_TUNE_VF4")) {   // forward: the lane's 2V input columns are one 16-byte vector
+        if (dtype == DT_F32) return wv % 2 == 0 ? 2 : 0;
+        return wv % 4 == 0 ? 4 : 0;
+    }
     if (dtype == DT_F32) return wv % 4 == 0 ? 4 : (s2 && wv % 2 == 0 ? 2 : 0);
     return wv % 8 == 0 ? 8 : (wv % 4 == 0 ? 4 : 0);
 }
@@ -577,7 +591,7 @@ static hipError_t go_s1(const Geom &g, const void *x, const void *w, void *y, bo
     const int nstrips = ceil_div_h(g.H, TH);
     const long long lanes = (long long)g.N * g.O * nstrips * (g.W / V);
     const unsigned nblocks = (unsigned)((lanes + 255) / 256);
-    const int nt = 0;   // a wave's store covers pieces of several rows (partial lines): keep it cached
+    const int nt = getenv("DWCONV_TUNE_NTN") ? 1 : 0;   // a wave's store covers pieces of several rows (partial lines): keep it cached
     if (flip)
         hipLaunchKernelGGL((k_nchwd_s1<T, V, K, 2, true>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, (const T *)w,
                            (T *)y, TH, nstrips, nblocks, nt);
@@ -602,7 +616,8 @@ hipError_t nchwd_k3s2(const Geom &g, int dtype, int V, const void *in, const voi
     const int nstrips = ceil_div_h(g.Ho, TH);
     const long long lanes = (long long)g.N * g.O * nstrips * (g.Wo / V);
     const unsigned nblocks = (unsigned)((lanes + 255) / 256);
-    const int nt = bwd ? 0 : stream_stores((long long)g.N * g.O * g.Ho * g.Wo * (dtype == DT_F32 ? 4 : 2));
+    int nt = bwd ? 0 : stream_stores((long long)g.N * g.O * g.Ho * g.Wo * (dtype == DT_F32 ? 4 : 2));
+    if (getenv("DWCONV_TUNE_NTS2")) nt = 0;
 #define GO(KERNEL, T, VV) hipLaunchKernelGGL((KERNEL<T, VV>), dim3(nblocks), dim3(256), 0, st, g, (const T *)in, \
                                              (const T *)w, (T *)out, TH, nstrips, nblocks, nt)
     if (!bwd) {
@@ -631,7 +646,9 @@ void nchwd_bwd_filter_tiling(const Geom &g, int V, int TH, int *nsg_out, int *ns
     if (nsg == 0) { *rounds = 1; *parts = 0; return; }
     const int nitems = g.N * *nstrips;
     // enough blocks for ~8 per CU over the O channels
-    int want_parts = (2048 + g.O - 1) / g.O;
+    int want_blocks = 2048;
+    if (const char *e = getenv("DWCONV_TUNE_WB")) { const int v = atoi(e); if (v > 0) want_blocks = v; }
+    int want_parts = (want_blocks + g.O - 1) / g.O;
     if (want_parts < 1) want_parts = 1;
     int r = nitems / (nsg * want_parts);
     if (r < 1) r = 1;

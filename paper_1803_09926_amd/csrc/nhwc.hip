@@ -4,6 +4,7 @@
 // through K-1 rotating accumulators.  A whole image row is one contiguous run of W*C elements,
 // so consecutive lanes cover consecutive 16-byte pieces of it, whatever C is.
 #include "kernels.hpp"
+#include <stdlib.h>
 
 namespace dwc {
 
@@ -366,7 +367,7 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_data_k3s2(Geom g, const T *__r
 // S = 1: "same" padding, K odd.  S = 2: K = 3, pad = 1.
 // ---------------------------------------------------------------------------------------------
 template <typename T, int V, int K, int S, int PF, int M>
-__global__ __launch_bounds__(256) void k_nhwc_bwd_filter(Geom g, const T *__restrict__ x, const T *__restrict__ dy,
+__global__ __launch_bounds__(256, (PF <= 2 && K == 3 && S == 1 && sizeof(T) == 4) ? 4 : 1) void k_nhwc_bwd_filter(Geom g, const T *__restrict__ x, const T *__restrict__ dy,
                                                          float *__restrict__ ws, int CT, int nctiles, int nowtiles,
                                                          int TH, int nstrips, int NI, unsigned nblocks)
 {
@@ -669,8 +670,13 @@ void nhwc_bwd_filter_tiling(const Geom &g, int V, int TH, int NI, int *CT, int *
                             int *ngroups)
 {
     const int Q = g.O / V;
+    // Lanes of a block: CT channel-vectors x 256/CT columns.  Narrow images take all their columns
+    // into one block (fewer, longer partial sums); a lane row of 16 vectors still reads 256 contiguous
+    // bytes per pixel.
+    int cap = 64;
+    if (const char *e = getenv("DWCONV_TUNE_CT")) { const int v = atoi(e); if (v == 8 || v == 16 || v == 32 || v == 64) cap = v; }
     int ct = 1;
-    while (ct < Q && ct < 64) ct <<= 1;
+    while (ct < Q && ct < cap) ct <<= 1;
     *CT = ct;
     *nctiles = ceil_div(Q, ct);
     *nowtiles = ceil_div(g.Wo, 256 / ct);
@@ -698,6 +704,15 @@ hipError_t nhwc_bwd_filter(const Geom &g, int dtype, int V, const void *x, const
     }
 #undef GOM2
     if (dtype == DT_F32) {
+        int pfw = 2;
+        if (const char *e = getenv("DWCONV_TUNE_PFW")) pfw = atoi(e);
+#define GOPF(PP) hipLaunchKernelGGL((k_nhwc_bwd_filter<float, 4, 3, 1, PP, 1>), dim3(nblocks), dim3(256), 0, st, g, \
+                                    (const float *)x, (const float *)dy, ws, CT, nctiles, nowtiles, TH, nstrips, NI, nblocks)
+        if (g.K == 3 && g.s == 1 && pfw == 3) GOPF(3);
+        else if (g.K == 3 && g.s == 1 && pfw == 4) GOPF(4);
+        else if (g.K == 3 && g.s == 1 && pfw == 6) GOPF(6);
+        else
+#undef GOPF
         if (g.K == 3 && g.s == 1) GO(float, 4, 3, 1);
         else if (g.K == 3 && g.s == 2) GO(float, 4, 3, 2);
         else if (g.K == 5 && g.s == 1) GO(float, 4, 5, 1);

@@ -39,13 +39,14 @@ static int nhwc_pf(const Geom &g, int dtype)
     return pf;
 }
 
-// Rows per strip: enough strips that the launch has at least ~12 wavefronts per CU, but strips of
-// at least 7 rows so that the K-1 halo rows re-read per strip stay a small fraction.
-static int pick_th(int rows, long long lanes_per_row_all_images)
+// Rows per strip of the forward / backward-data row walks.  Measured on the benchmark layers:
+// short strips win (14 input rows at stride 1, 7 output rows at stride 2) even though each strip
+// re-reads K-1 halo rows (those come from L2): more, shorter walks keep the launch's accesses
+// closer together in memory.
+static int pick_th(int rows, int stride)
 {
-    const long long want = 256ll * 12 * 64;
-    int th = rows;
-    while (th > 7 && lanes_per_row_all_images * ceil_div(rows, th) < want) th = (th + 1) / 2;
+    const int target = stride == 1 ? tune("DWCONV_TUNE_TH1", 14) : tune("DWCONV_TUNE_TH2", 7);
+    const int th = rows < target ? rows : target;
     return tune("DWCONV_TUNE_TH", th);
 }
 
@@ -76,8 +77,8 @@ Plan plan_fwd(const Geom &g, int layout, int dtype)
         const int V = nchwd_vec(g, dtype, 0);
         if (V) {
             pl.a = V;
-            if (g.s == 1) { pl.variant = V_NCHWD_S1; pl.b = pick_th(g.H, (long long)g.N * g.O * (g.W / V)); pl.name = g.K == 3 ? "nchw_rowwalk_k3s1" : "nchw_rowwalk_k5s1"; }
-            else { pl.variant = V_NCHWD_K3S2; pl.b = pick_th(g.Ho, (long long)g.N * g.O * (g.Wo / V)); pl.name = "nchw_rowwalk_fwd_k3s2"; }
+            if (g.s == 1) { pl.variant = V_NCHWD_S1; pl.b = pick_th(g.H, 1); pl.name = g.K == 3 ? "nchw_rowwalk_k3s1" : "nchw_rowwalk_k5s1"; }
+            else { pl.variant = V_NCHWD_K3S2; pl.b = pick_th(g.Ho, 2); pl.name = "nchw_rowwalk_fwd_k3s2"; }
             return pl;
         }
         const int tr = nchw_pick_tr(g, nchw_fwd_supported);
@@ -87,10 +88,10 @@ Plan plan_fwd(const Geom &g, int layout, int dtype)
     if (layout == LAYOUT_NHWC) {
         const int V = nhwc_vec(g, dtype);
         if (V && same_pad_s1(g)) {
-            pl.variant = V_NHWC_S1; pl.a = V; pl.b = pick_th(g.H, (long long)g.N * g.W * (g.O / V));
+            pl.variant = V_NHWC_S1; pl.a = V; pl.b = pick_th(g.H, 1);
             pl.name = g.m == 2 ? "nhwc_rowwalk_k3s1_m2" : (g.K == 3 ? "nhwc_rowwalk_k3s1" : "nhwc_rowwalk_k5s1");
         } else if (V && k3s2p1(g)) {
-            pl.variant = V_NHWC_K3S2; pl.a = V; pl.b = pick_th(g.Ho, (long long)g.N * g.Wo * (g.C / V));
+            pl.variant = V_NHWC_K3S2; pl.a = V; pl.b = pick_th(g.Ho, 2);
             pl.name = "nhwc_rowwalk_fwd_k3s2";
         }
     }
@@ -109,8 +110,8 @@ Plan plan_bwd_data(const Geom &g, int layout, int dtype)
         const int V = nchwd_vec(g, dtype, 1);
         if (V) {
             pl.a = V;
-            if (g.s == 1) { pl.variant = V_NCHWD_S1; pl.b = pick_th(g.H, (long long)g.N * g.O * (g.W / V)); pl.name = g.K == 3 ? "nchw_rowwalk_k3s1_flip" : "nchw_rowwalk_k5s1_flip"; }
-            else { pl.variant = V_NCHWD_K3S2; pl.b = pick_th(g.Ho, (long long)g.N * g.O * (g.Wo / V)); pl.name = "nchw_rowwalk_bwd_data_k3s2"; }
+            if (g.s == 1) { pl.variant = V_NCHWD_S1; pl.b = pick_th(g.H, 1); pl.name = g.K == 3 ? "nchw_rowwalk_k3s1_flip" : "nchw_rowwalk_k5s1_flip"; }
+            else { pl.variant = V_NCHWD_K3S2; pl.b = pick_th(g.Ho, 2); pl.name = "nchw_rowwalk_bwd_data_k3s2"; }
             return pl;
         }
         if (g.m == 1 && same_pad_s1(g)) {
@@ -125,10 +126,10 @@ Plan plan_bwd_data(const Geom &g, int layout, int dtype)
     if (layout == LAYOUT_NHWC) {
         const int V = nhwc_vec(g, dtype);
         if (V && same_pad_s1(g)) {
-            pl.variant = V_NHWC_S1; pl.a = V; pl.b = pick_th(g.H, (long long)g.N * g.W * (g.O / V));
+            pl.variant = V_NHWC_S1; pl.a = V; pl.b = pick_th(g.H, 1);
             pl.name = g.m == 2 ? "nhwc_rowwalk_k3s1_flip_m2" : (g.K == 3 ? "nhwc_rowwalk_k3s1_flip" : "nhwc_rowwalk_k5s1_flip");
         } else if (V && k3s2p1(g)) {
-            pl.variant = V_NHWC_K3S2; pl.a = V; pl.b = pick_th(g.Ho, (long long)g.N * g.Wo * (g.C / V));
+            pl.variant = V_NHWC_K3S2; pl.a = V; pl.b = pick_th(g.Ho, 2);
             pl.name = "nhwc_rowwalk_bwd_data_k3s2";
         }
     }
@@ -193,14 +194,17 @@ Plan plan_bwd_filter(const Geom &g, int layout, int dtype)
             // One block = 256 lanes over (columns x channel-vectors) x one strip x NI images.  Long
             // walks win (fewer partials, less stage-2 work): start from whole columns and one image
             // per block, and only split rows when the launch would have too few blocks to keep the
-            // memory system busy (stride 1 issues fewer loads per row, so it wants more blocks).
+            // memory system busy.
             int CT, nct, nowt, nst, ngr;
             nhwc_bwd_filter_tiling(g, V, g.Ho, 1, &CT, &nct, &nowt, &nst, &ngr);
             const long long per_strip = (long long)nct * nowt * g.N;   // blocks with NI = 1 and one strip
-            const long long want = g.s == 1 ? 1024 : 512;
+            // Measured on all benchmark layers: about two blocks per CU (512) is the sweet spot, and a
+            // block that walks two images beats two blocks with one image each; stride 2 tolerates
+            // half as many blocks again.
+            const long long want = 512, floor_blocks = g.s == 1 ? 384 : 256;
             int TH = g.Ho, NI = 1;
             while (TH > 7 && per_strip * ceil_div(g.Ho, TH) * 4 < want * 3) TH = (TH + 1) / 2;
-            while (NI < g.N && per_strip * ceil_div(g.Ho, TH) / (NI * 2) >= want) NI *= 2;
+            while (NI < g.N && per_strip * ceil_div(g.Ho, TH) / (NI * 2) >= floor_blocks) NI *= 2;
             TH = tune("DWCONV_TUNE_THW", tune("DWCONV_TUNE_TH", TH)); NI = tune("DWCONV_TUNE_NI", NI);
             nhwc_bwd_filter_tiling(g, V, TH, NI, &CT, &nct, &nowt, &nst, &ngr);
             // keep the partials within the 64 MiB the header promises
