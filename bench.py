@@ -28,6 +28,11 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="workload index 0..4 (default 2: the headline one)")
+    ap.add_argument("--order", choices=["layer", "train"], default="layer",
+                    help="launch order inside a step: layer by layer (fwd, bwd_filter, bwd_data of each), or as "
+                         "a training step runs them (all forwards, then the backward passes from the last layer up)")
+    ap.add_argument("--side-stream", action="store_true",
+                    help="enqueue each layer's filter gradient on a second stream, beside its input gradient")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the per-launch HIP-event pass")
     ap.add_argument("--report", action="store_true", help="print a per-layer table to stderr")
@@ -36,14 +41,16 @@ def parse():
     return ap.parse_args()
 
 
-def build_ops(dw, wl, cfg, torch):
+def build_ops(dw, wl, cfg, torch, order="layer", side=None):
     """Allocate per-layer buffers and return the list of launches that make one step."""
     import ctypes
     ops = []
     lib = dw.load()
     stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    stream2 = ctypes.c_void_p(side.cuda_stream) if side is not None else stream
     esz = 4 if cfg["dtype"] == wl.F32 else 2
     for layout in cfg["layouts"]:
+        fwd_ops, bwd_ops = [], []
         for li, (layer, repeat) in enumerate(cfg["layers"]):
             x, w, dy = wl.make_inputs_device(layer, cfg["N"], layout, cfg["dtype"], seed=1000 * 7 + li)
             d = dw.desc(cfg["N"], layer.C, layer.H, layer.W, layer.K, layer.stride, layer.pad, layer.mult,
@@ -73,18 +80,43 @@ def build_ops(dw, wl, cfg, torch):
                 rc = lib.dwconv_bwd_filter(dref, px, pdy, pdw, pws, nws, stream)
                 if rc: raise dw.DwconvError(rc, "dwconv_bwd_filter")
 
+            def run_bwd_filter_side(dref=dref, px=px, pdy=pdy, pdw=pdw, pws=pws, nws=nws, keep=keep):
+                rc = lib.dwconv_bwd_filter(dref, px, pdy, pdw, pws, nws, stream2)
+                if rc: raise dw.DwconvError(rc, "dwconv_bwd_filter")
+
             # order within a layer: forward, filter gradient, input gradient.  The two backward passes
             # both read dy; run back to back, the second finds much of it in the 256 MB Infinity Cache.
-            ops.append(dict(common, which=0, variant=dw.variant_name(d, 0), run=run_fwd))
-            ops.append(dict(common, which=2, variant=dw.variant_name(d, 2), run=run_bwd_filter))
-            ops.append(dict(common, which=1, variant=dw.variant_name(d, 1), run=run_bwd_data))
+            f = dict(common, which=0, variant=dw.variant_name(d, 0), run=run_fwd)
+            bf = dict(common, which=2, variant=dw.variant_name(d, 2), run=run_bwd_filter, run_side=run_bwd_filter_side)
+            bd = dict(common, which=1, variant=dw.variant_name(d, 1), run=run_bwd_data)
+            if order == "layer":
+                ops += [f, bf, bd]
+            else:
+                fwd_ops.append(f); bwd_ops.append((bf, bd))
+        if order == "train":
+            ops += fwd_ops
+            for bf, bd in reversed(bwd_ops):
+                ops += [bf, bd]
     return ops
 
 
-def run_step(ops):
+def run_step(ops, main=None, side=None):
+    """One step.  With a side stream the filter gradient of a layer is enqueued there once the layer's
+    forward is done, and runs beside the input gradient (the two are independent in a training step);
+    the step ends when both streams have drained into the main one."""
+    if side is None:
+        for op in ops:
+            for _ in range(op["repeat"]):
+                op["run"]()
+        return
     for op in ops:
         for _ in range(op["repeat"]):
-            op["run"]()
+            if op["which"] == 2:
+                side.wait_stream(main)
+                op["run_side"]()
+            else:
+                op["run"]()
+    main.wait_stream(side)
 
 
 def time_kernels(ops, steps, torch):
@@ -181,15 +213,17 @@ def main():
         dst.copy_(src); dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    ops = build_ops(dw, wl, cfg, torch)
+    main_stream = torch.cuda.current_stream()
+    side = torch.cuda.Stream() if args.side_stream else None
+    ops = build_ops(dw, wl, cfg, torch, args.order, side)
     step_bytes = sum(op["bytes"] * op["repeat"] for op in ops)
 
     for _ in range(args.warmup):
-        run_step(ops)
+        run_step(ops, main_stream, side)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        run_step(ops)
+        run_step(ops, main_stream, side)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
@@ -203,7 +237,7 @@ def main():
         "config": {"workload": cfg["name"], "batch": cfg["N"],
                    "layouts": ["NCHW" if l == wl.NCHW else "NHWC" for l in cfg["layouts"]],
                    "layers": len(cfg["layers"]), "passes": "fwd+bwd_data+bwd_filter",
-                   "step": "one fwd+bwd of the stack in every listed layout"},
+                   "step": "one fwd+bwd of the stack in every listed layout", "launch_order": args.order},
         "pct_of_peak_hbm": round(100.0 * gbs / PEAK_HBM_GBS, 2),
         "algorithmic_GB_per_step": round(step_bytes / 1e9, 4),
     }

@@ -591,7 +591,8 @@ static hipError_t go_s1(const Geom &g, const void *x, const void *w, void *y, bo
     const int nstrips = ceil_div_h(g.H, TH);
     const long long lanes = (long long)g.N * g.O * nstrips * (g.W / V);
     const unsigned nblocks = (unsigned)((lanes + 255) / 256);
-    const int nt = getenv("DWCONV_TUNE_NTN") ? 1 : 0;   // a wave's store covers pieces of several rows (partial lines): keep it cached
+    // a wave's store covers pieces of several rows (partial lines): keep it cached
+    const int nt = stream_stores(flip ? "NCHW_S1_BWD" : "NCHW_S1_FWD", (long long)g.N * g.O * g.H * g.W * sizeof(T), -1);
     if (flip)
         hipLaunchKernelGGL((k_nchwd_s1<T, V, K, 2, true>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, (const T *)w,
                            (T *)y, TH, nstrips, nblocks, nt);
@@ -616,8 +617,8 @@ hipError_t nchwd_k3s2(const Geom &g, int dtype, int V, const void *in, const voi
     const int nstrips = ceil_div_h(g.Ho, TH);
     const long long lanes = (long long)g.N * g.O * nstrips * (g.Wo / V);
     const unsigned nblocks = (unsigned)((lanes + 255) / 256);
-    int nt = bwd ? 0 : stream_stores((long long)g.N * g.O * g.Ho * g.Wo * (dtype == DT_F32 ? 4 : 2));
-    if (getenv("DWCONV_TUNE_NTS2")) nt = 0;
+    const int nt = bwd ? stream_stores("NCHW_S2_BWD", (long long)g.N * g.C * g.H * g.W * (dtype == DT_F32 ? 4 : 2), -1)
+                       : stream_stores("NCHW_S2_FWD", (long long)g.N * g.O * g.Ho * g.Wo * (dtype == DT_F32 ? 4 : 2));
 #define GO(KERNEL, T, VV) hipLaunchKernelGGL((KERNEL<T, VV>), dim3(nblocks), dim3(256), 0, st, g, (const T *)in, \
                                              (const T *)w, (T *)out, TH, nstrips, nblocks, nt)
     if (!bwd) {

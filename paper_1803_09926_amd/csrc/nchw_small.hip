@@ -48,7 +48,7 @@ __device__ __forceinline__ void flat_load(const T *__restrict__ src, int total, 
 
 // lds[e - a0] -> flat range [g0, g1) of dst; the first and last vector may be partial.
 template <typename T>
-__device__ __forceinline__ void flat_store(T *__restrict__ dst, int g0, int g1, const float *lds)
+__device__ __forceinline__ void flat_store(T *__restrict__ dst, int g0, int g1, const float *lds, bool stream)
 {
     constexpr int VE = ElemsS<T>::VE;
     const int a0 = g0 & ~(VE - 1);
@@ -61,7 +61,7 @@ __device__ __forceinline__ void flat_store(T *__restrict__ dst, int g0, int g1, 
             const float4 q = *reinterpret_cast<const float4 *>(lds + idx * VE + j);
             v[j] = q.x; v[j + 1] = q.y; v[j + 2] = q.z; v[j + 3] = q.w;
         }
-        if (a >= g0 && a + VE <= g1) Vec<T, VE>::store(dst + a, v);
+        if (a >= g0 && a + VE <= g1) store_vec<T, VE>(dst + a, v, stream);
         else {
 #pragma unroll
             for (int j = 0; j < VE; ++j)
@@ -76,7 +76,7 @@ __device__ __forceinline__ void flat_store(T *__restrict__ dst, int g0, int g1, 
 // ---------------------------------------------------------------------------------------------
 template <typename T, int K, int S, int W, bool FLIP>
 __global__ __launch_bounds__(256) void k_nchws_fwd(Geom g, const T *__restrict__ x, const T *__restrict__ w,
-                                                   T *__restrict__ y, int U, int nplanes, unsigned nblocks)
+                                                   T *__restrict__ y, int U, int nplanes, unsigned nblocks, int nt)
 {
     extern __shared__ float4 smem4[];
     constexpr int VE = ElemsS<T>::VE;
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(256) void k_nchws_fwd(Geom g, const T *__restrict__
     }
     __syncthreads();
 
-    flat_store<T>(y, go0, go0 + np * HoWo, lout);
+    flat_store<T>(y, go0, go0 + np * HoWo, lout, nt != 0);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -141,7 +141,7 @@ __global__ __launch_bounds__(256) void k_nchws_fwd(Geom g, const T *__restrict__
 // ---------------------------------------------------------------------------------------------
 template <typename T, int W>
 __global__ __launch_bounds__(256) void k_nchws_bwd_data_s2(Geom g, const T *__restrict__ dy, const T *__restrict__ w,
-                                                           T *__restrict__ dx, int U, int nplanes, unsigned nblocks)
+                                                           T *__restrict__ dx, int U, int nplanes, unsigned nblocks, int nt)
 {
     extern __shared__ float4 smem4[];
     constexpr int VE = ElemsS<T>::VE;
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(256) void k_nchws_bwd_data_s2(Geom g, const T *__re
     }
     __syncthreads();
 
-    flat_store<T>(dx, go0, go0 + np * HW, lout);
+    flat_store<T>(dx, go0, go0 + np * HW, lout, nt != 0);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -308,8 +308,10 @@ static hipError_t go_fwd(const Geom &g, const void *x, const void *w, void *y, b
     const size_t lds = lds_bytes_for(U, HW, HoWo, VE);
     const int nplanes = g.N * g.C;
     const unsigned nblocks = (unsigned)cdiv(nplanes, U);
+    // the block writes one contiguous range with whole 16-byte vectors: streamed
+    const int nt = stream_stores(flip ? "NCHW_SMALL_BWD" : "NCHW_SMALL_FWD", (long long)nplanes * HoWo * sizeof(T), 0);
 #define GO(KK, SS, WW, FL) hipLaunchKernelGGL((k_nchws_fwd<T, KK, SS, WW, FL>), dim3(nblocks), dim3(256), lds, st, g, \
-                                              (const T *)x, (const T *)w, (T *)y, U, nplanes, nblocks)
+                                              (const T *)x, (const T *)w, (T *)y, U, nplanes, nblocks, nt)
 #define PICK(KK, SS, WW) if (g.K == KK && g.s == SS && g.W == WW) { if (flip) GO(KK, SS, WW, true); else GO(KK, SS, WW, false); return hipGetLastError(); }
     PICK(3, 1, 7) PICK(3, 1, 14) PICK(3, 1, 28) PICK(3, 2, 14) PICK(3, 2, 28) PICK(5, 1, 7) PICK(5, 1, 14)
 #undef PICK
@@ -332,8 +334,9 @@ static hipError_t go_bwd_data_s2(const Geom &g, const void *dy, const void *w, v
     const size_t lds = lds_bytes_for(U, HoWo, HW, VE);
     const int nplanes = g.N * g.C;
     const unsigned nblocks = (unsigned)cdiv(nplanes, U);
+    const int nt = stream_stores("NCHW_SMALL_BWD", (long long)nplanes * HW * sizeof(T), 0);
 #define GO(WW) hipLaunchKernelGGL((k_nchws_bwd_data_s2<T, WW>), dim3(nblocks), dim3(256), lds, st, g, (const T *)dy, \
-                                  (const T *)w, (T *)dx, U, nplanes, nblocks)
+                                  (const T *)w, (T *)dx, U, nplanes, nblocks, nt)
     if (g.W == 14) GO(14);
     else if (g.W == 28) GO(28);
     else return hipErrorInvalidValue;

@@ -607,7 +607,7 @@ static hipError_t launch_s1(const Geom &g, const void *x, const void *w, void *y
     const int bs = flat_block(lanes);
     const int nchunks = ceil_div(lanes, bs), nstrips = ceil_div(g.H, TH);
     const unsigned nblocks = (unsigned)g.N * nchunks * nstrips;
-    const int nt = stream_stores((long long)g.N * g.H * g.W * (flip ? g.C : g.O) * sizeof(T));
+    const int nt = stream_stores(flip ? "NHWC_S1_BWD" : "NHWC_S1_FWD", (long long)g.N * g.H * g.W * (flip ? g.C : g.O) * sizeof(T), 0);
     if (flip)
         hipLaunchKernelGGL((k_nhwc_s1<T, V, K, PF, true, M>), dim3(nblocks), dim3(bs), 0, st, g, (const T *)x,
                            (const T *)w, (T *)y, TH, nstrips, nchunks, nblocks, nt);
@@ -649,7 +649,8 @@ hipError_t nhwc_k3s2(const Geom &g, int dtype, int V, const void *in, const void
     const unsigned nblocks = (unsigned)g.N * nchunks * nstrips;
     // forward: a wave's store is one contiguous run, and the pass is read-dominated: stream the output.
     // backward-data writes alternate pixel columns per instruction (partial lines): keep those cached.
-    const int nt = bwd ? 0 : stream_stores((long long)g.N * g.Ho * g.Wo * g.C * (dtype == DT_F32 ? 4 : 2));
+    const int nt = bwd ? stream_stores("NHWC_S2_BWD", (long long)g.N * g.H * g.W * g.C * (dtype == DT_F32 ? 4 : 2), 0)
+                       : stream_stores("NHWC_S2_FWD", (long long)g.N * g.Ho * g.Wo * g.C * (dtype == DT_F32 ? 4 : 2), 0);
 #define GO(KERNEL, T, VV) hipLaunchKernelGGL((KERNEL<T, VV>), dim3(nblocks), dim3(bs), 0, st, g, (const T *)in, \
                                              (const T *)w, (T *)out, TH, nstrips, nchunks, nblocks, nt)
     if (!bwd) {
