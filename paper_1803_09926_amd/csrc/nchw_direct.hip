@@ -127,6 +127,179 @@ __global__ __launch_bounds__(256) void k_nchwd_s1(Geom g, const T *__restrict__ 
 }
 
 // ---------------------------------------------------------------------------------------------
+// Whole-line write-out through LDS.  An output row of a plane is not a whole number of 128-byte
+// lines, but RS consecutive rows are (RS = 2 for rows of 448 bytes, 4 for 224), and they are
+// contiguous in memory.  Each lane parks the 16-byte vectors it produces for RS successive rows of
+// its work item in LDS; then the block's 256 * RS vectors are written in memory order with
+// streaming stores: entry e = tid + 256 k belongs to the work item of lane e / RS, and inside an
+// item the entries run over (row, vector column) like the addresses do.  Two LDS buffers alternate,
+// so one barrier per RS rows is enough.  Every lane of the block must take part (no early exit), the
+// rows per strip must be a multiple of RS, and all lanes must produce rows in lockstep.
+// ---------------------------------------------------------------------------------------------
+template <typename T, int RS>
+struct LineWriter {
+    int idx[RS], rows[RS];
+    T *ptr[RS];
+    int slot, buf, done;      // uniform over the block
+
+    // lanes are laid flat over (plane, strip, vector column); W4 vectors per row, VE elements per
+    // vector, TH output rows per strip, H x W output planes
+    __device__ __forceinline__ void init(unsigned lb, int W4, int VE, int nstrips, int nplanes, int TH, int H, int W, T *out)
+    {
+#pragma unroll
+        for (int k = 0; k < RS; ++k) {
+            const int e = threadIdx.x + 256 * k;
+            const int l = e / RS;
+            const unsigned psl = (lb * 256u + l) / (unsigned)W4;
+            const long long first = (long long)psl * W4 - (long long)lb * 256;
+            const int a = first > 0 ? (int)first : 0;
+            const int b = first + W4 < 256 ? (int)(first + W4) : 256;
+            const int cnt = b - a, rel = e - RS * a;
+            const int srow = rel / cnt, ll = a + rel - srow * cnt;
+            const int c4l = (int)((long long)ll - first);
+            const int pl = psl / (unsigned)nstrips, stl = psl - pl * nstrips;
+            const int o0 = stl * TH, o1 = min(H, o0 + TH);
+            idx[k] = srow * 256 + ll;
+            rows[k] = pl < nplanes ? o1 - (o0 + srow) : 0;     // rows from this entry's first one to the strip's end
+            ptr[k] = out + ((size_t)min(pl, nplanes - 1) * H + (o0 + srow)) * W + c4l * VE;
+        }
+        slot = 0; buf = 0; done = 0;
+    }
+
+    // the lane's vector of the next row of its item; writes out after every RS-th row
+    __device__ __forceinline__ void put(u4v_t (&stage)[2][RS * 256], const u4v_t &pk, int W)
+    {
+        stage[buf][slot * 256 + threadIdx.x] = pk;
+        if (++slot == RS) {
+            __syncthreads();
+#pragma unroll
+            for (int k = 0; k < RS; ++k)
+                if (done < rows[k]) {
+                    const u4v_t v = stage[buf][idx[k]];
+                    __builtin_nontemporal_store(v, reinterpret_cast<u4v_t *>(ptr[k] + (size_t)done * W));
+                }
+            slot = 0; buf ^= 1; done += RS;
+        }
+    }
+};
+
+template <typename T>
+__device__ __forceinline__ u4v_t pack16(const float (&r)[16 / sizeof(T)])
+{
+    u4v_t pk;
+    if constexpr (sizeof(T) == 4) {
+        pk.x = __float_as_uint(r[0]); pk.y = __float_as_uint(r[1]); pk.z = __float_as_uint(r[2]); pk.w = __float_as_uint(r[3]);
+    } else {
+        pk.x = (uint32_t)f32_to_bf16(r[0]) | ((uint32_t)f32_to_bf16(r[1]) << 16);
+        pk.y = (uint32_t)f32_to_bf16(r[2]) | ((uint32_t)f32_to_bf16(r[3]) << 16);
+        pk.z = (uint32_t)f32_to_bf16(r[4]) | ((uint32_t)f32_to_bf16(r[5]) << 16);
+        pk.w = (uint32_t)f32_to_bf16(r[6]) | ((uint32_t)f32_to_bf16(r[7]) << 16);
+    }
+    return pk;
+}
+
+// Stride-1 walk of k_nchwd_s1 with the whole-line write-out.
+template <typename T, int V, int K, int PF, bool FLIP, int RS>
+__global__ __launch_bounds__(256) void k_nchwd_s1_lines(Geom g, const T *__restrict__ x, const T *__restrict__ w,
+                                                        T *__restrict__ y, int TH, int nstrips, unsigned nblocks)
+{
+    static_assert(sizeof(T) * V == 16, "one 16-byte vector per lane and row");
+    constexpr int P = (K - 1) / 2;
+    constexpr int NW = V + 2 * P;
+    constexpr int R = PF + 1;
+    __shared__ u4v_t stage[2][RS * 256];
+    const int W4 = g.W / V;
+    const int nplanes = g.N * g.O;
+    const unsigned lb = xcd_remap(blockIdx.x, nblocks);
+    const unsigned f = lb * 256u + threadIdx.x;
+    const unsigned ps = f / (unsigned)W4;
+    const int c4 = f - ps * W4;
+    int plane = ps / (unsigned)nstrips;
+    const int strip = ps - plane * nstrips;
+    if (plane >= nplanes) plane = nplanes - 1;      // lanes past the end compute on the last plane; nothing of theirs is stored
+    const int n = plane / g.O, o = plane - n * g.O;
+    const int plane_in = n * g.C + o / g.m;
+
+    float wr[K][K];
+#pragma unroll
+    for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < K; ++kw) wr[kh][kw] = ldf(w + (o * K + (FLIP ? K - 1 - kh : kh)) * K + (FLIP ? K - 1 - kw : kw));
+
+    const bool has_left = c4 > 0, has_right = c4 < W4 - 1;
+    const T *xin = x + (size_t)plane_in * g.H * g.W + c4 * V;
+    const int oh0 = strip * TH;
+
+    LineWriter<T, RS> lw;
+    lw.init(lb, W4, V, nstrips, nplanes, TH, g.H, g.W, y);
+
+    int loff[P > 0 ? P : 1], roff[P > 0 ? P : 1];
+#pragma unroll
+    for (int i = 0; i < P; ++i) { loff[i] = has_left ? -(P - i) : 0; roff[i] = has_right ? V + i : V - 1; }
+
+    float ring[R][NW];
+    auto load_row = [&](int r, float (&dst)[NW]) {
+        const T *rp = xin + (size_t)min(max(r, 0), g.H - 1) * g.W;
+        float mid[V];
+        Vec<T, V>::load(rp, mid);
+#pragma unroll
+        for (int i = 0; i < P; ++i) { dst[i] = ldf(rp + loff[i]); dst[P + V + i] = ldf(rp + roff[i]); }
+#pragma unroll
+        for (int v = 0; v < V; ++v) dst[P + v] = mid[v];
+    };
+
+    float acc[K - 1 > 0 ? K - 1 : 1][V];
+#pragma unroll
+    for (int j = 0; j < K - 1; ++j)
+#pragma unroll
+        for (int v = 0; v < V; ++v) acc[j][v] = 0.f;
+
+    auto consume = [&](int idx, int r, const float (&raw)[NW]) {
+        const bool rowok = r >= 0 && r < g.H;
+        float cur[NW];
+#pragma unroll
+        for (int i = 0; i < NW; ++i) {
+            const bool ok = rowok && (i < P ? has_left : (i >= P + V ? has_right : true));
+            cur[i] = ok ? raw[i] : 0.f;
+        }
+        float out[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            float s = (K > 1) ? acc[0][v] : 0.f;
+#pragma unroll
+            for (int kw = 0; kw < K; ++kw) s = fmaf(wr[K - 1][kw], cur[v + kw], s);
+            out[v] = s;
+        }
+#pragma unroll
+        for (int jj = 0; jj < K - 1; ++jj)
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                float s = (jj + 1 < K - 1) ? acc[jj + 1][v] : 0.f;
+#pragma unroll
+                for (int kw = 0; kw < K; ++kw) s = fmaf(wr[K - 2 - jj][kw], cur[v + kw], s);
+                acc[jj][v] = s;
+            }
+        if (idx >= 2 * P) lw.put(stage, pack16<T>(out), g.W);      // the row just finished is output row oh0 + idx - 2P
+    };
+
+    const int r0 = oh0 - P, nrows = TH + 2 * P;
+#pragma unroll
+    for (int j = 0; j < PF; ++j) load_row(r0 + j, ring[j]);
+    int i = 0;
+#pragma unroll 1
+    for (; i + R <= nrows; i += R) {
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            load_row(r0 + i + j + PF, ring[(j + PF) % R]);
+            consume(i + j, r0 + i + j, ring[j]);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < R - 1; ++j)
+        if (i + j < nrows) consume(i + j, r0 + i + j, ring[j]);
+}
+
+// ---------------------------------------------------------------------------------------------
 // Forward, 3x3, stride 2, pad 1, W even.  A lane owns V adjacent output columns and walks down
 // the output rows: it needs input columns 2*V*c4 - 1 .. 2*V*c4 + 2V - 1 of rows 2oh-1, 2oh, 2oh+1
 // (row 2oh+1 is reused as the top row of output row oh+1).
@@ -277,6 +450,80 @@ __global__ __launch_bounds__(256) void k_nchwd_bwd_data_k3s2(Geom g, const T *__
             store_vec<T, 2 * V>(rp, ev, nt != 0);
             store_vec<T, 2 * V>(rp + g.W, od, nt != 0);
         }
+    };
+    int i = 0;
+#pragma unroll 1
+    for (; i + 3 <= TH; i += 3) {
+#pragma unroll
+        for (int j = 0; j < 3; ++j) {
+            load_row(a0 + i + j + 2, rows[(j + 2) % 3]);
+            emit(a0 + i + j, rows[j], rows[(j + 1) % 3]);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        if (i + j < TH) {
+            load_row(a0 + i + j + 2, rows[(j + 2) % 3]);
+            emit(a0 + i + j, rows[j], rows[(j + 1) % 3]);
+        }
+    }
+}
+
+// The same with the whole-line write-out (dx rows 2a and 2a+1 are RS = 2 rows of 2V-wide vectors).
+template <typename T, int V, int RS>
+__global__ __launch_bounds__(256) void k_nchwd_bwd_data_k3s2_lines(Geom g, const T *__restrict__ dy, const T *__restrict__ w,
+                                                                   T *__restrict__ dx, int TH, int nstrips, unsigned nblocks)
+{
+    static_assert(sizeof(T) * 2 * V == 16, "one 16-byte dx vector per lane and row");
+    __shared__ u4v_t stage[2][RS * 256];
+    const int Wo4 = g.Wo / V;
+    Lane ln = lane_of(nblocks, Wo4, nstrips, g.N * g.C);
+    if (!ln.valid) ln.plane = g.N * g.C - 1;     // lanes past the end compute on the last plane; nothing of theirs is stored
+    LineWriter<T, RS> lw;
+    lw.init(xcd_remap(blockIdx.x, nblocks), Wo4, 2 * V, nstrips, g.N * g.C, 2 * TH, g.H, g.W, dx);
+    const int o = ln.plane % g.C;
+    float wr[3][3];
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) wr[kh][kw] = ldf(w + (o * 3 + kh) * 3 + kw);
+    const bool has_right = ln.c4 < Wo4 - 1;
+    const T *dyin = dy + (size_t)ln.plane * g.Ho * g.Wo + ln.c4 * V;
+    const int a0 = ln.strip * TH;
+    const int roff = has_right ? V : V - 1;
+
+    // Raw loads (clamped row); the row below the image's last dy row and the column right of a
+    // row's last vector are masked at use.  Every lane walks TH dy rows, stores masked past the
+    // end of a shorter last strip.
+    auto load_row = [&](int a, float (&dst)[V + 1]) {
+        const T *rp = dyin + (size_t)min(a, g.Ho - 1) * g.Wo;
+        float m[V];
+        Vec<T, V>::load(rp, m);
+        dst[V] = ldf(rp + roff);
+#pragma unroll
+        for (int v = 0; v < V; ++v) dst[v] = m[v];
+    };
+
+    float rows[3][V + 1];
+    load_row(a0, rows[0]);
+    load_row(a0 + 1, rows[1]);
+    auto emit = [&](int a, const float (&Ar)[V + 1], const float (&Br)[V + 1]) {
+        const bool below = a + 1 < g.Ho;
+        float A[V + 1], B[V + 1];
+#pragma unroll
+        for (int v = 0; v < V; ++v) { A[v] = Ar[v]; B[v] = below ? Br[v] : 0.f; }
+        A[V] = has_right ? Ar[V] : 0.f;
+        B[V] = (has_right && below) ? Br[V] : 0.f;
+        float ev[2 * V], od[2 * V];   // dx rows 2a and 2a+1, the lane's 2V columns
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            ev[2 * v] = wr[1][1] * A[v];
+            ev[2 * v + 1] = fmaf(wr[1][0], A[v + 1], wr[1][2] * A[v]);
+            od[2 * v] = fmaf(wr[0][1], B[v], wr[2][1] * A[v]);
+            od[2 * v + 1] = fmaf(wr[0][0], B[v + 1], fmaf(wr[0][2], B[v], fmaf(wr[2][0], A[v + 1], wr[2][2] * A[v])));
+        }
+        lw.put(stage, pack16<T>(ev), g.W);
+        lw.put(stage, pack16<T>(od), g.W);
     };
     int i = 0;
 #pragma unroll 1
@@ -585,14 +832,42 @@ int nchwd_vec(const Geom &g, int dtype, int pass)
     return wv % 8 == 0 ? 8 : (wv % 4 == 0 ? 4 : 0);
 }
 
+// rows that together make whole 128-byte lines (0 if more than 4 would be needed)
+template <typename T>
+static int rows_per_line_group(int W)
+{
+    int rs = 1;
+    while (rs <= 4 && (rs * W * (int)sizeof(T)) % 128 != 0) rs <<= 1;
+    return rs <= 4 ? rs : 0;
+}
+
 template <typename T, int V, int K>
 static hipError_t go_s1(const Geom &g, const void *x, const void *w, void *y, bool flip, int TH, hipStream_t st)
 {
+    const long long out_bytes = (long long)g.N * g.O * g.H * g.W * sizeof(T);
+    if constexpr (sizeof(T) * V == 16) {
+        // whole-line write-out, streamed: rows grouped so that a group is a whole number of lines
+        const int rs = rows_per_line_group<T>(g.W);
+        if (rs >= 2 && g.H % rs == 0 && stream_stores(flip ? "NCHW_S1_BWD" : "NCHW_S1_FWD", out_bytes, 0)) {
+            TH = (TH + rs - 1) / rs * rs;
+            const int nstrips = ceil_div_h(g.H, TH);
+            const long long lanes = (long long)g.N * g.O * nstrips * (g.W / V);
+            const unsigned nblocks = (unsigned)((lanes + 255) / 256);
+#define GOL(FL, RSV) hipLaunchKernelGGL((k_nchwd_s1_lines<T, V, K, 2, FL, RSV>), dim3(nblocks), dim3(256), 0, st, g, \
+                                        (const T *)x, (const T *)w, (T *)y, TH, nstrips, nblocks)
+            if (rs == 2) { if (flip) GOL(true, 2); else GOL(false, 2); }
+            else { if (flip) GOL(true, 4); else GOL(false, 4); }
+#undef GOL
+            return hipGetLastError();
+        }
+    }
     const int nstrips = ceil_div_h(g.H, TH);
     const long long lanes = (long long)g.N * g.O * nstrips * (g.W / V);
     const unsigned nblocks = (unsigned)((lanes + 255) / 256);
-    // a wave's store covers pieces of several rows (partial lines): keep it cached
-    const int nt = stream_stores(flip ? "NCHW_S1_BWD" : "NCHW_S1_FWD", (long long)g.N * g.O * g.H * g.W * sizeof(T), -1);
+    // rows that are whole lines by themselves can be streamed as they are; otherwise a wave's store
+    // covers pieces of several rows (partial lines) and stays cached
+    const int whole = (g.W * (int)sizeof(T)) % 128 == 0;
+    const int nt = whole ? stream_stores(flip ? "NCHW_S1_BWD" : "NCHW_S1_FWD", out_bytes, 0) : 0;
     if (flip)
         hipLaunchKernelGGL((k_nchwd_s1<T, V, K, 2, true>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, (const T *)w,
                            (T *)y, TH, nstrips, nblocks, nt);
@@ -629,6 +904,23 @@ hipError_t nchwd_k3s2(const Geom &g, int dtype, int V, const void *in, const voi
         else return hipErrorInvalidValue;
     } else {
         // V = dy columns per lane; the lane stores 2V dx columns as one 16-byte vector per row
+        const int esz = dtype == DT_F32 ? 4 : 2;
+        int rs = 1;
+        while (rs <= 4 && (rs * g.W * esz) % 128 != 0) rs <<= 1;
+        if ((rs == 2 || rs == 4) && g.H % rs == 0 &&
+            stream_stores("NCHW_S2_BWD", (long long)g.N * g.C * g.H * g.W * esz, 0)) {
+            // whole-line write-out, streamed; 2*TH dx rows per strip must be whole row groups
+            const int TH2 = rs == 4 ? (TH + 1) / 2 * 2 : TH;
+            const int nst = ceil_div_h(g.Ho, TH2);
+            const unsigned nb = (unsigned)(((long long)g.N * g.O * nst * (g.Wo / V) + 255) / 256);
+#define GOL(T, VV, RSV) hipLaunchKernelGGL((k_nchwd_bwd_data_k3s2_lines<T, VV, RSV>), dim3(nb), dim3(256), 0, st, g, \
+                                           (const T *)in, (const T *)w, (T *)out, TH2, nst, nb)
+            if (dtype == DT_F32 && V == 2) { if (rs == 2) GOL(float, 2, 2); else GOL(float, 2, 4); }
+            else if (dtype == DT_BF16 && V == 4) { if (rs == 2) GOL(bf16_t, 4, 2); else GOL(bf16_t, 4, 4); }
+            else return hipErrorInvalidValue;
+#undef GOL
+            return hipGetLastError();
+        }
         if (dtype == DT_F32 && V == 2) GO(k_nchwd_bwd_data_k3s2, float, 2);
         else if (dtype == DT_BF16 && V == 4) GO(k_nchwd_bwd_data_k3s2, bf16_t, 4);
         else return hipErrorInvalidValue;
