@@ -12,6 +12,19 @@ namespace dwc {
 
 static inline int ceil_div_h(int a, int b) { return (a + b - 1) / b; }
 
+// Rows per group of the whole-line write-out for output rows of W elements of esz bytes: the
+// smallest group that is a whole number of 128-byte lines, capped at 4 rows (rows of 112 bytes
+// then make groups of whole 64-byte half lines, which measured as good).  0: not applicable
+// (rows that are whole lines by themselves, or too short).
+static int row_group(int W, int esz)
+{
+    int rs = 1;
+    while (rs <= 4 && (rs * W * esz) % 128 != 0) rs <<= 1;
+    if (rs == 8) rs = 4;
+    if (const char *e = getenv("DWCONV_TUNE_RSF")) { const int v = atoi(e); if (rs >= 2 && rs <= 4 && (v == 2 || v == 4)) rs = v; }
+    return (rs == 2 || rs == 4) ? rs : 0;
+}
+
 // flat lane index -> (plane, strip, vector column)
 struct Lane { int plane, strip, c4; bool valid; };
 __device__ __forceinline__ Lane lane_of(unsigned nblocks, int ncols, int nstrips, int nplanes)
@@ -374,6 +387,92 @@ __global__ __launch_bounds__(256) void k_nchwd_fwd_k3s2(Geom g, const T *__restr
             carry[v] = fmaf(wr[0][0], v == 0 ? lo : ro[j][2 * v], fmaf(wr[0][1], ro[j][2 * v + 1], wr[0][2] * ro[j][2 * v + 2]));
         }
         if (oh < oh1) store_vec<T, V>(yout + (size_t)oh * g.Wo, out, nt != 0);
+    };
+    int i = 0;
+#pragma unroll 1
+    for (; i + 2 <= TH; i += 2) {
+        load_row(2 * (oh0 + i) + 2, re[1]); load_row(2 * (oh0 + i) + 3, ro[1]);
+        step(oh0 + i, 0);
+        load_row(2 * (oh0 + i) + 4, re[0]); load_row(2 * (oh0 + i) + 5, ro[0]);
+        step(oh0 + i + 1, 1);
+    }
+    if (i < TH) step(oh0 + i, 0);
+}
+
+// The same with the whole-line write-out of the output rows.
+template <typename T, int V, int RS>
+__global__ __launch_bounds__(256) void k_nchwd_fwd_k3s2_lines(Geom g, const T *__restrict__ x, const T *__restrict__ w,
+                                                              T *__restrict__ y, int TH, int nstrips, unsigned nblocks)
+{
+    static_assert(sizeof(T) * V == 16, "one 16-byte output vector per lane and row");
+    __shared__ u4v_t stage[2][RS * 256];
+    constexpr int NW = 2 * V + 1;
+    const int Wo4 = g.Wo / V;
+    Lane ln = lane_of(nblocks, Wo4, nstrips, g.N * g.O);
+    if (!ln.valid) ln.plane = g.N * g.O - 1;     // lanes past the end compute on the last plane; nothing of theirs is stored
+    LineWriter<T, RS> lw;
+    lw.init(xcd_remap(blockIdx.x, nblocks), Wo4, V, nstrips, g.N * g.O, TH, g.Ho, g.Wo, y);
+    const int n = ln.plane / g.O, o = ln.plane - n * g.O;
+    const int plane_in = n * g.C + o / g.m;
+    float wr[3][3];
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) wr[kh][kw] = ldf(w + (o * 3 + kh) * 3 + kw);
+    const bool has_left = ln.c4 > 0;
+    const T *xin = x + (size_t)plane_in * g.H * g.W + ln.c4 * 2 * V;
+    const int oh0 = ln.strip * TH;
+    const int loff = has_left ? -1 : 0;
+
+    // Raw loads (clamped row), masks applied at use: with H = 2*Ho every row 2oh, 2oh+1 of a valid
+    // output row is inside the image, so only the left neighbour (first vector of a row) and the
+    // row above the image need a select.  Every lane walks TH output rows; lanes past the end of
+    // a shorter last strip keep going with their stores masked.
+    auto load_row = [&](int r, float (&dst)[NW]) {
+        const T *rp = xin + (size_t)min(max(r, 0), g.H - 1) * g.W;
+        if constexpr (2 * V * sizeof(T) <= 16) {
+            // the lane's 2V input columns are one 16-byte vector: consecutive lanes read consecutive vectors
+            float ab[2 * V];
+            Vec<T, 2 * V>::load(rp, ab);
+            dst[0] = ldf(rp + loff);
+#pragma unroll
+            for (int v = 0; v < 2 * V; ++v) dst[1 + v] = ab[v];
+        } else {
+            float a[V], b[V];
+            Vec<T, V>::load(rp, a);
+            Vec<T, V>::load(rp + V, b);
+            dst[0] = ldf(rp + loff);
+#pragma unroll
+            for (int v = 0; v < V; ++v) { dst[1 + v] = a[v]; dst[1 + V + v] = b[v]; }
+        }
+    };
+
+    float carry[V], re[2][NW], ro[2][NW];
+    {
+        float top[NW];
+        load_row(2 * oh0 - 1, top);
+        const bool topok = oh0 > 0;
+        const float l = has_left ? top[0] : 0.f;
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const float t = fmaf(wr[0][0], v == 0 ? l : top[2 * v], fmaf(wr[0][1], top[2 * v + 1], wr[0][2] * top[2 * v + 2]));
+            carry[v] = topok ? t : 0.f;
+        }
+    }
+    load_row(2 * oh0, re[0]);
+    load_row(2 * oh0 + 1, ro[0]);
+    auto step = [&](int oh, int j) {
+        const float le = has_left ? re[j][0] : 0.f, lo = has_left ? ro[j][0] : 0.f;
+        float out[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            float s = carry[v];
+            s = fmaf(wr[1][0], v == 0 ? le : re[j][2 * v], s); s = fmaf(wr[1][1], re[j][2 * v + 1], s); s = fmaf(wr[1][2], re[j][2 * v + 2], s);
+            s = fmaf(wr[2][0], v == 0 ? lo : ro[j][2 * v], s); s = fmaf(wr[2][1], ro[j][2 * v + 1], s); s = fmaf(wr[2][2], ro[j][2 * v + 2], s);
+            out[v] = s;
+            carry[v] = fmaf(wr[0][0], v == 0 ? lo : ro[j][2 * v], fmaf(wr[0][1], ro[j][2 * v + 1], wr[0][2] * ro[j][2 * v + 2]));
+        }
+        lw.put(stage, pack16<T>(out), g.Wo);
     };
     int i = 0;
 #pragma unroll 1
@@ -824,21 +923,16 @@ int nchwd_vec(const Geom &g, int dtype, int pass)
         if (dtype == DT_F32) return wv % 2 == 0 ? 2 : 0;
         return wv % 4 == 0 ? 4 : 0;
     }
-    if (s2 && pass == 0 && !getenv("DWCONV_TUNE_VF4")) {   // forward: the lane's 2V input columns are one 16-byte vector
+    if (s2 && pass == 0) {
+        // forward: 16-byte output vectors when the whole-line write-out applies; otherwise the lane's
+        // 2V input columns are one 16-byte vector
+        const int esz = dtype == DT_F32 ? 4 : 2, rs = row_group(g.Wo, esz);
+        if (rs && g.Ho % rs == 0 && wv % (16 / esz) == 0 && !getenv("DWCONV_TUNE_VF2")) return 16 / esz;
         if (dtype == DT_F32) return wv % 2 == 0 ? 2 : 0;
         return wv % 4 == 0 ? 4 : 0;
     }
     if (dtype == DT_F32) return wv % 4 == 0 ? 4 : (s2 && wv % 2 == 0 ? 2 : 0);
     return wv % 8 == 0 ? 8 : (wv % 4 == 0 ? 4 : 0);
-}
-
-// rows that together make whole 128-byte lines (0 if more than 4 would be needed)
-template <typename T>
-static int rows_per_line_group(int W)
-{
-    int rs = 1;
-    while (rs <= 4 && (rs * W * (int)sizeof(T)) % 128 != 0) rs <<= 1;
-    return rs <= 4 ? rs : 0;
 }
 
 template <typename T, int V, int K>
@@ -847,7 +941,7 @@ static hipError_t go_s1(const Geom &g, const void *x, const void *w, void *y, bo
     const long long out_bytes = (long long)g.N * g.O * g.H * g.W * sizeof(T);
     if constexpr (sizeof(T) * V == 16) {
         // whole-line write-out, streamed: rows grouped so that a group is a whole number of lines
-        const int rs = rows_per_line_group<T>(g.W);
+        const int rs = row_group(g.W, (int)sizeof(T));
         if (rs >= 2 && g.H % rs == 0 && stream_stores(flip ? "NCHW_S1_BWD" : "NCHW_S1_FWD", out_bytes, 0)) {
             TH = (TH + rs - 1) / rs * rs;
             const int nstrips = ceil_div_h(g.H, TH);
@@ -897,6 +991,20 @@ hipError_t nchwd_k3s2(const Geom &g, int dtype, int V, const void *in, const voi
 #define GO(KERNEL, T, VV) hipLaunchKernelGGL((KERNEL<T, VV>), dim3(nblocks), dim3(256), 0, st, g, (const T *)in, \
                                              (const T *)w, (T *)out, TH, nstrips, nblocks, nt)
     if (!bwd) {
+        const int esz = dtype == DT_F32 ? 4 : 2;
+        const int rs = row_group(g.Wo, esz);
+        if (rs && g.Ho % rs == 0 && V * esz == 16 &&
+            stream_stores("NCHW_S2_FWD", (long long)g.N * g.O * g.Ho * g.Wo * esz, 0)) {
+            const int TH2 = (TH + rs - 1) / rs * rs;
+            const int nst = ceil_div_h(g.Ho, TH2);
+            const unsigned nb = (unsigned)(((long long)g.N * g.O * nst * (g.Wo / V) + 255) / 256);
+#define GOL(T, VV, RSV) hipLaunchKernelGGL((k_nchwd_fwd_k3s2_lines<T, VV, RSV>), dim3(nb), dim3(256), 0, st, g, \
+                                           (const T *)in, (const T *)w, (T *)out, TH2, nst, nb)
+            if (dtype == DT_F32) { if (rs == 2) GOL(float, 4, 2); else GOL(float, 4, 4); }
+            else { if (rs == 2) GOL(bf16_t, 8, 2); else GOL(bf16_t, 8, 4); }
+#undef GOL
+            return hipGetLastError();
+        }
         if (dtype == DT_F32 && V == 4) GO(k_nchwd_fwd_k3s2, float, 4);
         else if (dtype == DT_F32 && V == 2) GO(k_nchwd_fwd_k3s2, float, 2);
         else if (dtype == DT_BF16 && V == 8) GO(k_nchwd_fwd_k3s2, bf16_t, 8);
@@ -905,9 +1013,8 @@ hipError_t nchwd_k3s2(const Geom &g, int dtype, int V, const void *in, const voi
     } else {
         // V = dy columns per lane; the lane stores 2V dx columns as one 16-byte vector per row
         const int esz = dtype == DT_F32 ? 4 : 2;
-        int rs = 1;
-        while (rs <= 4 && (rs * g.W * esz) % 128 != 0) rs <<= 1;
-        if ((rs == 2 || rs == 4) && g.H % rs == 0 &&
+        const int rs = row_group(g.W, esz);
+        if (rs && g.H % rs == 0 &&
             stream_stores("NCHW_S2_BWD", (long long)g.N * g.C * g.H * g.W * esz, 0)) {
             // whole-line write-out, streamed; 2*TH dx rows per strip must be whole row groups
             const int TH2 = rs == 4 ? (TH + 1) / 2 * 2 : TH;
