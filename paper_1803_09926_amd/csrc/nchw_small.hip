@@ -46,6 +46,45 @@ __device__ __forceinline__ void flat_load(const T *__restrict__ src, int total, 
     }
 }
 
+// The same in two halves, so that the loads of the next range can be in flight while the block
+// computes on the current one: issue into registers (up to FLAT_BATCH vectors per lane), commit to LDS.
+template <typename T> struct FlatRegs { static constexpr int BATCH = 16 / ElemsS<T>::VE * 2; float v[BATCH][ElemsS<T>::VE]; };
+template <typename T>
+__device__ __forceinline__ void flat_issue(const T *__restrict__ src, int total, int g0, int g1, FlatRegs<T> &r)
+{
+    constexpr int VE = ElemsS<T>::VE;
+    const int a0 = g0 & ~(VE - 1);
+    const int nvec = (g1 - a0 + VE - 1) / VE;
+#pragma unroll
+    for (int it = 0; it < FlatRegs<T>::BATCH; ++it) {
+        const int idx = it * 256 + (int)threadIdx.x;
+        if (idx < nvec) {
+            const int a = a0 + idx * VE;
+            if (a + VE <= total) Vec<T, VE>::load(src + a, r.v[it]);
+            else {
+#pragma unroll
+                for (int j = 0; j < VE; ++j) r.v[it][j] = (a + j < total) ? ldf(src + a + j) : 0.f;
+            }
+        }
+    }
+}
+template <typename T>
+__device__ __forceinline__ void flat_commit(int g0, int g1, const FlatRegs<T> &r, float *lds)
+{
+    constexpr int VE = ElemsS<T>::VE;
+    const int a0 = g0 & ~(VE - 1);
+    const int nvec = (g1 - a0 + VE - 1) / VE;
+#pragma unroll
+    for (int it = 0; it < FlatRegs<T>::BATCH; ++it) {
+        const int idx = it * 256 + (int)threadIdx.x;
+        if (idx < nvec) {
+#pragma unroll
+            for (int j = 0; j < VE; j += 4)
+                *reinterpret_cast<float4 *>(lds + idx * VE + j) = make_float4(r.v[it][j], r.v[it][j + 1], r.v[it][j + 2], r.v[it][j + 3]);
+        }
+    }
+}
+
 // lds[e - a0] -> flat range [g0, g1) of dst; the first and last vector may be partial.
 template <typename T>
 __device__ __forceinline__ void flat_store(T *__restrict__ dst, int g0, int g1, const float *lds, bool stream)
@@ -223,12 +262,24 @@ __global__ __launch_bounds__(256) void k_nchws_bwd_filter(Geom g, const T *__res
         rowi[kh] = min(max(ih, 0), g.H - 1);
     }
 
+    // the next image's planes are loaded into registers while this one is accumulated from LDS
+    FlatRegs<T> rx, rd;
+    {
+        const int gx0 = (n0 * g.C + c0) * HW, gd0 = (n0 * g.O + c0) * HoWo;
+        flat_issue<T>(x, g.N * g.C * HW, gx0, gx0 + nc * HW, rx);
+        flat_issue<T>(dy, g.N * g.O * HoWo, gd0, gd0 + nc * HoWo, rd);
+    }
     for (int n = n0; n < n1; ++n) {
         const int gx0 = (n * g.C + c0) * HW, gd0 = (n * g.O + c0) * HoWo;
         __syncthreads();
-        flat_load<T>(x, g.N * g.C * HW, gx0, gx0 + nc * HW, lx);
-        flat_load<T>(dy, g.N * g.O * HoWo, gd0, gd0 + nc * HoWo, ld);
+        flat_commit<T>(gx0, gx0 + nc * HW, rx, lx);
+        flat_commit<T>(gd0, gd0 + nc * HoWo, rd, ld);
         __syncthreads();
+        if (n + 1 < n1) {
+            const int hx0 = ((n + 1) * g.C + c0) * HW, hd0 = ((n + 1) * g.O + c0) * HoWo;
+            flat_issue<T>(x, g.N * g.C * HW, hx0, hx0 + nc * HW, rx);
+            flat_issue<T>(dy, g.N * g.O * HoWo, hd0, hd0 + nc * HoWo, rd);
+        }
         if (p < nc) {
             const float *xp = lx + (gx0 & (VE - 1)) + p * HW;
             const float *dp = ld + (gd0 & (VE - 1)) + p * HoWo + oh * WO;
@@ -357,6 +408,8 @@ void nchws_bwd_filter_tiling(const Geom &g, int dtype, int *U, int *NI, int *par
     if (u > g.C) u = g.C;
     const int HW = g.H * g.W, HoWo = g.Ho * g.Wo;
     while (u > 1 && lds_bytes_for(u, HW, HoWo, ve) > 60 * 1024) --u;
+    // a block's planes of one image must fit the register staging of the loader (8192 elements per tensor)
+    while (u > 1 && (u * HW + ve > 8192 || u * HoWo + ve > 8192)) --u;
     *U = u;
     // about 2048 blocks in the launch
     const int ncb = cdiv(g.C, u);
