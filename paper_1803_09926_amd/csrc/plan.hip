@@ -62,18 +62,19 @@ static int nchw_pick_tr(const Geom &g, bool (*fits)(const Geom &, int))
 }
 static bool fits_bwd_filter(const Geom &g, int tr) { return nchw_bwd_filter_parts(g, tr, 1) > 0; }
 
-// Small-plane NCHW kernels: rows of 7 or 14 always; rows of 28 when asked for (tuning switch).
-static bool use_small(const Geom &g, int pass)
+// Small-plane NCHW kernels: rows of 7 or 14 always; rows of 28 when the row-walk kernels cannot take
+// the shape (bf16 rows that are not whole 16-byte vectors) or when asked for (tuning switch).
+static bool use_small(const Geom &g, int dtype, int pass)
 {
     if (!nchws_supported(g, pass)) return false;
-    return g.W <= 14 || tune("DWCONV_TUNE_S28", 0) == 1;
+    return g.W <= 14 || tune("DWCONV_TUNE_S28", 0) == 1 || nchwd_vec(g, dtype, pass) == 0;
 }
 
 Plan plan_fwd(const Geom &g, int layout, int dtype)
 {
     Plan pl = {V_GENERIC, 0, 0, 0, 0, "generic"};
     if (layout == LAYOUT_NCHW) {
-        if (use_small(g, 0)) { pl.variant = V_NCHWS_FWD; pl.name = g.K == 5 ? "nchw_smallplane_k5s1" : (g.s == 1 ? "nchw_smallplane_k3s1" : "nchw_smallplane_fwd_k3s2"); return pl; }
+        if (use_small(g, dtype, 0)) { pl.variant = V_NCHWS_FWD; pl.name = g.K == 5 ? "nchw_smallplane_k5s1" : (g.s == 1 ? "nchw_smallplane_k3s1" : "nchw_smallplane_fwd_k3s2"); return pl; }
         const int V = nchwd_vec(g, dtype, 0);
         if (V) {
             pl.a = V;
@@ -102,7 +103,7 @@ Plan plan_bwd_data(const Geom &g, int layout, int dtype)
 {
     Plan pl = {V_GENERIC, 0, 0, 0, 0, "generic"};
     if (layout == LAYOUT_NCHW) {
-        if (use_small(g, 1)) {
+        if (use_small(g, dtype, 1)) {
             if (g.s == 1) { pl.variant = V_NCHWS_FWD; pl.name = g.K == 5 ? "nchw_smallplane_k5s1_flip" : "nchw_smallplane_k3s1_flip"; }
             else { pl.variant = V_NCHWS_BWD_DATA_S2; pl.name = "nchw_smallplane_bwd_data_k3s2"; }
             return pl;
@@ -140,7 +141,7 @@ Plan plan_bwd_filter(const Geom &g, int layout, int dtype)
 {
     Plan pl = {V_GENERIC, generic_bwd_filter_parts(g), 0, 0, 0, "generic"};
     if (layout == LAYOUT_NCHW) {
-        if (use_small(g, 2)) {
+        if (use_small(g, dtype, 2)) {
             int U, NI, parts;
             nchws_bwd_filter_tiling(g, dtype, &U, &NI, &parts);
             NI = tune("DWCONV_TUNE_NI", NI);

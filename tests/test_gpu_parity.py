@@ -58,6 +58,14 @@ AWKWARD = [
     (2, Layer("k5_tail7", 32, 7, 7, 5, 1, 2)),
     (2, Layer("k5_56", 8, 56, 56, 5, 1, 2)),
     (2, Layer("m2_56", 8, 56, 56, 3, 1, 1, 2)),
+    # NCHW whole-line write-out: short last strip, strip taller than the image, partly filled last block,
+    # and heights that rule it out (not a multiple of the row group)
+    (3, Layer("lines_h20_w28", 5, 20, 28)),
+    (1, Layer("lines_h10_w112", 3, 10, 112)),
+    (2, Layer("lines_h40_w56_s2", 3, 40, 56, 3, 2, 1)),
+    (1, Layer("lines_h24_w112_s2", 5, 24, 112, 3, 2, 1)),
+    (2, Layer("nolines_h18_w56", 3, 18, 56)),
+    (2, Layer("lines_k5_h12_w112", 2, 12, 112, 5, 1, 2)),
     (3, Layer("tall", 8, 70, 12)),
     (3, Layer("wide", 8, 6, 300)),
 ]
