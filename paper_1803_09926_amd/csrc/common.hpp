@@ -16,14 +16,17 @@ typedef uint16_t bf16_t;  // raw bf16 bits
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
-// Round to nearest, ties to even; NaN stays NaN (quiet bit forced).
-__device__ __forceinline__ bf16_t f32_to_bf16(float f)
+// fp32 -> bf16, round to nearest even, through the hardware convert of gfx950 (v_cvt_pk_bf16_f32:
+// two values per instruction; the bit-twiddled version costs about eight vector ALU operations per
+// value, as much as the nine multiply-adds of a 3x3 output).
+typedef float f2v_t __attribute__((ext_vector_type(2)));
+typedef __bf16 b2v_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x0040u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
+    const f2v_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, b2v_t));
 }
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) { return (bf16_t)(pack2_bf16(f, 0.f) & 0xffffu); }
 
 __device__ __forceinline__ float ldf(const float *p) { return *p; }
 __device__ __forceinline__ float ldf(const bf16_t *p) { return bf16_to_f32(*p); }
@@ -71,10 +74,10 @@ template <> struct Vec<bf16_t, 8> {
     static __device__ __forceinline__ void store(bf16_t *p, const float (&r)[8])
     {
         uint4 v;
-        v.x = (uint32_t)f32_to_bf16(r[0]) | ((uint32_t)f32_to_bf16(r[1]) << 16);
-        v.y = (uint32_t)f32_to_bf16(r[2]) | ((uint32_t)f32_to_bf16(r[3]) << 16);
-        v.z = (uint32_t)f32_to_bf16(r[4]) | ((uint32_t)f32_to_bf16(r[5]) << 16);
-        v.w = (uint32_t)f32_to_bf16(r[6]) | ((uint32_t)f32_to_bf16(r[7]) << 16);
+        v.x = pack2_bf16(r[0], r[1]);
+        v.y = pack2_bf16(r[2], r[3]);
+        v.z = pack2_bf16(r[4], r[5]);
+        v.w = pack2_bf16(r[6], r[7]);
         *reinterpret_cast<uint4 *>(p) = v;
     }
 };
@@ -88,8 +91,8 @@ template <> struct Vec<bf16_t, 4> {
     static __device__ __forceinline__ void store(bf16_t *p, const float (&r)[4])
     {
         uint2 v;
-        v.x = (uint32_t)f32_to_bf16(r[0]) | ((uint32_t)f32_to_bf16(r[1]) << 16);
-        v.y = (uint32_t)f32_to_bf16(r[2]) | ((uint32_t)f32_to_bf16(r[3]) << 16);
+        v.x = pack2_bf16(r[0], r[1]);
+        v.y = pack2_bf16(r[2], r[3]);
         *reinterpret_cast<uint2 *>(p) = v;
     }
 };
@@ -101,7 +104,7 @@ template <> struct Vec<bf16_t, 2> {
     }
     static __device__ __forceinline__ void store(bf16_t *p, const float (&r)[2])
     {
-        *reinterpret_cast<uint32_t *>(p) = (uint32_t)f32_to_bf16(r[0]) | ((uint32_t)f32_to_bf16(r[1]) << 16);
+        *reinterpret_cast<uint32_t *>(p) = pack2_bf16(r[0], r[1]);
     }
 };
 template <> struct Vec<bf16_t, 1> {
@@ -123,15 +126,15 @@ __device__ __forceinline__ void store_vec(T *p, const float (&r)[V], bool stream
         __builtin_nontemporal_store(v, reinterpret_cast<f4v_t *>(p));
     } else if constexpr (sizeof(T) == 2 && V == 8) {
         u4v_t v;
-        v.x = (uint32_t)f32_to_bf16(r[0]) | ((uint32_t)f32_to_bf16(r[1]) << 16);
-        v.y = (uint32_t)f32_to_bf16(r[2]) | ((uint32_t)f32_to_bf16(r[3]) << 16);
-        v.z = (uint32_t)f32_to_bf16(r[4]) | ((uint32_t)f32_to_bf16(r[5]) << 16);
-        v.w = (uint32_t)f32_to_bf16(r[6]) | ((uint32_t)f32_to_bf16(r[7]) << 16);
+        v.x = pack2_bf16(r[0], r[1]);
+        v.y = pack2_bf16(r[2], r[3]);
+        v.z = pack2_bf16(r[4], r[5]);
+        v.w = pack2_bf16(r[6], r[7]);
         __builtin_nontemporal_store(v, reinterpret_cast<u4v_t *>(p));
     } else if constexpr (sizeof(T) == 2 && V == 4) {
         u2v_t v;
-        v.x = (uint32_t)f32_to_bf16(r[0]) | ((uint32_t)f32_to_bf16(r[1]) << 16);
-        v.y = (uint32_t)f32_to_bf16(r[2]) | ((uint32_t)f32_to_bf16(r[3]) << 16);
+        v.x = pack2_bf16(r[0], r[1]);
+        v.y = pack2_bf16(r[2], r[3]);
         __builtin_nontemporal_store(v, reinterpret_cast<u2v_t *>(p));
     } else {
         Vec<T, V>::store(p, r);

@@ -203,10 +203,10 @@ __device__ __forceinline__ u4v_t pack16(const float (&r)[16 / sizeof(T)])
     if constexpr (sizeof(T) == 4) {
         pk.x = __float_as_uint(r[0]); pk.y = __float_as_uint(r[1]); pk.z = __float_as_uint(r[2]); pk.w = __float_as_uint(r[3]);
     } else {
-        pk.x = (uint32_t)f32_to_bf16(r[0]) | ((uint32_t)f32_to_bf16(r[1]) << 16);
-        pk.y = (uint32_t)f32_to_bf16(r[2]) | ((uint32_t)f32_to_bf16(r[3]) << 16);
-        pk.z = (uint32_t)f32_to_bf16(r[4]) | ((uint32_t)f32_to_bf16(r[5]) << 16);
-        pk.w = (uint32_t)f32_to_bf16(r[6]) | ((uint32_t)f32_to_bf16(r[7]) << 16);
+        pk.x = pack2_bf16(r[0], r[1]);
+        pk.y = pack2_bf16(r[2], r[3]);
+        pk.z = pack2_bf16(r[4], r[5]);
+        pk.w = pack2_bf16(r[6], r[7]);
     }
     return pk;
 }
