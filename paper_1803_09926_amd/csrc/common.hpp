@@ -114,6 +114,45 @@ template <> struct Vec<bf16_t, 1> {
 
 // Store V elements; `stream` = true marks the store non-temporal (the output of a large layer is
 // not read again by these kernels, so it should not displace the halo rows that are).
+// V consecutive elements kept as loaded (bf16 stays packed, two per register) and widened to
+// fp32 only where they are used: a prefetch ring of RawVec costs half the registers of a ring of
+// floats for bf16.
+template <typename T, int V> struct RawVec;
+template <int V> struct RawVec<float, V> {
+    float v[V];
+    __device__ __forceinline__ void load(const float *p) { Vec<float, V>::load(p, v); }
+    __device__ __forceinline__ void get(float (&r)[V]) const
+    {
+#pragma unroll
+        for (int i = 0; i < V; ++i) r[i] = v[i];
+    }
+    __device__ __forceinline__ void zero()
+    {
+#pragma unroll
+        for (int i = 0; i < V; ++i) v[i] = 0.f;
+    }
+};
+template <int V> struct RawVec<bf16_t, V> {
+    static_assert(V % 2 == 0, "bf16 vectors are whole 32-bit words");
+    uint32_t w[V / 2];
+    __device__ __forceinline__ void load(const bf16_t *p)
+    {
+        if constexpr (V == 8) { const uint4 q = *reinterpret_cast<const uint4 *>(p); w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w; }
+        else if constexpr (V == 4) { const uint2 q = *reinterpret_cast<const uint2 *>(p); w[0] = q.x; w[1] = q.y; }
+        else { static_assert(V == 2, "bf16 vectors of 2, 4 or 8"); w[0] = *reinterpret_cast<const uint32_t *>(p); }
+    }
+    __device__ __forceinline__ void get(float (&r)[V]) const
+    {
+#pragma unroll
+        for (int i = 0; i < V / 2; ++i) { r[2 * i] = __uint_as_float(w[i] << 16); r[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u); }
+    }
+    __device__ __forceinline__ void zero()
+    {
+#pragma unroll
+        for (int i = 0; i < V / 2; ++i) w[i] = 0u;
+    }
+};
+
 typedef float f4v_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u4v_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u2v_t __attribute__((ext_vector_type(2)));

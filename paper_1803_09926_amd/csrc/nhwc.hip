@@ -23,6 +23,8 @@ __device__ __forceinline__ Tile tile_of(unsigned nblocks, int nchunks, int nstri
 // the row ring, the rotating accumulators and one row of outputs, plus addressing.
 template <int V, int K, int PF> constexpr int S1_WAVES()
 {
+    // (counted as if every row of the ring were widened to fp32: a tighter budget for bf16, whose ring
+    // stays packed, made the compiler spill and cost 40 %)
     const int regs = K * K * V + (PF + 1) * K * V + (K - 1) * V + V + 24;
     return regs <= 64 ? 8 : regs <= 72 ? 7 : regs <= 84 ? 6 : regs <= 100 ? 5 : regs <= 128 ? 4 : regs <= 168 ? 3 : 2;
 }
@@ -90,11 +92,12 @@ __global__ __launch_bounds__(256, (S1_WAVES<V, K, PF>())) void k_nhwc_s1(
     // (a few redundant re-loads of the last row at the end of a strip).
     const int r0 = oh0 - P, r1 = oh1 + P;
     const int ra = max(r0, 0), rb = min(r1, g.H);
-    float ring[R][K][VI];
-    auto load_row = [&](int r, float (&dst)[K][VI]) {
+    // the ring keeps rows as loaded (bf16 packed) and widens them when the row is consumed
+    RawVec<T, VI> ring[R][K];
+    auto load_row = [&](int r, RawVec<T, VI> (&dst)[K]) {
         const T *rp = xin + (size_t)min(r, rb - 1) * rowstride;
 #pragma unroll
-        for (int kw = 0; kw < K; ++kw) Vec<T, VI>::load(rp + coloff[kw], dst[kw]);
+        for (int kw = 0; kw < K; ++kw) dst[kw].load(rp + coloff[kw]);
     };
     auto emit = [&](int oh, const float (&out)[V]) {
         if constexpr (VO == V) {
@@ -111,8 +114,11 @@ __global__ __launch_bounds__(256, (S1_WAVES<V, K, PF>())) void k_nhwc_s1(
             store_vec<T, VO>(yout + (size_t)oh * orowstride, red, nt != 0);
         }
     };
-    auto consume = [&](int r, const float (&cur)[K][VI]) {
+    auto consume = [&](int r, const RawVec<T, VI> (&raw)[K]) {
         // input row r is tap row kh of output row r + P - kh
+        float cur[K][VI];
+#pragma unroll
+        for (int kw = 0; kw < K; ++kw) raw[kw].get(cur[kw]);
         float out[V];
 #pragma unroll
         for (int v = 0; v < V; ++v) {
@@ -413,14 +419,13 @@ __global__ __launch_bounds__(256, (PF <= 2 && K == 3 && S == 1 && sizeof(T) == 4
         for (int n = n0; n < n1; ++n) {
             const T *xin = x + (size_t)n * g.H * xrow + cq * VX;
             const T *dyin = dy + ((size_t)n * g.Ho * g.Wo + ow) * g.O + cq * V;
-            auto load_x = [&](int r, float (&dst)[K][VX]) {
+            // rows are loaded ahead and stay as loaded (packed for bf16) until they are accumulated
+            auto load_xr = [&](int r, RawVec<T, VX> (&dst)[K]) {
                 const T *rp = xin + (size_t)min(max(r, 0), g.H - 1) * xrow;
 #pragma unroll
-                for (int kw = 0; kw < K; ++kw) Vec<T, VX>::load(rp + coloff[kw], dst[kw]);
+                for (int kw = 0; kw < K; ++kw) dst[kw].load(rp + coloff[kw]);
             };
-            auto load_dy = [&](int oh, float (&dst)[V]) {
-                Vec<T, V>::load(dyin + (size_t)min(max(oh, oh0), oh1 - 1) * dyrow, dst);
-            };
+            auto load_dr = [&](int oh, RawVec<T, V> &dst) { dst.load(dyin + (size_t)min(max(oh, oh0), oh1 - 1) * dyrow); };
             if constexpr (S == 1) {
                 // input row r meets dy row r + P - kh at tap row kh; dyw holds the K live dy rows
                 constexpr int R = PF + 1;
@@ -437,38 +442,47 @@ __global__ __launch_bounds__(256, (PF <= 2 && K == 3 && S == 1 && sizeof(T) == 4
 #pragma unroll
                     for (int v = 0; v < V; ++v) dyw[0][v] = d[v];
                 };
-                auto accumulate = [&](const float (&xr)[K][VX]) {
+                auto push_raw = [&](const RawVec<T, V> &d) {
+                    float dv[V];
+                    d.get(dv);
+                    push_dy(dv);
+                };
+                auto accumulate = [&](const RawVec<T, VX> (&xr)[K]) {
 #pragma unroll
-                    for (int kh = 0; kh < K; ++kh)
+                    for (int kw = 0; kw < K; ++kw) {
+                        float xv[VX];
+                        xr[kw].get(xv);
 #pragma unroll
-                        for (int kw = 0; kw < K; ++kw)
+                        for (int kh = 0; kh < K; ++kh)
 #pragma unroll
-                            for (int v = 0; v < V; ++v) acc[kh][kw][v] = fmaf(dyw[kh][v], xr[kw][v / M], acc[kh][kw][v]);
+                            for (int v = 0; v < V; ++v) acc[kh][kw][v] = fmaf(dyw[kh][v], xv[v / M], acc[kh][kw][v]);
+                    }
                 };
                 const int r0 = oh0 - P, r1 = oh1 + P;
                 const int ra = max(r0, 0), rb = min(r1, g.H);       // x rows inside the image
                 const int rm = min(rb, oh1 - P);                     // rows whose new dy row r+P is inside the strip
+                float zero[V];
+#pragma unroll
+                for (int v = 0; v < V; ++v) zero[v] = 0.f;
                 // rows above the image: their dy rows enter the window, nothing is accumulated
                 for (int r = r0; r < ra; ++r) {
-                    float d[V];
-                    load_dy(r + P, d);
-                    if (r + P >= oh1) {
-#pragma unroll
-                        for (int v = 0; v < V; ++v) d[v] = 0.f;
-                    }
-                    push_dy(d);
+                    RawVec<T, V> d;
+                    load_dr(r + P, d);
+                    if (r + P >= oh1) push_dy(zero);
+                    else push_raw(d);
                 }
-                float xr[R][K][VX], dr[R][V];
+                RawVec<T, VX> xr[R][K];
+                RawVec<T, V> dr[R];
 #pragma unroll
-                for (int j = 0; j < PF; ++j) { load_x(ra + j, xr[j]); load_dy(ra + j + P, dr[j]); }
+                for (int j = 0; j < PF; ++j) { load_xr(ra + j, xr[j]); load_dr(ra + j + P, dr[j]); }
                 int base = ra;
 #pragma unroll 1
                 for (; base + R <= rm; base += R) {
 #pragma unroll
                     for (int j = 0; j < R; ++j) {
-                        load_x(base + j + PF, xr[(j + PF) % R]);
-                        load_dy(base + j + PF + P, dr[(j + PF) % R]);
-                        push_dy(dr[j]);
+                        load_xr(base + j + PF, xr[(j + PF) % R]);
+                        load_dr(base + j + PF + P, dr[(j + PF) % R]);
+                        push_raw(dr[j]);
                         accumulate(xr[j]);
                     }
                 }
@@ -477,77 +491,67 @@ __global__ __launch_bounds__(256, (PF <= 2 && K == 3 && S == 1 && sizeof(T) == 4
 #pragma unroll
                 for (int j = 0; j < R - 1; ++j) {
                     if (base + j < rm) {
-                        push_dy(dr[j]);
+                        push_raw(dr[j]);
                         accumulate(xr[j]);
                     }
                 }
-                {
-                    float zero[V];
-#pragma unroll
-                    for (int v = 0; v < V; ++v) zero[v] = 0.f;
-                    for (int r = max(rm, ra); r < rb; ++r) {
-                        float xt[K][VX];
-                        load_x(r, xt);
-                        push_dy(zero);
-                        accumulate(xt);
-                    }
+                for (int r = max(rm, ra); r < rb; ++r) {
+                    RawVec<T, VX> xt[K];
+                    load_xr(r, xt);
+                    push_dy(zero);
+                    accumulate(xt);
                 }
             } else {
                 // output row oh meets input rows 2oh-1, 2oh, 2oh+1; row 2oh+1 is reused by oh+1.
                 // Rows [oh0, ohb) have all of 2oh, 2oh+1 inside the image; an odd H leaves one last
-                // row without its bottom tap row.  The next output row's loads are issued ahead.
+                // row without its bottom tap row.  The next output row's loads are issued ahead and stay
+                // as loaded (packed for bf16) until the row is accumulated.
                 const int ohb = min(oh1, g.H / 2);
-                float xa[K][VX], xb[2][K][VX], xc[2][K][VX], d[2][V];
-                if (2 * oh0 - 1 >= 0) load_x(2 * oh0 - 1, xa);
+                RawVec<T, VX> xa[K], xb[2][K], xc[2][K];
+                RawVec<T, V> d[2];
+                if (2 * oh0 - 1 >= 0) load_xr(2 * oh0 - 1, xa);
                 else {
 #pragma unroll
-                    for (int kw = 0; kw < K; ++kw)
-#pragma unroll
-                        for (int v = 0; v < VX; ++v) xa[kw][v] = 0.f;
+                    for (int kw = 0; kw < K; ++kw) xa[kw].zero();
                 }
-                load_x(2 * oh0, xb[0]); load_x(2 * oh0 + 1, xc[0]); load_dy(oh0, d[0]);
+                load_xr(2 * oh0, xb[0]); load_xr(2 * oh0 + 1, xc[0]); load_dr(oh0, d[0]);
+                auto tap_row = [&](int kh, const RawVec<T, VX> (&xr)[K], const float (&dv)[V]) {
+#pragma unroll
+                    for (int kw = 0; kw < K; ++kw) {
+                        float xv[VX];
+                        xr[kw].get(xv);
+#pragma unroll
+                        for (int v = 0; v < V; ++v) acc[kh][kw][v] = fmaf(dv[v], xv[v / M], acc[kh][kw][v]);
+                    }
+                };
                 auto step = [&](int j) {
+                    float dv[V];
+                    d[j].get(dv);
+                    tap_row(0, xa, dv); tap_row(1, xb[j], dv); tap_row(2, xc[j], dv);
 #pragma unroll
-                    for (int kw = 0; kw < K; ++kw)
-#pragma unroll
-                        for (int v = 0; v < V; ++v) {
-                            acc[0][kw][v] = fmaf(d[j][v], xa[kw][v / M], acc[0][kw][v]);
-                            acc[1][kw][v] = fmaf(d[j][v], xb[j][kw][v / M], acc[1][kw][v]);
-                            acc[2][kw][v] = fmaf(d[j][v], xc[j][kw][v / M], acc[2][kw][v]);
-                        }
-#pragma unroll
-                    for (int kw = 0; kw < K; ++kw)
-#pragma unroll
-                        for (int v = 0; v < VX; ++v) xa[kw][v] = xc[j][kw][v];
+                    for (int kw = 0; kw < K; ++kw) xa[kw] = xc[j][kw];
                 };
                 int oh = oh0;
 #pragma unroll 1
                 for (; oh + 2 <= ohb; oh += 2) {
-                    load_x(2 * oh + 2, xb[1]); load_x(2 * oh + 3, xc[1]); load_dy(oh + 1, d[1]);
+                    load_xr(2 * oh + 2, xb[1]); load_xr(2 * oh + 3, xc[1]); load_dr(oh + 1, d[1]);
                     step(0);
-                    load_x(2 * oh + 4, xb[0]); load_x(2 * oh + 5, xc[0]); load_dy(oh + 2, d[0]);
+                    load_xr(2 * oh + 4, xb[0]); load_xr(2 * oh + 5, xc[0]); load_dr(oh + 2, d[0]);
                     step(1);
                 }
                 if (oh < ohb) {
-                    load_x(2 * oh + 2, xb[1]); load_dy(oh + 1, d[1]);
+                    load_xr(2 * oh + 2, xb[1]); load_dr(oh + 1, d[1]);
                     step(0);
                     ++oh;
 #pragma unroll
-                    for (int kw = 0; kw < K; ++kw)
-#pragma unroll
-                        for (int v = 0; v < VX; ++v) xb[0][kw][v] = xb[1][kw][v];
-#pragma unroll
-                    for (int v = 0; v < V; ++v) d[0][v] = d[1][v];
+                    for (int kw = 0; kw < K; ++kw) xb[0][kw] = xb[1][kw];
+                    d[0] = d[1];
                 }
                 if (oh < oh1) {
                     // odd H: the last output row has no input row 2oh+1
-#pragma unroll
-                    for (int kw = 0; kw < K; ++kw)
-#pragma unroll
-                        for (int v = 0; v < V; ++v) {
-                            acc[0][kw][v] = fmaf(d[0][v], xa[kw][v / M], acc[0][kw][v]);
-                            acc[1][kw][v] = fmaf(d[0][v], xb[0][kw][v / M], acc[1][kw][v]);
-                        }
+                    float dv[V];
+                    d[0].get(dv);
+                    tap_row(0, xa, dv); tap_row(1, xb[0], dv);
                 }
             }
         }

@@ -26,6 +26,7 @@ static int nhwc_vec(const Geom &g, int dtype)
     else if (g.m != 1) return 0;
     if (dtype == DT_F32) return g.O % 4 == 0 ? 4 : 0;
     if (g.K == 5) return g.O % 4 == 0 ? 4 : 0;   // 25 taps x 8 channels would not fit in registers
+    if (tune("DWCONV_TUNE_VB", 8) == 4) return g.O % 4 == 0 ? 4 : 0;
     return g.O % 8 == 0 ? 8 : (g.O % 4 == 0 ? 4 : 0);
 }
 
@@ -187,10 +188,7 @@ Plan plan_bwd_filter(const Geom &g, int layout, int dtype)
         return pl;
     }
     if (layout == LAYOUT_NHWC) {
-        int V = nhwc_vec(g, dtype);
-        // bf16 stride 2: 8 channels per lane need more than 256 registers (three input rows per output
-        // row in flight); 4 channels per lane measured 1.5x faster
-        if (V == 8 && g.s == 2) V = 4;
+        const int V = nhwc_vec(g, dtype);
         if (V && (same_pad_s1(g) || k3s2p1(g))) {
             // One block = 256 lanes over (columns x channel-vectors) x one strip x NI images.  Long
             // walks win (fewer partials, less stage-2 work): start from whole columns and one image
