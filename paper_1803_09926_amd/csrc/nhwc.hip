@@ -639,6 +639,7 @@ hipError_t nhwc_s1(const Geom &g, int dtype, int V, const void *x, const void *w
         TRY(bf16_t, 8, 3, 1); TRY(bf16_t, 8, 3, 2); TRY(bf16_t, 8, 3, 3);
         TRY(bf16_t, 4, 3, 1); TRY(bf16_t, 4, 3, 2); TRY(bf16_t, 4, 3, 3);
         TRY(bf16_t, 4, 5, 1); TRY(bf16_t, 4, 5, 2);
+        TRY(bf16_t, 2, 5, 1); TRY(bf16_t, 2, 5, 2);
     }
 #undef TRY
     return hipErrorInvalidValue;
@@ -727,6 +728,7 @@ hipError_t nhwc_bwd_filter(const Geom &g, int dtype, int V, const void *x, const
         else if (g.K == 3 && g.s == 1) GO(bf16_t, 4, 3, 1);
         else if (g.K == 3 && g.s == 2 && V == 8) GO(bf16_t, 8, 3, 2);
         else if (g.K == 3 && g.s == 2) GO(bf16_t, 4, 3, 2);
+        else if (g.K == 5 && g.s == 1 && V == 2) GO(bf16_t, 2, 5, 1);
         else if (g.K == 5 && g.s == 1) GO(bf16_t, 4, 5, 1);
         else return hipErrorInvalidValue;
     }

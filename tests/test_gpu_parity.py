@@ -57,6 +57,7 @@ AWKWARD = [
     (2, Layer("c728_like", 182 * 4, 5, 6)),
     (2, Layer("k5_tail7", 32, 7, 7, 5, 1, 2)),
     (2, Layer("k5_56", 8, 56, 56, 5, 1, 2)),
+    (2, Layer("k5_c6", 6, 12, 12, 5, 1, 2)),
     (2, Layer("m2_56", 8, 56, 56, 3, 1, 1, 2)),
     # NCHW whole-line write-out: short last strip, strip taller than the image, partly filled last block,
     # and heights that rule it out (not a multiple of the row group)
