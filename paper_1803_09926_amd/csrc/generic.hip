@@ -137,8 +137,10 @@ __global__ __launch_bounds__(256) void k_generic_bwd_filter_nhwc(Geom g, const T
 }
 
 // Stage 2: dw[j] = sum_p ws[p*J + j].  A block owns JT consecutive j; PT = 256/JT threads per j
-// take the partials p = r, r+PT, r+2PT, ... eight at a time (eight independent loads in flight,
-// added in a fixed tree), then the PT sub-sums are added in a fixed tree through LDS.
+// take the partials p = r, r+PT, r+2PT, ... eight at a time.  All eight loads of a batch are issued
+// before the first is used, also in the last, partly filled batch (clamped index, value dropped):
+// the kernel is a few microseconds of pure load latency, so one latency per batch is what counts.
+// The batch is added in a fixed tree, then the PT sub-sums in a fixed tree through LDS.
 template <int JT>
 __global__ __launch_bounds__(256) void k_reduce_partials(const float *__restrict__ ws, int parts, int J,
                                                          float *__restrict__ dw)
@@ -150,14 +152,16 @@ __global__ __launch_bounds__(256) void k_reduce_partials(const float *__restrict
     float acc = 0.f;
     if (j < J) {
         const float *p0 = ws + j;
-        int p = r;
-        for (; p + 7 * PT < parts; p += 8 * PT) {
+        for (int p = r; p < parts; p += 8 * PT) {
             float v[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) v[i] = p0[(size_t)(p + i * PT) * J];
+            for (int i = 0; i < 8; ++i) {
+                const int q = p + i * PT;
+                const float t = p0[(size_t)min(q, parts - 1) * J];
+                v[i] = q < parts ? t : 0.f;
+            }
             acc += ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
         }
-        for (; p < parts; p += PT) acc += p0[(size_t)p * J];
     }
     red[r][jj] = acc;
     __syncthreads();
@@ -228,10 +232,19 @@ hipError_t generic_bwd_filter(const Geom &g, int layout, int dtype, const void *
 
 hipError_t reduce_partials(const float *ws, int parts, int J, float *dw, hipStream_t st)
 {
-    // small J: fewer j per block so that enough blocks exist to pull the partials in parallel
-    if (J >= 8192) hipLaunchKernelGGL(k_reduce_partials<16>, dim3((J + 15) / 16), dim3(256), 0, st, ws, parts, J, dw);
-    else if (J >= 2048) hipLaunchKernelGGL(k_reduce_partials<8>, dim3((J + 7) / 8), dim3(256), 0, st, ws, parts, J, dw);
-    else hipLaunchKernelGGL(k_reduce_partials<4>, dim3((J + 3) / 4), dim3(256), 0, st, ws, parts, J, dw);
+    // threads per output chosen so that one batch of eight loads per thread covers the partials
+    // (PT = 256/JT about parts/8), but enough blocks to spread small J over the chip
+    int jt = 4;
+    while (jt < 64 && (256 / jt) * 8 > parts && (J + 2 * jt - 1) / (2 * jt) >= 8) jt *= 2;
+#define GO(JT) hipLaunchKernelGGL(k_reduce_partials<JT>, dim3((J + JT - 1) / JT), dim3(256), 0, st, ws, parts, J, dw)
+    switch (jt) {
+    case 4: GO(4); break;
+    case 8: GO(8); break;
+    case 16: GO(16); break;
+    case 32: GO(32); break;
+    default: GO(64); break;
+    }
+#undef GO
     return hipGetLastError();
 }
 
