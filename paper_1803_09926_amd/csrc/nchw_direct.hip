@@ -313,6 +313,150 @@ __global__ __launch_bounds__(256) void k_nchwd_s1_lines(Geom g, const T *__restr
 }
 
 // ---------------------------------------------------------------------------------------------
+// bf16 stride-1 walk on packed pairs.  In NCHW two adjacent columns share a 32-bit word, and
+// gfx950 multiplies two bf16 pairs and adds both products to an fp32 accumulator in one
+// instruction (v_dot2c_f32_bf16), so the row stays packed: no widening, and a K-tap row of an
+// output costs ceil((K+1)/2) instructions instead of K.  A lane owns 8 columns = 4 words, plus the
+// aligned word left and right of them (columns -2,-1 and 8,9): P[i] = columns (2i-2, 2i-1).
+// Output column j reads columns j-P..j+P, which start in word (j-P+2)/2 at half (j+P)&1; the
+// filter row is packed twice, once for each starting half, with a zero in the unused half.
+// Accumulation is fp32 as in the other kernels; products of bf16 values are exact in fp32.
+// RS > 0: whole-line write-out of RS-row groups (LineWriter); RS == 0: direct 16-byte stores.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(b2v_t, a), __builtin_bit_cast(b2v_t, b), c, false);
+}
+
+template <int V, int K, int PF, bool FLIP, int RS>
+__global__ __launch_bounds__(256) void k_nchwd_s1_bf16x8(Geom g, const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
+                                                         bf16_t *__restrict__ y, int TH, int nstrips, unsigned nblocks)
+{
+    static_assert((V == 8 || V == 4) && (RS == 0 || V == 8), "8 columns per lane, or 4 without the whole-line write-out");
+    constexpr int P = (K - 1) / 2, R = PF + 1;
+    constexpr int NP = V / 2 + 2;                   // words per row and lane
+    constexpr int NT = (K + 2) / 2;                 // packed words per filter row (either starting half)
+    static_assert(K == 3 || K == 5, "left and right neighbours must fit one word each");
+    __shared__ u4v_t stage[2][(RS > 0 ? RS : 1) * 256];
+    const int W4 = g.W / V;
+    const int nplanes = g.N * g.O;
+    const unsigned lb = xcd_remap(blockIdx.x, nblocks);
+    const unsigned f = lb * 256u + threadIdx.x;
+    const unsigned ps = f / (unsigned)W4;
+    const int c4 = f - ps * W4;
+    int plane = ps / (unsigned)nstrips;
+    const int strip = ps - plane * nstrips;
+    const bool valid = plane < nplanes;
+    if (!valid) plane = nplanes - 1;      // lanes past the end compute on the last plane; nothing of theirs is stored
+    const int n = plane / g.O, o = plane - n * g.O;
+    const int plane_in = n * g.C + o / g.m;
+
+    // filter rows packed for both starting halves: wp[kh][q][t], q = (j + P) & 1
+    uint32_t wp[K][2][NT];
+#pragma unroll
+    for (int kh = 0; kh < K; ++kh) {
+        uint32_t wv[K];
+#pragma unroll
+        for (int kw = 0; kw < K; ++kw) wv[kw] = w[(o * K + (FLIP ? K - 1 - kh : kh)) * K + (FLIP ? K - 1 - kw : kw)];
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const int k0 = 2 * t - q, k1 = 2 * t + 1 - q;       // taps in the low and the high half
+                const uint32_t lo = (k0 >= 0 && k0 < K) ? wv[k0 < 0 ? 0 : (k0 < K ? k0 : 0)] : 0u;
+                const uint32_t hi = (k1 >= 0 && k1 < K) ? wv[k1 < 0 ? 0 : (k1 < K ? k1 : 0)] : 0u;
+                wp[kh][q][t] = lo | (hi << 16);
+            }
+    }
+
+    const bool has_left = c4 > 0, has_right = c4 < W4 - 1;
+    const bf16_t *xin = x + (size_t)plane_in * g.H * g.W + c4 * V;
+    bf16_t *yout = y + (size_t)plane * g.H * g.W + c4 * V;
+    const int oh0 = strip * TH, oh1 = min(g.H, oh0 + TH);
+    const int loff = has_left ? -2 : 0, roff = has_right ? V : V - 2;     // clamped into the lane's own words
+
+    LineWriter<bf16_t, (RS > 0 ? RS : 1)> lw;
+    if constexpr (RS > 0) lw.init(lb, W4, V, nstrips, nplanes, TH, g.H, g.W, y);
+
+    uint32_t ring[R][NP];
+    auto load_row = [&](int r, uint32_t (&dst)[NP]) {
+        const bf16_t *rp = xin + (size_t)min(max(r, 0), g.H - 1) * g.W;
+        if constexpr (V == 8) {
+            const uint4 mid = *reinterpret_cast<const uint4 *>(rp);
+            dst[1] = mid.x; dst[2] = mid.y; dst[3] = mid.z; dst[4] = mid.w;
+        } else {
+            const uint2 mid = *reinterpret_cast<const uint2 *>(rp);
+            dst[1] = mid.x; dst[2] = mid.y;
+        }
+        dst[0] = *reinterpret_cast<const uint32_t *>(rp + loff);
+        dst[NP - 1] = *reinterpret_cast<const uint32_t *>(rp + roff);
+    };
+
+    float acc[K - 1][V];
+#pragma unroll
+    for (int j = 0; j < K - 1; ++j)
+#pragma unroll
+        for (int v = 0; v < V; ++v) acc[j][v] = 0.f;
+
+    // contribution of input row `cur` through filter row kh to the lane's 8 outputs, added to `s`
+    auto tap_row = [&](int kh, const uint32_t (&cur)[NP], float (&s)[V]) {
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            const int q = (j + P) & 1, i0 = (j - P + 2) >> 1;
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                if (2 * t - q < K && 2 * t + 1 - q >= 0) s[j] = dot2_bf16(cur[i0 + t], wp[kh][q][t], s[j]);
+        }
+    };
+
+    auto consume = [&](int idx, int r, const uint32_t (&raw)[NP]) {
+        const bool rowok = r >= 0 && r < g.H;
+        uint32_t cur[NP];
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const bool ok = rowok && (i == 0 ? has_left : (i == NP - 1 ? has_right : true));
+            cur[i] = ok ? raw[i] : 0u;
+        }
+        float out[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) out[v] = acc[0][v];
+        tap_row(K - 1, cur, out);
+#pragma unroll
+        for (int jj = 0; jj < K - 1; ++jj) {
+            float s[V];
+#pragma unroll
+            for (int v = 0; v < V; ++v) s[v] = (jj + 1 < K - 1) ? acc[jj + 1][v] : 0.f;
+            tap_row(K - 2 - jj, cur, s);
+#pragma unroll
+            for (int v = 0; v < V; ++v) acc[jj][v] = s[v];
+        }
+        if (idx >= 2 * P) {        // the row just finished is output row oh0 + idx - 2P
+            if constexpr (RS > 0 && V == 8) lw.put(stage, pack16<bf16_t>(out), g.W);
+            else {
+                const int oh = r - P;
+                if (valid && oh < oh1) Vec<bf16_t, V>::store(yout + (size_t)oh * g.W, out);
+            }
+        }
+    };
+
+    const int r0 = oh0 - P, nrows = TH + 2 * P;
+#pragma unroll
+    for (int j = 0; j < PF; ++j) load_row(r0 + j, ring[j]);
+    int i = 0;
+#pragma unroll 1
+    for (; i + R <= nrows; i += R) {
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            load_row(r0 + i + j + PF, ring[(j + PF) % R]);
+            consume(i + j, r0 + i + j, ring[j]);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < R - 1; ++j)
+        if (i + j < nrows) consume(i + j, r0 + i + j, ring[j]);
+}
+
+// ---------------------------------------------------------------------------------------------
 // Forward, 3x3, stride 2, pad 1, W even.  A lane owns V adjacent output columns and walks down
 // the output rows: it needs input columns 2*V*c4 - 1 .. 2*V*c4 + 2V - 1 of rows 2oh-1, 2oh, 2oh+1
 // (row 2oh+1 is reused as the top row of output row oh+1).
@@ -949,6 +1093,15 @@ static hipError_t go_s1(const Geom &g, const void *x, const void *w, void *y, bo
             const unsigned nblocks = (unsigned)((lanes + 255) / 256);
 #define GOL(FL, RSV) hipLaunchKernelGGL((k_nchwd_s1_lines<T, V, K, 2, FL, RSV>), dim3(nblocks), dim3(256), 0, st, g, \
                                         (const T *)x, (const T *)w, (T *)y, TH, nstrips, nblocks)
+#define GOB(FL, RSV) hipLaunchKernelGGL((k_nchwd_s1_bf16x8<V, K, 2, FL, RSV>), dim3(nblocks), dim3(256), 0, st, g, \
+                                        (const bf16_t *)x, (const bf16_t *)w, (bf16_t *)y, TH, nstrips, nblocks)
+            if constexpr (sizeof(T) == 2 && V == 8) {      // bf16: packed-pair arithmetic
+                if (!getenv("DWCONV_TUNE_NODOT")) {
+                    if (rs == 2) { if (flip) GOB(true, 2); else GOB(false, 2); }
+                    else { if (flip) GOB(true, 4); else GOB(false, 4); }
+                    return hipGetLastError();
+                }
+            }
             if (rs == 2) { if (flip) GOL(true, 2); else GOL(false, 2); }
             else { if (flip) GOL(true, 4); else GOL(false, 4); }
 #undef GOL
@@ -960,6 +1113,13 @@ static hipError_t go_s1(const Geom &g, const void *x, const void *w, void *y, bo
     const unsigned nblocks = (unsigned)((lanes + 255) / 256);
     // rows that are whole lines by themselves can be streamed as they are; otherwise a wave's store
     // covers pieces of several rows (partial lines) and stays cached
+    if constexpr (sizeof(T) == 2) {
+        if (!getenv("DWCONV_TUNE_NODOT")) {
+            if (flip) GOB(true, 0); else GOB(false, 0);
+            return hipGetLastError();
+        }
+    }
+#undef GOB
     const int whole = (g.W * (int)sizeof(T)) % 128 == 0;
     const int nt = whole ? stream_stores(flip ? "NCHW_S1_BWD" : "NCHW_S1_FWD", out_bytes, 0) : 0;
     if (flip)
