@@ -1050,6 +1050,123 @@ __global__ __launch_bounds__(256) void k_nchwd_bwd_filter_s1(Geom g, const T *__
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Backward-filter stage 1 for bf16, stride 1, on packed pairs (see k_nchwd_s1_bf16x8): the dy row
+// and the x row both stay packed, and one v_dot2c_f32_bf16 adds dy[2m] x[2m+e] + dy[2m+1] x[2m+1+e]
+// to the tap's fp32 sum.  For an even column offset e = kw - P the x pair is a word as loaded; for
+// an odd one it straddles two words and is built once per x row with a funnel shift (V/2 + 1 of
+// them serve every odd offset).  Same block structure and reduction as k_nchwd_bwd_filter_s1.
+// ---------------------------------------------------------------------------------------------
+template <int V, int K>
+__global__ __launch_bounds__(256) void k_nchwd_bwd_filter_s1_bf16(Geom g, const bf16_t *__restrict__ x,
+                                                                  const bf16_t *__restrict__ dy, float *__restrict__ ws,
+                                                                  int TH, int nstrips, int nsg, int rounds)
+{
+    static_assert((V == 8 || V == 4) && (K == 3 || K == 5), "packed pairs with one neighbour word on each side");
+    __shared__ float red[4][K * K];
+    constexpr int P = (K - 1) / 2;
+    constexpr int NP = V / 2 + 2;       // x words per row and lane: columns -2 .. V+1
+    constexpr int ND = V / 2;           // dy words per row and lane
+    const int o = blockIdx.y, part = blockIdx.x;
+    const int ncols = g.W / V;
+    const int sg = threadIdx.x / ncols, c4 = threadIdx.x - sg * ncols;
+    const int nitems = g.N * nstrips;
+    const int c_in = o / g.m;
+    const bool has_left = c4 > 0, has_right = c4 < ncols - 1;
+
+    float acc[K][K];
+#pragma unroll
+    for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < K; ++kw) acc[kh][kw] = 0.f;
+
+    if (sg < nsg) {
+        const int loff = has_left ? -2 : 0, roff = has_right ? V : V - 2;
+        for (int rd = 0; rd < rounds; ++rd) {
+            const int item = (part * rounds + rd) * nsg + sg;
+            if (item >= nitems) break;
+            const int n = item / nstrips, strip = item - n * nstrips;
+            const int oh0 = strip * TH, oh1 = min(g.H, oh0 + TH);
+            const bf16_t *xin = x + ((size_t)n * g.C + c_in) * g.H * g.W + c4 * V;
+            const bf16_t *dyin = dy + ((size_t)n * g.O + o) * g.H * g.W + c4 * V;
+            auto load_words = [&](const bf16_t *p, uint32_t *dst) {
+                if constexpr (V == 8) { const uint4 q = *reinterpret_cast<const uint4 *>(p); dst[0] = q.x; dst[1] = q.y; dst[2] = q.z; dst[3] = q.w; }
+                else { const uint2 q = *reinterpret_cast<const uint2 *>(p); dst[0] = q.x; dst[1] = q.y; }
+            };
+            auto load_row = [&](int r, uint32_t (&xd)[NP], uint32_t (&dd)[ND]) {
+                const bf16_t *rp = xin + (size_t)min(max(r, 0), g.H - 1) * g.W;
+                load_words(rp, &xd[1]);
+                xd[0] = *reinterpret_cast<const uint32_t *>(rp + loff);
+                xd[NP - 1] = *reinterpret_cast<const uint32_t *>(rp + roff);
+                load_words(dyin + (size_t)min(max(r + P, 0), g.H - 1) * g.W, &dd[0]);
+            };
+            uint32_t dyw[K][ND];
+#pragma unroll
+            for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+                for (int m = 0; m < ND; ++m) dyw[kh][m] = 0u;
+            uint32_t xr[2][NP], dr[2][ND];
+            auto step = [&](int r, int j) {
+                const bool rowok = r >= 0 && r < g.H;
+                const bool dok = r + P >= oh0 && r + P < oh1;
+                uint32_t xe[NP], xo[NP - 1];       // aligned words; words shifted by one column: xo[i] = columns (2i-1, 2i)
+#pragma unroll
+                for (int i = 0; i < NP; ++i) {
+                    const bool ok = rowok && (i == 0 ? has_left : (i == NP - 1 ? has_right : true));
+                    xe[i] = ok ? xr[j][i] : 0u;
+                }
+#pragma unroll
+                for (int i = 0; i < NP - 1; ++i) xo[i] = __builtin_amdgcn_alignbit(xe[i + 1], xe[i], 16);
+#pragma unroll
+                for (int kh = K - 1; kh > 0; --kh)
+#pragma unroll
+                    for (int m = 0; m < ND; ++m) dyw[kh][m] = dyw[kh - 1][m];
+#pragma unroll
+                for (int m = 0; m < ND; ++m) dyw[0][m] = dok ? dr[j][m] : 0u;
+#pragma unroll
+                for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+                    for (int kw = 0; kw < K; ++kw) {
+                        const int e = kw - P;            // x column = dy column + e
+                        float sacc = acc[kh][kw];
+#pragma unroll
+                        for (int m = 0; m < ND; ++m) {
+                            // dy columns (2m, 2m+1) meet x columns (2m+e, 2m+1+e)
+                            const uint32_t xw = (e & 1) ? xo[m + (e + 1) / 2] : xe[m + 1 + e / 2];
+                            sacc = dot2_bf16(dyw[kh][m], xw, sacc);
+                        }
+                        acc[kh][kw] = sacc;
+                    }
+            };
+            const int r0 = oh0 - P, nrows = TH + 2 * P;
+            load_row(r0, xr[0], dr[0]);
+            int i = 0;
+#pragma unroll 1
+            for (; i + 2 <= nrows; i += 2) {
+                load_row(r0 + i + 1, xr[1], dr[1]);
+                step(r0 + i, 0);
+                load_row(r0 + i + 2, xr[0], dr[0]);
+                step(r0 + i + 1, 1);
+            }
+            if (i < nrows) step(r0 + i, 0);
+        }
+    }
+
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+#pragma unroll
+    for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < K; ++kw) {
+            const float s = wave_sum(acc[kh][kw]);
+            if (lane == 0) red[wv][kh * K + kw] = s;
+        }
+    __syncthreads();
+    if (threadIdx.x < K * K) {
+        const int t = threadIdx.x;
+        ws[((size_t)part * g.O + o) * (K * K) + t] = (red[0][t] + red[1][t]) + (red[2][t] + red[3][t]);
+    }
+}
+
 // ---- host side --------------------------------------------------------------------------------
 
 // vector width for the direct kernels (0 = not applicable): rows must be whole 16-byte vectors;
@@ -1225,6 +1342,16 @@ hipError_t nchwd_bwd_filter(const Geom &g, int dtype, int V, const void *x, cons
     dim3 grid(parts, g.O);
 #define GO(T, VV, SS) hipLaunchKernelGGL((k_nchwd_bwd_filter_k3<T, VV, SS>), grid, dim3(256), 0, st, g, (const T *)x, \
                                          (const T *)dy, ws, TH, nstrips, lg, rounds)
+    if (g.s == 1 && dtype == DT_BF16 && (g.K == 3 || g.K == 5) && (V == 8 || V == 4) && !(V == 4 && g.K == 3) &&
+        !getenv("DWCONV_TUNE_NODOT")) {
+        // bf16: packed-pair arithmetic (3x3 on 4-column lanes measured faster with the two-rows-ahead kernel below)
+#define GOD(VV, KK) hipLaunchKernelGGL((k_nchwd_bwd_filter_s1_bf16<VV, KK>), grid, dim3(256), 0, st, g, (const bf16_t *)x, \
+                                       (const bf16_t *)dy, ws, TH, nstrips, lg, rounds)
+        if (V == 8) { if (g.K == 3) GOD(8, 3); else GOD(8, 5); }
+        else GOD(4, 5);
+#undef GOD
+        return hipGetLastError();
+    }
     if (g.s == 1 && g.K == 5) {
 #define GO5(T, VV) hipLaunchKernelGGL((k_nchwd_bwd_filter_s1<T, VV, 5>), grid, dim3(256), 0, st, g, (const T *)x, \
                                       (const T *)dy, ws, TH, nstrips, lg, rounds)
