@@ -26,6 +26,11 @@ __device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi)
     const f2v_t v = {lo, hi};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, b2v_t));
 }
+// c + a.lo * b.lo + a.hi * b.hi on two packed bf16 pairs, accumulated in fp32 (v_dot2c_f32_bf16).
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(b2v_t, a), __builtin_bit_cast(b2v_t, b), c, false);
+}
 __device__ __forceinline__ bf16_t f32_to_bf16(float f) { return (bf16_t)(pack2_bf16(f, 0.f) & 0xffffu); }
 
 __device__ __forceinline__ float ldf(const float *p) { return *p; }

@@ -323,11 +323,6 @@ __global__ __launch_bounds__(256) void k_nchwd_s1_lines(Geom g, const T *__restr
 // Accumulation is fp32 as in the other kernels; products of bf16 values are exact in fp32.
 // RS > 0: whole-line write-out of RS-row groups (LineWriter); RS == 0: direct 16-byte stores.
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c)
-{
-    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(b2v_t, a), __builtin_bit_cast(b2v_t, b), c, false);
-}
-
 template <int V, int K, int PF, bool FLIP, int RS>
 __global__ __launch_bounds__(256) void k_nchwd_s1_bf16x8(Geom g, const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
                                                          bf16_t *__restrict__ y, int TH, int nstrips, unsigned nblocks)
