@@ -107,11 +107,25 @@ int dwconv_bwd_data(const dwconv_desc *desc, const void *dy, const void *w, void
 int dwconv_bwd_filter(const dwconv_desc *desc, const void *x, const void *dy, void *dw,
                       void *workspace, size_t workspace_bytes, void *stream);
 
+/* Whole backward pass of the layer in one call: dx as dwconv_bwd_data, dw as dwconv_bwd_filter
+ * (Section III-A, backward propagation: both gradients come from the same dy; the paper's Table III
+ * reports them as one "Backward" time).  Where a fused kernel exists (NHWC, 3x3, stride 1, pad 1,
+ * multiplier 1) dy and x are read once and the pass moves 2|x| + |y| elements instead of
+ * 2(|x| + |y|); every other shape runs the two passes one after the other on `stream`, with
+ * results identical to the separate calls.
+ * x, dy, w: device, read.  dx: device, every element written.  dw: device, fp32, written in full.
+ * workspace: device scratch of at least dwconv_bwd_workspace_bytes(desc) bytes, 16-byte aligned.
+ * Same error codes, same determinism (no atomics) as the separate entry points. */
+size_t dwconv_bwd_workspace_bytes(const dwconv_desc *desc);
+int dwconv_bwd(const dwconv_desc *desc, const void *x, const void *dy, const void *w, void *dx, void *dw,
+               void *workspace, size_t workspace_bytes, void *stream);
+
 /* Human-readable name of a status code; never NULL. */
 const char *dwconv_status_string(int status);
 
 /* Name of the kernel variant the dispatcher picks for `desc` and `pass` (0 fwd, 1 bwd_data,
- * 2 bwd_filter), e.g. "nhwc_rowwalk_k3s1_f32x4" or "generic".  Host-only; for reports and
+ * 2 bwd_filter, 3 the whole backward pass of dwconv_bwd: "separate" when it runs the two passes),
+ * e.g. "nhwc_rowwalk_k3s1" or "generic".  Host-only; for reports and
  * tests.  Returns "invalid" for an invalid desc. */
 const char *dwconv_variant_name(const dwconv_desc *desc, int pass);
 

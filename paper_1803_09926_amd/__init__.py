@@ -21,7 +21,8 @@ LIB_PATH = os.path.join(_HERE, "libdwconv.so")
 _lib = None
 
 EXPORTS = ("dwconv_out_dims", "dwconv_bwd_filter_workspace_bytes", "dwconv_fwd", "dwconv_bwd_data",
-           "dwconv_bwd_filter", "dwconv_status_string", "dwconv_variant_name")
+           "dwconv_bwd_filter", "dwconv_bwd_workspace_bytes", "dwconv_bwd", "dwconv_status_string",
+           "dwconv_variant_name")
 
 
 class Desc(ctypes.Structure):
@@ -51,6 +52,8 @@ def load():
     lib.dwconv_fwd.argtypes = [P, VP, VP, VP, VP]; lib.dwconv_fwd.restype = ctypes.c_int
     lib.dwconv_bwd_data.argtypes = [P, VP, VP, VP, VP]; lib.dwconv_bwd_data.restype = ctypes.c_int
     lib.dwconv_bwd_filter.argtypes = [P, VP, VP, VP, VP, ctypes.c_size_t, VP]; lib.dwconv_bwd_filter.restype = ctypes.c_int
+    lib.dwconv_bwd_workspace_bytes.argtypes = [P]; lib.dwconv_bwd_workspace_bytes.restype = ctypes.c_size_t
+    lib.dwconv_bwd.argtypes = [P, VP, VP, VP, VP, VP, VP, ctypes.c_size_t, VP]; lib.dwconv_bwd.restype = ctypes.c_int
     lib.dwconv_status_string.argtypes = [ctypes.c_int]; lib.dwconv_status_string.restype = ctypes.c_char_p
     lib.dwconv_variant_name.argtypes = [P, ctypes.c_int]; lib.dwconv_variant_name.restype = ctypes.c_char_p
     _lib = lib
@@ -79,6 +82,10 @@ def out_dims(d: Desc):
 
 def bwd_filter_workspace_bytes(d: Desc) -> int:
     return int(load().dwconv_bwd_filter_workspace_bytes(ctypes.byref(d)))
+
+
+def bwd_workspace_bytes(d: Desc) -> int:
+    return int(load().dwconv_bwd_workspace_bytes(ctypes.byref(d)))
 
 
 def _ptr(t):
@@ -141,3 +148,19 @@ def bwd_filter(d: Desc, x, dy, dw, workspace, stream=None):
     if rc != 0:
         raise DwconvError(rc, "dwconv_bwd_filter")
     return dw
+
+
+def bwd(d: Desc, x, dy, w, dx, dw, workspace, stream=None):
+    """Enqueue the whole backward pass: dx = input gradient, dw = filter gradient (fp32).  `workspace` is a
+    uint8 device tensor of at least bwd_workspace_bytes(d) bytes."""
+    nx, ny, nw = _sizes(d)
+    _check_tensor(x, "x", d, nx); _check_tensor(dy, "dy", d, ny); _check_tensor(w, "w", d, nw)
+    _check_tensor(dx, "dx", d, nx); _check_tensor(dw, "dw", d, nw, fp32_always=True)
+    if workspace is None or not workspace.is_cuda:
+        raise ValueError("workspace must be a device tensor")
+    nbytes = workspace.numel() * workspace.element_size()
+    rc = load().dwconv_bwd(ctypes.byref(d), _ptr(x), _ptr(dy), _ptr(w), _ptr(dx), _ptr(dw), _ptr(workspace),
+                           ctypes.c_size_t(nbytes), _stream(stream))
+    if rc != 0:
+        raise DwconvError(rc, "dwconv_bwd")
+    return dx, dw

@@ -112,13 +112,48 @@ const char *dwconv_status_string(int status)
     }
 }
 
+size_t dwconv_bwd_workspace_bytes(const dwconv_desc *desc)
+{
+    Geom g;
+    if (validate(desc, &g) != DWCONV_OK) return 0;
+    Plan pl = plan_bwd(g, desc->layout, desc->dtype);
+    if (pl.variant == V_GENERIC) pl = plan_bwd_filter(g, desc->layout, desc->dtype);
+    return (size_t)pl.parts * (size_t)g.O * g.K * g.K * sizeof(float);
+}
+
+int dwconv_bwd(const dwconv_desc *desc, const void *x, const void *dy, const void *w, void *dx, void *dw,
+               void *workspace, size_t workspace_bytes, void *stream)
+{
+    Geom g;
+    int rc = validate(desc, &g);
+    if (rc != DWCONV_OK) return rc;
+    if (!x || !dy || !w || !dx || !dw) return DWCONV_ERR_NULL;
+    if (misaligned(x) || misaligned(dy) || misaligned(w) || misaligned(dx) || misaligned(dw)) return DWCONV_ERR_ALIGN;
+    const Plan pl = plan_bwd(g, desc->layout, desc->dtype);
+    if (pl.variant == V_GENERIC) {
+        // no fused kernel for this shape: the two passes, filter gradient first (the input gradient
+        // then finds dy in cache)
+        rc = dwconv_bwd_filter(desc, x, dy, dw, workspace, workspace_bytes, stream);
+        if (rc != DWCONV_OK) return rc;
+        return dwconv_bwd_data(desc, dy, w, dx, stream);
+    }
+    const size_t need = (size_t)pl.parts * (size_t)g.O * g.K * g.K * sizeof(float);
+    if (!workspace || workspace_bytes < need) return DWCONV_ERR_WORKSPACE;
+    if (misaligned(workspace)) return DWCONV_ERR_ALIGN;
+    hipError_t e = launch_bwd_fused(pl, g, desc->layout, desc->dtype, x, dy, w, dx, (float *)workspace, (hipStream_t)stream);
+    if (e != hipSuccess) return DWCONV_ERR_LAUNCH;
+    e = reduce_partials((const float *)workspace, pl.parts, g.O * g.K * g.K, (float *)dw, (hipStream_t)stream);
+    return e == hipSuccess ? DWCONV_OK : DWCONV_ERR_LAUNCH;
+}
+
 const char *dwconv_variant_name(const dwconv_desc *desc, int pass)
 {
     Geom g;
-    if (validate(desc, &g) != DWCONV_OK || pass < 0 || pass > 2) return "invalid";
+    if (validate(desc, &g) != DWCONV_OK || pass < 0 || pass > 3) return "invalid";
     Plan pl = pass == 0 ? plan_fwd(g, desc->layout, desc->dtype)
             : pass == 1 ? plan_bwd_data(g, desc->layout, desc->dtype)
-                        : plan_bwd_filter(g, desc->layout, desc->dtype);
+            : pass == 2 ? plan_bwd_filter(g, desc->layout, desc->dtype)
+                        : plan_bwd(g, desc->layout, desc->dtype);
     return pl.name;
 }
 

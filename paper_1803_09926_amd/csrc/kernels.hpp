@@ -49,6 +49,10 @@ hipError_t nhwc_k3s2(const Geom &g, int dtype, int V, const void *in, const void
 // filter gradient stage 1; NI = images per block.
 void nhwc_bwd_filter_tiling(const Geom &g, int V, int TH, int NI, int *CT, int *nctiles, int *nowtiles, int *nstrips,
                             int *ngroups);
+// fused backward (input gradient + stage 1 of the filter gradient), 3x3 stride 1 (nhwc_fused.hip); tiling as nhwc_bwd_filter
+bool nhwc_bwd_fused_supported(const Geom &g, int dtype, int V);
+hipError_t nhwc_bwd_fused(const Geom &g, int dtype, int V, const void *x, const void *dy, const void *w, void *dx,
+                          float *ws, int TH, int NI, hipStream_t st);
 hipError_t nhwc_bwd_filter(const Geom &g, int dtype, int V, const void *x, const void *dy, float *ws, int TH, int NI,
                            hipStream_t st);
 

@@ -1,0 +1,210 @@
+// Fused backward pass for NHWC, 3x3, stride 1, pad 1, multiplier 1: the input gradient dx and the
+// stage-1 partial sums of the filter gradient dw from ONE walk over dy and x.  Run separately the
+// two passes read dy twice; fused, the backward pass moves 2|x| + |y| elements instead of
+// 2(|x| + |y|) and is one launch less.
+//
+// Mapping as in the filter-gradient kernel (nhwc.hip): a block is CT channel-vectors x 256/CT
+// columns, walks a strip of rows of NI images; a lane owns V channels of one column.  Step t of
+// the walk takes dy row t (three columns) and x row t-1 (three columns):
+//   input gradient:  dx[r][ow] = sum_{kh,kw} w[kh][kw] dy[r+1-kh][ow+1-kw]; dy row t is tap row
+//     kh = 0, 1, 2 of dx rows t-1, t, t+1, so two rotating accumulators finish dx row t-1 here;
+//   filter gradient: x row r = t-1 meets dy rows r+1-kh (centre column) at tap row kh; the three
+//     live dy rows sit in a small window; only dy rows inside the block's own strip count, while the
+//     input gradient needs the true halo rows: the window entry is masked, the loaded row is not.
+// Loads are unconditional with clamped rows, rows stay as loaded (packed for bf16) until used, and
+// every condition inside the walk is uniform over the block.  Padding columns: zeroed weights for the
+// input gradient, sums dropped after the walk for the filter gradient (as in nhwc.hip).
+#include "kernels.hpp"
+
+namespace dwc {
+
+template <typename T, int V, int PF>
+__global__ __launch_bounds__(256) void k_nhwc_bwd_fused_k3s1(Geom g, const T *__restrict__ x, const T *__restrict__ dy,
+                                                             const T *__restrict__ w, T *__restrict__ dx,
+                                                             float *__restrict__ ws, int CT, int nctiles, int nowtiles,
+                                                             int TH, int nstrips, int NI, unsigned nblocks, int nt)
+{
+    constexpr int K = 3, R = PF + 1;
+    __shared__ float red[4][V][64];
+    unsigned lb = xcd_remap(blockIdx.x, nblocks);
+    const int strip = lb % nstrips; lb /= nstrips;
+    const int owtile = lb % nowtiles; lb /= nowtiles;
+    const int ctile = lb % nctiles; const int ngroup = lb / nctiles;
+
+    const int OWT = 256 / CT;
+    const int tx = threadIdx.x % CT, ty = threadIdx.x / CT;
+    const int Q = g.C / V;
+    const int cq = ctile * CT + tx, ow = owtile * OWT + ty;
+    const bool active = cq < Q && ow < g.W;
+
+    float acc[K][K][V];
+#pragma unroll
+    for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < K; ++kw)
+#pragma unroll
+            for (int v = 0; v < V; ++v) acc[kh][kw][v] = 0.f;
+
+    if (active) {
+        bool colok[K];
+        int coloff[K];
+        float wd[K][K][V];      // wd[kh][j]: weight of dy column ow-1+j in tap row kh of the input gradient (= w[kh][2-j])
+#pragma unroll
+        for (int j = 0; j < K; ++j) {
+            const int iw = ow - 1 + j;
+            colok[j] = iw >= 0 && iw < g.W;
+            coloff[j] = (colok[j] ? iw : ow) * g.C;
+#pragma unroll
+            for (int kh = 0; kh < K; ++kh) {
+                Vec<T, V>::load(w + (kh * K + (2 - j)) * g.C + cq * V, wd[kh][j]);
+#pragma unroll
+                for (int v = 0; v < V; ++v) wd[kh][j][v] = colok[j] ? wd[kh][j][v] : 0.f;
+            }
+        }
+        const int rowlen = g.W * g.C;
+        const int oh0 = strip * TH, oh1 = min(g.H, oh0 + TH);
+        const int n0 = ngroup * NI, n1 = min(g.N, n0 + NI);
+        for (int n = n0; n < n1; ++n) {
+            const T *xin = x + (size_t)n * g.H * rowlen + cq * V;
+            const T *dyin = dy + (size_t)n * g.H * rowlen + cq * V;
+            T *dxout = dx + ((size_t)n * g.H * g.W + ow) * g.C + cq * V;
+
+            RawVec<T, V> dr[R][K], xr[R][K];
+            auto load_rows = [&](int t, RawVec<T, V> (&dd)[K], RawVec<T, V> (&xd)[K]) {
+                const T *dp = dyin + (size_t)min(max(t, 0), g.H - 1) * rowlen;
+                const T *xp = xin + (size_t)min(max(t - 1, 0), g.H - 1) * rowlen;
+#pragma unroll
+                for (int j = 0; j < K; ++j) { dd[j].load(dp + coloff[j]); xd[j].load(xp + coloff[j]); }
+            };
+
+            float A0[V], A1[V], dyw[K][V];
+#pragma unroll
+            for (int v = 0; v < V; ++v) { A0[v] = 0.f; A1[v] = 0.f; }
+#pragma unroll
+            for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+                for (int v = 0; v < V; ++v) dyw[kh][v] = 0.f;
+
+            auto consume = [&](int t, const RawVec<T, V> (&dd)[K], const RawVec<T, V> (&xd)[K]) {
+                const bool dyok = t >= 0 && t < g.H;                 // dy row t exists
+                const bool mine = t >= oh0 && t < oh1;               // ... and belongs to this block's strip
+                const bool xok = t - 1 >= 0 && t - 1 < g.H;          // x row t-1 exists (rows of other strips meet a zeroed window)
+                float d[K][V];
+#pragma unroll
+                for (int j = 0; j < K; ++j) {
+                    dd[j].get(d[j]);
+#pragma unroll
+                    for (int v = 0; v < V; ++v) d[j][v] = dyok ? d[j][v] : 0.f;
+                }
+                // input gradient: dy row t is tap row 0 of dx row t-1, tap row 1 of dx row t, tap row 2 of dx row t+1
+                float out[V];
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    float s0 = A0[v], s1 = A1[v], s2 = 0.f;
+#pragma unroll
+                    for (int j = 0; j < K; ++j) {
+                        s0 = fmaf(wd[0][j][v], d[j][v], s0);
+                        s1 = fmaf(wd[1][j][v], d[j][v], s1);
+                        s2 = fmaf(wd[2][j][v], d[j][v], s2);
+                    }
+                    out[v] = s0; A0[v] = s1; A1[v] = s2;
+                }
+                if (t - 1 >= oh0 && t - 1 < oh1) store_vec<T, V>(dxout + (size_t)(t - 1) * rowlen, out, nt != 0);
+                // filter gradient: x row t-1 meets dy rows t, t-1, t-2 (centre column) at tap rows 0, 1, 2
+#pragma unroll
+                for (int v = 0; v < V; ++v) { dyw[2][v] = dyw[1][v]; dyw[1][v] = dyw[0][v]; dyw[0][v] = mine ? d[1][v] : 0.f; }
+#pragma unroll
+                for (int kw = 0; kw < K; ++kw) {
+                    float xv[V];
+                    xd[kw].get(xv);
+#pragma unroll
+                    for (int v = 0; v < V; ++v) {
+                        const float xx = xok ? xv[v] : 0.f;
+#pragma unroll
+                        for (int kh = 0; kh < K; ++kh) acc[kh][kw][v] = fmaf(dyw[kh][v], xx, acc[kh][kw][v]);
+                    }
+                }
+            };
+
+            // steps t = oh0-1 .. oh1+1: the first brings the halo dy row above the strip, the last two the
+            // halo dy row below it and the x row below the strip's last dy row
+            const int t0 = oh0 - 1, nsteps = (oh1 - oh0) + 3;
+#pragma unroll
+            for (int j = 0; j < PF; ++j) load_rows(t0 + j, dr[j], xr[j]);
+            int i = 0;
+#pragma unroll 1
+            for (; i + R <= nsteps; i += R) {
+#pragma unroll
+                for (int j = 0; j < R; ++j) {
+                    load_rows(t0 + i + j + PF, dr[(j + PF) % R], xr[(j + PF) % R]);
+                    consume(t0 + i + j, dr[j], xr[j]);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < R - 1; ++j)
+                if (i + j < nsteps) consume(t0 + i + j, dr[j], xr[j]);
+        }
+        // taps on columns outside the image accumulated clamped data: drop them
+#pragma unroll
+        for (int kw = 0; kw < K; ++kw)
+            if (!colok[kw]) {
+#pragma unroll
+                for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+                    for (int v = 0; v < V; ++v) acc[kh][kw][v] = 0.f;
+            }
+    }
+
+    // ---- fixed-order block reduction, one tap at a time (as in the filter-gradient kernel) ----
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int part = (ngroup * nstrips + strip) * nowtiles + owtile;
+    float *wsp = ws + (size_t)part * (K * K * g.C);
+#pragma unroll
+    for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < K; ++kw) {
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                float s = wave_sum_strided(acc[kh][kw][v], CT);
+                red[wv][v][lane] = s;
+            }
+            __syncthreads();
+            if (wv == 0 && lane < CT && cq < Q) {
+                float o[V];
+#pragma unroll
+                for (int v = 0; v < V; ++v)
+                    o[v] = (red[0][v][lane] + red[1][v][lane]) + (red[2][v][lane] + red[3][v][lane]);
+#pragma unroll
+                for (int v = 0; v < V; ++v) wsp[(kh * K + kw) * g.C + cq * V + v] = o[v];
+            }
+            __syncthreads();
+        }
+}
+
+bool nhwc_bwd_fused_supported(const Geom &g, int dtype, int V)
+{
+    if (!(g.K == 3 && g.s == 1 && g.p == 1 && g.m == 1)) return false;
+    // bf16 with 8 channels per lane would need more than 256 registers
+    return (dtype == DT_F32 && V == 4) || (dtype == DT_BF16 && V == 4);
+}
+
+// Same tiling function as the filter gradient (nhwc_bwd_filter_tiling); partial sums at [part][kh][kw][c].
+hipError_t nhwc_bwd_fused(const Geom &g, int dtype, int V, const void *x, const void *dy, const void *w, void *dx,
+                          float *ws, int TH, int NI, hipStream_t st)
+{
+    if (!nhwc_bwd_fused_supported(g, dtype, V)) return hipErrorInvalidValue;
+    int CT, nctiles, nowtiles, nstrips, ngroups;
+    nhwc_bwd_filter_tiling(g, V, TH, NI, &CT, &nctiles, &nowtiles, &nstrips, &ngroups);
+    const unsigned nblocks = (unsigned)nctiles * nowtiles * nstrips * ngroups;
+    const int esz = dtype == DT_F32 ? 4 : 2;
+    const int nt = stream_stores("NHWC_FUSED_BWD", (long long)g.N * g.H * g.W * g.C * esz, 0);
+#define GO(T, VV) hipLaunchKernelGGL((k_nhwc_bwd_fused_k3s1<T, VV, 1>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, \
+                                     (const T *)dy, (const T *)w, (T *)dx, ws, CT, nctiles, nowtiles, TH, nstrips, NI, \
+                                     nblocks, nt)
+    if (dtype == DT_F32) GO(float, 4);
+    else GO(bf16_t, 4);
+#undef GO
+    return hipGetLastError();
+}
+
+}  // namespace dwc

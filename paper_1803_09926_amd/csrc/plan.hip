@@ -221,6 +221,24 @@ Plan plan_bwd_filter(const Geom &g, int layout, int dtype)
     return pl;
 }
 
+Plan plan_bwd(const Geom &g, int layout, int dtype)
+{
+    Plan pl = {V_GENERIC, 0, 0, 0, 0, "separate"};
+    if (layout == LAYOUT_NHWC && !getenv("DWCONV_TUNE_NOFUSE")) {
+        const int V = nhwc_vec(g, dtype);
+        if (V && nhwc_bwd_fused_supported(g, dtype, V)) {
+            // tiling of the filter gradient: its block count and partial sums decide
+            const Plan pf = plan_bwd_filter(g, layout, dtype);
+            if (pf.variant == V_NHWC_BWD_FILTER && pf.a == V) {
+                pl = pf;
+                pl.variant = V_NHWC_BWD_FUSED;
+                pl.name = "nhwc_bwd_fused_k3s1";
+            }
+        }
+    }
+    return pl;
+}
+
 hipError_t launch_fwd(const Plan &pl, const Geom &g, int layout, int dtype, const void *x, const void *w, void *y,
                       hipStream_t st)
 {
@@ -261,6 +279,14 @@ hipError_t launch_bwd_filter(const Plan &pl, const Geom &g, int layout, int dtyp
     case V_NCHWS_BWD_FILTER: return nchws_bwd_filter(g, dtype, x, dy, ws, pl.a, pl.c, st);
     default: return generic_bwd_filter(g, layout, dtype, x, dy, ws, pl.parts, st);
     }
+}
+
+hipError_t launch_bwd_fused(const Plan &pl, const Geom &g, int layout, int dtype, const void *x, const void *dy,
+                            const void *w, void *dx, float *ws, hipStream_t st)
+{
+    (void)layout;
+    if (pl.variant != V_NHWC_BWD_FUSED) return hipErrorInvalidValue;
+    return nhwc_bwd_fused(g, dtype, pl.a, x, dy, w, dx, ws, pl.b, pl.c, st);
 }
 
 }  // namespace dwc

@@ -19,6 +19,7 @@ enum Variant {
     V_NCHWS_FWD,        // small planes: forward / backward-data stride 1 (rotated filter)
     V_NCHWS_BWD_DATA_S2,
     V_NCHWS_BWD_FILTER, // a = U, c = NI
+    V_NHWC_BWD_FUSED,   // a = V, b = TH, c = NI (input gradient and filter gradient in one kernel)
 };
 
 struct Plan {
@@ -31,6 +32,8 @@ struct Plan {
 Plan plan_fwd(const Geom &g, int layout, int dtype);
 Plan plan_bwd_data(const Geom &g, int layout, int dtype);
 Plan plan_bwd_filter(const Geom &g, int layout, int dtype);
+// Whole backward pass (dx and dw).  V_GENERIC here means: no fused kernel, run the two passes one after the other.
+Plan plan_bwd(const Geom &g, int layout, int dtype);
 
 hipError_t launch_fwd(const Plan &pl, const Geom &g, int layout, int dtype, const void *x, const void *w, void *y,
                       hipStream_t st);
@@ -38,5 +41,7 @@ hipError_t launch_bwd_data(const Plan &pl, const Geom &g, int layout, int dtype,
                            void *dx, hipStream_t st);
 hipError_t launch_bwd_filter(const Plan &pl, const Geom &g, int layout, int dtype, const void *x, const void *dy,
                              float *ws, hipStream_t st);
+hipError_t launch_bwd_fused(const Plan &pl, const Geom &g, int layout, int dtype, const void *x, const void *dy,
+                            const void *w, void *dx, float *ws, hipStream_t st);
 
 }  // namespace dwc

@@ -69,6 +69,19 @@ def gpu_passes(layer, N, layout, dtype, xt, wt, dyt, stream=None, poison=True):
     return y, dx, dwt
 
 
+def gpu_bwd(layer, N, layout, dtype, xt, wt, dyt, stream=None):
+    """The whole backward pass through dwconv_bwd (fused where a fused kernel exists); outputs pre-filled with NaN."""
+    d = desc_for(layer, N, layout, dtype)
+    xs, ys, ws = shapes(layer, N, layout)
+    tdt = torch.float32 if dtype == wl.F32 else torch.bfloat16
+    dx = torch.full(xs, float("nan"), device="cuda", dtype=tdt)
+    dwt = torch.full(ws, float("nan"), device="cuda", dtype=torch.float32)
+    wsb = torch.full((max(dw.bwd_workspace_bytes(d), 16),), 0xFF, device="cuda", dtype=torch.uint8)
+    dw.bwd(d, xt, dyt, wt, dx, dwt, wsb, stream)
+    torch.cuda.synchronize()
+    return dx, dwt
+
+
 def check_layer_full(layer, N, layout, dtype, seed):
     """Whole-tensor, element-by-element comparison with the oracle (small problems)."""
     x, w, dy = wl.make_inputs(layer, N, layout, dtype, seed)
@@ -79,4 +92,9 @@ def check_layer_full(layer, N, layout, dtype, seed):
     tag = "%s N=%d layout=%d dtype=%d" % (layer.name, N, layout, dtype)
     assert_close(to_host(y), oracle.fwd(x, w, **kw), tol, "fwd " + tag)
     assert_close(to_host(dx), oracle.bwd_data(dy, w, x_shape=x.shape, **kw), tol, "bwd_data " + tag)
-    assert_close(to_host(dwt), oracle.bwd_filter(x, dy, **kw), tolf, "bwd_filter " + tag)
+    ref_dx = oracle.bwd_data(dy, w, x_shape=x.shape, **kw)
+    ref_dw = oracle.bwd_filter(x, dy, **kw)
+    assert_close(to_host(dwt), ref_dw, tolf, "bwd_filter " + tag)
+    dx2, dw2 = gpu_bwd(layer, N, layout, dtype, to_dev(x, dtype), to_dev(w, dtype), to_dev(dy, dtype))
+    assert_close(to_host(dx2), ref_dx, tol, "bwd (dx) " + tag)
+    assert_close(to_host(dw2), ref_dw, tolf, "bwd (dw) " + tag)

@@ -57,7 +57,9 @@ def test_bad_descriptors(field, value, code):
     assert lib.dwconv_fwd(ctypes.byref(d), A, B, Cp, None) == code
     assert lib.dwconv_bwd_data(ctypes.byref(d), A, B, Cp, None) == code
     assert lib.dwconv_bwd_filter(ctypes.byref(d), A, B, Cp, Dp, 1 << 30, None) == code
+    assert lib.dwconv_bwd(ctypes.byref(d), A, B, Cp, Dp, 0x5000, 0x6000, 1 << 30, None) == code
     assert dw.bwd_filter_workspace_bytes(d) == 0
+    assert dw.bwd_workspace_bytes(d) == 0
     assert dw.variant_name(d, 0) == "invalid"
 
 
@@ -129,3 +131,26 @@ def test_generic_fallback_is_selected_for_untuned_shapes():
     assert dw.variant_name(dw.desc(2, 6, 9, 9, 3, 1, 1, 1, dw.NHWC), 0) == "generic"       # C not a multiple of 4
     assert dw.variant_name(dw.desc(2, 8, 9, 9, 7, 1, 3, 1, dw.NCHW), 0) == "generic"       # 7x7
     assert dw.variant_name(dw.desc(2, 8, 9, 9, 3, 3, 1, 1, dw.NHWC), 2) == "generic"       # stride 3
+
+
+def test_whole_backward_entry_point_validates_before_launch():
+    lib = dw.load()
+    for layout in (dw.NCHW, dw.NHWC):
+        d = dw.desc(2, 8, 16, 16, 3, 1, 1, 1, layout)
+        need = dw.bwd_workspace_bytes(d)
+        assert 0 < need <= 64 << 20
+        args = [A, B, Cp, Dp, 0x5000]
+        for i in range(5):                                   # each of x, dy, w, dx, dw NULL in turn
+            a = list(args); a[i] = None
+            assert lib.dwconv_bwd(ctypes.byref(d), *a, 0x6000, need, None) == E_NULL
+        assert lib.dwconv_bwd(ctypes.byref(d), A + 4, B, Cp, Dp, 0x5000, 0x6000, need, None) == E_ALIGN
+        assert lib.dwconv_bwd(ctypes.byref(d), A, B, Cp, Dp, 0x5000, None, need, None) == E_WS
+        assert lib.dwconv_bwd(ctypes.byref(d), A, B, Cp, Dp, 0x5000, 0x6000, need - 1, None) == E_WS
+
+
+def test_whole_backward_variant_names():
+    # fused kernel: NHWC 3x3 stride 1 fp32; everything else runs the two passes
+    assert dw.variant_name(dw.desc(128, 32, 112, 112, 3, 1, 1, 1, dw.NHWC, dw.F32), 3) == "nhwc_bwd_fused_k3s1"
+    assert dw.variant_name(dw.desc(128, 64, 112, 112, 3, 2, 1, 1, dw.NHWC, dw.F32), 3) == "separate"
+    assert dw.variant_name(dw.desc(128, 32, 112, 112, 3, 1, 1, 1, dw.NCHW, dw.F32), 3) == "separate"
+    assert dw.variant_name(dw.desc(2, 6, 9, 9, 3, 1, 1, 1, dw.NHWC, dw.F32), 3) == "separate"

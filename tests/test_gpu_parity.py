@@ -109,7 +109,11 @@ def _sampled_check(layer, N, layout, dtype, seed):
     imgs = sorted({0, N // 2 - 1, N - 1})
     xh = gu.to_host(x[imgs]); dyh = gu.to_host(dy[imgs])
     gu.assert_close(gu.to_host(y[imgs]), oracle.fwd(xh, wh, **kw), tol, "fwd " + tag)
-    gu.assert_close(gu.to_host(dx[imgs]), oracle.bwd_data(dyh, wh, x_shape=xh.shape, **kw), tol, "bwd_data " + tag)
+    ref_dx = oracle.bwd_data(dyh, wh, x_shape=xh.shape, **kw)
+    gu.assert_close(gu.to_host(dx[imgs]), ref_dx, tol, "bwd_data " + tag)
+    # the whole backward pass in one call (fused kernel where there is one) against the same references
+    dx2, dw2 = gu.gpu_bwd(layer, N, layout, dtype, x, w, dy)
+    gu.assert_close(gu.to_host(dx2[imgs]), ref_dx, tol, "bwd (dx) " + tag)
     # bwd_filter: a few input channels (first, one in the middle, last) over the whole batch
     m = layer.mult
     for c in sorted({0, layer.C // 2 + 1 if layer.C > 2 else 0, layer.C - 1}):
@@ -119,7 +123,9 @@ def _sampled_check(layer, N, layout, dtype, seed):
             xc = gu.to_host(x[..., c:c + 1]); dyc = gu.to_host(dy[..., c * m:(c + 1) * m]); got = gu.to_host(dwt[..., c * m:(c + 1) * m])
         ref = oracle.bwd_filter(xc, dyc, **kw)
         gu.assert_close(got, ref, gu.TOL_F32_FILTER, "bwd_filter ch %d %s" % (c, tag))
-    del x, w, dy, y, dx, dwt
+        got2 = gu.to_host(dw2[c * m:(c + 1) * m]) if layout == wl.NCHW else gu.to_host(dw2[..., c * m:(c + 1) * m])
+        gu.assert_close(got2, ref, gu.TOL_F32_FILTER, "bwd (dw) ch %d %s" % (c, tag))
+    del x, w, dy, y, dx, dwt, dx2, dw2
     torch.cuda.empty_cache()
 
 
