@@ -19,7 +19,7 @@ import time
 
 PEAK_HBM_GBS = 8000.0
 METRIC = "ms and HBM GB/s (% of peak) per fwd+bwd of MobileNet-v1 dw stack, batch 128"
-PASS_NAMES = ("fwd", "bwd_data", "bwd_filter")
+PASS_NAMES = ("fwd", "bwd_data", "bwd_filter", "bwd")
 
 
 def parse():
@@ -31,6 +31,9 @@ def parse():
     ap.add_argument("--order", choices=["layer", "train"], default="layer",
                     help="launch order inside a step: layer by layer (fwd, bwd_filter, bwd_data of each), or as "
                          "a training step runs them (all forwards, then the backward passes from the last layer up)")
+    ap.add_argument("--fused-bwd", action="store_true",
+                    help="run the backward pass through dwconv_bwd (one call; a fused kernel where there is one, "
+                         "which reads dy once: its algorithmic bytes are 2|x|+|y| instead of 2(|x|+|y|))")
     ap.add_argument("--side-stream", action="store_true",
                     help="enqueue each layer's filter gradient on a second stream, beside its input gradient")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -41,7 +44,7 @@ def parse():
     return ap.parse_args()
 
 
-def build_ops(dw, wl, cfg, torch, order="layer", side=None):
+def build_ops(dw, wl, cfg, torch, order="layer", side=None, fused_bwd=False):
     """Allocate per-layer buffers and return the list of launches that make one step."""
     import ctypes
     ops = []
@@ -86,17 +89,33 @@ def build_ops(dw, wl, cfg, torch, order="layer", side=None):
 
             # order within a layer: forward, filter gradient, input gradient.  The two backward passes
             # both read dy; run back to back, the second finds much of it in the 256 MB Infinity Cache.
+            wsb = torch.empty(max(dw.bwd_workspace_bytes(d), 16), device="cuda", dtype=torch.uint8) if fused_bwd else ws
+            pwsb, nwsb = ctypes.c_void_p(wsb.data_ptr()), ctypes.c_size_t(wsb.numel())
+
+            def run_bwd(dref=dref, px=px, pdy=pdy, pw=pw, pdx=pdx, pdw=pdw, pwsb=pwsb, nwsb=nwsb, keep=(keep, wsb)):
+                rc = lib.dwconv_bwd(dref, px, pdy, pw, pdx, pdw, pwsb, nwsb, stream)
+                if rc: raise dw.DwconvError(rc, "dwconv_bwd")
+
             f = dict(common, which=0, variant=dw.variant_name(d, 0), run=run_fwd)
             bf = dict(common, which=2, variant=dw.variant_name(d, 2), run=run_bwd_filter, run_side=run_bwd_filter_side)
             bd = dict(common, which=1, variant=dw.variant_name(d, 1), run=run_bwd_data)
-            if order == "layer":
+            if fused_bwd:
+                vname = dw.variant_name(d, 3)
+                # a fused kernel reads x and dy once and writes dx; without one the call runs the two passes
+                bbytes = (2 * layer.x_elems(cfg["N"]) + layer.y_elems(cfg["N"])) * esz if vname != "separate" else 2 * nbytes
+                b = dict(common, which=3, variant=vname, run=run_bwd, bytes=bbytes)
+                if order == "layer":
+                    ops += [f, b]
+                else:
+                    fwd_ops.append(f); bwd_ops.append((b,))
+            elif order == "layer":
                 ops += [f, bf, bd]
             else:
                 fwd_ops.append(f); bwd_ops.append((bf, bd))
         if order == "train":
             ops += fwd_ops
-            for bf, bd in reversed(bwd_ops):
-                ops += [bf, bd]
+            for grp in reversed(bwd_ops):
+                ops += list(grp)
     return ops
 
 
@@ -215,7 +234,7 @@ def main():
         del src, dst
     main_stream = torch.cuda.current_stream()
     side = torch.cuda.Stream() if args.side_stream else None
-    ops = build_ops(dw, wl, cfg, torch, args.order, side)
+    ops = build_ops(dw, wl, cfg, torch, args.order, side, args.fused_bwd)
     step_bytes = sum(op["bytes"] * op["repeat"] for op in ops)
 
     for _ in range(args.warmup):
@@ -236,7 +255,7 @@ def main():
         "vs_baseline": None, "dtype": "f32" if cfg["dtype"] == wl.F32 else "bf16", "data": "synthetic",
         "config": {"workload": cfg["name"], "batch": cfg["N"],
                    "layouts": ["NCHW" if l == wl.NCHW else "NHWC" for l in cfg["layouts"]],
-                   "layers": len(cfg["layers"]), "passes": "fwd+bwd_data+bwd_filter",
+                   "layers": len(cfg["layers"]), "passes": "fwd+bwd(one call)" if args.fused_bwd else "fwd+bwd_data+bwd_filter",
                    "step": "one fwd+bwd of the stack in every listed layout", "launch_order": args.order},
         "pct_of_peak_hbm": round(100.0 * gbs / PEAK_HBM_GBS, 2),
         "algorithmic_GB_per_step": round(step_bytes / 1e9, 4),
@@ -248,7 +267,7 @@ def main():
         by_variant = {}
         for op, ms in zip(ops, kms):
             per_layout.setdefault(op["layout"], {"ms": 0.0, "bytes": 0, "tail_ms": 0.0, "stride2_ms": 0.0,
-                                                 "fwd_ms": 0.0, "bwd_data_ms": 0.0, "bwd_filter_ms": 0.0})
+                                                 "fwd_ms": 0.0, "bwd_data_ms": 0.0, "bwd_filter_ms": 0.0, "bwd_ms": 0.0})
             pl = per_layout[op["layout"]]
             pl["ms"] += ms * op["repeat"]; pl["bytes"] += op["bytes"] * op["repeat"]
             pl[PASS_NAMES[op["which"]] + "_ms"] += ms * op["repeat"]
