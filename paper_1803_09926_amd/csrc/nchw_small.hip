@@ -1,4 +1,4 @@
-// NCHW kernels for small planes (rows of 7, 14 or 28 elements; 3x3 filters, 5x5 at stride 1;
+// NCHW kernels for small planes (rows of 7, 14 or 28 elements, and 4 or 8 for 3x3; 3x3 filters, 5x5 at stride 1;
 // multiplier 1).
 // Rows this short are not whole 16-byte vectors, but consecutive planes are contiguous, so a block
 // takes a run of whole planes as ONE flat range: aligned 16-byte loads into LDS (all of a lane's
@@ -335,7 +335,7 @@ bool nchws_supported(const Geom &g, int pass)
     const bool k5 = g.K == 5 && g.p == 2 && g.s == 1;   // 5x5 stride 1 (backward-data runs the forward kernel with the rotated filter)
     if (!k3 && !k5) return false;
     if (g.K == 5 && g.W == 28) return false;     // 28-wide rows with 25 taps: too many registers per lane
-    if (!(g.W == 7 || g.W == 14 || g.W == 28)) return false;
+    if (!(g.W == 7 || g.W == 14 || g.W == 28 || (g.K == 3 && (g.W == 8 || (g.W == 4 && g.s == 1))))) return false;
     if (g.s == 2 && (g.W % 2 != 0 || g.H % 2 != 0)) return false;
     if (g.Ho > 32 || g.H > 32) return false;
     (void)pass;
@@ -365,6 +365,7 @@ static hipError_t go_fwd(const Geom &g, const void *x, const void *w, void *y, b
                                               (const T *)x, (const T *)w, (T *)y, U, nplanes, nblocks, nt)
 #define PICK(KK, SS, WW) if (g.K == KK && g.s == SS && g.W == WW) { if (flip) GO(KK, SS, WW, true); else GO(KK, SS, WW, false); return hipGetLastError(); }
     PICK(3, 1, 7) PICK(3, 1, 14) PICK(3, 1, 28) PICK(3, 2, 14) PICK(3, 2, 28) PICK(5, 1, 7) PICK(5, 1, 14)
+    PICK(3, 1, 4) PICK(3, 1, 8) PICK(3, 2, 8)
 #undef PICK
 #undef GO
     return hipErrorInvalidValue;
@@ -390,6 +391,7 @@ static hipError_t go_bwd_data_s2(const Geom &g, const void *dy, const void *w, v
                                   (const T *)w, (T *)dx, U, nplanes, nblocks, nt)
     if (g.W == 14) GO(14);
     else if (g.W == 28) GO(28);
+    else if (g.W == 8) GO(8);
     else return hipErrorInvalidValue;
 #undef GO
     return hipGetLastError();
@@ -438,6 +440,9 @@ static hipError_t go_bwd_filter(const Geom &g, const void *x, const void *dy, fl
     else if (g.K == 3 && g.s == 2 && g.W == 28) GO(3, 2, 28);
     else if (g.K == 5 && g.s == 1 && g.W == 7) GO(5, 1, 7);
     else if (g.K == 5 && g.s == 1 && g.W == 14) GO(5, 1, 14);
+    else if (g.K == 3 && g.s == 1 && g.W == 4) GO(3, 1, 4);
+    else if (g.K == 3 && g.s == 1 && g.W == 8) GO(3, 1, 8);
+    else if (g.K == 3 && g.s == 2 && g.W == 8) GO(3, 2, 8);
     else return hipErrorInvalidValue;
 #undef GO
     return hipGetLastError();

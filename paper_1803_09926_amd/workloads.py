@@ -92,8 +92,25 @@ def mobilenet_5x5() -> Tuple[Layer, ...]:
     return tuple(replace(l, name=l.name + "_k5", K=5, pad=2) for l in MOBILENET_V1 if l.stride == 1)
 
 
+def mobilenet_variant(width: float = 1.0, resolution: int = 224, shallow: bool = False) -> Tuple[Layer, ...]:
+    """Depthwise layers of the MobileNet variants of the paper's Table V: channels scaled by `width`
+    (0.75 -> 24, 48, 96, ...; 0.5 -> 16, 32, ...), input resolution 224 or 128 (first depthwise layer
+    at resolution/2), `shallow` drops the five 14x14x512 layers.  Shapes only."""
+    out = []
+    for i, l in enumerate(MOBILENET_V1, 1):
+        if shallow and 7 <= i <= 11:
+            continue
+        C = int(round(l.C * width))
+        H = l.H * resolution // 224
+        out.append(Layer("mobilenet_w%g_r%d_dw%02d_c%d_h%d_s%d" % (width, resolution, i, C, H, l.stride),
+                         C, H, H, 3, l.stride, 1, 1))
+    return tuple(out)
+
+
 def config(index: int) -> Dict:
-    """The five benchmark configurations, as dicts: N, layouts, dtype, layers [(Layer, repeat)]."""
+    """The benchmark configurations, as dicts: N, layouts, dtype, layers [(Layer, repeat)].
+    0..4: the five configurations of the benchmark spec; 5: the MobileNet variant shapes (width 0.75, width 0.5 at
+    resolution 128), as a second workload."""
     if index == 0:
         return dict(name="single_3x3_n8_c32_h112_f32_nchw", N=8, layouts=(NCHW,), dtype=F32,
                     layers=[(Layer("single_c32_h112", 32, 112, 112), 1)])
@@ -109,7 +126,11 @@ def config(index: int) -> Dict:
     if index == 4:
         return dict(name="mobilenet_v1_dw_b256_bf16", N=256, layouts=(NHWC, NCHW), dtype=BF16,
                     layers=[(l, 1) for l in MOBILENET_V1] + [(l, 1) for l in mobilenet_5x5()])
-    raise ValueError("config index must be 0..4")
+    if index == 5:
+        return dict(name="mobilenet_variants_b128_f32", N=128, layouts=(NCHW, NHWC), dtype=F32,
+                    layers=[(l, 1) for l in mobilenet_variant(0.75, 224)] +
+                           [(l, 1) for l in mobilenet_variant(0.5, 128)])
+    raise ValueError("config index must be 0..5")
 
 
 def round_to_bf16(a: np.ndarray) -> np.ndarray:

@@ -115,16 +115,20 @@ def test_workspace_is_bounded_for_every_benchmark_layer():
 
 
 def test_benchmark_layers_get_tuned_variants():
-    """No layer of the five benchmark configurations may fall back to the generic kernels."""
+    """No layer of the benchmark configurations (the five of the task and the MobileNet variant shapes) may
+    fall back to the generic kernels, and none of the variant shapes to the slow LDS-tile kernels."""
     from paper_1803_09926_amd import workloads as wl
-    for ci in range(5):
+    for ci in range(6):
         cfg = wl.config(ci)
         for layer, _ in cfg["layers"]:
             for layout in cfg["layouts"]:
                 d = dw.desc(cfg["N"], layer.C, layer.H, layer.W, layer.K, layer.stride, layer.pad, layer.mult,
                             layout, cfg["dtype"])
                 for which in range(3):
-                    assert dw.variant_name(d, which) != "generic", (ci, layer.name, layout, which)
+                    name = dw.variant_name(d, which)
+                    assert name != "generic", (ci, layer.name, layout, which)
+                    if ci == 5:
+                        assert not name.startswith("nchw_tile"), (ci, layer.name, layout, which, name)
 
 
 def test_generic_fallback_is_selected_for_untuned_shapes():

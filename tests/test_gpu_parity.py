@@ -58,6 +58,13 @@ AWKWARD = [
     (2, Layer("k5_tail7", 32, 7, 7, 5, 1, 2)),
     (2, Layer("k5_56", 8, 56, 56, 5, 1, 2)),
     (2, Layer("k5_c6", 6, 12, 12, 5, 1, 2)),
+    # MobileNet at resolution 128 ends in 8x8 and 4x4 planes
+    (5, Layer("r128_tail8", 40, 8, 8)),
+    (5, Layer("r128_tail8_s2", 40, 8, 8, 3, 2, 1)),
+    (5, Layer("r128_tail4", 72, 4, 4)),
+    (3, Layer("r128_16", 24, 16, 16)),
+    (3, Layer("r128_16_s2", 24, 16, 16, 3, 2, 1)),
+    (2, Layer("w075_c24", 24, 28, 28)),
     (2, Layer("m2_56", 8, 56, 56, 3, 1, 1, 2)),
     # NCHW whole-line write-out: short last strip, strip taller than the image, partly filled last block,
     # and heights that rule it out (not a multiple of the row group)
@@ -129,7 +136,7 @@ def _sampled_check(layer, N, layout, dtype, seed):
     torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("ci", [1, 2, 3, 4])
+@pytest.mark.parametrize("ci", [1, 2, 3, 4, 5])
 def test_benchmark_configs_full_size_sampled(gpu_lib, ci):
     cfg = wl.config(ci)
     for li, layer in enumerate(_distinct_layers(cfg)):
