@@ -145,6 +145,16 @@ def test_benchmark_configs_full_size_sampled(gpu_lib, ci):
             _sampled_check(layer, cfg["N"], layout, cfg["dtype"], seed=1000 * ci + li)
 
 
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_tensors_just_under_the_element_limit(gpu_lib, layout):
+    """x and y with 2 147 024 896 elements each (the library rejects 2^31 and more): every 32-bit index
+    in the kernels is at its largest.  Oracle on sampled images / channels as for the benchmark sizes."""
+    layer = Layer("near_max_c64_h724", 64, 724, 724)
+    assert layer.x_elems(64) < 2 ** 31 <= layer.x_elems(64) + 64 * 724 * 724
+    print("near-max", layout, flush=True)
+    _sampled_check(layer, 64, layout, wl.F32, seed=4242 + layout)
+
+
 def test_bwd_filter_is_bit_reproducible(gpu_lib):
     for layout in LAYOUTS:
         for layer, N in [(wl.MOBILENET_V1[0], 16), (wl.MOBILENET_V1[5], 16), (wl.MOBILENET_V1[12], 32)]:
