@@ -185,28 +185,33 @@ def stored_traffic(workload, kernel_key):
 
 
 def cpu_baseline(wl, cfg):
-    """The CPU oracle, as it stands, on a batch-reduced sample of the same workload."""
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: every layer, all three passes,
+    every listed layout, batch capped at 128 (about ten seconds of oracle time on 16 threads)."""
     import numpy as np
     import oracle
     cores = min(oracle.threads_available(), os.cpu_count() or 1)
-    Ns = 32
-    layout = cfg["layouts"][-1]
+    Ns = min(cfg["N"], 128)
     total_bytes, total_s = 0, 0.0
     esz = 4 if cfg["dtype"] == wl.F32 else 2
-    for li, (layer, repeat) in enumerate(cfg["layers"]):
-        x, w, dy = wl.make_inputs(layer, Ns, layout, cfg["dtype"], seed=li)
-        x64, w64, dy64 = x.astype(np.float64), w.astype(np.float64), dy.astype(np.float64)
-        kw = dict(K=layer.K, stride=layer.stride, pad=layer.pad, mult=layer.mult, layout=layout, nthreads=cores)
-        t0 = time.perf_counter()
-        oracle.fwd(x64, w64, **kw)
-        oracle.bwd_data(dy64, w64, x_shape=x64.shape, **kw)
-        oracle.bwd_filter(x64, dy64, **kw)
-        total_s += (time.perf_counter() - t0) * repeat
-        total_bytes += 3 * layer.pass_bytes(Ns, esz) * repeat
+    for layout in cfg["layouts"]:
+        for li, (layer, repeat) in enumerate(cfg["layers"]):
+            x, w, dy = wl.make_inputs(layer, Ns, layout, cfg["dtype"], seed=li)
+            x64, w64, dy64 = x.astype(np.float64), w.astype(np.float64), dy.astype(np.float64)
+            del x, dy
+            kw = dict(K=layer.K, stride=layer.stride, pad=layer.pad, mult=layer.mult, layout=layout, nthreads=cores)
+            t0 = time.perf_counter()
+            oracle.fwd(x64, w64, **kw)
+            oracle.bwd_data(dy64, w64, x_shape=x64.shape, **kw)
+            oracle.bwd_filter(x64, dy64, **kw)
+            total_s += (time.perf_counter() - t0) * repeat
+            total_bytes += 3 * layer.pass_bytes(Ns, esz) * repeat
+            del x64, dy64
     return dict(value=total_bytes / total_s / 1e9, unit="GB/s", cores=cores, kind="oracle",
-                sample="all layers of the workload, all three passes, batch reduced to %d, %s, fp64 loop nests, "
-                       "%d OpenMP threads; algorithmic bytes counted at the workload's element size" %
-                       (Ns, "NCHW" if layout == wl.NCHW else "NHWC", cores),
+                sample="all layers of the workload, all three passes, %s, batch %d%s, fp64 loop nests, %d OpenMP "
+                       "threads; timed: the oracle calls only (not input generation); algorithmic bytes counted at "
+                       "the workload's element size" %
+                       ("+".join("NCHW" if l == wl.NCHW else "NHWC" for l in cfg["layouts"]), Ns,
+                        "" if Ns == cfg["N"] else " (reduced from %d)" % cfg["N"], cores),
                 seconds=total_s)
 
 
