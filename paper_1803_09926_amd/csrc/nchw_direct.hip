@@ -21,7 +21,6 @@ static int row_group(int W, int esz)
     int rs = 1;
     while (rs <= 4 && (rs * W * esz) % 128 != 0) rs <<= 1;
     if (rs == 8) rs = 4;
-    if (const char *e = getenv("DWCONV_TUNE_RSF")) { const int v = atoi(e); if (rs >= 2 && rs <= 4 && (v == 2 || v == 4)) rs = v; }
     return (rs == 2 || rs == 4) ? rs : 0;
 }
 
@@ -1183,7 +1182,7 @@ int nchwd_vec(const Geom &g, int dtype, int pass)
         // forward: 16-byte output vectors when the whole-line write-out applies; otherwise the lane's
         // 2V input columns are one 16-byte vector
         const int esz = dtype == DT_F32 ? 4 : 2, rs = row_group(g.Wo, esz);
-        if (rs && g.Ho % rs == 0 && wv % (16 / esz) == 0 && !getenv("DWCONV_TUNE_VF2")) return 16 / esz;
+        if (rs && g.Ho % rs == 0 && wv % (16 / esz) == 0) return 16 / esz;
         if (dtype == DT_F32) return wv % 2 == 0 ? 2 : 0;
         return wv % 4 == 0 ? 4 : 0;
     }
@@ -1318,8 +1317,7 @@ void nchwd_bwd_filter_tiling(const Geom &g, int V, int TH, int *nsg_out, int *ns
     if (nsg == 0) { *rounds = 1; *parts = 0; return; }
     const int nitems = g.N * *nstrips;
     // enough blocks for ~8 per CU over the O channels
-    int want_blocks = 2048;
-    if (const char *e = getenv("DWCONV_TUNE_WB")) { const int v = atoi(e); if (v > 0) want_blocks = v; }
+    const int want_blocks = 2048;
     int want_parts = (want_blocks + g.O - 1) / g.O;
     if (want_parts < 1) want_parts = 1;
     int r = nitems / (nsg * want_parts);

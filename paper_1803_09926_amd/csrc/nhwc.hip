@@ -638,7 +638,6 @@ hipError_t nhwc_s1(const Geom &g, int dtype, int V, const void *x, const void *w
     } else {
         TRY(bf16_t, 8, 3, 1); TRY(bf16_t, 8, 3, 2); TRY(bf16_t, 8, 3, 3);
         TRY(bf16_t, 4, 3, 1); TRY(bf16_t, 4, 3, 2); TRY(bf16_t, 4, 3, 3);
-        TRY(bf16_t, 4, 5, 1); TRY(bf16_t, 4, 5, 2);
         TRY(bf16_t, 2, 5, 1); TRY(bf16_t, 2, 5, 2);
     }
 #undef TRY
@@ -676,11 +675,9 @@ void nhwc_bwd_filter_tiling(const Geom &g, int V, int TH, int NI, int *CT, int *
                             int *ngroups)
 {
     const int Q = g.O / V;
-    // Lanes of a block: CT channel-vectors x 256/CT columns.  Narrow images take all their columns
-    // into one block (fewer, longer partial sums); a lane row of 16 vectors still reads 256 contiguous
-    // bytes per pixel.
-    int cap = 64;
-    if (const char *e = getenv("DWCONV_TUNE_CT")) { const int v = atoi(e); if (v == 8 || v == 16 || v == 32 || v == 64) cap = v; }
+    // Lanes of a block: CT channel-vectors x 256/CT columns, up to 64 vectors (1 KB of a pixel) wide;
+    // narrower channel tiles with more columns measured slower.
+    const int cap = 64;
     int ct = 1;
     while (ct < Q && ct < cap) ct <<= 1;
     *CT = ct;
@@ -710,15 +707,6 @@ hipError_t nhwc_bwd_filter(const Geom &g, int dtype, int V, const void *x, const
     }
 #undef GOM2
     if (dtype == DT_F32) {
-        int pfw = 2;
-        if (const char *e = getenv("DWCONV_TUNE_PFW")) pfw = atoi(e);
-#define GOPF(PP) hipLaunchKernelGGL((k_nhwc_bwd_filter<float, 4, 3, 1, PP, 1>), dim3(nblocks), dim3(256), 0, st, g, \
-                                    (const float *)x, (const float *)dy, ws, CT, nctiles, nowtiles, TH, nstrips, NI, nblocks)
-        if (g.K == 3 && g.s == 1 && pfw == 3) GOPF(3);
-        else if (g.K == 3 && g.s == 1 && pfw == 4) GOPF(4);
-        else if (g.K == 3 && g.s == 1 && pfw == 6) GOPF(6);
-        else
-#undef GOPF
         if (g.K == 3 && g.s == 1) GO(float, 4, 3, 1);
         else if (g.K == 3 && g.s == 2) GO(float, 4, 3, 2);
         else if (g.K == 5 && g.s == 1) GO(float, 4, 5, 1);
@@ -729,7 +717,6 @@ hipError_t nhwc_bwd_filter(const Geom &g, int dtype, int V, const void *x, const
         else if (g.K == 3 && g.s == 2 && V == 8) GO(bf16_t, 8, 3, 2);
         else if (g.K == 3 && g.s == 2) GO(bf16_t, 4, 3, 2);
         else if (g.K == 5 && g.s == 1 && V == 2) GO(bf16_t, 2, 5, 1);
-        else if (g.K == 5 && g.s == 1) GO(bf16_t, 4, 5, 1);
         else return hipErrorInvalidValue;
     }
 #undef GO

@@ -25,9 +25,9 @@ static int nhwc_vec(const Geom &g, int dtype)
     if (g.m == 2) { if (!(g.K == 3 && g.s == 1 && g.p == 1)) return 0; }
     else if (g.m != 1) return 0;
     if (dtype == DT_F32) return g.O % 4 == 0 ? 4 : 0;
-    if (g.K == 5 && tune("DWCONV_TUNE_V5", 2) == 2) return g.O % 2 == 0 ? 2 : 0;   // 2 channels per lane: 110 registers instead of 208, 1.25x faster
-    if (g.K == 5) return g.O % 4 == 0 ? 4 : 0;   // 25 taps x 8 channels would not fit in registers
-    if (tune("DWCONV_TUNE_VB", 8) == 4) return g.O % 4 == 0 ? 4 : 0;
+    // 5x5: 25 taps x 8 channels would not fit in registers; 2 channels per lane take 110 registers
+    // instead of the 208 of 4 channels and measured 1.25x faster
+    if (g.K == 5) return g.O % 2 == 0 ? 2 : 0;
     return g.O % 8 == 0 ? 8 : (g.O % 4 == 0 ? 4 : 0);
 }
 
