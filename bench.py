@@ -184,6 +184,27 @@ def stored_traffic(workload, kernel_key):
     return None
 
 
+def copy_ceiling(torch):
+    """What a plain device-to-device copy reaches on this machine, as the achievable ceiling beside the 8 TB/s
+    peak: 205.5 MB (the first layer's input at batch 128) copied between six rotating buffer pairs, so every
+    copy starts cold like the benchmark's launches; bytes read + bytes written over the mean time of 24 copies."""
+    n = 205520896 // 4
+    bufs = [(torch.zeros(n, device="cuda"), torch.empty(n, device="cuda")) for _ in range(6)]
+    for a, b in bufs:
+        b.copy_(a)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 24
+    e0.record()
+    for i in range(reps):
+        a, b = bufs[i % len(bufs)]
+        b.copy_(a)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    return {"GBps": round(2 * n * 4 / ms / 1e6, 1), "bytes_per_copy": 2 * n * 4, "what": "hipMemcpy device-to-device, cold, back to back"}
+
+
 def cpu_baseline(wl, cfg):
     """The CPU oracle, as it stands, on a bounded sample of the same workload: every layer, all three passes,
     every listed layout, batch capped at 128 (about ten seconds of oracle time on 16 threads)."""
@@ -206,7 +227,17 @@ def cpu_baseline(wl, cfg):
             total_s += (time.perf_counter() - t0) * repeat
             total_bytes += 3 * layer.pass_bytes(Ns, esz) * repeat
             del x64, dy64
+    # one thread, on one mid-sized layer (the oracle is the same loop nest; only the outer loop is split)
+    mid = cfg["layers"][len(cfg["layers"]) // 2][0]
+    Nm = min(cfg["N"], 32)
+    x, w, dy = wl.make_inputs(mid, Nm, cfg["layouts"][-1], cfg["dtype"], seed=99)
+    x64, w64, dy64 = x.astype(np.float64), w.astype(np.float64), dy.astype(np.float64)
+    kw = dict(K=mid.K, stride=mid.stride, pad=mid.pad, mult=mid.mult, layout=cfg["layouts"][-1], nthreads=1)
+    t0 = time.perf_counter()
+    oracle.fwd(x64, w64, **kw); oracle.bwd_data(dy64, w64, x_shape=x64.shape, **kw); oracle.bwd_filter(x64, dy64, **kw)
+    single = 3 * mid.pass_bytes(Nm, esz) / (time.perf_counter() - t0) / 1e9
     return dict(value=total_bytes / total_s / 1e9, unit="GB/s", cores=cores, kind="oracle",
+                single_thread_GBps=round(single, 3), single_thread_sample="%s, batch %d, three passes" % (mid.name, Nm),
                 sample="all layers of the workload, all three passes, %s, batch %d%s, fp64 loop nests, %d OpenMP "
                        "threads; timed: the oracle calls only (not input generation); algorithmic bytes counted at "
                        "the workload's element size" %
@@ -304,6 +335,10 @@ def main():
                       v["bytes"] / v["ms"] / 1e6), file=sys.stderr)
             out["per_op"] = [[op["layer"], op["layout"], PASS_NAMES[op["which"]], op["variant"], round(ms, 4)]
                              for op, ms in zip(ops, kms)]
+
+    if not args.no_kernel_timing:
+        out["copy_ceiling"] = copy_ceiling(torch)
+        out["copy_ceiling"]["value_over_copy"] = round(gbs / out["copy_ceiling"]["GBps"], 3)
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, cfg)
