@@ -48,7 +48,11 @@ static int nhwc_pf(const Geom &g, int dtype)
 static int pick_th(int rows, int stride)
 {
     const int target = stride == 1 ? tune("DWCONV_TUNE_TH1", 14) : tune("DWCONV_TUNE_TH2", 7);
-    const int th = rows < target ? rows : target;
+    // balanced strips: the number of strips that brings their height closest to the target, then equal
+    // heights (19 rows are one strip of 19, not 14 + 5; 37 rows are 13 + 13 + 11)
+    int nstrips = (rows + target / 2) / target;
+    if (nstrips < 1) nstrips = 1;
+    const int th = ceil_div(rows, nstrips);
     return tune("DWCONV_TUNE_TH", th);
 }
 
