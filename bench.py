@@ -54,8 +54,26 @@ def build_ops(dw, wl, cfg, torch, order="layer", side=None, fused_bwd=False):
     esz = 4 if cfg["dtype"] == wl.F32 else 2
     for layout in cfg["layouts"]:
         fwd_ops, bwd_ops = [], []
+        # A layer that occurs `repeat` times in the stack gets several buffer sets, used in turn, so that at
+        # least ~640 MB (more than the 256 MB Infinity Cache) is touched before a set comes round again: every
+        # launch starts cold, as it does for the layers that occur once.
+        expanded = []
         for li, (layer, repeat) in enumerate(cfg["layers"]):
-            x, w, dy = wl.make_inputs_device(layer, cfg["N"], layout, cfg["dtype"], seed=1000 * 7 + li)
+            set_bytes = 2 * layer.pass_bytes(cfg["N"], esz)          # x, dx, y, dy
+            nsets = max(1, min(repeat, -(-(640 << 20) // set_bytes)))
+            expanded += [(li, layer, rep % nsets, rep < nsets) for rep in range(repeat)]
+        made = {}
+        for li, layer, si, fresh in expanded:
+            repeat = 1
+            if not fresh:
+                f, bf, bd, b = made[(li, si)]
+                if fused_bwd:
+                    if order == "layer": ops += [f, b]
+                    else: fwd_ops.append(f); bwd_ops.append((b,))
+                elif order == "layer": ops += [f, bf, bd]
+                else: fwd_ops.append(f); bwd_ops.append((bf, bd))
+                continue
+            x, w, dy = wl.make_inputs_device(layer, cfg["N"], layout, cfg["dtype"], seed=1000 * 7 + li + 131 * si)
             d = dw.desc(cfg["N"], layer.C, layer.H, layer.W, layer.K, layer.stride, layer.pad, layer.mult,
                         layout, cfg["dtype"])
             y = torch.empty_like(dy); dx = torch.empty_like(x)
@@ -99,6 +117,7 @@ def build_ops(dw, wl, cfg, torch, order="layer", side=None, fused_bwd=False):
             f = dict(common, which=0, variant=dw.variant_name(d, 0), run=run_fwd)
             bf = dict(common, which=2, variant=dw.variant_name(d, 2), run=run_bwd_filter, run_side=run_bwd_filter_side)
             bd = dict(common, which=1, variant=dw.variant_name(d, 1), run=run_bwd_data)
+            b = None
             if fused_bwd:
                 vname = dw.variant_name(d, 3)
                 # a fused kernel reads x and dy once and writes dx; without one the call runs the two passes
@@ -112,6 +131,7 @@ def build_ops(dw, wl, cfg, torch, order="layer", side=None, fused_bwd=False):
                 ops += [f, bf, bd]
             else:
                 fwd_ops.append(f); bwd_ops.append((bf, bd))
+            made[(li, si)] = (f, bf, bd, b)
         if order == "train":
             ops += fwd_ops
             for grp in reversed(bwd_ops):
