@@ -65,6 +65,11 @@ AWKWARD = [
     (3, Layer("r128_16", 24, 16, 16)),
     (3, Layer("r128_16_s2", 24, 16, 16, 3, 2, 1)),
     (2, Layer("w075_c24", 24, 28, 28)),
+    # rows wider than a block of lanes, and tall narrow maps
+    (1, Layer("wide_w1100", 4, 5, 1100)),
+    (1, Layer("wide_w1100_s2", 4, 6, 1100, 3, 2, 1)),
+    (1, Layer("tall_h300_w4", 8, 300, 4)),
+    (1, Layer("tall_h301_w8_s2", 8, 301, 8, 3, 2, 1)),
     (2, Layer("m2_56", 8, 56, 56, 3, 1, 1, 2)),
     # NCHW whole-line write-out: short last strip, strip taller than the image, partly filled last block,
     # and heights that rule it out (not a multiple of the row group)
