@@ -40,105 +40,6 @@ __device__ __forceinline__ Lane lane_of(unsigned nblocks, int ncols, int nstrips
 }
 
 // ---------------------------------------------------------------------------------------------
-// Forward, stride 1, "same" padding (K odd, pad (K-1)/2), any multiplier; FLIP = filter rotated
-// by 180 degrees = backward-data of the same layer (multiplier 1).
-// ---------------------------------------------------------------------------------------------
-template <typename T, int V, int K, int PF, bool FLIP>
-__global__ __launch_bounds__(256) void k_nchwd_s1(Geom g, const T *__restrict__ x, const T *__restrict__ w,
-                                                  T *__restrict__ y, int TH, int nstrips, unsigned nblocks, int nt)
-{
-    constexpr int P = (K - 1) / 2;
-    constexpr int NW = V + 2 * P;       // window: P left neighbours, V own columns, P right neighbours
-    constexpr int R = PF + 1;
-    const int W4 = g.W / V;
-    const Lane ln = lane_of(nblocks, W4, nstrips, g.N * g.O);
-    if (!ln.valid) return;
-    const int n = ln.plane / g.O, o = ln.plane - n * g.O;
-    const int plane_in = n * g.C + o / g.m;
-
-    float wr[K][K];
-#pragma unroll
-    for (int kh = 0; kh < K; ++kh)
-#pragma unroll
-        for (int kw = 0; kw < K; ++kw) wr[kh][kw] = ldf(w + (o * K + (FLIP ? K - 1 - kh : kh)) * K + (FLIP ? K - 1 - kw : kw));
-
-    const bool has_left = ln.c4 > 0, has_right = ln.c4 < W4 - 1;
-    const T *xin = x + (size_t)plane_in * g.H * g.W + ln.c4 * V;
-    T *yout = y + (size_t)ln.plane * g.H * g.W + ln.c4 * V;
-    const int oh0 = ln.strip * TH, oh1 = min(g.H, oh0 + TH);
-
-    // neighbour offsets, clamped into the lane's own vector when they fall outside the row
-    int loff[P > 0 ? P : 1], roff[P > 0 ? P : 1];
-#pragma unroll
-    for (int i = 0; i < P; ++i) { loff[i] = has_left ? -(P - i) : 0; roff[i] = has_right ? V + i : V - 1; }
-
-    // The ring holds raw loads (clamped addresses); padding is applied when a row is consumed, so
-    // nothing waits on a load until then.  Every lane walks the same number of rows (TH + 2P):
-    // lanes of the image's last, shorter strip run past it with their stores masked.
-    float ring[R][NW];
-    auto load_row = [&](int r, float (&dst)[NW]) {
-        const T *rp = xin + (size_t)min(max(r, 0), g.H - 1) * g.W;
-        float mid[V];
-        Vec<T, V>::load(rp, mid);
-#pragma unroll
-        for (int i = 0; i < P; ++i) { dst[i] = ldf(rp + loff[i]); dst[P + V + i] = ldf(rp + roff[i]); }
-#pragma unroll
-        for (int v = 0; v < V; ++v) dst[P + v] = mid[v];
-    };
-
-    float acc[K - 1 > 0 ? K - 1 : 1][V];
-#pragma unroll
-    for (int j = 0; j < K - 1; ++j)
-#pragma unroll
-        for (int v = 0; v < V; ++v) acc[j][v] = 0.f;
-
-    auto consume = [&](int r, const float (&raw)[NW]) {
-        const bool rowok = r >= 0 && r < g.H;
-        float cur[NW];
-#pragma unroll
-        for (int i = 0; i < NW; ++i) {
-            const bool ok = rowok && (i < P ? has_left : (i >= P + V ? has_right : true));
-            cur[i] = ok ? raw[i] : 0.f;
-        }
-        float out[V];
-#pragma unroll
-        for (int v = 0; v < V; ++v) {
-            float s = (K > 1) ? acc[0][v] : 0.f;
-#pragma unroll
-            for (int kw = 0; kw < K; ++kw) s = fmaf(wr[K - 1][kw], cur[v + kw], s);
-            out[v] = s;
-        }
-#pragma unroll
-        for (int jj = 0; jj < K - 1; ++jj)
-#pragma unroll
-            for (int v = 0; v < V; ++v) {
-                float s = (jj + 1 < K - 1) ? acc[jj + 1][v] : 0.f;
-#pragma unroll
-                for (int kw = 0; kw < K; ++kw) s = fmaf(wr[K - 2 - jj][kw], cur[v + kw], s);
-                acc[jj][v] = s;
-            }
-        const int oh = r - P;
-        if (oh >= oh0 && oh < oh1) store_vec<T, V>(yout + (size_t)oh * g.W, out, nt != 0);
-    };
-
-    const int r0 = oh0 - P, nrows = TH + 2 * P;
-#pragma unroll
-    for (int j = 0; j < PF; ++j) load_row(r0 + j, ring[j]);
-    int i = 0;
-#pragma unroll 1
-    for (; i + R <= nrows; i += R) {
-#pragma unroll
-        for (int j = 0; j < R; ++j) {
-            load_row(r0 + i + j + PF, ring[(j + PF) % R]);
-            consume(r0 + i + j, ring[j]);
-        }
-    }
-#pragma unroll
-    for (int j = 0; j < R - 1; ++j)
-        if (i + j < nrows) consume(r0 + i + j, ring[j]);
-}
-
-// ---------------------------------------------------------------------------------------------
 // Whole-line write-out through LDS.  An output row of a plane is not a whole number of 128-byte
 // lines, but RS consecutive rows are (RS = 2 for rows of 448 bytes, 4 for 224), and they are
 // contiguous in memory.  Each lane parks the 16-byte vectors it produces for RS successive rows of
@@ -210,16 +111,25 @@ __device__ __forceinline__ u4v_t pack16(const float (&r)[16 / sizeof(T)])
     return pk;
 }
 
-// Stride-1 walk of k_nchwd_s1 with the whole-line write-out.
+// ---------------------------------------------------------------------------------------------
+// Forward, stride 1, "same" padding (K odd, pad (K-1)/2), any multiplier; FLIP = filter rotated
+// by 180 degrees = backward-data of the same layer (multiplier 1).
+// A lane owns V adjacent columns and walks TH + 2P input rows with K-1 rotating accumulators; the
+// ring holds raw loads (clamped addresses), padding is applied when a row is consumed, and every
+// lane walks the same number of rows (lanes of a shorter last strip, and lanes past the last plane,
+// run on with their stores masked).
+// RS > 0: whole-line write-out of RS-row groups (needs 16-byte vectors, TH % RS == 0, H % RS == 0);
+// RS == 0: each lane stores its vector directly (streamed if nt).
+// ---------------------------------------------------------------------------------------------
 template <typename T, int V, int K, int PF, bool FLIP, int RS>
-__global__ __launch_bounds__(256) void k_nchwd_s1_lines(Geom g, const T *__restrict__ x, const T *__restrict__ w,
-                                                        T *__restrict__ y, int TH, int nstrips, unsigned nblocks)
+__global__ __launch_bounds__(256) void k_nchwd_s1(Geom g, const T *__restrict__ x, const T *__restrict__ w,
+                                                  T *__restrict__ y, int TH, int nstrips, unsigned nblocks, int nt)
 {
-    static_assert(sizeof(T) * V == 16, "one 16-byte vector per lane and row");
+    static_assert(RS == 0 || sizeof(T) * V == 16, "whole-line write-out: one 16-byte vector per lane and row");
     constexpr int P = (K - 1) / 2;
     constexpr int NW = V + 2 * P;
     constexpr int R = PF + 1;
-    __shared__ u4v_t stage[2][RS * 256];
+    __shared__ u4v_t stage[2][RS > 0 ? RS * 256 : 1];
     const int W4 = g.W / V;
     const int nplanes = g.N * g.O;
     const unsigned lb = xcd_remap(blockIdx.x, nblocks);
@@ -228,7 +138,8 @@ __global__ __launch_bounds__(256) void k_nchwd_s1_lines(Geom g, const T *__restr
     const int c4 = f - ps * W4;
     int plane = ps / (unsigned)nstrips;
     const int strip = ps - plane * nstrips;
-    if (plane >= nplanes) plane = nplanes - 1;      // lanes past the end compute on the last plane; nothing of theirs is stored
+    const bool valid = plane < nplanes;
+    if (!valid) plane = nplanes - 1;      // lanes past the end compute on the last plane; nothing of theirs is stored
     const int n = plane / g.O, o = plane - n * g.O;
     const int plane_in = n * g.C + o / g.m;
 
@@ -240,10 +151,11 @@ __global__ __launch_bounds__(256) void k_nchwd_s1_lines(Geom g, const T *__restr
 
     const bool has_left = c4 > 0, has_right = c4 < W4 - 1;
     const T *xin = x + (size_t)plane_in * g.H * g.W + c4 * V;
-    const int oh0 = strip * TH;
+    T *yout = y + (size_t)plane * g.H * g.W + c4 * V;
+    const int oh0 = strip * TH, oh1 = min(g.H, oh0 + TH);
 
-    LineWriter<T, RS> lw;
-    lw.init(lb, W4, V, nstrips, nplanes, TH, g.H, g.W, y);
+    LineWriter<T, (RS > 0 ? RS : 1)> lw;
+    if constexpr (RS > 0) lw.init(lb, W4, V, nstrips, nplanes, TH, g.H, g.W, y);
 
     int loff[P > 0 ? P : 1], roff[P > 0 ? P : 1];
 #pragma unroll
@@ -291,7 +203,10 @@ __global__ __launch_bounds__(256) void k_nchwd_s1_lines(Geom g, const T *__restr
                 for (int kw = 0; kw < K; ++kw) s = fmaf(wr[K - 2 - jj][kw], cur[v + kw], s);
                 acc[jj][v] = s;
             }
-        if (idx >= 2 * P) lw.put(stage, pack16<T>(out), g.W);      // the row just finished is output row oh0 + idx - 2P
+        if (idx >= 2 * P) {        // the row just finished is output row oh0 + idx - 2P
+            if constexpr (RS > 0) lw.put(stage, pack16<T>(out), g.W);
+            else if (valid && r - P < oh1) store_vec<T, V>(yout + (size_t)(r - P) * g.W, out, nt != 0);
+        }
     };
 
     const int r0 = oh0 - P, nrows = TH + 2 * P;
@@ -454,15 +369,21 @@ __global__ __launch_bounds__(256) void k_nchwd_s1_bf16x8(Geom g, const bf16_t *_
 // Forward, 3x3, stride 2, pad 1, W even.  A lane owns V adjacent output columns and walks down
 // the output rows: it needs input columns 2*V*c4 - 1 .. 2*V*c4 + 2V - 1 of rows 2oh-1, 2oh, 2oh+1
 // (row 2oh+1 is reused as the top row of output row oh+1).
+// RS > 0: whole-line write-out of the output rows in groups of RS; RS == 0: direct stores (streamed if nt).
 // ---------------------------------------------------------------------------------------------
-template <typename T, int V>
+template <typename T, int V, int RS>
 __global__ __launch_bounds__(256) void k_nchwd_fwd_k3s2(Geom g, const T *__restrict__ x, const T *__restrict__ w,
                                                         T *__restrict__ y, int TH, int nstrips, unsigned nblocks, int nt)
 {
+    static_assert(RS == 0 || sizeof(T) * V == 16, "whole-line write-out: one 16-byte output vector per lane and row");
+    __shared__ u4v_t stage[2][RS > 0 ? RS * 256 : 1];
     constexpr int NW = 2 * V + 1;
     const int Wo4 = g.Wo / V;
-    const Lane ln = lane_of(nblocks, Wo4, nstrips, g.N * g.O);
-    if (!ln.valid) return;
+    Lane ln = lane_of(nblocks, Wo4, nstrips, g.N * g.O);
+    const bool valid = ln.valid;
+    if (!valid) ln.plane = g.N * g.O - 1;     // lanes past the end compute on the last plane; nothing of theirs is stored
+    LineWriter<T, (RS > 0 ? RS : 1)> lw;
+    if constexpr (RS > 0) lw.init(xcd_remap(blockIdx.x, nblocks), Wo4, V, nstrips, g.N * g.O, TH, g.Ho, g.Wo, y);
     const int n = ln.plane / g.O, o = ln.plane - n * g.O;
     const int plane_in = n * g.C + o / g.m;
     float wr[3][3];
@@ -524,93 +445,8 @@ __global__ __launch_bounds__(256) void k_nchwd_fwd_k3s2(Geom g, const T *__restr
             out[v] = s;
             carry[v] = fmaf(wr[0][0], v == 0 ? lo : ro[j][2 * v], fmaf(wr[0][1], ro[j][2 * v + 1], wr[0][2] * ro[j][2 * v + 2]));
         }
-        if (oh < oh1) store_vec<T, V>(yout + (size_t)oh * g.Wo, out, nt != 0);
-    };
-    int i = 0;
-#pragma unroll 1
-    for (; i + 2 <= TH; i += 2) {
-        load_row(2 * (oh0 + i) + 2, re[1]); load_row(2 * (oh0 + i) + 3, ro[1]);
-        step(oh0 + i, 0);
-        load_row(2 * (oh0 + i) + 4, re[0]); load_row(2 * (oh0 + i) + 5, ro[0]);
-        step(oh0 + i + 1, 1);
-    }
-    if (i < TH) step(oh0 + i, 0);
-}
-
-// The same with the whole-line write-out of the output rows.
-template <typename T, int V, int RS>
-__global__ __launch_bounds__(256) void k_nchwd_fwd_k3s2_lines(Geom g, const T *__restrict__ x, const T *__restrict__ w,
-                                                              T *__restrict__ y, int TH, int nstrips, unsigned nblocks)
-{
-    static_assert(sizeof(T) * V == 16, "one 16-byte output vector per lane and row");
-    __shared__ u4v_t stage[2][RS * 256];
-    constexpr int NW = 2 * V + 1;
-    const int Wo4 = g.Wo / V;
-    Lane ln = lane_of(nblocks, Wo4, nstrips, g.N * g.O);
-    if (!ln.valid) ln.plane = g.N * g.O - 1;     // lanes past the end compute on the last plane; nothing of theirs is stored
-    LineWriter<T, RS> lw;
-    lw.init(xcd_remap(blockIdx.x, nblocks), Wo4, V, nstrips, g.N * g.O, TH, g.Ho, g.Wo, y);
-    const int n = ln.plane / g.O, o = ln.plane - n * g.O;
-    const int plane_in = n * g.C + o / g.m;
-    float wr[3][3];
-#pragma unroll
-    for (int kh = 0; kh < 3; ++kh)
-#pragma unroll
-        for (int kw = 0; kw < 3; ++kw) wr[kh][kw] = ldf(w + (o * 3 + kh) * 3 + kw);
-    const bool has_left = ln.c4 > 0;
-    const T *xin = x + (size_t)plane_in * g.H * g.W + ln.c4 * 2 * V;
-    const int oh0 = ln.strip * TH;
-    const int loff = has_left ? -1 : 0;
-
-    // Raw loads (clamped row), masks applied at use: with H = 2*Ho every row 2oh, 2oh+1 of a valid
-    // output row is inside the image, so only the left neighbour (first vector of a row) and the
-    // row above the image need a select.  Every lane walks TH output rows; lanes past the end of
-    // a shorter last strip keep going with their stores masked.
-    auto load_row = [&](int r, float (&dst)[NW]) {
-        const T *rp = xin + (size_t)min(max(r, 0), g.H - 1) * g.W;
-        if constexpr (2 * V * sizeof(T) <= 16) {
-            // the lane's 2V input columns are one 16-byte vector: consecutive lanes read consecutive vectors
-            float ab[2 * V];
-            Vec<T, 2 * V>::load(rp, ab);
-            dst[0] = ldf(rp + loff);
-#pragma unroll
-            for (int v = 0; v < 2 * V; ++v) dst[1 + v] = ab[v];
-        } else {
-            float a[V], b[V];
-            Vec<T, V>::load(rp, a);
-            Vec<T, V>::load(rp + V, b);
-            dst[0] = ldf(rp + loff);
-#pragma unroll
-            for (int v = 0; v < V; ++v) { dst[1 + v] = a[v]; dst[1 + V + v] = b[v]; }
-        }
-    };
-
-    float carry[V], re[2][NW], ro[2][NW];
-    {
-        float top[NW];
-        load_row(2 * oh0 - 1, top);
-        const bool topok = oh0 > 0;
-        const float l = has_left ? top[0] : 0.f;
-#pragma unroll
-        for (int v = 0; v < V; ++v) {
-            const float t = fmaf(wr[0][0], v == 0 ? l : top[2 * v], fmaf(wr[0][1], top[2 * v + 1], wr[0][2] * top[2 * v + 2]));
-            carry[v] = topok ? t : 0.f;
-        }
-    }
-    load_row(2 * oh0, re[0]);
-    load_row(2 * oh0 + 1, ro[0]);
-    auto step = [&](int oh, int j) {
-        const float le = has_left ? re[j][0] : 0.f, lo = has_left ? ro[j][0] : 0.f;
-        float out[V];
-#pragma unroll
-        for (int v = 0; v < V; ++v) {
-            float s = carry[v];
-            s = fmaf(wr[1][0], v == 0 ? le : re[j][2 * v], s); s = fmaf(wr[1][1], re[j][2 * v + 1], s); s = fmaf(wr[1][2], re[j][2 * v + 2], s);
-            s = fmaf(wr[2][0], v == 0 ? lo : ro[j][2 * v], s); s = fmaf(wr[2][1], ro[j][2 * v + 1], s); s = fmaf(wr[2][2], ro[j][2 * v + 2], s);
-            out[v] = s;
-            carry[v] = fmaf(wr[0][0], v == 0 ? lo : ro[j][2 * v], fmaf(wr[0][1], ro[j][2 * v + 1], wr[0][2] * ro[j][2 * v + 2]));
-        }
-        lw.put(stage, pack16<T>(out), g.Wo);
+        if constexpr (RS > 0) lw.put(stage, pack16<T>(out), g.Wo);
+        else if (valid && oh < oh1) store_vec<T, V>(yout + (size_t)oh * g.Wo, out, nt != 0);
     };
     int i = 0;
 #pragma unroll 1
@@ -632,14 +468,21 @@ __global__ __launch_bounds__(256) void k_nchwd_fwd_k3s2_lines(Geom g, const T *_
 //   dx[2a  ][2b+1] = w10 dy[a][b+1] + w12 dy[a][b]
 //   dx[2a+1][2b  ] = w01 dy[a+1][b] + w21 dy[a][b]
 //   dx[2a+1][2b+1] = w00 dy[a+1][b+1] + w02 dy[a+1][b] + w20 dy[a][b+1] + w22 dy[a][b]
+// RS > 0: whole-line write-out (dx rows 2a and 2a+1 are two rows of a group); RS == 0: direct stores.
 // ---------------------------------------------------------------------------------------------
-template <typename T, int V>
+template <typename T, int V, int RS>
 __global__ __launch_bounds__(256) void k_nchwd_bwd_data_k3s2(Geom g, const T *__restrict__ dy, const T *__restrict__ w,
                                                              T *__restrict__ dx, int TH, int nstrips, unsigned nblocks, int nt)
 {
+    static_assert(sizeof(T) * 2 * V == 16, "one 16-byte dx vector per lane and row");
+    __shared__ u4v_t stage[2][RS > 0 ? RS * 256 : 1];
     const int Wo4 = g.Wo / V;
-    const Lane ln = lane_of(nblocks, Wo4, nstrips, g.N * g.C);
-    if (!ln.valid) return;
+    Lane ln = lane_of(nblocks, Wo4, nstrips, g.N * g.C);
+    const bool valid = ln.valid;
+    if (!valid) ln.plane = g.N * g.C - 1;     // lanes past the end compute on the last plane; nothing of theirs is stored
+    LineWriter<T, (RS > 0 ? RS : 1)> lw;
+    if constexpr (RS > 0) lw.init(xcd_remap(blockIdx.x, nblocks), Wo4, 2 * V, nstrips, g.N * g.C, 2 * TH, g.H, g.W, dx);
+    T *dxout = dx + (size_t)ln.plane * g.H * g.W + ln.c4 * 2 * V;
     const int o = ln.plane % g.C;
     float wr[3][3];
 #pragma unroll
@@ -648,7 +491,6 @@ __global__ __launch_bounds__(256) void k_nchwd_bwd_data_k3s2(Geom g, const T *__
         for (int kw = 0; kw < 3; ++kw) wr[kh][kw] = ldf(w + (o * 3 + kh) * 3 + kw);
     const bool has_right = ln.c4 < Wo4 - 1;
     const T *dyin = dy + (size_t)ln.plane * g.Ho * g.Wo + ln.c4 * V;
-    T *dxout = dx + (size_t)ln.plane * g.H * g.W + ln.c4 * 2 * V;
     const int a0 = ln.strip * TH, a1 = min(g.Ho, a0 + TH);
     const int roff = has_right ? V : V - 1;
 
@@ -682,85 +524,14 @@ __global__ __launch_bounds__(256) void k_nchwd_bwd_data_k3s2(Geom g, const T *__
             od[2 * v] = fmaf(wr[0][1], B[v], wr[2][1] * A[v]);
             od[2 * v + 1] = fmaf(wr[0][0], B[v + 1], fmaf(wr[0][2], B[v], fmaf(wr[2][0], A[v + 1], wr[2][2] * A[v])));
         }
-        if (a < a1) {
+        if constexpr (RS > 0) {
+            lw.put(stage, pack16<T>(ev), g.W);
+            lw.put(stage, pack16<T>(od), g.W);
+        } else if (valid && a < a1) {
             T *rp = dxout + (size_t)(2 * a) * g.W;
             store_vec<T, 2 * V>(rp, ev, nt != 0);
             store_vec<T, 2 * V>(rp + g.W, od, nt != 0);
         }
-    };
-    int i = 0;
-#pragma unroll 1
-    for (; i + 3 <= TH; i += 3) {
-#pragma unroll
-        for (int j = 0; j < 3; ++j) {
-            load_row(a0 + i + j + 2, rows[(j + 2) % 3]);
-            emit(a0 + i + j, rows[j], rows[(j + 1) % 3]);
-        }
-    }
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        if (i + j < TH) {
-            load_row(a0 + i + j + 2, rows[(j + 2) % 3]);
-            emit(a0 + i + j, rows[j], rows[(j + 1) % 3]);
-        }
-    }
-}
-
-// The same with the whole-line write-out (dx rows 2a and 2a+1 are RS = 2 rows of 2V-wide vectors).
-template <typename T, int V, int RS>
-__global__ __launch_bounds__(256) void k_nchwd_bwd_data_k3s2_lines(Geom g, const T *__restrict__ dy, const T *__restrict__ w,
-                                                                   T *__restrict__ dx, int TH, int nstrips, unsigned nblocks)
-{
-    static_assert(sizeof(T) * 2 * V == 16, "one 16-byte dx vector per lane and row");
-    __shared__ u4v_t stage[2][RS * 256];
-    const int Wo4 = g.Wo / V;
-    Lane ln = lane_of(nblocks, Wo4, nstrips, g.N * g.C);
-    if (!ln.valid) ln.plane = g.N * g.C - 1;     // lanes past the end compute on the last plane; nothing of theirs is stored
-    LineWriter<T, RS> lw;
-    lw.init(xcd_remap(blockIdx.x, nblocks), Wo4, 2 * V, nstrips, g.N * g.C, 2 * TH, g.H, g.W, dx);
-    const int o = ln.plane % g.C;
-    float wr[3][3];
-#pragma unroll
-    for (int kh = 0; kh < 3; ++kh)
-#pragma unroll
-        for (int kw = 0; kw < 3; ++kw) wr[kh][kw] = ldf(w + (o * 3 + kh) * 3 + kw);
-    const bool has_right = ln.c4 < Wo4 - 1;
-    const T *dyin = dy + (size_t)ln.plane * g.Ho * g.Wo + ln.c4 * V;
-    const int a0 = ln.strip * TH;
-    const int roff = has_right ? V : V - 1;
-
-    // Raw loads (clamped row); the row below the image's last dy row and the column right of a
-    // row's last vector are masked at use.  Every lane walks TH dy rows, stores masked past the
-    // end of a shorter last strip.
-    auto load_row = [&](int a, float (&dst)[V + 1]) {
-        const T *rp = dyin + (size_t)min(a, g.Ho - 1) * g.Wo;
-        float m[V];
-        Vec<T, V>::load(rp, m);
-        dst[V] = ldf(rp + roff);
-#pragma unroll
-        for (int v = 0; v < V; ++v) dst[v] = m[v];
-    };
-
-    float rows[3][V + 1];
-    load_row(a0, rows[0]);
-    load_row(a0 + 1, rows[1]);
-    auto emit = [&](int a, const float (&Ar)[V + 1], const float (&Br)[V + 1]) {
-        const bool below = a + 1 < g.Ho;
-        float A[V + 1], B[V + 1];
-#pragma unroll
-        for (int v = 0; v < V; ++v) { A[v] = Ar[v]; B[v] = below ? Br[v] : 0.f; }
-        A[V] = has_right ? Ar[V] : 0.f;
-        B[V] = (has_right && below) ? Br[V] : 0.f;
-        float ev[2 * V], od[2 * V];   // dx rows 2a and 2a+1, the lane's 2V columns
-#pragma unroll
-        for (int v = 0; v < V; ++v) {
-            ev[2 * v] = wr[1][1] * A[v];
-            ev[2 * v + 1] = fmaf(wr[1][0], A[v + 1], wr[1][2] * A[v]);
-            od[2 * v] = fmaf(wr[0][1], B[v], wr[2][1] * A[v]);
-            od[2 * v + 1] = fmaf(wr[0][0], B[v + 1], fmaf(wr[0][2], B[v], fmaf(wr[2][0], A[v + 1], wr[2][2] * A[v])));
-        }
-        lw.put(stage, pack16<T>(ev), g.W);
-        lw.put(stage, pack16<T>(od), g.W);
     };
     int i = 0;
 #pragma unroll 1
@@ -1202,8 +973,8 @@ static hipError_t go_s1(const Geom &g, const void *x, const void *w, void *y, bo
             const int nstrips = ceil_div_h(g.H, TH);
             const long long lanes = (long long)g.N * g.O * nstrips * (g.W / V);
             const unsigned nblocks = (unsigned)((lanes + 255) / 256);
-#define GOL(FL, RSV) hipLaunchKernelGGL((k_nchwd_s1_lines<T, V, K, 2, FL, RSV>), dim3(nblocks), dim3(256), 0, st, g, \
-                                        (const T *)x, (const T *)w, (T *)y, TH, nstrips, nblocks)
+#define GOL(FL, RSV) hipLaunchKernelGGL((k_nchwd_s1<T, V, K, 2, FL, RSV>), dim3(nblocks), dim3(256), 0, st, g, \
+                                        (const T *)x, (const T *)w, (T *)y, TH, nstrips, nblocks, 1)
 #define GOB(FL, RSV) hipLaunchKernelGGL((k_nchwd_s1_bf16x8<V, K, 2, FL, RSV>), dim3(nblocks), dim3(256), 0, st, g, \
                                         (const bf16_t *)x, (const bf16_t *)w, (bf16_t *)y, TH, nstrips, nblocks)
             if constexpr (sizeof(T) == 2 && V == 8) {      // bf16: packed-pair arithmetic
@@ -1234,10 +1005,10 @@ static hipError_t go_s1(const Geom &g, const void *x, const void *w, void *y, bo
     const int whole = (g.W * (int)sizeof(T)) % 128 == 0;
     const int nt = whole ? stream_stores(flip ? "NCHW_S1_BWD" : "NCHW_S1_FWD", out_bytes, 0) : 0;
     if (flip)
-        hipLaunchKernelGGL((k_nchwd_s1<T, V, K, 2, true>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, (const T *)w,
+        hipLaunchKernelGGL((k_nchwd_s1<T, V, K, 2, true, 0>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, (const T *)w,
                            (T *)y, TH, nstrips, nblocks, nt);
     else
-        hipLaunchKernelGGL((k_nchwd_s1<T, V, K, 2, false>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, (const T *)w,
+        hipLaunchKernelGGL((k_nchwd_s1<T, V, K, 2, false, 0>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, (const T *)w,
                            (T *)y, TH, nstrips, nblocks, nt);
     return hipGetLastError();
 }
@@ -1259,7 +1030,7 @@ hipError_t nchwd_k3s2(const Geom &g, int dtype, int V, const void *in, const voi
     const unsigned nblocks = (unsigned)((lanes + 255) / 256);
     const int nt = bwd ? stream_stores("NCHW_S2_BWD", (long long)g.N * g.C * g.H * g.W * (dtype == DT_F32 ? 4 : 2), -1)
                        : stream_stores("NCHW_S2_FWD", (long long)g.N * g.O * g.Ho * g.Wo * (dtype == DT_F32 ? 4 : 2));
-#define GO(KERNEL, T, VV) hipLaunchKernelGGL((KERNEL<T, VV>), dim3(nblocks), dim3(256), 0, st, g, (const T *)in, \
+#define GO(KERNEL, T, VV) hipLaunchKernelGGL((KERNEL<T, VV, 0>), dim3(nblocks), dim3(256), 0, st, g, (const T *)in, \
                                              (const T *)w, (T *)out, TH, nstrips, nblocks, nt)
     if (!bwd) {
         const int esz = dtype == DT_F32 ? 4 : 2;
@@ -1269,8 +1040,8 @@ hipError_t nchwd_k3s2(const Geom &g, int dtype, int V, const void *in, const voi
             const int TH2 = (TH + rs - 1) / rs * rs;
             const int nst = ceil_div_h(g.Ho, TH2);
             const unsigned nb = (unsigned)(((long long)g.N * g.O * nst * (g.Wo / V) + 255) / 256);
-#define GOL(T, VV, RSV) hipLaunchKernelGGL((k_nchwd_fwd_k3s2_lines<T, VV, RSV>), dim3(nb), dim3(256), 0, st, g, \
-                                           (const T *)in, (const T *)w, (T *)out, TH2, nst, nb)
+#define GOL(T, VV, RSV) hipLaunchKernelGGL((k_nchwd_fwd_k3s2<T, VV, RSV>), dim3(nb), dim3(256), 0, st, g, \
+                                           (const T *)in, (const T *)w, (T *)out, TH2, nst, nb, 1)
             if (dtype == DT_F32) { if (rs == 2) GOL(float, 4, 2); else GOL(float, 4, 4); }
             else { if (rs == 2) GOL(bf16_t, 8, 2); else GOL(bf16_t, 8, 4); }
 #undef GOL
@@ -1291,8 +1062,8 @@ hipError_t nchwd_k3s2(const Geom &g, int dtype, int V, const void *in, const voi
             const int TH2 = rs == 4 ? (TH + 1) / 2 * 2 : TH;
             const int nst = ceil_div_h(g.Ho, TH2);
             const unsigned nb = (unsigned)(((long long)g.N * g.O * nst * (g.Wo / V) + 255) / 256);
-#define GOL(T, VV, RSV) hipLaunchKernelGGL((k_nchwd_bwd_data_k3s2_lines<T, VV, RSV>), dim3(nb), dim3(256), 0, st, g, \
-                                           (const T *)in, (const T *)w, (T *)out, TH2, nst, nb)
+#define GOL(T, VV, RSV) hipLaunchKernelGGL((k_nchwd_bwd_data_k3s2<T, VV, RSV>), dim3(nb), dim3(256), 0, st, g, \
+                                           (const T *)in, (const T *)w, (T *)out, TH2, nst, nb, 1)
             if (dtype == DT_F32 && V == 2) { if (rs == 2) GOL(float, 2, 2); else GOL(float, 2, 4); }
             else if (dtype == DT_BF16 && V == 4) { if (rs == 2) GOL(bf16_t, 4, 2); else GOL(bf16_t, 4, 4); }
             else return hipErrorInvalidValue;

@@ -30,14 +30,14 @@ VARIANT_KERNELS = {
     "bwd_filter:nhwc_bwd_filter_k3s2": [r"k_nhwc_bwd_filter<\w+, \d+, 3, 2, \d+, 1>"],
     "bwd_filter:nhwc_bwd_filter_k5s1": [r"k_nhwc_bwd_filter<\w+, \d+, 5, 1, \d+, 1>"],
     "bwd_filter:nhwc_bwd_filter_k3s1_m2": [r"k_nhwc_bwd_filter<\w+, \d+, 3, 1, \d+, 2>"],
-    # k_nchwd_s1<T, V, K, PF, FLIP> and k_nchwd_s1_lines<T, V, K, PF, FLIP, RS> (whole-line write-out)
+    # k_nchwd_s1<T, V, K, PF, FLIP, RS> (RS > 0: whole-line write-out)
     # bf16: k_nchwd_s1_bf16x8<V, K, PF, FLIP, RS> (packed pairs)
-    "fwd:nchw_rowwalk_k3s1": [r"k_nchwd_s1(_lines)?<\w+, \d+, 3, \d+, false[,>]", r"k_nchwd_s1_bf16x8<\d+, 3, \d+, false,"],
-    "bwd_data:nchw_rowwalk_k3s1_flip": [r"k_nchwd_s1(_lines)?<\w+, \d+, 3, \d+, true[,>]", r"k_nchwd_s1_bf16x8<\d+, 3, \d+, true,"],
-    "fwd:nchw_rowwalk_k5s1": [r"k_nchwd_s1(_lines)?<\w+, \d+, 5, \d+, false[,>]", r"k_nchwd_s1_bf16x8<\d+, 5, \d+, false,"],
-    "bwd_data:nchw_rowwalk_k5s1_flip": [r"k_nchwd_s1(_lines)?<\w+, \d+, 5, \d+, true[,>]", r"k_nchwd_s1_bf16x8<\d+, 5, \d+, true,"],
-    "fwd:nchw_rowwalk_fwd_k3s2": [r"k_nchwd_fwd_k3s2(_lines)?<"],
-    "bwd_data:nchw_rowwalk_bwd_data_k3s2": [r"k_nchwd_bwd_data_k3s2(_lines)?<"],
+    "fwd:nchw_rowwalk_k3s1": [r"k_nchwd_s1<\w+, \d+, 3, \d+, false[,>]", r"k_nchwd_s1_bf16x8<\d+, 3, \d+, false,"],
+    "bwd_data:nchw_rowwalk_k3s1_flip": [r"k_nchwd_s1<\w+, \d+, 3, \d+, true[,>]", r"k_nchwd_s1_bf16x8<\d+, 3, \d+, true,"],
+    "fwd:nchw_rowwalk_k5s1": [r"k_nchwd_s1<\w+, \d+, 5, \d+, false[,>]", r"k_nchwd_s1_bf16x8<\d+, 5, \d+, false,"],
+    "bwd_data:nchw_rowwalk_k5s1_flip": [r"k_nchwd_s1<\w+, \d+, 5, \d+, true[,>]", r"k_nchwd_s1_bf16x8<\d+, 5, \d+, true,"],
+    "fwd:nchw_rowwalk_fwd_k3s2": [r"k_nchwd_fwd_k3s2<"],
+    "bwd_data:nchw_rowwalk_bwd_data_k3s2": [r"k_nchwd_bwd_data_k3s2<"],
     "bwd_filter:nchw_rowwalk_bwd_filter_k3s1": [r"k_nchwd_bwd_filter_k3<\w+, \d+, 1>", r"k_nchwd_bwd_filter_s1_bf16<\d+, 3>"],
     "bwd_filter:nchw_rowwalk_bwd_filter_k3s2": [r"k_nchwd_bwd_filter_k3<\w+, \d+, 2>"],
     "bwd_filter:nchw_rowwalk_bwd_filter_k5s1": [r"k_nchwd_bwd_filter_s1<\w+, \d+, 5>", r"k_nchwd_bwd_filter_s1_bf16<\d+, 5>"],
