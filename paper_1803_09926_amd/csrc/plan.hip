@@ -165,6 +165,12 @@ Plan plan_bwd_filter(const Geom &g, int layout, int dtype)
             int TH = tune("DWCONV_TUNE_THW", tune("DWCONV_TUNE_TH", g.Ho > 56 ? (g.Ho + 1) / 2 : (g.s == 2 && g.Ho >= 28 ? (g.Ho + 1) / 2 : g.Ho)));
             int lg, nst, rounds, parts;
             nchwd_bwd_filter_tiling(g, V, TH, &lg, &nst, &rounds, &parts);
+            // small batches: shorter strips until the launch has about two blocks per CU (one block = one
+            // channel x a group of (image, strip) items)
+            while (TH > 7 && parts >= 1 && (long long)parts * g.O < 512 && !getenv("DWCONV_TUNE_THW") && !getenv("DWCONV_TUNE_TH")) {
+                TH = (TH + 1) / 2;
+                nchwd_bwd_filter_tiling(g, V, TH, &lg, &nst, &rounds, &parts);
+            }
             if (lg >= 1 && parts >= 1 && (long long)parts * g.O * g.K * g.K * 4 <= (64ll << 20)) {
                 pl.variant = V_NCHWD_BWD_FILTER; pl.a = V; pl.b = TH; pl.parts = parts;
                 pl.name = g.K == 5 ? "nchw_rowwalk_bwd_filter_k5s1"
