@@ -75,6 +75,10 @@ hipError_t nchwd_s1(const Geom &g, int dtype, int V, const void *x, const void *
 hipError_t nchwd_k3s2(const Geom &g, int dtype, int V, const void *in, const void *w, void *out, bool bwd, int TH,
                       hipStream_t st);
 void nchwd_bwd_filter_tiling(const Geom &g, int V, int TH, int *items_per_round, int *nstrips, int *rounds, int *parts);
+// fused backward, 3x3 stride 1 fp32 (input gradient + stage 1 of the filter gradient); returns the row group (0: not applicable)
+int nchwd_bwd_fused_rs(const Geom &g, int dtype, int V);
+hipError_t nchwd_bwd_fused(const Geom &g, int dtype, int V, const void *x, const void *dy, const void *w, void *dx,
+                           float *ws, int TH, hipStream_t st);
 hipError_t nchwd_bwd_filter(const Geom &g, int dtype, int V, const void *x, const void *dy, float *ws, int TH,
                             hipStream_t st);
 

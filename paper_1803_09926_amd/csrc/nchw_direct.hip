@@ -932,6 +932,172 @@ __global__ __launch_bounds__(256) void k_nchwd_bwd_filter_s1_bf16(Geom g, const 
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Fused backward pass, NCHW, 3x3, stride 1, pad 1, multiplier 1: the input gradient dx and the
+// stage-1 partial sums of the filter gradient from one walk over dy and x (dy is read once).
+// Block structure of the filter-gradient kernel above: grid = (parts, C), a block works on one
+// channel, lanes flat over (item, vector column) with nsg (image, strip) items per round.  Step t
+// of the walk takes dy row t and x row t-1, each with its left and right neighbour column:
+//   input gradient:  dx[r][c] = sum_{kh,kw} w[kh][kw] dy[r+1-kh][c+1-kw]; dy row t is tap row 0, 1, 2
+//     of dx rows t-1, t, t+1 (two rotating accumulators; the filter is uniform over the block);
+//   filter gradient: x row t-1 meets dy rows t, t-1, t-2 (own columns) at tap rows 0, 1, 2; only dy
+//     rows inside the item's own strip count there, while the input gradient needs the true halo
+//     rows: the window entry is masked, the loaded row is not.
+// dx leaves through the whole-line write-out (RS rows per group; needs TH % RS == 0, H % RS == 0),
+// so every lane of the block walks every round in lockstep: lanes without an item (the last few
+// lanes of the block, a partly filled last round) run on clamped addresses with everything masked.
+// ---------------------------------------------------------------------------------------------
+template <typename T, int V, int RS>
+__global__ __launch_bounds__(256) void k_nchwd_bwd_fused_k3s1(Geom g, const T *__restrict__ x, const T *__restrict__ dy,
+                                                              const T *__restrict__ w, T *__restrict__ dx,
+                                                              float *__restrict__ ws, int TH, int nstrips, int nsg,
+                                                              int rounds)
+{
+    static_assert(sizeof(T) * V == 16, "whole-line write-out: one 16-byte vector per lane and row");
+    __shared__ float red[4][9];
+    __shared__ u4v_t stage[2][RS * 256];
+    constexpr int NW = V + 2;
+    const int o = blockIdx.y, part = blockIdx.x;
+    const int ncols = g.W / V;
+    const int sg = threadIdx.x / ncols, c4 = threadIdx.x - sg * ncols;
+    const int nitems = g.N * nstrips;
+    const bool has_left = c4 > 0, has_right = c4 < ncols - 1;
+    const int loff = has_left ? -1 : 0, roff = has_right ? V : V - 1;
+    const size_t plane = (size_t)g.H * g.W;
+
+    float wr[3][3];
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) wr[kh][kw] = ldf(w + (o * 3 + kh) * 3 + kw);
+
+    float acc[3][3];
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) acc[kh][kw] = 0.f;
+
+    LineWriter<T, RS> lw;
+    lw.slot = 0; lw.buf = 0; lw.done = 0;
+
+    for (int rd = 0; rd < rounds; ++rd) {
+        const int item0 = (part * rounds + rd) * nsg;
+        const int item = item0 + sg;
+        const bool live = sg < nsg && item < nitems;
+        const int itc = min(item, nitems - 1);                 // clamped: loads stay in bounds
+        const int n = itc / nstrips, strip = itc - n * nstrips;
+        const int oh0 = strip * TH, oh1 = min(g.H, oh0 + TH);
+        const T *xin = x + ((size_t)n * g.C + o) * plane + c4 * V;
+        const T *dyin = dy + ((size_t)n * g.C + o) * plane + c4 * V;
+        // write-out entries of this round: entry e = tid + 256 k belongs to the item slot of lane e / RS;
+        // inside an item entries run over (row, vector column)
+#pragma unroll
+        for (int k = 0; k < RS; ++k) {
+            const int e = threadIdx.x + 256 * k;
+            const int l = e / RS;
+            const int sgl = l / ncols, a = sgl * ncols;
+            const int rel = e - RS * a;
+            const int srow = rel / ncols, c4l = rel - srow * ncols;
+            const int iteml = item0 + sgl;
+            const bool ok = sgl < nsg && iteml < nitems;
+            const int itl = min(iteml, nitems - 1);
+            const int nl = itl / nstrips, stl = itl - nl * nstrips;
+            const int o0 = stl * TH, o1 = min(g.H, o0 + TH);
+            lw.idx[k] = min(srow, RS - 1) * 256 + min(a + c4l, 255);
+            lw.rows[k] = ok ? o1 - (o0 + srow) : 0;
+            lw.ptr[k] = dx + (((size_t)nl * g.C + o) * g.H + min(o0 + srow, g.H - 1)) * g.W + c4l * V;
+        }
+        lw.done = 0;
+
+        auto load_row = [&](int t, float (&dd)[NW], float (&xd)[NW]) {
+            const T *dp = dyin + (size_t)min(max(t, 0), g.H - 1) * g.W;
+            const T *xp = xin + (size_t)min(max(t - 1, 0), g.H - 1) * g.W;
+            float m[V];
+            Vec<T, V>::load(dp, m);
+            dd[0] = ldf(dp + loff); dd[V + 1] = ldf(dp + roff);
+#pragma unroll
+            for (int v = 0; v < V; ++v) dd[1 + v] = m[v];
+            Vec<T, V>::load(xp, m);
+            xd[0] = ldf(xp + loff); xd[V + 1] = ldf(xp + roff);
+#pragma unroll
+            for (int v = 0; v < V; ++v) xd[1 + v] = m[v];
+        };
+
+        float A0[V], A1[V], dyw[3][V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) { A0[v] = 0.f; A1[v] = 0.f; dyw[0][v] = 0.f; dyw[1][v] = 0.f; dyw[2][v] = 0.f; }
+
+        float dr[2][NW], xr[2][NW];
+        auto consume = [&](int step, int t, const float (&dd)[NW], const float (&xd)[NW]) {
+            const bool dyok = t >= 0 && t < g.H;
+            const bool mine = live && t >= oh0 && t < oh1;
+            const bool xok = t - 1 >= 0 && t - 1 < g.H;
+            float d[NW], xv[NW];
+#pragma unroll
+            for (int i = 0; i < NW; ++i) {
+                const bool colok = i == 0 ? has_left : (i == V + 1 ? has_right : true);
+                d[i] = (dyok && colok) ? dd[i] : 0.f;
+                xv[i] = (xok && colok) ? xd[i] : 0.f;
+            }
+            // input gradient: dx column c (window index c + 1) reads dy columns c+1-kw = window index c + 2 - kw
+            float out[V];
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                float s0 = A0[v], s1 = A1[v], s2 = 0.f;
+#pragma unroll
+                for (int kw = 0; kw < 3; ++kw) {
+                    s0 = fmaf(wr[0][kw], d[v + 2 - kw], s0);
+                    s1 = fmaf(wr[1][kw], d[v + 2 - kw], s1);
+                    s2 = fmaf(wr[2][kw], d[v + 2 - kw], s2);
+                }
+                out[v] = s0; A0[v] = s1; A1[v] = s2;
+            }
+            // dx row t-1 = oh0 + step - 2 leaves at steps 2 .. TH+1, the same for every lane (rows past the
+            // strip's end are masked in the write-out)
+            if (step >= 2 && step < TH + 2) lw.put(stage, pack16<T>(out), g.W);
+            // filter gradient
+#pragma unroll
+            for (int v = 0; v < V; ++v) { dyw[2][v] = dyw[1][v]; dyw[1][v] = dyw[0][v]; dyw[0][v] = mine ? d[1 + v] : 0.f; }
+#pragma unroll
+            for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+                for (int kw = 0; kw < 3; ++kw) {
+                    float sacc = acc[kh][kw];
+#pragma unroll
+                    for (int v = 0; v < V; ++v) sacc = fmaf(dyw[kh][v], xv[v + kw], sacc);
+                    acc[kh][kw] = sacc;
+                }
+        };
+
+        // steps t = oh0-1 .. oh0+TH+1 for every lane (the same count, whatever the strip's real height)
+        const int t0 = oh0 - 1, nsteps = TH + 3;
+        load_row(t0, dr[0], xr[0]);
+        int i = 0;
+#pragma unroll 1
+        for (; i + 2 <= nsteps; i += 2) {
+            load_row(t0 + i + 1, dr[1], xr[1]);
+            consume(i, t0 + i, dr[0], xr[0]);
+            load_row(t0 + i + 2, dr[0], xr[0]);
+            consume(i + 1, t0 + i + 1, dr[1], xr[1]);
+        }
+        if (i < nsteps) consume(i, t0 + i, dr[0], xr[0]);
+    }
+
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) {
+            const float s = wave_sum(acc[kh][kw]);
+            if (lane == 0) red[wv][kh * 3 + kw] = s;
+        }
+    __syncthreads();
+    if (threadIdx.x < 9) {
+        const int t = threadIdx.x;
+        ws[((size_t)part * g.C + o) * 9 + t] = (red[0][t] + red[1][t]) + (red[2][t] + red[3][t]);
+    }
+}
+
 // ---- host side --------------------------------------------------------------------------------
 
 // vector width for the direct kernels (0 = not applicable): rows must be whole 16-byte vectors;
@@ -1136,6 +1302,31 @@ hipError_t nchwd_bwd_filter(const Geom &g, int dtype, int V, const void *x, cons
         else if (dtype == DT_BF16 && V == 4) GO(bf16_t, 4, 2);
         else return hipErrorInvalidValue;
     }
+#undef GO
+    return hipGetLastError();
+}
+
+// Fused backward: same tiling as the filter gradient, strip height a multiple of the row group.
+int nchwd_bwd_fused_rs(const Geom &g, int dtype, int V)
+{
+    if (!(g.K == 3 && g.s == 1 && g.p == 1 && g.m == 1)) return 0;
+    if (!(dtype == DT_F32 && V == 4)) return 0;
+    const int rs = row_group(g.W, 4);
+    return (rs && g.H % rs == 0 && g.W / V <= 256) ? rs : 0;
+}
+
+hipError_t nchwd_bwd_fused(const Geom &g, int dtype, int V, const void *x, const void *dy, const void *w, void *dx,
+                           float *ws, int TH, hipStream_t st)
+{
+    const int rs = nchwd_bwd_fused_rs(g, dtype, V);
+    if (!rs || TH % rs != 0) return hipErrorInvalidValue;
+    int lg, nstrips, rounds, parts;
+    nchwd_bwd_filter_tiling(g, V, TH, &lg, &nstrips, &rounds, &parts);
+    if (lg < 1 || parts < 1) return hipErrorInvalidValue;
+    dim3 grid(parts, g.C);
+#define GO(RSV) hipLaunchKernelGGL((k_nchwd_bwd_fused_k3s1<float, 4, RSV>), grid, dim3(256), 0, st, g, (const float *)x, \
+                                   (const float *)dy, (const float *)w, (float *)dx, ws, TH, nstrips, lg, rounds)
+    if (rs == 2) GO(2); else GO(4);
 #undef GO
     return hipGetLastError();
 }

@@ -246,6 +246,23 @@ Plan plan_bwd(const Geom &g, int layout, int dtype)
             }
         }
     }
+    if (layout == LAYOUT_NCHW && !getenv("DWCONV_TUNE_NOFUSE")) {
+        const Plan pf = plan_bwd_filter(g, layout, dtype);
+        if (pf.variant == V_NCHWD_BWD_FILTER) {
+            const int rs = nchwd_bwd_fused_rs(g, dtype, pf.a);
+            if (rs) {
+                // the filter gradient's tiling with the strip height rounded up to whole row groups
+                const int TH = (pf.b + rs - 1) / rs * rs;
+                int lg, nst, rounds, parts;
+                nchwd_bwd_filter_tiling(g, pf.a, TH, &lg, &nst, &rounds, &parts);
+                if (lg >= 1 && parts >= 1 && (long long)parts * g.O * g.K * g.K * 4 <= (64ll << 20)) {
+                    pl = pf;
+                    pl.variant = V_NCHWD_BWD_FUSED; pl.b = TH; pl.parts = parts;
+                    pl.name = "nchw_bwd_fused_k3s1";
+                }
+            }
+        }
+    }
     return pl;
 }
 
@@ -295,6 +312,7 @@ hipError_t launch_bwd_fused(const Plan &pl, const Geom &g, int layout, int dtype
                             const void *w, void *dx, float *ws, hipStream_t st)
 {
     (void)layout;
+    if (pl.variant == V_NCHWD_BWD_FUSED) return nchwd_bwd_fused(g, dtype, pl.a, x, dy, w, dx, ws, pl.b, st);
     if (pl.variant != V_NHWC_BWD_FUSED) return hipErrorInvalidValue;
     return nhwc_bwd_fused(g, dtype, pl.a, x, dy, w, dx, ws, pl.b, pl.c, st);
 }

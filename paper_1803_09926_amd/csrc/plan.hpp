@@ -20,6 +20,7 @@ enum Variant {
     V_NCHWS_BWD_DATA_S2,
     V_NCHWS_BWD_FILTER, // a = U, c = NI
     V_NHWC_BWD_FUSED,   // a = V, b = TH, c = NI (input gradient and filter gradient in one kernel)
+    V_NCHWD_BWD_FUSED,  // a = V, b = TH
 };
 
 struct Plan {
