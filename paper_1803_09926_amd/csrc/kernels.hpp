@@ -87,6 +87,11 @@ bool nchws_supported(const Geom &g, int pass);
 hipError_t nchws_fwd(const Geom &g, int dtype, const void *x, const void *w, void *y, bool flip, hipStream_t st);
 hipError_t nchws_bwd_data_s2(const Geom &g, int dtype, const void *dy, const void *w, void *dx, hipStream_t st);
 void nchws_bwd_filter_tiling(const Geom &g, int dtype, int *U, int *NI, int *parts);
+// fused backward on small planes (3x3 stride 1): x and dy staged in LDS once for both gradients
+bool nchws_bwd_fused_supported(const Geom &g);
+void nchws_bwd_fused_tiling(const Geom &g, int dtype, int *U, int *NI, int *parts);
+hipError_t nchws_bwd_fused(const Geom &g, int dtype, const void *x, const void *dy, const void *w, void *dx, float *ws,
+                           int U, int NI, hipStream_t st);
 hipError_t nchws_bwd_filter(const Geom &g, int dtype, const void *x, const void *dy, float *ws, int U, int NI,
                             hipStream_t st);
 

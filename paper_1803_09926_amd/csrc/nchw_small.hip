@@ -322,6 +322,138 @@ __global__ __launch_bounds__(256) void k_nchws_bwd_filter(Geom g, const T *__res
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Fused backward pass, 3x3, stride 1, pad 1, row width W (template): the planes of x and dy of one
+// image are staged in LDS once and serve both gradients.  Block and lane mapping of the
+// filter-gradient kernel above (U consecutive channels, NI images; a lane owns (channel, row)):
+// the lane accumulates its 9 partial sums from the x rows around its dy row, and it computes row
+// `oh` of dx from the dy rows around it with the rotated filter; the dx planes go to a third
+// LDS area and leave as one flat range with aligned 16-byte streaming stores.
+// ---------------------------------------------------------------------------------------------
+template <typename T, int W>
+__global__ __launch_bounds__(256) void k_nchws_bwd_fused(Geom g, const T *__restrict__ x, const T *__restrict__ dy,
+                                                         const T *__restrict__ w, T *__restrict__ dx,
+                                                         float *__restrict__ ws, int U, int NI, int ncblocks,
+                                                         unsigned nblocks, int nt)
+{
+    extern __shared__ float4 smem4[];
+    constexpr int VE = ElemsS<T>::VE;
+    constexpr int K = 3;
+    const int HW = g.H * W;
+    const unsigned lb = xcd_remap(blockIdx.x, nblocks);
+    const int cblk = lb % ncblocks, part = lb / ncblocks;
+    const int c0 = cblk * U, nc = min(U, g.C - c0);
+    const int n0 = part * NI, n1 = min(g.N, n0 + NI);
+    const int area = (U * HW + 2 * VE + 3) & ~3;
+    float *lx = reinterpret_cast<float *>(smem4);
+    float *ld = lx + area;
+    float *lo = ld + area;
+
+    const int p = threadIdx.x / g.H, oh = threadIdx.x - p * g.H;
+    const bool own = p < nc;
+    float acc[K][K];
+#pragma unroll
+    for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < K; ++kw) acc[kh][kw] = 0.f;
+    bool rowok[K];
+    int rowi[K];
+    float wr[K][K];          // rotated filter of the lane's channel, rows outside the image zeroed
+#pragma unroll
+    for (int kh = 0; kh < K; ++kh) {
+        const int ih = oh - 1 + kh;
+        rowok[kh] = ih >= 0 && ih < g.H;
+        rowi[kh] = min(max(ih, 0), g.H - 1);
+#pragma unroll
+        for (int kw = 0; kw < K; ++kw) {
+            const float t = ldf(w + ((c0 + min(p, nc - 1)) * K + (K - 1 - kh)) * K + (K - 1 - kw));
+            wr[kh][kw] = rowok[kh] ? t : 0.f;
+        }
+    }
+
+    FlatRegs<T> rx, rd;
+    {
+        const int g0 = (n0 * g.C + c0) * HW;
+        flat_issue<T>(x, g.N * g.C * HW, g0, g0 + nc * HW, rx);
+        flat_issue<T>(dy, g.N * g.C * HW, g0, g0 + nc * HW, rd);
+    }
+    for (int n = n0; n < n1; ++n) {
+        const int g0 = (n * g.C + c0) * HW;       // x, dy and dx planes of this image and channel block: the same flat range
+        __syncthreads();                          // the previous image's dx has left the staging area
+        flat_commit<T>(g0, g0 + nc * HW, rx, lx);
+        flat_commit<T>(g0, g0 + nc * HW, rd, ld);
+        __syncthreads();
+        if (n + 1 < n1) {
+            const int h0 = ((n + 1) * g.C + c0) * HW;
+            flat_issue<T>(x, g.N * g.C * HW, h0, h0 + nc * HW, rx);
+            flat_issue<T>(dy, g.N * g.C * HW, h0, h0 + nc * HW, rd);
+        }
+        if (own) {
+            const int off = (g0 & (VE - 1)) + p * HW;
+            const float *xp = lx + off, *dpl = ld + off;
+            // filter gradient: dy row oh against x rows oh-1, oh, oh+1
+            float d[W];
+#pragma unroll
+            for (int j = 0; j < W; ++j) d[j] = dpl[oh * W + j];
+#pragma unroll
+            for (int kh = 0; kh < K; ++kh) {
+                const float *rp = xp + rowi[kh] * W;
+                float row[W];
+#pragma unroll
+                for (int i = 0; i < W; ++i) { const float t = rp[i]; row[i] = rowok[kh] ? t : 0.f; }
+#pragma unroll
+                for (int kw = 0; kw < K; ++kw) {
+                    float s = acc[kh][kw];
+#pragma unroll
+                    for (int j = 0; j < W; ++j) {
+                        const int iw = j - 1 + kw;
+                        if (iw >= 0 && iw < W) s = fmaf(d[j], row[iw], s);
+                    }
+                    acc[kh][kw] = s;
+                }
+            }
+            // input gradient: row oh of dx = rotated filter over dy rows oh-1, oh, oh+1
+            float out[W];
+#pragma unroll
+            for (int j = 0; j < W; ++j) out[j] = 0.f;
+#pragma unroll
+            for (int kh = 0; kh < K; ++kh) {
+                const float *rp = dpl + rowi[kh] * W;
+                float row[W];
+#pragma unroll
+                for (int i = 0; i < W; ++i) row[i] = (kh == 1) ? d[i] : rp[i];
+#pragma unroll
+                for (int j = 0; j < W; ++j)
+#pragma unroll
+                    for (int kw = 0; kw < K; ++kw) {
+                        const int iw = j - 1 + kw;
+                        if (iw >= 0 && iw < W) out[j] = fmaf(wr[kh][kw], row[iw], out[j]);
+                    }
+            }
+            float *op = lo + off + oh * W;
+#pragma unroll
+            for (int j = 0; j < W; ++j) op[j] = out[j];
+        }
+        __syncthreads();
+        flat_store<T>(dx, g0, g0 + nc * HW, lo, nt != 0);
+    }
+
+    // rows of a channel are added in row order (fixed), through LDS
+    __syncthreads();
+    float *red = lx;     // 256 * 9 floats across the staging areas (the host sizes the LDS for it)
+#pragma unroll
+    for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < K; ++kw) red[threadIdx.x * (K * K) + kh * K + kw] = own ? acc[kh][kw] : 0.f;
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < nc * K * K; idx += 256) {
+        const int pc = idx / (K * K), t = idx - pc * (K * K);
+        float s = 0.f;
+        for (int r = 0; r < g.H; ++r) s += red[(pc * g.H + r) * (K * K) + t];
+        ws[((size_t)part * g.C + c0 + pc) * (K * K) + t] = s;
+    }
+}
+
 // ---- host side --------------------------------------------------------------------------------
 
 static inline int cdiv(int a, int b) { return (a + b - 1) / b; }
@@ -452,6 +584,60 @@ hipError_t nchws_bwd_filter(const Geom &g, int dtype, const void *x, const void 
                             hipStream_t st)
 {
     return dtype == DT_F32 ? go_bwd_filter<float>(g, x, dy, ws, U, NI, st) : go_bwd_filter<bf16_t>(g, x, dy, ws, U, NI, st);
+}
+
+// Fused backward on small planes: tiling of the filter gradient, with U bounded by the three LDS areas.
+bool nchws_bwd_fused_supported(const Geom &g)
+{
+    return nchws_supported(g, 2) && g.K == 3 && g.s == 1 && g.p == 1 && g.m == 1 && g.W != 28;
+}
+
+static size_t lds_bytes_fused(int U, int plane, int ve)
+{
+    const size_t area = (size_t)((U * plane + 2 * ve + 3) & ~3);
+    size_t b = (3 * area + 4) * sizeof(float);
+    return b < 256 * 9 * sizeof(float) ? 256 * 9 * sizeof(float) : b;
+}
+
+void nchws_bwd_fused_tiling(const Geom &g, int dtype, int *U, int *NI, int *parts)
+{
+    nchws_bwd_filter_tiling(g, dtype, U, NI, parts);
+    const int ve = dtype == DT_F32 ? 4 : 8;
+    while (*U > 1 && lds_bytes_fused(*U, g.H * g.W, ve) > 60 * 1024) --*U;
+    const int ncb = cdiv(g.C, *U);
+    int ni = (int)(((long long)g.N * ncb) / 2048);
+    if (ni < 1) ni = 1;
+    if (ni > g.N) ni = g.N;
+    *NI = ni;
+    *parts = cdiv(g.N, ni);
+}
+
+template <typename T>
+static hipError_t go_bwd_fused(const Geom &g, const void *x, const void *dy, const void *w, void *dx, float *ws, int U,
+                               int NI, hipStream_t st)
+{
+    constexpr int VE = ElemsS<T>::VE;
+    const size_t lds = lds_bytes_fused(U, g.H * g.W, VE);
+    const int ncb = cdiv(g.C, U);
+    const unsigned nblocks = (unsigned)ncb * cdiv(g.N, NI);
+    const int nt = stream_stores("NCHW_SMALL_BWD", (long long)g.N * g.C * g.H * g.W * sizeof(T), 0);
+#define GO(WW) hipLaunchKernelGGL((k_nchws_bwd_fused<T, WW>), dim3(nblocks), dim3(256), lds, st, g, (const T *)x, \
+                                  (const T *)dy, (const T *)w, (T *)dx, ws, U, NI, ncb, nblocks, nt)
+    if (g.W == 14) GO(14);
+    else if (g.W == 7) GO(7);
+    else if (g.W == 8) GO(8);
+    else if (g.W == 4) GO(4);
+    else return hipErrorInvalidValue;
+#undef GO
+    return hipGetLastError();
+}
+
+hipError_t nchws_bwd_fused(const Geom &g, int dtype, const void *x, const void *dy, const void *w, void *dx, float *ws,
+                           int U, int NI, hipStream_t st)
+{
+    if (!nchws_bwd_fused_supported(g)) return hipErrorInvalidValue;
+    return dtype == DT_F32 ? go_bwd_fused<float>(g, x, dy, w, dx, ws, U, NI, st)
+                           : go_bwd_fused<bf16_t>(g, x, dy, w, dx, ws, U, NI, st);
 }
 
 }  // namespace dwc

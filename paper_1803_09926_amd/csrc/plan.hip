@@ -248,6 +248,15 @@ Plan plan_bwd(const Geom &g, int layout, int dtype)
     }
     if (layout == LAYOUT_NCHW && !getenv("DWCONV_TUNE_NOFUSE")) {
         const Plan pf = plan_bwd_filter(g, layout, dtype);
+        if (pf.variant == V_NCHWS_BWD_FILTER && nchws_bwd_fused_supported(g)) {
+            int U, NI, parts;
+            nchws_bwd_fused_tiling(g, dtype, &U, &NI, &parts);
+            if ((long long)parts * g.O * g.K * g.K * 4 <= (64ll << 20)) {
+                pl = pf;
+                pl.variant = V_NCHWS_BWD_FUSED; pl.a = U; pl.c = NI; pl.parts = parts;
+                pl.name = "nchw_smallplane_bwd_fused_k3s1";
+            }
+        }
         if (pf.variant == V_NCHWD_BWD_FILTER) {
             const int rs = nchwd_bwd_fused_rs(g, dtype, pf.a);
             if (rs) {
@@ -313,6 +322,7 @@ hipError_t launch_bwd_fused(const Plan &pl, const Geom &g, int layout, int dtype
 {
     (void)layout;
     if (pl.variant == V_NCHWD_BWD_FUSED) return nchwd_bwd_fused(g, dtype, pl.a, x, dy, w, dx, ws, pl.b, st);
+    if (pl.variant == V_NCHWS_BWD_FUSED) return nchws_bwd_fused(g, dtype, x, dy, w, dx, ws, pl.a, pl.c, st);
     if (pl.variant != V_NHWC_BWD_FUSED) return hipErrorInvalidValue;
     return nhwc_bwd_fused(g, dtype, pl.a, x, dy, w, dx, ws, pl.b, pl.c, st);
 }

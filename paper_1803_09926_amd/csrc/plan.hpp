@@ -21,6 +21,7 @@ enum Variant {
     V_NCHWS_BWD_FILTER, // a = U, c = NI
     V_NHWC_BWD_FUSED,   // a = V, b = TH, c = NI (input gradient and filter gradient in one kernel)
     V_NCHWD_BWD_FUSED,  // a = V, b = TH
+    V_NCHWS_BWD_FUSED,  // a = U, c = NI
 };
 
 struct Plan {
