@@ -108,10 +108,11 @@ int dwconv_bwd_filter(const dwconv_desc *desc, const void *x, const void *dy, vo
                       void *workspace, size_t workspace_bytes, void *stream);
 
 /* Whole backward pass of the layer in one call: dx as dwconv_bwd_data, dw as dwconv_bwd_filter
- * (Section III-A, backward propagation: both gradients come from the same dy; the paper's Table III
- * reports them as one "Backward" time).  Where a fused kernel exists (3x3, stride 1, pad 1, multiplier 1:
- * NHWC; NCHW fp32 with rows of whole 16-byte vectors; NCHW planes with rows of 4, 7, 8 or 14) dy and x are read once and the pass moves 2|x| + |y| elements instead of
- * 2(|x| + |y|); every other shape runs the two passes one after the other on `stream`, with
+ * (Section III-A, backward propagation: both gradients come from the same dy; the paper's
+ * Table III reports them as one "Backward" time).  Where a fused kernel exists (3x3, stride 1,
+ * pad 1, multiplier 1: NHWC; NCHW fp32 with rows of whole 16-byte vectors; NCHW planes with
+ * rows of 4, 7, 8 or 14) dy and x are read once and the pass moves 2|x| + |y| elements instead
+ * of 2(|x| + |y|); every other shape runs the two passes one after the other on `stream`, with
  * results identical to the separate calls.
  * x, dy, w: device, read.  dx: device, every element written.  dw: device, fp32, written in full.
  * workspace: device scratch of at least dwconv_bwd_workspace_bytes(desc) bytes, 16-byte aligned.

@@ -51,6 +51,10 @@ VARIANT_KERNELS = {
     "fwd:nchw_smallplane_k5s1": [r"k_nchws_fwd<\w+, 5, 1, \d+, false>"],
     "bwd_data:nchw_smallplane_k5s1_flip": [r"k_nchws_fwd<\w+, 5, 1, \d+, true>"],
     "bwd_filter:nchw_smallplane_bwd_filter_k5s1": [r"k_nchws_bwd_filter<\w+, 5, 1, \d+>"],
+    # whole backward pass in one kernel (dwconv_bwd)
+    "bwd:nhwc_bwd_fused_k3s1": [r"k_nhwc_bwd_fused_k3s1<"],
+    "bwd:nchw_bwd_fused_k3s1": [r"k_nchwd_bwd_fused_k3s1<"],
+    "bwd:nchw_smallplane_bwd_fused_k3s1": [r"k_nchws_bwd_fused<"],
 }
 
 
