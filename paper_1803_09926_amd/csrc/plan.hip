@@ -162,7 +162,11 @@ Plan plan_bwd_filter(const Geom &g, int layout, int dtype)
         }
         const int V = nchwd_vec(g, dtype, 2);
         if (V) {
-            int TH = tune("DWCONV_TUNE_THW", tune("DWCONV_TUNE_TH", g.Ho > 56 ? (g.Ho + 1) / 2 : (g.s == 2 && g.Ho >= 28 ? (g.Ho + 1) / 2 : g.Ho)));
+            // strip height (measured on the benchmark layers): stride 2 wants short strips of 7 output rows,
+            // fp32 stride 1 on large planes 14 rows, everything else whole planes up to 56 rows
+            int TH = g.s == 2 && g.Ho >= 28 ? 7
+                     : (g.s == 1 && dtype == DT_F32 && g.Ho >= 56 ? 14 : (g.Ho > 56 ? (g.Ho + 1) / 2 : g.Ho));
+            TH = tune("DWCONV_TUNE_THW", tune("DWCONV_TUNE_TH", TH));
             int lg, nst, rounds, parts;
             nchwd_bwd_filter_tiling(g, V, TH, &lg, &nst, &rounds, &parts);
             // small batches: shorter strips until the launch has about two blocks per CU (one block = one
