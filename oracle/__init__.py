@@ -9,7 +9,8 @@ definition of a depthwise convolution, paper Section II and Section III-A, Eq. 3
 and Eq. 4).  This module only compiles that file with gcc and marshals numpy
 arrays into it.  ``dense_identity`` holds a second, separately written route to
 the same results (the paper's block-diagonal dense convolution), used to pin
-the loop nests on tiny inputs.
+the loop nests on tiny inputs.  ``gconv`` is the oracle of the group-convolution
+extension (more than one channel per group), with its own C file.
 """
 from __future__ import annotations
 
