@@ -130,6 +130,53 @@ const char *dwconv_status_string(int status);
  * tests.  Returns "invalid" for an invalid desc. */
 const char *dwconv_variant_name(const dwconv_desc *desc, int pass);
 
+/* ---- Group convolution: more than one channel per group ------------------------------------------
+ *
+ * Section V-B (extensibility): a depthwise convolution is the group convolution whose number of
+ * groups equals its number of channels; with fewer groups the 0/1 mask of Eq. 2 keeps, for an output
+ * channel, the K x K blocks of every input channel of its own group.  As for the depthwise layer,
+ * the dense masked product is not what runs: the passes are direct stencils over the Cg = C/groups
+ * input channels of a group, still bound by memory for small Cg.
+ *
+ * The C input and O output channels are split into `groups` runs of Cg = C/groups and Og = O/groups
+ * consecutive channels; output channel o reads input channels (o/Og)*Cg .. (o/Og)*Cg + Cg - 1.
+ *   layout NCHW: x, dx [N,C,H,W];  y, dy [N,O,Ho,Wo];  w, dw [O,Cg,K,K]
+ *   layout NHWC: x, dx [N,H,W,C];  y, dy [N,Ho,Wo,O];  w, dw [K,K,Cg,O]
+ * All other conventions (cross-correlation, padding, output size, dtypes, dw in fp32, pointers,
+ * alignment, stream, errors, determinism) are those of the depthwise entry points above.
+ * groups == C (Cg == 1) is the depthwise layer with multiplier O/C and runs on its kernels.
+ *
+ *   fwd        y[n,o,oh,ow]   = sum_{ci<Cg,kh,kw} w[o,ci,kh,kw] * x[n,(o/Og)*Cg+ci,oh*s-p+kh,ow*s-p+kw]
+ *   bwd_data   dx[n,c,ih,iw]  = sum over the Og output channels o of the group of c and the taps
+ *                               (kh,kw) that land on (ih,iw) of w[o,c%Cg,kh,kw] * dy[n,o,oh,ow]
+ *   bwd_filter dw[o,ci,kh,kw] = sum_{n,oh,ow} dy[n,o,oh,ow] * x[n,(o/Og)*Cg+ci,oh*s-p+kh,ow*s-p+kw]
+ */
+typedef struct dwconv_group_desc {
+    int32_t N, C, H, W; /* input tensor dims, all >= 1                                    */
+    int32_t K;          /* square K x K filter, 1 <= K <= DWCONV_MAX_K                    */
+    int32_t stride;     /* >= 1                                                           */
+    int32_t pad;        /* >= 0                                                           */
+    int32_t groups;     /* >= 1, divides C and O (otherwise DWCONV_ERR_BAD_DIM)           */
+    int32_t O;          /* output channels, >= 1                                          */
+    int32_t layout;     /* enum dwconv_layout                                             */
+    int32_t dtype;      /* enum dwconv_dtype                                              */
+} dwconv_group_desc;
+
+/* Output spatial size; host-only.  Ho, Wo may be NULL. */
+int gconv_out_dims(const dwconv_group_desc *desc, int32_t *Ho, int32_t *Wo);
+/* Device scratch gconv_bwd_filter needs; host-only; 0 for an invalid desc; at most 64 MiB. */
+size_t gconv_bwd_filter_workspace_bytes(const dwconv_group_desc *desc);
+/* x, w: device, read.  y: device, written in full. */
+int gconv_fwd(const dwconv_group_desc *desc, const void *x, const void *w, void *y, void *stream);
+/* dy, w: device, read.  dx: device, every element written. */
+int gconv_bwd_data(const dwconv_group_desc *desc, const void *dy, const void *w, void *dx, void *stream);
+/* x, dy: device, read.  dw: device, fp32, written in full.  workspace as for dwconv_bwd_filter;
+ * two-stage reduction without atomics, bit-identical from run to run. */
+int gconv_bwd_filter(const dwconv_group_desc *desc, const void *x, const void *dy, void *dw,
+                     void *workspace, size_t workspace_bytes, void *stream);
+/* Name of the kernel variant for `pass` (0 fwd, 1 bwd_data, 2 bwd_filter); "invalid" for a bad desc. */
+const char *gconv_variant_name(const dwconv_group_desc *desc, int pass);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,13 +22,21 @@ _lib = None
 
 EXPORTS = ("dwconv_out_dims", "dwconv_bwd_filter_workspace_bytes", "dwconv_fwd", "dwconv_bwd_data",
            "dwconv_bwd_filter", "dwconv_bwd_workspace_bytes", "dwconv_bwd", "dwconv_status_string",
-           "dwconv_variant_name")
+           "dwconv_variant_name",
+           "gconv_out_dims", "gconv_bwd_filter_workspace_bytes", "gconv_fwd", "gconv_bwd_data", "gconv_bwd_filter",
+           "gconv_variant_name")
 
 
 class Desc(ctypes.Structure):
     """Mirror of struct dwconv_desc."""
     _fields_ = [(k, ctypes.c_int32) for k in
                 ("N", "C", "H", "W", "K", "stride", "pad", "mult", "layout", "dtype")]
+
+
+class GroupDesc(ctypes.Structure):
+    """Mirror of struct dwconv_group_desc."""
+    _fields_ = [(k, ctypes.c_int32) for k in
+                ("N", "C", "H", "W", "K", "stride", "pad", "groups", "O", "layout", "dtype")]
 
 
 class DwconvError(RuntimeError):
@@ -56,6 +64,13 @@ def load():
     lib.dwconv_bwd.argtypes = [P, VP, VP, VP, VP, VP, VP, ctypes.c_size_t, VP]; lib.dwconv_bwd.restype = ctypes.c_int
     lib.dwconv_status_string.argtypes = [ctypes.c_int]; lib.dwconv_status_string.restype = ctypes.c_char_p
     lib.dwconv_variant_name.argtypes = [P, ctypes.c_int]; lib.dwconv_variant_name.restype = ctypes.c_char_p
+    G = ctypes.POINTER(GroupDesc)
+    lib.gconv_out_dims.argtypes = [G, I32P, I32P]; lib.gconv_out_dims.restype = ctypes.c_int
+    lib.gconv_bwd_filter_workspace_bytes.argtypes = [G]; lib.gconv_bwd_filter_workspace_bytes.restype = ctypes.c_size_t
+    lib.gconv_fwd.argtypes = [G, VP, VP, VP, VP]; lib.gconv_fwd.restype = ctypes.c_int
+    lib.gconv_bwd_data.argtypes = [G, VP, VP, VP, VP]; lib.gconv_bwd_data.restype = ctypes.c_int
+    lib.gconv_bwd_filter.argtypes = [G, VP, VP, VP, VP, ctypes.c_size_t, VP]; lib.gconv_bwd_filter.restype = ctypes.c_int
+    lib.gconv_variant_name.argtypes = [G, ctypes.c_int]; lib.gconv_variant_name.restype = ctypes.c_char_p
     _lib = lib
     return lib
 
@@ -164,3 +179,66 @@ def bwd(d: Desc, x, dy, w, dx, dw, workspace, stream=None):
     if rc != 0:
         raise DwconvError(rc, "dwconv_bwd")
     return dx, dw
+
+
+# ---- group convolution (more than one channel per group) ----------------------------------------------
+
+def group_desc(N, C, H, W, K=3, stride=1, pad=1, groups=1, O=None, layout=NCHW, dtype=F32) -> GroupDesc:
+    return GroupDesc(int(N), int(C), int(H), int(W), int(K), int(stride), int(pad), int(groups),
+                     int(C if O is None else O), int(layout), int(dtype))
+
+
+def gconv_variant_name(d: GroupDesc, which: int) -> str:
+    return load().gconv_variant_name(ctypes.byref(d), int(which)).decode()
+
+
+def gconv_out_dims(d: GroupDesc):
+    ho, wo = ctypes.c_int32(0), ctypes.c_int32(0)
+    rc = load().gconv_out_dims(ctypes.byref(d), ctypes.byref(ho), ctypes.byref(wo))
+    if rc != 0:
+        raise DwconvError(rc, "gconv_out_dims")
+    return ho.value, wo.value
+
+
+def gconv_bwd_filter_workspace_bytes(d: GroupDesc) -> int:
+    return int(load().gconv_bwd_filter_workspace_bytes(ctypes.byref(d)))
+
+
+def _gsizes(d: GroupDesc):
+    ho, wo = gconv_out_dims(d)
+    return d.N * d.C * d.H * d.W, d.N * d.O * ho * wo, d.O * (d.C // d.groups) * d.K * d.K
+
+
+def gconv_fwd(d: GroupDesc, x, w, y, stream=None):
+    """Enqueue y = group cross-correlation of x with w (w [O,Cg,K,K] for NCHW, [K,K,Cg,O] for NHWC)."""
+    nx, ny, nw = _gsizes(d)
+    _check_tensor(x, "x", d, nx); _check_tensor(w, "w", d, nw); _check_tensor(y, "y", d, ny)
+    rc = load().gconv_fwd(ctypes.byref(d), _ptr(x), _ptr(w), _ptr(y), _stream(stream))
+    if rc != 0:
+        raise DwconvError(rc, "gconv_fwd")
+    return y
+
+
+def gconv_bwd_data(d: GroupDesc, dy, w, dx, stream=None):
+    """Enqueue dx = input gradient of the group convolution."""
+    nx, ny, nw = _gsizes(d)
+    _check_tensor(dy, "dy", d, ny); _check_tensor(w, "w", d, nw); _check_tensor(dx, "dx", d, nx)
+    rc = load().gconv_bwd_data(ctypes.byref(d), _ptr(dy), _ptr(w), _ptr(dx), _stream(stream))
+    if rc != 0:
+        raise DwconvError(rc, "gconv_bwd_data")
+    return dx
+
+
+def gconv_bwd_filter(d: GroupDesc, x, dy, dw, workspace, stream=None):
+    """Enqueue dw = filter gradient (fp32) of the group convolution.  `workspace` is a uint8 device tensor of
+    at least gconv_bwd_filter_workspace_bytes(d) bytes."""
+    nx, ny, nw = _gsizes(d)
+    _check_tensor(x, "x", d, nx); _check_tensor(dy, "dy", d, ny); _check_tensor(dw, "dw", d, nw, fp32_always=True)
+    if workspace is None or not workspace.is_cuda:
+        raise ValueError("workspace must be a device tensor")
+    nbytes = workspace.numel() * workspace.element_size()
+    rc = load().gconv_bwd_filter(ctypes.byref(d), _ptr(x), _ptr(dy), _ptr(dw), _ptr(workspace),
+                                 ctypes.c_size_t(nbytes), _stream(stream))
+    if rc != 0:
+        raise DwconvError(rc, "gconv_bwd_filter")
+    return dw

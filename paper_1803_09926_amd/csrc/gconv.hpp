@@ -1,0 +1,47 @@
+// Group convolution (more than one channel per group): geometry and host-side launch entry points.
+#pragma once
+#include "kernels.hpp"
+
+namespace dwc {
+
+struct GGeom {
+    int N, C, H, W;     // input dims
+    int K, s, p;        // filter size, stride, pad
+    int G, O;           // groups, output channels
+    int Cg, Og;         // input / output channels per group
+    int Ho, Wo;
+};
+
+enum GVariant { GV_GENERIC = 0, GV_NCHW_K3S1, GV_NHWC_K3S1 };
+
+struct GPlan {
+    int variant;
+    int parts;          // bwd_filter: partial sums per weight entry
+    int a, b, c;        // variant-specific tiling
+    const char *name;
+};
+
+// ---- generic kernels: any K, stride, pad, group size, both layouts (gconv.hip) ---------------------
+hipError_t gconv_generic_fwd(const GGeom &g, int layout, int dtype, const void *x, const void *w, void *y, hipStream_t st);
+hipError_t gconv_generic_bwd_data(const GGeom &g, int layout, int dtype, const void *dy, const void *w, void *dx,
+                                  hipStream_t st);
+int gconv_generic_bwd_filter_parts(const GGeom &g);
+hipError_t gconv_generic_bwd_filter(const GGeom &g, int layout, int dtype, const void *x, const void *dy, float *ws,
+                                    int parts, hipStream_t st);
+
+// ---- NCHW row-walk kernels, 3x3 stride 1 pad 1, 2, 4 or 8 channels per group on both sides (gconv_nchw.hip)
+bool gconv_nchw_supported(const GGeom &g);
+// flip = false: forward (in = x, out = y); flip = true: backward-data (in = dy, out = dx)
+hipError_t gconv_nchw_s1(const GGeom &g, int dtype, const void *in, const void *w, void *out, bool flip, hipStream_t st);
+int gconv_nchw_bwd_filter_parts(const GGeom &g);
+hipError_t gconv_nchw_bwd_filter(const GGeom &g, int dtype, const void *x, const void *dy, float *ws, int parts,
+                                 hipStream_t st);
+
+// ---- NHWC row-walk kernels, same shapes (gconv_nhwc.hip) ----------------------------------------------
+bool gconv_nhwc_supported(const GGeom &g);
+hipError_t gconv_nhwc_s1(const GGeom &g, int dtype, const void *in, const void *w, void *out, bool flip, hipStream_t st);
+int gconv_nhwc_bwd_filter_parts(const GGeom &g);
+hipError_t gconv_nhwc_bwd_filter(const GGeom &g, int dtype, const void *x, const void *dy, float *ws, int parts,
+                                 hipStream_t st);
+
+}  // namespace dwc

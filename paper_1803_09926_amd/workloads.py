@@ -196,3 +196,22 @@ def make_inputs_device(layer: Layer, N: int, layout: int, dtype: int, seed: int,
     w = (torch.randn(ws, generator=gen, device=device, dtype=torch.float32) / layer.K).to(tdt)
     dy = torch.randn(ys, generator=gen, device=device, dtype=torch.float32).to(tdt)
     return x, w, dy
+
+
+def make_group_inputs(N, C, O, groups, H, W, K, stride, pad, layout, dtype, seed):
+    """Inputs of a group convolution, as float32 numpy arrays in `layout`:
+    x [N,C,H,W] / [N,H,W,C] ~ N(0,1);  w [O,Cg,K,K] / [K,K,Cg,O] ~ N(0, 1/(K*K*Cg));  dy ~ N(0,1)."""
+    rng = np.random.default_rng(seed)
+    Cg = C // groups
+    Ho = (H + 2 * pad - K) // stride + 1
+    Wo = (W + 2 * pad - K) // stride + 1
+    x = rng.standard_normal((N, C, H, W), dtype=np.float32)
+    w = rng.standard_normal((O, Cg, K, K), dtype=np.float32) / np.float32(K * np.sqrt(Cg))
+    dy = rng.standard_normal((N, O, Ho, Wo), dtype=np.float32)
+    if dtype == BF16:
+        x, w, dy = round_to_bf16(x), round_to_bf16(w), round_to_bf16(dy)
+    if layout == NHWC:
+        x = np.ascontiguousarray(x.transpose(0, 2, 3, 1))
+        dy = np.ascontiguousarray(dy.transpose(0, 2, 3, 1))
+        w = np.ascontiguousarray(w.transpose(2, 3, 1, 0))
+    return x, w, dy

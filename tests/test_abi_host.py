@@ -17,7 +17,7 @@ A, B, Cp, Dp = 0x1000, 0x2000, 0x3000, 0x4000   # fake aligned "device" addresse
 
 def test_library_exports_every_declared_symbol():
     text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
-    declared = set(re.findall(r"\b(dwconv_[a-z_]+)\s*\(", text))
+    declared = set(re.findall(r"\b((?:dwconv|gconv)_[a-z_]+)\s*\(", text))
     assert declared == set(dw.EXPORTS), declared ^ set(dw.EXPORTS)
     lib = dw.load()
     for name in declared:
@@ -161,3 +161,66 @@ def test_whole_backward_variant_names():
     assert dw.variant_name(dw.desc(128, 512, 14, 14, 3, 2, 1, 1, dw.NCHW, dw.F32), 3) == "separate"      # stride 2
     assert dw.variant_name(dw.desc(128, 32, 112, 112, 3, 1, 1, 1, dw.NCHW, dw.BF16), 3) == "separate"
     assert dw.variant_name(dw.desc(2, 6, 9, 9, 3, 1, 1, 1, dw.NHWC, dw.F32), 3) == "separate"
+
+
+# ---- group convolution entry points --------------------------------------------------------------------
+
+def test_group_desc_struct_matches_header_field_order():
+    text = open(HEADER).read()
+    body = re.search(r"typedef struct dwconv_group_desc \{(.*?)\} dwconv_group_desc;", text, re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = []
+    for decl in re.findall(r"int32_t\s+([^;]+);", body):
+        fields += [f.strip() for f in decl.split(",")]
+    assert fields == [f[0] for f in dw.GroupDesc._fields_]
+    assert ctypes.sizeof(dw.GroupDesc) == 4 * len(fields)
+
+
+@pytest.mark.parametrize("field,value,code", [
+    ("N", 0, E_DIM), ("C", 0, E_DIM), ("H", 0, E_DIM), ("W", -3, E_DIM), ("K", 0, E_DIM), ("stride", 0, E_DIM),
+    ("pad", -1, E_DIM), ("groups", 0, E_DIM), ("O", 0, E_DIM), ("groups", 3, E_DIM), ("O", 10, E_DIM),
+    ("layout", 2, E_ENUM), ("dtype", -1, E_ENUM), ("K", 16, E_UNSUP), ("N", 1 << 20, E_LARGE),
+])
+def test_group_bad_descriptors(field, value, code):
+    d = dw.group_desc(2, 8, 16, 16, groups=4, O=8)
+    setattr(d, field, value)
+    lib = dw.load()
+    assert lib.gconv_out_dims(ctypes.byref(d), None, None) == code
+    assert lib.gconv_fwd(ctypes.byref(d), A, B, Cp, None) == code
+    assert lib.gconv_bwd_data(ctypes.byref(d), A, B, Cp, None) == code
+    assert lib.gconv_bwd_filter(ctypes.byref(d), A, B, Cp, Dp, 1 << 30, None) == code
+    assert dw.gconv_bwd_filter_workspace_bytes(d) == 0
+    assert dw.gconv_variant_name(d, 0) == "invalid"
+
+
+def test_group_null_misaligned_and_workspace_errors():
+    lib = dw.load()
+    for layout in (dw.NCHW, dw.NHWC):
+        for groups in (2, 8):                    # 4 channels per group, and the depthwise special case
+            d = dw.group_desc(2, 8, 16, 16, groups=groups, O=8, layout=layout)
+            ref = ctypes.byref(d)
+            assert lib.gconv_fwd(None, A, B, Cp, None) == E_NULL
+            for args in [(None, B, Cp), (A, None, Cp), (A, B, None)]:
+                assert lib.gconv_fwd(ref, *args, None) == E_NULL
+                assert lib.gconv_bwd_data(ref, *args, None) == E_NULL
+                assert lib.gconv_bwd_filter(ref, *args, Dp, 1 << 30, None) == E_NULL
+            for args in [(A + 4, B, Cp), (A, B + 8, Cp), (A, B, Cp + 2)]:
+                assert lib.gconv_fwd(ref, *args, None) == E_ALIGN
+                assert lib.gconv_bwd_data(ref, *args, None) == E_ALIGN
+                assert lib.gconv_bwd_filter(ref, *args, Dp, 1 << 30, None) == E_ALIGN
+            need = dw.gconv_bwd_filter_workspace_bytes(d)
+            assert 0 < need <= (64 << 20)
+            assert lib.gconv_bwd_filter(ref, A, B, Cp, None, need, None) == E_WS
+            assert lib.gconv_bwd_filter(ref, A, B, Cp, Dp, need - 1, None) == E_WS
+
+
+def test_group_variants_and_depthwise_delegation():
+    assert dw.gconv_out_dims(dw.group_desc(1, 8, 7, 9, 3, 2, 1, groups=2, O=4)) == (4, 5)
+    # one channel per group is the depthwise layer (here with multiplier 2) and reports its variant
+    d = dw.group_desc(128, 32, 112, 112, groups=32, O=32, layout=dw.NHWC)
+    assert dw.gconv_variant_name(d, 0) == dw.variant_name(dw.desc(128, 32, 112, 112, layout=dw.NHWC), 0)
+    d = dw.group_desc(8, 16, 20, 20, groups=16, O=32, layout=dw.NCHW)
+    assert dw.gconv_variant_name(d, 2) == dw.variant_name(dw.desc(8, 16, 20, 20, mult=2), 2)
+    # untuned group shapes fall back to the generic group kernels
+    assert dw.gconv_variant_name(dw.group_desc(2, 12, 9, 9, 5, 1, 2, groups=4, O=12), 0) == "group_generic"
+    assert dw.gconv_variant_name(dw.group_desc(2, 12, 9, 9, 3, 2, 1, groups=4, O=12, layout=dw.NHWC), 1) == "group_generic"
