@@ -27,7 +27,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, help="workload index 0..5 (default 2: the headline one; 5: MobileNet variant shapes)")
+    ap.add_argument("--config", type=int, default=2,
+                    help="workload index 0..6 (default 2: the headline one; 5: MobileNet variant shapes; 6: group convolutions)")
     ap.add_argument("--order", choices=["layer", "train"], default="layer",
                     help="launch order inside a step: layer by layer (fwd, bwd_filter, bwd_data of each), or as "
                          "a training step runs them (all forwards, then the backward passes from the last layer up)")
@@ -74,11 +75,22 @@ def build_ops(dw, wl, cfg, torch, order="layer", side=None, fused_bwd=False):
                 else: fwd_ops.append(f); bwd_ops.append((bf, bd))
                 continue
             x, w, dy = wl.make_inputs_device(layer, cfg["N"], layout, cfg["dtype"], seed=1000 * 7 + li + 131 * si)
-            d = dw.desc(cfg["N"], layer.C, layer.H, layer.W, layer.K, layer.stride, layer.pad, layer.mult,
-                        layout, cfg["dtype"])
+            grouped = layer.cg > 1          # a group convolution: the gconv_* entry points
+            if grouped:
+                if fused_bwd:
+                    raise SystemExit("bench.py: --fused-bwd has no group-convolution entry point")
+                d = dw.group_desc(cfg["N"], layer.C, layer.H, layer.W, layer.K, layer.stride, layer.pad, layer.groups,
+                                  layer.O, layout, cfg["dtype"])
+                f_fwd, f_bd, f_bf = lib.gconv_fwd, lib.gconv_bwd_data, lib.gconv_bwd_filter
+                ws_bytes, vname = dw.gconv_bwd_filter_workspace_bytes(d), dw.gconv_variant_name
+            else:
+                d = dw.desc(cfg["N"], layer.C, layer.H, layer.W, layer.K, layer.stride, layer.pad, layer.mult,
+                            layout, cfg["dtype"])
+                f_fwd, f_bd, f_bf = lib.dwconv_fwd, lib.dwconv_bwd_data, lib.dwconv_bwd_filter
+                ws_bytes, vname = dw.bwd_filter_workspace_bytes(d), dw.variant_name
             y = torch.empty_like(dy); dx = torch.empty_like(x)
             dwt = torch.empty(w.shape, device="cuda", dtype=torch.float32)
-            ws = torch.empty(max(dw.bwd_filter_workspace_bytes(d), 16), device="cuda", dtype=torch.uint8)
+            ws = torch.empty(max(ws_bytes, 16), device="cuda", dtype=torch.uint8)
             nbytes = layer.pass_bytes(cfg["N"], esz)
             common = dict(layer=layer.name, li=li, layout="NCHW" if layout == wl.NCHW else "NHWC",
                           bytes=nbytes, repeat=repeat, stride=layer.stride, H=layer.H)
@@ -89,20 +101,20 @@ def build_ops(dw, wl, cfg, torch, order="layer", side=None, fused_bwd=False):
             nws = ctypes.c_size_t(ws.numel())
             keep = (d, x, w, dy, y, dx, dwt, ws)
 
-            def run_fwd(dref=dref, px=px, pw=pw, py=py, keep=keep):
-                rc = lib.dwconv_fwd(dref, px, pw, py, stream)
+            def run_fwd(dref=dref, px=px, pw=pw, py=py, keep=keep, f_fwd=f_fwd):
+                rc = f_fwd(dref, px, pw, py, stream)
                 if rc: raise dw.DwconvError(rc, "dwconv_fwd")
 
-            def run_bwd_data(dref=dref, pdy=pdy, pw=pw, pdx=pdx, keep=keep):
-                rc = lib.dwconv_bwd_data(dref, pdy, pw, pdx, stream)
+            def run_bwd_data(dref=dref, pdy=pdy, pw=pw, pdx=pdx, keep=keep, f_bd=f_bd):
+                rc = f_bd(dref, pdy, pw, pdx, stream)
                 if rc: raise dw.DwconvError(rc, "dwconv_bwd_data")
 
-            def run_bwd_filter(dref=dref, px=px, pdy=pdy, pdw=pdw, pws=pws, nws=nws, keep=keep):
-                rc = lib.dwconv_bwd_filter(dref, px, pdy, pdw, pws, nws, stream)
+            def run_bwd_filter(dref=dref, px=px, pdy=pdy, pdw=pdw, pws=pws, nws=nws, keep=keep, f_bf=f_bf):
+                rc = f_bf(dref, px, pdy, pdw, pws, nws, stream)
                 if rc: raise dw.DwconvError(rc, "dwconv_bwd_filter")
 
-            def run_bwd_filter_side(dref=dref, px=px, pdy=pdy, pdw=pdw, pws=pws, nws=nws, keep=keep):
-                rc = lib.dwconv_bwd_filter(dref, px, pdy, pdw, pws, nws, stream2)
+            def run_bwd_filter_side(dref=dref, px=px, pdy=pdy, pdw=pdw, pws=pws, nws=nws, keep=keep, f_bf=f_bf):
+                rc = f_bf(dref, px, pdy, pdw, pws, nws, stream2)
                 if rc: raise dw.DwconvError(rc, "dwconv_bwd_filter")
 
             # order within a layer: forward, filter gradient, input gradient.  The two backward passes
@@ -114,9 +126,9 @@ def build_ops(dw, wl, cfg, torch, order="layer", side=None, fused_bwd=False):
                 rc = lib.dwconv_bwd(dref, px, pdy, pw, pdx, pdw, pwsb, nwsb, stream)
                 if rc: raise dw.DwconvError(rc, "dwconv_bwd")
 
-            f = dict(common, which=0, variant=dw.variant_name(d, 0), run=run_fwd)
-            bf = dict(common, which=2, variant=dw.variant_name(d, 2), run=run_bwd_filter, run_side=run_bwd_filter_side)
-            bd = dict(common, which=1, variant=dw.variant_name(d, 1), run=run_bwd_data)
+            f = dict(common, which=0, variant=vname(d, 0), run=run_fwd)
+            bf = dict(common, which=2, variant=vname(d, 2), run=run_bwd_filter, run_side=run_bwd_filter_side)
+            bd = dict(common, which=1, variant=vname(d, 1), run=run_bwd_data)
             b = None
             if fused_bwd:
                 vname = dw.variant_name(d, 3)
@@ -236,25 +248,40 @@ def cpu_baseline(wl, cfg):
     esz = 4 if cfg["dtype"] == wl.F32 else 2
     for layout in cfg["layouts"]:
         for li, (layer, repeat) in enumerate(cfg["layers"]):
-            x, w, dy = wl.make_inputs(layer, Ns, layout, cfg["dtype"], seed=li)
+            if layer.cg > 1:
+                from oracle import gconv as orc
+                x, w, dy = wl.make_group_inputs(Ns, layer.C, layer.O, layer.groups, layer.H, layer.W, layer.K,
+                                                layer.stride, layer.pad, layout, cfg["dtype"], seed=li)
+                kw = dict(K=layer.K, stride=layer.stride, pad=layer.pad, groups=layer.groups, O=layer.O, layout=layout,
+                          nthreads=cores)
+            else:
+                orc = oracle
+                x, w, dy = wl.make_inputs(layer, Ns, layout, cfg["dtype"], seed=li)
+                kw = dict(K=layer.K, stride=layer.stride, pad=layer.pad, mult=layer.mult, layout=layout, nthreads=cores)
             x64, w64, dy64 = x.astype(np.float64), w.astype(np.float64), dy.astype(np.float64)
             del x, dy
-            kw = dict(K=layer.K, stride=layer.stride, pad=layer.pad, mult=layer.mult, layout=layout, nthreads=cores)
             t0 = time.perf_counter()
-            oracle.fwd(x64, w64, **kw)
-            oracle.bwd_data(dy64, w64, x_shape=x64.shape, **kw)
-            oracle.bwd_filter(x64, dy64, **kw)
+            orc.fwd(x64, w64, **kw)
+            orc.bwd_data(dy64, w64, x_shape=x64.shape, **kw)
+            orc.bwd_filter(x64, dy64, **kw)
             total_s += (time.perf_counter() - t0) * repeat
             total_bytes += 3 * layer.pass_bytes(Ns, esz) * repeat
             del x64, dy64
     # one thread, on one mid-sized layer (the oracle is the same loop nest; only the outer loop is split)
     mid = cfg["layers"][len(cfg["layers"]) // 2][0]
     Nm = min(cfg["N"], 32)
-    x, w, dy = wl.make_inputs(mid, Nm, cfg["layouts"][-1], cfg["dtype"], seed=99)
+    if mid.cg > 1:
+        from oracle import gconv as orc
+        x, w, dy = wl.make_group_inputs(Nm, mid.C, mid.O, mid.groups, mid.H, mid.W, mid.K, mid.stride, mid.pad,
+                                        cfg["layouts"][-1], cfg["dtype"], seed=99)
+        kw = dict(K=mid.K, stride=mid.stride, pad=mid.pad, groups=mid.groups, O=mid.O, layout=cfg["layouts"][-1], nthreads=1)
+    else:
+        orc = oracle
+        x, w, dy = wl.make_inputs(mid, Nm, cfg["layouts"][-1], cfg["dtype"], seed=99)
+        kw = dict(K=mid.K, stride=mid.stride, pad=mid.pad, mult=mid.mult, layout=cfg["layouts"][-1], nthreads=1)
     x64, w64, dy64 = x.astype(np.float64), w.astype(np.float64), dy.astype(np.float64)
-    kw = dict(K=mid.K, stride=mid.stride, pad=mid.pad, mult=mid.mult, layout=cfg["layouts"][-1], nthreads=1)
     t0 = time.perf_counter()
-    oracle.fwd(x64, w64, **kw); oracle.bwd_data(dy64, w64, x_shape=x64.shape, **kw); oracle.bwd_filter(x64, dy64, **kw)
+    orc.fwd(x64, w64, **kw); orc.bwd_data(dy64, w64, x_shape=x64.shape, **kw); orc.bwd_filter(x64, dy64, **kw)
     single = 3 * mid.pass_bytes(Nm, esz) / (time.perf_counter() - t0) / 1e9
     return dict(value=total_bytes / total_s / 1e9, unit="GB/s", cores=cores, kind="oracle",
                 single_thread_GBps=round(single, 3), single_thread_sample="%s, batch %d, three passes" % (mid.name, Nm),

@@ -1,7 +1,420 @@
+// Group convolution, NCHW, 3x3 stride 1 pad 1, rows that are whole 4-column vectors; any number of channels
+// per group on either side.
+//
+// Forward / backward-data (k_gconv_nchw_s1): a block works on one group and OB of its output channels; a
+// lane owns 4 consecutive columns of one (image, strip) and walks the strip's rows.  The group's filters sit
+// in LDS as [input channel][tap][output channel]: every lane of the block reads the same entries (a
+// broadcast).  One step of the walk takes one row of ONE input channel: three loads (the 4-column vector and
+// its two neighbours), 9*OB weights from LDS, 36*OB multiply-adds into three rotating rows of accumulators.
+// The loop over input channels is a real loop, so the kernel serves any group size, and the next step's row
+// is loaded before the current one is used.  Input rows above and below a strip feed only one output row:
+// the other two thirds of their arithmetic are skipped (the step index is uniform over the block).
+// Backward-data is the same walk over dy with the roles of the channels swapped and the taps reversed.
+//
+// Filter gradient (k_gconv_nchw_bwd_filter): a block works on one input channel b of a group and OB of the
+// group's output channels; a lane owns 4 columns of (image, strip) items and keeps 9*OB sums.  Per output row
+// it loads that row of the OB dy planes and one new row of x (a window of three x rows rotates), 36*OB
+// multiply-adds.  At the end the sums are added over the wavefront (butterfly), over the four wavefronts
+// through LDS, and the block writes one partial per weight entry; the shared second stage adds the partials.
 #include "gconv.hpp"
+
 namespace dwc {
-bool gconv_nchw_supported(const GGeom &) { return false; }
-hipError_t gconv_nchw_s1(const GGeom &, int, const void *, const void *, void *, bool, hipStream_t) { return hipErrorInvalidValue; }
-int gconv_nchw_bwd_filter_parts(const GGeom &) { return 0; }
-hipError_t gconv_nchw_bwd_filter(const GGeom &, int, const void *, const void *, float *, int, hipStream_t) { return hipErrorInvalidValue; }
+
+template <int OB> struct LdsW;
+template <> struct LdsW<4> {
+    static __device__ __forceinline__ void get(const float *p, float (&r)[4])
+    {
+        const float4 q = *reinterpret_cast<const float4 *>(p);
+        r[0] = q.x; r[1] = q.y; r[2] = q.z; r[3] = q.w;
+    }
+};
+template <> struct LdsW<2> {
+    static __device__ __forceinline__ void get(const float *p, float (&r)[2])
+    {
+        const float2 q = *reinterpret_cast<const float2 *>(p);
+        r[0] = q.x; r[1] = q.y;
+    }
+};
+template <> struct LdsW<1> {
+    static __device__ __forceinline__ void get(const float *p, float (&r)[1]) { r[0] = *p; }
+};
+
+// One row of one plane as a lane sees it: its V columns and the two neighbours, as loaded.
+template <typename T, int V> struct RowIn {
+    RawVec<T, V> v;
+    T l, r;
+    __device__ __forceinline__ void load(const T *row, int col0, int W)
+    {
+        v.load(row + col0);
+        l = row[max(col0 - 1, 0)];
+        r = row[min(col0 + V, W - 1)];
+    }
+    // x[0..V+1] = columns col0-1 .. col0+V, zero outside the row or when the row itself is outside the image
+    __device__ __forceinline__ void get(float (&x)[V + 2], bool rowok, int col0, int W) const
+    {
+        float c[V];
+        v.get(c);
+        x[0] = (rowok && col0 > 0) ? ldf(&l) : 0.f;
+        x[V + 1] = (rowok && col0 + V < W) ? ldf(&r) : 0.f;
+#pragma unroll
+        for (int j = 0; j < V; ++j) x[1 + j] = rowok ? c[j] : 0.f;
+    }
+};
+
+// R = steps loaded ahead (a ring of R rows in registers, R divides CI); the walk is the flat sequence of
+// (input row t, input channel b) steps.  The three rows of accumulators change roles from one input row to
+// the next; the row loop is unrolled by three so that this costs no register moves.
+template <typename T, int V, int OB, int R, bool FLIP>
+__global__ __launch_bounds__(256) void k_gconv_nchw_s1(GGeom g, const T *__restrict__ in, const T *__restrict__ w,
+                                                       T *__restrict__ out, int CI, int CO, int CIN_T, int COUT_T, int TH,
+                                                       int nstrips, int ncv, int nlanes, int nlb, unsigned nblocks, int nt)
+{
+    extern __shared__ __align__(16) float wl[];     // [CI][3][3][OB]: input channel, tap row, tap column, output
+    unsigned lb = xcd_remap(blockIdx.x, nblocks);
+    const int nchunks = CO / OB;
+    const int chunk = lb % nchunks; lb /= nchunks;
+    const int lblk = lb % nlb; const int grp = lb / nlb;
+
+    for (int i = threadIdx.x; i < CI * 9 * OB; i += 256) {
+        const int a = i % OB, tap = (i / OB) % 9, b = i / (9 * OB);
+        int widx;
+        if (!FLIP) widx = ((grp * g.Og + chunk * OB + a) * g.Cg + b) * 9 + tap;          // output a, input b
+        else       widx = ((grp * g.Og + b) * g.Cg + chunk * OB + a) * 9 + (8 - tap);    // dx channel a, dy channel b
+        wl[i] = ldf(w + widx);
+    }
+    __syncthreads();
+
+    const int H = g.H, W = g.W, HW = H * W;
+    const int idx = lblk * 256 + threadIdx.x;
+    const bool active = idx < nlanes;
+    const int id = min(idx, nlanes - 1);
+    const int cv = id % ncv, t1 = id / ncv, strip = t1 % nstrips, n = t1 / nstrips;
+    const int col0 = cv * V, oh0 = strip * TH, oh1 = min(H, oh0 + TH);
+    const T *ibase = in + ((size_t)n * CIN_T + (size_t)grp * CI) * HW;
+    T *obase = out + ((size_t)n * COUT_T + (size_t)grp * CO + chunk * OB) * HW + col0;
+
+    float A0[OB][V], A1[OB][V], A2[OB][V];
+#pragma unroll
+    for (int a = 0; a < OB; ++a)
+#pragma unroll
+        for (int j = 0; j < V; ++j) { A0[a][j] = 0.f; A1[a][j] = 0.f; A2[a][j] = 0.f; }
+
+    RowIn<T, V> ring[R];
+    int lt = 0, lbb = 0;                // (row step, channel) of the next load; uniform over the block
+    auto issue = [&](RowIn<T, V> &slot) {
+        const int rn = min(max(oh0 - 1 + lt, 0), H - 1);      // clamped: loads past the walk's end are unused
+        slot.load(ibase + (size_t)lbb * HW + (size_t)rn * W, col0, W);
+        if (++lbb == CI) { lbb = 0; ++lt; }
+    };
+#pragma unroll
+    for (int j = 0; j < R; ++j) issue(ring[j]);
+
+    // tap row kh of input row t feeds output row t - kh (in strip-local step numbers: step t is input row
+    // oh0 - 1 + t, and output row oh0 + t - 2 is complete after it)
+    // The filters are read from LDS one (input channel, tap row) at a time: 3*OB values, the same for every
+    // lane.  The read for the next sub-step is issued before the current sub-step's 3*OB*V multiply-adds,
+    // so its latency is hidden; wn always holds the next sub-step's weights (those of sub-step 0 between rows).
+    float wn[3][OB];
+    auto wread = [&](int q) {
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) LdsW<OB>::get(wl + (q * 3 + kw) * OB, wn[kw]);
+    };
+    wread(0);
+    auto fma_row = [&](float (&P)[OB][V], const float (&wc)[3][OB], const float (&x)[V + 2]) {
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw)
+#pragma unroll
+            for (int a = 0; a < OB; ++a)
+#pragma unroll
+                for (int q = 0; q < V; ++q) P[a][q] = fmaf(wc[kw][a], x[q + kw], P[a][q]);
+    };
+    // One input row, all CI channels.  P2 collects tap row 0 (a fresh output row), P1 tap row 1, P0 tap row 2
+    // (the output row that is complete afterwards: stored, then cleared for its next role).
+    auto row_pass = [&](float (&P0)[OB][V], float (&P1)[OB][V], float (&P2)[OB][V], int t) {
+        const int r = oh0 - 1 + t;
+        const bool rowok = r >= 0 && r < H;
+        const bool f0 = t <= TH - 1, f1 = t >= 1 && t <= TH, f2 = t >= 2;   // uniform: the output rows this row feeds
+#pragma unroll 1
+        for (int b0 = 0; b0 < CI; b0 += R) {
+            // all R rows out of the ring first, then the next R loads into it, then the arithmetic: the loads
+            // have the whole group's arithmetic to arrive, also when the wait at the top of the next group
+            // is for every outstanding load
+            float xs[R][V + 2];
+#pragma unroll
+            for (int j = 0; j < R; ++j) ring[j].get(xs[j], rowok, col0, W);
+#pragma unroll
+            for (int j = 0; j < R; ++j) issue(ring[j]);
+            if (f0 && f1 && f2) {               // an interior row
+#pragma unroll
+                for (int j = 0; j < R; ++j) {
+#pragma unroll
+                    for (int kh = 0; kh < 3; ++kh) {
+                        float wc[3][OB];
+#pragma unroll
+                        for (int kw = 0; kw < 3; ++kw)
+#pragma unroll
+                            for (int a = 0; a < OB; ++a) wc[kw][a] = wn[kw][a];
+                        int qn = (b0 + j) * 3 + kh + 1;
+                        if (qn == 3 * CI) qn = 0;
+                        wread(qn);
+                        fma_row(kh == 0 ? P2 : (kh == 1 ? P1 : P0), wc, xs[j]);
+                        __builtin_amdgcn_sched_barrier(0);      // keeps the reads one sub-step ahead, not more
+                    }
+                }
+            } else {                            // first two and last two rows of the strip: unpipelined
+#pragma unroll
+                for (int j = 0; j < R; ++j) {
+                    float wc[3][OB];
+                    if (f0) {
+#pragma unroll
+                        for (int kw = 0; kw < 3; ++kw) LdsW<OB>::get(wl + (((b0 + j) * 3 + 0) * 3 + kw) * OB, wc[kw]);
+                        fma_row(P2, wc, xs[j]);
+                    }
+                    if (f1) {
+#pragma unroll
+                        for (int kw = 0; kw < 3; ++kw) LdsW<OB>::get(wl + (((b0 + j) * 3 + 1) * 3 + kw) * OB, wc[kw]);
+                        fma_row(P1, wc, xs[j]);
+                    }
+                    if (f2) {
+#pragma unroll
+                        for (int kw = 0; kw < 3; ++kw) LdsW<OB>::get(wl + (((b0 + j) * 3 + 2) * 3 + kw) * OB, wc[kw]);
+                        fma_row(P0, wc, xs[j]);
+                    }
+                }
+            }
+        }
+        const int orow = r - 1;
+        if (f2 && active && orow < oh1) {
+#pragma unroll
+            for (int a = 0; a < OB; ++a) store_vec<T, V>(obase + (size_t)a * HW + (size_t)orow * W, P0[a], nt != 0);
+        }
+#pragma unroll
+        for (int a = 0; a < OB; ++a)
+#pragma unroll
+            for (int q = 0; q < V; ++q) P0[a][q] = 0.f;
+    };
+#pragma unroll 1
+    for (int t = 0; t < TH + 2; t += 3) {
+        row_pass(A0, A1, A2, t);
+        if (t + 1 < TH + 2) row_pass(A1, A2, A0, t + 1);
+        if (t + 2 < TH + 2) row_pass(A2, A0, A1, t + 2);
+    }
 }
+
+// Filter gradient, stage 1.  Block: (group, input channel b, chunk of OB output channels, part).
+template <typename T, int V, int OB>
+__global__ __launch_bounds__(256) void k_gconv_nchw_bwd_filter(GGeom g, const T *__restrict__ x, const T *__restrict__ dy,
+                                                               float *__restrict__ ws, int TH, int nstrips, int ncv,
+                                                               int nitems, int parts, unsigned nblocks, int J)
+{
+    __shared__ float red[4][9 * OB];
+    unsigned lb = xcd_remap(blockIdx.x, nblocks);
+    const int nchunks = g.Og / OB;
+    const int b = lb % g.Cg; lb /= g.Cg;
+    const int chunk = lb % nchunks; lb /= nchunks;
+    const int part = lb % parts; const int grp = lb / parts;
+
+    const int H = g.H, W = g.W, HW = H * W;
+    float acc[OB][3][3];
+#pragma unroll
+    for (int a = 0; a < OB; ++a)
+#pragma unroll
+        for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw) acc[a][kh][kw] = 0.f;
+
+    for (int item = part * 256 + threadIdx.x; item < nitems; item += parts * 256) {
+        const int cv = item % ncv, t1 = item / ncv, strip = t1 % nstrips, n = t1 / nstrips;
+        const int col0 = cv * V, oh0 = strip * TH, oh1 = min(H, oh0 + TH);
+        const T *xp = x + ((size_t)n * g.C + (size_t)grp * g.Cg + b) * HW;
+        const T *dp = dy + ((size_t)n * g.O + (size_t)grp * g.Og + chunk * OB) * HW + col0;
+
+        // window of three x rows: X0 = row oh-1, X1 = row oh, X2 = row oh+1
+        float X0[V + 2], X1[V + 2], X2[V + 2];
+        {
+            RowIn<T, V> q;
+            q.load(xp + (size_t)max(oh0 - 1, 0) * W, col0, W);
+            q.get(X1, oh0 - 1 >= 0, col0, W);
+            q.load(xp + (size_t)oh0 * W, col0, W);
+            q.get(X2, true, col0, W);
+        }
+        // two output rows ahead: slot j holds x row oh+1 and the dy rows oh of output row oh = oh0 + j (mod 2)
+        RowIn<T, V> xn[2];
+        RawVec<T, V> dn[2][OB];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            xn[j].load(xp + (size_t)min(oh0 + j + 1, H - 1) * W, col0, W);
+#pragma unroll
+            for (int a = 0; a < OB; ++a) dn[j][a].load(dp + (size_t)a * HW + (size_t)min(oh0 + j, H - 1) * W);
+        }
+        for (int oh = oh0; oh < oh1; oh += 2) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int cur = oh + j;
+                const bool valid = cur < oh1;           // an odd strip height leaves one empty step at the end
+#pragma unroll
+                for (int q = 0; q < V + 2; ++q) { X0[q] = X1[q]; X1[q] = X2[q]; }
+                xn[j].get(X2, cur + 1 < H, col0, W);
+                float d[OB][V];
+#pragma unroll
+                for (int a = 0; a < OB; ++a) {
+                    dn[j][a].get(d[a]);
+#pragma unroll
+                    for (int q = 0; q < V; ++q) d[a][q] = valid ? d[a][q] : 0.f;
+                }
+                xn[j].load(xp + (size_t)min(cur + 3, H - 1) * W, col0, W);
+#pragma unroll
+                for (int a = 0; a < OB; ++a) dn[j][a].load(dp + (size_t)a * HW + (size_t)min(cur + 2, H - 1) * W);
+#pragma unroll
+                for (int a = 0; a < OB; ++a)
+#pragma unroll
+                    for (int kw = 0; kw < 3; ++kw)
+#pragma unroll
+                        for (int q = 0; q < V; ++q) {
+                            acc[a][0][kw] = fmaf(d[a][q], X0[q + kw], acc[a][0][kw]);
+                            acc[a][1][kw] = fmaf(d[a][q], X1[q + kw], acc[a][1][kw]);
+                            acc[a][2][kw] = fmaf(d[a][q], X2[q + kw], acc[a][2][kw]);
+                        }
+            }
+        }
+    }
+
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+#pragma unroll
+    for (int a = 0; a < OB; ++a)
+#pragma unroll
+        for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw) {
+                const float s = wave_sum(acc[a][kh][kw]);
+                if (lane == 0) red[wv][(a * 3 + kh) * 3 + kw] = s;
+            }
+    __syncthreads();
+    if (threadIdx.x < 9 * OB) {
+        const int e = threadIdx.x, a = e / 9, tap = e % 9;
+        const int o = grp * g.Og + chunk * OB + a;
+        ws[(size_t)part * J + ((size_t)o * g.Cg + b) * 9 + tap] = (red[0][e] + red[1][e]) + (red[2][e] + red[3][e]);
+    }
+}
+
+// ---- host side ---------------------------------------------------------------------------------------------
+
+static int pick_ob(int CO) { return CO % 4 == 0 ? 4 : (CO % 2 == 0 ? 2 : 1); }
+static int pick_v(int W) { return W % 4 == 0 ? 4 : (W % 2 == 0 ? 2 : 0); }
+static int gtune(const char *name, int dflt)
+{
+    const char *e = getenv(name);
+    return e && *e ? atoi(e) : dflt;
+}
+
+bool gconv_nchw_supported(const GGeom &g)
+{
+    if (!(g.K == 3 && g.s == 1 && g.p == 1)) return false;
+    if (pick_v(g.W) == 0) return false;
+    // the group's filters for one block have to fit in LDS with room to spare
+    const int ob_f = pick_ob(g.Og), ob_b = pick_ob(g.Cg);
+    if ((long long)g.Cg * 9 * ob_f * 4 > 32768 || (long long)g.Og * 9 * ob_b * 4 > 32768) return false;
+    return true;
+}
+
+// strip height: the tallest of whole plane / 28 / 14 / 7 rows that still gives the launch about two
+// blocks per compute unit
+static int gconv_pick_th(const GGeom &g, long long blocks_per_lane_block_row)
+{
+    const int forced = gtune("DWCONV_TUNE_GTH", 0);
+    if (forced > 0) return forced < g.H ? forced : g.H;
+    const int cands[4] = {g.H, 28, 14, 7};
+    const int ncv = g.W / pick_v(g.W);
+    const long long want = gtune("DWCONV_TUNE_GBLOCKS", 512);
+    for (int i = 0; i < 4; ++i) {
+        const int th = cands[i] < g.H ? cands[i] : g.H;
+        const long long nlanes = (long long)g.N * ((g.H + th - 1) / th) * ncv;
+        if (((nlanes + 255) / 256) * blocks_per_lane_block_row >= want) return th;
+    }
+    return g.H < 7 ? g.H : 7;
+}
+
+hipError_t gconv_nchw_s1(const GGeom &g, int dtype, const void *in, const void *w, void *out, bool flip, hipStream_t st)
+{
+    if (!gconv_nchw_supported(g)) return hipErrorInvalidValue;
+    const int CI = flip ? g.Og : g.Cg, CO = flip ? g.Cg : g.Og;
+    const int CIN_T = flip ? g.O : g.C, COUT_T = flip ? g.C : g.O;
+    const int OB = pick_ob(CO), V = pick_v(g.W);
+    const int nchunks = CO / OB;
+    const int TH = gconv_pick_th(g, (long long)g.G * nchunks);
+    const int nstrips = (g.H + TH - 1) / TH, ncv = g.W / V;
+    const long long nl = (long long)g.N * nstrips * ncv;
+    const long long nlb = (nl + 255) / 256;
+    const long long nb = nlb * g.G * nchunks;
+    if (nl >= (1ll << 31) || nb >= (1ll << 31)) return hipErrorInvalidValue;
+    const int nlanes = (int)nl;
+    const unsigned nblocks = (unsigned)nb;
+    const size_t lds = (size_t)CI * 9 * OB * sizeof(float);
+    const int esz = dtype == DT_F32 ? 4 : 2;
+    const int nt = stream_stores(flip ? "GROUP_NCHW_BWD" : "GROUP_NCHW_FWD", (long long)g.N * COUT_T * g.H * g.W * esz);
+    int R = CI % 2 == 0 ? 2 : 1;      // two steps ahead keeps the kernel within 128 registers
+    const int rforce = gtune("DWCONV_TUNE_GR", 0);
+    if (rforce > 0 && CI % rforce == 0) R = rforce;
+#define GO5(T, VV, OBB, RR, FL)                                                                                             \
+    hipLaunchKernelGGL((k_gconv_nchw_s1<T, VV, OBB, RR, FL>), dim3(nblocks), dim3(256), lds, st, g, (const T *)in,          \
+                       (const T *)w, (T *)out, CI, CO, CIN_T, COUT_T, TH, nstrips, ncv, nlanes, (int)nlb, nblocks, nt)
+#define GO4(T, VV, OBB, RR) do { if (flip) GO5(T, VV, OBB, RR, true); else GO5(T, VV, OBB, RR, false); } while (0)
+#define GO3(T, VV, OBB) do { if (R == 4) GO4(T, VV, OBB, 4); else if (R == 2) GO4(T, VV, OBB, 2); else GO4(T, VV, OBB, 1); } while (0)
+#define GO2(T, VV) do { if (OB == 4) GO3(T, VV, 4); else if (OB == 2) GO3(T, VV, 2); else GO3(T, VV, 1); } while (0)
+    if (dtype == DT_F32) { if (V == 4) GO2(float, 4); else GO2(float, 2); }
+    else                 { if (V == 4) GO2(bf16_t, 4); else GO2(bf16_t, 2); }
+#undef GO2
+#undef GO3
+#undef GO4
+#undef GO5
+    return hipGetLastError();
+}
+
+// Filter-gradient tiling: strip height, and partials per weight entry (each part = 256 lanes that stride
+// over the (image, strip, column-vector) items).
+static void gconv_nchw_bwd_filter_tiling(const GGeom &g, int *TH, int *nstrips, int *nitems, int *parts)
+{
+    const int OB = pick_ob(g.Og);
+    const long long per_part_row = (long long)g.G * g.Cg * (g.Og / OB);
+    const int th = gconv_pick_th(g, per_part_row);
+    const int ns = (g.H + th - 1) / th;
+    const long long ni = (long long)g.N * ns * (g.W / pick_v(g.W));
+    // about 2048 blocks in the launch, each lane with at least one item, at most 64 partials
+    long long p = (gtune("DWCONV_TUNE_GWBLOCKS", 2048) + per_part_row - 1) / per_part_row;
+    const long long maxp = (ni + 255) / 256;
+    if (p > maxp) p = maxp;
+    if (p > 64) p = 64;
+    if (p < 1) p = 1;
+    *TH = th; *nstrips = ns; *nitems = (int)(ni < (1ll << 31) ? ni : 0); *parts = (int)p;
+}
+
+int gconv_nchw_bwd_filter_parts(const GGeom &g)
+{
+    int TH, ns, ni, parts;
+    gconv_nchw_bwd_filter_tiling(g, &TH, &ns, &ni, &parts);
+    return parts;
+}
+
+hipError_t gconv_nchw_bwd_filter(const GGeom &g, int dtype, const void *x, const void *dy, float *ws, int parts,
+                                 hipStream_t st)
+{
+    if (!gconv_nchw_supported(g)) return hipErrorInvalidValue;
+    int TH, nstrips, nitems, p2;
+    gconv_nchw_bwd_filter_tiling(g, &TH, &nstrips, &nitems, &p2);
+    if (p2 != parts || nitems < 1) return hipErrorInvalidValue;
+    const int OB = pick_ob(g.Og), V = pick_v(g.W);
+    const long long nb = (long long)g.G * parts * (g.Og / OB) * g.Cg;
+    if (nb >= (1ll << 31)) return hipErrorInvalidValue;
+    const unsigned nblocks = (unsigned)nb;
+    const int J = g.O * g.Cg * 9;
+#define GO3(T, VV, OBB) hipLaunchKernelGGL((k_gconv_nchw_bwd_filter<T, VV, OBB>), dim3(nblocks), dim3(256), 0, st, g,      \
+                                           (const T *)x, (const T *)dy, ws, TH, nstrips, g.W / VV, nitems, parts, nblocks, J)
+#define GO2(T, VV) do { if (OB == 4) GO3(T, VV, 4); else if (OB == 2) GO3(T, VV, 2); else GO3(T, VV, 1); } while (0)
+    if (dtype == DT_F32) { if (V == 4) GO2(float, 4); else GO2(float, 2); }
+    else                 { if (V == 4) GO2(bf16_t, 4); else GO2(bf16_t, 2); }
+#undef GO2
+#undef GO3
+    return hipGetLastError();
+}
+
+}  // namespace dwc

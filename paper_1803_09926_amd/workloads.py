@@ -34,10 +34,15 @@ class Layer:
     stride: int = 1
     pad: int = 1
     mult: int = 1
+    cg: int = 1          # input (= output) channels per group; 1 is the depthwise layer, > 1 a group convolution
 
     @property
     def O(self) -> int:
         return self.C * self.mult
+
+    @property
+    def groups(self) -> int:
+        return self.C // self.cg
 
     @property
     def Ho(self) -> int:
@@ -58,7 +63,7 @@ class Layer:
         return (self.x_elems(N) + self.y_elems(N)) * elem_bytes
 
     def pass_flops(self, N: int) -> int:
-        return 2 * self.K * self.K * self.y_elems(N)
+        return 2 * self.K * self.K * self.cg * self.y_elems(N)
 
 
 def _mb(i, C, H, s):
@@ -87,6 +92,17 @@ XCEPTION: Tuple[Tuple[Layer, int], ...] = (
 )
 
 
+def _gc(C, H, cg):
+    return Layer("group_c%d_h%d_cg%d" % (C, H, cg), C, H, H, 3, 1, 1, 1, cg)
+
+
+# Group convolutions (3x3, stride 1, as many output as input channels) on MobileNet-sized planes:
+# 2, 4 and 8 channels per group.
+GROUP_LAYERS: Tuple[Layer, ...] = (
+    _gc(64, 112, 2), _gc(128, 56, 4), _gc(256, 28, 4), _gc(256, 28, 8), _gc(512, 14, 4),
+)
+
+
 def mobilenet_5x5() -> Tuple[Layer, ...]:
     """The nine stride-1 MobileNet layers with a 5x5 pad-2 filter."""
     return tuple(replace(l, name=l.name + "_k5", K=5, pad=2) for l in MOBILENET_V1 if l.stride == 1)
@@ -110,7 +126,8 @@ def mobilenet_variant(width: float = 1.0, resolution: int = 224, shallow: bool =
 def config(index: int) -> Dict:
     """The benchmark configurations, as dicts: N, layouts, dtype, layers [(Layer, repeat)].
     0..4: the five configurations of the benchmark spec; 5: the MobileNet variant shapes (width 0.75, width 0.5 at
-    resolution 128), as a second workload."""
+    resolution 128), as a second workload; 6: group convolutions with 2, 4 and 8 channels per group on
+    MobileNet-sized planes."""
     if index == 0:
         return dict(name="single_3x3_n8_c32_h112_f32_nchw", N=8, layouts=(NCHW,), dtype=F32,
                     layers=[(Layer("single_c32_h112", 32, 112, 112), 1)])
@@ -130,7 +147,10 @@ def config(index: int) -> Dict:
         return dict(name="mobilenet_variants_b128_f32", N=128, layouts=(NCHW, NHWC), dtype=F32,
                     layers=[(l, 1) for l in mobilenet_variant(0.75, 224)] +
                            [(l, 1) for l in mobilenet_variant(0.5, 128)])
-    raise ValueError("config index must be 0..5")
+    if index == 6:
+        return dict(name="group_conv_b128_f32", N=128, layouts=(NCHW, NHWC), dtype=F32,
+                    layers=[(l, 1) for l in GROUP_LAYERS])
+    raise ValueError("config index must be 0..6")
 
 
 def round_to_bf16(a: np.ndarray) -> np.ndarray:
@@ -190,10 +210,12 @@ def make_inputs_device(layer: Layer, N: int, layout: int, dtype: int, seed: int,
     tdt = torch.float32 if dtype == F32 else torch.bfloat16
     if layout == NCHW:
         xs, ys, ws = (N, layer.C, layer.H, layer.W), (N, layer.O, layer.Ho, layer.Wo), (layer.O, layer.K, layer.K)
+        if layer.cg > 1: ws = (layer.O, layer.cg, layer.K, layer.K)
     else:
         xs, ys, ws = (N, layer.H, layer.W, layer.C), (N, layer.Ho, layer.Wo, layer.O), (layer.K, layer.K, layer.O)
+        if layer.cg > 1: ws = (layer.K, layer.K, layer.cg, layer.O)
     x = torch.randn(xs, generator=gen, device=device, dtype=torch.float32).to(tdt)
-    w = (torch.randn(ws, generator=gen, device=device, dtype=torch.float32) / layer.K).to(tdt)
+    w = (torch.randn(ws, generator=gen, device=device, dtype=torch.float32) / (layer.K * layer.cg ** 0.5)).to(tdt)
     dy = torch.randn(ys, generator=gen, device=device, dtype=torch.float32).to(tdt)
     return x, w, dy
 
