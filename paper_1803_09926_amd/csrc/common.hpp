@@ -158,6 +158,13 @@ template <int V> struct RawVec<bf16_t, V> {
     }
 };
 
+template <> struct RawVec<bf16_t, 1> {
+    bf16_t w;
+    __device__ __forceinline__ void load(const bf16_t *p) { w = *p; }
+    __device__ __forceinline__ void get(float (&r)[1]) const { r[0] = bf16_to_f32(w); }
+    __device__ __forceinline__ void zero() { w = 0; }
+};
+
 typedef float f4v_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u4v_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u2v_t __attribute__((ext_vector_type(2)));

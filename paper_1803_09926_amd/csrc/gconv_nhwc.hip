@@ -1,7 +1,400 @@
+// Group convolution, NHWC, 3x3 stride 1 pad 1, groups of 2, 4 or 8 channels on the side that is read.
+//
+// The channels of a group are contiguous in a pixel, so the depthwise row-walk carries over: a lane owns OB
+// consecutive channels of the tensor that is written, at one pixel column, and walks down the rows of its
+// strip.  Per input row it loads, for each of the three columns it needs, the CG channels of its group (one or
+// two 16-byte vectors; the lanes of a group load the same addresses, which the memory pipeline merges), and
+// updates two rotating rows of accumulators plus the finished output row: 9*CG*OB multiply-adds.  The lane's
+// 9*CG*OB filter entries stay in registers for the whole walk (OB is chosen so that they are at most 72).
+// Columns outside the image get zeroed weights; rows outside the image are handled as in the depthwise
+// kernel (the walk starts at the first valid row, rows below the image only flush the accumulators).
+// Backward-data is the same walk over dy with the channel roles swapped and the taps reversed.
+//
+// Filter gradient: same lane mapping (OB output channels of one column), 9*CG*OB sums per lane.  Step r of
+// the walk takes x row r (three columns, CG channels) and dy row r+1 (own column, OB channels); x row r meets
+// dy rows r+1, r, r-1 at tap rows 0, 1, 2, so a window of three dy rows rotates.  Sums are added over the
+// columns of the block (wavefront butterfly, then LDS across the wavefronts) in a fixed order; one partial
+// per block and weight entry goes to the workspace for the shared second stage.
 #include "gconv.hpp"
+
 namespace dwc {
-bool gconv_nhwc_supported(const GGeom &) { return false; }
-hipError_t gconv_nhwc_s1(const GGeom &, int, const void *, const void *, void *, bool, hipStream_t) { return hipErrorInvalidValue; }
-int gconv_nhwc_bwd_filter_parts(const GGeom &) { return 0; }
-hipError_t gconv_nhwc_bwd_filter(const GGeom &, int, const void *, const void *, float *, int, hipStream_t) { return hipErrorInvalidValue; }
+
+// CG consecutive channels as loaded (bf16 stays packed until used)
+template <typename T, int CG> struct InVec {
+    static constexpr int VW = CG <= 4 ? CG : 4, NV = CG / VW;
+    RawVec<T, VW> v[NV];
+    __device__ __forceinline__ void load(const T *p)
+    {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) v[i].load(p + i * VW);
+    }
+    __device__ __forceinline__ void get(float (&r)[CG]) const
+    {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            float t[VW];
+            v[i].get(t);
+#pragma unroll
+            for (int j = 0; j < VW; ++j) r[i * VW + j] = t[j];
+        }
+    }
+};
+
+// filter entry (kh, kw, ci, o) of the NHWC layout [3][3][Cg][O]
+__device__ __forceinline__ int wat_nhwc(const GGeom &g, int kh, int kw, int ci, int o) { return ((kh * 3 + kw) * g.Cg + ci) * g.O + o; }
+
+template <typename T, int CG, int OB, int PF, bool FLIP>
+__global__ __launch_bounds__(256) void k_gconv_nhwc_s1(GGeom g, const T *__restrict__ in, const T *__restrict__ w,
+                                                       T *__restrict__ out, int TH, int nstrips, int nchunks,
+                                                       unsigned nblocks, int nt)
+{
+    constexpr int R = PF + 1;
+    unsigned lb = xcd_remap(blockIdx.x, nblocks);
+    const int strip = lb % nstrips; lb /= nstrips;
+    const int chunk = lb % nchunks; const int n = lb / nchunks;
+
+    const int CIT = FLIP ? g.O : g.C, COT = FLIP ? g.C : g.O;     // channels per pixel: read, written
+    const int CGW = FLIP ? g.Cg : g.Og;                           // channels per group in the tensor written
+    const int Q = COT / OB;
+    const int f = chunk * blockDim.x + threadIdx.x;
+    if (f >= g.W * Q) return;
+    const int cq = f % Q, ow = f / Q;
+    const int o0 = cq * OB, grp = o0 / CGW, sub = o0 % CGW;
+
+    int coloff[3];
+    float wr[3][3][CG][OB];
+#pragma unroll
+    for (int kw = 0; kw < 3; ++kw) {
+        const int iw = ow - 1 + kw;
+        const bool ok = iw >= 0 && iw < g.W;
+        coloff[kw] = (ok ? iw - ow : 0) * CIT;
+#pragma unroll
+        for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+            for (int b = 0; b < CG; ++b)
+#pragma unroll
+                for (int a = 0; a < OB; ++a) {
+                    // forward: output o0+a from input b of the group; backward-data: dx channel sub+a of the
+                    // group from dy channel b of the group, taps reversed
+                    const int idx = FLIP ? wat_nhwc(g, 2 - kh, 2 - kw, sub + a, grp * g.Og + b) : wat_nhwc(g, kh, kw, b, o0 + a);
+                    wr[kh][kw][b][a] = ok ? ldf(w + idx) : 0.f;
+                }
+    }
+
+    const int oh0 = strip * TH, oh1 = min(g.H, oh0 + TH);
+    const int rowstride = g.W * CIT, orowstride = g.W * COT;
+    const T *xin = in + (size_t)n * g.H * rowstride + (size_t)ow * CIT + grp * CG;
+    T *yout = out + (size_t)n * g.H * orowstride + (size_t)ow * COT + o0;
+
+    float acc[2][OB];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int a = 0; a < OB; ++a) acc[j][a] = 0.f;
+
+    const int r0 = oh0 - 1, r1 = oh1 + 1;
+    const int ra = max(r0, 0), rb = min(r1, g.H);
+    InVec<T, CG> ring[R][3];
+    auto load_row = [&](int r, InVec<T, CG> (&dst)[3]) {
+        const T *rp = xin + (size_t)min(r, rb - 1) * rowstride;
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) dst[kw].load(rp + coloff[kw]);
+    };
+    auto consume = [&](int r, const InVec<T, CG> (&raw)[3]) {
+        // input row r is tap row kh of output row r + 1 - kh
+        float cur[3][CG];
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) raw[kw].get(cur[kw]);
+        float o[OB];
+#pragma unroll
+        for (int a = 0; a < OB; ++a) {
+            float s2 = acc[0][a], s1 = acc[1][a], s0 = 0.f;
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw)
+#pragma unroll
+                for (int b = 0; b < CG; ++b) {
+                    s2 = fmaf(wr[2][kw][b][a], cur[kw][b], s2);
+                    s1 = fmaf(wr[1][kw][b][a], cur[kw][b], s1);
+                    s0 = fmaf(wr[0][kw][b][a], cur[kw][b], s0);
+                }
+            o[a] = s2; acc[0][a] = s1; acc[1][a] = s0;
+        }
+        const int oh = r - 1;
+        if (oh >= oh0) store_vec<T, OB>(yout + (size_t)oh * orowstride, o, nt != 0);
+    };
+
+#pragma unroll
+    for (int j = 0; j < PF; ++j) load_row(ra + j, ring[j]);
+    int base = ra;
+#pragma unroll 1
+    for (; base + R <= rb; base += R) {
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            load_row(base + j + PF, ring[(j + PF) % R]);
+            consume(base + j, ring[j]);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < R - 1; ++j)
+        if (base + j < rb) consume(base + j, ring[j]);
+    // rows below the image: zero rows, each completes one more output row
+    for (int r = rb; r < r1; ++r) {
+        float o[OB];
+#pragma unroll
+        for (int a = 0; a < OB; ++a) { o[a] = acc[0][a]; acc[0][a] = acc[1][a]; acc[1][a] = 0.f; }
+        const int oh = r - 1;
+        if (oh >= oh0) store_vec<T, OB>(yout + (size_t)oh * orowstride, o, nt != 0);
+    }
 }
+
+// Filter gradient, stage 1.  Block: CT lanes over the OB-channel sub-vectors x 256/CT columns, one strip of
+// NI images.  ws[part][kh][kw][ci][o].
+template <typename T, int CG, int OB>
+__global__ __launch_bounds__(256) void k_gconv_nhwc_bwd_filter(GGeom g, const T *__restrict__ x, const T *__restrict__ dy,
+                                                               float *__restrict__ ws, int CT, int nctiles, int nowtiles,
+                                                               int TH, int nstrips, int NI, unsigned nblocks, int J)
+{
+    __shared__ float red[4][CG * OB][64];
+    unsigned lb = xcd_remap(blockIdx.x, nblocks);
+    const int strip = lb % nstrips; lb /= nstrips;
+    const int owtile = lb % nowtiles; lb /= nowtiles;
+    const int ctile = lb % nctiles; const int ngroup = lb / nctiles;
+
+    const int OWT = 256 / CT;
+    const int tx = threadIdx.x % CT, ty = threadIdx.x / CT;
+    const int Q = g.O / OB;
+    const int cq = ctile * CT + tx, ow = owtile * OWT + ty;
+    const bool active = cq < Q && ow < g.W;
+    const int o0 = cq * OB, grp = o0 / g.Og;
+
+    float acc[3][3][CG][OB];
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw)
+#pragma unroll
+            for (int b = 0; b < CG; ++b)
+#pragma unroll
+                for (int a = 0; a < OB; ++a) acc[kh][kw][b][a] = 0.f;
+
+    if (active) {
+        bool colok[3];
+        int coloff[3];
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) {
+            const int iw = ow - 1 + kw;
+            colok[kw] = iw >= 0 && iw < g.W;
+            coloff[kw] = (colok[kw] ? iw : ow) * g.C;
+        }
+        const int xrow = g.W * g.C, drow = g.W * g.O;
+        const int oh0 = strip * TH, oh1 = min(g.H, oh0 + TH);
+        const int n0 = ngroup * NI, n1 = min(g.N, n0 + NI);
+        for (int n = n0; n < n1; ++n) {
+            const T *xin = x + (size_t)n * g.H * xrow + grp * CG;
+            const T *dyin = dy + ((size_t)n * g.H * g.W + ow) * g.O + o0;
+            float dyw[3][OB];
+#pragma unroll
+            for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+                for (int a = 0; a < OB; ++a) dyw[kh][a] = 0.f;
+            // step r: x row r and dy row r+1; one step ahead in registers
+            InVec<T, CG> xr[2][3];
+            RawVec<T, OB> dr[2];
+            auto load_step = [&](int r, InVec<T, CG> (&xd)[3], RawVec<T, OB> &dd) {
+                const T *xp = xin + (size_t)min(max(r, 0), g.H - 1) * xrow;
+#pragma unroll
+                for (int kw = 0; kw < 3; ++kw) xd[kw].load(xp + coloff[kw]);
+                dd.load(dyin + (size_t)min(max(r + 1, 0), g.H - 1) * drow);
+            };
+            auto consume = [&](int r, const InVec<T, CG> (&xd)[3], const RawVec<T, OB> &dd) {
+                const bool xok = r >= 0 && r < g.H;
+                const bool dok = r + 1 >= oh0 && r + 1 < oh1;       // only dy rows of this block's strip count
+                float d[OB];
+                dd.get(d);
+#pragma unroll
+                for (int a = 0; a < OB; ++a) { dyw[2][a] = dyw[1][a]; dyw[1][a] = dyw[0][a]; dyw[0][a] = dok ? d[a] : 0.f; }
+#pragma unroll
+                for (int kw = 0; kw < 3; ++kw) {
+                    float xv[CG];
+                    xd[kw].get(xv);
+#pragma unroll
+                    for (int b = 0; b < CG; ++b) {
+                        const float xx = xok ? xv[b] : 0.f;
+#pragma unroll
+                        for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+                            for (int a = 0; a < OB; ++a) acc[kh][kw][b][a] = fmaf(dyw[kh][a], xx, acc[kh][kw][b][a]);
+                    }
+                }
+            };
+            // x rows oh0-1 .. oh1: TH + 2 steps
+            const int r0 = oh0 - 1, nsteps = (oh1 - oh0) + 2;
+            load_step(r0, xr[0], dr[0]);
+            int i = 0;
+#pragma unroll 1
+            for (; i + 2 <= nsteps; i += 2) {
+                load_step(r0 + i + 1, xr[1], dr[1]);
+                consume(r0 + i, xr[0], dr[0]);
+                load_step(r0 + i + 2, xr[0], dr[0]);
+                consume(r0 + i + 1, xr[1], dr[1]);
+            }
+            if (i < nsteps) consume(r0 + i, xr[0], dr[0]);
+        }
+        // taps on columns outside the image accumulated clamped data: drop them
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw)
+            if (!colok[kw]) {
+#pragma unroll
+                for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+                    for (int b = 0; b < CG; ++b)
+#pragma unroll
+                        for (int a = 0; a < OB; ++a) acc[kh][kw][b][a] = 0.f;
+            }
+    }
+
+    // fixed-order block reduction, one tap at a time
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int part = (ngroup * nstrips + strip) * nowtiles + owtile;
+    float *wsp = ws + (size_t)part * J;
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) {
+#pragma unroll
+            for (int b = 0; b < CG; ++b)
+#pragma unroll
+                for (int a = 0; a < OB; ++a) red[wv][b * OB + a][lane] = wave_sum_strided(acc[kh][kw][b][a], CT);
+            __syncthreads();
+            if (wv == 0 && lane < CT && cq < Q) {
+#pragma unroll
+                for (int b = 0; b < CG; ++b)
+#pragma unroll
+                    for (int a = 0; a < OB; ++a) {
+                        const int e = b * OB + a;
+                        wsp[((kh * 3 + kw) * g.Cg + b) * g.O + o0 + a] =
+                            (red[0][e][lane] + red[1][e][lane]) + (red[2][e][lane] + red[3][e][lane]);
+                    }
+            }
+            __syncthreads();
+        }
+}
+
+// ---- host side ---------------------------------------------------------------------------------------------
+
+static inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+// channels written per lane: as many as keep the lane's 9*CG*OB filter entries within 72 registers
+static int nhwc_ob(int CG, int CGW)
+{
+    int ob = 72 / (9 * CG);
+    if (ob > 4) ob = 4;
+    while (ob > 1 && (CGW % ob != 0 || (ob & (ob - 1)) != 0)) --ob;
+    return ob < 1 ? 1 : ob;
+}
+
+bool gconv_nhwc_supported(const GGeom &g)
+{
+    if (!(g.K == 3 && g.s == 1 && g.p == 1)) return false;
+    // both directions: the channels read per group are 2, 4 or 8 (forward reads Cg, backward-data reads Og)
+    const bool cg_ok = g.Cg == 2 || g.Cg == 4 || g.Cg == 8, og_ok = g.Og == 2 || g.Og == 4 || g.Og == 8;
+    return cg_ok && og_ok;
+}
+
+static int nhwc_pick_th(int rows)
+{
+    const int target = 14;
+    int ns = (rows + target / 2) / target;
+    if (ns < 1) ns = 1;
+    return cdiv(rows, ns);
+}
+
+template <typename T, int CG, int OB, int PF>
+static hipError_t launch_gs1(const GGeom &g, const void *in, const void *w, void *out, bool flip, hipStream_t st)
+{
+    const int COT = flip ? g.C : g.O;
+    const int lanes = g.W * (COT / OB);
+    const int bs = 256;
+    const int TH = nhwc_pick_th(g.H);
+    const int nchunks = cdiv(lanes, bs), nstrips = cdiv(g.H, TH);
+    const long long nb = (long long)g.N * nchunks * nstrips;
+    if (nb >= (1ll << 31)) return hipErrorInvalidValue;
+    const unsigned nblocks = (unsigned)nb;
+    const int nt = stream_stores(flip ? "GROUP_NHWC_BWD" : "GROUP_NHWC_FWD", (long long)g.N * g.H * g.W * COT * sizeof(T), 0);
+    if (flip)
+        hipLaunchKernelGGL((k_gconv_nhwc_s1<T, CG, OB, PF, true>), dim3(nblocks), dim3(bs), 0, st, g, (const T *)in,
+                           (const T *)w, (T *)out, TH, nstrips, nchunks, nblocks, nt);
+    else
+        hipLaunchKernelGGL((k_gconv_nhwc_s1<T, CG, OB, PF, false>), dim3(nblocks), dim3(bs), 0, st, g, (const T *)in,
+                           (const T *)w, (T *)out, TH, nstrips, nchunks, nblocks, nt);
+    return hipGetLastError();
+}
+
+hipError_t gconv_nhwc_s1(const GGeom &g, int dtype, const void *in, const void *w, void *out, bool flip, hipStream_t st)
+{
+    if (!gconv_nhwc_supported(g)) return hipErrorInvalidValue;
+    const int CG = flip ? g.Og : g.Cg, CGW = flip ? g.Cg : g.Og;
+    const int OB = nhwc_ob(CG, CGW);
+#define TRY(T, CGG, OBB, PPF) if (CG == CGG && OB == OBB) return launch_gs1<T, CGG, OBB, PPF>(g, in, w, out, flip, st)
+    if (dtype == DT_F32) {
+        TRY(float, 2, 4, 2); TRY(float, 2, 2, 2); TRY(float, 4, 2, 2); TRY(float, 4, 1, 2); TRY(float, 8, 1, 1);
+    } else {
+        TRY(bf16_t, 2, 4, 2); TRY(bf16_t, 2, 2, 2); TRY(bf16_t, 4, 2, 2); TRY(bf16_t, 4, 1, 2); TRY(bf16_t, 8, 1, 1);
+    }
+#undef TRY
+    return hipErrorInvalidValue;
+}
+
+// Filter-gradient tiling.  CT: lanes over sub-vectors (a power of two up to 64), 256/CT columns per block.
+static void gconv_nhwc_bwd_filter_tiling(const GGeom &g, int *OBp, int *CT, int *nctiles, int *nowtiles, int *TH,
+                                         int *nstrips, int *NI, int *ngroups)
+{
+    const int OB = nhwc_ob(g.Cg, g.Og);
+    const int Q = g.O / OB;
+    int ct = 1;
+    while (ct < 64 && ct < Q) ct *= 2;
+    const int nct = cdiv(Q, ct), nowt = cdiv(g.W, 256 / ct);
+    // whole columns unless the launch would have too few blocks; then about two blocks per compute unit,
+    // a block walking several images when there are plenty
+    int th = g.H;
+    const long long per_strip = (long long)nct * nowt * g.N;
+    while (th > 7 && per_strip * cdiv(g.H, th) < 384) th = (th + 1) / 2;
+    int ni = 1;
+    while (ni < g.N && per_strip * cdiv(g.H, th) / (ni * 2) >= 384) ni *= 2;
+    const long long J = (long long)g.O * g.Cg * 9;
+    while ((long long)nowt * cdiv(g.H, th) * cdiv(g.N, ni) * J * 4 > (64ll << 20)) {
+        if (ni < g.N) ni *= 2; else if (th < g.H) th *= 2; else break;
+    }
+    *OBp = OB; *CT = ct; *nctiles = nct; *nowtiles = nowt; *TH = th; *nstrips = cdiv(g.H, th); *NI = ni;
+    *ngroups = cdiv(g.N, ni);
+}
+
+int gconv_nhwc_bwd_filter_parts(const GGeom &g)
+{
+    int OB, CT, nct, nowt, TH, nst, NI, ngr;
+    gconv_nhwc_bwd_filter_tiling(g, &OB, &CT, &nct, &nowt, &TH, &nst, &NI, &ngr);
+    return nowt * nst * ngr;
+}
+
+hipError_t gconv_nhwc_bwd_filter(const GGeom &g, int dtype, const void *x, const void *dy, float *ws, int parts,
+                                 hipStream_t st)
+{
+    if (!gconv_nhwc_supported(g)) return hipErrorInvalidValue;
+    int OB, CT, nct, nowt, TH, nst, NI, ngr;
+    gconv_nhwc_bwd_filter_tiling(g, &OB, &CT, &nct, &nowt, &TH, &nst, &NI, &ngr);
+    if (parts != nowt * nst * ngr) return hipErrorInvalidValue;
+    const long long nb = (long long)nct * nowt * nst * ngr;
+    if (nb >= (1ll << 31)) return hipErrorInvalidValue;
+    const unsigned nblocks = (unsigned)nb;
+    const int J = g.O * g.Cg * 9;
+#define TRY(T, CGG, OBB) if (g.Cg == CGG && OB == OBB) { hipLaunchKernelGGL((k_gconv_nhwc_bwd_filter<T, CGG, OBB>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, (const T *)dy, ws, CT, nct, nowt, TH, nst, NI, nblocks, J); return hipGetLastError(); }
+    if (dtype == DT_F32) {
+        TRY(float, 2, 4); TRY(float, 2, 2); TRY(float, 4, 2); TRY(float, 4, 1); TRY(float, 8, 1);
+    } else {
+        TRY(bf16_t, 2, 4); TRY(bf16_t, 2, 2); TRY(bf16_t, 4, 2); TRY(bf16_t, 4, 1); TRY(bf16_t, 8, 1);
+    }
+#undef TRY
+    return hipErrorInvalidValue;
+}
+
+}  // namespace dwc

@@ -40,6 +40,15 @@ CASES = [
     ("depthwise_m2", 2, 8, 16, 8, 12, 12, 3, 1, 1),
     ("g4_many_strips", 1, 8, 8, 2, 70, 28, 3, 1, 1),
     ("g4_wide", 1, 4, 4, 1, 5, 1100, 3, 1, 1),
+    # channel counts per group that differ between the two sides, and tilings with ragged edges
+    ("cg2_og4", 3, 8, 16, 4, 17, 20, 3, 1, 1),
+    ("cg2_og8", 2, 4, 16, 2, 9, 12, 3, 1, 1),
+    ("cg8_og2", 2, 16, 4, 2, 10, 14, 3, 1, 1),
+    ("cg8_og8_w30", 3, 24, 24, 3, 33, 30, 3, 1, 1),
+    ("cg4_c132_h40", 5, 132, 132, 33, 40, 6, 3, 1, 1),
+    ("cg2_c6_tall", 7, 6, 6, 3, 61, 10, 3, 1, 1),
+    ("cg4_h1", 2, 8, 8, 2, 1, 16, 3, 1, 1),
+    ("cg4_w2", 2, 8, 8, 2, 9, 2, 3, 1, 1),
 ]
 
 
