@@ -1,21 +1,23 @@
-// Group convolution, NCHW, 3x3 stride 1 pad 1, rows that are whole 4-column vectors; any number of channels
-// per group on either side.
+// Group convolution, NCHW, 3x3 stride 1 pad 1, rows that are whole 4- or 2-column vectors; any number of
+// channels per group on either side.
 //
 // Forward / backward-data (k_gconv_nchw_s1): a block works on one group and OB of its output channels; a
-// lane owns 4 consecutive columns of one (image, strip) and walks the strip's rows.  The group's filters sit
-// in LDS as [input channel][tap][output channel]: every lane of the block reads the same entries (a
-// broadcast).  One step of the walk takes one row of ONE input channel: three loads (the 4-column vector and
-// its two neighbours), 9*OB weights from LDS, 36*OB multiply-adds into three rotating rows of accumulators.
-// The loop over input channels is a real loop, so the kernel serves any group size, and the next step's row
-// is loaded before the current one is used.  Input rows above and below a strip feed only one output row:
-// the other two thirds of their arithmetic are skipped (the step index is uniform over the block).
-// Backward-data is the same walk over dy with the roles of the channels swapped and the taps reversed.
+// lane owns V consecutive columns of one (image, strip) and walks the strip's rows.  The group's filters sit
+// in LDS as [input channel][tap row][tap column][output channel]: every lane of the block reads the same
+// entries (a broadcast), one (input channel, tap row) ahead of the multiply-adds that use them.  One step of
+// the walk takes one row of ONE input channel: three loads (the V-column vector and its two neighbours),
+// 9*OB weights, 9*OB*V multiply-adds into three rows of accumulators.  The loop over input channels is a real
+// loop, so the kernel serves any group size; rows are loaded R steps ahead, R at a time.  Input rows above and
+// below a strip feed only one or two output rows: the rest of their arithmetic is skipped (the step index is
+// uniform over the block).  Backward-data is the same walk over dy with the roles of the channels swapped and
+// the taps reversed.
 //
 // Filter gradient (k_gconv_nchw_bwd_filter): a block works on one input channel b of a group and OB of the
-// group's output channels; a lane owns 4 columns of (image, strip) items and keeps 9*OB sums.  Per output row
-// it loads that row of the OB dy planes and one new row of x (a window of three x rows rotates), 36*OB
-// multiply-adds.  At the end the sums are added over the wavefront (butterfly), over the four wavefronts
-// through LDS, and the block writes one partial per weight entry; the shared second stage adds the partials.
+// group's output channels; a lane owns V columns of (image, strip) items and keeps 9*OB sums.  Per output row
+// it takes that row of the OB dy planes and one new row of x (a window of three x rows rotates), 9*OB*V
+// multiply-adds; rows are loaded two output rows ahead.  At the end the sums are added over the wavefront
+// (butterfly), over the four wavefronts through LDS, and the block writes one partial per weight entry; the
+// shared second stage adds the partials.
 #include "gconv.hpp"
 
 namespace dwc {
