@@ -55,6 +55,13 @@ VARIANT_KERNELS = {
     "bwd:nhwc_bwd_fused_k3s1": [r"k_nhwc_bwd_fused_k3s1<"],
     "bwd:nchw_bwd_fused_k3s1": [r"k_nchwd_bwd_fused_k3s1<"],
     "bwd:nchw_smallplane_bwd_fused_k3s1": [r"k_nchws_bwd_fused<"],
+    # group convolution: k_gconv_nchw_s1<T, V, OB, R, FLIP>, k_gconv_nhwc_s1<T, CG, OB, PF, FLIP>
+    "fwd:group_nchw_rowwalk_k3s1": [r"k_gconv_nchw_s1<\w+, \d+, \d+, \d+, false>"],
+    "bwd_data:group_nchw_rowwalk_k3s1_flip": [r"k_gconv_nchw_s1<\w+, \d+, \d+, \d+, true>"],
+    "bwd_filter:group_nchw_bwd_filter_k3s1": [r"k_gconv_nchw_bwd_filter<"],
+    "fwd:group_nhwc_rowwalk_k3s1": [r"k_gconv_nhwc_s1<\w+, \d+, \d+, \d+, false>"],
+    "bwd_data:group_nhwc_rowwalk_k3s1_flip": [r"k_gconv_nhwc_s1<\w+, \d+, \d+, \d+, true>"],
+    "bwd_filter:group_nhwc_bwd_filter_k3s1": [r"k_gconv_nhwc_bwd_filter<"],
 }
 
 
