@@ -1,0 +1,116 @@
+"""On-box comparison with the paper's own route: diagonalwise refactorization with grouping.
+
+COMPARISON ONLY, never a code path of the library.  For every depthwise layer of MobileNet-v1 (the shapes of
+the paper's Table III) this times
+
+  * this library's kernels through the C ABI (forward; backward = backward-filter + backward-data), and
+  * the refactorised dense route of Section III: the channels are split into groups of S (Section III-B,
+    grouping "by size"), each group's filters are placed on the block diagonal of an S x (S*K*K) matrix
+    (Eq. 1), the input is unrolled with im2col (Section II) and the two are multiplied with a plain batched
+    GEMM (torch.matmul, i.e. rocBLAS / hipBLASLt); backward = the two transposed GEMMs, col2im, and the mask
+    of Eq. 4 on the weight gradient.  There is no cuDNN analogue here and none is claimed: the point is the
+    S-fold redundant arithmetic and the 9-fold im2col traffic on this chip, i.e. the shape of the paper's
+    Fig. 5 (time against group size).
+
+Usage:  python -m paper_1803_09926_amd.dense_comparison [--batch 64] [--sizes 16,32,64,128] [--iters 5]
+Prints one table row per layer and a JSON line with the totals.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+
+
+def _time(fn, torch, iters):
+    fn(); fn()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(iters):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / iters
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--batch", type=int, default=64)
+    ap.add_argument("--sizes", default="16,32,64,128")
+    ap.add_argument("--iters", type=int, default=5)
+    args = ap.parse_args()
+    import torch
+    import torch.nn.functional as F
+    import paper_1803_09926_amd as dw
+    from paper_1803_09926_amd import workloads as wl
+    if not torch.cuda.is_available():
+        sys.exit("dense_comparison needs a GPU")
+    dw.load()
+    N = args.batch
+    sizes = [int(s) for s in args.sizes.split(",")]
+    print("%-28s %9s %9s | %s" % ("layer (batch %d, fp32 NCHW)" % N, "ours fwd", "ours bwd",
+                                  "  ".join("S=%-4d fwd / bwd ms" % s for s in sizes)))
+    tot = {"ours_fwd": 0.0, "ours_bwd": 0.0}
+    for li, layer in enumerate(wl.MOBILENET_V1):
+        x, w, dy = wl.make_inputs_device(layer, N, wl.NCHW, wl.F32, seed=li)
+        C, H, W, K, s, p = layer.C, layer.H, layer.W, layer.K, layer.stride, layer.pad
+        Ho, Wo, L = layer.Ho, layer.Wo, layer.Ho * layer.Wo
+        d = dw.desc(N, C, H, W, K, s, p, 1, wl.NCHW, wl.F32)
+        y = torch.empty_like(dy); dx = torch.empty_like(x); dwt = torch.empty_like(w)
+        ws = torch.empty(max(dw.bwd_filter_workspace_bytes(d), 16), device="cuda", dtype=torch.uint8)
+        t_f = _time(lambda: dw.fwd(d, x, w, y), torch, args.iters)
+        t_b = _time(lambda: (dw.bwd_filter(d, x, dy, dwt, ws), dw.bwd_data(d, dy, w, dx)), torch, args.iters)
+        tot["ours_fwd"] += t_f; tot["ours_bwd"] += t_b
+        cells = []
+        for S in sizes:
+            if C % S != 0:
+                cells.append("%-22s" % "-")
+                continue
+            G = C // S
+            # Eq. 1: the S filters of a group on the block diagonal of an S x (S*K*K) matrix; Eq. 2: the mask
+            What = torch.zeros(G, S, S * K * K, device="cuda")
+            A = torch.zeros(S, S * K * K, device="cuda")
+            wv = w.view(G, S, K * K)
+            for i in range(S):
+                What[:, i, i * K * K:(i + 1) * K * K] = wv[:, i]
+                A[i, i * K * K:(i + 1) * K * K] = 1.0
+            cols_keep = {}
+
+            def fwd():
+                cols = F.unfold(x.view(N * G, S, H, W), K, padding=p, stride=s).view(N, G, S * K * K, L)
+                cols_keep["c"] = cols
+                return torch.matmul(What.unsqueeze(0), cols).view(N, C, Ho, Wo)
+
+            def bwd():
+                cols = cols_keep["c"]
+                dz = dy.view(N, G, S, L)
+                dcols = torch.matmul(What.transpose(1, 2).unsqueeze(0), dz)
+                gx = F.fold(dcols.view(N * G, S * K * K, L), (H, W), K, padding=p, stride=s).view(N, C, H, W)
+                gw = (torch.matmul(dz, cols.transpose(2, 3)).sum(0) * A.unsqueeze(0))        # Eq. 4
+                return gx, gw
+
+            z = fwd()
+            dw.fwd(d, x, w, y)
+            torch.cuda.synchronize()
+            err = float((z - y).abs().max() / y.abs().max())
+            assert err < 1e-4, (layer.name, S, err)      # the two routes compute the same layer
+            gx, gw = bwd()
+            dw.bwd_data(d, dy, w, dx)
+            torch.cuda.synchronize()
+            assert float((gx - dx).abs().max() / dx.abs().max()) < 1e-4, (layer.name, S)
+            td_f = _time(fwd, torch, args.iters)
+            td_b = _time(bwd, torch, args.iters)
+            tot.setdefault("dense_fwd_S%d" % S, 0.0); tot.setdefault("dense_bwd_S%d" % S, 0.0)
+            tot["dense_fwd_S%d" % S] += td_f; tot["dense_bwd_S%d" % S] += td_b
+            cells.append("%8.3f / %-11.3f" % (td_f, td_b))
+            del What, A, z, gx, gw
+            cols_keep.clear()
+            torch.cuda.empty_cache()
+        print("%-28s %9.4f %9.4f | %s" % (layer.name[10:], t_f, t_b, "  ".join(cells)), flush=True)
+    print(json.dumps({"batch": N, "unit": "ms, sum over the 13 layers (a dense total covers only the layers whose "
+                      "channel count the group size divides)", **{k: round(v, 3) for k, v in tot.items()}}))
+
+
+if __name__ == "__main__":
+    main()
