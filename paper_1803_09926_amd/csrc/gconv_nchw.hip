@@ -301,12 +301,22 @@ __global__ __launch_bounds__(256) void k_gconv_nchw_bwd_filter(GGeom g, const T 
 
 // ---- host side ---------------------------------------------------------------------------------------------
 
-static int pick_ob(int CO) { return CO % 4 == 0 ? 4 : (CO % 2 == 0 ? 2 : 1); }
-static int pick_v(int W) { return W % 4 == 0 ? 4 : (W % 2 == 0 ? 2 : 0); }
 static int gtune(const char *name, int dflt)
 {
     const char *e = getenv(name);
     return e && *e ? atoi(e) : dflt;
+}
+static int pick_ob(int CO)
+{
+    const int cap = gtune("DWCONV_TUNE_GOB", 4);
+    return (CO % 4 == 0 && cap >= 4) ? 4 : ((CO % 2 == 0 && cap >= 2) ? 2 : 1);
+}
+// columns per lane; the forward / backward-data walk measured faster with two columns per lane on rows of up
+// to 56 elements (fewer registers, more wavefronts in flight), the filter gradient with four throughout
+static int pick_v(int W, bool walk = false)
+{
+    const int cap = gtune("DWCONV_TUNE_GV", walk && W <= 56 ? 2 : 4);
+    return (W % 4 == 0 && cap >= 4) ? 4 : (W % 2 == 0 ? 2 : 0);
 }
 
 bool gconv_nchw_supported(const GGeom &g)
@@ -321,12 +331,12 @@ bool gconv_nchw_supported(const GGeom &g)
 
 // strip height: the tallest of whole plane / 28 / 14 / 7 rows that still gives the launch about two
 // blocks per compute unit
-static int gconv_pick_th(const GGeom &g, long long blocks_per_lane_block_row)
+static int gconv_pick_th(const GGeom &g, long long blocks_per_lane_block_row, bool walk)
 {
     const int forced = gtune("DWCONV_TUNE_GTH", 0);
     if (forced > 0) return forced < g.H ? forced : g.H;
     const int cands[4] = {g.H, 28, 14, 7};
-    const int ncv = g.W / pick_v(g.W);
+    const int ncv = g.W / pick_v(g.W, walk);
     const long long want = gtune("DWCONV_TUNE_GBLOCKS", 512);
     for (int i = 0; i < 4; ++i) {
         const int th = cands[i] < g.H ? cands[i] : g.H;
@@ -341,9 +351,9 @@ hipError_t gconv_nchw_s1(const GGeom &g, int dtype, const void *in, const void *
     if (!gconv_nchw_supported(g)) return hipErrorInvalidValue;
     const int CI = flip ? g.Og : g.Cg, CO = flip ? g.Cg : g.Og;
     const int CIN_T = flip ? g.O : g.C, COUT_T = flip ? g.C : g.O;
-    const int OB = pick_ob(CO), V = pick_v(g.W);
+    const int OB = pick_ob(CO), V = pick_v(g.W, true);
     const int nchunks = CO / OB;
-    const int TH = gconv_pick_th(g, (long long)g.G * nchunks);
+    const int TH = gconv_pick_th(g, (long long)g.G * nchunks, true);
     const int nstrips = (g.H + TH - 1) / TH, ncv = g.W / V;
     const long long nl = (long long)g.N * nstrips * ncv;
     const long long nlb = (nl + 255) / 256;
@@ -378,7 +388,7 @@ static void gconv_nchw_bwd_filter_tiling(const GGeom &g, int *TH, int *nstrips, 
 {
     const int OB = pick_ob(g.Og);
     const long long per_part_row = (long long)g.G * g.Cg * (g.Og / OB);
-    const int th = gconv_pick_th(g, per_part_row);
+    const int th = gconv_pick_th(g, per_part_row, false);
     const int ns = (g.H + th - 1) / th;
     const long long ni = (long long)g.N * ns * (g.W / pick_v(g.W));
     // about 2048 blocks in the launch, each lane with at least one item, at most 64 partials

@@ -43,7 +43,9 @@ template <typename T, int CG> struct InVec {
 // filter entry (kh, kw, ci, o) of the NHWC layout [3][3][Cg][O]
 __device__ __forceinline__ int wat_nhwc(const GGeom &g, int kh, int kw, int ci, int o) { return ((kh * 3 + kw) * g.Cg + ci) * g.O + o; }
 
-template <typename T, int CG, int OB, int PF, bool FLIP>
+// GPL = groups per lane: with two channels per group a lane takes two adjacent groups (then OB is the whole
+// group), so that its loads and stores are 16 bytes wide.
+template <typename T, int CG, int OB, int GPL, int PF, bool FLIP>
 __global__ __launch_bounds__(256) void k_gconv_nhwc_s1(GGeom g, const T *__restrict__ in, const T *__restrict__ w,
                                                        T *__restrict__ out, int TH, int nstrips, int nchunks,
                                                        unsigned nblocks, int nt)
@@ -55,14 +57,15 @@ __global__ __launch_bounds__(256) void k_gconv_nhwc_s1(GGeom g, const T *__restr
 
     const int CIT = FLIP ? g.O : g.C, COT = FLIP ? g.C : g.O;     // channels per pixel: read, written
     const int CGW = FLIP ? g.Cg : g.Og;                           // channels per group in the tensor written
-    const int Q = COT / OB;
+    constexpr int OL = OB * GPL, IL = CG * GPL;                   // channels written / read per lane
+    const int Q = COT / OL;
     const int f = chunk * blockDim.x + threadIdx.x;
     if (f >= g.W * Q) return;
     const int cq = f % Q, ow = f / Q;
-    const int o0 = cq * OB, grp = o0 / CGW, sub = o0 % CGW;
+    const int o0 = cq * OL, grp = o0 / CGW, sub = o0 % CGW;      // GPL > 1: sub == 0 and OB == CGW
 
     int coloff[3];
-    float wr[3][3][CG][OB];
+    float wr[3][3][GPL][CG][OB];
 #pragma unroll
     for (int kw = 0; kw < 3; ++kw) {
         const int iw = ow - 1 + kw;
@@ -71,14 +74,17 @@ __global__ __launch_bounds__(256) void k_gconv_nhwc_s1(GGeom g, const T *__restr
 #pragma unroll
         for (int kh = 0; kh < 3; ++kh)
 #pragma unroll
-            for (int b = 0; b < CG; ++b)
+            for (int gi = 0; gi < GPL; ++gi)
 #pragma unroll
-                for (int a = 0; a < OB; ++a) {
-                    // forward: output o0+a from input b of the group; backward-data: dx channel sub+a of the
-                    // group from dy channel b of the group, taps reversed
-                    const int idx = FLIP ? wat_nhwc(g, 2 - kh, 2 - kw, sub + a, grp * g.Og + b) : wat_nhwc(g, kh, kw, b, o0 + a);
-                    wr[kh][kw][b][a] = ok ? ldf(w + idx) : 0.f;
-                }
+                for (int b = 0; b < CG; ++b)
+#pragma unroll
+                    for (int a = 0; a < OB; ++a) {
+                        // forward: output o0+gi*OB+a from input b of its group; backward-data: dx channel sub+a of
+                        // group grp+gi from dy channel b of that group, taps reversed
+                        const int idx = FLIP ? wat_nhwc(g, 2 - kh, 2 - kw, sub + a, (grp + gi) * g.Og + b)
+                                             : wat_nhwc(g, kh, kw, b, o0 + gi * OB + a);
+                        wr[kh][kw][gi][b][a] = ok ? ldf(w + idx) : 0.f;
+                    }
     }
 
     const int oh0 = strip * TH, oh1 = min(g.H, oh0 + TH);
@@ -86,41 +92,43 @@ __global__ __launch_bounds__(256) void k_gconv_nhwc_s1(GGeom g, const T *__restr
     const T *xin = in + (size_t)n * g.H * rowstride + (size_t)ow * CIT + grp * CG;
     T *yout = out + (size_t)n * g.H * orowstride + (size_t)ow * COT + o0;
 
-    float acc[2][OB];
+    float acc[2][OL];
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int a = 0; a < OB; ++a) acc[j][a] = 0.f;
+        for (int a = 0; a < OL; ++a) acc[j][a] = 0.f;
 
     const int r0 = oh0 - 1, r1 = oh1 + 1;
     const int ra = max(r0, 0), rb = min(r1, g.H);
-    InVec<T, CG> ring[R][3];
-    auto load_row = [&](int r, InVec<T, CG> (&dst)[3]) {
+    InVec<T, IL> ring[R][3];
+    auto load_row = [&](int r, InVec<T, IL> (&dst)[3]) {
         const T *rp = xin + (size_t)min(r, rb - 1) * rowstride;
 #pragma unroll
         for (int kw = 0; kw < 3; ++kw) dst[kw].load(rp + coloff[kw]);
     };
-    auto consume = [&](int r, const InVec<T, CG> (&raw)[3]) {
+    auto consume = [&](int r, const InVec<T, IL> (&raw)[3]) {
         // input row r is tap row kh of output row r + 1 - kh
-        float cur[3][CG];
+        float cur[3][IL];
 #pragma unroll
         for (int kw = 0; kw < 3; ++kw) raw[kw].get(cur[kw]);
-        float o[OB];
+        float o[OL];
 #pragma unroll
-        for (int a = 0; a < OB; ++a) {
-            float s2 = acc[0][a], s1 = acc[1][a], s0 = 0.f;
+        for (int gi = 0; gi < GPL; ++gi)
 #pragma unroll
-            for (int kw = 0; kw < 3; ++kw)
+            for (int a = 0; a < OB; ++a) {
+                float s2 = acc[0][gi * OB + a], s1 = acc[1][gi * OB + a], s0 = 0.f;
 #pragma unroll
-                for (int b = 0; b < CG; ++b) {
-                    s2 = fmaf(wr[2][kw][b][a], cur[kw][b], s2);
-                    s1 = fmaf(wr[1][kw][b][a], cur[kw][b], s1);
-                    s0 = fmaf(wr[0][kw][b][a], cur[kw][b], s0);
-                }
-            o[a] = s2; acc[0][a] = s1; acc[1][a] = s0;
-        }
+                for (int kw = 0; kw < 3; ++kw)
+#pragma unroll
+                    for (int b = 0; b < CG; ++b) {
+                        s2 = fmaf(wr[2][kw][gi][b][a], cur[kw][gi * CG + b], s2);
+                        s1 = fmaf(wr[1][kw][gi][b][a], cur[kw][gi * CG + b], s1);
+                        s0 = fmaf(wr[0][kw][gi][b][a], cur[kw][gi * CG + b], s0);
+                    }
+                o[gi * OB + a] = s2; acc[0][gi * OB + a] = s1; acc[1][gi * OB + a] = s0;
+            }
         const int oh = r - 1;
-        if (oh >= oh0) store_vec<T, OB>(yout + (size_t)oh * orowstride, o, nt != 0);
+        if (oh >= oh0) store_vec<T, OL>(yout + (size_t)oh * orowstride, o, nt != 0);
     };
 
 #pragma unroll
@@ -139,11 +147,11 @@ __global__ __launch_bounds__(256) void k_gconv_nhwc_s1(GGeom g, const T *__restr
         if (base + j < rb) consume(base + j, ring[j]);
     // rows below the image: zero rows, each completes one more output row
     for (int r = rb; r < r1; ++r) {
-        float o[OB];
+        float o[OL];
 #pragma unroll
-        for (int a = 0; a < OB; ++a) { o[a] = acc[0][a]; acc[0][a] = acc[1][a]; acc[1][a] = 0.f; }
+        for (int a = 0; a < OL; ++a) { o[a] = acc[0][a]; acc[0][a] = acc[1][a]; acc[1][a] = 0.f; }
         const int oh = r - 1;
-        if (oh >= oh0) store_vec<T, OB>(yout + (size_t)oh * orowstride, o, nt != 0);
+        if (oh >= oh0) store_vec<T, OL>(yout + (size_t)oh * orowstride, o, nt != 0);
     }
 }
 
@@ -309,11 +317,11 @@ static int nhwc_pick_th(int rows)
     return cdiv(rows, ns);
 }
 
-template <typename T, int CG, int OB, int PF>
+template <typename T, int CG, int OB, int GPL, int PF>
 static hipError_t launch_gs1(const GGeom &g, const void *in, const void *w, void *out, bool flip, hipStream_t st)
 {
     const int COT = flip ? g.C : g.O;
-    const int lanes = g.W * (COT / OB);
+    const int lanes = g.W * (COT / (OB * GPL));
     const int bs = 256;
     const int TH = nhwc_pick_th(g.H);
     const int nchunks = cdiv(lanes, bs), nstrips = cdiv(g.H, TH);
@@ -322,10 +330,10 @@ static hipError_t launch_gs1(const GGeom &g, const void *in, const void *w, void
     const unsigned nblocks = (unsigned)nb;
     const int nt = stream_stores(flip ? "GROUP_NHWC_BWD" : "GROUP_NHWC_FWD", (long long)g.N * g.H * g.W * COT * sizeof(T), 0);
     if (flip)
-        hipLaunchKernelGGL((k_gconv_nhwc_s1<T, CG, OB, PF, true>), dim3(nblocks), dim3(bs), 0, st, g, (const T *)in,
+        hipLaunchKernelGGL((k_gconv_nhwc_s1<T, CG, OB, GPL, PF, true>), dim3(nblocks), dim3(bs), 0, st, g, (const T *)in,
                            (const T *)w, (T *)out, TH, nstrips, nchunks, nblocks, nt);
     else
-        hipLaunchKernelGGL((k_gconv_nhwc_s1<T, CG, OB, PF, false>), dim3(nblocks), dim3(bs), 0, st, g, (const T *)in,
+        hipLaunchKernelGGL((k_gconv_nhwc_s1<T, CG, OB, GPL, PF, false>), dim3(nblocks), dim3(bs), 0, st, g, (const T *)in,
                            (const T *)w, (T *)out, TH, nstrips, nchunks, nblocks, nt);
     return hipGetLastError();
 }
@@ -335,11 +343,13 @@ hipError_t gconv_nhwc_s1(const GGeom &g, int dtype, const void *in, const void *
     if (!gconv_nhwc_supported(g)) return hipErrorInvalidValue;
     const int CG = flip ? g.Og : g.Cg, CGW = flip ? g.Cg : g.Og;
     const int OB = nhwc_ob(CG, CGW);
-#define TRY(T, CGG, OBB, PPF) if (CG == CGG && OB == OBB) return launch_gs1<T, CGG, OBB, PPF>(g, in, w, out, flip, st)
+    // two channels per group on both sides and an even number of groups: two groups per lane
+    const int GPL = (CG == 2 && CGW == 2 && g.G % 2 == 0 && !getenv("DWCONV_TUNE_GGPL1")) ? 2 : 1;
+#define TRY(T, CGG, OBB, GG, PPF) if (CG == CGG && OB == OBB && GPL == GG) return launch_gs1<T, CGG, OBB, GG, PPF>(g, in, w, out, flip, st)
     if (dtype == DT_F32) {
-        TRY(float, 2, 4, 2); TRY(float, 2, 2, 2); TRY(float, 4, 2, 2); TRY(float, 4, 1, 2); TRY(float, 8, 1, 1);
+        TRY(float, 2, 4, 1, 2); TRY(float, 2, 2, 1, 2); TRY(float, 2, 2, 2, 2); TRY(float, 4, 2, 1, 2); TRY(float, 4, 1, 1, 2); TRY(float, 8, 1, 1, 1);
     } else {
-        TRY(bf16_t, 2, 4, 2); TRY(bf16_t, 2, 2, 2); TRY(bf16_t, 4, 2, 2); TRY(bf16_t, 4, 1, 2); TRY(bf16_t, 8, 1, 1);
+        TRY(bf16_t, 2, 4, 1, 2); TRY(bf16_t, 2, 2, 1, 2); TRY(bf16_t, 2, 2, 2, 2); TRY(bf16_t, 4, 2, 1, 2); TRY(bf16_t, 4, 1, 1, 2); TRY(bf16_t, 8, 1, 1, 1);
     }
 #undef TRY
     return hipErrorInvalidValue;
