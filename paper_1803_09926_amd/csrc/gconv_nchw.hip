@@ -4,13 +4,12 @@
 // Forward / backward-data (k_gconv_nchw_s1): a block works on one group and OB of its output channels; a
 // lane owns V consecutive columns of one (image, strip) and walks the strip's rows.  The group's filters sit
 // in LDS as [input channel][tap row][tap column][output channel]: every lane of the block reads the same
-// entries (a broadcast), one (input channel, tap row) ahead of the multiply-adds that use them.  One step of
-// the walk takes one row of ONE input channel: three loads (the V-column vector and its two neighbours),
-// 9*OB weights, 9*OB*V multiply-adds into three rows of accumulators.  The loop over input channels is a real
-// loop, so the kernel serves any group size; rows are loaded R steps ahead, R at a time.  Input rows above and
-// below a strip feed only one or two output rows: the rest of their arithmetic is skipped (the step index is
-// uniform over the block).  Backward-data is the same walk over dy with the roles of the channels swapped and
-// the taps reversed.
+// entries (a broadcast).  One step of the walk takes one row of ONE input channel: three loads (the V-column
+// vector and its two neighbours), 9*OB weights, 9*OB*V multiply-adds into three rows of accumulators.  The
+// loop over input channels is a real loop, so the kernel serves any group size; the row of the next step is
+// loaded while the current one is used.  Input rows above and below a strip feed only one or two output
+// rows: the rest of their arithmetic is skipped (the step index is uniform over the block).  Backward-data
+// is the same walk over dy with the roles of the channels swapped and the taps reversed.
 //
 // Filter gradient (k_gconv_nchw_bwd_filter): a block works on one input channel b of a group and OB of the
 // group's output channels; a lane owns V columns of (image, strip) items and keeps 9*OB sums.  Per output row
@@ -63,15 +62,17 @@ template <typename T, int V> struct RowIn {
     }
 };
 
-// R = steps loaded ahead (a ring of R rows in registers, R divides CI); the walk is the flat sequence of
-// (input row t, input channel b) steps.  The three rows of accumulators change roles from one input row to
-// the next; the row loop is unrolled by three so that this costs no register moves.
-template <typename T, int V, int OB, int R, bool FLIP>
+// Forward / backward-data walk: a loop over the input rows, inside it a loop over the input channels, one row of
+// one channel loaded a step ahead, the weights of a step read from LDS as the step runs.  The accumulator rows
+// change roles by register moves once per input row.  Few registers (five or more wavefronts per SIMD).  Variants
+// with deeper prefetch rings, weights read a sub-step ahead, weights in scalar registers, and a row loop
+// unrolled by three to avoid the moves all measured within a few per cent of this one.
+template <typename T, int V, int OB, bool FLIP>
 __global__ __launch_bounds__(256) void k_gconv_nchw_s1(GGeom g, const T *__restrict__ in, const T *__restrict__ w,
-                                                       T *__restrict__ out, int CI, int CO, int CIN_T, int COUT_T, int TH,
-                                                       int nstrips, int ncv, int nlanes, int nlb, unsigned nblocks, int nt)
+                                                        T *__restrict__ out, int CI, int CO, int CIN_T, int COUT_T, int TH,
+                                                        int nstrips, int ncv, int nlanes, int nlb, unsigned nblocks, int nt)
 {
-    extern __shared__ __align__(16) float wl[];     // [CI][3][3][OB]: input channel, tap row, tap column, output
+    extern __shared__ __align__(16) float wl[];     // [CI][3][3][OB]
     unsigned lb = xcd_remap(blockIdx.x, nblocks);
     const int nchunks = CO / OB;
     const int chunk = lb % nchunks; lb /= nchunks;
@@ -80,8 +81,8 @@ __global__ __launch_bounds__(256) void k_gconv_nchw_s1(GGeom g, const T *__restr
     for (int i = threadIdx.x; i < CI * 9 * OB; i += 256) {
         const int a = i % OB, tap = (i / OB) % 9, b = i / (9 * OB);
         int widx;
-        if (!FLIP) widx = ((grp * g.Og + chunk * OB + a) * g.Cg + b) * 9 + tap;          // output a, input b
-        else       widx = ((grp * g.Og + b) * g.Cg + chunk * OB + a) * 9 + (8 - tap);    // dx channel a, dy channel b
+        if (!FLIP) widx = ((grp * g.Og + chunk * OB + a) * g.Cg + b) * 9 + tap;
+        else       widx = ((grp * g.Og + b) * g.Cg + chunk * OB + a) * 9 + (8 - tap);
         wl[i] = ldf(w + widx);
     }
     __syncthreads();
@@ -101,105 +102,47 @@ __global__ __launch_bounds__(256) void k_gconv_nchw_s1(GGeom g, const T *__restr
 #pragma unroll
         for (int j = 0; j < V; ++j) { A0[a][j] = 0.f; A1[a][j] = 0.f; A2[a][j] = 0.f; }
 
-    RowIn<T, V> ring[R];
-    int lt = 0, lbb = 0;                // (row step, channel) of the next load; uniform over the block
-    auto issue = [&](RowIn<T, V> &slot) {
-        const int rn = min(max(oh0 - 1 + lt, 0), H - 1);      // clamped: loads past the walk's end are unused
-        slot.load(ibase + (size_t)lbb * HW + (size_t)rn * W, col0, W);
-        if (++lbb == CI) { lbb = 0; ++lt; }
-    };
+    auto fma_row = [&](float (&P)[OB][V], const float *wk, const float (&x)[V + 2]) {
 #pragma unroll
-    for (int j = 0; j < R; ++j) issue(ring[j]);
-
-    // tap row kh of input row t feeds output row t - kh (in strip-local step numbers: step t is input row
-    // oh0 - 1 + t, and output row oh0 + t - 2 is complete after it)
-    // The filters are read from LDS one (input channel, tap row) at a time: 3*OB values, the same for every
-    // lane.  The read for the next sub-step is issued before the current sub-step's 3*OB*V multiply-adds,
-    // so its latency is hidden; wn always holds the next sub-step's weights (those of sub-step 0 between rows).
-    float wn[3][OB];
-    auto wread = [&](int q) {
-#pragma unroll
-        for (int kw = 0; kw < 3; ++kw) LdsW<OB>::get(wl + (q * 3 + kw) * OB, wn[kw]);
-    };
-    wread(0);
-    auto fma_row = [&](float (&P)[OB][V], const float (&wc)[3][OB], const float (&x)[V + 2]) {
-#pragma unroll
-        for (int kw = 0; kw < 3; ++kw)
+        for (int kw = 0; kw < 3; ++kw) {
+            float wv[OB];
+            LdsW<OB>::get(wk + kw * OB, wv);
 #pragma unroll
             for (int a = 0; a < OB; ++a)
 #pragma unroll
-                for (int q = 0; q < V; ++q) P[a][q] = fmaf(wc[kw][a], x[q + kw], P[a][q]);
+                for (int q = 0; q < V; ++q) P[a][q] = fmaf(wv[a], x[q + kw], P[a][q]);
+        }
     };
-    // One input row, all CI channels.  P2 collects tap row 0 (a fresh output row), P1 tap row 1, P0 tap row 2
-    // (the output row that is complete afterwards: stored, then cleared for its next role).
-    auto row_pass = [&](float (&P0)[OB][V], float (&P1)[OB][V], float (&P2)[OB][V], int t) {
+
+    RowIn<T, V> cur;
+    cur.load(ibase + (size_t)min(max(oh0 - 1, 0), H - 1) * W, col0, W);
+#pragma unroll 1
+    for (int t = 0; t < TH + 2; ++t) {
         const int r = oh0 - 1 + t;
         const bool rowok = r >= 0 && r < H;
-        const bool f0 = t <= TH - 1, f1 = t >= 1 && t <= TH, f2 = t >= 2;   // uniform: the output rows this row feeds
+        const bool f0 = t <= TH - 1, f1 = t >= 1 && t <= TH, f2 = t >= 2;   // uniform over the block
+        const int rnext = min(max(r + 1, 0), H - 1);
 #pragma unroll 1
-        for (int b0 = 0; b0 < CI; b0 += R) {
-            // all R rows out of the ring first, then the next R loads into it, then the arithmetic: the loads
-            // have the whole group's arithmetic to arrive, also when the wait at the top of the next group
-            // is for every outstanding load
-            float xs[R][V + 2];
-#pragma unroll
-            for (int j = 0; j < R; ++j) ring[j].get(xs[j], rowok, col0, W);
-#pragma unroll
-            for (int j = 0; j < R; ++j) issue(ring[j]);
-            if (f0 && f1 && f2) {               // an interior row
-#pragma unroll
-                for (int j = 0; j < R; ++j) {
-#pragma unroll
-                    for (int kh = 0; kh < 3; ++kh) {
-                        float wc[3][OB];
-#pragma unroll
-                        for (int kw = 0; kw < 3; ++kw)
-#pragma unroll
-                            for (int a = 0; a < OB; ++a) wc[kw][a] = wn[kw][a];
-                        int qn = (b0 + j) * 3 + kh + 1;
-                        if (qn == 3 * CI) qn = 0;
-                        wread(qn);
-                        fma_row(kh == 0 ? P2 : (kh == 1 ? P1 : P0), wc, xs[j]);
-                        __builtin_amdgcn_sched_barrier(0);      // keeps the reads one sub-step ahead, not more
-                    }
-                }
-            } else {                            // first two and last two rows of the strip: unpipelined
-#pragma unroll
-                for (int j = 0; j < R; ++j) {
-                    float wc[3][OB];
-                    if (f0) {
-#pragma unroll
-                        for (int kw = 0; kw < 3; ++kw) LdsW<OB>::get(wl + (((b0 + j) * 3 + 0) * 3 + kw) * OB, wc[kw]);
-                        fma_row(P2, wc, xs[j]);
-                    }
-                    if (f1) {
-#pragma unroll
-                        for (int kw = 0; kw < 3; ++kw) LdsW<OB>::get(wl + (((b0 + j) * 3 + 1) * 3 + kw) * OB, wc[kw]);
-                        fma_row(P1, wc, xs[j]);
-                    }
-                    if (f2) {
-#pragma unroll
-                        for (int kw = 0; kw < 3; ++kw) LdsW<OB>::get(wl + (((b0 + j) * 3 + 2) * 3 + kw) * OB, wc[kw]);
-                        fma_row(P0, wc, xs[j]);
-                    }
-                }
-            }
+        for (int b = 0; b < CI; ++b) {
+            float x[V + 2];
+            cur.get(x, rowok, col0, W);
+            // next step's row (next channel, or channel 0 of the next input row); the last one is unused
+            const bool wrap = b + 1 == CI;
+            cur.load(ibase + (size_t)(wrap ? 0 : b + 1) * HW + (size_t)(wrap ? rnext : min(max(r, 0), H - 1)) * W, col0, W);
+            const float *wb = wl + b * 9 * OB;
+            if (f0) fma_row(A2, wb, x);
+            if (f1) fma_row(A1, wb + 3 * OB, x);
+            if (f2) fma_row(A0, wb + 6 * OB, x);
         }
         const int orow = r - 1;
         if (f2 && active && orow < oh1) {
 #pragma unroll
-            for (int a = 0; a < OB; ++a) store_vec<T, V>(obase + (size_t)a * HW + (size_t)orow * W, P0[a], nt != 0);
+            for (int a = 0; a < OB; ++a) store_vec<T, V>(obase + (size_t)a * HW + (size_t)orow * W, A0[a], nt != 0);
         }
 #pragma unroll
         for (int a = 0; a < OB; ++a)
 #pragma unroll
-            for (int q = 0; q < V; ++q) P0[a][q] = 0.f;
-    };
-#pragma unroll 1
-    for (int t = 0; t < TH + 2; t += 3) {
-        row_pass(A0, A1, A2, t);
-        if (t + 1 < TH + 2) row_pass(A1, A2, A0, t + 1);
-        if (t + 2 < TH + 2) row_pass(A2, A0, A1, t + 2);
+            for (int q = 0; q < V; ++q) { A0[a][q] = A1[a][q]; A1[a][q] = A2[a][q]; A2[a][q] = 0.f; }
     }
 }
 
@@ -364,21 +307,22 @@ hipError_t gconv_nchw_s1(const GGeom &g, int dtype, const void *in, const void *
     const size_t lds = (size_t)CI * 9 * OB * sizeof(float);
     const int esz = dtype == DT_F32 ? 4 : 2;
     const int nt = stream_stores(flip ? "GROUP_NCHW_BWD" : "GROUP_NCHW_FWD", (long long)g.N * COUT_T * g.H * g.W * esz);
-    int R = CI % 2 == 0 ? 2 : 1;      // two steps ahead keeps the kernel within 128 registers
-    const int rforce = gtune("DWCONV_TUNE_GR", 0);
-    if (rforce > 0 && CI % rforce == 0) R = rforce;
-#define GO5(T, VV, OBB, RR, FL)                                                                                             \
-    hipLaunchKernelGGL((k_gconv_nchw_s1<T, VV, OBB, RR, FL>), dim3(nblocks), dim3(256), lds, st, g, (const T *)in,          \
-                       (const T *)w, (T *)out, CI, CO, CIN_T, COUT_T, TH, nstrips, ncv, nlanes, (int)nlb, nblocks, nt)
-#define GO4(T, VV, OBB, RR) do { if (flip) GO5(T, VV, OBB, RR, true); else GO5(T, VV, OBB, RR, false); } while (0)
-#define GO3(T, VV, OBB) do { if (R == 4) GO4(T, VV, OBB, 4); else if (R == 2) GO4(T, VV, OBB, 2); else GO4(T, VV, OBB, 1); } while (0)
+#define GO4(T, VV, OBB)                                                                                                     \
+    do {                                                                                                                    \
+        if (flip) hipLaunchKernelGGL((k_gconv_nchw_s1<T, VV, OBB, true>), dim3(nblocks), dim3(256), lds, st, g,             \
+                                     (const T *)in, (const T *)w, (T *)out, CI, CO, CIN_T, COUT_T, TH, nstrips, ncv, nlanes, \
+                                     (int)nlb, nblocks, nt);                                                                \
+        else hipLaunchKernelGGL((k_gconv_nchw_s1<T, VV, OBB, false>), dim3(nblocks), dim3(256), lds, st, g,                 \
+                                (const T *)in, (const T *)w, (T *)out, CI, CO, CIN_T, COUT_T, TH, nstrips, ncv, nlanes,     \
+                                (int)nlb, nblocks, nt);                                                                     \
+    } while (0)
+#define GO3(T, VV, OBB) GO4(T, VV, OBB)
 #define GO2(T, VV) do { if (OB == 4) GO3(T, VV, 4); else if (OB == 2) GO3(T, VV, 2); else GO3(T, VV, 1); } while (0)
     if (dtype == DT_F32) { if (V == 4) GO2(float, 4); else GO2(float, 2); }
     else                 { if (V == 4) GO2(bf16_t, 4); else GO2(bf16_t, 2); }
 #undef GO2
 #undef GO3
 #undef GO4
-#undef GO5
     return hipGetLastError();
 }
 
