@@ -224,3 +224,17 @@ def test_group_variants_and_depthwise_delegation():
     # untuned group shapes fall back to the generic group kernels
     assert dw.gconv_variant_name(dw.group_desc(2, 12, 9, 9, 5, 1, 2, groups=4, O=12), 0) == "group_generic"
     assert dw.gconv_variant_name(dw.group_desc(2, 12, 9, 9, 3, 2, 1, groups=4, O=12, layout=dw.NHWC), 1) == "group_generic"
+
+
+def test_group_benchmark_layers_get_tuned_variants():
+    from paper_1803_09926_amd import workloads as wl
+    cfg = wl.config(6)
+    for layer, _ in cfg["layers"]:
+        for layout in cfg["layouts"]:
+            d = dw.group_desc(cfg["N"], layer.C, layer.H, layer.W, layer.K, layer.stride, layer.pad, layer.groups,
+                              layer.O, layout, cfg["dtype"])
+            assert dw.gconv_out_dims(d) == (layer.Ho, layer.Wo)
+            assert 0 < dw.gconv_bwd_filter_workspace_bytes(d) <= (64 << 20)
+            for which in range(3):
+                name = dw.gconv_variant_name(d, which)
+                assert name.startswith("group_") and name != "group_generic", (layer.name, layout, which, name)

@@ -91,3 +91,65 @@ def test_group_bwd_filter_is_deterministic():
         a = run_gpu(case, layout, wl.F32, x, w, dy)[2]
         b = run_gpu(case, layout, wl.F32, x, w, dy)[2]
         assert torch.equal(a, b)
+
+
+def test_group_benchmark_workload_full_size_sampled():
+    """The group-convolution benchmark workload at its full size, in the launch configuration bench.py times;
+    oracle on sampled images (fwd, bwd_data: images are independent) and on sampled groups over the whole batch
+    (bwd_filter: groups are independent)."""
+    cfg = wl.config(6)
+    N = cfg["N"]
+    for li, (layer, _) in enumerate(cfg["layers"]):
+        for layout in cfg["layouts"]:
+            print("group workload", layer.name, "layout", layout, flush=True)
+            C, G, Cg = layer.C, layer.groups, layer.cg
+            x, w, dy = wl.make_inputs_device(layer, N, layout, cfg["dtype"], seed=6000 + li)
+            d = dw.group_desc(N, C, layer.H, layer.W, 3, 1, 1, G, C, layout, cfg["dtype"])
+            y = torch.full_like(dy, float("nan")); dx = torch.full_like(x, float("nan"))
+            dwt = torch.full(w.shape, float("nan"), device="cuda", dtype=torch.float32)
+            wsb = torch.full((max(dw.gconv_bwd_filter_workspace_bytes(d), 16),), 0xFF, device="cuda", dtype=torch.uint8)
+            dw.gconv_fwd(d, x, w, y); dw.gconv_bwd_data(d, dy, w, dx); dw.gconv_bwd_filter(d, x, dy, dwt, wsb)
+            torch.cuda.synchronize()
+            tag = "%s layout=%d" % (layer.name, layout)
+            kw = dict(K=3, stride=1, pad=1, groups=G, O=C, layout=layout, nthreads=8)
+            wh = gu.to_host(w)
+            imgs = sorted({0, N // 2 - 1, N - 1})
+            xh, dyh = gu.to_host(x[imgs]), gu.to_host(dy[imgs])
+            gu.assert_close(gu.to_host(y[imgs]), og.fwd(xh, wh, **kw), gu.TOL_F32, "gconv fwd " + tag)
+            gu.assert_close(gu.to_host(dx[imgs]), og.bwd_data(dyh, wh, x_shape=xh.shape, **kw), gu.TOL_F32, "gconv bwd_data " + tag)
+            kw1 = dict(K=3, stride=1, pad=1, groups=1, O=Cg, layout=layout, nthreads=8)
+            for gi in sorted({0, G // 2 + 1 if G > 2 else 0, G - 1}):
+                sl = slice(gi * Cg, (gi + 1) * Cg)
+                if layout == wl.NCHW:
+                    xc, dyc, got = gu.to_host(x[:, sl]), gu.to_host(dy[:, sl]), gu.to_host(dwt[sl])
+                else:
+                    xc, dyc, got = gu.to_host(x[..., sl]), gu.to_host(dy[..., sl]), gu.to_host(dwt[..., sl])
+                gu.assert_close(got, og.bwd_filter(xc, dyc, **kw1), gu.TOL_F32_FILTER, "gconv bwd_filter group %d %s" % (gi, tag))
+            del x, w, dy, y, dx, dwt
+            torch.cuda.empty_cache()
+
+
+def test_group_conv_writes_nothing_outside_its_outputs():
+    G_ = 256
+    for dtype in DTYPES:
+        tdt = torch.float32 if dtype == wl.F32 else torch.bfloat16
+        for layout in LAYOUTS:
+            for case in [("gb1", 3, 8, 8, 2, 13, 12, 3, 1, 1), ("gb2", 2, 16, 16, 8, 9, 14, 3, 1, 1), ("gb3", 2, 12, 12, 4, 7, 9, 3, 2, 1)]:
+                name, N, C, O, G, H, W, K, s, p = case
+                x, w, dy = wl.make_group_inputs(N, C, O, G, H, W, K, s, p, layout, dtype, seed=3)
+                xt, wt, dyt = gu.to_dev(x, dtype), gu.to_dev(w, dtype), gu.to_dev(dy, dtype)
+                d = dw.group_desc(N, C, H, W, K, s, p, G, O, layout, dtype)
+
+                def guarded(n, dt):
+                    n_pad = (n + 7) // 8 * 8
+                    buf = torch.full((n_pad + 2 * G_,), 12345.0, device="cuda", dtype=dt)
+                    return buf, buf[G_:G_ + n]
+                ybuf, yv = guarded(dy.size, tdt)
+                dxbuf, dxv = guarded(x.size, tdt)
+                dwbuf, dwv = guarded(w.size, torch.float32)
+                wsb = torch.zeros(max(dw.gconv_bwd_filter_workspace_bytes(d), 16), device="cuda", dtype=torch.uint8)
+                dw.gconv_fwd(d, xt, wt, yv); dw.gconv_bwd_data(d, dyt, wt, dxv); dw.gconv_bwd_filter(d, xt, dyt, dwv, wsb)
+                torch.cuda.synchronize()
+                for buf, v in [(ybuf, yv), (dxbuf, dxv), (dwbuf, dwv)]:
+                    n = v.numel()
+                    assert (buf[:G_] == 12345.0).all() and (buf[G_ + n:] == 12345.0).all(), (name, layout, dtype)
