@@ -67,8 +67,8 @@ template <typename T, int V> struct RowIn {
 // change roles by register moves once per input row.  Few registers (five or more wavefronts per SIMD).  Variants
 // with deeper prefetch rings, weights read a sub-step ahead, weights in scalar registers, and a row loop
 // unrolled by three to avoid the moves all measured within a few per cent of this one.
-template <typename T, int V, int OB, bool FLIP>
-__global__ __launch_bounds__(256) void k_gconv_nchw_s1(GGeom g, const T *__restrict__ in, const T *__restrict__ w,
+template <typename T, int V, int OB, int R, bool FLIP>
+__global__ __launch_bounds__(256, (R == 4 && V == 4 && OB == 4) ? 4 : 1) void k_gconv_nchw_s1(GGeom g, const T *__restrict__ in, const T *__restrict__ w,
                                                         T *__restrict__ out, int CI, int CO, int CIN_T, int COUT_T, int TH,
                                                         int nstrips, int ncv, int nlanes, int nlb, unsigned nblocks, int nt)
 {
@@ -114,25 +114,37 @@ __global__ __launch_bounds__(256) void k_gconv_nchw_s1(GGeom g, const T *__restr
         }
     };
 
-    RowIn<T, V> cur;
-    cur.load(ibase + (size_t)min(max(oh0 - 1, 0), H - 1) * W, col0, W);
+    // R rows (steps of the flat (input row, channel) sequence) are kept in flight: all R are taken out of the
+    // ring, the next R loads are issued into it, then the R steps are computed.  What bounds this kernel is the
+    // number of bytes in flight (wavefronts x rows ahead x 24 bytes per lane) against the memory latency.
+    RowIn<T, V> ring[R];
+    int lt = 0, lbb = 0;                // (row step, channel) of the next load; uniform over the block
+    auto issue = [&](RowIn<T, V> &slot) {
+        const int rn = min(max(oh0 - 1 + lt, 0), H - 1);      // clamped: loads past the walk's end are unused
+        slot.load(ibase + (size_t)lbb * HW + (size_t)rn * W, col0, W);
+        if (++lbb == CI) { lbb = 0; ++lt; }
+    };
+#pragma unroll
+    for (int j = 0; j < R; ++j) issue(ring[j]);
 #pragma unroll 1
     for (int t = 0; t < TH + 2; ++t) {
         const int r = oh0 - 1 + t;
         const bool rowok = r >= 0 && r < H;
         const bool f0 = t <= TH - 1, f1 = t >= 1 && t <= TH, f2 = t >= 2;   // uniform over the block
-        const int rnext = min(max(r + 1, 0), H - 1);
 #pragma unroll 1
-        for (int b = 0; b < CI; ++b) {
-            float x[V + 2];
-            cur.get(x, rowok, col0, W);
-            // next step's row (next channel, or channel 0 of the next input row); the last one is unused
-            const bool wrap = b + 1 == CI;
-            cur.load(ibase + (size_t)(wrap ? 0 : b + 1) * HW + (size_t)(wrap ? rnext : min(max(r, 0), H - 1)) * W, col0, W);
-            const float *wb = wl + b * 9 * OB;
-            if (f0) fma_row(A2, wb, x);
-            if (f1) fma_row(A1, wb + 3 * OB, x);
-            if (f2) fma_row(A0, wb + 6 * OB, x);
+        for (int b0 = 0; b0 < CI; b0 += R) {
+            float xs[R][V + 2];
+#pragma unroll
+            for (int j = 0; j < R; ++j) ring[j].get(xs[j], rowok, col0, W);
+#pragma unroll
+            for (int j = 0; j < R; ++j) issue(ring[j]);
+#pragma unroll
+            for (int j = 0; j < R; ++j) {
+                const float *wb = wl + (b0 + j) * 9 * OB;
+                if (f0) fma_row(A2, wb, xs[j]);
+                if (f1) fma_row(A1, wb + 3 * OB, xs[j]);
+                if (f2) fma_row(A0, wb + 6 * OB, xs[j]);
+            }
         }
         const int orow = r - 1;
         if (f2 && active && orow < oh1) {
@@ -307,22 +319,26 @@ hipError_t gconv_nchw_s1(const GGeom &g, int dtype, const void *in, const void *
     const size_t lds = (size_t)CI * 9 * OB * sizeof(float);
     const int esz = dtype == DT_F32 ? 4 : 2;
     const int nt = stream_stores(flip ? "GROUP_NCHW_BWD" : "GROUP_NCHW_FWD", (long long)g.N * COUT_T * g.H * g.W * esz);
-#define GO4(T, VV, OBB)                                                                                                     \
+    // rows in flight per lane: R must divide the channels read per group
+    int R = CI % 4 == 0 ? 4 : (CI % 2 == 0 ? 2 : 1);
+    const int rcap = gtune("DWCONV_TUNE_GR", 4);
+    while (R > rcap) R /= 2;
+#define GO5(T, VV, OBB, RR)                                                                                                 \
     do {                                                                                                                    \
-        if (flip) hipLaunchKernelGGL((k_gconv_nchw_s1<T, VV, OBB, true>), dim3(nblocks), dim3(256), lds, st, g,             \
+        if (flip) hipLaunchKernelGGL((k_gconv_nchw_s1<T, VV, OBB, RR, true>), dim3(nblocks), dim3(256), lds, st, g,         \
                                      (const T *)in, (const T *)w, (T *)out, CI, CO, CIN_T, COUT_T, TH, nstrips, ncv, nlanes, \
                                      (int)nlb, nblocks, nt);                                                                \
-        else hipLaunchKernelGGL((k_gconv_nchw_s1<T, VV, OBB, false>), dim3(nblocks), dim3(256), lds, st, g,                 \
+        else hipLaunchKernelGGL((k_gconv_nchw_s1<T, VV, OBB, RR, false>), dim3(nblocks), dim3(256), lds, st, g,             \
                                 (const T *)in, (const T *)w, (T *)out, CI, CO, CIN_T, COUT_T, TH, nstrips, ncv, nlanes,     \
                                 (int)nlb, nblocks, nt);                                                                     \
     } while (0)
-#define GO3(T, VV, OBB) GO4(T, VV, OBB)
+#define GO3(T, VV, OBB) do { if (R == 4) GO5(T, VV, OBB, 4); else if (R == 2) GO5(T, VV, OBB, 2); else GO5(T, VV, OBB, 1); } while (0)
 #define GO2(T, VV) do { if (OB == 4) GO3(T, VV, 4); else if (OB == 2) GO3(T, VV, 2); else GO3(T, VV, 1); } while (0)
     if (dtype == DT_F32) { if (V == 4) GO2(float, 4); else GO2(float, 2); }
     else                 { if (V == 4) GO2(bf16_t, 4); else GO2(bf16_t, 2); }
 #undef GO2
 #undef GO3
-#undef GO4
+#undef GO5
     return hipGetLastError();
 }
 
