@@ -40,23 +40,37 @@ template <> struct LdsW<1> {
     static __device__ __forceinline__ void get(const float *p, float (&r)[1]) { r[0] = *p; }
 };
 
-// One row of one plane as a lane sees it: its V columns and the two neighbours, as loaded.
-template <typename T, int V> struct RowIn {
+// One row of one plane as a lane sees it: its V columns and the two neighbours.  Consecutive lanes own consecutive
+// column vectors, so the neighbour columns come from the neighbour lanes by a wavefront shuffle when the row is
+// used; only the first and the last lane of a wavefront load theirs (a load with one active lane).  This halves
+// the vector-memory instructions of the walk (SHFL; without it every lane loads its two neighbours).  Lanes at the two ends of a row get the zero padding instead, so a
+// neighbour lane that belongs to another work item is never consulted.
+template <typename T, int V, bool SHFL> struct RowIn {
     RawVec<T, V> v;
     T l, r;
     __device__ __forceinline__ void load(const T *row, int col0, int W)
     {
+        const int lane = threadIdx.x & 63;
         v.load(row + col0);
-        l = row[max(col0 - 1, 0)];
-        r = row[min(col0 + V, W - 1)];
+        T lv = 0, rv = 0;
+        if (!SHFL || lane == 0) lv = row[max(col0 - 1, 0)];
+        if (!SHFL || lane == 63) rv = row[min(col0 + V, W - 1)];
+        l = lv; r = rv;
     }
     // x[0..V+1] = columns col0-1 .. col0+V, zero outside the row or when the row itself is outside the image
     __device__ __forceinline__ void get(float (&x)[V + 2], bool rowok, int col0, int W) const
     {
+        const int lane = threadIdx.x & 63;
         float c[V];
         v.get(c);
-        x[0] = (rowok && col0 > 0) ? ldf(&l) : 0.f;
-        x[V + 1] = (rowok && col0 + V < W) ? ldf(&r) : 0.f;
+        float left = ldf(&l), right = ldf(&r);
+        if (SHFL) {
+            const float sl = __shfl_up(c[V - 1], 1, 64), sr = __shfl_down(c[0], 1, 64);
+            if (lane != 0) left = sl;
+            if (lane != 63) right = sr;
+        }
+        x[0] = (rowok && col0 > 0) ? left : 0.f;
+        x[V + 1] = (rowok && col0 + V < W) ? right : 0.f;
 #pragma unroll
         for (int j = 0; j < V; ++j) x[1 + j] = rowok ? c[j] : 0.f;
     }
@@ -67,8 +81,8 @@ template <typename T, int V> struct RowIn {
 // change roles by register moves once per input row.  Few registers (five or more wavefronts per SIMD).  Variants
 // with deeper prefetch rings, weights read a sub-step ahead, weights in scalar registers, and a row loop
 // unrolled by three to avoid the moves all measured within a few per cent of this one.
-template <typename T, int V, int OB, int R, bool FLIP>
-__global__ __launch_bounds__(256, (R == 4 && V == 4 && OB == 4) ? 4 : 1) void k_gconv_nchw_s1(GGeom g, const T *__restrict__ in, const T *__restrict__ w,
+template <typename T, int V, int OB, int R, bool FLIP, bool SHFL>
+__global__ __launch_bounds__(256) void k_gconv_nchw_s1(GGeom g, const T *__restrict__ in, const T *__restrict__ w,
                                                         T *__restrict__ out, int CI, int CO, int CIN_T, int COUT_T, int TH,
                                                         int nstrips, int ncv, int nlanes, int nlb, unsigned nblocks, int nt)
 {
@@ -117,9 +131,9 @@ __global__ __launch_bounds__(256, (R == 4 && V == 4 && OB == 4) ? 4 : 1) void k_
     // R rows (steps of the flat (input row, channel) sequence) are kept in flight: all R are taken out of the
     // ring, the next R loads are issued into it, then the R steps are computed.  What bounds this kernel is the
     // number of bytes in flight (wavefronts x rows ahead x 24 bytes per lane) against the memory latency.
-    RowIn<T, V> ring[R];
+    RowIn<T, V, SHFL> ring[R];
     int lt = 0, lbb = 0;                // (row step, channel) of the next load; uniform over the block
-    auto issue = [&](RowIn<T, V> &slot) {
+    auto issue = [&](RowIn<T, V, SHFL> &slot) {
         const int rn = min(max(oh0 - 1 + lt, 0), H - 1);      // clamped: loads past the walk's end are unused
         slot.load(ibase + (size_t)lbb * HW + (size_t)rn * W, col0, W);
         if (++lbb == CI) { lbb = 0; ++lt; }
@@ -159,7 +173,7 @@ __global__ __launch_bounds__(256, (R == 4 && V == 4 && OB == 4) ? 4 : 1) void k_
 }
 
 // Filter gradient, stage 1.  Block: (group, input channel b, chunk of OB output channels, part).
-template <typename T, int V, int OB>
+template <typename T, int V, int OB, bool SHFL>
 __global__ __launch_bounds__(256) void k_gconv_nchw_bwd_filter(GGeom g, const T *__restrict__ x, const T *__restrict__ dy,
                                                                float *__restrict__ ws, int TH, int nstrips, int ncv,
                                                                int nitems, int parts, unsigned nblocks, int J)
@@ -189,14 +203,14 @@ __global__ __launch_bounds__(256) void k_gconv_nchw_bwd_filter(GGeom g, const T 
         // window of three x rows: X0 = row oh-1, X1 = row oh, X2 = row oh+1
         float X0[V + 2], X1[V + 2], X2[V + 2];
         {
-            RowIn<T, V> q;
+            RowIn<T, V, SHFL> q;
             q.load(xp + (size_t)max(oh0 - 1, 0) * W, col0, W);
             q.get(X1, oh0 - 1 >= 0, col0, W);
             q.load(xp + (size_t)oh0 * W, col0, W);
             q.get(X2, true, col0, W);
         }
         // two output rows ahead: slot j holds x row oh+1 and the dy rows oh of output row oh = oh0 + j (mod 2)
-        RowIn<T, V> xn[2];
+        RowIn<T, V, SHFL> xn[2];
         RawVec<T, V> dn[2][OB];
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
@@ -325,10 +339,10 @@ hipError_t gconv_nchw_s1(const GGeom &g, int dtype, const void *in, const void *
     while (R > rcap) R /= 2;
 #define GO5(T, VV, OBB, RR)                                                                                                 \
     do {                                                                                                                    \
-        if (flip) hipLaunchKernelGGL((k_gconv_nchw_s1<T, VV, OBB, RR, true>), dim3(nblocks), dim3(256), lds, st, g,         \
+        if (flip) hipLaunchKernelGGL((k_gconv_nchw_s1<T, VV, OBB, RR, true, (VV == 2)>), dim3(nblocks), dim3(256), lds, st, g, \
                                      (const T *)in, (const T *)w, (T *)out, CI, CO, CIN_T, COUT_T, TH, nstrips, ncv, nlanes, \
                                      (int)nlb, nblocks, nt);                                                                \
-        else hipLaunchKernelGGL((k_gconv_nchw_s1<T, VV, OBB, RR, false>), dim3(nblocks), dim3(256), lds, st, g,             \
+        else hipLaunchKernelGGL((k_gconv_nchw_s1<T, VV, OBB, RR, false, (VV == 2)>), dim3(nblocks), dim3(256), lds, st, g,  \
                                 (const T *)in, (const T *)w, (T *)out, CI, CO, CIN_T, COUT_T, TH, nstrips, ncv, nlanes,     \
                                 (int)nlb, nblocks, nt);                                                                     \
     } while (0)
@@ -379,8 +393,15 @@ hipError_t gconv_nchw_bwd_filter(const GGeom &g, int dtype, const void *x, const
     if (nb >= (1ll << 31)) return hipErrorInvalidValue;
     const unsigned nblocks = (unsigned)nb;
     const int J = g.O * g.Cg * 9;
-#define GO3(T, VV, OBB) hipLaunchKernelGGL((k_gconv_nchw_bwd_filter<T, VV, OBB>), dim3(nblocks), dim3(256), 0, st, g,      \
-                                           (const T *)x, (const T *)dy, ws, TH, nstrips, g.W / VV, nitems, parts, nblocks, J)
+    // neighbour columns by wavefront shuffle: measured faster for groups of 8 and on 14-wide rows, slower on 28
+    const bool shfl = gtune("DWCONV_TUNE_GWSHFL", (g.Cg >= 8 || g.W <= 14) ? 1 : 0) != 0;
+#define GO3(T, VV, OBB)                                                                                                     \
+    do {                                                                                                                    \
+        if (shfl) hipLaunchKernelGGL((k_gconv_nchw_bwd_filter<T, VV, OBB, true>), dim3(nblocks), dim3(256), 0, st, g,       \
+                                     (const T *)x, (const T *)dy, ws, TH, nstrips, g.W / VV, nitems, parts, nblocks, J);    \
+        else hipLaunchKernelGGL((k_gconv_nchw_bwd_filter<T, VV, OBB, false>), dim3(nblocks), dim3(256), 0, st, g,           \
+                                (const T *)x, (const T *)dy, ws, TH, nstrips, g.W / VV, nitems, parts, nblocks, J);         \
+    } while (0)
 #define GO2(T, VV) do { if (OB == 4) GO3(T, VV, 4); else if (OB == 2) GO3(T, VV, 2); else GO3(T, VV, 1); } while (0)
     if (dtype == DT_F32) { if (V == 4) GO2(float, 4); else GO2(float, 2); }
     else                 { if (V == 4) GO2(bf16_t, 4); else GO2(bf16_t, 2); }
