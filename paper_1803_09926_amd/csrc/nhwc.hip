@@ -169,6 +169,133 @@ __global__ __launch_bounds__(256, (S1_WAVES<V, K, PF>())) void k_nhwc_s1(
 }
 
 // ---------------------------------------------------------------------------------------------
+// Stride 1, "same" padding, multiplier 1, TWO output columns per lane.  The 5x5 walk on two channels per lane
+// is bound by the number of memory instructions (five 4-byte loads and a store per 50 multiply-adds); with two
+// adjacent columns a lane loads K+1 input columns for two outputs and the same filter registers serve both.
+// Padding: input values of columns outside the image are zeroed when the row is consumed (the filter cannot
+// carry the zeros here, since a tap meets different columns for the two outputs).
+// ---------------------------------------------------------------------------------------------
+template <typename T, int V, int K, int PF, bool FLIP, int NCOL>
+__global__ __launch_bounds__(256) void k_nhwc_s1_2col(Geom g, const T *__restrict__ x, const T *__restrict__ w,
+                                                      T *__restrict__ y, int TH, int nstrips, int nchunks,
+                                                      unsigned nblocks, int nt)
+{
+    constexpr int P = (K - 1) / 2;
+    constexpr int R = PF + 1;
+    constexpr int NC = K + NCOL - 1;      // input columns per lane
+    const Tile tl = tile_of(nblocks, nchunks, nstrips);
+    const int Q = g.C / V, W2 = (g.W + NCOL - 1) / NCOL;
+    const int f = tl.chunk * blockDim.x + threadIdx.x;
+    if (f >= W2 * Q) return;
+    const int cq = f % Q, ow = (f / Q) * NCOL;     // the last lane of a row may own fewer than NCOL columns
+
+    int coloff[NC];
+    bool colok[NC];
+#pragma unroll
+    for (int j = 0; j < NC; ++j) {
+        const int iw = ow - P + j;
+        colok[j] = iw >= 0 && iw < g.W;
+        coloff[j] = (colok[j] ? iw - ow : 0) * g.C;
+    }
+    float wr[K][K][V];
+#pragma unroll
+    for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < K; ++kw) {
+            const int sh = FLIP ? K - 1 - kh : kh, sw = FLIP ? K - 1 - kw : kw;
+            Vec<T, V>::load(w + (sh * K + sw) * g.C + cq * V, wr[kh][kw]);
+        }
+
+    const int oh0 = tl.strip * TH, oh1 = min(g.H, oh0 + TH);
+    const int rowstride = g.W * g.C;
+    const T *xin = x + (size_t)tl.n * g.H * rowstride + (size_t)ow * g.C + cq * V;
+    T *yout = y + (size_t)tl.n * g.H * rowstride + (size_t)ow * g.C + cq * V;
+
+    float acc[K - 1][NCOL][V];
+#pragma unroll
+    for (int j = 0; j < K - 1; ++j)
+#pragma unroll
+        for (int c = 0; c < NCOL; ++c)
+#pragma unroll
+            for (int v = 0; v < V; ++v) acc[j][c][v] = 0.f;
+
+    const int r0 = oh0 - P, r1 = oh1 + P;
+    const int ra = max(r0, 0), rb = min(r1, g.H);
+    RawVec<T, V> ring[R][NC];
+    auto load_row = [&](int r, RawVec<T, V> (&dst)[NC]) {
+        const T *rp = xin + (size_t)min(r, rb - 1) * rowstride;
+#pragma unroll
+        for (int j = 0; j < NC; ++j) dst[j].load(rp + coloff[j]);
+    };
+    auto emit = [&](int oh, const float (&out)[NCOL][V]) {
+        T *op = yout + (size_t)oh * rowstride;
+#pragma unroll
+        for (int c = 0; c < NCOL; ++c)
+            if (ow + c < g.W) store_vec<T, V>(op + c * g.C, out[c], nt != 0);
+    };
+    auto consume = [&](int r, const RawVec<T, V> (&raw)[NC]) {
+        float cur[NC][V];
+#pragma unroll
+        for (int j = 0; j < NC; ++j) {
+            raw[j].get(cur[j]);
+#pragma unroll
+            for (int v = 0; v < V; ++v) cur[j][v] = colok[j] ? cur[j][v] : 0.f;
+        }
+        float out[NCOL][V];
+#pragma unroll
+        for (int c = 0; c < NCOL; ++c)
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                float s = acc[0][c][v];
+#pragma unroll
+                for (int kw = 0; kw < K; ++kw) s = fmaf(wr[K - 1][kw][v], cur[c + kw][v], s);
+                out[c][v] = s;
+            }
+#pragma unroll
+        for (int j = 0; j < K - 1; ++j)
+#pragma unroll
+            for (int c = 0; c < NCOL; ++c)
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    float s = (j + 1 < K - 1) ? acc[j + 1][c][v] : 0.f;
+#pragma unroll
+                    for (int kw = 0; kw < K; ++kw) s = fmaf(wr[K - 2 - j][kw][v], cur[c + kw][v], s);
+                    acc[j][c][v] = s;
+                }
+        const int oh = r - P;
+        if (oh >= oh0) emit(oh, out);
+    };
+
+#pragma unroll
+    for (int j = 0; j < PF; ++j) load_row(ra + j, ring[j]);
+    int base = ra;
+#pragma unroll 1
+    for (; base + R <= rb; base += R) {
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            load_row(base + j + PF, ring[(j + PF) % R]);
+            consume(base + j, ring[j]);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < R - 1; ++j)
+        if (base + j < rb) consume(base + j, ring[j]);
+    for (int r = rb; r < r1; ++r) {
+        float out[NCOL][V];
+#pragma unroll
+        for (int c = 0; c < NCOL; ++c)
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                out[c][v] = acc[0][c][v];
+#pragma unroll
+                for (int j = 0; j < K - 1; ++j) acc[j][c][v] = (j + 1 < K - 1) ? acc[j + 1][c][v] : 0.f;
+            }
+        const int oh = r - P;
+        if (oh >= oh0) emit(oh, out);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Forward, 3x3, stride 2, pad 1, multiplier 1.  A lane owns output column ow and walks down the
 // output rows; input row 2*oh+1 is shared by output rows oh (tap row 2) and oh+1 (tap row 0).
 // The two input rows of the next output row are loaded while the current one is computed.
@@ -621,9 +748,35 @@ static hipError_t launch_s1(const Geom &g, const void *x, const void *w, void *y
     return hipGetLastError();
 }
 
+template <typename T, int V, int K, int PF, int NCOL>
+static hipError_t launch_s1_2col(const Geom &g, const void *x, const void *w, void *y, bool flip, int TH, hipStream_t st)
+{
+    const int lanes = ((g.W + NCOL - 1) / NCOL) * (g.C / V);
+    const int bs = flat_block(lanes);
+    const int nchunks = ceil_div(lanes, bs), nstrips = ceil_div(g.H, TH);
+    const unsigned nblocks = (unsigned)g.N * nchunks * nstrips;
+    const int nt = stream_stores(flip ? "NHWC_S1_BWD" : "NHWC_S1_FWD", (long long)g.N * g.H * g.W * g.C * sizeof(T), 0);
+    if (flip)
+        hipLaunchKernelGGL((k_nhwc_s1_2col<T, V, K, PF, true, NCOL>), dim3(nblocks), dim3(bs), 0, st, g, (const T *)x,
+                           (const T *)w, (T *)y, TH, nstrips, nchunks, nblocks, nt);
+    else
+        hipLaunchKernelGGL((k_nhwc_s1_2col<T, V, K, PF, false, NCOL>), dim3(nblocks), dim3(bs), 0, st, g, (const T *)x,
+                           (const T *)w, (T *)y, TH, nstrips, nchunks, nblocks, nt);
+    return hipGetLastError();
+}
+
 hipError_t nhwc_s1(const Geom &g, int dtype, int V, const void *x, const void *w, void *y, bool flip, int TH, int PF,
                    hipStream_t st)
 {
+    // bf16 5x5 on two channels per lane: two output columns per lane (fewer memory instructions)
+    if (dtype == DT_BF16 && g.m == 1 && g.K == 5 && V == 2 && !getenv("DWCONV_TUNE_NO2COL")) {
+        const char *e = getenv("DWCONV_TUNE_NCOL");
+        const int ncol = e ? atoi(e) : 2;
+        if (ncol == 4) return launch_s1_2col<bf16_t, 2, 5, 2, 4>(g, x, w, y, flip, TH, st);
+        if (ncol == 3) return launch_s1_2col<bf16_t, 2, 5, 2, 3>(g, x, w, y, flip, TH, st);
+        if (PF == 1) return launch_s1_2col<bf16_t, 2, 5, 1, 2>(g, x, w, y, flip, TH, st);
+        return launch_s1_2col<bf16_t, 2, 5, 2, 2>(g, x, w, y, flip, TH, st);
+    }
 #define TRY(T, VV, KK, PPF) if (g.m == 1 && g.K == KK && V == VV && PF == PPF) return launch_s1<T, VV, KK, PPF, 1>(g, x, w, y, flip, TH, st)
     // channel multiplier 2: 3x3, two rows ahead
     if (g.m == 2 && g.K == 3) {
