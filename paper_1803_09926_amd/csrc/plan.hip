@@ -203,7 +203,10 @@ Plan plan_bwd_filter(const Geom &g, int layout, int dtype)
         return pl;
     }
     if (layout == LAYOUT_NHWC) {
-        const int V = nhwc_vec(g, dtype);
+        int V = nhwc_vec(g, dtype);
+        // bf16 on small planes: four channels per lane (124 registers, four wavefronts per SIMD) measured faster
+        // than eight (182 registers, two wavefronts)
+        if (V == 8 && tune("DWCONV_TUNE_WV", g.W <= 14 ? 4 : 8) == 4) V = 4;
         if (V && (same_pad_s1(g) || k3s2p1(g))) {
             // One block = 256 lanes over (columns x channel-vectors) x one strip x NI images.  Long
             // walks win (fewer partials, less stage-2 work): start from whole columns and one image
