@@ -19,8 +19,8 @@ VARIANT_KERNELS = {
     # k_nhwc_s1<T, V, K, PF, FLIP, M>
     "fwd:nhwc_rowwalk_k3s1": [r"k_nhwc_s1<\w+, \d+, 3, \d+, false, 1>"],
     "bwd_data:nhwc_rowwalk_k3s1_flip": [r"k_nhwc_s1<\w+, \d+, 3, \d+, true, 1>"],
-    "fwd:nhwc_rowwalk_k5s1": [r"k_nhwc_s1<\w+, \d+, 5, \d+, false, 1>"],
-    "bwd_data:nhwc_rowwalk_k5s1_flip": [r"k_nhwc_s1<\w+, \d+, 5, \d+, true, 1>"],
+    "fwd:nhwc_rowwalk_k5s1": [r"k_nhwc_s1<\w+, \d+, 5, \d+, false, 1>", r"k_nhwc_s1_2col<\w+, \d+, 5, \d+, false,"],
+    "bwd_data:nhwc_rowwalk_k5s1_flip": [r"k_nhwc_s1<\w+, \d+, 5, \d+, true, 1>", r"k_nhwc_s1_2col<\w+, \d+, 5, \d+, true,"],
     "fwd:nhwc_rowwalk_k3s1_m2": [r"k_nhwc_s1<\w+, \d+, 3, \d+, false, 2>"],
     "bwd_data:nhwc_rowwalk_k3s1_flip_m2": [r"k_nhwc_s1<\w+, \d+, 3, \d+, true, 2>"],
     "fwd:nhwc_rowwalk_fwd_k3s2": [r"k_nhwc_fwd_k3s2<"],
