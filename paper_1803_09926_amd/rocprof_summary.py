@@ -17,50 +17,50 @@ import sys
 # bench.py's "<pass>:<variant>" keys -> the kernel(s) that implement them (regex on the demangled name)
 VARIANT_KERNELS = {
     # k_nhwc_s1<T, V, K, PF, FLIP, M>
-    "fwd:nhwc_rowwalk_k3s1": [r"k_nhwc_s1<\w+, \d+, 3, \d+, false, 1>"],
-    "bwd_data:nhwc_rowwalk_k3s1_flip": [r"k_nhwc_s1<\w+, \d+, 3, \d+, true, 1>"],
-    "fwd:nhwc_rowwalk_k5s1": [r"k_nhwc_s1<\w+, \d+, 5, \d+, false, 1>", r"k_nhwc_s1_2col<\w+, \d+, 5, \d+, false,"],
-    "bwd_data:nhwc_rowwalk_k5s1_flip": [r"k_nhwc_s1<\w+, \d+, 5, \d+, true, 1>", r"k_nhwc_s1_2col<\w+, \d+, 5, \d+, true,"],
-    "fwd:nhwc_rowwalk_k3s1_m2": [r"k_nhwc_s1<\w+, \d+, 3, \d+, false, 2>"],
-    "bwd_data:nhwc_rowwalk_k3s1_flip_m2": [r"k_nhwc_s1<\w+, \d+, 3, \d+, true, 2>"],
+    "fwd:nhwc_rowwalk_k3s1": [r"k_nhwc_s1<[\w ]+, \d+, 3, \d+, false, 1>"],
+    "bwd_data:nhwc_rowwalk_k3s1_flip": [r"k_nhwc_s1<[\w ]+, \d+, 3, \d+, true, 1>"],
+    "fwd:nhwc_rowwalk_k5s1": [r"k_nhwc_s1<[\w ]+, \d+, 5, \d+, false, 1>", r"k_nhwc_s1_2col<[\w ]+, \d+, 5, \d+, false,"],
+    "bwd_data:nhwc_rowwalk_k5s1_flip": [r"k_nhwc_s1<[\w ]+, \d+, 5, \d+, true, 1>", r"k_nhwc_s1_2col<[\w ]+, \d+, 5, \d+, true,"],
+    "fwd:nhwc_rowwalk_k3s1_m2": [r"k_nhwc_s1<[\w ]+, \d+, 3, \d+, false, 2>"],
+    "bwd_data:nhwc_rowwalk_k3s1_flip_m2": [r"k_nhwc_s1<[\w ]+, \d+, 3, \d+, true, 2>"],
     "fwd:nhwc_rowwalk_fwd_k3s2": [r"k_nhwc_fwd_k3s2<"],
     "bwd_data:nhwc_rowwalk_bwd_data_k3s2": [r"k_nhwc_bwd_data_k3s2<"],
     # k_nhwc_bwd_filter<T, V, K, S, PF, M>
-    "bwd_filter:nhwc_bwd_filter_k3s1": [r"k_nhwc_bwd_filter<\w+, \d+, 3, 1, \d+, 1>"],
-    "bwd_filter:nhwc_bwd_filter_k3s2": [r"k_nhwc_bwd_filter<\w+, \d+, 3, 2, \d+, 1>"],
-    "bwd_filter:nhwc_bwd_filter_k5s1": [r"k_nhwc_bwd_filter<\w+, \d+, 5, 1, \d+, 1>"],
-    "bwd_filter:nhwc_bwd_filter_k3s1_m2": [r"k_nhwc_bwd_filter<\w+, \d+, 3, 1, \d+, 2>"],
+    "bwd_filter:nhwc_bwd_filter_k3s1": [r"k_nhwc_bwd_filter<[\w ]+, \d+, 3, 1, \d+, 1>"],
+    "bwd_filter:nhwc_bwd_filter_k3s2": [r"k_nhwc_bwd_filter<[\w ]+, \d+, 3, 2, \d+, 1>"],
+    "bwd_filter:nhwc_bwd_filter_k5s1": [r"k_nhwc_bwd_filter<[\w ]+, \d+, 5, 1, \d+, 1>"],
+    "bwd_filter:nhwc_bwd_filter_k3s1_m2": [r"k_nhwc_bwd_filter<[\w ]+, \d+, 3, 1, \d+, 2>"],
     # k_nchwd_s1<T, V, K, PF, FLIP, RS> (RS > 0: whole-line write-out)
     # bf16: k_nchwd_s1_bf16x8<V, K, PF, FLIP, RS> (packed pairs)
-    "fwd:nchw_rowwalk_k3s1": [r"k_nchwd_s1<\w+, \d+, 3, \d+, false[,>]", r"k_nchwd_s1_bf16x8<\d+, 3, \d+, false,"],
-    "bwd_data:nchw_rowwalk_k3s1_flip": [r"k_nchwd_s1<\w+, \d+, 3, \d+, true[,>]", r"k_nchwd_s1_bf16x8<\d+, 3, \d+, true,"],
-    "fwd:nchw_rowwalk_k5s1": [r"k_nchwd_s1<\w+, \d+, 5, \d+, false[,>]", r"k_nchwd_s1_bf16x8<\d+, 5, \d+, false,"],
-    "bwd_data:nchw_rowwalk_k5s1_flip": [r"k_nchwd_s1<\w+, \d+, 5, \d+, true[,>]", r"k_nchwd_s1_bf16x8<\d+, 5, \d+, true,"],
+    "fwd:nchw_rowwalk_k3s1": [r"k_nchwd_s1<[\w ]+, \d+, 3, \d+, false[,>]", r"k_nchwd_s1_bf16x8<\d+, 3, \d+, false,"],
+    "bwd_data:nchw_rowwalk_k3s1_flip": [r"k_nchwd_s1<[\w ]+, \d+, 3, \d+, true[,>]", r"k_nchwd_s1_bf16x8<\d+, 3, \d+, true,"],
+    "fwd:nchw_rowwalk_k5s1": [r"k_nchwd_s1<[\w ]+, \d+, 5, \d+, false[,>]", r"k_nchwd_s1_bf16x8<\d+, 5, \d+, false,"],
+    "bwd_data:nchw_rowwalk_k5s1_flip": [r"k_nchwd_s1<[\w ]+, \d+, 5, \d+, true[,>]", r"k_nchwd_s1_bf16x8<\d+, 5, \d+, true,"],
     "fwd:nchw_rowwalk_fwd_k3s2": [r"k_nchwd_fwd_k3s2<"],
     "bwd_data:nchw_rowwalk_bwd_data_k3s2": [r"k_nchwd_bwd_data_k3s2<"],
-    "bwd_filter:nchw_rowwalk_bwd_filter_k3s1": [r"k_nchwd_bwd_filter_k3<\w+, \d+, 1>", r"k_nchwd_bwd_filter_s1_bf16<\d+, 3>"],
-    "bwd_filter:nchw_rowwalk_bwd_filter_k3s2": [r"k_nchwd_bwd_filter_k3<\w+, \d+, 2>"],
-    "bwd_filter:nchw_rowwalk_bwd_filter_k5s1": [r"k_nchwd_bwd_filter_s1<\w+, \d+, 5>", r"k_nchwd_bwd_filter_s1_bf16<\d+, 5>"],
+    "bwd_filter:nchw_rowwalk_bwd_filter_k3s1": [r"k_nchwd_bwd_filter_k3<[\w ]+, \d+, 1>", r"k_nchwd_bwd_filter_s1_bf16<\d+, 3>"],
+    "bwd_filter:nchw_rowwalk_bwd_filter_k3s2": [r"k_nchwd_bwd_filter_k3<[\w ]+, \d+, 2>"],
+    "bwd_filter:nchw_rowwalk_bwd_filter_k5s1": [r"k_nchwd_bwd_filter_s1<[\w ]+, \d+, 5>", r"k_nchwd_bwd_filter_s1_bf16<\d+, 5>"],
     # k_nchws_fwd<T, K, S, W, FLIP>, k_nchws_bwd_filter<T, K, S, W>
-    "fwd:nchw_smallplane_k3s1": [r"k_nchws_fwd<\w+, 3, 1, \d+, false>"],
-    "bwd_data:nchw_smallplane_k3s1_flip": [r"k_nchws_fwd<\w+, 3, 1, \d+, true>"],
-    "fwd:nchw_smallplane_fwd_k3s2": [r"k_nchws_fwd<\w+, 3, 2, \d+, false>"],
+    "fwd:nchw_smallplane_k3s1": [r"k_nchws_fwd<[\w ]+, 3, 1, \d+, false>"],
+    "bwd_data:nchw_smallplane_k3s1_flip": [r"k_nchws_fwd<[\w ]+, 3, 1, \d+, true>"],
+    "fwd:nchw_smallplane_fwd_k3s2": [r"k_nchws_fwd<[\w ]+, 3, 2, \d+, false>"],
     "bwd_data:nchw_smallplane_bwd_data_k3s2": [r"k_nchws_bwd_data_s2<"],
-    "bwd_filter:nchw_smallplane_bwd_filter_k3s1": [r"k_nchws_bwd_filter<\w+, 3, 1, \d+>"],
-    "bwd_filter:nchw_smallplane_bwd_filter_k3s2": [r"k_nchws_bwd_filter<\w+, 3, 2, \d+>"],
-    "fwd:nchw_smallplane_k5s1": [r"k_nchws_fwd<\w+, 5, 1, \d+, false>"],
-    "bwd_data:nchw_smallplane_k5s1_flip": [r"k_nchws_fwd<\w+, 5, 1, \d+, true>"],
-    "bwd_filter:nchw_smallplane_bwd_filter_k5s1": [r"k_nchws_bwd_filter<\w+, 5, 1, \d+>"],
+    "bwd_filter:nchw_smallplane_bwd_filter_k3s1": [r"k_nchws_bwd_filter<[\w ]+, 3, 1, \d+>"],
+    "bwd_filter:nchw_smallplane_bwd_filter_k3s2": [r"k_nchws_bwd_filter<[\w ]+, 3, 2, \d+>"],
+    "fwd:nchw_smallplane_k5s1": [r"k_nchws_fwd<[\w ]+, 5, 1, \d+, false>"],
+    "bwd_data:nchw_smallplane_k5s1_flip": [r"k_nchws_fwd<[\w ]+, 5, 1, \d+, true>"],
+    "bwd_filter:nchw_smallplane_bwd_filter_k5s1": [r"k_nchws_bwd_filter<[\w ]+, 5, 1, \d+>"],
     # whole backward pass in one kernel (dwconv_bwd)
     "bwd:nhwc_bwd_fused_k3s1": [r"k_nhwc_bwd_fused_k3s1<"],
     "bwd:nchw_bwd_fused_k3s1": [r"k_nchwd_bwd_fused_k3s1<"],
     "bwd:nchw_smallplane_bwd_fused_k3s1": [r"k_nchws_bwd_fused<"],
     # group convolution: k_gconv_nchw_s1<T, V, OB, R, FLIP>, k_gconv_nhwc_s1<T, CG, OB, PF, FLIP>
-    "fwd:group_nchw_rowwalk_k3s1": [r"k_gconv_nchw_s1<\w+, \d+, \d+, \d+, false>"],
-    "bwd_data:group_nchw_rowwalk_k3s1_flip": [r"k_gconv_nchw_s1<\w+, \d+, \d+, \d+, true>"],
+    "fwd:group_nchw_rowwalk_k3s1": [r"k_gconv_nchw_s1<[\w ]+, \d+, \d+, \d+, false>"],
+    "bwd_data:group_nchw_rowwalk_k3s1_flip": [r"k_gconv_nchw_s1<[\w ]+, \d+, \d+, \d+, true>"],
     "bwd_filter:group_nchw_bwd_filter_k3s1": [r"k_gconv_nchw_bwd_filter<"],
-    "fwd:group_nhwc_rowwalk_k3s1": [r"k_gconv_nhwc_s1<\w+, \d+, \d+, \d+, false>"],
-    "bwd_data:group_nhwc_rowwalk_k3s1_flip": [r"k_gconv_nhwc_s1<\w+, \d+, \d+, \d+, true>"],
+    "fwd:group_nhwc_rowwalk_k3s1": [r"k_gconv_nhwc_s1<[\w ]+, \d+, \d+, \d+, false>"],
+    "bwd_data:group_nhwc_rowwalk_k3s1_flip": [r"k_gconv_nhwc_s1<[\w ]+, \d+, \d+, \d+, true>"],
     "bwd_filter:group_nhwc_bwd_filter_k3s1": [r"k_gconv_nhwc_bwd_filter<"],
 }
 
