@@ -173,7 +173,10 @@ __global__ __launch_bounds__(256) void k_gconv_nchw_s1(GGeom g, const T *__restr
 }
 
 // Filter gradient, stage 1.  Block: (group, input channel b, chunk of OB output channels, part).
-template <typename T, int V, int OB, bool SHFL>
+// WSPLIT: the four wavefronts of a block take four different input channels b and the SAME 64 work items, so the
+// dy rows they all need are fetched once per block (the other three reads hit the L1) instead of once per input
+// channel from L2; each wavefront then owns its sums and writes its own partial.
+template <typename T, int V, int OB, bool SHFL, bool WSPLIT>
 __global__ __launch_bounds__(256) void k_gconv_nchw_bwd_filter(GGeom g, const T *__restrict__ x, const T *__restrict__ dy,
                                                                float *__restrict__ ws, int TH, int nstrips, int ncv,
                                                                int nitems, int parts, unsigned nblocks, int J)
@@ -181,9 +184,13 @@ __global__ __launch_bounds__(256) void k_gconv_nchw_bwd_filter(GGeom g, const T 
     __shared__ float red[4][9 * OB];
     unsigned lb = xcd_remap(blockIdx.x, nblocks);
     const int nchunks = g.Og / OB;
-    const int b = lb % g.Cg; lb /= g.Cg;
+    const int nbq = WSPLIT ? g.Cg / 4 : g.Cg;
+    const int bq = lb % nbq; lb /= nbq;
+    const int b = WSPLIT ? bq * 4 + (int)(threadIdx.x >> 6) : bq;
     const int chunk = lb % nchunks; lb /= nchunks;
     const int part = lb % parts; const int grp = lb / parts;
+    constexpr int LPB = WSPLIT ? 64 : 256;          // work items per block and iteration
+    const int lidx = WSPLIT ? (int)(threadIdx.x & 63) : (int)threadIdx.x;
 
     const int H = g.H, W = g.W, HW = H * W;
     float acc[OB][3][3];
@@ -194,7 +201,7 @@ __global__ __launch_bounds__(256) void k_gconv_nchw_bwd_filter(GGeom g, const T 
 #pragma unroll
             for (int kw = 0; kw < 3; ++kw) acc[a][kh][kw] = 0.f;
 
-    for (int item = part * 256 + threadIdx.x; item < nitems; item += parts * 256) {
+    for (int item = part * LPB + lidx; item < nitems; item += parts * LPB) {
         const int cv = item % ncv, t1 = item / ncv, strip = t1 % nstrips, n = t1 / nstrips;
         const int col0 = cv * V, oh0 = strip * TH, oh1 = min(H, oh0 + TH);
         const T *xp = x + ((size_t)n * g.C + (size_t)grp * g.Cg + b) * HW;
@@ -261,7 +268,14 @@ __global__ __launch_bounds__(256) void k_gconv_nchw_bwd_filter(GGeom g, const T 
                 if (lane == 0) red[wv][(a * 3 + kh) * 3 + kw] = s;
             }
     __syncthreads();
-    if (threadIdx.x < 9 * OB) {
+    if (WSPLIT) {
+        // every wavefront holds the finished sums of its own input channel
+        if (lane < 9 * OB) {
+            const int e = lane, a = e / 9, tap = e % 9;
+            const int o = grp * g.Og + chunk * OB + a;
+            ws[(size_t)part * J + ((size_t)o * g.Cg + b) * 9 + tap] = red[wv][e];
+        }
+    } else if (threadIdx.x < 9 * OB) {
         const int e = threadIdx.x, a = e / 9, tap = e % 9;
         const int o = grp * g.Og + chunk * OB + a;
         ws[(size_t)part * J + ((size_t)o * g.Cg + b) * 9 + tap] = (red[0][e] + red[1][e]) + (red[2][e] + red[3][e]);
@@ -358,18 +372,22 @@ hipError_t gconv_nchw_s1(const GGeom &g, int dtype, const void *in, const void *
 
 // Filter-gradient tiling: strip height, and partials per weight entry (each part = 256 lanes that stride
 // over the (image, strip, column-vector) items).
+static bool gconv_nchw_wsplit(const GGeom &g) { return g.Cg % 4 == 0 && gtune("DWCONV_TUNE_GWSPLIT", 1) != 0; }
+
 static void gconv_nchw_bwd_filter_tiling(const GGeom &g, int *TH, int *nstrips, int *nitems, int *parts)
 {
     const int OB = pick_ob(g.Og);
-    const long long per_part_row = (long long)g.G * g.Cg * (g.Og / OB);
+    const bool ws = gconv_nchw_wsplit(g);
+    const long long per_part_row = (long long)g.G * (ws ? g.Cg / 4 : g.Cg) * (g.Og / OB);
     const int th = gconv_pick_th(g, per_part_row, false);
     const int ns = (g.H + th - 1) / th;
     const long long ni = (long long)g.N * ns * (g.W / pick_v(g.W));
-    // about 2048 blocks in the launch, each lane with at least one item, at most 64 partials
-    long long p = (gtune("DWCONV_TUNE_GWBLOCKS", 2048) + per_part_row - 1) / per_part_row;
-    const long long maxp = (ni + 255) / 256;
+    // about 2048 blocks in the launch (1024 measured better for the wavefront-split kernel on groups of 4), each
+    // lane with at least one item, a bounded number of partials
+    long long p = (gtune("DWCONV_TUNE_GWBLOCKS", ws && g.Cg == 4 ? 1024 : 2048) + per_part_row - 1) / per_part_row;
+    const long long maxp = ws ? (ni + 63) / 64 : (ni + 255) / 256;
     if (p > maxp) p = maxp;
-    if (p > 64) p = 64;
+    if (p > (ws ? 128 : 64)) p = ws ? 128 : 64;
     if (p < 1) p = 1;
     *TH = th; *nstrips = ns; *nitems = (int)(ni < (1ll << 31) ? ni : 0); *parts = (int)p;
 }
@@ -389,24 +407,28 @@ hipError_t gconv_nchw_bwd_filter(const GGeom &g, int dtype, const void *x, const
     gconv_nchw_bwd_filter_tiling(g, &TH, &nstrips, &nitems, &p2);
     if (p2 != parts || nitems < 1) return hipErrorInvalidValue;
     const int OB = pick_ob(g.Og), V = pick_v(g.W);
-    const long long nb = (long long)g.G * parts * (g.Og / OB) * g.Cg;
+    const bool wsplit = gconv_nchw_wsplit(g);
+    const long long nb = (long long)g.G * parts * (g.Og / OB) * (wsplit ? g.Cg / 4 : g.Cg);
     if (nb >= (1ll << 31)) return hipErrorInvalidValue;
     const unsigned nblocks = (unsigned)nb;
     const int J = g.O * g.Cg * 9;
     // neighbour columns by wavefront shuffle: measured faster for groups of 8 and on 14-wide rows, slower on 28
     const bool shfl = gtune("DWCONV_TUNE_GWSHFL", (g.Cg >= 8 || g.W <= 14) ? 1 : 0) != 0;
+#define GOK(T, VV, OBB, SH, WS) hipLaunchKernelGGL((k_gconv_nchw_bwd_filter<T, VV, OBB, SH, WS>), dim3(nblocks), dim3(256), 0, st, \
+                                                   g, (const T *)x, (const T *)dy, ws, TH, nstrips, g.W / VV, nitems, parts, nblocks, J)
 #define GO3(T, VV, OBB)                                                                                                     \
     do {                                                                                                                    \
-        if (shfl) hipLaunchKernelGGL((k_gconv_nchw_bwd_filter<T, VV, OBB, true>), dim3(nblocks), dim3(256), 0, st, g,       \
-                                     (const T *)x, (const T *)dy, ws, TH, nstrips, g.W / VV, nitems, parts, nblocks, J);    \
-        else hipLaunchKernelGGL((k_gconv_nchw_bwd_filter<T, VV, OBB, false>), dim3(nblocks), dim3(256), 0, st, g,           \
-                                (const T *)x, (const T *)dy, ws, TH, nstrips, g.W / VV, nitems, parts, nblocks, J);         \
+        if (shfl && wsplit) GOK(T, VV, OBB, true, true);                                                                    \
+        else if (shfl) GOK(T, VV, OBB, true, false);                                                                        \
+        else if (wsplit) GOK(T, VV, OBB, false, true);                                                                      \
+        else GOK(T, VV, OBB, false, false);                                                                                 \
     } while (0)
 #define GO2(T, VV) do { if (OB == 4) GO3(T, VV, 4); else if (OB == 2) GO3(T, VV, 2); else GO3(T, VV, 1); } while (0)
     if (dtype == DT_F32) { if (V == 4) GO2(float, 4); else GO2(float, 2); }
     else                 { if (V == 4) GO2(bf16_t, 4); else GO2(bf16_t, 2); }
 #undef GO2
 #undef GO3
+#undef GOK
     return hipGetLastError();
 }
 
