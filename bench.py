@@ -37,6 +37,10 @@ def parse():
                          "which reads dy once: its algorithmic bytes are 2|x|+|y| instead of 2(|x|+|y|))")
     ap.add_argument("--side-stream", action="store_true",
                     help="enqueue each layer's filter gradient on a second stream, beside its input gradient")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph and replay it for the timed steps (the library only enqueues "
+                         "kernels on the stream it is given, so a step is capturable); removes the host's launch cost, "
+                         "which shows on the small-batch workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the per-launch HIP-event pass")
     ap.add_argument("--report", action="store_true", help="print a per-layer table to stderr")
@@ -315,17 +319,34 @@ def main():
         dst.copy_(src); dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    if args.graph and args.side_stream:
+        print("bench.py: --graph and --side-stream cannot be combined", file=sys.stderr)
+        sys.exit(2)
+    graph = None
+    if args.graph:
+        # the launches are bound to the stream that is current when they are built: build and capture on one stream
+        cap = torch.cuda.Stream()
+        torch.cuda.set_stream(cap)
     main_stream = torch.cuda.current_stream()
     side = torch.cuda.Stream() if args.side_stream else None
     ops = build_ops(dw, wl, cfg, torch, args.order, side, args.fused_bwd)
     step_bytes = sum(op["bytes"] * op["repeat"] for op in ops)
+    if args.graph:
+        run_step(ops, main_stream, side)           # one eager step first (loads the kernels)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=main_stream):
+            run_step(ops, main_stream, side)
+        step = graph.replay
+    else:
+        step = lambda: run_step(ops, main_stream, side)
 
     for _ in range(args.warmup):
-        run_step(ops, main_stream, side)
+        step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        run_step(ops, main_stream, side)
+        step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
@@ -339,7 +360,8 @@ def main():
         "config": {"workload": cfg["name"], "batch": cfg["N"],
                    "layouts": ["NCHW" if l == wl.NCHW else "NHWC" for l in cfg["layouts"]],
                    "layers": len(cfg["layers"]), "passes": "fwd+bwd(one call)" if args.fused_bwd else "fwd+bwd_data+bwd_filter",
-                   "step": "one fwd+bwd of the stack in every listed layout", "launch_order": args.order},
+                   "step": "one fwd+bwd of the stack in every listed layout", "launch_order": args.order,
+                   "launch": "hip graph replay" if args.graph else "eager"},
         "pct_of_peak_hbm": round(100.0 * gbs / PEAK_HBM_GBS, 2),
         "algorithmic_GB_per_step": round(step_bytes / 1e9, 4),
     }

@@ -227,3 +227,36 @@ def test_binding_rejects_wrong_tensors(gpu_lib):
     if dw.bwd_filter_workspace_bytes(d) > 16:
         with pytest.raises(dw.DwconvError):
             dw.bwd_filter(d, x, y, dwt, small)
+
+
+def test_hip_graph_replay_matches_eager(gpu_lib):
+    """The library only enqueues kernels on the stream it is given (no allocation, no copy, no synchronisation,
+    no memset), so a training step can be captured into a HIP graph.  The graph is replayed several times, with
+    eager work (re-poisoning the outputs) and synchronisations between the replays; every replay has to reproduce
+    the eager results bit for bit."""
+    cases = [(Layer("graph_s1", 32, 28, 28), 4), (Layer("graph_s2", 16, 28, 28, 3, 2, 1), 4), (Layer("graph_tail", 64, 7, 7), 8)]
+    for layout in LAYOUTS:
+        for layer, N in cases:
+            x, w, dy = wl.make_inputs(layer, N, layout, wl.F32, 21)
+            xt, wt, dyt = gu.to_dev(x, wl.F32), gu.to_dev(w, wl.F32), gu.to_dev(dy, wl.F32)
+            ref = gu.gpu_passes(layer, N, layout, wl.F32, xt, wt, dyt)
+            ref_b = gu.gpu_bwd(layer, N, layout, wl.F32, xt, wt, dyt)
+            d = gu.desc_for(layer, N, layout, wl.F32)
+            y = torch.empty_like(ref[0]); dx = torch.empty_like(ref[1]); dwt = torch.empty_like(ref[2])
+            dx2 = torch.empty_like(ref[1]); dw2 = torch.empty_like(ref[2])
+            wsb = torch.empty(max(dw.bwd_filter_workspace_bytes(d), 16), device="cuda", dtype=torch.uint8)
+            wsb2 = torch.empty(max(dw.bwd_workspace_bytes(d), 16), device="cuda", dtype=torch.uint8)
+            s = torch.cuda.Stream()
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=s):
+                dw.fwd(d, xt, wt, y, s); dw.bwd_filter(d, xt, dyt, dwt, wsb, s); dw.bwd_data(d, dyt, wt, dx, s)
+                dw.bwd(d, xt, dyt, wt, dx2, dw2, wsb2, s)
+            for rep in range(3):
+                for t in (y, dx, dwt, dx2, dw2):
+                    t.fill_(float("nan"))           # eager work between the replays
+                torch.cuda.synchronize()
+                g.replay()
+                torch.cuda.synchronize()
+                for got, want in ((y, ref[0]), (dx, ref[1]), (dwt, ref[2]), (dx2, ref_b[0]), (dw2, ref_b[1])):
+                    assert torch.equal(got, want), (layer.name, layout, rep)
