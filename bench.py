@@ -39,8 +39,8 @@ def parse():
                     help="enqueue each layer's filter gradient on a second stream, beside its input gradient")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step into a HIP graph and replay it for the timed steps (the library only enqueues "
-                         "kernels on the stream it is given, so a step is capturable); removes the host's launch cost, "
-                         "which shows on the small-batch workloads")
+                         "kernels on the stream it is given, so a step is capturable); takes the host's launch cost "
+                         "out of the timed region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the per-launch HIP-event pass")
     ap.add_argument("--report", action="store_true", help="print a per-layer table to stderr")
