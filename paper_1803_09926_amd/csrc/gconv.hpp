@@ -44,4 +44,12 @@ int gconv_nhwc_bwd_filter_parts(const GGeom &g);
 hipError_t gconv_nhwc_bwd_filter(const GGeom &g, int dtype, const void *x, const void *dy, float *ws, int parts,
                                  hipStream_t st);
 
+// ---- NHWC lane-exchange walk: 4 or 8 channels per group on both sides (gconv_nhwc_xchg.hip); gconv_nhwc_s1
+// forwards to it where it applies
+bool gconv_nhwc_xchg_supported(const GGeom &g);
+hipError_t gconv_nhwc_xchg_s1(const GGeom &g, int dtype, const void *in, const void *w, void *out, bool flip, hipStream_t st);
+// filter gradient, stage 1: the tiling comes from gconv_nhwc_bwd_filter (one channel per lane)
+hipError_t gconv_nhwc_xchg_bwd_filter(const GGeom &g, int dtype, const void *x, const void *dy, float *ws, int CT, int nctiles,
+                                      int nowtiles, int TH, int nstrips, int NI, unsigned nblocks, int J, hipStream_t st);
+
 }  // namespace dwc

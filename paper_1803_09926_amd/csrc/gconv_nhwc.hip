@@ -341,6 +341,7 @@ static hipError_t launch_gs1(const GGeom &g, const void *in, const void *w, void
 hipError_t gconv_nhwc_s1(const GGeom &g, int dtype, const void *in, const void *w, void *out, bool flip, hipStream_t st)
 {
     if (!gconv_nhwc_supported(g)) return hipErrorInvalidValue;
+    if (gconv_nhwc_xchg_supported(g)) return gconv_nhwc_xchg_s1(g, dtype, in, w, out, flip, st);
     const int CG = flip ? g.Og : g.Cg, CGW = flip ? g.Cg : g.Og;
     const int OB = nhwc_ob(CG, CGW);
     // two channels per group on both sides and an even number of groups: two groups per lane
@@ -359,7 +360,8 @@ hipError_t gconv_nhwc_s1(const GGeom &g, int dtype, const void *in, const void *
 static void gconv_nhwc_bwd_filter_tiling(const GGeom &g, int *OBp, int *CT, int *nctiles, int *nowtiles, int *TH,
                                          int *nstrips, int *NI, int *ngroups)
 {
-    const int OB = nhwc_ob(g.Cg, g.Og);
+    // the lane-exchange kernel takes one channel per lane
+    const int OB = gconv_nhwc_xchg_supported(g) && !getenv("DWCONV_TUNE_GNOXCHGW") ? 1 : nhwc_ob(g.Cg, g.Og);
     const int Q = g.O / OB;
     int ct = 1;
     while (ct < 64 && ct < Q) ct *= 2;
@@ -397,6 +399,8 @@ hipError_t gconv_nhwc_bwd_filter(const GGeom &g, int dtype, const void *x, const
     if (nb >= (1ll << 31)) return hipErrorInvalidValue;
     const unsigned nblocks = (unsigned)nb;
     const int J = g.O * g.Cg * 9;
+    if (gconv_nhwc_xchg_supported(g) && !getenv("DWCONV_TUNE_GNOXCHGW"))
+        return gconv_nhwc_xchg_bwd_filter(g, dtype, x, dy, ws, CT, nct, nowt, TH, nst, NI, nblocks, J, st);
 #define TRY(T, CGG, OBB) if (g.Cg == CGG && OB == OBB) { hipLaunchKernelGGL((k_gconv_nhwc_bwd_filter<T, CGG, OBB>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, (const T *)dy, ws, CT, nct, nowt, TH, nst, NI, nblocks, J); return hipGetLastError(); }
     if (dtype == DT_F32) {
         TRY(float, 2, 4); TRY(float, 2, 2); TRY(float, 4, 2); TRY(float, 4, 1); TRY(float, 8, 1);

@@ -55,13 +55,14 @@ VARIANT_KERNELS = {
     "bwd:nhwc_bwd_fused_k3s1": [r"k_nhwc_bwd_fused_k3s1<"],
     "bwd:nchw_bwd_fused_k3s1": [r"k_nchwd_bwd_fused_k3s1<"],
     "bwd:nchw_smallplane_bwd_fused_k3s1": [r"k_nchws_bwd_fused<"],
-    # group convolution: k_gconv_nchw_s1<T, V, OB, R, FLIP>, k_gconv_nhwc_s1<T, CG, OB, PF, FLIP>
-    "fwd:group_nchw_rowwalk_k3s1": [r"k_gconv_nchw_s1<[\w ]+, \d+, \d+, \d+, false>"],
-    "bwd_data:group_nchw_rowwalk_k3s1_flip": [r"k_gconv_nchw_s1<[\w ]+, \d+, \d+, \d+, true>"],
+    # group convolution: k_gconv_nchw_s1<T, V, OB, R, FLIP, SHFL>, k_gconv_nhwc_s1<T, CG, OB, GPL, PF, FLIP>
+    "fwd:group_nchw_rowwalk_k3s1": [r"k_gconv_nchw_s1<[\w ]+, \d+, \d+, \d+, false[,>]"],
+    "bwd_data:group_nchw_rowwalk_k3s1_flip": [r"k_gconv_nchw_s1<[\w ]+, \d+, \d+, \d+, true[,>]"],
     "bwd_filter:group_nchw_bwd_filter_k3s1": [r"k_gconv_nchw_bwd_filter<"],
-    "fwd:group_nhwc_rowwalk_k3s1": [r"k_gconv_nhwc_s1<[\w ]+, \d+, \d+, \d+, false>"],
-    "bwd_data:group_nhwc_rowwalk_k3s1_flip": [r"k_gconv_nhwc_s1<[\w ]+, \d+, \d+, \d+, true>"],
-    "bwd_filter:group_nhwc_bwd_filter_k3s1": [r"k_gconv_nhwc_bwd_filter<"],
+    # k_gconv_nhwc_xchg<T, CG, V, PF, FLIP>: the lane-exchange walk (groups of 4 or 8 channels)
+    "fwd:group_nhwc_rowwalk_k3s1": [r"k_gconv_nhwc_s1<[\w ]+, \d+, \d+, \d+, \d+, false>", r"k_gconv_nhwc_xchg<[\w ]+, \d+, \d+, \d+, false>"],
+    "bwd_data:group_nhwc_rowwalk_k3s1_flip": [r"k_gconv_nhwc_s1<[\w ]+, \d+, \d+, \d+, \d+, true>", r"k_gconv_nhwc_xchg<[\w ]+, \d+, \d+, \d+, true>"],
+    "bwd_filter:group_nhwc_bwd_filter_k3s1": [r"k_gconv_nhwc_bwd_filter<", r"k_gconv_nhwc_xchg_bwd_filter<"],
 }
 
 
