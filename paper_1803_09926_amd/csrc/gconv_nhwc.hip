@@ -83,7 +83,8 @@ __global__ __launch_bounds__(256) void k_gconv_nhwc_s1(GGeom g, const T *__restr
                         // group grp+gi from dy channel b of that group, taps reversed
                         const int idx = FLIP ? wat_nhwc(g, 2 - kh, 2 - kw, sub + a, (grp + gi) * g.Og + b)
                                              : wat_nhwc(g, kh, kw, b, o0 + gi * OB + a);
-                        wr[kh][kw][gi][b][a] = ok ? ldf(w + idx) : 0.f;
+                        const float wv = ldf(w + idx);     // unconditional: a select, not a branch per entry
+                        wr[kh][kw][gi][b][a] = ok ? wv : 0.f;
                     }
     }
 
@@ -311,7 +312,7 @@ bool gconv_nhwc_supported(const GGeom &g)
 
 static int nhwc_pick_th(int rows)
 {
-    const int target = 14;
+    const int target = 28;
     int ns = (rows + target / 2) / target;
     if (ns < 1) ns = 1;
     return cdiv(rows, ns);
@@ -323,7 +324,8 @@ static hipError_t launch_gs1(const GGeom &g, const void *in, const void *w, void
     const int COT = flip ? g.C : g.O;
     const int lanes = g.W * (COT / (OB * GPL));
     const int bs = 256;
-    const int TH = nhwc_pick_th(g.H);
+    const char *eth = getenv("DWCONV_TUNE_GHTH");
+    const int TH = eth && atoi(eth) > 0 ? atoi(eth) : nhwc_pick_th(g.H);
     const int nchunks = cdiv(lanes, bs), nstrips = cdiv(g.H, TH);
     const long long nb = (long long)g.N * nchunks * nstrips;
     if (nb >= (1ll << 31)) return hipErrorInvalidValue;
@@ -373,6 +375,8 @@ static void gconv_nhwc_bwd_filter_tiling(const GGeom &g, int *OBp, int *CT, int 
     while (th > 7 && per_strip * cdiv(g.H, th) < 384) th = (th + 1) / 2;
     int ni = 1;
     while (ni < g.N && per_strip * cdiv(g.H, th) / (ni * 2) >= 384) ni *= 2;
+    if (const char *e = getenv("DWCONV_TUNE_GHWTH")) if (atoi(e) > 0) th = atoi(e);
+    if (const char *e = getenv("DWCONV_TUNE_GHWNI")) if (atoi(e) > 0) ni = atoi(e);
     const long long J = (long long)g.O * g.Cg * 9;
     while ((long long)nowt * cdiv(g.H, th) * cdiv(g.N, ni) * J * 4 > (64ll << 20)) {
         if (ni < g.N) ni *= 2; else if (th < g.H) th *= 2; else break;

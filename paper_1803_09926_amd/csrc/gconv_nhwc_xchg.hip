@@ -112,7 +112,8 @@ __global__ __launch_bounds__(256) void k_gconv_nhwc_xchg(GGeom g, const T *__res
                             const int rd = (sub ^ j) * V + t, wrt = sub * V + a;   // positions in the group: read, written
                             const int idx = FLIP ? wat_nhwc_x(g, 2 - kh, 2 - kw, wrt, grp * CG + rd)
                                                  : wat_nhwc_x(g, kh, kw, rd, grp * CG + wrt);
-                            wr[kw][t][a][h][q][kh] = ok ? ldf(w + idx) : 0.f;
+                            const float wv = ldf(w + idx);     // unconditional: a select, not a branch per entry
+                            wr[kw][t][a][h][q][kh] = ok ? wv : 0.f;
                         }
     }
 
