@@ -84,6 +84,48 @@ def test_group_conv_matches_oracle(case, layout, dtype):
     gu.assert_close(gu.to_host(dwt), og.bwd_filter(x, dy, **kw), gu.TOL_F32_FILTER, "gconv bwd_filter " + tag)
 
 
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+def test_group_nhwc_exchange_kernels_forced_tilings(monkeypatch, dtype):
+    """The lane-exchange NHWC kernels pick several images per block and whole-column strips only on large
+    tensors; the tiling overrides force those paths (ragged last image group, ragged last strip, shallow and deep
+    prefetch, two channels per lane) at sizes the oracle checks element by element."""
+    cases = [("x_cg4", 5, 24, 24, 6, 13, 10, 3, 1, 1), ("x_cg8", 7, 16, 16, 2, 11, 9, 3, 1, 1)]
+    knobs = [
+        {"DWCONV_TUNE_GXNI": "3", "DWCONV_TUNE_GXTH": "5", "DWCONV_TUNE_GHWNI": "3", "DWCONV_TUNE_GHWTH": "5"},
+        {"DWCONV_TUNE_GXNI": "2", "DWCONV_TUNE_GXPF": "2", "DWCONV_TUNE_GHWNI": "4"},
+        {"DWCONV_TUNE_GXNI": "8", "DWCONV_TUNE_GXTH": "4", "DWCONV_TUNE_GHWTH": "3", "DWCONV_TUNE_GHWNI": "1"},
+    ]
+    for case in cases:
+        name, N, C, O, G, H, W, K, s, p = case
+        x, w, dy = wl.make_group_inputs(N, C, O, G, H, W, K, s, p, wl.NHWC, dtype, seed=99)
+        kw = dict(K=K, stride=s, pad=p, groups=G, O=O, layout=wl.NHWC, nthreads=8)
+        want = (og.fwd(x, w, **kw), og.bwd_data(dy, w, x_shape=x.shape, **kw), og.bwd_filter(x, dy, **kw))
+        tol = gu.TOL_F32 if dtype == wl.F32 else gu.TOL_BF16
+        for kn in knobs:
+            if name == "x_cg8" and kn.get("DWCONV_TUNE_GXV") == "2":
+                continue
+            with monkeypatch.context() as m:
+                for k, v in kn.items():
+                    m.setenv(k, v)
+                print("case", name, "knobs", kn, flush=True)
+                y, dx, dwt = run_gpu(case, wl.NHWC, dtype, x, w, dy)
+            tag = "%s %s dtype=%d" % (name, kn, dtype)
+            gu.assert_close(gu.to_host(y), want[0], tol, "gconv fwd " + tag)
+            gu.assert_close(gu.to_host(dx), want[1], tol, "gconv bwd_data " + tag)
+            gu.assert_close(gu.to_host(dwt), want[2], gu.TOL_F32_FILTER, "gconv bwd_filter " + tag)
+    # two channels per lane (groups of 4 over two lanes)
+    case = cases[0]
+    name, N, C, O, G, H, W, K, s, p = case
+    x, w, dy = wl.make_group_inputs(N, C, O, G, H, W, K, s, p, wl.NHWC, dtype, seed=98)
+    kw = dict(K=K, stride=s, pad=p, groups=G, O=O, layout=wl.NHWC, nthreads=8)
+    with monkeypatch.context() as m:
+        m.setenv("DWCONV_TUNE_GXV", "2")
+        y, dx, dwt = run_gpu(case, wl.NHWC, dtype, x, w, dy)
+    tol = gu.TOL_F32 if dtype == wl.F32 else gu.TOL_BF16
+    gu.assert_close(gu.to_host(y), og.fwd(x, w, **kw), tol, "gconv fwd two channels per lane")
+    gu.assert_close(gu.to_host(dx), og.bwd_data(dy, w, x_shape=x.shape, **kw), tol, "gconv bwd_data two channels per lane")
+
+
 def test_group_bwd_filter_is_deterministic():
     case = ("det", 4, 32, 32, 8, 28, 28, 3, 1, 1)
     for layout in LAYOUTS:
