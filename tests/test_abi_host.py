@@ -238,3 +238,37 @@ def test_group_benchmark_layers_get_tuned_variants():
             for which in range(3):
                 name = dw.gconv_variant_name(d, which)
                 assert name.startswith("group_") and name != "group_generic", (layer.name, layout, which, name)
+
+
+def test_dpp_operands_are_not_written_just_before_they_are_read(tmp_path):
+    """The lane-exchange group kernels write their DPP multiply-adds as inline assembly, where the compiler does
+    not insert the wait states the hardware needs between a vector-ALU write of a register and a DPP read of it
+    (two instructions).  Check the generated ISA: no DPP source register is the destination of one of the two
+    preceding vector-ALU instructions."""
+    import re
+    import shutil
+    import subprocess
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    if not os.path.exists(hipcc):
+        pytest.skip("hipcc not available")
+    src = os.path.join(ROOT, "paper_1803_09926_amd", "csrc", "gconv_nhwc_xchg.hip")
+    out = str(tmp_path / "xchg.s")
+    subprocess.run([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=fast", "-Xclang", "-target-feature",
+                    "-Xclang", "-packed-fp32-ops", "-S", "--cuda-device-only", "-o", out, src],
+                   check=True, capture_output=True, timeout=600)
+    # instruction lines only (inline-assembly lines are not indented like the compiler's own)
+    lines = [l.strip() for l in open(out)]
+    lines = [l for l in lines if re.match(r"[a-z]+_[a-z0-9_]+( |$)", l)]
+    ndpp = 0
+    for i, l in enumerate(lines):
+        m = re.match(r"v_\w+_dpp (v\d+), (v\d+)", l)
+        if not m:
+            continue
+        ndpp += 1
+        for k in (1, 2):
+            p = lines[i - k]
+            if p.startswith("s_nop"):
+                break
+            w = re.match(r"v_\w+ (v\d+)", p)
+            assert not (w and w.group(1) == m.group(2)), "DPP read of %s right after its write: %r then %r" % (m.group(2), p, l)
+    assert ndpp > 1000      # the kernels do use the DPP form
