@@ -28,7 +28,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2,
-                    help="workload index 0..6 (default 2: the headline one; 5: MobileNet variant shapes; 6: group convolutions)")
+                    help="workload index 0..7 (default 2: the headline one; 5: MobileNet variant shapes; 6: group convolutions; "
+                         "7: group convolutions in bf16)")
     ap.add_argument("--order", choices=["layer", "train"], default="layer",
                     help="launch order inside a step: layer by layer (fwd, bwd_filter, bwd_data of each), or as "
                          "a training step runs them (all forwards, then the backward passes from the last layer up)")

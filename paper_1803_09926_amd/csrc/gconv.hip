@@ -201,7 +201,7 @@ hipError_t gconv_generic_bwd_filter(const GGeom &g, int layout, int dtype, const
 
 // ---- variant selection -------------------------------------------------------------------------------
 
-static GPlan gplan(const GGeom &g, int layout, int pass)
+static GPlan gplan(const GGeom &g, int layout, int dtype, int pass)
 {
     GPlan pl = {GV_GENERIC, pass == 2 ? gconv_generic_bwd_filter_parts(g) : 0, 0, 0, 0, "group_generic"};
     if (getenv("DWCONV_TUNE_GROUP_GENERIC")) return pl;
@@ -212,7 +212,7 @@ static GPlan gplan(const GGeom &g, int layout, int pass)
     } else if (layout == LAYOUT_NHWC && gconv_nhwc_supported(g)) {
         pl.variant = GV_NHWC_K3S1;
         pl.name = pass == 0 ? "group_nhwc_rowwalk_k3s1" : pass == 1 ? "group_nhwc_rowwalk_k3s1_flip" : "group_nhwc_bwd_filter_k3s1";
-        if (pass == 2) pl.parts = gconv_nhwc_bwd_filter_parts(g);
+        if (pass == 2) pl.parts = gconv_nhwc_bwd_filter_parts(g, dtype);
     }
     return pl;
 }
@@ -277,7 +277,7 @@ size_t gconv_bwd_filter_workspace_bytes(const dwconv_group_desc *desc)
         const dwconv_desc q = as_depthwise(desc);
         return dwconv_bwd_filter_workspace_bytes(&q);
     }
-    const GPlan pl = gplan(g, desc->layout, 2);
+    const GPlan pl = gplan(g, desc->layout, desc->dtype, 2);
     return (size_t)pl.parts * (size_t)g.O * g.Cg * g.K * g.K * sizeof(float);
 }
 
@@ -292,7 +292,7 @@ int gconv_fwd(const dwconv_group_desc *desc, const void *x, const void *w, void 
     }
     if (!x || !w || !y) return DWCONV_ERR_NULL;
     if (gmisaligned(x) || gmisaligned(w) || gmisaligned(y)) return DWCONV_ERR_ALIGN;
-    const GPlan pl = gplan(g, desc->layout, 0);
+    const GPlan pl = gplan(g, desc->layout, desc->dtype, 0);
     hipError_t e;
     if (pl.variant == GV_NCHW_K3S1) e = gconv_nchw_s1(g, desc->dtype, x, w, y, false, (hipStream_t)stream);
     else if (pl.variant == GV_NHWC_K3S1) e = gconv_nhwc_s1(g, desc->dtype, x, w, y, false, (hipStream_t)stream);
@@ -311,7 +311,7 @@ int gconv_bwd_data(const dwconv_group_desc *desc, const void *dy, const void *w,
     }
     if (!dy || !w || !dx) return DWCONV_ERR_NULL;
     if (gmisaligned(dy) || gmisaligned(w) || gmisaligned(dx)) return DWCONV_ERR_ALIGN;
-    const GPlan pl = gplan(g, desc->layout, 1);
+    const GPlan pl = gplan(g, desc->layout, desc->dtype, 1);
     hipError_t e;
     if (pl.variant == GV_NCHW_K3S1) e = gconv_nchw_s1(g, desc->dtype, dy, w, dx, true, (hipStream_t)stream);
     else if (pl.variant == GV_NHWC_K3S1) e = gconv_nhwc_s1(g, desc->dtype, dy, w, dx, true, (hipStream_t)stream);
@@ -331,7 +331,7 @@ int gconv_bwd_filter(const dwconv_group_desc *desc, const void *x, const void *d
     }
     if (!x || !dy || !dw) return DWCONV_ERR_NULL;
     if (gmisaligned(x) || gmisaligned(dy) || gmisaligned(dw)) return DWCONV_ERR_ALIGN;
-    const GPlan pl = gplan(g, desc->layout, 2);
+    const GPlan pl = gplan(g, desc->layout, desc->dtype, 2);
     const int J = g.O * g.Cg * g.K * g.K;
     const size_t need = (size_t)pl.parts * (size_t)J * sizeof(float);
     if (!workspace || workspace_bytes < need) return DWCONV_ERR_WORKSPACE;
@@ -353,7 +353,7 @@ const char *gconv_variant_name(const dwconv_group_desc *desc, int pass)
         const dwconv_desc q = as_depthwise(desc);
         return dwconv_variant_name(&q, pass);
     }
-    return gplan(g, desc->layout, pass).name;
+    return gplan(g, desc->layout, desc->dtype, pass).name;
 }
 
 }  // extern "C"

@@ -40,7 +40,7 @@ hipError_t gconv_nchw_bwd_filter(const GGeom &g, int dtype, const void *x, const
 // ---- NHWC row-walk kernels, same shapes (gconv_nhwc.hip) ----------------------------------------------
 bool gconv_nhwc_supported(const GGeom &g);
 hipError_t gconv_nhwc_s1(const GGeom &g, int dtype, const void *in, const void *w, void *out, bool flip, hipStream_t st);
-int gconv_nhwc_bwd_filter_parts(const GGeom &g);
+int gconv_nhwc_bwd_filter_parts(const GGeom &g, int dtype);
 hipError_t gconv_nhwc_bwd_filter(const GGeom &g, int dtype, const void *x, const void *dy, float *ws, int parts,
                                  hipStream_t st);
 

@@ -358,12 +358,20 @@ hipError_t gconv_nhwc_s1(const GGeom &g, int dtype, const void *in, const void *
     return hipErrorInvalidValue;
 }
 
+// Which filter-gradient kernel: the lane-exchange one where it applies, except for bf16 groups of 4, where its
+// 2-byte loads per lane measured slower than the 8-byte ones of the first form (groups of 8: the other way round).
+static bool nhwc_bwd_filter_xchg(const GGeom &g, int dtype)
+{
+    if (!gconv_nhwc_xchg_supported(g) || getenv("DWCONV_TUNE_GNOXCHGW")) return false;
+    return !(dtype == DT_BF16 && g.Cg == 4) || getenv("DWCONV_TUNE_GXCHGW");
+}
+
 // Filter-gradient tiling.  CT: lanes over sub-vectors (a power of two up to 64), 256/CT columns per block.
-static void gconv_nhwc_bwd_filter_tiling(const GGeom &g, int *OBp, int *CT, int *nctiles, int *nowtiles, int *TH,
+static void gconv_nhwc_bwd_filter_tiling(const GGeom &g, int dtype, int *OBp, int *CT, int *nctiles, int *nowtiles, int *TH,
                                          int *nstrips, int *NI, int *ngroups)
 {
     // the lane-exchange kernel takes one channel per lane
-    const int OB = gconv_nhwc_xchg_supported(g) && !getenv("DWCONV_TUNE_GNOXCHGW") ? 1 : nhwc_ob(g.Cg, g.Og);
+    const int OB = nhwc_bwd_filter_xchg(g, dtype) ? 1 : nhwc_ob(g.Cg, g.Og);
     const int Q = g.O / OB;
     int ct = 1;
     while (ct < 64 && ct < Q) ct *= 2;
@@ -385,10 +393,10 @@ static void gconv_nhwc_bwd_filter_tiling(const GGeom &g, int *OBp, int *CT, int 
     *ngroups = cdiv(g.N, ni);
 }
 
-int gconv_nhwc_bwd_filter_parts(const GGeom &g)
+int gconv_nhwc_bwd_filter_parts(const GGeom &g, int dtype)
 {
     int OB, CT, nct, nowt, TH, nst, NI, ngr;
-    gconv_nhwc_bwd_filter_tiling(g, &OB, &CT, &nct, &nowt, &TH, &nst, &NI, &ngr);
+    gconv_nhwc_bwd_filter_tiling(g, dtype, &OB, &CT, &nct, &nowt, &TH, &nst, &NI, &ngr);
     return nowt * nst * ngr;
 }
 
@@ -397,13 +405,13 @@ hipError_t gconv_nhwc_bwd_filter(const GGeom &g, int dtype, const void *x, const
 {
     if (!gconv_nhwc_supported(g)) return hipErrorInvalidValue;
     int OB, CT, nct, nowt, TH, nst, NI, ngr;
-    gconv_nhwc_bwd_filter_tiling(g, &OB, &CT, &nct, &nowt, &TH, &nst, &NI, &ngr);
+    gconv_nhwc_bwd_filter_tiling(g, dtype, &OB, &CT, &nct, &nowt, &TH, &nst, &NI, &ngr);
     if (parts != nowt * nst * ngr) return hipErrorInvalidValue;
     const long long nb = (long long)nct * nowt * nst * ngr;
     if (nb >= (1ll << 31)) return hipErrorInvalidValue;
     const unsigned nblocks = (unsigned)nb;
     const int J = g.O * g.Cg * 9;
-    if (gconv_nhwc_xchg_supported(g) && !getenv("DWCONV_TUNE_GNOXCHGW"))
+    if (nhwc_bwd_filter_xchg(g, dtype))
         return gconv_nhwc_xchg_bwd_filter(g, dtype, x, dy, ws, CT, nct, nowt, TH, nst, NI, nblocks, J, st);
 #define TRY(T, CGG, OBB) if (g.Cg == CGG && OB == OBB) { hipLaunchKernelGGL((k_gconv_nhwc_bwd_filter<T, CGG, OBB>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, (const T *)dy, ws, CT, nct, nowt, TH, nst, NI, nblocks, J); return hipGetLastError(); }
     if (dtype == DT_F32) {

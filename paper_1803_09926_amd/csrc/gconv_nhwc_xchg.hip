@@ -388,9 +388,9 @@ static hipError_t launch_x(const GGeom &g, const void *in, const void *w, void *
 hipError_t gconv_nhwc_xchg_s1(const GGeom &g, int dtype, const void *in, const void *w, void *out, bool flip, hipStream_t st)
 {
     if (!gconv_nhwc_xchg_supported(g)) return hipErrorInvalidValue;
-    // one channel per lane (9*CG filter registers): measured faster than two for groups of 4, and two channels of
-    // a group of 8 would need 144 filter registers
-    const int V = xtune("DWCONV_TUNE_GXV", 1);
+    // one channel per lane (9*CG filter registers): measured faster than two for fp32 groups of 4, and two channels
+    // of a group of 8 would need 144 filter registers; bf16 groups of 4 take two (4-byte loads instead of 2-byte ones)
+    const int V = g.Cg == 8 ? 1 : xtune("DWCONV_TUNE_GXV", dtype == DT_BF16 ? 2 : 1);
     const int PF = xtune("DWCONV_TUNE_GXPF", 5);     // rows in flight: 4-byte loads need many
 #define TRY(T, CGG, VV, PPF) if (g.Cg == CGG && V == VV && PF == PPF) return launch_x<T, CGG, VV, PPF>(g, in, w, out, flip, st)
     if (dtype == DT_F32) {

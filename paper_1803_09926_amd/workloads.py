@@ -127,7 +127,7 @@ def config(index: int) -> Dict:
     """The benchmark configurations, as dicts: N, layouts, dtype, layers [(Layer, repeat)].
     0..4: the five configurations of the benchmark spec; 5: the MobileNet variant shapes (width 0.75, width 0.5 at
     resolution 128), as a second workload; 6: group convolutions with 2, 4 and 8 channels per group on
-    MobileNet-sized planes."""
+    MobileNet-sized planes; 7: the same in bf16 storage at batch 256."""
     if index == 0:
         return dict(name="single_3x3_n8_c32_h112_f32_nchw", N=8, layouts=(NCHW,), dtype=F32,
                     layers=[(Layer("single_c32_h112", 32, 112, 112), 1)])
@@ -150,7 +150,10 @@ def config(index: int) -> Dict:
     if index == 6:
         return dict(name="group_conv_b128_f32", N=128, layouts=(NCHW, NHWC), dtype=F32,
                     layers=[(l, 1) for l in GROUP_LAYERS])
-    raise ValueError("config index must be 0..6")
+    if index == 7:
+        return dict(name="group_conv_b256_bf16", N=256, layouts=(NCHW, NHWC), dtype=BF16,
+                    layers=[(l, 1) for l in GROUP_LAYERS])
+    raise ValueError("config index must be 0..7")
 
 
 def round_to_bf16(a: np.ndarray) -> np.ndarray:

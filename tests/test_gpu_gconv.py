@@ -135,17 +135,19 @@ def test_group_bwd_filter_is_deterministic():
         assert torch.equal(a, b)
 
 
-def test_group_benchmark_workload_full_size_sampled():
-    """The group-convolution benchmark workload at its full size, in the launch configuration bench.py times;
+@pytest.mark.parametrize("ci", [6, 7], ids=["f32_b128", "bf16_b256"])
+def test_group_benchmark_workload_full_size_sampled(ci):
+    """The group-convolution benchmark workloads at their full size, in the launch configuration bench.py times;
     oracle on sampled images (fwd, bwd_data: images are independent) and on sampled groups over the whole batch
     (bwd_filter: groups are independent)."""
-    cfg = wl.config(6)
+    cfg = wl.config(ci)
     N = cfg["N"]
+    tol = gu.TOL_F32 if cfg["dtype"] == wl.F32 else gu.TOL_BF16
     for li, (layer, _) in enumerate(cfg["layers"]):
         for layout in cfg["layouts"]:
             print("group workload", layer.name, "layout", layout, flush=True)
             C, G, Cg = layer.C, layer.groups, layer.cg
-            x, w, dy = wl.make_inputs_device(layer, N, layout, cfg["dtype"], seed=6000 + li)
+            x, w, dy = wl.make_inputs_device(layer, N, layout, cfg["dtype"], seed=1000 * ci + li)
             d = dw.group_desc(N, C, layer.H, layer.W, 3, 1, 1, G, C, layout, cfg["dtype"])
             y = torch.full_like(dy, float("nan")); dx = torch.full_like(x, float("nan"))
             dwt = torch.full(w.shape, float("nan"), device="cuda", dtype=torch.float32)
@@ -157,8 +159,8 @@ def test_group_benchmark_workload_full_size_sampled():
             wh = gu.to_host(w)
             imgs = sorted({0, N // 2 - 1, N - 1})
             xh, dyh = gu.to_host(x[imgs]), gu.to_host(dy[imgs])
-            gu.assert_close(gu.to_host(y[imgs]), og.fwd(xh, wh, **kw), gu.TOL_F32, "gconv fwd " + tag)
-            gu.assert_close(gu.to_host(dx[imgs]), og.bwd_data(dyh, wh, x_shape=xh.shape, **kw), gu.TOL_F32, "gconv bwd_data " + tag)
+            gu.assert_close(gu.to_host(y[imgs]), og.fwd(xh, wh, **kw), tol, "gconv fwd " + tag)
+            gu.assert_close(gu.to_host(dx[imgs]), og.bwd_data(dyh, wh, x_shape=xh.shape, **kw), tol, "gconv bwd_data " + tag)
             kw1 = dict(K=3, stride=1, pad=1, groups=1, O=Cg, layout=layout, nthreads=8)
             for gi in sorted({0, G // 2 + 1 if G > 2 else 0, G - 1}):
                 sl = slice(gi * Cg, (gi + 1) * Cg)
