@@ -13,6 +13,37 @@ namespace dwc {
 template <typename T> struct ElemsS { static constexpr int VE = 16 / sizeof(T); };
 
 // Flat range [g0, g1) of `src` -> lds[e - a0], a0 = g0 rounded down to a 16-byte boundary.
+// Everything that can be decided for the whole block is: batches past the range are skipped by a uniform
+// branch, lanes past the range in the last batch re-load its last vector (and do not commit it), and the
+// element-wise path exists only for a range whose last vector sticks out of the tensor.  Per-lane branches
+// around every vector cost these kernels a tenth of their time.
+template <typename T, int VE>
+__device__ __forceinline__ void flat_load_vec(const T *__restrict__ src, int total, int a0, int nvec, int idx, bool whole,
+                                              float (&v)[VE])
+{
+    const int a = a0 + min(idx, nvec - 1) * VE;
+    if (whole) { Vec<T, VE>::load(src + a, v); return; }        // uniform branch: the usual case has no lane mask at all
+    if (a + VE <= total) Vec<T, VE>::load(src + a, v);
+    else {
+#pragma unroll
+        for (int j = 0; j < VE; ++j) { const float t = ldf(src + min(a + j, total - 1)); v[j] = (a + j < total) ? t : 0.f; }
+    }
+}
+template <int VE>
+__device__ __forceinline__ void flat_commit_vec(float *lds, int nvec, int first, const float (&v)[VE])
+{
+    const int idx = first + (int)threadIdx.x;
+    if (first + 256 <= nvec) {                          // uniform: whole batches commit without a lane mask
+#pragma unroll
+        for (int j = 0; j < VE; j += 4)
+            *reinterpret_cast<float4 *>(lds + idx * VE + j) = make_float4(v[j], v[j + 1], v[j + 2], v[j + 3]);
+    } else if (idx < nvec) {
+#pragma unroll
+        for (int j = 0; j < VE; j += 4)
+            *reinterpret_cast<float4 *>(lds + idx * VE + j) = make_float4(v[j], v[j + 1], v[j + 2], v[j + 3]);
+    }
+}
+
 template <typename T>
 __device__ __forceinline__ void flat_load(const T *__restrict__ src, int total, int g0, int g1, float *lds)
 {
@@ -20,28 +51,18 @@ __device__ __forceinline__ void flat_load(const T *__restrict__ src, int total, 
     constexpr int BATCH = 16 / VE * 2;
     const int a0 = g0 & ~(VE - 1);
     const int nvec = (g1 - a0 + VE - 1) / VE;
+    const bool whole = a0 + nvec * VE <= total;         // uniform
     for (int base = 0; base < nvec; base += BATCH * 256) {
         float v[BATCH][VE];
 #pragma unroll
         for (int it = 0; it < BATCH; ++it) {
-            const int idx = base + it * 256 + (int)threadIdx.x;
-            if (idx < nvec) {
-                const int a = a0 + idx * VE;
-                if (a + VE <= total) Vec<T, VE>::load(src + a, v[it]);
-                else {
-#pragma unroll
-                    for (int j = 0; j < VE; ++j) v[it][j] = (a + j < total) ? ldf(src + a + j) : 0.f;
-                }
-            }
+            if (base + it * 256 >= nvec) break;          // uniform over the block
+            flat_load_vec<T, VE>(src, total, a0, nvec, base + it * 256 + (int)threadIdx.x, whole, v[it]);
         }
 #pragma unroll
         for (int it = 0; it < BATCH; ++it) {
-            const int idx = base + it * 256 + (int)threadIdx.x;
-            if (idx < nvec) {
-#pragma unroll
-                for (int j = 0; j < VE; j += 4)
-                    *reinterpret_cast<float4 *>(lds + idx * VE + j) = make_float4(v[it][j], v[it][j + 1], v[it][j + 2], v[it][j + 3]);
-            }
+            if (base + it * 256 >= nvec) break;
+            flat_commit_vec<VE>(lds, nvec, base + it * 256, v[it]);
         }
     }
 }
@@ -55,17 +76,11 @@ __device__ __forceinline__ void flat_issue(const T *__restrict__ src, int total,
     constexpr int VE = ElemsS<T>::VE;
     const int a0 = g0 & ~(VE - 1);
     const int nvec = (g1 - a0 + VE - 1) / VE;
+    const bool whole = a0 + nvec * VE <= total;
 #pragma unroll
     for (int it = 0; it < FlatRegs<T>::BATCH; ++it) {
-        const int idx = it * 256 + (int)threadIdx.x;
-        if (idx < nvec) {
-            const int a = a0 + idx * VE;
-            if (a + VE <= total) Vec<T, VE>::load(src + a, r.v[it]);
-            else {
-#pragma unroll
-                for (int j = 0; j < VE; ++j) r.v[it][j] = (a + j < total) ? ldf(src + a + j) : 0.f;
-            }
-        }
+        if (it * 256 >= nvec) break;                     // uniform over the block
+        flat_load_vec<T, VE>(src, total, a0, nvec, it * 256 + (int)threadIdx.x, whole, r.v[it]);
     }
 }
 template <typename T>
@@ -76,12 +91,8 @@ __device__ __forceinline__ void flat_commit(int g0, int g1, const FlatRegs<T> &r
     const int nvec = (g1 - a0 + VE - 1) / VE;
 #pragma unroll
     for (int it = 0; it < FlatRegs<T>::BATCH; ++it) {
-        const int idx = it * 256 + (int)threadIdx.x;
-        if (idx < nvec) {
-#pragma unroll
-            for (int j = 0; j < VE; j += 4)
-                *reinterpret_cast<float4 *>(lds + idx * VE + j) = make_float4(r.v[it][j], r.v[it][j + 1], r.v[it][j + 2], r.v[it][j + 3]);
-        }
+        if (it * 256 >= nvec) break;                     // uniform over the block
+        flat_commit_vec<ElemsS<T>::VE>(lds, nvec, it * 256, r.v[it]);
     }
 }
 
@@ -92,7 +103,8 @@ __device__ __forceinline__ void flat_store(T *__restrict__ dst, int g0, int g1, 
     constexpr int VE = ElemsS<T>::VE;
     const int a0 = g0 & ~(VE - 1);
     const int nvec = (g1 - a0 + VE - 1) / VE;
-    for (int idx = threadIdx.x; idx < nvec; idx += 256) {
+    const bool aligned = ((g0 | g1) & (VE - 1)) == 0;   // uniform: no partial vector at either end
+    auto one = [&](int idx, bool plain) {
         const int a = a0 + idx * VE;
         float v[VE];
 #pragma unroll
@@ -100,12 +112,17 @@ __device__ __forceinline__ void flat_store(T *__restrict__ dst, int g0, int g1, 
             const float4 q = *reinterpret_cast<const float4 *>(lds + idx * VE + j);
             v[j] = q.x; v[j + 1] = q.y; v[j + 2] = q.z; v[j + 3] = q.w;
         }
-        if (a >= g0 && a + VE <= g1) store_vec<T, VE>(dst + a, v, stream);
+        if (plain || (a >= g0 && a + VE <= g1)) store_vec<T, VE>(dst + a, v, stream);
         else {
 #pragma unroll
             for (int j = 0; j < VE; ++j)
                 if (a + j >= g0 && a + j < g1) stf(dst + a + j, v[j]);
         }
+    };
+    for (int first = 0; first < nvec; first += 256) {    // uniform trip count
+        const int idx = first + (int)threadIdx.x;
+        if (aligned && first + 256 <= nvec) one(idx, true);          // uniform: a whole batch of whole vectors
+        else if (idx < nvec) one(idx, false);
     }
 }
 
