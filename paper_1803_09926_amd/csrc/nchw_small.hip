@@ -67,9 +67,10 @@ __device__ __forceinline__ void flat_load(const T *__restrict__ src, int total, 
     }
 }
 
-// The same in two halves, so that the loads of the next range can be in flight while the block
-// computes on the current one: issue into registers (up to FLAT_BATCH vectors per lane), commit to LDS.
-template <typename T> struct FlatRegs { static constexpr int BATCH = 16 / ElemsS<T>::VE * 2; float v[BATCH][ElemsS<T>::VE]; };
+// The same in two halves, so that the loads of the next range can be in flight while the block computes on the
+// current one: issue into registers (up to BATCH 16-byte vectors per lane, kept as loaded: bf16 stays packed, which
+// halves the registers a stage in flight costs), commit to LDS (widening bf16 there).
+template <typename T> struct FlatRegs { static constexpr int BATCH = 16 / ElemsS<T>::VE * 2; uint4 raw[BATCH]; };
 template <typename T>
 __device__ __forceinline__ void flat_issue(const T *__restrict__ src, int total, int g0, int g1, FlatRegs<T> &r)
 {
@@ -80,7 +81,20 @@ __device__ __forceinline__ void flat_issue(const T *__restrict__ src, int total,
 #pragma unroll
     for (int it = 0; it < FlatRegs<T>::BATCH; ++it) {
         if (it * 256 >= nvec) break;                     // uniform over the block
-        flat_load_vec<T, VE>(src, total, a0, nvec, it * 256 + (int)threadIdx.x, whole, r.v[it]);
+        const int a = a0 + min(it * 256 + (int)threadIdx.x, nvec - 1) * VE;
+        if (whole || a + VE <= total) r.raw[it] = *reinterpret_cast<const uint4 *>(src + a);
+        else {                                           // the last vector of a tensor whose size is not a multiple of VE
+            uint32_t wds[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int j = 0; j < VE; ++j) {
+                const T t = src[min(a + j, total - 1)];
+                uint32_t bits;
+                if constexpr (sizeof(T) == 4) bits = __float_as_uint(t); else bits = (uint32_t)t;
+                if (a + j >= total) bits = 0u;
+                if constexpr (sizeof(T) == 4) wds[j] = bits; else wds[j / 2] |= bits << (16 * (j & 1));
+            }
+            r.raw[it] = make_uint4(wds[0], wds[1], wds[2], wds[3]);
+        }
     }
 }
 template <typename T>
@@ -92,7 +106,17 @@ __device__ __forceinline__ void flat_commit(int g0, int g1, const FlatRegs<T> &r
 #pragma unroll
     for (int it = 0; it < FlatRegs<T>::BATCH; ++it) {
         if (it * 256 >= nvec) break;                     // uniform over the block
-        flat_commit_vec<ElemsS<T>::VE>(lds, nvec, it * 256, r.v[it]);
+        const uint4 q = r.raw[it];
+        float v[VE];
+        if constexpr (sizeof(T) == 4) {
+            v[0] = __uint_as_float(q.x); v[1] = __uint_as_float(q.y); v[2] = __uint_as_float(q.z); v[3] = __uint_as_float(q.w);
+        } else {
+            v[0] = __uint_as_float(q.x << 16); v[1] = __uint_as_float(q.x & 0xffff0000u);
+            v[2] = __uint_as_float(q.y << 16); v[3] = __uint_as_float(q.y & 0xffff0000u);
+            v[4] = __uint_as_float(q.z << 16); v[5] = __uint_as_float(q.z & 0xffff0000u);
+            v[6] = __uint_as_float(q.w << 16); v[7] = __uint_as_float(q.w & 0xffff0000u);
+        }
+        flat_commit_vec<VE>(lds, nvec, it * 256, v);
     }
 }
 
