@@ -27,8 +27,10 @@
  * may alias an input.  `stream` is a hipStream_t passed as void* (NULL = the default stream).
  * The library never allocates, frees, copies or synchronises: all work is enqueued
  * asynchronously on `stream` and the buffers must stay alive until the stream reaches it.
- * There is no global mutable state; concurrent calls on different streams are safe as long as
- * they use different workspaces.
+ * Concurrent calls on different streams are safe as long as they use different workspaces.  The
+ * only global state is a snapshot of the DWCONV_TUNE_* tuning variables, which is taken once and
+ * is empty unless DWCONV_TUNE=1 was set in the environment (see dwconv_tuning_reload below): no
+ * call reads the environment, and a workspace query and the launch that follows always agree.
  *
  * Errors: 0 on success, a negative dwconv_status otherwise.  Arguments are validated on the
  * host before the first HIP call, and on a validation failure nothing is enqueued.
@@ -79,7 +81,9 @@ typedef struct dwconv_desc {
 int dwconv_out_dims(const dwconv_desc *desc, int32_t *Ho, int32_t *Wo);
 
 /* Bytes of device scratch that dwconv_bwd_filter needs for `desc` (partial sums of the
- * two-stage reduction).  Host-only.  Returns 0 for an invalid desc; never more than 64 MiB. */
+ * two-stage reduction).  Host-only.  Returns 0 for an invalid desc.  Never more than
+ * max(64 MiB, O*K*K*4): shapes whose partial sums would not fit in 64 MiB run with a single
+ * partial, the size of dw itself. */
 size_t dwconv_bwd_filter_workspace_bytes(const dwconv_desc *desc);
 
 /* Forward pass (Section III-A: z(i) = w(i) . C(i), Eq. 3):
@@ -130,6 +134,13 @@ const char *dwconv_status_string(int status);
  * tests.  Returns "invalid" for an invalid desc. */
 const char *dwconv_variant_name(const dwconv_desc *desc, int pass);
 
+/* Tuning hook, not needed in normal use.  The dispatcher's tile sizes can be overridden through
+ * DWCONV_TUNE_* environment variables, but only as a snapshot: it is taken at the first call into
+ * the library, and holds nothing unless DWCONV_TUNE=1 is set then.  This call takes a new snapshot
+ * (after the caller changed the environment) and returns the number of variables it holds.  It must
+ * not overlap any other call into the library, and a workspace size queried before it is stale. */
+int dwconv_tuning_reload(void);
+
 /* ---- Group convolution: more than one channel per group ------------------------------------------
  *
  * Section V-B (extensibility): a depthwise convolution is the group convolution whose number of
@@ -164,7 +175,8 @@ typedef struct dwconv_group_desc {
 
 /* Output spatial size; host-only.  Ho, Wo may be NULL. */
 int gconv_out_dims(const dwconv_group_desc *desc, int32_t *Ho, int32_t *Wo);
-/* Device scratch gconv_bwd_filter needs; host-only; 0 for an invalid desc; at most 64 MiB. */
+/* Device scratch gconv_bwd_filter needs; host-only; 0 for an invalid desc; at most
+ * max(64 MiB, O*Cg*K*K*4), as for the depthwise layer. */
 size_t gconv_bwd_filter_workspace_bytes(const dwconv_group_desc *desc);
 /* x, w: device, read.  y: device, written in full. */
 int gconv_fwd(const dwconv_group_desc *desc, const void *x, const void *w, void *y, void *stream);

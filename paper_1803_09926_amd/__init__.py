@@ -6,6 +6,7 @@ computation runs in the HIP kernels of libdwconv.so; there is no CPU or PyTorch 
 """
 from __future__ import annotations
 
+import contextlib
 import ctypes
 import os
 
@@ -22,7 +23,7 @@ _lib = None
 
 EXPORTS = ("dwconv_out_dims", "dwconv_bwd_filter_workspace_bytes", "dwconv_fwd", "dwconv_bwd_data",
            "dwconv_bwd_filter", "dwconv_bwd_workspace_bytes", "dwconv_bwd", "dwconv_status_string",
-           "dwconv_variant_name",
+           "dwconv_variant_name", "dwconv_tuning_reload",
            "gconv_out_dims", "gconv_bwd_filter_workspace_bytes", "gconv_fwd", "gconv_bwd_data", "gconv_bwd_filter",
            "gconv_variant_name")
 
@@ -64,6 +65,7 @@ def load():
     lib.dwconv_bwd.argtypes = [P, VP, VP, VP, VP, VP, VP, ctypes.c_size_t, VP]; lib.dwconv_bwd.restype = ctypes.c_int
     lib.dwconv_status_string.argtypes = [ctypes.c_int]; lib.dwconv_status_string.restype = ctypes.c_char_p
     lib.dwconv_variant_name.argtypes = [P, ctypes.c_int]; lib.dwconv_variant_name.restype = ctypes.c_char_p
+    lib.dwconv_tuning_reload.argtypes = []; lib.dwconv_tuning_reload.restype = ctypes.c_int
     G = ctypes.POINTER(GroupDesc)
     lib.gconv_out_dims.argtypes = [G, I32P, I32P]; lib.gconv_out_dims.restype = ctypes.c_int
     lib.gconv_bwd_filter_workspace_bytes.argtypes = [G]; lib.gconv_bwd_filter_workspace_bytes.restype = ctypes.c_size_t
@@ -85,6 +87,33 @@ def status_string(status: int) -> str:
 
 def variant_name(d: Desc, which: int) -> str:
     return load().dwconv_variant_name(ctypes.byref(d), int(which)).decode()
+
+
+def tuning_reload() -> int:
+    """Take a new snapshot of the DWCONV_TUNE_* environment variables (tuning sweeps and forced-tiling tests only;
+    holds nothing unless DWCONV_TUNE=1 is set).  Returns the number of variables in the snapshot."""
+    return int(load().dwconv_tuning_reload())
+
+
+@contextlib.contextmanager
+def tuning_overrides(knobs: dict):
+    """Run a block with the given DWCONV_TUNE_* variables in force (tuning sweeps and forced-tiling tests): sets them and
+    the master switch, takes a snapshot, and on exit restores the environment and takes the snapshot again."""
+    names = list(knobs) + ["DWCONV_TUNE"]
+    saved = {k: os.environ.get(k) for k in names}
+    try:
+        for k, v in knobs.items():
+            os.environ[k] = str(v)
+        os.environ["DWCONV_TUNE"] = "1"
+        tuning_reload()
+        yield
+    finally:
+        for k, v in saved.items():
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = v
+        tuning_reload()
 
 
 def out_dims(d: Desc):

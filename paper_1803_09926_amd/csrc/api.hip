@@ -146,6 +146,8 @@ int dwconv_bwd(const dwconv_desc *desc, const void *x, const void *dy, const voi
     return e == hipSuccess ? DWCONV_OK : DWCONV_ERR_LAUNCH;
 }
 
+int dwconv_tuning_reload(void) { return tune_reload(); }
+
 const char *dwconv_variant_name(const dwconv_desc *desc, int pass)
 {
     Geom g;

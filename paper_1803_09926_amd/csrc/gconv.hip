@@ -34,8 +34,9 @@ template <typename T, int LAYOUT>
 __global__ __launch_bounds__(256) void k_gconv_generic_fwd(GGeom g, const T *__restrict__ x, const T *__restrict__ w,
                                                            T *__restrict__ y, int total)
 {
-    const int idx = blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total) return;
+    const unsigned uidx = blockIdx.x * 256u + threadIdx.x;   // the last block may reach past 2^31
+    if (uidx >= (unsigned)total) return;
+    int idx = (int)uidx;
     int n, o, oh, ow;
     gunflat<LAYOUT>(idx, g.O, g.Ho, g.Wo, n, o, oh, ow);
     const int c0 = (o / g.Og) * g.Cg;
@@ -57,8 +58,9 @@ template <typename T, int LAYOUT>
 __global__ __launch_bounds__(256) void k_gconv_generic_bwd_data(GGeom g, const T *__restrict__ dy,
                                                                 const T *__restrict__ w, T *__restrict__ dx, int total)
 {
-    const int idx = blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total) return;
+    const unsigned uidx = blockIdx.x * 256u + threadIdx.x;   // the last block may reach past 2^31
+    if (uidx >= (unsigned)total) return;
+    int idx = (int)uidx;
     int n, c, ih, iw;
     gunflat<LAYOUT>(idx, g.C, g.H, g.W, n, c, ih, iw);
     const int o0 = (c / g.Cg) * g.Og, ci = c % g.Cg;
@@ -143,7 +145,7 @@ __global__ __launch_bounds__(256) void k_gconv_generic_bwd_filter_nhwc(GGeom g, 
 hipError_t gconv_generic_fwd(const GGeom &g, int layout, int dtype, const void *x, const void *w, void *y, hipStream_t st)
 {
     const int total = g.N * g.O * g.Ho * g.Wo;
-    dim3 grid((total + 255) / 256), block(256);
+    dim3 grid((unsigned)(((long long)total + 255) / 256)), block(256);
 #define LAUNCH(T, L) hipLaunchKernelGGL((k_gconv_generic_fwd<T, L>), grid, block, 0, st, g, (const T *)x, (const T *)w, (T *)y, total)
     if (dtype == DT_F32) { if (layout == LAYOUT_NCHW) LAUNCH(float, LAYOUT_NCHW); else LAUNCH(float, LAYOUT_NHWC); }
     else                 { if (layout == LAYOUT_NCHW) LAUNCH(bf16_t, LAYOUT_NCHW); else LAUNCH(bf16_t, LAYOUT_NHWC); }
@@ -155,7 +157,7 @@ hipError_t gconv_generic_bwd_data(const GGeom &g, int layout, int dtype, const v
                                   hipStream_t st)
 {
     const int total = g.N * g.C * g.H * g.W;
-    dim3 grid((total + 255) / 256), block(256);
+    dim3 grid((unsigned)(((long long)total + 255) / 256)), block(256);
 #define LAUNCH(T, L) hipLaunchKernelGGL((k_gconv_generic_bwd_data<T, L>), grid, block, 0, st, g, (const T *)dy, (const T *)w, (T *)dx, total)
     if (dtype == DT_F32) { if (layout == LAYOUT_NCHW) LAUNCH(float, LAYOUT_NCHW); else LAUNCH(float, LAYOUT_NHWC); }
     else                 { if (layout == LAYOUT_NCHW) LAUNCH(bf16_t, LAYOUT_NCHW); else LAUNCH(bf16_t, LAYOUT_NHWC); }
@@ -204,7 +206,7 @@ hipError_t gconv_generic_bwd_filter(const GGeom &g, int layout, int dtype, const
 static GPlan gplan(const GGeom &g, int layout, int dtype, int pass)
 {
     GPlan pl = {GV_GENERIC, pass == 2 ? gconv_generic_bwd_filter_parts(g) : 0, 0, 0, 0, "group_generic"};
-    if (getenv("DWCONV_TUNE_GROUP_GENERIC")) return pl;
+    if (tune_env("DWCONV_TUNE_GROUP_GENERIC")) return pl;
     if (layout == LAYOUT_NCHW && gconv_nchw_supported(g)) {
         pl.variant = GV_NCHW_K3S1;
         pl.name = pass == 0 ? "group_nchw_rowwalk_k3s1" : pass == 1 ? "group_nchw_rowwalk_k3s1_flip" : "group_nchw_bwd_filter_k3s1";
@@ -213,6 +215,11 @@ static GPlan gplan(const GGeom &g, int layout, int dtype, int pass)
         pl.variant = GV_NHWC_K3S1;
         pl.name = pass == 0 ? "group_nhwc_rowwalk_k3s1" : pass == 1 ? "group_nhwc_rowwalk_k3s1_flip" : "group_nhwc_bwd_filter_k3s1";
         if (pass == 2) pl.parts = gconv_nhwc_bwd_filter_parts(g, dtype);
+    }
+    // a tuned filter gradient whose partial sums would not fit in 64 MiB (very wide rows): the generic kernels
+    if (pass == 2 && pl.variant != GV_GENERIC && (long long)pl.parts * g.O * g.Cg * g.K * g.K * 4 > (64ll << 20)) {
+        const GPlan gen = {GV_GENERIC, gconv_generic_bwd_filter_parts(g), 0, 0, 0, "group_generic"};
+        return gen;
     }
     return pl;
 }

@@ -286,7 +286,7 @@ __global__ __launch_bounds__(256) void k_gconv_nchw_bwd_filter(GGeom g, const T 
 
 static int gtune(const char *name, int dflt)
 {
-    const char *e = getenv(name);
+    const char *e = tune_env(name);
     return e && *e ? atoi(e) : dflt;
 }
 static int pick_ob(int CO)

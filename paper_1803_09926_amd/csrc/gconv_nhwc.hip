@@ -324,7 +324,7 @@ static hipError_t launch_gs1(const GGeom &g, const void *in, const void *w, void
     const int COT = flip ? g.C : g.O;
     const int lanes = g.W * (COT / (OB * GPL));
     const int bs = 256;
-    const char *eth = getenv("DWCONV_TUNE_GHTH");
+    const char *eth = tune_env("DWCONV_TUNE_GHTH");
     const int TH = eth && atoi(eth) > 0 ? atoi(eth) : nhwc_pick_th(g.H);
     const int nchunks = cdiv(lanes, bs), nstrips = cdiv(g.H, TH);
     const long long nb = (long long)g.N * nchunks * nstrips;
@@ -347,7 +347,7 @@ hipError_t gconv_nhwc_s1(const GGeom &g, int dtype, const void *in, const void *
     const int CG = flip ? g.Og : g.Cg, CGW = flip ? g.Cg : g.Og;
     const int OB = nhwc_ob(CG, CGW);
     // two channels per group on both sides and an even number of groups: two groups per lane
-    const int GPL = (CG == 2 && CGW == 2 && g.G % 2 == 0 && !getenv("DWCONV_TUNE_GGPL1")) ? 2 : 1;
+    const int GPL = (CG == 2 && CGW == 2 && g.G % 2 == 0 && !tune_env("DWCONV_TUNE_GGPL1")) ? 2 : 1;
 #define TRY(T, CGG, OBB, GG, PPF) if (CG == CGG && OB == OBB && GPL == GG) return launch_gs1<T, CGG, OBB, GG, PPF>(g, in, w, out, flip, st)
     if (dtype == DT_F32) {
         TRY(float, 2, 4, 1, 2); TRY(float, 2, 2, 1, 2); TRY(float, 2, 2, 2, 2); TRY(float, 4, 2, 1, 2); TRY(float, 4, 1, 1, 2); TRY(float, 8, 1, 1, 1);
@@ -362,8 +362,8 @@ hipError_t gconv_nhwc_s1(const GGeom &g, int dtype, const void *in, const void *
 // 2-byte loads per lane measured slower than the 8-byte ones of the first form (groups of 8: the other way round).
 static bool nhwc_bwd_filter_xchg(const GGeom &g, int dtype)
 {
-    if (!gconv_nhwc_xchg_supported(g) || getenv("DWCONV_TUNE_GNOXCHGW")) return false;
-    return !(dtype == DT_BF16 && g.Cg == 4) || getenv("DWCONV_TUNE_GXCHGW");
+    if (!gconv_nhwc_xchg_supported(g) || tune_env("DWCONV_TUNE_GNOXCHGW")) return false;
+    return !(dtype == DT_BF16 && g.Cg == 4) || tune_env("DWCONV_TUNE_GXCHGW");
 }
 
 // Filter-gradient tiling.  CT: lanes over sub-vectors (a power of two up to 64), 256/CT columns per block.
@@ -383,8 +383,8 @@ static void gconv_nhwc_bwd_filter_tiling(const GGeom &g, int dtype, int *OBp, in
     while (th > 7 && per_strip * cdiv(g.H, th) < 384) th = (th + 1) / 2;
     int ni = 1;
     while (ni < g.N && per_strip * cdiv(g.H, th) / (ni * 2) >= 384) ni *= 2;
-    if (const char *e = getenv("DWCONV_TUNE_GHWTH")) if (atoi(e) > 0) th = atoi(e);
-    if (const char *e = getenv("DWCONV_TUNE_GHWNI")) if (atoi(e) > 0) ni = atoi(e);
+    if (const char *e = tune_env("DWCONV_TUNE_GHWTH")) if (atoi(e) > 0) th = atoi(e);
+    if (const char *e = tune_env("DWCONV_TUNE_GHWNI")) if (atoi(e) > 0) ni = atoi(e);
     const long long J = (long long)g.O * g.Cg * 9;
     while ((long long)nowt * cdiv(g.H, th) * cdiv(g.N, ni) * J * 4 > (64ll << 20)) {
         if (ni < g.N) ni *= 2; else if (th < g.H) th *= 2; else break;

@@ -346,13 +346,13 @@ __global__ __launch_bounds__(256) void k_gconv_nhwc_xchg_bwd_filter(GGeom g, con
 static inline int cdivx(int a, int b) { return (a + b - 1) / b; }
 static int xtune(const char *name, int dflt)
 {
-    const char *e = getenv(name);
+    const char *e = tune_env(name);
     return e && *e ? atoi(e) : dflt;
 }
 
 bool gconv_nhwc_xchg_supported(const GGeom &g)
 {
-    if (getenv("DWCONV_TUNE_GNOXCHG")) return false;
+    if (tune_env("DWCONV_TUNE_GNOXCHG")) return false;
     return g.K == 3 && g.s == 1 && g.p == 1 && g.Cg == g.Og && (g.Cg == 4 || g.Cg == 8);
 }
 

@@ -32,8 +32,9 @@ template <typename T, int LAYOUT>
 __global__ __launch_bounds__(256) void k_generic_fwd(Geom g, const T *__restrict__ x, const T *__restrict__ w,
                                                      T *__restrict__ y, int total)
 {
-    int idx = blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total) return;
+    const unsigned uidx = blockIdx.x * 256u + threadIdx.x;   // the last block may reach past 2^31
+    if (uidx >= (unsigned)total) return;
+    int idx = (int)uidx;
     int n, o, oh, ow;
     unflat<LAYOUT>(idx, g.O, g.Ho, g.Wo, n, o, oh, ow);
     const int c = o / g.m;
@@ -54,8 +55,9 @@ template <typename T, int LAYOUT>
 __global__ __launch_bounds__(256) void k_generic_bwd_data(Geom g, const T *__restrict__ dy, const T *__restrict__ w,
                                                           T *__restrict__ dx, int total)
 {
-    int idx = blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total) return;
+    const unsigned uidx = blockIdx.x * 256u + threadIdx.x;   // the last block may reach past 2^31
+    if (uidx >= (unsigned)total) return;
+    int idx = (int)uidx;
     int n, c, ih, iw;
     unflat<LAYOUT>(idx, g.C, g.H, g.W, n, c, ih, iw);
     float acc = 0.f;
@@ -178,7 +180,7 @@ __global__ __launch_bounds__(256) void k_reduce_partials(const float *__restrict
 hipError_t generic_fwd(const Geom &g, int layout, int dtype, const void *x, const void *w, void *y, hipStream_t st)
 {
     const int total = g.N * g.O * g.Ho * g.Wo;
-    dim3 grid((total + 255) / 256), block(256);
+    dim3 grid((unsigned)(((long long)total + 255) / 256)), block(256);
 #define LAUNCH(T, L) hipLaunchKernelGGL((k_generic_fwd<T, L>), grid, block, 0, st, g, (const T *)x, (const T *)w, (T *)y, total)
     if (dtype == DT_F32) { if (layout == LAYOUT_NCHW) LAUNCH(float, LAYOUT_NCHW); else LAUNCH(float, LAYOUT_NHWC); }
     else                 { if (layout == LAYOUT_NCHW) LAUNCH(bf16_t, LAYOUT_NCHW); else LAUNCH(bf16_t, LAYOUT_NHWC); }
@@ -189,7 +191,7 @@ hipError_t generic_fwd(const Geom &g, int layout, int dtype, const void *x, cons
 hipError_t generic_bwd_data(const Geom &g, int layout, int dtype, const void *dy, const void *w, void *dx, hipStream_t st)
 {
     const int total = g.N * g.C * g.H * g.W;
-    dim3 grid((total + 255) / 256), block(256);
+    dim3 grid((unsigned)(((long long)total + 255) / 256)), block(256);
 #define LAUNCH(T, L) hipLaunchKernelGGL((k_generic_bwd_data<T, L>), grid, block, 0, st, g, (const T *)dy, (const T *)w, (T *)dx, total)
     if (dtype == DT_F32) { if (layout == LAYOUT_NCHW) LAUNCH(float, LAYOUT_NCHW); else LAUNCH(float, LAYOUT_NHWC); }
     else                 { if (layout == LAYOUT_NCHW) LAUNCH(bf16_t, LAYOUT_NCHW); else LAUNCH(bf16_t, LAYOUT_NHWC); }

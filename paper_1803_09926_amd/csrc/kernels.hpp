@@ -2,6 +2,7 @@
 // the launch.  All pointers are device pointers; T-typed tensors are passed as void*.
 #pragma once
 #include "common.hpp"
+#include "tune.hpp"
 #include <stdio.h>
 #include <stdlib.h>
 
@@ -10,16 +11,18 @@ namespace dwc {
 enum { LAYOUT_NCHW = 0, LAYOUT_NHWC = 1 };
 
 // Whether a kernel family writes its output with non-temporal stores.  `dflt_min_bytes` is the
-// smallest output for which it does (negative: never).  DWCONV_TUNE_NT=0/1 overrides every family,
-// DWCONV_TUNE_NT_<family>=0/1 one of them (tuning runs only).
+// smallest output for which it does (negative: never).  In a tuning snapshot DWCONV_TUNE_NT=0/1
+// overrides every family and DWCONV_TUNE_NT_<family>=0/1 one of them.
 inline int stream_stores(const char *family, long long out_bytes, long long dflt_min_bytes = 64ll << 20)
 {
-    char name[64];
-    snprintf(name, sizeof name, "DWCONV_TUNE_NT_%s", family);
-    const char *e = getenv(name);
-    if (e && *e) return atoi(e) != 0;
-    e = getenv("DWCONV_TUNE_NT");
-    if (e && *e) return atoi(e) != 0;
+    if (tune_active()) {
+        char name[64];
+        snprintf(name, sizeof name, "DWCONV_TUNE_NT_%s", family);
+        const char *e = tune_env(name);
+        if (e) return atoi(e) != 0;
+        e = tune_env("DWCONV_TUNE_NT");
+        if (e) return atoi(e) != 0;
+    }
     return dflt_min_bytes >= 0 && out_bytes >= dflt_min_bytes;
 }
 enum { DT_F32 = 0, DT_BF16 = 1 };

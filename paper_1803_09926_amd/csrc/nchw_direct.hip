@@ -1109,6 +1109,7 @@ int nchwd_vec(const Geom &g, int dtype, int pass)
     if (!s1 && !s2) return 0;
     if (pass == 1 && g.m != 1) return 0;
     if (pass == 2 && g.K != 3 && !(g.K == 5 && s1)) return 0;
+    if (pass == 2 && g.O > 65535) return 0;      // the filter-gradient launches put the channel on gridDim.y
     if (g.H < 16) return 0;                      // small planes go to the LDS-tile kernels
     const int wv = s1 ? g.W : g.Wo;              // the dimension that lanes split into vectors
     if (s2 && pass == 1) {                       // dy columns per lane; dx is stored 2V wide
@@ -1144,7 +1145,7 @@ static hipError_t go_s1(const Geom &g, const void *x, const void *w, void *y, bo
 #define GOB(FL, RSV) hipLaunchKernelGGL((k_nchwd_s1_bf16x8<V, K, 2, FL, RSV>), dim3(nblocks), dim3(256), 0, st, g, \
                                         (const bf16_t *)x, (const bf16_t *)w, (bf16_t *)y, TH, nstrips, nblocks)
             if constexpr (sizeof(T) == 2 && V == 8) {      // bf16: packed-pair arithmetic
-                if (!getenv("DWCONV_TUNE_NODOT")) {
+                if (!tune_env("DWCONV_TUNE_NODOT")) {
                     if (rs == 2) { if (flip) GOB(true, 2); else GOB(false, 2); }
                     else { if (flip) GOB(true, 4); else GOB(false, 4); }
                     return hipGetLastError();
@@ -1162,7 +1163,7 @@ static hipError_t go_s1(const Geom &g, const void *x, const void *w, void *y, bo
     // rows that are whole lines by themselves can be streamed as they are; otherwise a wave's store
     // covers pieces of several rows (partial lines) and stays cached
     if constexpr (sizeof(T) == 2) {
-        if (!getenv("DWCONV_TUNE_NODOT")) {
+        if (!tune_env("DWCONV_TUNE_NODOT")) {
             if (flip) GOB(true, 0); else GOB(false, 0);
             return hipGetLastError();
         }
@@ -1273,7 +1274,7 @@ hipError_t nchwd_bwd_filter(const Geom &g, int dtype, int V, const void *x, cons
 #define GO(T, VV, SS) hipLaunchKernelGGL((k_nchwd_bwd_filter_k3<T, VV, SS>), grid, dim3(256), 0, st, g, (const T *)x, \
                                          (const T *)dy, ws, TH, nstrips, lg, rounds)
     if (g.s == 1 && dtype == DT_BF16 && (g.K == 3 || g.K == 5) && (V == 8 || V == 4) && !(V == 4 && g.K == 3) &&
-        !getenv("DWCONV_TUNE_NODOT")) {
+        !tune_env("DWCONV_TUNE_NODOT")) {
         // bf16: packed-pair arithmetic (3x3 on 4-column lanes measured faster with the two-rows-ahead kernel below)
 #define GOD(VV, KK) hipLaunchKernelGGL((k_nchwd_bwd_filter_s1_bf16<VV, KK>), grid, dim3(256), 0, st, g, (const bf16_t *)x, \
                                        (const bf16_t *)dy, ws, TH, nstrips, lg, rounds)

@@ -769,8 +769,8 @@ hipError_t nhwc_s1(const Geom &g, int dtype, int V, const void *x, const void *w
                    hipStream_t st)
 {
     // bf16 5x5 on two channels per lane: two output columns per lane (fewer memory instructions)
-    if (dtype == DT_BF16 && g.m == 1 && g.K == 5 && V == 2 && !getenv("DWCONV_TUNE_NO2COL")) {
-        const char *e = getenv("DWCONV_TUNE_NCOL");
+    if (dtype == DT_BF16 && g.m == 1 && g.K == 5 && V == 2 && !tune_env("DWCONV_TUNE_NO2COL")) {
+        const char *e = tune_env("DWCONV_TUNE_NCOL");
         const int ncol = e ? atoi(e) : 2;
         if (ncol == 4) return launch_s1_2col<bf16_t, 2, 5, 2, 4>(g, x, w, y, flip, TH, st);
         if (ncol == 3) return launch_s1_2col<bf16_t, 2, 5, 2, 3>(g, x, w, y, flip, TH, st);

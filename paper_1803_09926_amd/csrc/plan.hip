@@ -6,11 +6,11 @@ namespace dwc {
 
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-// Optional overrides for tuning runs (unset in normal use): DWCONV_TUNE_TH, DWCONV_TUNE_NI.
+// Optional overrides for tuning runs, from the snapshot of tune.hpp (empty in normal use).
 static int tune(const char *name, int dflt)
 {
-    const char *e = getenv(name);
-    if (!e || !*e) return dflt;
+    const char *e = tune_env(name);
+    if (!e) return dflt;
     int v = atoi(e);
     return v > 0 ? v : dflt;
 }
@@ -171,7 +171,7 @@ Plan plan_bwd_filter(const Geom &g, int layout, int dtype)
             nchwd_bwd_filter_tiling(g, V, TH, &lg, &nst, &rounds, &parts);
             // small batches: shorter strips until the launch has about two blocks per CU (one block = one
             // channel x a group of (image, strip) items)
-            while (TH > 7 && parts >= 1 && (long long)parts * g.O < 512 && !getenv("DWCONV_TUNE_THW") && !getenv("DWCONV_TUNE_TH")) {
+            while (TH > 7 && parts >= 1 && (long long)parts * g.O < 512 && !tune_env("DWCONV_TUNE_THW") && !tune_env("DWCONV_TUNE_TH")) {
                 TH = (TH + 1) / 2;
                 nchwd_bwd_filter_tiling(g, V, TH, &lg, &nst, &rounds, &parts);
             }
@@ -223,12 +223,17 @@ Plan plan_bwd_filter(const Geom &g, int layout, int dtype)
             while (TH > 7 && per_strip * ceil_div(g.Ho, TH) * 4 < want * 3) TH = (TH + 1) / 2;
             while (NI < g.N && per_strip * ceil_div(g.Ho, TH) / (NI * 2) >= floor_blocks) NI *= 2;
             TH = tune("DWCONV_TUNE_THW", tune("DWCONV_TUNE_TH", TH)); NI = tune("DWCONV_TUNE_NI", NI);
+            if (TH > g.Ho) TH = g.Ho;
+            if (NI > g.N) NI = g.N;
             nhwc_bwd_filter_tiling(g, V, TH, NI, &CT, &nct, &nowt, &nst, &ngr);
-            // keep the partials within the 64 MiB the header promises
-            while ((long long)nowt * nst * ngr * g.O * g.K * g.K * 4 > (64ll << 20)) {
-                if (NI < g.N) NI *= 2; else TH *= 2;
+            // keep the partials within 64 MiB: more images per block, then taller strips; a shape that is
+            // still above it with whole columns of the whole batch per block (very many channels times very
+            // wide rows) goes to the generic kernels, whose partials are a single O*K*K array in that case
+            while ((long long)nowt * nst * ngr * g.O * g.K * g.K * 4 > (64ll << 20) && (NI < g.N || TH < g.Ho)) {
+                if (NI < g.N) NI = NI * 2 < g.N ? NI * 2 : g.N; else TH = TH * 2 < g.Ho ? TH * 2 : g.Ho;
                 nhwc_bwd_filter_tiling(g, V, TH, NI, &CT, &nct, &nowt, &nst, &ngr);
             }
+            if ((long long)nowt * nst * ngr * g.O * g.K * g.K * 4 > (64ll << 20)) return pl;
             pl.variant = V_NHWC_BWD_FILTER; pl.a = V; pl.b = TH; pl.c = NI;
             pl.parts = nowt * nst * ngr;
             pl.name = g.m == 2 ? "nhwc_bwd_filter_k3s1_m2"
@@ -241,7 +246,7 @@ Plan plan_bwd_filter(const Geom &g, int layout, int dtype)
 Plan plan_bwd(const Geom &g, int layout, int dtype)
 {
     Plan pl = {V_GENERIC, 0, 0, 0, 0, "separate"};
-    if (layout == LAYOUT_NHWC && !getenv("DWCONV_TUNE_NOFUSE")) {
+    if (layout == LAYOUT_NHWC && !tune_env("DWCONV_TUNE_NOFUSE")) {
         const int V = nhwc_vec(g, dtype);
         if (V && nhwc_bwd_fused_supported(g, dtype, V)) {
             // tiling of the filter gradient: its block count and partial sums decide
@@ -253,7 +258,7 @@ Plan plan_bwd(const Geom &g, int layout, int dtype)
             }
         }
     }
-    if (layout == LAYOUT_NCHW && !getenv("DWCONV_TUNE_NOFUSE")) {
+    if (layout == LAYOUT_NCHW && !tune_env("DWCONV_TUNE_NOFUSE")) {
         const Plan pf = plan_bwd_filter(g, layout, dtype);
         if (pf.variant == V_NCHWS_BWD_FILTER && nchws_bwd_fused_supported(g)) {
             int U, NI, parts;

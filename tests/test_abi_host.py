@@ -272,3 +272,84 @@ def test_dpp_operands_are_not_written_just_before_they_are_read(tmp_path):
             w = re.match(r"v_\w+ (v\d+)", p)
             assert not (w and w.group(1) == m.group(2)), "DPP read of %s right after its write: %r then %r" % (m.group(2), p, l)
     assert ndpp > 1000      # the kernels do use the DPP form
+
+
+def _ws_bound(d):
+    O = d.C * d.mult
+    return max(64 << 20, O * d.K * d.K * 4)
+
+
+def test_planner_terminates_and_bounds_the_workspace_on_extreme_shapes():
+    """Valid descriptors with very many channels, very wide rows or one-pixel planes: the host-side planning
+    (variant, workspace size, both backward plans) must return, name a variant, and keep the workspace within
+    max(64 MiB, the size of dw)."""
+    shapes = [
+        # N, C, H, W, K, s, p, m
+        (2, 65536, 1, 147, 3, 1, 1, 1), (8, 1024, 1, 5000, 3, 1, 1, 2), (1, 2097152, 1, 1, 3, 1, 1, 1),
+        (1, 4194304, 1, 1, 3, 1, 1, 1), (1, 70000, 16, 16, 3, 1, 1, 1), (1, 70000, 16, 16, 3, 2, 1, 1),
+        (1, 131072, 16, 16, 5, 1, 2, 1), (4, 8, 1, 60000, 3, 1, 1, 1), (1, 4, 30000, 1, 3, 1, 1, 1),
+        (1, 65540, 2, 8000, 3, 1, 1, 1), (3, 100000, 7, 7, 3, 1, 1, 1), (3, 100000, 14, 14, 3, 2, 1, 1),
+        (1, 8, 20000, 8, 5, 1, 2, 1), (16, 32768, 8, 8, 3, 1, 1, 2), (1, 1 << 20, 4, 4, 15, 1, 7, 1),
+    ]
+    for N, C, H, W, K, s, p, m in shapes:
+        for layout in (dw.NCHW, dw.NHWC):
+            for dtype in (dw.F32, dw.BF16):
+                d = dw.desc(N, C, H, W, K, s, p, m, layout, dtype)
+                tag = (N, C, H, W, K, s, p, m, layout, dtype)
+                for which in range(4):
+                    assert dw.variant_name(d, which) not in ("", "invalid"), tag
+                assert 0 < dw.bwd_filter_workspace_bytes(d) <= _ws_bound(d), tag
+                assert 0 < dw.bwd_workspace_bytes(d) <= _ws_bound(d), tag
+                # a workspace that is too small is refused before any launch
+                assert dw.load().dwconv_bwd_filter(ctypes.byref(d), A, B, Cp, Dp, 8, None) == E_WS, tag
+
+
+def test_planner_sweep_of_channels_and_widths():
+    for C in (4, 60, 1000, 4096, 65535, 65536, 65537, 300000):
+        for W in (1, 7, 14, 16, 56, 148, 1000, 5000):
+            for H in (1, 16):
+                if C * H * W >= 1 << 30:
+                    continue
+                for layout in (dw.NCHW, dw.NHWC):
+                    d = dw.desc(2, C, H, W, 3, 1, 1, 1, layout, dw.F32)
+                    assert dw.variant_name(d, 2) != "invalid"
+                    assert 0 < dw.bwd_filter_workspace_bytes(d) <= _ws_bound(d), (C, H, W, layout)
+                    assert 0 < dw.bwd_workspace_bytes(d) <= _ws_bound(d), (C, H, W, layout)
+
+
+def test_group_workspace_bound_on_extreme_shapes():
+    for (N, C, O, G, H, W, K) in [(1, 65536, 65536, 8192, 4, 4, 15), (2, 4096, 8192, 512, 1, 3000, 3),
+                                  (1, 262144, 262144, 65536, 2, 2, 3), (4, 64, 64, 16, 1, 40000, 3)]:
+        for layout in (dw.NCHW, dw.NHWC):
+            d = dw.group_desc(N, C, H, W, K, 1, K // 2, G, O, layout, dw.F32)
+            bound = max(64 << 20, O * (C // G) * K * K * 4)
+            assert 0 < dw.gconv_bwd_filter_workspace_bytes(d) <= bound, (N, C, O, G, H, W, K, layout)
+            assert dw.gconv_variant_name(d, 2) != "invalid"
+
+
+def test_tuning_variables_are_a_snapshot_behind_a_master_switch(monkeypatch):
+    """No call reads the environment: a DWCONV_TUNE_* variable set after the library's first use changes nothing
+    until dwconv_tuning_reload, and nothing at all without the master switch DWCONV_TUNE=1."""
+    d = dw.desc(128, 128, 56, 56, 3, 1, 1, 1, dw.NHWC, dw.F32)
+    assert dw.tuning_reload() == 0
+    base = dw.bwd_filter_workspace_bytes(d)
+    monkeypatch.setenv("DWCONV_TUNE_NI", "1")
+    monkeypatch.setenv("DWCONV_TUNE_THW", "7")
+    assert dw.bwd_filter_workspace_bytes(d) == base            # not read on the call
+    assert dw.tuning_reload() == 0                             # master switch off: still nothing
+    assert dw.bwd_filter_workspace_bytes(d) == base
+    monkeypatch.setenv("DWCONV_TUNE", "1")
+    assert dw.bwd_filter_workspace_bytes(d) == base            # still the old snapshot
+    assert dw.tuning_reload() == 2
+    forced = dw.bwd_filter_workspace_bytes(d)
+    assert forced > base                                       # one image and 7 rows per block: more partials
+    monkeypatch.setenv("DWCONV_TUNE_NI", "-5")                 # nonsense values are clamped, never negative
+    monkeypatch.setenv("DWCONV_TUNE_THW", "99999999999")
+    assert dw.tuning_reload() == 2
+    assert 0 < dw.bwd_filter_workspace_bytes(d) <= 64 << 20
+    monkeypatch.delenv("DWCONV_TUNE")
+    assert dw.tuning_reload() == 0
+    assert dw.bwd_filter_workspace_bytes(d) == base
+    with dw.tuning_overrides({"DWCONV_TUNE_NI": 1, "DWCONV_TUNE_THW": 7}):
+        assert dw.bwd_filter_workspace_bytes(d) == forced
+    assert dw.bwd_filter_workspace_bytes(d) == base

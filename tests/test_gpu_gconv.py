@@ -85,7 +85,7 @@ def test_group_conv_matches_oracle(case, layout, dtype):
 
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
-def test_group_nhwc_exchange_kernels_forced_tilings(monkeypatch, dtype):
+def test_group_nhwc_exchange_kernels_forced_tilings(dtype):
     """The lane-exchange NHWC kernels pick several images per block and whole-column strips only on large
     tensors; the tiling overrides force those paths (ragged last image group, ragged last strip, shallow and deep
     prefetch, two channels per lane) at sizes the oracle checks element by element."""
@@ -104,9 +104,7 @@ def test_group_nhwc_exchange_kernels_forced_tilings(monkeypatch, dtype):
         for kn in knobs:
             if name == "x_cg8" and kn.get("DWCONV_TUNE_GXV") == "2":
                 continue
-            with monkeypatch.context() as m:
-                for k, v in kn.items():
-                    m.setenv(k, v)
+            with dw.tuning_overrides(kn):
                 print("case", name, "knobs", kn, flush=True)
                 y, dx, dwt = run_gpu(case, wl.NHWC, dtype, x, w, dy)
             tag = "%s %s dtype=%d" % (name, kn, dtype)
@@ -118,8 +116,7 @@ def test_group_nhwc_exchange_kernels_forced_tilings(monkeypatch, dtype):
     name, N, C, O, G, H, W, K, s, p = case
     x, w, dy = wl.make_group_inputs(N, C, O, G, H, W, K, s, p, wl.NHWC, dtype, seed=98)
     kw = dict(K=K, stride=s, pad=p, groups=G, O=O, layout=wl.NHWC, nthreads=8)
-    with monkeypatch.context() as m:
-        m.setenv("DWCONV_TUNE_GXV", "2")
+    with dw.tuning_overrides({"DWCONV_TUNE_GXV": "2"}):
         y, dx, dwt = run_gpu(case, wl.NHWC, dtype, x, w, dy)
     tol = gu.TOL_F32 if dtype == wl.F32 else gu.TOL_BF16
     gu.assert_close(gu.to_host(y), og.fwd(x, w, **kw), tol, "gconv fwd two channels per lane")
