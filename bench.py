@@ -18,6 +18,8 @@ import sys
 import time
 
 PEAK_HBM_GBS = 8000.0
+# fp32 vector peak: 256 compute units x 128 fp32 multiply-add lanes per clock x 2 flops x 2.4 GHz
+PEAK_ALU_TFLOPS = 157.3
 METRIC = "ms and HBM GB/s (% of peak) per fwd+bwd of MobileNet-v1 dw stack, batch 128"
 PASS_NAMES = ("fwd", "bwd_data", "bwd_filter", "bwd")
 
@@ -97,8 +99,10 @@ def build_ops(dw, wl, cfg, torch, order="layer", side=None, fused_bwd=False):
             dwt = torch.empty(w.shape, device="cuda", dtype=torch.float32)
             ws = torch.empty(max(ws_bytes, 16), device="cuda", dtype=torch.uint8)
             nbytes = layer.pass_bytes(cfg["N"], esz)
+            # algorithmic flops of one pass: a multiply-add per tap (and per input channel of the group) and output element
+            nflops = 2 * layer.K * layer.K * layer.cg * layer.y_elems(cfg["N"])
             common = dict(layer=layer.name, li=li, layout="NCHW" if layout == wl.NCHW else "NHWC",
-                          bytes=nbytes, repeat=repeat, stride=layer.stride, H=layer.H)
+                          bytes=nbytes, flops=nflops, repeat=repeat, stride=layer.stride, H=layer.H)
             # Pre-marshalled C-ABI calls (pointers and descriptor fixed once), so that the host enqueues
             # faster than the GPU drains and the timed region measures the kernels, not Python.
             dref = ctypes.byref(d)
@@ -139,7 +143,7 @@ def build_ops(dw, wl, cfg, torch, order="layer", side=None, fused_bwd=False):
                 vname = dw.variant_name(d, 3)
                 # a fused kernel reads x and dy once and writes dx; without one the call runs the two passes
                 bbytes = (2 * layer.x_elems(cfg["N"]) + layer.y_elems(cfg["N"])) * esz if vname != "separate" else 2 * nbytes
-                b = dict(common, which=3, variant=vname, run=run_bwd, bytes=bbytes)
+                b = dict(common, which=3, variant=vname, run=run_bwd, bytes=bbytes, flops=2 * nflops)
                 if order == "layer":
                     ops += [f, b]
                 else:
@@ -206,19 +210,32 @@ def time_kernels(ops, steps, torch):
     return out, overhead
 
 
-def stored_traffic(workload, kernel_key):
-    """HBM bytes per launch of `kernel_key` from the committed rocprofv3 counter summary (FETCH_SIZE +
-    WRITE_SIZE, each scaled by a plain copy of known size), or None if that summary has no such line."""
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic_%s.txt" % workload)
-    try:
-        with open(path) as f:
-            for line in f:
-                tok = line.split()
-                if len(tok) >= 3 and tok[0] == "traffic" and tok[1] == kernel_key:
-                    return int(float(tok[2]))
-    except OSError:
-        pass
-    return None
+def stored_profile(workload, kernel_key):
+    """What the committed rocprofv3 summaries of this workload say about `kernel_key`: HBM bytes per launch
+    (FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy of known size) from profiles/hbm_traffic_<workload>.txt, and
+    the average duration inside the profiled steps from profiles/kernel_stats_<workload>.txt (lines
+    "traffic <key> <bytes>" and "instep <key> <launches> <avg us>"), with the commit that last changed each file so
+    that a summary older than the kernels is visible."""
+    import subprocess
+    root = os.path.dirname(os.path.abspath(__file__))
+    out = {"traffic": None, "traffic_file": None, "in_step_avg_us": None, "stats_file": None}
+    for kind, tag, field in (("hbm_traffic", "traffic", "traffic"), ("kernel_stats", "instep", "in_step_avg_us")):
+        rel = os.path.join("profiles", "%s_%s.txt" % (kind, workload))
+        try:
+            with open(os.path.join(root, rel)) as f:
+                for line in f:
+                    tok = line.split()
+                    if len(tok) >= 3 and tok[0] == tag and tok[1] == kernel_key:
+                        out[field] = int(float(tok[2])) if tag == "traffic" else float(tok[3])
+        except OSError:
+            continue
+        try:
+            h = subprocess.run(["git", "-C", root, "log", "-1", "--format=%h", "--", rel], capture_output=True,
+                               text=True, timeout=10).stdout.strip()
+        except (OSError, subprocess.SubprocessError):
+            h = ""
+        out["traffic_file" if tag == "traffic" else "stats_file"] = rel + ("@" + h if h else "")
+    return out
 
 
 def copy_ceiling(torch):
@@ -380,19 +397,56 @@ def main():
             if op["H"] <= 14: pl["tail_ms"] += ms * op["repeat"]
             if op["stride"] == 2: pl["stride2_ms"] += ms * op["repeat"]
             key = PASS_NAMES[op["which"]] + ":" + op["variant"]
-            v = by_variant.setdefault(key, {"ms": 0.0, "bytes": 0, "launches": 0})
+            v = by_variant.setdefault(key, {"ms": 0.0, "bytes": 0, "flops": 0, "launches": 0})
             v["ms"] += ms * op["repeat"]; v["bytes"] += op["bytes"] * op["repeat"]; v["launches"] += op["repeat"]
+            v["flops"] += op["flops"] * op["repeat"]
         out["kernel_ms_per_stack"] = {k: {kk: round(vv, 4) for kk, vv in v.items() if kk != "bytes"} |
                                       {"GBps": round(v["bytes"] / v["ms"] / 1e6, 1)} for k, v in per_layout.items()}
         dom_key = max(by_variant, key=lambda k: by_variant[k]["ms"])
         dom = by_variant[dom_key]
-        achieved = dom["bytes"] / dom["ms"] / 1e6   # GB/s
-        out["roofline"] = {"bound": "hbm", "kernel": dom_key, "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
-                           "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4),
-                           "traffic": stored_traffic(cfg["name"], dom_key),
-                           "launches_per_step": dom["launches"], "event_overhead_subtracted_ms": round(ev_overhead, 5),
-                           "avg_launch_ms": round(dom["ms"] / dom["launches"], 5),
-                           "algorithmic_bytes_per_launch": int(dom["bytes"] / dom["launches"])}
+        # The kernels of a step run back to back, and each lasts longer there than between two events (the event
+        # records leave a gap in which the previous kernel's write-back drains).  In-step duration = bracketed
+        # duration scaled by (wall time of a step) / (sum of all bracketed durations); the rocprofv3 kernel trace
+        # of the same command (profiles/kernel_stats_<workload>.txt) gives the same figure within a few per cent.
+        sum_bracketed = sum(ms * op["repeat"] for op, ms in zip(ops, kms))
+        stretch = max(1.0, ms_per_step / sum_bracketed) if not args.side_stream else 1.0
+        ms_in_step = dom["ms"] * stretch
+        hbm_in_step = dom["bytes"] / ms_in_step / 1e6                    # GB/s
+        hbm_bracketed = dom["bytes"] / dom["ms"] / 1e6
+        alu_in_step = dom["flops"] / ms_in_step / 1e9                    # TFLOP/s
+        ai = dom["flops"] / dom["bytes"]
+        # which roofline binds: the one whose peak gives the longer minimum time for this kernel's bytes and flops
+        alu_binds = dom["flops"] / (PEAK_ALU_TFLOPS * 1e12) > dom["bytes"] / (PEAK_HBM_GBS * 1e9)
+        prof = stored_profile(cfg["name"], dom_key)
+        roof = {"bound": "alu" if alu_binds else "hbm", "kernel": dom_key,
+                "achieved": round(alu_in_step if alu_binds else hbm_in_step, 1),
+                "peak": PEAK_ALU_TFLOPS if alu_binds else PEAK_HBM_GBS, "unit": "TFLOP/s" if alu_binds else "GB/s",
+                "frac": round(alu_in_step / PEAK_ALU_TFLOPS if alu_binds else hbm_in_step / PEAK_HBM_GBS, 4),
+                "frac_is": "in-step: event-bracketed launch time x (step wall time / sum of bracketed times)",
+                "frac_bracketed": round(hbm_bracketed / PEAK_HBM_GBS, 4),
+                "in_step_stretch": round(stretch, 4),
+                "traffic": prof["traffic"], "traffic_from": prof["traffic_file"],
+                "launches_per_step": dom["launches"], "event_overhead_subtracted_ms": round(ev_overhead, 5),
+                "avg_launch_ms": round(ms_in_step / dom["launches"], 5),
+                "avg_launch_ms_bracketed": round(dom["ms"] / dom["launches"], 5),
+                "algorithmic_bytes_per_launch": int(dom["bytes"] / dom["launches"]),
+                "algorithmic_flops_per_launch": int(dom["flops"] / dom["launches"]),
+                "flop_per_byte": round(ai, 2)}
+        if prof["in_step_avg_us"]:
+            # the same fraction from the committed kernel trace (average duration of this kernel inside the steps)
+            roof["frac_profile"] = round(dom["bytes"] / dom["launches"] / (prof["in_step_avg_us"] * 1e-6) / 1e9 / PEAK_HBM_GBS, 4)
+            roof["profile_from"] = prof["stats_file"]
+        if ai > 10.0:
+            # near the ridge (157.3 TFLOP/s / 8 TB/s = 19.7 flop/B): both fractions
+            roof["frac_hbm"] = round(hbm_in_step / PEAK_HBM_GBS, 4)
+            roof["frac_alu"] = round(alu_in_step / PEAK_ALU_TFLOPS, 4)
+        out["roofline"] = roof
+        # every kernel family of the step, against both rooflines (in-step durations)
+        out["per_kernel"] = {k: {"launches": v["launches"], "in_step_ms": round(v["ms"] * stretch, 4),
+                                 "frac_hbm": round(v["bytes"] / (v["ms"] * stretch) / 1e6 / PEAK_HBM_GBS, 4),
+                                 "frac_alu": round(v["flops"] / (v["ms"] * stretch) / 1e9 / PEAK_ALU_TFLOPS, 4),
+                                 "flop_per_byte": round(v["flops"] / v["bytes"], 2)}
+                             for k, v in sorted(by_variant.items(), key=lambda kv: -kv[1]["ms"])}
         if args.report:
             print("%-34s %-5s %-10s %-28s %9s %9s %7s" % ("layer", "lay", "pass", "variant", "ms", "GB/s", "%peak"),
                   file=sys.stderr)

@@ -22,6 +22,57 @@ import json
 import sys
 
 
+class DenseRoute:
+    """The refactorised layer of Section III for one group size S, on NCHW fp32 device tensors.
+
+    Eq. 1: the S filters of a group sit on the block diagonal of an S x (S*K*K) matrix; Eq. 2: the 0/1 mask of the
+    same shape; forward = im2col (Section II) and one batched GEMM per group; backward = the two transposed GEMMs,
+    col2im, and the mask of Eq. 4 on the dense weight gradient."""
+
+    def __init__(self, w, N, C, H, W, K, stride, pad, S):
+        import torch
+        assert C % S == 0
+        self.N, self.C, self.H, self.W, self.K, self.s, self.p, self.S, self.G = N, C, H, W, K, stride, pad, S, C // S
+        self.Ho, self.Wo = (H + 2 * pad - K) // stride + 1, (W + 2 * pad - K) // stride + 1
+        G, KK = self.G, K * K
+        self.What = torch.zeros(G, S, S * KK, device=w.device)
+        self.A = torch.zeros(S, S * KK, device=w.device)
+        wv = w.reshape(G, S, KK)
+        for i in range(S):
+            self.What[:, i, i * KK:(i + 1) * KK] = wv[:, i]
+            self.A[i, i * KK:(i + 1) * KK] = 1.0
+        self.cols = None
+
+    def fwd(self, x):
+        import torch
+        import torch.nn.functional as F
+        N, G, S, K = self.N, self.G, self.S, self.K
+        L = self.Ho * self.Wo
+        self.cols = F.unfold(x.view(N * G, S, self.H, self.W), K, padding=self.p, stride=self.s).view(N, G, S * K * K, L)
+        return torch.matmul(self.What.unsqueeze(0), self.cols).view(N, self.C, self.Ho, self.Wo)
+
+    def bwd(self, dy):
+        """Input gradient [N,C,H,W] and the masked dense weight gradient [G,S,S*K*K] (needs the im2col matrix that
+        fwd left behind, as a training step has it)."""
+        import torch
+        import torch.nn.functional as F
+        N, G, S, K = self.N, self.G, self.S, self.K
+        L = self.Ho * self.Wo
+        dz = dy.view(N, G, S, L)
+        dcols = torch.matmul(self.What.transpose(1, 2).unsqueeze(0), dz)
+        gx = F.fold(dcols.view(N * G, S * K * K, L), (self.H, self.W), K, padding=self.p, stride=self.s)
+        gw = torch.matmul(dz, self.cols.transpose(2, 3)).sum(0) * self.A.unsqueeze(0)        # Eq. 4
+        return gx.view(N, self.C, self.H, self.W), gw
+
+    def filter_gradient(self, gw):
+        """The per-channel filter gradient [C,K,K]: the diagonal blocks of the masked dense gradient."""
+        import torch
+        G, S, KK = self.G, self.S, self.K * self.K
+        blocks = gw.view(G, S, S, KK)
+        idx = torch.arange(S, device=gw.device)
+        return blocks[:, idx, idx, :].reshape(self.C, self.K, self.K)
+
+
 def _time(fn, torch, iters):
     fn(); fn()
     torch.cuda.synchronize()
@@ -41,7 +92,6 @@ def main():
     ap.add_argument("--iters", type=int, default=5)
     args = ap.parse_args()
     import torch
-    import torch.nn.functional as F
     import paper_1803_09926_amd as dw
     from paper_1803_09926_amd import workloads as wl
     if not torch.cuda.is_available():
@@ -67,29 +117,9 @@ def main():
             if C % S != 0:
                 cells.append("%-22s" % "-")
                 continue
-            G = C // S
-            # Eq. 1: the S filters of a group on the block diagonal of an S x (S*K*K) matrix; Eq. 2: the mask
-            What = torch.zeros(G, S, S * K * K, device="cuda")
-            A = torch.zeros(S, S * K * K, device="cuda")
-            wv = w.view(G, S, K * K)
-            for i in range(S):
-                What[:, i, i * K * K:(i + 1) * K * K] = wv[:, i]
-                A[i, i * K * K:(i + 1) * K * K] = 1.0
-            cols_keep = {}
-
-            def fwd():
-                cols = F.unfold(x.view(N * G, S, H, W), K, padding=p, stride=s).view(N, G, S * K * K, L)
-                cols_keep["c"] = cols
-                return torch.matmul(What.unsqueeze(0), cols).view(N, C, Ho, Wo)
-
-            def bwd():
-                cols = cols_keep["c"]
-                dz = dy.view(N, G, S, L)
-                dcols = torch.matmul(What.transpose(1, 2).unsqueeze(0), dz)
-                gx = F.fold(dcols.view(N * G, S * K * K, L), (H, W), K, padding=p, stride=s).view(N, C, H, W)
-                gw = (torch.matmul(dz, cols.transpose(2, 3)).sum(0) * A.unsqueeze(0))        # Eq. 4
-                return gx, gw
-
+            route = DenseRoute(w, N, C, H, W, K, s, p, S)
+            fwd = lambda: route.fwd(x)
+            bwd = lambda: route.bwd(dy)
             z = fwd()
             dw.fwd(d, x, w, y)
             torch.cuda.synchronize()
@@ -104,8 +134,7 @@ def main():
             tot.setdefault("dense_fwd_S%d" % S, 0.0); tot.setdefault("dense_bwd_S%d" % S, 0.0)
             tot["dense_fwd_S%d" % S] += td_f; tot["dense_bwd_S%d" % S] += td_b
             cells.append("%8.3f / %-11.3f" % (td_f, td_b))
-            del What, A, z, gx, gw
-            cols_keep.clear()
+            del route, z, gx, gw
             torch.cuda.empty_cache()
         print("%-28s %9.4f %9.4f | %s" % (layer.name[10:], t_f, t_b, "  ".join(cells)), flush=True)
     print(json.dumps({"batch": N, "unit": "ms, sum over the 13 layers (a dense total covers only the layers whose "

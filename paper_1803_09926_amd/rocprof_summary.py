@@ -1,7 +1,7 @@
 """Turn rocprofv3 CSV output of `bench.py` into the short text summaries kept under profiles/.
 
 Usage:
-  python -m paper_1803_09926_amd.rocprof_summary stats   <dir with *_kernel_stats.csv>
+  python -m paper_1803_09926_amd.rocprof_summary stats   <dir with *_kernel_stats.csv> [workload index of bench.py --config]
   python -m paper_1803_09926_amd.rocprof_summary traffic <FETCH_SIZE dir> <WRITE_SIZE dir>
 
 `traffic` expects both runs to contain bench.py's --calibrate-copy dispatches (a plain device copy
@@ -78,7 +78,7 @@ def short(name):
     return name.replace("void dwc::", "").replace("dwc::", "")
 
 
-def stats(d):
+def stats(d, config=None):
     rows = list(csv.DictReader(open(_one(os.path.join(d, "*kernel_stats.csv")))))
     rows = [r for r in rows if "dwc::" in r["Name"]]
     total = sum(int(r["TotalDurationNs"]) for r in rows)
@@ -88,6 +88,63 @@ def stats(d):
             short(r["Name"])[:64], int(r["Calls"]), int(r["TotalDurationNs"]) / 1e3, float(r["AverageNs"]) / 1e3,
             int(r["MinNs"]) / 1e3, int(r["MaxNs"]) / 1e3, 100.0 * int(r["TotalDurationNs"]) / total))
     print("sum over the library's kernels: %.1f us" % (total / 1e3))
+    # bench.py's keys: launches and average duration inside the profiled steps of the kernel(s) behind each key
+    print("# bench.py keys: instep <pass:variant> <dispatches> <average us per dispatch, inside the profiled steps>")
+    per_key = {}
+    for key, pats in VARIANT_KERNELS.items():
+        ks = [r for r in rows if any(re.search(p, short(r["Name"])) for p in pats)]
+        if not ks:
+            continue
+        calls = sum(int(r["Calls"]) for r in ks)
+        tot = sum(int(r["TotalDurationNs"]) for r in ks) / 1e3
+        per_key[key] = (calls, tot)
+        print("instep %s %d %.2f" % (key, calls, tot / calls))
+    if config is None:
+        return
+    # per layout and pass: time per step from the trace against the algorithmic bytes of the workload
+    import paper_1803_09926_amd as dw
+    from paper_1803_09926_amd import workloads as wl
+    cfg = wl.config(config)
+    esz = 4 if cfg["dtype"] == wl.F32 else 2
+    launches, nbytes = {}, {}
+    for layout in cfg["layouts"]:
+        for layer, repeat in cfg["layers"]:
+            if layer.cg > 1:
+                d = dw.group_desc(cfg["N"], layer.C, layer.H, layer.W, layer.K, layer.stride, layer.pad, layer.groups,
+                                  layer.O, layout, cfg["dtype"])
+                vname = dw.gconv_variant_name
+            else:
+                d = dw.desc(cfg["N"], layer.C, layer.H, layer.W, layer.K, layer.stride, layer.pad, layer.mult, layout, cfg["dtype"])
+                vname = dw.variant_name
+            for which, pname in enumerate(("fwd", "bwd_data", "bwd_filter")):
+                key = pname + ":" + vname(d, which)
+                launches[key] = launches.get(key, 0) + repeat
+                nbytes[key] = nbytes.get(key, 0) + repeat * layer.pass_bytes(cfg["N"], esz)
+    missing = [k for k in launches if k not in per_key]
+    if missing:
+        print("# keys of the workload with no kernel in the trace: " + ", ".join(missing))
+    known = [k for k in launches if k in per_key]
+    steps = sorted(per_key[k][0] / launches[k] for k in known)[len(known) // 2]
+    red = [r for r in rows if "k_reduce_partials" in r["Name"]]
+    red_us = sum(int(r["TotalDurationNs"]) for r in red) / 1e3
+    nfilter = sum(v for k, v in launches.items() if k.startswith("bwd_filter:"))
+    print("# workload %s: %.0f steps in the trace; per layout and pass, per step: kernel time, algorithmic bytes, rate" % (cfg["name"], steps))
+    print("# (bwd_filter = stage 1 + its share of the stage-2 launches k_reduce_partials, split by launch count)")
+    print("%-6s %-11s %10s %12s %9s %7s" % ("layout", "pass", "us/step", "MB/step", "GB/s", "%peak"))
+    grand_us = grand_b = 0.0
+    for lay in ("nchw", "nhwc"):
+        for pname in ("fwd", "bwd_data", "bwd_filter"):
+            ks = [k for k in known if k.startswith(pname + ":") and ("_" + lay + "_" in "_" + k.split(":")[1] + "_")]
+            if not ks:
+                continue
+            us = sum(per_key[k][1] for k in ks) / steps
+            if pname == "bwd_filter" and nfilter:
+                us += red_us / steps * sum(launches[k] for k in ks) / nfilter
+            b = sum(nbytes[k] for k in ks)
+            grand_us += us; grand_b += b
+            print("pass %-6s %-11s %10.1f %12.1f %9.1f %7.2f" % (lay, pname, us, b / 1e6, b / us / 1e3, b / us / 1e3 / 80.0))
+    if grand_us:
+        print("pass %-6s %-11s %10.1f %12.1f %9.1f %7.2f" % ("all", "all", grand_us, grand_b / 1e6, grand_b / grand_us / 1e3, grand_b / grand_us / 1e3 / 80.0))
 
 
 def _counter(d, cname):
@@ -127,7 +184,7 @@ def traffic(dfetch, dwrite):
 
 if __name__ == "__main__":
     if len(sys.argv) >= 3 and sys.argv[1] == "stats":
-        stats(sys.argv[2])
+        stats(sys.argv[2], int(sys.argv[3]) if len(sys.argv) >= 4 else None)
     elif len(sys.argv) >= 4 and sys.argv[1] == "traffic":
         traffic(sys.argv[2], sys.argv[3])
     else:

@@ -81,6 +81,14 @@ AWKWARD = [
     (2, Layer("lines_k5_h12_w112", 2, 12, 112, 5, 1, 2)),
     (3, Layer("tall", 8, 70, 12)),
     (3, Layer("wide", 8, 6, 300)),
+    # NHWC multiplier 2 with O % 8 == 4 (bf16 takes four channels per lane); small planes that are not square;
+    # a stride-2 small plane of 6 x 8
+    (2, Layer("m2_c6", 6, 12, 12, 3, 1, 1, 2)),
+    (3, Layer("small_h20_w14", 8, 20, 14)),
+    (3, Layer("small_h9_w7", 8, 9, 7)),
+    (3, Layer("small_h6_w8_s2", 8, 6, 8, 3, 2, 1)),
+    (3, Layer("small_h10_w14_s2", 8, 10, 14, 3, 2, 1)),
+    (2, Layer("small_k5_h9_w14", 8, 9, 14, 5, 1, 2)),
 ]
 
 
@@ -158,6 +166,21 @@ def test_tensors_just_under_the_element_limit(gpu_lib, layout):
     assert layer.x_elems(64) < 2 ** 31 <= layer.x_elems(64) + 64 * 724 * 724
     print("near-max", layout, flush=True)
     _sampled_check(layer, 64, layout, wl.F32, seed=4242 + layout)
+
+
+@pytest.mark.parametrize("name,N,layer", [
+    ("stride2", 64, Layer("near_max_c64_h724_s2", 64, 724, 724, 3, 2, 1)),
+    ("small_planes", 5461, Layer("near_max_c2000_h14", 2000, 14, 14)),
+    ("small_planes_s2", 5461, Layer("near_max_c2000_h14_s2", 2000, 14, 14, 3, 2, 1)),
+    ("generic_k2", 64, Layer("near_max_c64_h724_k2", 64, 724, 724, 2, 1, 0)),
+], ids=["stride2", "small_planes", "small_planes_s2", "generic_k2"])
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_other_kernel_families_just_under_the_element_limit(gpu_lib, layout, name, N, layer):
+    """The stride-2 walks, the small-plane kernels and the generic kernels with their 32-bit indices at their
+    largest (x has 2.14e9 elements); oracle on sampled images / channels."""
+    assert 2 ** 31 - 2 ** 24 < layer.x_elems(N) < 2 ** 31
+    print("near-max", name, layout, flush=True)
+    _sampled_check(layer, N, layout, wl.F32, seed=4300 + layout)
 
 
 def test_bwd_filter_is_bit_reproducible(gpu_lib):
