@@ -210,6 +210,51 @@ __device__ __forceinline__ float wave_sum_strided(float v, int lo_stride)
     return v;
 }
 
+// Block-wide fixed-order sum of K*K*V per-lane partial sums (the end of a filter-gradient walk in the
+// NHWC mapping: a block of 4 wavefronts, lane tx + j*CT of every wavefront owns channel vector tx).
+// For each value: butterfly over the lanes of a wavefront that own the same channels, then the
+// wavefronts 1..3 park their sums in LDS and wavefront 0 adds (w0 + w1) + (w2 + w3) and hands the
+// total of tap (kh, kw), channel v to `emit(kh, kw, v, total)` on its lanes below CT.  The values go
+// through LDS in chunks of CH, one barrier pair per chunk instead of one per tap: the per-tap form
+// cost a block of a 5x5 layer fifty barriers, several microseconds that short walks never won back.
+constexpr int reduce_chunk(int nacc)
+{
+    int ch = nacc < 36 ? nacc : 36;
+    while (nacc % ch) --ch;
+    return ch;
+}
+template <int K, int V, typename F>
+__device__ __forceinline__ void block_reduce_taps(const float (&acc)[K][K][V], int CT, float *lds, F emit)
+{
+    constexpr int NACC = K * K * V, CH = reduce_chunk(NACC);
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    float (*red)[CH][64] = reinterpret_cast<float (*)[CH][64]>(lds);       // [3][CH][64]
+#pragma unroll
+    for (int c0 = 0; c0 < NACC; c0 += CH) {
+        float s[CH];
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int e = c0 + i, v = e % V, kw = (e / V) % K, kh = e / (V * K);
+            s[i] = wave_sum_strided(acc[kh][kw][v], CT);
+        }
+        if (wv > 0) {
+#pragma unroll
+            for (int i = 0; i < CH; ++i) red[wv - 1][i][lane] = s[i];
+        }
+        __syncthreads();
+        if (wv == 0 && lane < CT) {
+#pragma unroll
+            for (int i = 0; i < CH; ++i) {
+                const int e = c0 + i, v = e % V, kw = (e / V) % K, kh = e / (V * K);
+                emit(kh, kw, v, (s[i] + red[0][i][lane]) + (red[1][i][lane] + red[2][i][lane]));
+            }
+        }
+        if (c0 + CH < NACC) __syncthreads();
+    }
+}
+// floats of LDS that block_reduce_taps needs
+template <int K, int V> struct ReduceLds { static constexpr int FLOATS = 3 * reduce_chunk(K * K * V) * 64; };
+
 // The dispatcher launches workgroups round-robin over the 8 XCDs (each with its own L2).
 // This maps the hardware block id to a logical one so that each XCD walks a contiguous range
 // of logical ids: blocks that share halo rows then share an L2 and run close in time.

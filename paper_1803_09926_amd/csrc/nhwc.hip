@@ -505,7 +505,7 @@ __global__ __launch_bounds__(256, (PF <= 2 && K == 3 && S == 1 && sizeof(T) == 4
                                                          int TH, int nstrips, int NI, unsigned nblocks)
 {
     constexpr int P = (K - 1) / 2;   // also the pad for S == 2, K == 3
-    __shared__ float red[4][V][64];
+    __shared__ float red[ReduceLds<K, V>::FLOATS];
     unsigned lb = xcd_remap(blockIdx.x, nblocks);
     const int strip = lb % nstrips; lb /= nstrips;
     const int owtile = lb % nowtiles; lb /= nowtiles;
@@ -693,30 +693,12 @@ __global__ __launch_bounds__(256, (PF <= 2 && K == 3 && S == 1 && sizeof(T) == 4
             }
     }
 
-    // ---- fixed-order block reduction, one tap at a time ----
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    // ---- fixed-order block reduction ----
     const int part = (ngroup * nstrips + strip) * nowtiles + owtile;
     float *wsp = ws + (size_t)part * (K * K * g.O);
-#pragma unroll
-    for (int kh = 0; kh < K; ++kh)
-#pragma unroll
-        for (int kw = 0; kw < K; ++kw) {
-#pragma unroll
-            for (int v = 0; v < V; ++v) {
-                float s = wave_sum_strided(acc[kh][kw][v], CT);
-                red[wv][v][lane] = s;
-            }
-            __syncthreads();
-            if (wv == 0 && lane < CT && cq < Q) {
-                float o[V];
-#pragma unroll
-                for (int v = 0; v < V; ++v)
-                    o[v] = (red[0][v][lane] + red[1][v][lane]) + (red[2][v][lane] + red[3][v][lane]);
-#pragma unroll
-                for (int v = 0; v < V; ++v) wsp[(kh * K + kw) * g.O + cq * V + v] = o[v];
-            }
-            __syncthreads();
-        }
+    block_reduce_taps<K, V>(acc, CT, red, [&](int kh, int kw, int v, float total) {
+        if (cq < Q) wsp[(kh * K + kw) * g.O + cq * V + v] = total;
+    });
 }
 
 // ---- host side --------------------------------------------------------------------------------

@@ -25,7 +25,7 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_fused_k3s1(Geom g, const T *__
                                                              int TH, int nstrips, int NI, unsigned nblocks, int nt)
 {
     constexpr int K = 3, R = PF + 1;
-    __shared__ float red[4][V][64];
+    __shared__ float red[ReduceLds<K, V>::FLOATS];
     unsigned lb = xcd_remap(blockIdx.x, nblocks);
     const int strip = lb % nstrips; lb /= nstrips;
     const int owtile = lb % nowtiles; lb /= nowtiles;
@@ -155,30 +155,12 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_fused_k3s1(Geom g, const T *__
             }
     }
 
-    // ---- fixed-order block reduction, one tap at a time (as in the filter-gradient kernel) ----
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    // ---- fixed-order block reduction (as in the filter-gradient kernel) ----
     const int part = (ngroup * nstrips + strip) * nowtiles + owtile;
     float *wsp = ws + (size_t)part * (K * K * g.C);
-#pragma unroll
-    for (int kh = 0; kh < K; ++kh)
-#pragma unroll
-        for (int kw = 0; kw < K; ++kw) {
-#pragma unroll
-            for (int v = 0; v < V; ++v) {
-                float s = wave_sum_strided(acc[kh][kw][v], CT);
-                red[wv][v][lane] = s;
-            }
-            __syncthreads();
-            if (wv == 0 && lane < CT && cq < Q) {
-                float o[V];
-#pragma unroll
-                for (int v = 0; v < V; ++v)
-                    o[v] = (red[0][v][lane] + red[1][v][lane]) + (red[2][v][lane] + red[3][v][lane]);
-#pragma unroll
-                for (int v = 0; v < V; ++v) wsp[(kh * K + kw) * g.C + cq * V + v] = o[v];
-            }
-            __syncthreads();
-        }
+    block_reduce_taps<K, V>(acc, CT, red, [&](int kh, int kw, int v, float total) {
+        if (cq < Q) wsp[(kh * K + kw) * g.C + cq * V + v] = total;
+    });
 }
 
 bool nhwc_bwd_fused_supported(const Geom &g, int dtype, int V)
