@@ -57,7 +57,9 @@ enum dwconv_status {
     DWCONV_ERR_ALIGN = -5,       /* a data pointer is not 16-byte aligned                         */
     DWCONV_ERR_UNSUPPORTED = -6, /* K > DWCONV_MAX_K                                              */
     DWCONV_ERR_LAUNCH = -7,      /* HIP reported an error when the kernel was launched            */
-    DWCONV_ERR_TOO_LARGE = -8    /* a tensor has 2^31 or more elements (kernels index in 32 bit)  */
+    DWCONV_ERR_TOO_LARGE = -8,   /* a tensor has 2^31 or more elements (kernels index in 32 bit)  */
+    DWCONV_ERR_SCRATCH = -9      /* dwconv_bwd_filter_noalloc: the shape needs more scratch than   */
+                                 /* DWCONV_NOALLOC_SCRATCH_BYTES                                    */
 };
 
 #define DWCONV_MAX_K 15
@@ -110,6 +112,20 @@ int dwconv_bwd_data(const dwconv_desc *desc, const void *dy, const void *w, void
  * partials in a fixed order.  The result is bit-identical from run to run. */
 int dwconv_bwd_filter(const dwconv_desc *desc, const void *x, const void *dy, void *dw,
                       void *workspace, size_t workspace_bytes, void *stream);
+
+/* dwconv_bwd_filter for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results (bit for bit) and
+ * error codes as dwconv_bwd_filter, without the workspace: the partial sums go to an array of
+ * DWCONV_NOALLOC_SCRATCH_BYTES that is part of the library's device code (each GPU the library runs
+ * on holds one copy until the process ends).  A shape whose partial sums need more (see
+ * dwconv_bwd_filter_workspace_bytes; every layer of the benchmark workloads needs less than 9 MB)
+ * returns DWCONV_ERR_SCRATCH and enqueues nothing.  The call allocates and frees nothing and
+ * does not synchronise.  The device of `stream` must be the current device.  All calls on one
+ * GPU share the one array: two calls that may overlap on that GPU (different streams, or
+ * different threads) race; calls on one stream are ordered and safe.  Contents left by an earlier
+ * call are never read. */
+#define DWCONV_NOALLOC_SCRATCH_BYTES (16u << 20)
+int dwconv_bwd_filter_noalloc(const dwconv_desc *desc, const void *x, const void *dy, void *dw, void *stream);
 
 /* Whole backward pass of the layer in one call: dx as dwconv_bwd_data, dw as dwconv_bwd_filter
  * (Section III-A, backward propagation: both gradients come from the same dy; the paper's

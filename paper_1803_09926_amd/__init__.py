@@ -23,7 +23,7 @@ _lib = None
 
 EXPORTS = ("dwconv_out_dims", "dwconv_bwd_filter_workspace_bytes", "dwconv_fwd", "dwconv_bwd_data",
            "dwconv_bwd_filter", "dwconv_bwd_workspace_bytes", "dwconv_bwd", "dwconv_status_string",
-           "dwconv_variant_name", "dwconv_tuning_reload",
+           "dwconv_variant_name", "dwconv_tuning_reload", "dwconv_bwd_filter_noalloc",
            "gconv_out_dims", "gconv_bwd_filter_workspace_bytes", "gconv_fwd", "gconv_bwd_data", "gconv_bwd_filter",
            "gconv_variant_name")
 
@@ -65,6 +65,7 @@ def load():
     lib.dwconv_bwd.argtypes = [P, VP, VP, VP, VP, VP, VP, ctypes.c_size_t, VP]; lib.dwconv_bwd.restype = ctypes.c_int
     lib.dwconv_status_string.argtypes = [ctypes.c_int]; lib.dwconv_status_string.restype = ctypes.c_char_p
     lib.dwconv_variant_name.argtypes = [P, ctypes.c_int]; lib.dwconv_variant_name.restype = ctypes.c_char_p
+    lib.dwconv_bwd_filter_noalloc.argtypes = [P, VP, VP, VP, VP]; lib.dwconv_bwd_filter_noalloc.restype = ctypes.c_int
     lib.dwconv_tuning_reload.argtypes = []; lib.dwconv_tuning_reload.restype = ctypes.c_int
     G = ctypes.POINTER(GroupDesc)
     lib.gconv_out_dims.argtypes = [G, I32P, I32P]; lib.gconv_out_dims.restype = ctypes.c_int
@@ -191,6 +192,17 @@ def bwd_filter(d: Desc, x, dy, dw, workspace, stream=None):
                                   ctypes.c_size_t(nbytes), _stream(stream))
     if rc != 0:
         raise DwconvError(rc, "dwconv_bwd_filter")
+    return dw
+
+
+def bwd_filter_noalloc(d: Desc, x, dy, dw, stream=None):
+    """Enqueue dw = filter gradient (fp32) through the entry point that allocates nothing and takes no workspace
+    (the partial sums go to a fixed array inside the library; shapes that need more raise DWCONV_ERR_SCRATCH)."""
+    nx, ny, nw = _sizes(d)
+    _check_tensor(x, "x", d, nx); _check_tensor(dy, "dy", d, ny); _check_tensor(dw, "dw", d, nw, fp32_always=True)
+    rc = load().dwconv_bwd_filter_noalloc(ctypes.byref(d), _ptr(x), _ptr(dy), _ptr(dw), _stream(stream))
+    if rc != 0:
+        raise DwconvError(rc, "dwconv_bwd_filter_noalloc")
     return dw
 
 

@@ -6,7 +6,8 @@
 
 using namespace dwc;
 
-static int validate(const dwconv_desc *d, Geom *g)
+namespace dwc {
+int validate_desc(const dwconv_desc *d, Geom *g)
 {
     if (!d) return DWCONV_ERR_NULL;
     if (d->layout != DWCONV_NCHW && d->layout != DWCONV_NHWC) return DWCONV_ERR_BAD_ENUM;
@@ -31,6 +32,9 @@ static int validate(const dwconv_desc *d, Geom *g)
     }
     return DWCONV_OK;
 }
+}  // namespace dwc
+
+static inline int validate(const dwconv_desc *d, Geom *g) { return validate_desc(d, g); }
 
 static inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
@@ -108,6 +112,7 @@ const char *dwconv_status_string(int status)
     case DWCONV_ERR_UNSUPPORTED: return "unsupported (K larger than DWCONV_MAX_K)";
     case DWCONV_ERR_LAUNCH: return "HIP kernel launch failed";
     case DWCONV_ERR_TOO_LARGE: return "tensor has 2^31 or more elements";
+    case DWCONV_ERR_SCRATCH: return "shape needs more scratch than the library's static buffer holds (use dwconv_bwd_filter with a workspace)";
     default: return "unknown status";
     }
 }

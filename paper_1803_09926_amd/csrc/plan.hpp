@@ -1,6 +1,7 @@
 // Kernel-variant selection.  A Plan is computed on the host from the geometry alone, so the
 // workspace query and the launch always agree.
 #pragma once
+#include "../../include/dwconv.h"
 #include "kernels.hpp"
 
 namespace dwc {
@@ -30,6 +31,9 @@ struct Plan {
     int a, b, c;       // variant-specific launch parameters
     const char *name;
 };
+
+// Checks a descriptor on the host (no HIP call) and fills the geometry; returns a dwconv_status.
+int validate_desc(const dwconv_desc *d, Geom *g);
 
 Plan plan_fwd(const Geom &g, int layout, int dtype);
 Plan plan_bwd_data(const Geom &g, int layout, int dtype);
