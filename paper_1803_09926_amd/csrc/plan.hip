@@ -47,7 +47,8 @@ static int nhwc_pf(const Geom &g, int dtype)
 // closer together in memory.
 static int pick_th(int rows, int stride, int dflt1 = 14)
 {
-    const int target = stride == 1 ? tune("DWCONV_TUNE_TH1", dflt1) : tune("DWCONV_TUNE_TH2", 7);
+    // stride 2: 7 output rows, 4 on tall maps (56 output rows and more: 1-4 % on the 112x112 and 56x56 layers)
+    const int target = stride == 1 ? tune("DWCONV_TUNE_TH1", dflt1) : tune("DWCONV_TUNE_TH2", rows >= 56 ? 4 : 7);
     // balanced strips: the number of strips that brings their height closest to the target, then equal
     // heights (19 rows are one strip of 19, not 14 + 5; 37 rows are 13 + 13 + 11)
     int nstrips = (rows + target / 2) / target;
@@ -73,12 +74,20 @@ static int nchw_pick_tr(const Geom &g, bool (*fits)(const Geom &, int))
 }
 static bool fits_bwd_filter(const Geom &g, int tr) { return nchw_bwd_filter_parts(g, tr, 1) > 0; }
 
-// Small-plane NCHW kernels: rows of 7 or 14 always; rows of 28 when the row-walk kernels cannot take
-// the shape (bf16 rows that are not whole 16-byte vectors) or when asked for (tuning switch).
+// Small-plane NCHW kernels: rows of up to 14 always, and whenever the row walk cannot take the shape (bf16 rows that
+// are not whole 16-byte vectors).  Rows of 28, where both families apply, go to whichever measured faster inside the
+// benchmark step: the filter gradient always to the small-plane kernel (37 against 46 us on the 28x28x256 layer at
+// batch 128, 23 against 29 us on its stride-2 sibling), the fp32 forward at stride 1 and the fp32 input gradient at
+// stride 2 too (42 against 47 us, 21 against 22 us); the stride-1 input gradient and everything else in bf16 stay
+// with the row walk.
 static bool use_small(const Geom &g, int dtype, int pass)
 {
     if (!nchws_supported(g, pass)) return false;
-    return g.W <= 14 || tune("DWCONV_TUNE_S28", 0) == 1 || nchwd_vec(g, dtype, pass) == 0;
+    if (g.W <= 14 || nchwd_vec(g, dtype, pass) == 0) return true;
+    if (const char *e = tune_env("DWCONV_TUNE_S28")) return atoi(e) == 1;
+    if (pass == 2) return true;
+    if (dtype != DT_F32) return false;
+    return (pass == 0 && g.s == 1) || (pass == 1 && g.s == 2);
 }
 
 Plan plan_fwd(const Geom &g, int layout, int dtype)
@@ -148,45 +157,51 @@ Plan plan_bwd_data(const Geom &g, int layout, int dtype)
     return pl;
 }
 
+// NCHW filter gradient on the small-plane kernels / on the row walk; false if the family does not take the shape.
+static bool plan_bwd_filter_nchws(const Geom &g, int dtype, Plan &pl)
+{
+    int U, NI, parts;
+    nchws_bwd_filter_tiling(g, dtype, &U, &NI, &parts);
+    NI = tune("DWCONV_TUNE_NI", NI);
+    if (NI > g.N) NI = g.N;
+    parts = ceil_div(g.N, NI);
+    if ((long long)parts * g.O * g.K * g.K * 4 > (64ll << 20)) return false;
+    pl.variant = V_NCHWS_BWD_FILTER; pl.a = U; pl.b = 0; pl.c = NI; pl.parts = parts;
+    pl.name = g.K == 5 ? "nchw_smallplane_bwd_filter_k5s1"
+                       : (g.s == 1 ? "nchw_smallplane_bwd_filter_k3s1" : "nchw_smallplane_bwd_filter_k3s2");
+    return true;
+}
+
+static bool plan_bwd_filter_nchwd(const Geom &g, int dtype, Plan &pl)
+{
+    const int V = nchwd_vec(g, dtype, 2);
+    if (!V) return false;
+    // strip height (measured on the benchmark layers): stride 2 wants short strips of 7 output rows,
+    // fp32 stride 1 on large planes 14 rows, everything else whole planes up to 56 rows
+    int TH = g.s == 2 && g.Ho >= 28 ? 7
+             : (g.s == 1 && dtype == DT_F32 && g.Ho >= 56 ? 14 : (g.Ho > 56 ? (g.Ho + 1) / 2 : g.Ho));
+    TH = tune("DWCONV_TUNE_THW", tune("DWCONV_TUNE_TH", TH));
+    int lg, nst, rounds, parts;
+    nchwd_bwd_filter_tiling(g, V, TH, &lg, &nst, &rounds, &parts);
+    // small batches: shorter strips until the launch has about two blocks per CU (one block = one
+    // channel x a group of (image, strip) items)
+    while (TH > 7 && parts >= 1 && (long long)parts * g.O < 512 && !tune_env("DWCONV_TUNE_THW") && !tune_env("DWCONV_TUNE_TH")) {
+        TH = (TH + 1) / 2;
+        nchwd_bwd_filter_tiling(g, V, TH, &lg, &nst, &rounds, &parts);
+    }
+    if (!(lg >= 1 && parts >= 1 && (long long)parts * g.O * g.K * g.K * 4 <= (64ll << 20))) return false;
+    pl.variant = V_NCHWD_BWD_FILTER; pl.a = V; pl.b = TH; pl.c = 0; pl.parts = parts;
+    pl.name = g.K == 5 ? "nchw_rowwalk_bwd_filter_k5s1"
+                       : (g.s == 1 ? "nchw_rowwalk_bwd_filter_k3s1" : "nchw_rowwalk_bwd_filter_k3s2");
+    return true;
+}
+
 Plan plan_bwd_filter(const Geom &g, int layout, int dtype)
 {
     Plan pl = {V_GENERIC, generic_bwd_filter_parts(g), 0, 0, 0, "generic"};
     if (layout == LAYOUT_NCHW) {
-        if (use_small(g, dtype, 2)) {
-            int U, NI, parts;
-            nchws_bwd_filter_tiling(g, dtype, &U, &NI, &parts);
-            NI = tune("DWCONV_TUNE_NI", NI);
-            if (NI > g.N) NI = g.N;
-            parts = ceil_div(g.N, NI);
-            if ((long long)parts * g.O * g.K * g.K * 4 <= (64ll << 20)) {
-                pl.variant = V_NCHWS_BWD_FILTER; pl.a = U; pl.c = NI; pl.parts = parts;
-                pl.name = g.K == 5 ? "nchw_smallplane_bwd_filter_k5s1"
-                                   : (g.s == 1 ? "nchw_smallplane_bwd_filter_k3s1" : "nchw_smallplane_bwd_filter_k3s2");
-                return pl;
-            }
-        }
-        const int V = nchwd_vec(g, dtype, 2);
-        if (V) {
-            // strip height (measured on the benchmark layers): stride 2 wants short strips of 7 output rows,
-            // fp32 stride 1 on large planes 14 rows, everything else whole planes up to 56 rows
-            int TH = g.s == 2 && g.Ho >= 28 ? 7
-                     : (g.s == 1 && dtype == DT_F32 && g.Ho >= 56 ? 14 : (g.Ho > 56 ? (g.Ho + 1) / 2 : g.Ho));
-            TH = tune("DWCONV_TUNE_THW", tune("DWCONV_TUNE_TH", TH));
-            int lg, nst, rounds, parts;
-            nchwd_bwd_filter_tiling(g, V, TH, &lg, &nst, &rounds, &parts);
-            // small batches: shorter strips until the launch has about two blocks per CU (one block = one
-            // channel x a group of (image, strip) items)
-            while (TH > 7 && parts >= 1 && (long long)parts * g.O < 512 && !tune_env("DWCONV_TUNE_THW") && !tune_env("DWCONV_TUNE_TH")) {
-                TH = (TH + 1) / 2;
-                nchwd_bwd_filter_tiling(g, V, TH, &lg, &nst, &rounds, &parts);
-            }
-            if (lg >= 1 && parts >= 1 && (long long)parts * g.O * g.K * g.K * 4 <= (64ll << 20)) {
-                pl.variant = V_NCHWD_BWD_FILTER; pl.a = V; pl.b = TH; pl.parts = parts;
-                pl.name = g.K == 5 ? "nchw_rowwalk_bwd_filter_k5s1"
-                                   : (g.s == 1 ? "nchw_rowwalk_bwd_filter_k3s1" : "nchw_rowwalk_bwd_filter_k3s2");
-                return pl;
-            }
-        }
+        if (use_small(g, dtype, 2) && plan_bwd_filter_nchws(g, dtype, pl)) return pl;
+        if (plan_bwd_filter_nchwd(g, dtype, pl)) return pl;
         const int tr = nchw_pick_tr(g, fits_bwd_filter);
         if (tr) {
             // images per block: keep about 4096 blocks in the launch
@@ -265,17 +280,20 @@ Plan plan_bwd(const Geom &g, int layout, int dtype)
         }
     }
     if (layout == LAYOUT_NCHW && !tune_env("DWCONV_TUNE_NOFUSE")) {
-        const Plan pf = plan_bwd_filter(g, layout, dtype);
-        if (pf.variant == V_NCHWS_BWD_FILTER && nchws_bwd_fused_supported(g)) {
+        // a fused kernel of either family, whichever the separate filter gradient would run on
+        Plan pf = pl;
+        if (use_small(g, dtype, 2) && nchws_bwd_fused_supported(g) && plan_bwd_filter_nchws(g, dtype, pf)) {
             int U, NI, parts;
             nchws_bwd_fused_tiling(g, dtype, &U, &NI, &parts);
             if ((long long)parts * g.O * g.K * g.K * 4 <= (64ll << 20)) {
                 pl = pf;
                 pl.variant = V_NCHWS_BWD_FUSED; pl.a = U; pl.c = NI; pl.parts = parts;
                 pl.name = "nchw_smallplane_bwd_fused_k3s1";
+                return pl;
             }
         }
-        if (pf.variant == V_NCHWD_BWD_FILTER) {
+        pf = pl;
+        if (plan_bwd_filter_nchwd(g, dtype, pf)) {
             const int rs = nchwd_bwd_fused_rs(g, dtype, pf.a);
             if (rs) {
                 // the filter gradient's tiling with the strip height rounded up to whole row groups
