@@ -163,9 +163,160 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_fused_k3s1(Geom g, const T *__
     });
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Fused backward pass, 3x3, stride 2, pad 1, multiplier 1, even H and W.  Mapping and tiling of the
+// stride-2 filter gradient (nhwc.hip): a lane owns V channels of dy column b and walks the dy rows a
+// of its strip.  Step a holds dy rows a and a+1 (columns b and b+1) and x rows 2a-1, 2a, 2a+1
+// (columns 2b-1, 2b, 2b+1):
+//   input gradient: the 2x2 block dx[2a..2a+1][2b..2b+1] from dy[a..a+1][b..b+1], as in
+//     k_nhwc_bwd_data_k3s2 (a missing column b+1 meets zeroed weights, a missing row a+1 is a
+//     block-uniform condition);
+//   filter gradient: dy[a][b] against the 3x3 x window, x row 2a+1 is kept as the top row of step a+1.
+// dy row a+1 and x rows 2a+2, 2a+3 of the next step are loaded while the current one is computed and
+// stay as loaded (packed for bf16) until then.  dy is read once: the pass moves 2|x| + |y| elements.
+// ---------------------------------------------------------------------------------------------
+template <typename T, int V>
+__global__ __launch_bounds__(256) void k_nhwc_bwd_fused_k3s2(Geom g, const T *__restrict__ x, const T *__restrict__ dy,
+                                                             const T *__restrict__ w, T *__restrict__ dx,
+                                                             float *__restrict__ ws, int CT, int nctiles, int nowtiles,
+                                                             int TH, int nstrips, int NI, unsigned nblocks, int nt)
+{
+    constexpr int K = 3;
+    __shared__ float red[ReduceLds<K, V>::FLOATS];
+    unsigned lb = xcd_remap(blockIdx.x, nblocks);
+    const int strip = lb % nstrips; lb /= nstrips;
+    const int owtile = lb % nowtiles; lb /= nowtiles;
+    const int ctile = lb % nctiles; const int ngroup = lb / nctiles;
+
+    const int OWT = 256 / CT;
+    const int tx = threadIdx.x % CT, ty = threadIdx.x / CT;
+    const int Q = g.C / V;
+    const int cq = ctile * CT + tx, b = owtile * OWT + ty;
+    const bool active = cq < Q && b < g.Wo;
+
+    float acc[K][K][V];
+#pragma unroll
+    for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < K; ++kw)
+#pragma unroll
+            for (int v = 0; v < V; ++v) acc[kh][kw][v] = 0.f;
+
+    if (active) {
+        const bool has_b1 = b + 1 < g.Wo;        // dy column b+1 exists
+        const bool has_left = b > 0;             // x column 2b-1 exists
+        float wr[K][K][V];
+#pragma unroll
+        for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+            for (int kw = 0; kw < K; ++kw) {
+                Vec<T, V>::load(w + (kh * K + kw) * g.C + cq * V, wr[kh][kw]);
+                if (kw == 0) {
+#pragma unroll
+                    for (int v = 0; v < V; ++v) wr[kh][kw][v] = has_b1 ? wr[kh][kw][v] : 0.f;   // w?0 multiplies dy[.][b+1]
+                }
+            }
+        const int dyrow = g.Wo * g.C, xrow = g.W * g.C;
+        const int off1 = has_b1 ? g.C : 0;
+        const int xoff0 = has_left ? -g.C : 0;   // clamped; the sums of that tap column are dropped after the walk
+        const int a0 = strip * TH, a1 = min(g.Ho, a0 + TH);
+        const int n0 = ngroup * NI, n1 = min(g.N, n0 + NI);
+        for (int n = n0; n < n1; ++n) {
+            const T *dyin = dy + ((size_t)n * g.Ho * g.Wo + b) * g.C + cq * V;
+            const T *xin = x + ((size_t)n * g.H * g.W + 2 * b) * g.C + cq * V;
+            T *dxout = dx + ((size_t)n * g.H * g.W + 2 * b) * g.C + cq * V;
+            auto load_dy = [&](int a, RawVec<T, V> (&d)[2]) {
+                const T *rp = dyin + (size_t)min(a, g.Ho - 1) * dyrow;
+                d[0].load(rp); d[1].load(rp + off1);
+            };
+            auto load_x = [&](int r, RawVec<T, V> (&xd)[K]) {
+                const T *rp = xin + (size_t)min(max(r, 0), g.H - 1) * xrow;
+                xd[0].load(rp + xoff0); xd[1].load(rp); xd[2].load(rp + g.C);
+            };
+            RawVec<T, V> dcur[2], dnext[2][2], xa[K], xb[2][K], xc[2][K];
+            load_dy(a0, dcur);
+            if (a0 > 0) load_x(2 * a0 - 1, xa);
+            else {
+#pragma unroll
+                for (int kw = 0; kw < K; ++kw) xa[kw].zero();
+            }
+            load_dy(a0 + 1, dnext[0]); load_x(2 * a0, xb[0]); load_x(2 * a0 + 1, xc[0]);
+            auto step = [&](int a, int j) {
+                const bool below = a + 1 < g.Ho;
+                float A0[V], A1[V], B0[V], B1[V];
+                dcur[0].get(A0); dcur[1].get(A1); dnext[j][0].get(B0); dnext[j][1].get(B1);
+                float o00[V], o01[V], o10[V], o11[V];
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    o00[v] = wr[1][1][v] * A0[v];
+                    o01[v] = fmaf(wr[1][0][v], A1[v], wr[1][2][v] * A0[v]);
+                    o10[v] = wr[2][1][v] * A0[v];
+                    o11[v] = fmaf(wr[2][0][v], A1[v], wr[2][2][v] * A0[v]);
+                }
+                if (below) {
+#pragma unroll
+                    for (int v = 0; v < V; ++v) {
+                        o10[v] = fmaf(wr[0][1][v], B0[v], o10[v]);
+                        o11[v] = fmaf(wr[0][0][v], B1[v], fmaf(wr[0][2][v], B0[v], o11[v]));
+                    }
+                }
+                T *r0p = dxout + (size_t)(2 * a) * xrow;
+                store_vec<T, V>(r0p, o00, nt != 0);
+                store_vec<T, V>(r0p + g.C, o01, nt != 0);
+                store_vec<T, V>(r0p + xrow, o10, nt != 0);
+                store_vec<T, V>(r0p + xrow + g.C, o11, nt != 0);
+                // filter gradient: dy[a][b] meets x rows 2a-1, 2a, 2a+1 at tap rows 0, 1, 2
+#pragma unroll
+                for (int kw = 0; kw < K; ++kw) {
+                    float x0[V], x1[V], x2[V];
+                    xa[kw].get(x0); xb[j][kw].get(x1); xc[j][kw].get(x2);
+#pragma unroll
+                    for (int v = 0; v < V; ++v) {
+                        acc[0][kw][v] = fmaf(A0[v], x0[v], acc[0][kw][v]);
+                        acc[1][kw][v] = fmaf(A0[v], x1[v], acc[1][kw][v]);
+                        acc[2][kw][v] = fmaf(A0[v], x2[v], acc[2][kw][v]);
+                    }
+                }
+                dcur[0] = dnext[j][0]; dcur[1] = dnext[j][1];
+#pragma unroll
+                for (int kw = 0; kw < K; ++kw) xa[kw] = xc[j][kw];
+            };
+            int a = a0;
+#pragma unroll 1
+            for (; a + 2 <= a1; a += 2) {
+                load_dy(a + 2, dnext[1]); load_x(2 * a + 2, xb[1]); load_x(2 * a + 3, xc[1]);
+                step(a, 0);
+                load_dy(a + 3, dnext[0]); load_x(2 * a + 4, xb[0]); load_x(2 * a + 5, xc[0]);
+                step(a + 1, 1);
+            }
+            if (a < a1) step(a, 0);
+        }
+        // the left tap column of the lanes at b = 0 accumulated clamped data: drop it
+        if (!has_left) {
+#pragma unroll
+            for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+                for (int v = 0; v < V; ++v) acc[kh][0][v] = 0.f;
+        }
+    }
+
+    const int part = (ngroup * nstrips + strip) * nowtiles + owtile;
+    float *wsp = ws + (size_t)part * (K * K * g.C);
+    block_reduce_taps<K, V>(acc, CT, red, [&](int kh, int kw, int v, float total) {
+        if (cq < Q) wsp[(kh * K + kw) * g.C + cq * V + v] = total;
+    });
+}
+
 bool nhwc_bwd_fused_supported(const Geom &g, int dtype, int V)
 {
-    if (!(g.K == 3 && g.s == 1 && g.p == 1 && g.m == 1)) return false;
+    if (!(g.K == 3 && g.p == 1 && g.m == 1)) return false;
+    // stride 2 (even maps): 12 % faster than the two passes on 112x112 maps, equal within 2 % on smaller ones
+    if (g.s == 2) {
+        const char *e = tune_env("DWCONV_TUNE_FUSE_S2H");        // tuning: smallest map height that takes the fused kernel
+        if (g.H % 2 != 0 || g.W % 2 != 0 || g.H < (e ? atoi(e) : 2)) return false;
+    }
+    else if (g.s != 1) return false;
     // bf16 with 8 channels per lane would need more than 256 registers
     return (dtype == DT_F32 && V == 4) || (dtype == DT_BF16 && V == 4);
 }
@@ -183,9 +334,14 @@ hipError_t nhwc_bwd_fused(const Geom &g, int dtype, int V, const void *x, const 
 #define GO(T, VV) hipLaunchKernelGGL((k_nhwc_bwd_fused_k3s1<T, VV, 1>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, \
                                      (const T *)dy, (const T *)w, (T *)dx, ws, CT, nctiles, nowtiles, TH, nstrips, NI, \
                                      nblocks, nt)
-    if (dtype == DT_F32) GO(float, 4);
+#define GO2(T, VV) hipLaunchKernelGGL((k_nhwc_bwd_fused_k3s2<T, VV>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, \
+                                      (const T *)dy, (const T *)w, (T *)dx, ws, CT, nctiles, nowtiles, TH, nstrips, NI, \
+                                      nblocks, nt)
+    if (g.s == 2) { if (dtype == DT_F32) GO2(float, 4); else GO2(bf16_t, 4); }
+    else if (dtype == DT_F32) GO(float, 4);
     else GO(bf16_t, 4);
 #undef GO
+#undef GO2
     return hipGetLastError();
 }
 

@@ -275,7 +275,7 @@ Plan plan_bwd(const Geom &g, int layout, int dtype)
             if (pf.variant == V_NHWC_BWD_FILTER && pf.a == V) {
                 pl = pf;
                 pl.variant = V_NHWC_BWD_FUSED;
-                pl.name = "nhwc_bwd_fused_k3s1";
+                pl.name = g.s == 1 ? "nhwc_bwd_fused_k3s1" : "nhwc_bwd_fused_k3s2";
             }
         }
     }
