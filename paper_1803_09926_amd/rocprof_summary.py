@@ -25,11 +25,11 @@ VARIANT_KERNELS = {
     "bwd_data:nhwc_rowwalk_k3s1_flip_m2": [r"k_nhwc_s1<[\w ]+, \d+, 3, \d+, true, 2>"],
     "fwd:nhwc_rowwalk_fwd_k3s2": [r"k_nhwc_fwd_k3s2<"],
     "bwd_data:nhwc_rowwalk_bwd_data_k3s2": [r"k_nhwc_bwd_data_k3s2<"],
-    # k_nhwc_bwd_filter<T, V, K, S, PF, M>
-    "bwd_filter:nhwc_bwd_filter_k3s1": [r"k_nhwc_bwd_filter<[\w ]+, \d+, 3, 1, \d+, 1>"],
-    "bwd_filter:nhwc_bwd_filter_k3s2": [r"k_nhwc_bwd_filter<[\w ]+, \d+, 3, 2, \d+, 1>"],
-    "bwd_filter:nhwc_bwd_filter_k5s1": [r"k_nhwc_bwd_filter<[\w ]+, \d+, 5, 1, \d+, 1>"],
-    "bwd_filter:nhwc_bwd_filter_k3s1_m2": [r"k_nhwc_bwd_filter<[\w ]+, \d+, 3, 1, \d+, 2>"],
+    # k_nhwc_bwd_filter<T, V, K, S, PF, M, FLAT>
+    "bwd_filter:nhwc_bwd_filter_k3s1": [r"k_nhwc_bwd_filter<[\w ]+, \d+, 3, 1, \d+, 1, \w+>"],
+    "bwd_filter:nhwc_bwd_filter_k3s2": [r"k_nhwc_bwd_filter<[\w ]+, \d+, 3, 2, \d+, 1, \w+>"],
+    "bwd_filter:nhwc_bwd_filter_k5s1": [r"k_nhwc_bwd_filter<[\w ]+, \d+, 5, 1, \d+, 1, \w+>"],
+    "bwd_filter:nhwc_bwd_filter_k3s1_m2": [r"k_nhwc_bwd_filter<[\w ]+, \d+, 3, 1, \d+, 2, \w+>"],
     # k_nchwd_s1<T, V, K, PF, FLIP, RS> (RS > 0: whole-line write-out)
     # bf16: k_nchwd_s1_bf16x8<V, K, PF, FLIP, RS> (packed pairs)
     "fwd:nchw_rowwalk_k3s1": [r"k_nchwd_s1<[\w ]+, \d+, 3, \d+, false[,>]", r"k_nchwd_s1_bf16x8<\d+, 3, \d+, false,"],
@@ -53,6 +53,7 @@ VARIANT_KERNELS = {
     "bwd_filter:nchw_smallplane_bwd_filter_k5s1": [r"k_nchws_bwd_filter<[\w ]+, 5, 1, \d+>"],
     # whole backward pass in one kernel (dwconv_bwd)
     "bwd:nhwc_bwd_fused_k3s1": [r"k_nhwc_bwd_fused_k3s1<"],
+    "bwd:nhwc_bwd_fused_k3s2": [r"k_nhwc_bwd_fused_k3s2<"],
     "bwd:nchw_bwd_fused_k3s1": [r"k_nchwd_bwd_fused_k3s1<"],
     "bwd:nchw_smallplane_bwd_fused_k3s1": [r"k_nchws_bwd_fused<"],
     # group convolution: k_gconv_nchw_s1<T, V, OB, R, FLIP, SHFL>, k_gconv_nhwc_s1<T, CG, OB, GPL, PF, FLIP>
