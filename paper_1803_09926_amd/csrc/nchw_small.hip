@@ -154,9 +154,11 @@ __device__ __forceinline__ void flat_store(T *__restrict__ dst, int g0, int g1, 
 // Forward K x K (K odd), pad (K-1)/2, stride S, row width W (template).  FLIP: filter rotated by 180 degrees
 // (backward-data of the stride-1 layer).  U planes per block, one lane per (plane, output row).
 // ---------------------------------------------------------------------------------------------
+// TPB tiles of U planes per block, one after the other (tile lb*TPB + i): the next tile's planes are loaded into
+// registers while the current tile is computed from LDS and written out, so a block's memory latency is paid once.
 template <typename T, int K, int S, int W, bool FLIP>
 __global__ __launch_bounds__(256) void k_nchws_fwd(Geom g, const T *__restrict__ x, const T *__restrict__ w,
-                                                   T *__restrict__ y, int U, int nplanes, unsigned nblocks, int nt)
+                                                   T *__restrict__ y, int U, int nplanes, unsigned nblocks, int nt, int TPB)
 {
     extern __shared__ float4 smem4[];
     constexpr int VE = ElemsS<T>::VE;
@@ -164,15 +166,32 @@ __global__ __launch_bounds__(256) void k_nchws_fwd(Geom g, const T *__restrict__
     constexpr int WO = (W + 2 * P - K) / S + 1;
     const int HW = g.H * W, HoWo = g.Ho * WO;
     const unsigned lb = xcd_remap(blockIdx.x, nblocks);
-    const int p0 = lb * U, np = min(U, nplanes - p0);
     float *lin = reinterpret_cast<float *>(smem4);
     float *lout = lin + ((U * HW + 2 * VE + 3) & ~3);
-    const int gi0 = p0 * HW, go0 = p0 * HoWo;
-
-    flat_load<T>(x, g.N * g.C * HW, gi0, gi0 + np * HW, lin);
-    __syncthreads();
-
+    const int total = g.N * g.C * HW;
     const int p = threadIdx.x / g.Ho, oh = threadIdx.x - p * g.Ho;
+
+    // TPB == 0: a single tile whose planes do not fit the register staging (more than 8192 elements): loaded straight into LDS
+    const int ntl = TPB > 0 ? TPB : 1;
+    FlatRegs<T> regs;
+    if (TPB > 0) {
+        const int q0 = (int)(lb * ntl) * U, nq = min(U, nplanes - q0);
+        flat_issue<T>(x, total, q0 * HW, (q0 + nq) * HW, regs);
+    }
+    for (int ti = 0; ti < ntl; ++ti) {
+    const int p0 = (int)(lb * ntl + ti) * U;
+    if (p0 >= nplanes) break;                       // uniform over the block
+    const int np = min(U, nplanes - p0);
+    const int gi0 = p0 * HW, go0 = p0 * HoWo;
+    if (ti > 0) __syncthreads();                    // the previous tile's write-out has read lout, its compute lin
+    if (TPB > 0) flat_commit<T>(gi0, gi0 + np * HW, regs, lin);
+    else flat_load<T>(x, total, gi0, gi0 + np * HW, lin);
+    __syncthreads();
+    if (ti + 1 < ntl && p0 + U < nplanes) {
+        const int q0 = p0 + U, nq = min(U, nplanes - q0);
+        flat_issue<T>(x, total, q0 * HW, (q0 + nq) * HW, regs);
+    }
+
     if (p < np) {
         const int c = (p0 + p) % g.C;
         float wr[K][K];
@@ -213,6 +232,7 @@ __global__ __launch_bounds__(256) void k_nchws_fwd(Geom g, const T *__restrict__
     __syncthreads();
 
     flat_store<T>(y, go0, go0 + np * HoWo, lout, nt != 0);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -531,11 +551,19 @@ static hipError_t go_fwd(const Geom &g, const void *x, const void *w, void *y, b
     while (U > 1 && lds_bytes_for(U, HW, HoWo, VE) > 60 * 1024) --U;
     const size_t lds = lds_bytes_for(U, HW, HoWo, VE);
     const int nplanes = g.N * g.C;
-    const unsigned nblocks = (unsigned)cdiv(nplanes, U);
+    const int ntiles = cdiv(nplanes, U);
+    // tiles per block: two on large launches (measured against 1, 3 and 4 on the 14x14 and 7x7 layers at batch 128:
+    // 3 to 10 % on the input gradient and the 7x7 forward; three tiles leave a short last round of blocks and lose)
+    int tpb = ntiles >= 2048 ? 2 : 1;
+    if (const char *e = tune_env("DWCONV_TUNE_STPB")) tpb = atoi(e);
+    if (tpb < 1) tpb = 1;
+    if (tpb > 8) tpb = 8;
+    if (U * HW + VE > 8192) tpb = 0;            // too large for the register staging: one tile per block, loaded straight into LDS
+    const unsigned nblocks = (unsigned)cdiv(ntiles, tpb > 0 ? tpb : 1);
     // the block writes one contiguous range with whole 16-byte vectors: streamed
     const int nt = stream_stores(flip ? "NCHW_SMALL_BWD" : "NCHW_SMALL_FWD", (long long)nplanes * HoWo * sizeof(T), 0);
 #define GO(KK, SS, WW, FL) hipLaunchKernelGGL((k_nchws_fwd<T, KK, SS, WW, FL>), dim3(nblocks), dim3(256), lds, st, g, \
-                                              (const T *)x, (const T *)w, (T *)y, U, nplanes, nblocks, nt)
+                                              (const T *)x, (const T *)w, (T *)y, U, nplanes, nblocks, nt, tpb)
 #define PICK(KK, SS, WW) if (g.K == KK && g.s == SS && g.W == WW) { if (flip) GO(KK, SS, WW, true); else GO(KK, SS, WW, false); return hipGetLastError(); }
     PICK(3, 1, 7) PICK(3, 1, 14) PICK(3, 1, 28) PICK(3, 2, 14) PICK(3, 2, 28) PICK(5, 1, 7) PICK(5, 1, 14)
     PICK(3, 1, 4) PICK(3, 1, 8) PICK(3, 2, 8)
