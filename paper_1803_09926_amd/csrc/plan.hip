@@ -45,10 +45,12 @@ static int nhwc_pf(const Geom &g, int dtype)
 // short strips win (14 input rows at stride 1, 7 output rows at stride 2) even though each strip
 // re-reads K-1 halo rows (those come from L2): more, shorter walks keep the launch's accesses
 // closer together in memory.
-static int pick_th(int rows, int stride, int dflt1 = 14)
+static int pick_th(int rows, int stride, int dflt1 = 14, int dflt2 = 0)
 {
-    // stride 2: 7 output rows, 4 on tall maps (56 output rows and more: 1-4 % on the 112x112 and 56x56 layers)
-    const int target = stride == 1 ? tune("DWCONV_TUNE_TH1", dflt1) : tune("DWCONV_TUNE_TH2", rows >= 56 ? 4 : 7);
+    // stride 2: 7 output rows, 4 on tall maps (56 output rows and more: 1-4 % on the 112x112 and 56x56 layers);
+    // the NCHW input gradient on tall maps 2 (its 112x112 layer: 118 -> 110 us inside the step; NHWC lost 1 % with it)
+    if (dflt2 == 0) dflt2 = rows >= 56 ? 4 : 7;
+    const int target = stride == 1 ? tune("DWCONV_TUNE_TH1", dflt1) : tune("DWCONV_TUNE_TH2", dflt2);
     // balanced strips: the number of strips that brings their height closest to the target, then equal
     // heights (19 rows are one strip of 19, not 14 + 5; 37 rows are 13 + 13 + 11)
     int nstrips = (rows + target / 2) / target;
@@ -60,7 +62,9 @@ static int pick_th(int rows, int stride, int dflt1 = 14)
 // Strip height of the NCHW stride-1 row walk.  The bf16 kernels are bound by their vector-ALU work (twice the
 // elements per byte), so the K-1 halo rows a strip computes again cost them more than they cost the fp32 kernels:
 // strips of 28 rows measured 2-9 % faster than 14 on the bf16 layers.
-static int nchwd_th1(int dtype) { return dtype == DT_BF16 ? 28 : 14; }
+// fp32: 14 rows on rows of 112 elements; on rows of 56 and fewer (whole-line write-out in groups of four rows) 8 rows
+// measured 3-4 % faster than 14 inside the step, on the forward pass and on the input gradient.
+static int nchwd_th1(int dtype, int W) { return dtype == DT_BF16 ? 28 : (W <= 56 ? 8 : 14); }
 
 // NCHW: rows per unit.  Small planes are taken whole; larger ones in strips of 8 output rows
 // (halo rows come from L2), shrunk until the tile fits in LDS.
@@ -98,7 +102,7 @@ Plan plan_fwd(const Geom &g, int layout, int dtype)
         const int V = nchwd_vec(g, dtype, 0);
         if (V) {
             pl.a = V;
-            if (g.s == 1) { pl.variant = V_NCHWD_S1; pl.b = pick_th(g.H, 1, nchwd_th1(dtype)); pl.name = g.K == 3 ? "nchw_rowwalk_k3s1" : "nchw_rowwalk_k5s1"; }
+            if (g.s == 1) { pl.variant = V_NCHWD_S1; pl.b = pick_th(g.H, 1, nchwd_th1(dtype, g.W)); pl.name = g.K == 3 ? "nchw_rowwalk_k3s1" : "nchw_rowwalk_k5s1"; }
             else { pl.variant = V_NCHWD_K3S2; pl.b = pick_th(g.Ho, 2); pl.name = "nchw_rowwalk_fwd_k3s2"; }
             return pl;
         }
@@ -131,8 +135,8 @@ Plan plan_bwd_data(const Geom &g, int layout, int dtype)
         const int V = nchwd_vec(g, dtype, 1);
         if (V) {
             pl.a = V;
-            if (g.s == 1) { pl.variant = V_NCHWD_S1; pl.b = pick_th(g.H, 1, nchwd_th1(dtype)); pl.name = g.K == 3 ? "nchw_rowwalk_k3s1_flip" : "nchw_rowwalk_k5s1_flip"; }
-            else { pl.variant = V_NCHWD_K3S2; pl.b = pick_th(g.Ho, 2); pl.name = "nchw_rowwalk_bwd_data_k3s2"; }
+            if (g.s == 1) { pl.variant = V_NCHWD_S1; pl.b = pick_th(g.H, 1, nchwd_th1(dtype, g.W)); pl.name = g.K == 3 ? "nchw_rowwalk_k3s1_flip" : "nchw_rowwalk_k5s1_flip"; }
+            else { pl.variant = V_NCHWD_K3S2; pl.b = pick_th(g.Ho, 2, 14, g.Ho >= 56 ? 2 : 0); pl.name = "nchw_rowwalk_bwd_data_k3s2"; }
             return pl;
         }
         if (g.m == 1 && same_pad_s1(g)) {
