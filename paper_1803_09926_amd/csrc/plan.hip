@@ -81,9 +81,9 @@ static bool fits_bwd_filter(const Geom &g, int tr) { return nchw_bwd_filter_part
 // Small-plane NCHW kernels: rows of up to 14 always, and whenever the row walk cannot take the shape (bf16 rows that
 // are not whole 16-byte vectors).  Rows of 28, where both families apply, go to whichever measured faster inside the
 // benchmark step: the filter gradient always to the small-plane kernel (37 against 46 us on the 28x28x256 layer at
-// batch 128, 23 against 29 us on its stride-2 sibling), the fp32 forward at stride 1 and the fp32 input gradient at
-// stride 2 too (42 against 47 us, 21 against 22 us); the stride-1 input gradient and everything else in bf16 stay
-// with the row walk.
+// batch 128, 23 against 29 us on its stride-2 sibling), the fp32 forward and the fp32 input gradient at stride 2
+// too (stride-1 forward 42 against 47 us, stride-2 forward 28 against 31 us, stride-2 input gradient 21 against
+// 22 us); the stride-1 input gradient and everything else in bf16 stay with the row walk.
 static bool use_small(const Geom &g, int dtype, int pass)
 {
     if (!nchws_supported(g, pass)) return false;
@@ -91,7 +91,7 @@ static bool use_small(const Geom &g, int dtype, int pass)
     if (const char *e = tune_env("DWCONV_TUNE_S28")) return atoi(e) == 1;
     if (pass == 2) return true;
     if (dtype != DT_F32) return false;
-    return (pass == 0 && g.s == 1) || (pass == 1 && g.s == 2);
+    return pass == 0 || (pass == 1 && g.s == 2);
 }
 
 Plan plan_fwd(const Geom &g, int layout, int dtype)
