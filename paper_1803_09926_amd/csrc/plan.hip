@@ -31,11 +31,15 @@ static int nhwc_vec(const Geom &g, int dtype)
     return g.O % 8 == 0 ? 8 : (g.O % 4 == 0 ? 4 : 0);
 }
 
-// Rows loaded ahead in the NHWC stride-1 kernel (5x5 keeps 25 taps x V in registers: one row less).
+// Rows loaded ahead in the NHWC stride-1 kernel.  fp32 3x3: four (inside the step the nine forward launches of the
+// MobileNet stack take 522 us with four rows in flight against 531 with two; the small layers, whose wavefronts are
+// all resident at once, gain most); bf16 3x3: three (input gradient 886 -> 870 us over the bf16 stack).  5x5 keeps
+// 25 taps x V in registers: two rows.
 static int nhwc_pf(const Geom &g, int dtype)
 {
-    int pf = tune("DWCONV_TUNE_PF", 2);
+    int pf = tune("DWCONV_TUNE_PF", (g.K == 3 && g.m == 1) ? (dtype == DT_F32 ? 4 : 3) : 2);
     if (g.K == 5 && pf > 2) pf = 2;
+    if (g.m != 1 && pf > 2) pf = 2;
     if (pf > 3 && !(dtype == DT_F32 && g.K == 3)) pf = 3;
     if (pf > 4) pf = 4;
     return pf;
