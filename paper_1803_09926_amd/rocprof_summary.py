@@ -2,7 +2,7 @@
 
 Usage:
   python -m paper_1803_09926_amd.rocprof_summary stats   <dir with *_kernel_stats.csv> [workload index of bench.py --config]
-  python -m paper_1803_09926_amd.rocprof_summary traffic <FETCH_SIZE dir> <WRITE_SIZE dir>
+  python -m paper_1803_09926_amd.rocprof_summary traffic <FETCH_SIZE dir> <WRITE_SIZE dir> [workload index]
 
 `traffic` expects both runs to contain bench.py's --calibrate-copy dispatches (a plain device copy
 of 2^30 bytes): each counter is scaled so that the copy reads (writes) exactly 2^30 bytes.
@@ -79,6 +79,29 @@ def short(name):
     return name.replace("void dwc::", "").replace("dwc::", "")
 
 
+def _workload_keys(config):
+    """bench.py's "<pass>:<variant>" keys of a workload: launches per step and algorithmic bytes per step of each."""
+    import paper_1803_09926_amd as dw
+    from paper_1803_09926_amd import workloads as wl
+    cfg = wl.config(config)
+    esz = 4 if cfg["dtype"] == wl.F32 else 2
+    launches, nbytes = {}, {}
+    for layout in cfg["layouts"]:
+        for layer, repeat in cfg["layers"]:
+            if layer.cg > 1:
+                d = dw.group_desc(cfg["N"], layer.C, layer.H, layer.W, layer.K, layer.stride, layer.pad, layer.groups,
+                                  layer.O, layout, cfg["dtype"])
+                vname = dw.gconv_variant_name
+            else:
+                d = dw.desc(cfg["N"], layer.C, layer.H, layer.W, layer.K, layer.stride, layer.pad, layer.mult, layout, cfg["dtype"])
+                vname = dw.variant_name
+            for which, pname in enumerate(("fwd", "bwd_data", "bwd_filter")):
+                key = pname + ":" + vname(d, which)
+                launches[key] = launches.get(key, 0) + repeat
+                nbytes[key] = nbytes.get(key, 0) + repeat * layer.pass_bytes(cfg["N"], esz)
+    return launches, nbytes
+
+
 def stats(d, config=None):
     rows = list(csv.DictReader(open(_one(os.path.join(d, "*kernel_stats.csv")))))
     rows = [r for r in rows if "dwc::" in r["Name"]]
@@ -103,24 +126,9 @@ def stats(d, config=None):
     if config is None:
         return
     # per layout and pass: time per step from the trace against the algorithmic bytes of the workload
-    import paper_1803_09926_amd as dw
     from paper_1803_09926_amd import workloads as wl
     cfg = wl.config(config)
-    esz = 4 if cfg["dtype"] == wl.F32 else 2
-    launches, nbytes = {}, {}
-    for layout in cfg["layouts"]:
-        for layer, repeat in cfg["layers"]:
-            if layer.cg > 1:
-                d = dw.group_desc(cfg["N"], layer.C, layer.H, layer.W, layer.K, layer.stride, layer.pad, layer.groups,
-                                  layer.O, layout, cfg["dtype"])
-                vname = dw.gconv_variant_name
-            else:
-                d = dw.desc(cfg["N"], layer.C, layer.H, layer.W, layer.K, layer.stride, layer.pad, layer.mult, layout, cfg["dtype"])
-                vname = dw.variant_name
-            for which, pname in enumerate(("fwd", "bwd_data", "bwd_filter")):
-                key = pname + ":" + vname(d, which)
-                launches[key] = launches.get(key, 0) + repeat
-                nbytes[key] = nbytes.get(key, 0) + repeat * layer.pass_bytes(cfg["N"], esz)
+    launches, nbytes = _workload_keys(config)
     missing = [k for k in launches if k not in per_key]
     if missing:
         print("# keys of the workload with no kernel in the trace: " + ", ".join(missing))
@@ -162,7 +170,7 @@ def _counter(d, cname):
     return unit, cal, per
 
 
-def traffic(dfetch, dwrite):
+def traffic(dfetch, dwrite, config=None):
     fu, fcal, fper = _counter(dfetch, "FETCH_SIZE")
     wu, wcal, wper = _counter(dwrite, "WRITE_SIZE")
     print("# calibration: a device copy of 2^30 bytes reads FETCH_SIZE = %s and writes WRITE_SIZE = %s" % (fcal, wcal))
@@ -174,6 +182,7 @@ def traffic(dfetch, dwrite):
         print("%-64s %7d %14.0f %14.0f %14.0f" % (k[:64], len(fper[k]), f, w, f + w))
     print("# bench.py keys: mean HBM bytes per launch over every dispatch of the kernel(s) behind the key")
     print("# (for bwd_filter: stage 1 only; the stage-2 kernel k_reduce_partials is listed above)")
+    measured = {}
     for key, pats in VARIANT_KERNELS.items():
         ks = [k for k in fper if any(re.search(p, k) for p in pats)]
         if not ks:
@@ -181,12 +190,23 @@ def traffic(dfetch, dwrite):
         calls = sum(len(fper[k]) for k in ks)
         val = (sum(sum(fper[k]) for k in ks) + sum(sum(wper.get(k, [])) for k in ks)) / calls
         print("traffic %s %.0f" % (key, val))
+        measured[key] = val
+    if config is None:
+        return
+    # measured HBM bytes per launch against the algorithmic bytes of the same launches (mean over the key's layers)
+    launches, nbytes = _workload_keys(config)
+    print("# measured HBM traffic over algorithmic bytes (|x| + |y|) per launch, per bench.py key of workload %d" % config)
+    print("%-48s %14s %14s %7s" % ("key", "measured_B", "algorithmic_B", "ratio"))
+    for key in measured:
+        if key in launches:
+            alg = nbytes[key] / launches[key]
+            print("ratio %-42s %14.0f %14.0f %7.3f" % (key, measured[key], alg, measured[key] / alg))
 
 
 if __name__ == "__main__":
     if len(sys.argv) >= 3 and sys.argv[1] == "stats":
         stats(sys.argv[2], int(sys.argv[3]) if len(sys.argv) >= 4 else None)
     elif len(sys.argv) >= 4 and sys.argv[1] == "traffic":
-        traffic(sys.argv[2], sys.argv[3])
+        traffic(sys.argv[2], sys.argv[3], int(sys.argv[4]) if len(sys.argv) >= 5 else None)
     else:
         sys.exit(__doc__)
