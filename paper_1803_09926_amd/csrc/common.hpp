@@ -117,6 +117,57 @@ template <> struct Vec<bf16_t, 1> {
     static __device__ __forceinline__ void store(bf16_t *p, const float (&r)[1]) { *p = f32_to_bf16(r[0]); }
 };
 
+// ---- buffer addressing --------------------------------------------------------------------
+// A raw buffer descriptor over `bytes` bytes at `base` (one image of a tensor: at most 2 GiB).  A load takes the
+// lane's byte offset in a vector register and a wavefront-uniform byte offset in a scalar register, so a walk down
+// the rows of an image needs no vector address arithmetic per row; a flat global load takes a 64-bit vector add
+// for every address, which the kernels bound by their vector-ALU work (bf16, 5x5) cannot afford.  A read at or
+// beyond `bytes` returns zero instead of faulting.  Word 3 of the descriptor is the untyped 32-bit data format of
+// this chip family.
+typedef uint32_t u4raw_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u2raw_t __attribute__((ext_vector_type(2)));
+struct BufView {
+    // A view covers at most 2 GiB, so this lane offset is outside every view whatever uniform offset is added to
+    // it (the sum stays below 4 GiB): the way a lane asks for a zero.
+    static constexpr uint32_t OUTSIDE = 0x80000000u;
+    __amdgpu_buffer_rsrc_t rsrc;
+    // base and bytes must be the same in every lane; they are pinned to scalar registers here, so that a load never
+    // falls back to a loop over distinct descriptors when the compiler cannot prove it
+    __device__ __forceinline__ BufView(const void *base, uint32_t bytes)
+        : rsrc(__builtin_amdgcn_make_buffer_rsrc(uniform_ptr(base), 0, (int)uniform(bytes), 0x00020000)) {}
+    static __device__ __forceinline__ uint32_t uniform(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+    static __device__ __forceinline__ void *uniform_ptr(const void *p)
+    {
+        const uint64_t a = (uint64_t)p;
+        return (void *)(((uint64_t)uniform((uint32_t)(a >> 32)) << 32) | uniform((uint32_t)a));
+    }
+    __device__ __forceinline__ uint32_t b32(uint32_t voff, uint32_t soff) const
+    {
+        return __builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)voff, (int)uniform(soff), 0);
+    }
+    __device__ __forceinline__ u2raw_t b64(uint32_t voff, uint32_t soff) const
+    {
+        return __builtin_amdgcn_raw_buffer_load_b64(rsrc, (int)voff, (int)uniform(soff), 0);
+    }
+    __device__ __forceinline__ u4raw_t b128(uint32_t voff, uint32_t soff) const
+    {
+        return __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)voff, (int)uniform(soff), 0);
+    }
+    // stores; NT marks the store non-temporal (cache-policy bit 1 of the instruction)
+    template <bool NT> __device__ __forceinline__ void st32(uint32_t d, uint32_t voff, uint32_t soff) const
+    {
+        __builtin_amdgcn_raw_buffer_store_b32(d, rsrc, (int)voff, (int)uniform(soff), NT ? 2 : 0);
+    }
+    template <bool NT> __device__ __forceinline__ void st64(u2raw_t d, uint32_t voff, uint32_t soff) const
+    {
+        __builtin_amdgcn_raw_buffer_store_b64(d, rsrc, (int)voff, (int)uniform(soff), NT ? 2 : 0);
+    }
+    template <bool NT> __device__ __forceinline__ void st128(u4raw_t d, uint32_t voff, uint32_t soff) const
+    {
+        __builtin_amdgcn_raw_buffer_store_b128(d, rsrc, (int)voff, (int)uniform(soff), NT ? 2 : 0);
+    }
+};
+
 // Store V elements; `stream` = true marks the store non-temporal (the output of a large layer is
 // not read again by these kernels, so it should not displace the halo rows that are).
 // V consecutive elements kept as loaded (bf16 stays packed, two per register) and widened to
@@ -126,6 +177,13 @@ template <typename T, int V> struct RawVec;
 template <int V> struct RawVec<float, V> {
     float v[V];
     __device__ __forceinline__ void load(const float *p) { Vec<float, V>::load(p, v); }
+    // V floats at byte offset voff (per lane) + soff (uniform) of the view
+    __device__ __forceinline__ void load_buf(const BufView &b, uint32_t voff, uint32_t soff)
+    {
+        if constexpr (V == 4) { const u4raw_t q = b.b128(voff, soff); v[0] = __uint_as_float(q.x); v[1] = __uint_as_float(q.y); v[2] = __uint_as_float(q.z); v[3] = __uint_as_float(q.w); }
+        else if constexpr (V == 2) { const u2raw_t q = b.b64(voff, soff); v[0] = __uint_as_float(q.x); v[1] = __uint_as_float(q.y); }
+        else { static_assert(V == 1, "float vectors of 1, 2 or 4"); v[0] = __uint_as_float(b.b32(voff, soff)); }
+    }
     __device__ __forceinline__ void get(float (&r)[V]) const
     {
 #pragma unroll
@@ -145,6 +203,12 @@ template <int V> struct RawVec<bf16_t, V> {
         if constexpr (V == 8) { const uint4 q = *reinterpret_cast<const uint4 *>(p); w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w; }
         else if constexpr (V == 4) { const uint2 q = *reinterpret_cast<const uint2 *>(p); w[0] = q.x; w[1] = q.y; }
         else { static_assert(V == 2, "bf16 vectors of 2, 4 or 8"); w[0] = *reinterpret_cast<const uint32_t *>(p); }
+    }
+    __device__ __forceinline__ void load_buf(const BufView &b, uint32_t voff, uint32_t soff)
+    {
+        if constexpr (V == 8) { const u4raw_t q = b.b128(voff, soff); w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w; }
+        else if constexpr (V == 4) { const u2raw_t q = b.b64(voff, soff); w[0] = q.x; w[1] = q.y; }
+        else w[0] = b.b32(voff, soff);
     }
     __device__ __forceinline__ void get(float (&r)[V]) const
     {
@@ -190,6 +254,27 @@ __device__ __forceinline__ void store_vec(T *p, const float (&r)[V], bool stream
     } else {
         Vec<T, V>::store(p, r);
     }
+}
+
+// store_vec through a buffer view: V elements at byte offset voff (per lane) + soff (uniform)
+template <typename T, int V, bool NT>
+__device__ __forceinline__ void store_buf_nt(const BufView &b, uint32_t voff, uint32_t soff, const float (&r)[V])
+{
+    if constexpr (sizeof(T) == 4) {
+        if constexpr (V == 4) { u4raw_t d = {__float_as_uint(r[0]), __float_as_uint(r[1]), __float_as_uint(r[2]), __float_as_uint(r[3])}; b.st128<NT>(d, voff, soff); }
+        else if constexpr (V == 2) { u2raw_t d = {__float_as_uint(r[0]), __float_as_uint(r[1])}; b.st64<NT>(d, voff, soff); }
+        else { static_assert(V == 1, "float vectors of 1, 2 or 4"); b.st32<NT>(__float_as_uint(r[0]), voff, soff); }
+    } else {
+        if constexpr (V == 8) { u4raw_t d = {pack2_bf16(r[0], r[1]), pack2_bf16(r[2], r[3]), pack2_bf16(r[4], r[5]), pack2_bf16(r[6], r[7])}; b.st128<NT>(d, voff, soff); }
+        else if constexpr (V == 4) { u2raw_t d = {pack2_bf16(r[0], r[1]), pack2_bf16(r[2], r[3])}; b.st64<NT>(d, voff, soff); }
+        else { static_assert(V == 2, "bf16 vectors of 2, 4 or 8"); b.st32<NT>(pack2_bf16(r[0], r[1]), voff, soff); }
+    }
+}
+template <typename T, int V>
+__device__ __forceinline__ void store_buf(const BufView &b, uint32_t voff, uint32_t soff, const float (&r)[V], bool stream)
+{
+    if (stream) store_buf_nt<T, V, true>(b, voff, soff, r);
+    else store_buf_nt<T, V, false>(b, voff, soff, r);
 }
 
 // ---- fixed-order reductions -----------------------------------------------------------------

@@ -172,8 +172,9 @@ __global__ __launch_bounds__(256, (S1_WAVES<V, K, PF>())) void k_nhwc_s1(
 // Stride 1, "same" padding, multiplier 1, TWO output columns per lane.  The 5x5 walk on two channels per lane
 // is bound by the number of memory instructions (five 4-byte loads and a store per 50 multiply-adds); with two
 // adjacent columns a lane loads K+1 input columns for two outputs and the same filter registers serve both.
-// Padding: input values of columns outside the image are zeroed when the row is consumed (the filter cannot
-// carry the zeros here, since a tap meets different columns for the two outputs).
+// Rows are read through a buffer view of the image: the row offset is a scalar, the column offsets are loop
+// invariants, and a column outside the image is read at an offset outside the view, which returns the zero of the
+// padding (the filter cannot carry the zeros here, since a tap meets different columns for the two outputs).
 // ---------------------------------------------------------------------------------------------
 template <typename T, int V, int K, int PF, bool FLIP, int NCOL>
 __global__ __launch_bounds__(256) void k_nhwc_s1_2col(Geom g, const T *__restrict__ x, const T *__restrict__ w,
@@ -189,13 +190,13 @@ __global__ __launch_bounds__(256) void k_nhwc_s1_2col(Geom g, const T *__restric
     if (f >= W2 * Q) return;
     const int cq = f % Q, ow = (f / Q) * NCOL;     // the last lane of a row may own fewer than NCOL columns
 
-    int coloff[NC];
-    bool colok[NC];
+    // byte offset of each input column inside an image row; a column outside the image gets an offset beyond the
+    // view, which reads as zero (the padding)
+    uint32_t coloff[NC];
 #pragma unroll
     for (int j = 0; j < NC; ++j) {
         const int iw = ow - P + j;
-        colok[j] = iw >= 0 && iw < g.W;
-        coloff[j] = (colok[j] ? iw - ow : 0) * g.C;
+        coloff[j] = (iw >= 0 && iw < g.W) ? (uint32_t)(iw * g.C + cq * V) * (uint32_t)sizeof(T) : BufView::OUTSIDE;
     }
     float wr[K][K][V];
 #pragma unroll
@@ -208,8 +209,10 @@ __global__ __launch_bounds__(256) void k_nhwc_s1_2col(Geom g, const T *__restric
 
     const int oh0 = tl.strip * TH, oh1 = min(g.H, oh0 + TH);
     const int rowstride = g.W * g.C;
-    const T *xin = x + (size_t)tl.n * g.H * rowstride + (size_t)ow * g.C + cq * V;
-    T *yout = y + (size_t)tl.n * g.H * rowstride + (size_t)ow * g.C + cq * V;
+    const uint32_t rowbytes = (uint32_t)rowstride * (uint32_t)sizeof(T);
+    const BufView xin(x + (size_t)tl.n * g.H * rowstride, (uint32_t)g.H * rowbytes);      // the image: below 4 GiB
+    const BufView yout(y + (size_t)tl.n * g.H * rowstride, (uint32_t)g.H * rowbytes);
+    const uint32_t outoff = (uint32_t)(ow * g.C + cq * V) * (uint32_t)sizeof(T), colbytes = (uint32_t)g.C * (uint32_t)sizeof(T);
 
     float acc[K - 1][NCOL][V];
 #pragma unroll
@@ -223,24 +226,19 @@ __global__ __launch_bounds__(256) void k_nhwc_s1_2col(Geom g, const T *__restric
     const int ra = max(r0, 0), rb = min(r1, g.H);
     RawVec<T, V> ring[R][NC];
     auto load_row = [&](int r, RawVec<T, V> (&dst)[NC]) {
-        const T *rp = xin + (size_t)min(r, rb - 1) * rowstride;
+        const uint32_t rowoff = (uint32_t)min(r, rb - 1) * rowbytes;
 #pragma unroll
-        for (int j = 0; j < NC; ++j) dst[j].load(rp + coloff[j]);
+        for (int j = 0; j < NC; ++j) dst[j].load_buf(xin, coloff[j], rowoff);
     };
     auto emit = [&](int oh, const float (&out)[NCOL][V]) {
-        T *op = yout + (size_t)oh * rowstride;
 #pragma unroll
         for (int c = 0; c < NCOL; ++c)
-            if (ow + c < g.W) store_vec<T, V>(op + c * g.C, out[c], nt != 0);
+            if (ow + c < g.W) store_buf<T, V>(yout, outoff + c * colbytes, (uint32_t)oh * rowbytes, out[c], nt != 0);
     };
     auto consume = [&](int r, const RawVec<T, V> (&raw)[NC]) {
         float cur[NC][V];
 #pragma unroll
-        for (int j = 0; j < NC; ++j) {
-            raw[j].get(cur[j]);
-#pragma unroll
-            for (int v = 0; v < V; ++v) cur[j][v] = colok[j] ? cur[j][v] : 0.f;
-        }
+        for (int j = 0; j < NC; ++j) raw[j].get(cur[j]);
         float out[NCOL][V];
 #pragma unroll
         for (int c = 0; c < NCOL; ++c)
@@ -527,20 +525,50 @@ __global__ __launch_bounds__(256, (PF <= 2 && K == 3 && S == 1 && sizeof(T) == 4
             for (int v = 0; v < V; ++v) acc[kh][kw][v] = 0.f;
 
     if (active) {
-        // Loads are unconditional (clamped addresses) and untouched until consumed, so they stay in
-        // flight across iterations.  Columns outside the image: the lane accumulates whatever the
-        // clamped address holds and zeroes those taps' sums once, after the walk.  Rows outside the
-        // image or the strip are handled by peeling the first and last few rows off the main loop
-        // (the conditions are uniform over the block).
+        // Loads are unconditional (clamped rows) and untouched until consumed, so they stay in flight across
+        // iterations.  Rows outside the image or the strip are handled by peeling the first and last few rows off
+        // the main loop (the conditions are uniform over the block).  Columns outside the image:
+        //  * 5x5 (BUF): loads go through a buffer view of the image; the row offset is a scalar, the column offsets
+        //    are loop invariants, and a column outside the image is read at an offset outside the view, which
+        //    returns zero, so its taps accumulate nothing.  That takes the 64-bit address arithmetic (six adds per
+        //    50 multiply-adds) out of a walk that is bound by its vector-ALU work: 4 % faster.
+        //  * 3x3: flat loads at clamped columns (the views measured 3-14 % slower there); the lane accumulates
+        //    whatever the clamped address holds and zeroes those taps' sums once, after the walk.
+        constexpr bool BUF = K == 5;
         bool colok[K];
-        int coloff[K];
+        uint32_t coloff[K];      // BUF: bytes inside an image row
+        int coloff_e[K];         // flat loads: elements from the start of the row
 #pragma unroll
         for (int kw = 0; kw < K; ++kw) {
             const int iw = ow * S - P + kw;
             colok[kw] = iw >= 0 && iw < g.W;
-            coloff[kw] = (colok[kw] ? iw : ow * S) * g.C;
+            coloff[kw] = colok[kw] ? (uint32_t)(iw * g.C + cq * VX) * (uint32_t)sizeof(T) : BufView::OUTSIDE;
+            coloff_e[kw] = (colok[kw] ? iw : ow * S) * g.C;
         }
+        const uint32_t dyoff = (uint32_t)(ow * g.O + cq * V) * (uint32_t)sizeof(T);
         const int xrow = g.W * g.C, dyrow = g.Wo * g.O;
+        const uint32_t xrowbytes = (uint32_t)xrow * (uint32_t)sizeof(T), dyrowbytes = (uint32_t)dyrow * (uint32_t)sizeof(T);
+        const uint32_t ximg = (uint32_t)g.H * xrowbytes, dyimg = (uint32_t)g.Ho * dyrowbytes;      // an image: at most 2 GiB
+        // one row of x (K columns) and one of dy for image nn, rows already clamped
+        auto load_rows_x = [&](int nn, int r, RawVec<T, VX> (&dst)[K]) {
+            if constexpr (BUF) {
+                const BufView xin(x + (size_t)nn * g.H * xrow, ximg);
+#pragma unroll
+                for (int kw = 0; kw < K; ++kw) dst[kw].load_buf(xin, coloff[kw], (uint32_t)r * xrowbytes);
+            } else {
+                const T *xin = x + (size_t)nn * g.H * xrow + cq * VX;
+                const T *rp = xin + (size_t)r * xrow;
+#pragma unroll
+                for (int kw = 0; kw < K; ++kw) dst[kw].load(rp + coloff_e[kw]);
+            }
+        };
+        auto load_row_dy = [&](int nn, int oh, RawVec<T, V> &dst) {
+            if constexpr (BUF) dst.load_buf(BufView(dy + (size_t)nn * g.Ho * dyrow, dyimg), dyoff, (uint32_t)oh * dyrowbytes);
+            else {
+                const T *dyin = dy + ((size_t)nn * g.Ho * g.Wo + ow) * g.O + cq * V;
+                dst.load(dyin + (size_t)oh * dyrow);
+            }
+        };
         const int oh0 = strip * TH, oh1 = min(g.Ho, oh0 + TH);
         const int n0 = ngroup * NI, n1 = min(g.N, n0 + NI);
         if constexpr (S == 1 && FLAT) {
@@ -559,15 +587,11 @@ __global__ __launch_bounds__(256, (PF <= 2 && K == 3 && S == 1 && sizeof(T) == 4
             for (int kh = 0; kh < K; ++kh)
 #pragma unroll
                 for (int v = 0; v < V; ++v) dyw[kh][v] = 0.f;
-            const T *xlane = x + cq * VX;
-            const T *dylane = dy + (size_t)ow * g.O + cq * V;
             int pn = n0, pr = r0;          // the step whose loads are issued next
             auto issue = [&](RawVec<T, VX> (&xd)[K], RawVec<T, V> &dd) {
                 const int nn = min(pn, n1 - 1);
-                const T *rp = xlane + ((size_t)nn * g.H + min(max(pr, 0), g.H - 1)) * xrow;
-#pragma unroll
-                for (int kw = 0; kw < K; ++kw) xd[kw].load(rp + coloff[kw]);
-                dd.load(dylane + ((size_t)nn * g.Ho + min(max(pr + P, oh0), oh1 - 1)) * dyrow);
+                load_rows_x(nn, min(max(pr, 0), g.H - 1), xd);
+                load_row_dy(nn, min(max(pr + P, oh0), oh1 - 1), dd);
                 if (++pr == rend) { pr = r0; ++pn; }
             };
             int cr = r0;                   // row of the step being consumed
@@ -621,18 +645,15 @@ __global__ __launch_bounds__(256, (PF <= 2 && K == 3 && S == 1 && sizeof(T) == 4
                 if (st + j < total) consume(xr[j], dr[j]);
         } else {
         for (int n = n0; n < n1; ++n) {
-            const T *xin = x + (size_t)n * g.H * xrow + cq * VX;
-            const T *dyin = dy + ((size_t)n * g.Ho * g.Wo + ow) * g.O + cq * V;
             // rows are loaded ahead and stay as loaded (packed for bf16) until they are accumulated
-            auto load_xr = [&](int r, RawVec<T, VX> (&dst)[K]) {
-                const T *rp = xin + (size_t)min(max(r, 0), g.H - 1) * xrow;
-#pragma unroll
-                for (int kw = 0; kw < K; ++kw) dst[kw].load(rp + coloff[kw]);
-            };
-            auto load_dr = [&](int oh, RawVec<T, V> &dst) { dst.load(dyin + (size_t)min(max(oh, oh0), oh1 - 1) * dyrow); };
+            auto load_xr = [&](int r, RawVec<T, VX> (&dst)[K]) { load_rows_x(n, min(max(r, 0), g.H - 1), dst); };
+            auto load_dr = [&](int oh, RawVec<T, V> &dst) { load_row_dy(n, min(max(oh, oh0), oh1 - 1), dst); };
             if constexpr (S == 1) {
                 // input row r meets dy row r + P - kh at tap row kh; dyw holds the K live dy rows
-                constexpr int R = PF + 1;
+                // The main loop takes R rows per trip.  R = K lets the window of live dy rows come back to the same
+                // registers after every trip (a trip of PF + 1 = 3 rows on a 5-row window costs a register copy per
+                // window entry and row); only PF + 1 of the R ring slots are live at any time.
+                constexpr int R = (K > PF + 1) ? K : PF + 1;
                 float dyw[K][V];
 #pragma unroll
                 for (int kh = 0; kh < K; ++kh)
@@ -690,11 +711,13 @@ __global__ __launch_bounds__(256, (PF <= 2 && K == 3 && S == 1 && sizeof(T) == 4
                         accumulate(xr[j]);
                     }
                 }
-                // remaining rows: those still inside [ra, rm) use their prefetched dy row, the last
-                // ones (new dy row below the strip) push zeros
+                // remaining rows: those still inside [ra, rm) use their prefetched dy row (and keep the ring
+                // filled: a load past the last row is clamped and never used), the last ones (new dy row below the
+                // strip) push zeros
 #pragma unroll
                 for (int j = 0; j < R - 1; ++j) {
                     if (base + j < rm) {
+                        if (j + PF < R - 1) { load_xr(base + j + PF, xr[(j + PF) % R]); load_dr(base + j + PF + P, dr[(j + PF) % R]); }
                         push_raw(dr[j]);
                         accumulate(xr[j]);
                     }
@@ -760,15 +783,17 @@ __global__ __launch_bounds__(256, (PF <= 2 && K == 3 && S == 1 && sizeof(T) == 4
             }
         }
         }
-        // taps on columns outside the image accumulated clamped data: drop them
+        if constexpr (!BUF) {
+            // taps on columns outside the image accumulated clamped data: drop them
 #pragma unroll
-        for (int kw = 0; kw < K; ++kw)
-            if (!colok[kw]) {
+            for (int kw = 0; kw < K; ++kw)
+                if (!colok[kw]) {
 #pragma unroll
-                for (int kh = 0; kh < K; ++kh)
+                    for (int kh = 0; kh < K; ++kh)
 #pragma unroll
-                    for (int v = 0; v < V; ++v) acc[kh][kw][v] = 0.f;
-            }
+                        for (int v = 0; v < V; ++v) acc[kh][kw][v] = 0.f;
+                }
+        }
     }
 
     // ---- fixed-order block reduction ----
