@@ -527,11 +527,9 @@ bool nchws_supported(const Geom &g, int pass)
     const bool k3 = g.K == 3 && g.p == 1 && (g.s == 1 || g.s == 2);
     const bool k5 = g.K == 5 && g.p == 2 && g.s == 1;   // 5x5 stride 1 (backward-data runs the forward kernel with the rotated filter)
     if (!k3 && !k5) return false;
-    if (g.K == 5 && g.W == 28) return false;     // 28-wide rows with 25 taps: too many registers per lane
     if (!(g.W == 7 || g.W == 14 || g.W == 28 || (g.K == 3 && (g.W == 8 || (g.W == 4 && g.s == 1))))) return false;
     if (g.s == 2 && (g.W % 2 != 0 || g.H % 2 != 0)) return false;
     if (g.Ho > 32 || g.H > 32) return false;
-    (void)pass;
     return true;
 }
 
@@ -569,7 +567,7 @@ static hipError_t go_fwd(const Geom &g, const void *x, const void *w, void *y, b
 #define GO(KK, SS, WW, FL) hipLaunchKernelGGL((k_nchws_fwd<T, KK, SS, WW, FL>), dim3(nblocks), dim3(256), lds, st, g, \
                                               (const T *)x, (const T *)w, (T *)y, U, nplanes, nblocks, nt, tpb)
 #define PICK(KK, SS, WW) if (g.K == KK && g.s == SS && g.W == WW) { if (flip) GO(KK, SS, WW, true); else GO(KK, SS, WW, false); return hipGetLastError(); }
-    PICK(3, 1, 7) PICK(3, 1, 14) PICK(3, 1, 28) PICK(3, 2, 14) PICK(3, 2, 28) PICK(5, 1, 7) PICK(5, 1, 14)
+    PICK(3, 1, 7) PICK(3, 1, 14) PICK(3, 1, 28) PICK(3, 2, 14) PICK(3, 2, 28) PICK(5, 1, 7) PICK(5, 1, 14) PICK(5, 1, 28)
     PICK(3, 1, 4) PICK(3, 1, 8) PICK(3, 2, 8)
 #undef PICK
 #undef GO
@@ -649,6 +647,7 @@ static hipError_t go_bwd_filter(const Geom &g, const void *x, const void *dy, fl
     else if (g.K == 3 && g.s == 2 && g.W == 28) GO(3, 2, 28);
     else if (g.K == 5 && g.s == 1 && g.W == 7) GO(5, 1, 7);
     else if (g.K == 5 && g.s == 1 && g.W == 14) GO(5, 1, 14);
+    else if (g.K == 5 && g.s == 1 && g.W == 28) GO(5, 1, 28);
     else if (g.K == 3 && g.s == 1 && g.W == 4) GO(3, 1, 4);
     else if (g.K == 3 && g.s == 1 && g.W == 8) GO(3, 1, 8);
     else if (g.K == 3 && g.s == 2 && g.W == 8) GO(3, 2, 8);

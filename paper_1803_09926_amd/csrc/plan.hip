@@ -95,15 +95,17 @@ static bool fits_bwd_filter(const Geom &g, int tr) { return nchw_bwd_filter_part
 // benchmark step: the filter gradient always to the small-plane kernel (37 against 46 us on the 28x28x256 layer at
 // batch 128, 23 against 29 us on its stride-2 sibling), the fp32 forward and the fp32 input gradient at stride 2
 // too (stride-1 forward 42 against 47 us, stride-2 forward 28 against 31 us, stride-2 input gradient 21 against
-// 22 us); the stride-1 input gradient and everything else in bf16 stay with the row walk.
+// 22 us); the fp32 stride-1 input gradient stays with the row walk; bf16 see below.
 static bool use_small(const Geom &g, int dtype, int pass)
 {
     if (!nchws_supported(g, pass)) return false;
     if (g.W <= 14 || nchwd_vec(g, dtype, pass) == 0) return true;
     if (const char *e = tune_env("DWCONV_TUNE_S28")) return atoi(e) == 1;
     if (pass == 2) return true;
-    if (dtype != DT_F32) return false;
-    return pass == 0 || (pass == 1 && g.s == 2);
+    if (dtype == DT_F32) return pass == 0 || (pass == 1 && g.s == 2);
+    // bf16 at stride 1 (the 28x28 layer at batch 256): 3x3 forward 54 against 73 us, 3x3 input gradient 47 against
+    // 59 us, 5x5 forward 71 against 74 us; the 5x5 input gradient stays with the row walk (63 against 64 us)
+    return g.s == 1 && (g.K == 3 || pass == 0);
 }
 
 Plan plan_fwd(const Geom &g, int layout, int dtype)

@@ -89,6 +89,9 @@ AWKWARD = [
     (3, Layer("small_h6_w8_s2", 8, 6, 8, 3, 2, 1)),
     (3, Layer("small_h10_w14_s2", 8, 10, 14, 3, 2, 1)),
     (2, Layer("small_k5_h9_w14", 8, 9, 14, 5, 1, 2)),
+    # 5x5 on 28-wide rows: small-plane forward and filter gradient, row-walk input gradient in bf16
+    (3, Layer("small_k5_h28_w28", 12, 28, 28, 5, 1, 2)),
+    (2, Layer("small_k5_h17_w28", 5, 17, 28, 5, 1, 2)),
     # tall stride-2 maps (the NHWC fused backward kernel takes even maps of 112 rows and more)
     (2, Layer("s2_h112_w12", 8, 112, 12, 3, 2, 1)),
     (3, Layer("s2_h114_w10_c20", 20, 114, 10, 3, 2, 1)),
