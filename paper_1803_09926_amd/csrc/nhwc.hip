@@ -689,17 +689,37 @@ __global__ __launch_bounds__(256, (PF <= 2 && K == 3 && S == 1 && sizeof(T) == 4
                 float zero[V];
 #pragma unroll
                 for (int v = 0; v < V; ++v) zero[v] = 0.f;
-                // rows above the image: their dy rows enter the window, nothing is accumulated
-                for (int r = r0; r < ra; ++r) {
-                    RawVec<T, V> d;
-                    load_dr(r + P, d);
-                    if (r + P >= oh1) push_dy(zero);
-                    else push_raw(d);
-                }
+                // 5x5 bf16: the image's first loads all go out together, i.e. the first PF rows of the walk and the
+                // dy rows of the (up to P) rows above the image, which enter the window without anything being
+                // accumulated: one memory latency per image instead of one per row above it plus one for the walk.
+                // The other variants have no registers to spare for it (the fp32 3x3 kernel would spill).
+                constexpr bool TOGETHER = K == 5 && sizeof(T) == 2;
                 RawVec<T, VX> xr[R][K];
                 RawVec<T, V> dr[R];
+                if constexpr (TOGETHER) {
+                    RawVec<T, V> above[P];
 #pragma unroll
-                for (int j = 0; j < PF; ++j) { load_xr(ra + j, xr[j]); load_dr(ra + j + P, dr[j]); }
+                    for (int j = 0; j < PF; ++j) { load_xr(ra + j, xr[j]); load_dr(ra + j + P, dr[j]); }
+#pragma unroll
+                    for (int i = 0; i < P; ++i)
+                        if (r0 + i < ra) load_dr(r0 + i + P, above[i]);
+#pragma unroll
+                    for (int i = 0; i < P; ++i)
+                        if (r0 + i < ra) {
+                            if (r0 + i + P >= oh1) push_dy(zero);
+                            else push_raw(above[i]);
+                        }
+                } else {
+                    // rows above the image: their dy rows enter the window, nothing is accumulated
+                    for (int r = r0; r < ra; ++r) {
+                        RawVec<T, V> d;
+                        load_dr(r + P, d);
+                        if (r + P >= oh1) push_dy(zero);
+                        else push_raw(d);
+                    }
+#pragma unroll
+                    for (int j = 0; j < PF; ++j) { load_xr(ra + j, xr[j]); load_dr(ra + j + P, dr[j]); }
+                }
                 int base = ra;
 #pragma unroll 1
                 for (; base + R <= rm; base += R) {
