@@ -156,7 +156,9 @@ __device__ __forceinline__ void flat_store(T *__restrict__ dst, int g0, int g1, 
 // ---------------------------------------------------------------------------------------------
 // TPB tiles of U planes per block, one after the other (tile lb*TPB + i): the next tile's planes are loaded into
 // registers while the current tile is computed from LDS and written out, so a block's memory latency is paid once.
-template <typename T, int K, int S, int W, bool FLIP>
+// INPLACE: the outputs (a lane's whole row, held in registers) go back into the LDS area of the inputs once every
+// lane has read its rows, which halves the block's LDS and doubles the blocks per CU on 28-wide planes.
+template <typename T, int K, int S, int W, bool FLIP, bool INPLACE>
 __global__ __launch_bounds__(256) void k_nchws_fwd(Geom g, const T *__restrict__ x, const T *__restrict__ w,
                                                    T *__restrict__ y, int U, int nplanes, unsigned nblocks, int nt, int TPB)
 {
@@ -167,7 +169,7 @@ __global__ __launch_bounds__(256) void k_nchws_fwd(Geom g, const T *__restrict__
     const int HW = g.H * W, HoWo = g.Ho * WO;
     const unsigned lb = xcd_remap(blockIdx.x, nblocks);
     float *lin = reinterpret_cast<float *>(smem4);
-    float *lout = lin + ((U * HW + 2 * VE + 3) & ~3);
+    float *lout = INPLACE ? lin : lin + ((U * HW + 2 * VE + 3) & ~3);
     const int total = g.N * g.C * HW;
     const int p = threadIdx.x / g.Ho, oh = threadIdx.x - p * g.Ho;
 
@@ -192,6 +194,7 @@ __global__ __launch_bounds__(256) void k_nchws_fwd(Geom g, const T *__restrict__
         flat_issue<T>(x, total, q0 * HW, (q0 + nq) * HW, regs);
     }
 
+    float out[WO];
     if (p < np) {
         const int c = (p0 + p) % g.C;
         float wr[K][K];
@@ -207,7 +210,6 @@ __global__ __launch_bounds__(256) void k_nchws_fwd(Geom g, const T *__restrict__
             }
         }
         const float *pl = lin + (gi0 & (VE - 1)) + p * HW;
-        float out[WO];
 #pragma unroll
         for (int j = 0; j < WO; ++j) out[j] = 0.f;
 #pragma unroll
@@ -225,9 +227,19 @@ __global__ __launch_bounds__(256) void k_nchws_fwd(Geom g, const T *__restrict__
                     if (iw >= 0 && iw < W) out[j] = fmaf(wr[kh][kw], row[iw], out[j]);
                 }
         }
-        float *op = lout + (go0 & (VE - 1)) + p * HoWo + oh * WO;
+        if constexpr (!INPLACE) {
+            float *op = lout + (go0 & (VE - 1)) + p * HoWo + oh * WO;
 #pragma unroll
-        for (int j = 0; j < WO; ++j) op[j] = out[j];
+            for (int j = 0; j < WO; ++j) op[j] = out[j];
+        }
+    }
+    if constexpr (INPLACE) {
+        __syncthreads();                            // every lane has read its input rows
+        if (p < np) {
+            float *op = lout + (go0 & (VE - 1)) + p * HoWo + oh * WO;
+#pragma unroll
+            for (int j = 0; j < WO; ++j) op[j] = out[j];
+        }
     }
     __syncthreads();
 
@@ -551,7 +563,10 @@ static hipError_t go_fwd(const Geom &g, const void *x, const void *w, void *y, b
     // elements): the 28-wide stride-2 forward takes 10 planes per tile instead of 15 and is 13 % faster for it
     while (U > 1 && U * HW + VE > 8192) --U;
     if (const char *e = tune_env("DWCONV_TUNE_SU")) { if (atoi(e) >= 1 && atoi(e) < U) U = atoi(e); }
-    const size_t lds = lds_bytes_for(U, HW, HoWo, VE);
+    // outputs back into the input area when two areas would leave room for at most three blocks per CU
+    bool inplace = g.W == 28 && lds_bytes_for(U, HW, HoWo, VE) > 40 * 1024;
+    if (const char *e = tune_env("DWCONV_TUNE_SINPLACE")) inplace = g.W == 28 && atoi(e) != 0;
+    const size_t lds = inplace ? lds_bytes_for(U, HW, 0, VE) : lds_bytes_for(U, HW, HoWo, VE);
     const int nplanes = g.N * g.C;
     const int ntiles = cdiv(nplanes, U);
     // tiles per block: two on large launches (measured against 1, 3 and 4 on the 14x14 and 7x7 layers at batch 128:
@@ -564,11 +579,14 @@ static hipError_t go_fwd(const Geom &g, const void *x, const void *w, void *y, b
     const unsigned nblocks = (unsigned)cdiv(ntiles, tpb > 0 ? tpb : 1);
     // the block writes one contiguous range with whole 16-byte vectors: streamed
     const int nt = stream_stores(flip ? "NCHW_SMALL_BWD" : "NCHW_SMALL_FWD", (long long)nplanes * HoWo * sizeof(T), 0);
-#define GO(KK, SS, WW, FL) hipLaunchKernelGGL((k_nchws_fwd<T, KK, SS, WW, FL>), dim3(nblocks), dim3(256), lds, st, g, \
-                                              (const T *)x, (const T *)w, (T *)y, U, nplanes, nblocks, nt, tpb)
-#define PICK(KK, SS, WW) if (g.K == KK && g.s == SS && g.W == WW) { if (flip) GO(KK, SS, WW, true); else GO(KK, SS, WW, false); return hipGetLastError(); }
+#define GO(KK, SS, WW, FL, IP) hipLaunchKernelGGL((k_nchws_fwd<T, KK, SS, WW, FL, IP>), dim3(nblocks), dim3(256), lds, st, g, \
+                                                  (const T *)x, (const T *)w, (T *)y, U, nplanes, nblocks, nt, tpb)
+#define PICK(KK, SS, WW) if (g.K == KK && g.s == SS && g.W == WW && !inplace) { if (flip) GO(KK, SS, WW, true, false); else GO(KK, SS, WW, false, false); return hipGetLastError(); }
+#define PICKIP(KK, SS, WW) if (g.K == KK && g.s == SS && g.W == WW && inplace) { if (flip) GO(KK, SS, WW, true, true); else GO(KK, SS, WW, false, true); return hipGetLastError(); }
     PICK(3, 1, 7) PICK(3, 1, 14) PICK(3, 1, 28) PICK(3, 2, 14) PICK(3, 2, 28) PICK(5, 1, 7) PICK(5, 1, 14) PICK(5, 1, 28)
     PICK(3, 1, 4) PICK(3, 1, 8) PICK(3, 2, 8)
+    PICKIP(3, 1, 28) PICKIP(3, 2, 28) PICKIP(5, 1, 28)
+#undef PICKIP
 #undef PICK
 #undef GO
     return hipErrorInvalidValue;

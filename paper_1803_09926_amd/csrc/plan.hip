@@ -103,9 +103,9 @@ static bool use_small(const Geom &g, int dtype, int pass)
     if (const char *e = tune_env("DWCONV_TUNE_S28")) return atoi(e) == 1;
     if (pass == 2) return true;
     if (dtype == DT_F32) return pass == 0 || (pass == 1 && g.s == 2);
-    // bf16 at stride 1 (the 28x28 layer at batch 256): 3x3 forward 54 against 73 us, 3x3 input gradient 47 against
-    // 59 us, 5x5 forward 71 against 74 us; the 5x5 input gradient stays with the row walk (63 against 64 us)
-    return g.s == 1 && (g.K == 3 || pass == 0);
+    // bf16 at stride 1 (the 28x28 layer at batch 256, outputs staged in place): 3x3 forward 46 against 73 us, 3x3
+    // input gradient 39 against 59 us, 5x5 forward 56 against 74 us, 5x5 input gradient 50 against 63 us
+    return g.s == 1;
 }
 
 Plan plan_fwd(const Geom &g, int layout, int dtype)

@@ -41,15 +41,15 @@ VARIANT_KERNELS = {
     "bwd_filter:nchw_rowwalk_bwd_filter_k3s1": [r"k_nchwd_bwd_filter_k3<[\w ]+, \d+, 1>", r"k_nchwd_bwd_filter_s1_bf16<\d+, 3>"],
     "bwd_filter:nchw_rowwalk_bwd_filter_k3s2": [r"k_nchwd_bwd_filter_k3<[\w ]+, \d+, 2>"],
     "bwd_filter:nchw_rowwalk_bwd_filter_k5s1": [r"k_nchwd_bwd_filter_s1<[\w ]+, \d+, 5>", r"k_nchwd_bwd_filter_s1_bf16<\d+, 5>"],
-    # k_nchws_fwd<T, K, S, W, FLIP>, k_nchws_bwd_filter<T, K, S, W>
-    "fwd:nchw_smallplane_k3s1": [r"k_nchws_fwd<[\w ]+, 3, 1, \d+, false>"],
-    "bwd_data:nchw_smallplane_k3s1_flip": [r"k_nchws_fwd<[\w ]+, 3, 1, \d+, true>"],
-    "fwd:nchw_smallplane_fwd_k3s2": [r"k_nchws_fwd<[\w ]+, 3, 2, \d+, false>"],
+    # k_nchws_fwd<T, K, S, W, FLIP, INPLACE>, k_nchws_bwd_filter<T, K, S, W>
+    "fwd:nchw_smallplane_k3s1": [r"k_nchws_fwd<[\w ]+, 3, 1, \d+, false, \w+>"],
+    "bwd_data:nchw_smallplane_k3s1_flip": [r"k_nchws_fwd<[\w ]+, 3, 1, \d+, true, \w+>"],
+    "fwd:nchw_smallplane_fwd_k3s2": [r"k_nchws_fwd<[\w ]+, 3, 2, \d+, false, \w+>"],
     "bwd_data:nchw_smallplane_bwd_data_k3s2": [r"k_nchws_bwd_data_s2<"],
     "bwd_filter:nchw_smallplane_bwd_filter_k3s1": [r"k_nchws_bwd_filter<[\w ]+, 3, 1, \d+>"],
     "bwd_filter:nchw_smallplane_bwd_filter_k3s2": [r"k_nchws_bwd_filter<[\w ]+, 3, 2, \d+>"],
-    "fwd:nchw_smallplane_k5s1": [r"k_nchws_fwd<[\w ]+, 5, 1, \d+, false>"],
-    "bwd_data:nchw_smallplane_k5s1_flip": [r"k_nchws_fwd<[\w ]+, 5, 1, \d+, true>"],
+    "fwd:nchw_smallplane_k5s1": [r"k_nchws_fwd<[\w ]+, 5, 1, \d+, false, \w+>"],
+    "bwd_data:nchw_smallplane_k5s1_flip": [r"k_nchws_fwd<[\w ]+, 5, 1, \d+, true, \w+>"],
     "bwd_filter:nchw_smallplane_bwd_filter_k5s1": [r"k_nchws_bwd_filter<[\w ]+, 5, 1, \d+>"],
     # whole backward pass in one kernel (dwconv_bwd)
     "bwd:nhwc_bwd_fused_k3s1": [r"k_nhwc_bwd_fused_k3s1<"],
