@@ -55,7 +55,9 @@ static int nhwc_pf(const Geom &g, int dtype)
 static int pick_th(int rows, int stride, int dflt1 = 14, int dflt2 = 0)
 {
     // stride 2: 7 output rows, 4 on tall maps (56 output rows and more: 1-4 % on the 112x112 and 56x56 layers);
-    // the NCHW input gradient on tall maps 2 (its 112x112 layer: 118 -> 110 us inside the step; NHWC lost 1 % with it)
+    // the input gradient takes 4 dy rows on every map (28 dy rows: NHWC 45.2 -> 42.2 us, NCHW 44.0 -> 42.5 us; 14 dy
+    // rows: NHWC 21.1 -> 19.5 us) and in NCHW 2 on tall maps (its 112x112 layer: 118 -> 110 us inside the step; NHWC
+    // lost 1 % with it)
     if (dflt2 == 0) dflt2 = rows >= 56 ? 4 : 7;
     const int target = stride == 1 ? tune("DWCONV_TUNE_TH1", dflt1) : tune("DWCONV_TUNE_TH2", dflt2);
     // balanced strips: the number of strips that brings their height closest to the target, then equal
@@ -150,7 +152,7 @@ Plan plan_bwd_data(const Geom &g, int layout, int dtype)
         if (V) {
             pl.a = V;
             if (g.s == 1) { pl.variant = V_NCHWD_S1; pl.b = pick_th(g.H, 1, nchwd_th1(dtype, g.W)); pl.name = g.K == 3 ? "nchw_rowwalk_k3s1_flip" : "nchw_rowwalk_k5s1_flip"; }
-            else { pl.variant = V_NCHWD_K3S2; pl.b = pick_th(g.Ho, 2, 14, g.Ho >= 56 ? 2 : 0); pl.name = "nchw_rowwalk_bwd_data_k3s2"; }
+            else { pl.variant = V_NCHWD_K3S2; pl.b = pick_th(g.Ho, 2, 14, g.Ho >= 56 ? 2 : 4); pl.name = "nchw_rowwalk_bwd_data_k3s2"; }
             return pl;
         }
         if (g.m == 1 && same_pad_s1(g)) {
@@ -168,7 +170,7 @@ Plan plan_bwd_data(const Geom &g, int layout, int dtype)
             pl.variant = V_NHWC_S1; pl.a = V; pl.b = pick_th(g.H, 1, nhwc_th1(dtype));
             pl.name = g.m == 2 ? "nhwc_rowwalk_k3s1_flip_m2" : (g.K == 3 ? "nhwc_rowwalk_k3s1_flip" : "nhwc_rowwalk_k5s1_flip");
         } else if (V && k3s2p1(g)) {
-            pl.variant = V_NHWC_K3S2; pl.a = V; pl.b = pick_th(g.Ho, 2);
+            pl.variant = V_NHWC_K3S2; pl.a = V; pl.b = pick_th(g.Ho, 2, 14, 4);
             pl.name = "nhwc_rowwalk_bwd_data_k3s2";
         }
     }
