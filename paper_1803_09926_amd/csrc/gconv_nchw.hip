@@ -29,6 +29,13 @@ template <> struct LdsW<4> {
         r[0] = q.x; r[1] = q.y; r[2] = q.z; r[3] = q.w;
     }
 };
+template <> struct LdsW<8> {
+    static __device__ __forceinline__ void get(const float *p, float (&r)[8])
+    {
+        const float4 q = *reinterpret_cast<const float4 *>(p), t = *reinterpret_cast<const float4 *>(p + 4);
+        r[0] = q.x; r[1] = q.y; r[2] = q.z; r[3] = q.w; r[4] = t.x; r[5] = t.y; r[6] = t.z; r[7] = t.w;
+    }
+};
 template <> struct LdsW<2> {
     static __device__ __forceinline__ void get(const float *p, float (&r)[2])
     {
@@ -314,12 +321,12 @@ bool gconv_nchw_supported(const GGeom &g)
 
 // strip height: the tallest of whole plane / 28 / 14 / 7 rows that still gives the launch about two
 // blocks per compute unit
-static int gconv_pick_th(const GGeom &g, long long blocks_per_lane_block_row, bool walk)
+static int gconv_pick_th(const GGeom &g, long long blocks_per_lane_block_row, bool walk, int v = 0)
 {
     const int forced = gtune("DWCONV_TUNE_GTH", 0);
     if (forced > 0) return forced < g.H ? forced : g.H;
     const int cands[4] = {g.H, 28, 14, 7};
-    const int ncv = g.W / pick_v(g.W, walk);
+    const int ncv = g.W / (v > 0 ? v : pick_v(g.W, walk));
     const long long want = gtune("DWCONV_TUNE_GBLOCKS", 512);
     for (int i = 0; i < 4; ++i) {
         const int th = cands[i] < g.H ? cands[i] : g.H;
@@ -334,9 +341,13 @@ hipError_t gconv_nchw_s1(const GGeom &g, int dtype, const void *in, const void *
     if (!gconv_nchw_supported(g)) return hipErrorInvalidValue;
     const int CI = flip ? g.Og : g.Cg, CO = flip ? g.Cg : g.Og;
     const int CIN_T = flip ? g.O : g.C, COUT_T = flip ? g.C : g.O;
-    const int OB = pick_ob(CO), V = pick_v(g.W, true);
+    int V = pick_v(g.W, true);
+    // bf16 on wide rows: eight columns per lane, so that a lane's accesses are 16 bytes as in fp32
+    if (dtype == DT_BF16 && V == 4 && g.W % 8 == 0 && gtune("DWCONV_TUNE_GV8", 1) != 0) V = 8;
+    // all eight output channels of a group of 8 in one block on two-column lanes (the input is then read once)
+    const int OB = (V == 2 && CO == 8 && gtune("DWCONV_TUNE_GOB8", 1) != 0) ? 8 : pick_ob(CO);
     const int nchunks = CO / OB;
-    const int TH = gconv_pick_th(g, (long long)g.G * nchunks, true);
+    const int TH = gconv_pick_th(g, (long long)g.G * nchunks, true, V);
     const int nstrips = (g.H + TH - 1) / TH, ncv = g.W / V;
     const long long nl = (long long)g.N * nstrips * ncv;
     const long long nlb = (nl + 255) / 256;
@@ -362,8 +373,9 @@ hipError_t gconv_nchw_s1(const GGeom &g, int dtype, const void *in, const void *
     } while (0)
 #define GO3(T, VV, OBB) do { if (R == 4) GO5(T, VV, OBB, 4); else if (R == 2) GO5(T, VV, OBB, 2); else GO5(T, VV, OBB, 1); } while (0)
 #define GO2(T, VV) do { if (OB == 4) GO3(T, VV, 4); else if (OB == 2) GO3(T, VV, 2); else GO3(T, VV, 1); } while (0)
-    if (dtype == DT_F32) { if (V == 4) GO2(float, 4); else GO2(float, 2); }
-    else                 { if (V == 4) GO2(bf16_t, 4); else GO2(bf16_t, 2); }
+    if (OB == 8) { if (dtype == DT_F32) GO3(float, 2, 8); else GO3(bf16_t, 2, 8); }
+    else if (dtype == DT_F32) { if (V == 4) GO2(float, 4); else GO2(float, 2); }
+    else                 { if (V == 8) GO2(bf16_t, 8); else if (V == 4) GO2(bf16_t, 4); else GO2(bf16_t, 2); }
 #undef GO2
 #undef GO3
 #undef GO5
