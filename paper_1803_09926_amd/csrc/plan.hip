@@ -216,7 +216,8 @@ static bool plan_bwd_filter_nchwd(const Geom &g, int dtype, Plan &pl)
     return true;
 }
 
-Plan plan_bwd_filter(const Geom &g, int layout, int dtype)
+// force_v > 0: channels per lane of the NHWC kernel (the fused backward kernel has four in either type)
+static Plan plan_bwd_filter_v(const Geom &g, int layout, int dtype, int force_v)
 {
     Plan pl = {V_GENERIC, generic_bwd_filter_parts(g), 0, 0, 0, "generic"};
     if (layout == LAYOUT_NCHW) {
@@ -247,6 +248,7 @@ Plan plan_bwd_filter(const Geom &g, int layout, int dtype)
         // bf16 on small planes: four channels per lane (124 registers, four wavefronts per SIMD) measured faster
         // than eight (182 registers, two wavefronts)
         if (V == 8 && tune("DWCONV_TUNE_WV", g.W <= 14 ? 4 : 8) == 4) V = 4;
+        if (force_v > 0 && V >= force_v) V = force_v;
         if (V && (same_pad_s1(g) || k3s2p1(g))) {
             // One block = 256 lanes over (columns x channel-vectors) x one strip x NI images.  Long
             // walks win (fewer partials, less stage-2 work): start from whole columns and one image
@@ -284,14 +286,18 @@ Plan plan_bwd_filter(const Geom &g, int layout, int dtype)
     return pl;
 }
 
+Plan plan_bwd_filter(const Geom &g, int layout, int dtype) { return plan_bwd_filter_v(g, layout, dtype, 0); }
+
 Plan plan_bwd(const Geom &g, int layout, int dtype)
 {
     Plan pl = {V_GENERIC, 0, 0, 0, 0, "separate"};
     if (layout == LAYOUT_NHWC && !tune_env("DWCONV_TUNE_NOFUSE")) {
-        const int V = nhwc_vec(g, dtype);
+        // the fused kernel takes four channels per lane in either type (bf16 with eight would need more than 256 registers)
+        int V = nhwc_vec(g, dtype);
+        if (V == 8 && g.W <= tune("DWCONV_TUNE_FUSE_BF16W", 14)) V = 4;
         if (V && nhwc_bwd_fused_supported(g, dtype, V)) {
             // tiling of the filter gradient: its block count and partial sums decide
-            const Plan pf = plan_bwd_filter(g, layout, dtype);
+            const Plan pf = plan_bwd_filter_v(g, layout, dtype, V);
             if (pf.variant == V_NHWC_BWD_FILTER && pf.a == V) {
                 pl = pf;
                 pl.variant = V_NHWC_BWD_FUSED;
