@@ -24,13 +24,11 @@ static int nhwc_vec(const Geom &g, int dtype)
     // multiplier 2 has a fast path for 3x3 stride 1 only; the vector counts OUTPUT channels
     if (g.m == 2) { if (!(g.K == 3 && g.s == 1 && g.p == 1)) return 0; }
     else if (g.m != 1) return 0;
-    // the kernels address one image through a buffer view of at most 2 GiB
-    const long long es = dtype == DT_F32 ? 4 : 2, lim = 1LL << 31;
-    if ((long long)g.H * g.W * g.C * es > lim || (long long)g.Ho * g.Wo * g.O * es > lim) return 0;
     if (dtype == DT_F32) return g.O % 4 == 0 ? 4 : 0;
     // 5x5: 25 taps x 8 channels would not fit in registers; 2 channels per lane take 110 registers
-    // instead of the 208 of 4 channels and measured 1.25x faster
-    if (g.K == 5) return g.O % 2 == 0 ? 2 : 0;
+    // instead of the 208 of 4 channels and measured 1.25x faster.  These kernels address one image through a
+    // buffer view of at most 2 GiB.
+    if (g.K == 5) return (g.O % 2 == 0 && (long long)g.H * g.W * g.C * 2 <= (1LL << 31)) ? 2 : 0;
     return g.O % 8 == 0 ? 8 : (g.O % 4 == 0 ? 4 : 0);
 }
 

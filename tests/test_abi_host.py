@@ -163,6 +163,21 @@ def test_whole_backward_variant_names():
     assert dw.variant_name(dw.desc(128, 512, 14, 14, 3, 2, 1, 1, dw.NCHW, dw.F32), 3) == "separate"      # stride 2
     assert dw.variant_name(dw.desc(128, 32, 112, 112, 3, 1, 1, 1, dw.NCHW, dw.BF16), 3) == "separate"
     assert dw.variant_name(dw.desc(2, 6, 9, 9, 3, 1, 1, 1, dw.NHWC, dw.F32), 3) == "separate"
+    # bf16 NHWC: the fused kernels (four channels per lane) on planes of up to 14 columns, two passes on wider maps
+    assert dw.variant_name(dw.desc(256, 512, 14, 14, 3, 1, 1, 1, dw.NHWC, dw.BF16), 3) == "nhwc_bwd_fused_k3s1"
+    assert dw.variant_name(dw.desc(256, 512, 14, 14, 3, 2, 1, 1, dw.NHWC, dw.BF16), 3) == "nhwc_bwd_fused_k3s2"
+    assert dw.variant_name(dw.desc(256, 128, 56, 56, 3, 1, 1, 1, dw.NHWC, dw.BF16), 3) == "separate"
+
+
+def test_buffer_view_kernels_stay_within_two_gib_images():
+    # the bf16 5x5 NHWC kernels address an image through a 32-bit buffer view: an image above 2 GiB goes to the
+    # generic kernels, an image of exactly 2 GiB and every 3x3 shape keep the row walk
+    big = dw.desc(1, 8192, 512, 257, 5, 1, 2, 1, dw.NHWC, dw.BF16)
+    assert [dw.variant_name(big, i) for i in range(3)] == ["generic"] * 3
+    edge = dw.desc(1, 16384, 256, 256, 5, 1, 2, 1, dw.NHWC, dw.BF16)
+    assert dw.variant_name(edge, 0) == "nhwc_rowwalk_k5s1" and dw.variant_name(edge, 1) == "nhwc_rowwalk_k5s1_flip"
+    k3 = dw.desc(1, 16384, 256, 256, 3, 1, 1, 1, dw.NHWC, dw.F32)          # a 4 GiB image
+    assert dw.variant_name(k3, 0) == "nhwc_rowwalk_k3s1" and dw.variant_name(k3, 2) == "nhwc_bwd_filter_k3s1"
 
 
 # ---- group convolution entry points --------------------------------------------------------------------
