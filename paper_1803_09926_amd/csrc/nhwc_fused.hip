@@ -5,15 +5,18 @@
 //
 // Mapping as in the filter-gradient kernel (nhwc.hip): a block is CT channel-vectors x 256/CT
 // columns, walks a strip of rows of NI images; a lane owns V channels of one column.  Step t of
-// the walk takes dy row t (three columns) and x row t-1 (three columns):
+// the walk takes dy row t (three columns) and x row t+1 (the lane's own column only):
 //   input gradient:  dx[r][ow] = sum_{kh,kw} w[kh][kw] dy[r+1-kh][ow+1-kw]; dy row t is tap row
 //     kh = 0, 1, 2 of dx rows t-1, t, t+1, so two rotating accumulators finish dx row t-1 here;
-//   filter gradient: x row r = t-1 meets dy rows r+1-kh (centre column) at tap row kh; the three
-//     live dy rows sit in a small window; only dy rows inside the block's own strip count, while the
-//     input gradient needs the true halo rows: the window entry is masked, the loaded row is not.
-// Loads are unconditional with clamped rows, rows stay as loaded (packed for bf16) until used, and
-// every condition inside the walk is uniform over the block.  Padding columns: zeroed weights for the
-// input gradient, sums dropped after the walk for the filter gradient (as in nhwc.hip).
+//   filter gradient: dw[kh][kw] = sum dy[oh][ow] x[oh-1+kh][ow-1+kw] is summed per x column c instead
+//     of per dy column: the lane's x column meets dy[t][c+1-kw] at tap column kw, and x rows t-1, t, t+1
+//     (a three-row window of the lane's own column) at tap rows 0, 1, 2.  The three dy columns are there
+//     for the input gradient anyway, so the walk loads four vectors per step instead of six and keeps
+//     a third fewer rows in its prefetch ring.  Only dy rows inside the block's own strip count (uniform
+//     branch), while the input gradient needs the true halo rows.
+// Loads go through buffer views of the image (scalar row offsets; a column outside the image is read
+// outside the view and returns the zero of the padding, for both gradients), rows are clamped, stay as
+// loaded (packed for bf16) until used, and every condition inside the walk is uniform over the block.
 #include "kernels.hpp"
 
 namespace dwc {
@@ -46,49 +49,52 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_fused_k3s1(Geom g, const T *__
             for (int v = 0; v < V; ++v) acc[kh][kw][v] = 0.f;
 
     if (active) {
-        bool colok[K];
-        int coloff[K];
+        // byte offsets of dy columns ow-1, ow, ow+1 inside an image row; a column outside the image is read at an
+        // offset outside the buffer view and comes back as the zero of the padding, for both gradients
+        uint32_t coloff[K];
         float wd[K][K][V];      // wd[kh][j]: weight of dy column ow-1+j in tap row kh of the input gradient (= w[kh][2-j])
 #pragma unroll
         for (int j = 0; j < K; ++j) {
             const int iw = ow - 1 + j;
-            colok[j] = iw >= 0 && iw < g.W;
-            coloff[j] = (colok[j] ? iw : ow) * g.C;
+            coloff[j] = (iw >= 0 && iw < g.W) ? (uint32_t)(iw * g.C + cq * V) * (uint32_t)sizeof(T) : BufView::OUTSIDE;
 #pragma unroll
-            for (int kh = 0; kh < K; ++kh) {
-                Vec<T, V>::load(w + (kh * K + (2 - j)) * g.C + cq * V, wd[kh][j]);
-#pragma unroll
-                for (int v = 0; v < V; ++v) wd[kh][j][v] = colok[j] ? wd[kh][j][v] : 0.f;
-            }
+            for (int kh = 0; kh < K; ++kh) Vec<T, V>::load(w + (kh * K + (2 - j)) * g.C + cq * V, wd[kh][j]);
         }
         const int rowlen = g.W * g.C;
+        const uint32_t rowbytes = (uint32_t)rowlen * (uint32_t)sizeof(T), imgbytes = (uint32_t)g.H * rowbytes;   // at most 2 GiB
         const int oh0 = strip * TH, oh1 = min(g.H, oh0 + TH);
         const int n0 = ngroup * NI, n1 = min(g.N, n0 + NI);
         for (int n = n0; n < n1; ++n) {
-            const T *xin = x + (size_t)n * g.H * rowlen + cq * V;
-            const T *dyin = dy + (size_t)n * g.H * rowlen + cq * V;
-            T *dxout = dx + ((size_t)n * g.H * g.W + ow) * g.C + cq * V;
+            const BufView xin(x + (size_t)n * g.H * rowlen, imgbytes), dyin(dy + (size_t)n * g.H * rowlen, imgbytes);
+            const BufView dxout(dx + (size_t)n * g.H * rowlen, imgbytes);
 
-            RawVec<T, V> dr[R][K], xr[R][K];
-            auto load_rows = [&](int t, RawVec<T, V> (&dd)[K], RawVec<T, V> (&xd)[K]) {
-                const T *dp = dyin + (size_t)min(max(t, 0), g.H - 1) * rowlen;
-                const T *xp = xin + (size_t)min(max(t - 1, 0), g.H - 1) * rowlen;
+            // step t brings dy row t (three columns) and x row t+1 (the lane's own column)
+            RawVec<T, V> dr[R][K], xr[R];
+            auto load_rows = [&](int t, RawVec<T, V> (&dd)[K], RawVec<T, V> &xd) {
+                const uint32_t dro = (uint32_t)min(max(t, 0), g.H - 1) * rowbytes;
 #pragma unroll
-                for (int j = 0; j < K; ++j) { dd[j].load(dp + coloff[j]); xd[j].load(xp + coloff[j]); }
+                for (int j = 0; j < K; ++j) dd[j].load_buf(dyin, coloff[j], dro);
+                xd.load_buf(xin, coloff[1], (uint32_t)min(max(t + 1, 0), g.H - 1) * rowbytes);
             };
 
-            float A0[V], A1[V], dyw[K][V];
+            // xw[kh] = x row t-1+kh at the lane's column (zero outside the image); A0, A1: the two unfinished dx rows
+            float A0[V], A1[V], xw[K][V];
 #pragma unroll
             for (int v = 0; v < V; ++v) { A0[v] = 0.f; A1[v] = 0.f; }
+            const int t0 = oh0 - 1, nsteps = (oh1 - oh0) + 2;       // t = oh0-1 .. oh1: the dy rows a strip's dx needs
+            {
+                // x row t0 enters the window ahead of the first step (it becomes row t-1 of the strip's first dy row)
+                RawVec<T, V> first;
+                first.load_buf(xin, coloff[1], (uint32_t)max(t0, 0) * rowbytes);
+                float f[V];
+                first.get(f);
 #pragma unroll
-            for (int kh = 0; kh < K; ++kh)
-#pragma unroll
-                for (int v = 0; v < V; ++v) dyw[kh][v] = 0.f;
+                for (int v = 0; v < V; ++v) { xw[0][v] = 0.f; xw[1][v] = 0.f; xw[2][v] = t0 >= 0 ? f[v] : 0.f; }
+            }
 
-            auto consume = [&](int t, const RawVec<T, V> (&dd)[K], const RawVec<T, V> (&xd)[K]) {
+            auto consume = [&](int t, const RawVec<T, V> (&dd)[K], const RawVec<T, V> &xd) {
                 const bool dyok = t >= 0 && t < g.H;                 // dy row t exists
                 const bool mine = t >= oh0 && t < oh1;               // ... and belongs to this block's strip
-                const bool xok = t - 1 >= 0 && t - 1 < g.H;          // x row t-1 exists (rows of other strips meet a zeroed window)
                 float d[K][V];
 #pragma unroll
                 for (int j = 0; j < K; ++j) {
@@ -109,26 +115,28 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_fused_k3s1(Geom g, const T *__
                     }
                     out[v] = s0; A0[v] = s1; A1[v] = s2;
                 }
-                if (t - 1 >= oh0 && t - 1 < oh1) store_vec<T, V>(dxout + (size_t)(t - 1) * rowlen, out, nt != 0);
-                // filter gradient: x row t-1 meets dy rows t, t-1, t-2 (centre column) at tap rows 0, 1, 2
-#pragma unroll
-                for (int v = 0; v < V; ++v) { dyw[2][v] = dyw[1][v]; dyw[1][v] = dyw[0][v]; dyw[0][v] = mine ? d[1][v] : 0.f; }
-#pragma unroll
-                for (int kw = 0; kw < K; ++kw) {
+                if (t - 1 >= oh0 && t - 1 < oh1) store_buf<T, V>(dxout, coloff[1], (uint32_t)(t - 1) * rowbytes, out, nt != 0);
+                // filter gradient, summed per x column: the lane's x column c meets dy[t][c+1-kw] at tap column kw, and x
+                // rows t-1, t, t+1 at tap rows 0, 1, 2 (the sum over all columns is the same as per dy column)
+                {
                     float xv[V];
-                    xd[kw].get(xv);
+                    xd.get(xv);
+                    const bool xok = t + 1 < g.H;                    // t + 1 >= 0 always (t >= -1)
 #pragma unroll
-                    for (int v = 0; v < V; ++v) {
-                        const float xx = xok ? xv[v] : 0.f;
+                    for (int v = 0; v < V; ++v) { xw[0][v] = xw[1][v]; xw[1][v] = xw[2][v]; xw[2][v] = xok ? xv[v] : 0.f; }
+                }
+                if (mine) {
 #pragma unroll
-                        for (int kh = 0; kh < K; ++kh) acc[kh][kw][v] = fmaf(dyw[kh][v], xx, acc[kh][kw][v]);
-                    }
+                    for (int kw = 0; kw < K; ++kw)
+#pragma unroll
+                        for (int v = 0; v < V; ++v) {
+                            const float dd1 = d[2 - kw][v];
+#pragma unroll
+                            for (int kh = 0; kh < K; ++kh) acc[kh][kw][v] = fmaf(dd1, xw[kh][v], acc[kh][kw][v]);
+                        }
                 }
             };
 
-            // steps t = oh0-1 .. oh1+1: the first brings the halo dy row above the strip, the last two the
-            // halo dy row below it and the x row below the strip's last dy row
-            const int t0 = oh0 - 1, nsteps = (oh1 - oh0) + 3;
 #pragma unroll
             for (int j = 0; j < PF; ++j) load_rows(t0 + j, dr[j], xr[j]);
             int i = 0;
@@ -144,15 +152,6 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_fused_k3s1(Geom g, const T *__
             for (int j = 0; j < R - 1; ++j)
                 if (i + j < nsteps) consume(t0 + i + j, dr[j], xr[j]);
         }
-        // taps on columns outside the image accumulated clamped data: drop them
-#pragma unroll
-        for (int kw = 0; kw < K; ++kw)
-            if (!colok[kw]) {
-#pragma unroll
-                for (int kh = 0; kh < K; ++kh)
-#pragma unroll
-                    for (int v = 0; v < V; ++v) acc[kh][kw][v] = 0.f;
-            }
     }
 
     // ---- fixed-order block reduction (as in the filter-gradient kernel) ----
@@ -331,15 +330,17 @@ hipError_t nhwc_bwd_fused(const Geom &g, int dtype, int V, const void *x, const 
     const unsigned nblocks = (unsigned)nctiles * nowtiles * nstrips * ngroups;
     const int esz = dtype == DT_F32 ? 4 : 2;
     const int nt = stream_stores("NHWC_FUSED_BWD", (long long)g.N * g.H * g.W * g.C * esz, 0);
-#define GO(T, VV) hipLaunchKernelGGL((k_nhwc_bwd_fused_k3s1<T, VV, 1>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, \
+#define GO(T, VV, PP) hipLaunchKernelGGL((k_nhwc_bwd_fused_k3s1<T, VV, PP>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, \
                                      (const T *)dy, (const T *)w, (T *)dx, ws, CT, nctiles, nowtiles, TH, nstrips, NI, \
                                      nblocks, nt)
 #define GO2(T, VV) hipLaunchKernelGGL((k_nhwc_bwd_fused_k3s2<T, VV>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, \
                                       (const T *)dy, (const T *)w, (T *)dx, ws, CT, nctiles, nowtiles, TH, nstrips, NI, \
                                       nblocks, nt)
+    const char *fpf = tune_env("DWCONV_TUNE_FPF");
+    const int pf = fpf ? atoi(fpf) : 2;       // two rows ahead: 2 % faster than one although it leaves two wavefronts per SIMD in fp32
     if (g.s == 2) { if (dtype == DT_F32) GO2(float, 4); else GO2(bf16_t, 4); }
-    else if (dtype == DT_F32) GO(float, 4);
-    else GO(bf16_t, 4);
+    else if (dtype == DT_F32) { if (pf == 2) GO(float, 4, 2); else GO(float, 4, 1); }
+    else { if (pf == 2) GO(bf16_t, 4, 2); else GO(bf16_t, 4, 1); }
 #undef GO
 #undef GO2
     return hipGetLastError();
