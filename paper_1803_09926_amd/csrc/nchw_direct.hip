@@ -937,12 +937,14 @@ __global__ __launch_bounds__(256) void k_nchwd_bwd_filter_s1_bf16(Geom g, const 
 // stage-1 partial sums of the filter gradient from one walk over dy and x (dy is read once).
 // Block structure of the filter-gradient kernel above: grid = (parts, C), a block works on one
 // channel, lanes flat over (item, vector column) with nsg (image, strip) items per round.  Step t
-// of the walk takes dy row t and x row t-1, each with its left and right neighbour column:
+// of the walk takes dy row t with its left and right neighbour column, and x row t+1 (own columns):
 //   input gradient:  dx[r][c] = sum_{kh,kw} w[kh][kw] dy[r+1-kh][c+1-kw]; dy row t is tap row 0, 1, 2
 //     of dx rows t-1, t, t+1 (two rotating accumulators; the filter is uniform over the block);
-//   filter gradient: x row t-1 meets dy rows t, t-1, t-2 (own columns) at tap rows 0, 1, 2; only dy
-//     rows inside the item's own strip count there, while the input gradient needs the true halo
-//     rows: the window entry is masked, the loaded row is not.
+//   filter gradient, summed per x column instead of per dy column: x column c meets dy[t][c+1-kw] at
+//     tap column kw and x rows t-1, t, t+1 (a three-row window of the lane's own columns) at tap rows
+//     0, 1, 2.  The dy neighbours are there for the input gradient anyway, so x needs none: four load
+//     instructions per step instead of six.  Only dy rows inside the item's own strip count (the products
+//     are masked), while the input gradient needs the true halo rows.
 // dx leaves through the whole-line write-out (RS rows per group; needs TH % RS == 0, H % RS == 0),
 // so every lane of the block walks every round in lockstep: lanes without an item (the last few
 // lanes of the block, a partly filled last round) run on clamped addresses with everything masked.
@@ -1009,35 +1011,37 @@ __global__ __launch_bounds__(256) void k_nchwd_bwd_fused_k3s1(Geom g, const T *_
         }
         lw.done = 0;
 
-        auto load_row = [&](int t, float (&dd)[NW], float (&xd)[NW]) {
+        auto load_row = [&](int t, float (&dd)[NW], float (&xd)[V]) {
             const T *dp = dyin + (size_t)min(max(t, 0), g.H - 1) * g.W;
-            const T *xp = xin + (size_t)min(max(t - 1, 0), g.H - 1) * g.W;
+            const T *xp = xin + (size_t)min(max(t + 1, 0), g.H - 1) * g.W;
             float m[V];
             Vec<T, V>::load(dp, m);
             dd[0] = ldf(dp + loff); dd[V + 1] = ldf(dp + roff);
 #pragma unroll
             for (int v = 0; v < V; ++v) dd[1 + v] = m[v];
-            Vec<T, V>::load(xp, m);
-            xd[0] = ldf(xp + loff); xd[V + 1] = ldf(xp + roff);
-#pragma unroll
-            for (int v = 0; v < V; ++v) xd[1 + v] = m[v];
+            Vec<T, V>::load(xp, xd);
         };
 
-        float A0[V], A1[V], dyw[3][V];
+        // xw[kh] = x row t-1+kh at the lane's columns (zero outside the image); x row t0 enters ahead of the first step
+        float A0[V], A1[V], xw[3][V];
+        const int t0 = oh0 - 1;
+        {
+            float f[V];
+            Vec<T, V>::load(xin + (size_t)max(t0, 0) * g.W, f);
 #pragma unroll
-        for (int v = 0; v < V; ++v) { A0[v] = 0.f; A1[v] = 0.f; dyw[0][v] = 0.f; dyw[1][v] = 0.f; dyw[2][v] = 0.f; }
+            for (int v = 0; v < V; ++v) { A0[v] = 0.f; A1[v] = 0.f; xw[0][v] = 0.f; xw[1][v] = 0.f; xw[2][v] = t0 >= 0 ? f[v] : 0.f; }
+        }
 
-        float dr[2][NW], xr[2][NW];
-        auto consume = [&](int step, int t, const float (&dd)[NW], const float (&xd)[NW]) {
+        float dr[2][NW], xr[2][V];
+        auto consume = [&](int step, int t, const float (&dd)[NW], const float (&xd)[V]) {
             const bool dyok = t >= 0 && t < g.H;
             const bool mine = live && t >= oh0 && t < oh1;
-            const bool xok = t - 1 >= 0 && t - 1 < g.H;
-            float d[NW], xv[NW];
+            const bool xok = t + 1 < g.H;
+            float d[NW];
 #pragma unroll
             for (int i = 0; i < NW; ++i) {
                 const bool colok = i == 0 ? has_left : (i == V + 1 ? has_right : true);
                 d[i] = (dyok && colok) ? dd[i] : 0.f;
-                xv[i] = (xok && colok) ? xd[i] : 0.f;
             }
             // input gradient: dx column c (window index c + 1) reads dy columns c+1-kw = window index c + 2 - kw
             float out[V];
@@ -1055,22 +1059,25 @@ __global__ __launch_bounds__(256) void k_nchwd_bwd_fused_k3s1(Geom g, const T *_
             // dx row t-1 = oh0 + step - 2 leaves at steps 2 .. TH+1, the same for every lane (rows past the
             // strip's end are masked in the write-out)
             if (step >= 2 && step < TH + 2) lw.put(stage, pack16<T>(out), g.W);
-            // filter gradient
+            // filter gradient: x column c (index v) against dy column c+1-kw (window index v + 2 - kw)
 #pragma unroll
-            for (int v = 0; v < V; ++v) { dyw[2][v] = dyw[1][v]; dyw[1][v] = dyw[0][v]; dyw[0][v] = mine ? d[1 + v] : 0.f; }
+            for (int v = 0; v < V; ++v) { xw[0][v] = xw[1][v]; xw[1][v] = xw[2][v]; xw[2][v] = xok ? xd[v] : 0.f; }
+            float dm[NW];
 #pragma unroll
-            for (int kh = 0; kh < 3; ++kh)
+            for (int i = 0; i < NW; ++i) dm[i] = mine ? d[i] : 0.f;
 #pragma unroll
-                for (int kw = 0; kw < 3; ++kw) {
+            for (int kw = 0; kw < 3; ++kw)
+#pragma unroll
+                for (int kh = 0; kh < 3; ++kh) {
                     float sacc = acc[kh][kw];
 #pragma unroll
-                    for (int v = 0; v < V; ++v) sacc = fmaf(dyw[kh][v], xv[v + kw], sacc);
+                    for (int v = 0; v < V; ++v) sacc = fmaf(dm[v + 2 - kw], xw[kh][v], sacc);
                     acc[kh][kw] = sacc;
                 }
         };
 
-        // steps t = oh0-1 .. oh0+TH+1 for every lane (the same count, whatever the strip's real height)
-        const int t0 = oh0 - 1, nsteps = TH + 3;
+        // steps t = oh0-1 .. oh0+TH for every lane (the same count, whatever the strip's real height)
+        const int nsteps = TH + 2;
         load_row(t0, dr[0], xr[0]);
         int i = 0;
 #pragma unroll 1
