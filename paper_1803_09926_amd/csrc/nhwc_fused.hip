@@ -167,11 +167,14 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_fused_k3s1(Geom g, const T *__
 // Fused backward pass, 3x3, stride 2, pad 1, multiplier 1, even H and W.  Mapping and tiling of the
 // stride-2 filter gradient (nhwc.hip): a lane owns V channels of dy column b and walks the dy rows a
 // of its strip.  Step a holds dy rows a and a+1 (columns b and b+1) and x rows 2a-1, 2a, 2a+1
-// (columns 2b-1, 2b, 2b+1):
+// (columns 2b and 2b+1):
 //   input gradient: the 2x2 block dx[2a..2a+1][2b..2b+1] from dy[a..a+1][b..b+1], as in
-//     k_nhwc_bwd_data_k3s2 (a missing column b+1 meets zeroed weights, a missing row a+1 is a
-//     block-uniform condition);
-//   filter gradient: dy[a][b] against the 3x3 x window, x row 2a+1 is kept as the top row of step a+1.
+//     k_nhwc_bwd_data_k3s2 (a missing column b+1 is read outside the buffer view and is zero, a missing
+//     row a+1 is a block-uniform condition);
+//   filter gradient, summed per x column: x column 2b meets dy[a][b] at tap column 1, x column 2b+1
+//     meets dy[a][b] at tap column 2 and dy[a][b+1] at tap column 0 (every x element is then loaded by
+//     exactly one lane: two x vectors per row instead of three); x row 2a+1 is kept as the top row of
+//     step a+1.
 // dy row a+1 and x rows 2a+2, 2a+3 of the next step are loaded while the current one is computed and
 // stay as loaded (packed for bf16) until then.  dy is read once: the pass moves 2|x| + |y| elements.
 // ---------------------------------------------------------------------------------------------
@@ -203,43 +206,37 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_fused_k3s2(Geom g, const T *__
             for (int v = 0; v < V; ++v) acc[kh][kw][v] = 0.f;
 
     if (active) {
-        const bool has_b1 = b + 1 < g.Wo;        // dy column b+1 exists
-        const bool has_left = b > 0;             // x column 2b-1 exists
         float wr[K][K][V];
 #pragma unroll
         for (int kh = 0; kh < K; ++kh)
 #pragma unroll
-            for (int kw = 0; kw < K; ++kw) {
-                Vec<T, V>::load(w + (kh * K + kw) * g.C + cq * V, wr[kh][kw]);
-                if (kw == 0) {
-#pragma unroll
-                    for (int v = 0; v < V; ++v) wr[kh][kw][v] = has_b1 ? wr[kh][kw][v] : 0.f;   // w?0 multiplies dy[.][b+1]
-                }
-            }
-        const int dyrow = g.Wo * g.C, xrow = g.W * g.C;
-        const int off1 = has_b1 ? g.C : 0;
-        const int xoff0 = has_left ? -g.C : 0;   // clamped; the sums of that tap column are dropped after the walk
+            for (int kw = 0; kw < K; ++kw) Vec<T, V>::load(w + (kh * K + kw) * g.C + cq * V, wr[kh][kw]);
+        // buffer views of the image: dy column b+1 of the last lane of a row is read outside the view and comes
+        // back as zero, for both gradients
+        const uint32_t es = (uint32_t)sizeof(T);
+        const uint32_t dyrowb = (uint32_t)(g.Wo * g.C) * es, xrowb = (uint32_t)(g.W * g.C) * es, cb = (uint32_t)g.C * es;
+        const uint32_t dyoff0 = (uint32_t)(b * g.C + cq * V) * es;
+        const uint32_t dyoff1 = b + 1 < g.Wo ? dyoff0 + cb : BufView::OUTSIDE;
+        const uint32_t xoff = (uint32_t)(2 * b * g.C + cq * V) * es;       // x / dx column 2b; column 2b+1 is one pixel on
         const int a0 = strip * TH, a1 = min(g.Ho, a0 + TH);
         const int n0 = ngroup * NI, n1 = min(g.N, n0 + NI);
         for (int n = n0; n < n1; ++n) {
-            const T *dyin = dy + ((size_t)n * g.Ho * g.Wo + b) * g.C + cq * V;
-            const T *xin = x + ((size_t)n * g.H * g.W + 2 * b) * g.C + cq * V;
-            T *dxout = dx + ((size_t)n * g.H * g.W + 2 * b) * g.C + cq * V;
+            const BufView dyin(dy + (size_t)n * g.Ho * g.Wo * g.C, (uint32_t)g.Ho * dyrowb);
+            const BufView xin(x + (size_t)n * g.H * g.W * g.C, (uint32_t)g.H * xrowb);
+            const BufView dxout(dx + (size_t)n * g.H * g.W * g.C, (uint32_t)g.H * xrowb);
             auto load_dy = [&](int a, RawVec<T, V> (&d)[2]) {
-                const T *rp = dyin + (size_t)min(a, g.Ho - 1) * dyrow;
-                d[0].load(rp); d[1].load(rp + off1);
+                const uint32_t ro = (uint32_t)min(a, g.Ho - 1) * dyrowb;
+                d[0].load_buf(dyin, dyoff0, ro); d[1].load_buf(dyin, dyoff1, ro);
             };
-            auto load_x = [&](int r, RawVec<T, V> (&xd)[K]) {
-                const T *rp = xin + (size_t)min(max(r, 0), g.H - 1) * xrow;
-                xd[0].load(rp + xoff0); xd[1].load(rp); xd[2].load(rp + g.C);
+            // the lane's two x columns 2b and 2b+1 (the filter gradient is summed per x column)
+            auto load_x = [&](int r, RawVec<T, V> (&xd)[2]) {
+                const uint32_t ro = (uint32_t)min(max(r, 0), g.H - 1) * xrowb;
+                xd[0].load_buf(xin, xoff, ro); xd[1].load_buf(xin, xoff + cb, ro);
             };
-            RawVec<T, V> dcur[2], dnext[2][2], xa[K], xb[2][K], xc[2][K];
+            RawVec<T, V> dcur[2], dnext[2][2], xa[2], xb[2][2], xc[2][2];
             load_dy(a0, dcur);
             if (a0 > 0) load_x(2 * a0 - 1, xa);
-            else {
-#pragma unroll
-                for (int kw = 0; kw < K; ++kw) xa[kw].zero();
-            }
+            else { xa[0].zero(); xa[1].zero(); }
             load_dy(a0 + 1, dnext[0]); load_x(2 * a0, xb[0]); load_x(2 * a0 + 1, xc[0]);
             auto step = [&](int a, int j) {
                 const bool below = a + 1 < g.Ho;
@@ -260,26 +257,32 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_fused_k3s2(Geom g, const T *__
                         o11[v] = fmaf(wr[0][0][v], B1[v], fmaf(wr[0][2][v], B0[v], o11[v]));
                     }
                 }
-                T *r0p = dxout + (size_t)(2 * a) * xrow;
-                store_vec<T, V>(r0p, o00, nt != 0);
-                store_vec<T, V>(r0p + g.C, o01, nt != 0);
-                store_vec<T, V>(r0p + xrow, o10, nt != 0);
-                store_vec<T, V>(r0p + xrow + g.C, o11, nt != 0);
-                // filter gradient: dy[a][b] meets x rows 2a-1, 2a, 2a+1 at tap rows 0, 1, 2
-#pragma unroll
-                for (int kw = 0; kw < K; ++kw) {
-                    float x0[V], x1[V], x2[V];
-                    xa[kw].get(x0); xb[j][kw].get(x1); xc[j][kw].get(x2);
+                const uint32_t r0 = (uint32_t)(2 * a) * xrowb;
+                store_buf<T, V>(dxout, xoff, r0, o00, nt != 0);
+                store_buf<T, V>(dxout, xoff + cb, r0, o01, nt != 0);
+                store_buf<T, V>(dxout, xoff, r0 + xrowb, o10, nt != 0);
+                store_buf<T, V>(dxout, xoff + cb, r0 + xrowb, o11, nt != 0);
+                // filter gradient per x column: x rows 2a-1, 2a, 2a+1 are tap rows 0, 1, 2; x column 2b meets dy[a][b] at
+                // tap column 1, x column 2b+1 meets dy[a][b] at tap column 2 and dy[a][b+1] at tap column 0
+                {
+                    float e0[V], e1[V], e2[V], f0[V], f1[V], f2[V];
+                    xa[0].get(e0); xb[j][0].get(e1); xc[j][0].get(e2);
+                    xa[1].get(f0); xb[j][1].get(f1); xc[j][1].get(f2);
 #pragma unroll
                     for (int v = 0; v < V; ++v) {
-                        acc[0][kw][v] = fmaf(A0[v], x0[v], acc[0][kw][v]);
-                        acc[1][kw][v] = fmaf(A0[v], x1[v], acc[1][kw][v]);
-                        acc[2][kw][v] = fmaf(A0[v], x2[v], acc[2][kw][v]);
+                        acc[0][1][v] = fmaf(A0[v], e0[v], acc[0][1][v]);
+                        acc[1][1][v] = fmaf(A0[v], e1[v], acc[1][1][v]);
+                        acc[2][1][v] = fmaf(A0[v], e2[v], acc[2][1][v]);
+                        acc[0][2][v] = fmaf(A0[v], f0[v], acc[0][2][v]);
+                        acc[1][2][v] = fmaf(A0[v], f1[v], acc[1][2][v]);
+                        acc[2][2][v] = fmaf(A0[v], f2[v], acc[2][2][v]);
+                        acc[0][0][v] = fmaf(A1[v], f0[v], acc[0][0][v]);
+                        acc[1][0][v] = fmaf(A1[v], f1[v], acc[1][0][v]);
+                        acc[2][0][v] = fmaf(A1[v], f2[v], acc[2][0][v]);
                     }
                 }
                 dcur[0] = dnext[j][0]; dcur[1] = dnext[j][1];
-#pragma unroll
-                for (int kw = 0; kw < K; ++kw) xa[kw] = xc[j][kw];
+                xa[0] = xc[j][0]; xa[1] = xc[j][1];
             };
             int a = a0;
 #pragma unroll 1
@@ -290,13 +293,6 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_fused_k3s2(Geom g, const T *__
                 step(a + 1, 1);
             }
             if (a < a1) step(a, 0);
-        }
-        // the left tap column of the lanes at b = 0 accumulated clamped data: drop it
-        if (!has_left) {
-#pragma unroll
-            for (int kh = 0; kh < K; ++kh)
-#pragma unroll
-                for (int v = 0; v < V; ++v) acc[kh][0][v] = 0.f;
         }
     }
 
