@@ -292,7 +292,7 @@ Plan plan_bwd(const Geom &g, int layout, int dtype)
     if (layout == LAYOUT_NHWC && !tune_env("DWCONV_TUNE_NOFUSE")) {
         // the fused kernel takes four channels per lane in either type (bf16 with eight would need more than 256 registers)
         int V = nhwc_vec(g, dtype);
-        if (V == 8 && g.W <= tune("DWCONV_TUNE_FUSE_BF16W", 14)) V = 4;
+        if (V == 8 && g.W <= tune("DWCONV_TUNE_FUSE_BF16W", 65536)) V = 4;
         if (V && nhwc_bwd_fused_supported(g, dtype, V)) {
             // tiling of the filter gradient: its block count and partial sums decide
             const Plan pf = plan_bwd_filter_v(g, layout, dtype, V);

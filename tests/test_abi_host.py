@@ -163,10 +163,11 @@ def test_whole_backward_variant_names():
     assert dw.variant_name(dw.desc(128, 512, 14, 14, 3, 2, 1, 1, dw.NCHW, dw.F32), 3) == "separate"      # stride 2
     assert dw.variant_name(dw.desc(128, 32, 112, 112, 3, 1, 1, 1, dw.NCHW, dw.BF16), 3) == "separate"
     assert dw.variant_name(dw.desc(2, 6, 9, 9, 3, 1, 1, 1, dw.NHWC, dw.F32), 3) == "separate"
-    # bf16 NHWC: the fused kernels (four channels per lane) on planes of up to 14 columns, two passes on wider maps
+    # bf16 NHWC: the fused kernels with four channels per lane
     assert dw.variant_name(dw.desc(256, 512, 14, 14, 3, 1, 1, 1, dw.NHWC, dw.BF16), 3) == "nhwc_bwd_fused_k3s1"
     assert dw.variant_name(dw.desc(256, 512, 14, 14, 3, 2, 1, 1, dw.NHWC, dw.BF16), 3) == "nhwc_bwd_fused_k3s2"
-    assert dw.variant_name(dw.desc(256, 128, 56, 56, 3, 1, 1, 1, dw.NHWC, dw.BF16), 3) == "separate"
+    assert dw.variant_name(dw.desc(256, 128, 56, 56, 3, 1, 1, 1, dw.NHWC, dw.BF16), 3) == "nhwc_bwd_fused_k3s1"
+    assert dw.variant_name(dw.desc(256, 128, 56, 56, 5, 1, 2, 1, dw.NHWC, dw.BF16), 3) == "separate"
 
 
 def test_buffer_view_kernels_stay_within_two_gib_images():
