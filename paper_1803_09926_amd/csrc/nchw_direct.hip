@@ -1105,6 +1105,169 @@ __global__ __launch_bounds__(256) void k_nchwd_bwd_fused_k3s1(Geom g, const T *_
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Fused backward pass, NCHW, 3x3, stride 2, pad 1, multiplier 1, W = 2*Wo, H = 2*Ho.  Block structure of
+// the stride-1 fused kernel above (grid = (parts, C), lanes flat over (item, vector column), rounds of nsg
+// (image, strip) items).  A lane owns V adjacent dy columns b and the 2V x / dx columns 2b, 2b+1 under them,
+// and walks the TH dy rows a of its strip; step a holds dy rows a and a+1 (the lane's columns and the one to
+// their right) and x rows 2a-1, 2a, 2a+1 (the lane's own 2V columns, one 16-byte vector per row):
+//   input gradient: dx rows 2a and 2a+1 as in k_nchwd_bwd_data_k3s2, through the whole-line write-out;
+//   filter gradient, summed per x column: x column 2b meets dy[a][b] at tap column 1, x column 2b+1 meets
+//     dy[a][b] at tap column 2 and dy[a][b+1] at tap column 0; x rows 2a-1, 2a, 2a+1 are tap rows 0, 1, 2,
+//     and row 2a+1 stays as the top row of step a+1.  Every x element is loaded by exactly one lane.
+// dy is read once: the pass moves 2|x| + |y| elements.  Every lane walks TH steps in lockstep (whole-line
+// write-out); lanes without an item and steps past a shorter last strip run on clamped rows, masked.
+// Needs (2 TH) % RS == 0 and H % RS == 0.
+// ---------------------------------------------------------------------------------------------
+template <typename T, int V, int RS>
+__global__ __launch_bounds__(256) void k_nchwd_bwd_fused_k3s2(Geom g, const T *__restrict__ x, const T *__restrict__ dy,
+                                                              const T *__restrict__ w, T *__restrict__ dx,
+                                                              float *__restrict__ ws, int TH, int nstrips, int nsg,
+                                                              int rounds)
+{
+    static_assert(sizeof(T) * 2 * V == 16, "one 16-byte x / dx vector per lane and row");
+    __shared__ float red[4][9];
+    __shared__ u4v_t stage[2][RS * 256];
+    constexpr int XV = 2 * V;
+    const int o = blockIdx.y, part = blockIdx.x;
+    const int ncols = g.Wo / V;
+    const int sg = threadIdx.x / ncols, c4 = threadIdx.x - sg * ncols;
+    const int nitems = g.N * nstrips;
+    const bool has_right = c4 < ncols - 1;
+    const int roff = has_right ? V : V - 1;
+    const size_t xplane = (size_t)g.H * g.W, dyplane = (size_t)g.Ho * g.Wo;
+
+    float wr[3][3];
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) wr[kh][kw] = ldf(w + (o * 3 + kh) * 3 + kw);
+
+    float acc[3][3];
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) acc[kh][kw] = 0.f;
+
+    LineWriter<T, RS> lw;
+    lw.slot = 0; lw.buf = 0; lw.done = 0;
+
+    for (int rd = 0; rd < rounds; ++rd) {
+        const int item0 = (part * rounds + rd) * nsg;
+        const int item = item0 + sg;
+        const bool live = sg < nsg && item < nitems;
+        const int itc = min(item, nitems - 1);                 // clamped: loads stay in bounds
+        const int n = itc / nstrips, strip = itc - n * nstrips;
+        const int a0 = strip * TH, a1 = min(g.Ho, a0 + TH);
+        const T *xin = x + ((size_t)n * g.C + o) * xplane + c4 * XV;
+        const T *dyin = dy + ((size_t)n * g.C + o) * dyplane + c4 * V;
+        // write-out entries of this round (dx rows of 2 TH per item, W / XV vectors per row = ncols)
+#pragma unroll
+        for (int k = 0; k < RS; ++k) {
+            const int e = threadIdx.x + 256 * k;
+            const int l = e / RS;
+            const int sgl = l / ncols, a = sgl * ncols;
+            const int rel = e - RS * a;
+            const int srow = rel / ncols, c4l = rel - srow * ncols;
+            const int iteml = item0 + sgl;
+            const bool ok = sgl < nsg && iteml < nitems;
+            const int itl = min(iteml, nitems - 1);
+            const int nl = itl / nstrips, stl = itl - nl * nstrips;
+            const int o0 = stl * 2 * TH, o1 = min(g.H, o0 + 2 * TH);
+            lw.idx[k] = min(srow, RS - 1) * 256 + min(a + c4l, 255);
+            lw.rows[k] = ok ? o1 - (o0 + srow) : 0;
+            lw.ptr[k] = dx + (((size_t)nl * g.C + o) * g.H + min(o0 + srow, g.H - 1)) * g.W + c4l * XV;
+        }
+        lw.done = 0;
+
+        auto load_dy = [&](int a, float (&dst)[V + 1]) {
+            const T *rp = dyin + (size_t)min(a, g.Ho - 1) * g.Wo;
+            float m[V];
+            Vec<T, V>::load(rp, m);
+            dst[V] = ldf(rp + roff);
+#pragma unroll
+            for (int v = 0; v < V; ++v) dst[v] = m[v];
+        };
+        auto load_x = [&](int r, float (&dst)[XV]) { Vec<T, XV>::load(xin + (size_t)min(max(r, 0), g.H - 1) * g.W, dst); };
+
+        // xa = x row 2a-1 (zero above the image), kept from the previous step's row 2a+1; dA, dB = dy rows a, a+1
+        float xa[XV], xe[2][XV], xo[2][XV], dA[V + 1], dB[V + 1], dC[V + 1];
+        load_x(2 * a0 - 1, xa);
+#pragma unroll
+        for (int i = 0; i < XV; ++i) xa[i] = a0 > 0 ? xa[i] : 0.f;
+        load_dy(a0, dA); load_dy(a0 + 1, dB);
+        load_x(2 * a0, xe[0]); load_x(2 * a0 + 1, xo[0]);
+
+        auto step = [&](int a, const float (&Ar)[V + 1], const float (&Br)[V + 1], const float (&X1)[XV], const float (&X2)[XV]) {
+            const bool below = a + 1 < g.Ho;
+            const bool mine = live && a < a1;
+            float A[V + 1], B[V + 1];
+#pragma unroll
+            for (int v = 0; v < V; ++v) { A[v] = Ar[v]; B[v] = below ? Br[v] : 0.f; }
+            A[V] = has_right ? Ar[V] : 0.f;
+            B[V] = (has_right && below) ? Br[V] : 0.f;
+            float ev[XV], od[XV];   // dx rows 2a and 2a+1, the lane's 2V columns
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                ev[2 * v] = wr[1][1] * A[v];
+                ev[2 * v + 1] = fmaf(wr[1][0], A[v + 1], wr[1][2] * A[v]);
+                od[2 * v] = fmaf(wr[0][1], B[v], wr[2][1] * A[v]);
+                od[2 * v + 1] = fmaf(wr[0][0], B[v + 1], fmaf(wr[0][2], B[v], fmaf(wr[2][0], A[v + 1], wr[2][2] * A[v])));
+            }
+            lw.put(stage, pack16<T>(ev), g.W);
+            lw.put(stage, pack16<T>(od), g.W);
+            // filter gradient (only dy rows of the lane's own strip and item)
+            float D[V + 1];
+#pragma unroll
+            for (int v = 0; v <= V; ++v) D[v] = mine ? A[v] : 0.f;
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                acc[0][1] = fmaf(D[v], xa[2 * v], acc[0][1]);
+                acc[1][1] = fmaf(D[v], X1[2 * v], acc[1][1]);
+                acc[2][1] = fmaf(D[v], X2[2 * v], acc[2][1]);
+                acc[0][2] = fmaf(D[v], xa[2 * v + 1], acc[0][2]);
+                acc[1][2] = fmaf(D[v], X1[2 * v + 1], acc[1][2]);
+                acc[2][2] = fmaf(D[v], X2[2 * v + 1], acc[2][2]);
+                acc[0][0] = fmaf(D[v + 1], xa[2 * v + 1], acc[0][0]);
+                acc[1][0] = fmaf(D[v + 1], X1[2 * v + 1], acc[1][0]);
+                acc[2][0] = fmaf(D[v + 1], X2[2 * v + 1], acc[2][0]);
+            }
+#pragma unroll
+            for (int i = 0; i < XV; ++i) xa[i] = X2[i];
+        };
+
+        // every lane walks TH steps; the rows of the next step are loaded while this one is computed
+        auto advance = [&](int a, int j) {
+            load_dy(a + 2, dC);
+            load_x(2 * a + 2, xe[j ^ 1]); load_x(2 * a + 3, xo[j ^ 1]);
+            step(a, dA, dB, xe[j], xo[j]);
+#pragma unroll
+            for (int v = 0; v <= V; ++v) { dA[v] = dB[v]; dB[v] = dC[v]; }
+        };
+        int i = 0;
+#pragma unroll 1
+        for (; i + 2 <= TH; i += 2) {
+            advance(a0 + i, 0);
+            advance(a0 + i + 1, 1);
+        }
+        if (i < TH) advance(a0 + i, 0);
+    }
+
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) {
+            const float s = wave_sum(acc[kh][kw]);
+            if (lane == 0) red[wv][kh * 3 + kw] = s;
+        }
+    __syncthreads();
+    if (threadIdx.x < 9) {
+        const int t = threadIdx.x;
+        ws[((size_t)part * g.C + o) * 9 + t] = (red[0][t] + red[1][t]) + (red[2][t] + red[3][t]);
+    }
+}
+
 // ---- host side --------------------------------------------------------------------------------
 
 // vector width for the direct kernels (0 = not applicable): rows must be whole 16-byte vectors;
@@ -1317,7 +1480,14 @@ hipError_t nchwd_bwd_filter(const Geom &g, int dtype, int V, const void *x, cons
 // Fused backward: same tiling as the filter gradient, strip height a multiple of the row group.
 int nchwd_bwd_fused_rs(const Geom &g, int dtype, int V)
 {
-    if (!(g.K == 3 && g.s == 1 && g.p == 1 && g.m == 1)) return 0;
+    if (!(g.K == 3 && g.p == 1 && g.m == 1)) return 0;
+    if (g.s == 2) {
+        // stride 2: fp32, two dy columns (four dx columns = one 16-byte vector) per lane
+        if (!(dtype == DT_F32 && V == 2 && g.H % 2 == 0 && g.W % 2 == 0 && g.Wo % 2 == 0)) return 0;
+        const int rs = row_group(g.W, 4);
+        return (rs && g.H % rs == 0 && g.Wo / V <= 256) ? rs : 0;
+    }
+    if (g.s != 1) return 0;
     // bf16 rows of whole 16-byte vectors: 0.3 % of the bf16 step against the two packed-pair passes, one launch fewer
     const bool bf = dtype == DT_BF16 && V == 8 && !tune_env("DWCONV_TUNE_NOFUSE_NCHW_BF16");
     if (!((dtype == DT_F32 && V == 4) || bf)) return 0;
@@ -1329,16 +1499,20 @@ hipError_t nchwd_bwd_fused(const Geom &g, int dtype, int V, const void *x, const
                            float *ws, int TH, hipStream_t st)
 {
     const int rs = nchwd_bwd_fused_rs(g, dtype, V);
-    if (!rs || TH % rs != 0) return hipErrorInvalidValue;
+    if (!rs || (g.s * TH) % rs != 0) return hipErrorInvalidValue;
     int lg, nstrips, rounds, parts;
     nchwd_bwd_filter_tiling(g, V, TH, &lg, &nstrips, &rounds, &parts);
     if (lg < 1 || parts < 1) return hipErrorInvalidValue;
     dim3 grid(parts, g.C);
 #define GO(T, VV, RSV) hipLaunchKernelGGL((k_nchwd_bwd_fused_k3s1<T, VV, RSV>), grid, dim3(256), 0, st, g, (const T *)x, \
                                           (const T *)dy, (const T *)w, (T *)dx, ws, TH, nstrips, lg, rounds)
-    if (dtype == DT_F32) { if (rs == 2) GO(float, 4, 2); else GO(float, 4, 4); }
+#define GO2(RSV) hipLaunchKernelGGL((k_nchwd_bwd_fused_k3s2<float, 2, RSV>), grid, dim3(256), 0, st, g, (const float *)x, \
+                                    (const float *)dy, (const float *)w, (float *)dx, ws, TH, nstrips, lg, rounds)
+    if (g.s == 2) { if (rs == 2) GO2(2); else GO2(4); }
+    else if (dtype == DT_F32) { if (rs == 2) GO(float, 4, 2); else GO(float, 4, 4); }
     else { if (rs == 2) GO(bf16_t, 8, 2); else GO(bf16_t, 8, 4); }
 #undef GO
+#undef GO2
     return hipGetLastError();
 }
 

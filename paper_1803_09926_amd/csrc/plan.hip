@@ -317,7 +317,24 @@ Plan plan_bwd(const Geom &g, int layout, int dtype)
             }
         }
         pf = pl;
-        if (plan_bwd_filter_nchwd(g, dtype, pf)) {
+        if (g.s == 2 && !use_small(g, dtype, 2) && !tune_env("DWCONV_TUNE_NOFUSE_NCHW_S2") && plan_bwd_filter_nchwd(g, dtype, pf)) {
+            // stride 2 on row-walk shapes: two dy columns per lane, strips of the filter gradient's height made even
+            // where a write-out group is four dx rows
+            const int V2 = 2, rs = nchwd_bwd_fused_rs(g, dtype, V2);
+            if (rs) {
+                const int TH = (2 * pf.b) % rs == 0 ? pf.b : pf.b + 1;
+                int lg, nst, rounds, parts;
+                nchwd_bwd_filter_tiling(g, V2, TH, &lg, &nst, &rounds, &parts);
+                if (lg >= 1 && parts >= 1 && (long long)parts * g.O * g.K * g.K * 4 <= (64ll << 20)) {
+                    pl = pf;
+                    pl.variant = V_NCHWD_BWD_FUSED; pl.a = V2; pl.b = TH; pl.parts = parts;
+                    pl.name = "nchw_bwd_fused_k3s2";
+                    return pl;
+                }
+            }
+        }
+        pf = pl;
+        if (g.s == 1 && plan_bwd_filter_nchwd(g, dtype, pf)) {
             const int rs = nchwd_bwd_fused_rs(g, dtype, pf.a);
             if (rs) {
                 // the filter gradient's tiling with the strip height rounded up to whole row groups

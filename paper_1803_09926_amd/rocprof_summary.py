@@ -55,6 +55,7 @@ VARIANT_KERNELS = {
     "bwd:nhwc_bwd_fused_k3s1": [r"k_nhwc_bwd_fused_k3s1<"],
     "bwd:nhwc_bwd_fused_k3s2": [r"k_nhwc_bwd_fused_k3s2<"],
     "bwd:nchw_bwd_fused_k3s1": [r"k_nchwd_bwd_fused_k3s1<"],
+    "bwd:nchw_bwd_fused_k3s2": [r"k_nchwd_bwd_fused_k3s2<"],
     "bwd:nchw_smallplane_bwd_fused_k3s1": [r"k_nchws_bwd_fused<"],
     # group convolution: k_gconv_nchw_s1<T, V, OB, R, FLIP, SHFL>, k_gconv_nhwc_s1<T, CG, OB, GPL, PF, FLIP>
     "fwd:group_nchw_rowwalk_k3s1": [r"k_gconv_nchw_s1<[\w ]+, \d+, \d+, \d+, false[,>]"],
