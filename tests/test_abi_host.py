@@ -153,14 +153,17 @@ def test_whole_backward_entry_point_validates_before_launch():
 
 
 def test_whole_backward_variant_names():
-    # fused kernels: NHWC 3x3 stride 1, NCHW 3x3 stride 1 fp32 on row-walk shapes; everything else runs the two passes
+    # fused kernels: NHWC 3x3 stride 1 and 2, NCHW 3x3 stride 1 (row-walk shapes, small planes) and fp32 stride 2 on row-walk
+    # shapes; everything else runs the two passes
     assert dw.variant_name(dw.desc(128, 32, 112, 112, 3, 1, 1, 1, dw.NHWC, dw.F32), 3) == "nhwc_bwd_fused_k3s1"
     assert dw.variant_name(dw.desc(128, 64, 112, 112, 3, 2, 1, 1, dw.NHWC, dw.F32), 3) == "nhwc_bwd_fused_k3s2"
     assert dw.variant_name(dw.desc(4, 64, 115, 116, 3, 2, 1, 1, dw.NHWC, dw.F32), 3) == "separate"     # odd height
     assert dw.variant_name(dw.desc(128, 128, 56, 56, 3, 2, 1, 1, dw.NHWC, dw.F32), 3) == "nhwc_bwd_fused_k3s2"
     assert dw.variant_name(dw.desc(128, 32, 112, 112, 3, 1, 1, 1, dw.NCHW, dw.F32), 3) == "nchw_bwd_fused_k3s1"
     assert dw.variant_name(dw.desc(128, 512, 14, 14, 3, 1, 1, 1, dw.NCHW, dw.F32), 3) == "nchw_smallplane_bwd_fused_k3s1"
-    assert dw.variant_name(dw.desc(128, 512, 14, 14, 3, 2, 1, 1, dw.NCHW, dw.F32), 3) == "separate"      # stride 2
+    assert dw.variant_name(dw.desc(128, 512, 14, 14, 3, 2, 1, 1, dw.NCHW, dw.F32), 3) == "separate"      # stride 2, small planes
+    assert dw.variant_name(dw.desc(128, 64, 112, 112, 3, 2, 1, 1, dw.NCHW, dw.F32), 3) == "nchw_bwd_fused_k3s2"
+    assert dw.variant_name(dw.desc(128, 64, 112, 112, 3, 2, 1, 1, dw.NCHW, dw.BF16), 3) == "separate"
     assert dw.variant_name(dw.desc(128, 32, 112, 112, 3, 1, 1, 1, dw.NCHW, dw.BF16), 3) == "nchw_bwd_fused_k3s1"
     assert dw.variant_name(dw.desc(128, 32, 112, 112, 5, 1, 2, 1, dw.NCHW, dw.BF16), 3) == "separate"                    # 5x5
     assert dw.variant_name(dw.desc(2, 6, 9, 9, 3, 1, 1, 1, dw.NHWC, dw.F32), 3) == "separate"
