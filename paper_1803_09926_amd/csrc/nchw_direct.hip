@@ -565,7 +565,8 @@ __global__ __launch_bounds__(256) void k_nchwd_bwd_filter_k3(Geom g, const T *__
                                                              int rounds)
 {
     __shared__ float red[4][9];
-    constexpr int NW = (S == 1) ? V + 2 : 2 * V + 1;
+    constexpr int NW = (S == 1) ? V + 2 : 2 * V;       // x columns per lane and row; stride 2: the 2V columns under the lane's dy columns
+    constexpr int ND = (S == 1) ? V : V + 1;            // dy columns per lane and row; stride 2: and the one to their right
     const int o = blockIdx.y, part = blockIdx.x;
     const int ncols = g.Wo / V;                         // vectors per dy row
     // lanes are laid flat over (item, vector column): nsg = 256 / ncols items per round, no padding
@@ -605,24 +606,28 @@ __global__ __launch_bounds__(256) void k_nchwd_bwd_filter_k3(Geom g, const T *__
                     float a[V], b[V];
                     Vec<T, V>::load(rp, a);
                     Vec<T, V>::load(rp + V, b);
-                    dst[0] = ldf(rp + loff);
 #pragma unroll
-                    for (int v = 0; v < V; ++v) { dst[1 + v] = a[v]; dst[1 + V + v] = b[v]; }
+                    for (int v = 0; v < V; ++v) { dst[v] = a[v]; dst[V + v] = b[v]; }
                 }
             };
             auto mask_x = [&](int r, float (&row)[NW]) {
                 const bool rowok = r >= 0 && r < g.H;
 #pragma unroll
                 for (int i = 0; i < NW; ++i) {
-                    const bool ok = rowok && (i == 0 ? has_left : ((S == 1 && i == V + 1) ? has_right : true));
+                    const bool ok = rowok && (S == 2 ? true : (i == 0 ? has_left : (i == V + 1 ? has_right : true)));
                     row[i] = ok ? row[i] : 0.f;
                 }
             };
-            auto load_dy = [&](int oh, float (&dst)[V]) {
-                Vec<T, V>::load(dyin + (size_t)min(oh, g.Ho - 1) * g.Wo, dst);
+            auto load_dy = [&](int oh, float (&dst)[ND]) {
+                const T *rp = dyin + (size_t)min(oh, g.Ho - 1) * g.Wo;
+                float m[V];
+                Vec<T, V>::load(rp, m);
+#pragma unroll
+                for (int v = 0; v < V; ++v) dst[v] = m[v];
+                if constexpr (S == 2) dst[V] = ldf(rp + roff);
             };
             // x rows oh*S-1, oh*S, oh*S+1 meet dy row oh at tap rows 0, 1, 2.
-            float xa[NW], xb[NW], xc[3][NW], d[3][V], xs[2][NW];
+            float xa[NW], xb[NW], xc[3][NW], d[3][ND], xs[2][NW];
             load_x(oh0 * S - 1, xa);
             mask_x(oh0 * S - 1, xa);
             if constexpr (S == 1) {
@@ -661,20 +666,27 @@ __global__ __launch_bounds__(256) void k_nchwd_bwd_filter_k3(Geom g, const T *__
                     if (i + j < TH) step(oh0 + i + j, j);
             } else {
                 load_x(2 * oh0, xs[0]); load_x(2 * oh0 + 1, xc[0]); load_dy(oh0, d[0]);
+                // summed per x column (the sum over all lanes is the same as per dy column): x column 2b meets dy[oh][b]
+                // at tap column 1, x column 2b+1 meets dy[oh][b] at tap column 2 and dy[oh][b+1] at tap column 0, so a lane
+                // needs no x neighbour and every x element is loaded by exactly one lane
                 auto step = [&](int oh, int j) {
                     // rows 2oh and 2oh+1 are inside the image for every valid oh (H = 2*Ho)
-                    const float ls = has_left ? xs[j][0] : 0.f, lc = has_left ? xc[j][0] : 0.f;
-                    xs[j][0] = ls; xc[j][0] = lc;
                     const bool dok = oh < oh1;
+                    float D[V + 1];
+#pragma unroll
+                    for (int v = 0; v < V; ++v) D[v] = dok ? d[j][v] : 0.f;
+                    D[V] = (dok && has_right) ? d[j][V] : 0.f;
 #pragma unroll
                     for (int v = 0; v < V; ++v) {
-                        const float dv = dok ? d[j][v] : 0.f;
-#pragma unroll
-                        for (int kw = 0; kw < 3; ++kw) {
-                            acc[0][kw] = fmaf(dv, xa[2 * v + kw], acc[0][kw]);
-                            acc[1][kw] = fmaf(dv, xs[j][2 * v + kw], acc[1][kw]);
-                            acc[2][kw] = fmaf(dv, xc[j][2 * v + kw], acc[2][kw]);
-                        }
+                        acc[0][1] = fmaf(D[v], xa[2 * v], acc[0][1]);
+                        acc[1][1] = fmaf(D[v], xs[j][2 * v], acc[1][1]);
+                        acc[2][1] = fmaf(D[v], xc[j][2 * v], acc[2][1]);
+                        acc[0][2] = fmaf(D[v], xa[2 * v + 1], acc[0][2]);
+                        acc[1][2] = fmaf(D[v], xs[j][2 * v + 1], acc[1][2]);
+                        acc[2][2] = fmaf(D[v], xc[j][2 * v + 1], acc[2][2]);
+                        acc[0][0] = fmaf(D[v + 1], xa[2 * v + 1], acc[0][0]);
+                        acc[1][0] = fmaf(D[v + 1], xs[j][2 * v + 1], acc[1][0]);
+                        acc[2][0] = fmaf(D[v + 1], xc[j][2 * v + 1], acc[2][0]);
                     }
 #pragma unroll
                     for (int i = 0; i < NW; ++i) xa[i] = xc[j][i];
