@@ -1,11 +1,12 @@
 """Turn rocprofv3 CSV output of `bench.py` into the short text summaries kept under profiles/.
 
 Usage:
-  python -m paper_1803_09926_amd.rocprof_summary stats   <dir with *_kernel_stats.csv> [workload index of bench.py --config]
+  python -m paper_1803_09926_amd.rocprof_summary stats   <dir with *_kernel_stats.csv> [workload index of bench.py --config [fused]]
   python -m paper_1803_09926_amd.rocprof_summary traffic <FETCH_SIZE dir> <WRITE_SIZE dir> [workload index]
 
 `traffic` expects both runs to contain bench.py's --calibrate-copy dispatches (a plain device copy
 of 2^30 bytes): each counter is scaled so that the copy reads (writes) exactly 2^30 bytes.
+`fused` after the workload index: the trace is of `bench.py --fused-bwd`.
 Output goes to stdout.
 """
 import csv
@@ -80,8 +81,10 @@ def short(name):
     return name.replace("void dwc::", "").replace("dwc::", "")
 
 
-def _workload_keys(config):
-    """bench.py's "<pass>:<variant>" keys of a workload: launches per step and algorithmic bytes per step of each."""
+def _workload_keys(config, fused=False):
+    """bench.py's "<pass>:<variant>" keys of a workload: launches per step and algorithmic bytes per step of each.
+    fused: the step of `bench.py --fused-bwd`, whose backward pass is one dwconv_bwd call per layer (key "bwd:<variant>",
+    2|x| + |y| elements) where a fused kernel exists and the two separate passes elsewhere."""
     import paper_1803_09926_amd as dw
     from paper_1803_09926_amd import workloads as wl
     cfg = wl.config(config)
@@ -96,14 +99,21 @@ def _workload_keys(config):
             else:
                 d = dw.desc(cfg["N"], layer.C, layer.H, layer.W, layer.K, layer.stride, layer.pad, layer.mult, layout, cfg["dtype"])
                 vname = dw.variant_name
+            whole = vname(d, 3) if (fused and layer.cg == 1) else "separate"
             for which, pname in enumerate(("fwd", "bwd_data", "bwd_filter")):
+                if which > 0 and whole != "separate":
+                    continue
                 key = pname + ":" + vname(d, which)
                 launches[key] = launches.get(key, 0) + repeat
                 nbytes[key] = nbytes.get(key, 0) + repeat * layer.pass_bytes(cfg["N"], esz)
+            if whole != "separate":
+                key = "bwd:" + whole
+                launches[key] = launches.get(key, 0) + repeat
+                nbytes[key] = nbytes.get(key, 0) + repeat * (2 * layer.x_elems(cfg["N"]) + layer.y_elems(cfg["N"])) * esz
     return launches, nbytes
 
 
-def stats(d, config=None):
+def stats(d, config=None, fused=False):
     rows = list(csv.DictReader(open(_one(os.path.join(d, "*kernel_stats.csv")))))
     rows = [r for r in rows if "dwc::" in r["Name"]]
     total = sum(int(r["TotalDurationNs"]) for r in rows)
@@ -129,7 +139,7 @@ def stats(d, config=None):
     # per layout and pass: time per step from the trace against the algorithmic bytes of the workload
     from paper_1803_09926_amd import workloads as wl
     cfg = wl.config(config)
-    launches, nbytes = _workload_keys(config)
+    launches, nbytes = _workload_keys(config, fused)
     missing = [k for k in launches if k not in per_key]
     if missing:
         print("# keys of the workload with no kernel in the trace: " + ", ".join(missing))
@@ -137,18 +147,18 @@ def stats(d, config=None):
     steps = sorted(per_key[k][0] / launches[k] for k in known)[len(known) // 2]
     red = [r for r in rows if "k_reduce_partials" in r["Name"]]
     red_us = sum(int(r["TotalDurationNs"]) for r in red) / 1e3
-    nfilter = sum(v for k, v in launches.items() if k.startswith("bwd_filter:"))
+    nfilter = sum(v for k, v in launches.items() if k.startswith("bwd_filter:") or k.startswith("bwd:"))
     print("# workload %s: %.0f steps in the trace; per layout and pass, per step: kernel time, algorithmic bytes, rate" % (cfg["name"], steps))
-    print("# (bwd_filter = stage 1 + its share of the stage-2 launches k_reduce_partials, split by launch count)")
+    print("# (bwd_filter, and bwd = the whole backward pass in one call: stage 1 + its share of the stage-2 launches k_reduce_partials, split by launch count)")
     print("%-6s %-11s %10s %12s %9s %7s" % ("layout", "pass", "us/step", "MB/step", "GB/s", "%peak"))
     grand_us = grand_b = 0.0
     for lay in ("nchw", "nhwc"):
-        for pname in ("fwd", "bwd_data", "bwd_filter"):
+        for pname in ("fwd", "bwd_data", "bwd_filter", "bwd"):
             ks = [k for k in known if k.startswith(pname + ":") and ("_" + lay + "_" in "_" + k.split(":")[1] + "_")]
             if not ks:
                 continue
             us = sum(per_key[k][1] for k in ks) / steps
-            if pname == "bwd_filter" and nfilter:
+            if pname in ("bwd_filter", "bwd") and nfilter:
                 us += red_us / steps * sum(launches[k] for k in ks) / nfilter
             b = sum(nbytes[k] for k in ks)
             grand_us += us; grand_b += b
@@ -206,7 +216,7 @@ def traffic(dfetch, dwrite, config=None):
 
 if __name__ == "__main__":
     if len(sys.argv) >= 3 and sys.argv[1] == "stats":
-        stats(sys.argv[2], int(sys.argv[3]) if len(sys.argv) >= 4 else None)
+        stats(sys.argv[2], int(sys.argv[3]) if len(sys.argv) >= 4 else None, fused=len(sys.argv) >= 5 and sys.argv[4] == "fused")
     elif len(sys.argv) >= 4 and sys.argv[1] == "traffic":
         traffic(sys.argv[2], sys.argv[3], int(sys.argv[4]) if len(sys.argv) >= 5 else None)
     else:
