@@ -527,6 +527,125 @@ __global__ __launch_bounds__(256) void k_nchws_bwd_fused(Geom g, const T *__rest
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Fused backward pass, 3x3, stride 2, pad 1, x row width W (template, even; H even): block mapping of
+// the kernel above, one lane per (channel, dy row a).  The lane adds dy row a against x rows 2a-1,
+// 2a, 2a+1 into its 9 partial sums and computes dx rows 2a and 2a+1 from dy rows a and a+1.  The dx
+// rows stay in registers until every lane has read its x rows, then take the place of x in LDS and
+// leave as one flat range: two staging areas instead of three, which is what lets a block of
+// 28-wide planes keep ten channels.
+// ---------------------------------------------------------------------------------------------
+template <typename T, int W>
+__global__ __launch_bounds__(256) void k_nchws_bwd_fused_s2(Geom g, const T *__restrict__ x, const T *__restrict__ dy,
+                                                            const T *__restrict__ w, T *__restrict__ dx,
+                                                            float *__restrict__ ws, int U, int NI, int ncblocks,
+                                                            unsigned nblocks, int nt)
+{
+    extern __shared__ float4 smem4[];
+    constexpr int VE = ElemsS<T>::VE;
+    constexpr int K = 3, WO = W / 2;
+    const int HW = g.H * W, HoWo = g.Ho * WO;
+    const unsigned lb = xcd_remap(blockIdx.x, nblocks);
+    const int cblk = lb % ncblocks, part = lb / ncblocks;
+    const int c0 = cblk * U, nc = min(U, g.C - c0);
+    const int n0 = part * NI, n1 = min(g.N, n0 + NI);
+    float *lx = reinterpret_cast<float *>(smem4);                 // x planes, then the dx planes
+    float *ld = lx + ((U * HW + 2 * VE + 3) & ~3);
+
+    const int p = threadIdx.x / g.Ho, a = threadIdx.x - p * g.Ho;
+    const bool own = p < nc;
+    const bool has_up = a > 0, has_b = a + 1 < g.Ho;
+    float acc[K][K];
+#pragma unroll
+    for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < K; ++kw) acc[kh][kw] = 0.f;
+    float wr[K][K];
+#pragma unroll
+    for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < K; ++kw) wr[kh][kw] = ldf(w + ((c0 + min(p, nc - 1)) * K + kh) * K + kw);
+
+    FlatRegs<T> rx, rd;
+    {
+        const int gx0 = (n0 * g.C + c0) * HW, gd0 = (n0 * g.C + c0) * HoWo;
+        flat_issue<T>(x, g.N * g.C * HW, gx0, gx0 + nc * HW, rx);
+        flat_issue<T>(dy, g.N * g.C * HoWo, gd0, gd0 + nc * HoWo, rd);
+    }
+    for (int n = n0; n < n1; ++n) {
+        const int gx0 = (n * g.C + c0) * HW, gd0 = (n * g.C + c0) * HoWo;
+        __syncthreads();                          // the previous image's dx has left the staging area
+        flat_commit<T>(gx0, gx0 + nc * HW, rx, lx);
+        flat_commit<T>(gd0, gd0 + nc * HoWo, rd, ld);
+        __syncthreads();
+        if (n + 1 < n1) {
+            const int hx0 = ((n + 1) * g.C + c0) * HW, hd0 = ((n + 1) * g.C + c0) * HoWo;
+            flat_issue<T>(x, g.N * g.C * HW, hx0, hx0 + nc * HW, rx);
+            flat_issue<T>(dy, g.N * g.C * HoWo, hd0, hd0 + nc * HoWo, rd);
+        }
+        float o0[W], o1[W];                       // dx rows 2a and 2a+1
+        if (own) {
+            const float *xp = lx + (gx0 & (VE - 1)) + p * HW;
+            const float *dp = ld + (gd0 & (VE - 1)) + p * HoWo;
+            float A[WO + 1], B[WO + 1];           // dy rows a and a+1, a zero to their right
+            const float *ra = dp + a * WO, *rb = dp + (has_b ? a + 1 : a) * WO;
+#pragma unroll
+            for (int j = 0; j < WO; ++j) { A[j] = ra[j]; const float t = rb[j]; B[j] = has_b ? t : 0.f; }
+            A[WO] = 0.f; B[WO] = 0.f;
+            // filter gradient: x rows 2a-1, 2a, 2a+1; dy column j meets x column 2j-1+kw
+#pragma unroll
+            for (int kh = 0; kh < K; ++kh) {
+                const int ih = 2 * a - 1 + kh;
+                const float *rp = xp + (kh == 0 && !has_up ? 0 : ih) * W;
+                float row[W];
+#pragma unroll
+                for (int i = 0; i < W; ++i) { const float t = rp[i]; row[i] = (kh == 0 && !has_up) ? 0.f : t; }
+#pragma unroll
+                for (int kw = 0; kw < K; ++kw) {
+                    float sacc = acc[kh][kw];
+#pragma unroll
+                    for (int j = 0; j < WO; ++j) {
+                        const int iw = 2 * j - 1 + kw;
+                        if (iw >= 0 && iw < W) sacc = fmaf(A[j], row[iw], sacc);
+                    }
+                    acc[kh][kw] = sacc;
+                }
+            }
+            // input gradient (Eq. 3 at stride 2): rows 2a, 2a+1
+#pragma unroll
+            for (int b = 0; b < WO; ++b) {
+                o0[2 * b] = wr[1][1] * A[b];
+                o0[2 * b + 1] = fmaf(wr[1][0], A[b + 1], wr[1][2] * A[b]);
+                o1[2 * b] = fmaf(wr[0][1], B[b], wr[2][1] * A[b]);
+                o1[2 * b + 1] = fmaf(wr[0][0], B[b + 1], fmaf(wr[0][2], B[b], fmaf(wr[2][0], A[b + 1], wr[2][2] * A[b])));
+            }
+        }
+        __syncthreads();                          // every lane has read its x rows
+        if (own) {
+            float *op = lx + (gx0 & (VE - 1)) + p * HW + (2 * a) * W;
+#pragma unroll
+            for (int i = 0; i < W; ++i) { op[i] = o0[i]; op[W + i] = o1[i]; }
+        }
+        __syncthreads();
+        flat_store<T>(dx, gx0, gx0 + nc * HW, lx, nt != 0);
+    }
+
+    // rows of a channel are added in row order (fixed), through LDS
+    __syncthreads();
+    float *red = lx;     // 256 * 9 floats across the staging areas (the host sizes the LDS for it)
+#pragma unroll
+    for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < K; ++kw) red[threadIdx.x * (K * K) + kh * K + kw] = own ? acc[kh][kw] : 0.f;
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < nc * K * K; idx += 256) {
+        const int pc = idx / (K * K), t = idx - pc * (K * K);
+        float sum = 0.f;
+        for (int r = 0; r < g.Ho; ++r) sum += red[(pc * g.Ho + r) * (K * K) + t];
+        ws[((size_t)part * g.C + c0 + pc) * (K * K) + t] = sum;
+    }
+}
+
 // ---- host side --------------------------------------------------------------------------------
 
 static inline int cdiv(int a, int b) { return (a + b - 1) / b; }
@@ -683,7 +802,9 @@ hipError_t nchws_bwd_filter(const Geom &g, int dtype, const void *x, const void 
 // Fused backward on small planes: tiling of the filter gradient, with U bounded by the three LDS areas.
 bool nchws_bwd_fused_supported(const Geom &g)
 {
-    return nchws_supported(g, 2) && g.K == 3 && g.s == 1 && g.p == 1 && g.m == 1 && g.W != 28;
+    if (!(nchws_supported(g, 2) && g.K == 3 && g.p == 1 && g.m == 1)) return false;
+    if (g.s == 1) return g.W != 28;
+    return g.W == 28 || g.W == 14 || g.W == 8;      // stride 2 (even H and W by nchws_supported)
 }
 
 static size_t lds_bytes_fused(int U, int plane, int ve)
@@ -692,12 +813,19 @@ static size_t lds_bytes_fused(int U, int plane, int ve)
     size_t b = (3 * area + 4) * sizeof(float);
     return b < 256 * 9 * sizeof(float) ? 256 * 9 * sizeof(float) : b;
 }
+// stride 2: the x area (which the dx planes reuse) and the dy area
+static size_t lds_bytes_fused_s2(int U, int in_plane, int out_plane, int ve)
+{
+    const size_t b = lds_bytes_for(U, in_plane, out_plane, ve);
+    return b < 256 * 9 * sizeof(float) ? 256 * 9 * sizeof(float) : b;
+}
 
 void nchws_bwd_fused_tiling(const Geom &g, int dtype, int *U, int *NI, int *parts)
 {
-    nchws_bwd_filter_tiling(g, dtype, U, NI, parts);
+    nchws_bwd_filter_tiling(g, dtype, U, NI, parts);       // U within the LDS and register staging of x and dy
     const int ve = dtype == DT_F32 ? 4 : 8;
-    while (*U > 1 && lds_bytes_fused(*U, g.H * g.W, ve) > 60 * 1024) --*U;
+    if (g.s == 1)
+        while (*U > 1 && lds_bytes_fused(*U, g.H * g.W, ve) > 60 * 1024) --*U;
     const int ncb = cdiv(g.C, *U);
     int ni = (int)(((long long)g.N * ncb) / 2048);
     if (ni < 1) ni = 1;
@@ -711,10 +839,21 @@ static hipError_t go_bwd_fused(const Geom &g, const void *x, const void *dy, con
                                int NI, hipStream_t st)
 {
     constexpr int VE = ElemsS<T>::VE;
-    const size_t lds = lds_bytes_fused(U, g.H * g.W, VE);
+    const size_t lds = g.s == 1 ? lds_bytes_fused(U, g.H * g.W, VE) : lds_bytes_fused_s2(U, g.H * g.W, g.Ho * g.Wo, VE);
     const int ncb = cdiv(g.C, U);
     const unsigned nblocks = (unsigned)ncb * cdiv(g.N, NI);
     const int nt = stream_stores("NCHW_SMALL_BWD", (long long)g.N * g.C * g.H * g.W * sizeof(T), 0);
+    if (g.s == 2) {
+        if (U * g.Ho > 256 || U * g.H * g.W + VE > 8192 || lds > 64 * 1024) return hipErrorInvalidValue;
+#define GO2(WW) hipLaunchKernelGGL((k_nchws_bwd_fused_s2<T, WW>), dim3(nblocks), dim3(256), lds, st, g, (const T *)x, \
+                                   (const T *)dy, (const T *)w, (T *)dx, ws, U, NI, ncb, nblocks, nt)
+        if (g.W == 28) GO2(28);
+        else if (g.W == 14) GO2(14);
+        else if (g.W == 8) GO2(8);
+        else return hipErrorInvalidValue;
+#undef GO2
+        return hipGetLastError();
+    }
 #define GO(WW) hipLaunchKernelGGL((k_nchws_bwd_fused<T, WW>), dim3(nblocks), dim3(256), lds, st, g, (const T *)x, \
                                   (const T *)dy, (const T *)w, (T *)dx, ws, U, NI, ncb, nblocks, nt)
     if (g.W == 14) GO(14);

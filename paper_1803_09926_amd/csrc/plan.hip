@@ -312,7 +312,7 @@ Plan plan_bwd(const Geom &g, int layout, int dtype)
             if ((long long)parts * g.O * g.K * g.K * 4 <= (64ll << 20)) {
                 pl = pf;
                 pl.variant = V_NCHWS_BWD_FUSED; pl.a = U; pl.c = NI; pl.parts = parts;
-                pl.name = "nchw_smallplane_bwd_fused_k3s1";
+                pl.name = g.s == 1 ? "nchw_smallplane_bwd_fused_k3s1" : "nchw_smallplane_bwd_fused_k3s2";
                 return pl;
             }
         }

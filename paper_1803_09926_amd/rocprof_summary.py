@@ -58,6 +58,7 @@ VARIANT_KERNELS = {
     "bwd:nchw_bwd_fused_k3s1": [r"k_nchwd_bwd_fused_k3s1<"],
     "bwd:nchw_bwd_fused_k3s2": [r"k_nchwd_bwd_fused_k3s2<"],
     "bwd:nchw_smallplane_bwd_fused_k3s1": [r"k_nchws_bwd_fused<"],
+    "bwd:nchw_smallplane_bwd_fused_k3s2": [r"k_nchws_bwd_fused_s2<"],
     # group convolution: k_gconv_nchw_s1<T, V, OB, R, FLIP, SHFL>, k_gconv_nhwc_s1<T, CG, OB, GPL, PF, FLIP>
     "fwd:group_nchw_rowwalk_k3s1": [r"k_gconv_nchw_s1<[\w ]+, \d+, \d+, \d+, false[,>]"],
     "bwd_data:group_nchw_rowwalk_k3s1_flip": [r"k_gconv_nchw_s1<[\w ]+, \d+, \d+, \d+, true[,>]"],
