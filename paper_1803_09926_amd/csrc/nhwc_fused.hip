@@ -1,4 +1,4 @@
-// Fused backward pass for NHWC, 3x3, stride 1, pad 1, multiplier 1: the input gradient dx and the
+// Fused backward pass for NHWC, 3x3, stride 1, pad 1, multiplier 1 or 2: the input gradient dx and the
 // stage-1 partial sums of the filter gradient dw from ONE walk over dy and x.  Run separately the
 // two passes read dy twice; fused, the backward pass moves 2|x| + |y| elements instead of
 // 2(|x| + |y|) and is one launch less.
@@ -21,7 +21,10 @@
 
 namespace dwc {
 
-template <typename T, int V, int PF>
+// M = 2 (channel multiplier 2): the lane's V output channels sit on V/2 input channels, so x and dx are
+// vectors of V/2 channels, an element of dx adds up the terms of its two outputs, and an element of x
+// meets the dy of both.
+template <typename T, int V, int PF, int M = 1>
 __global__ __launch_bounds__(256) void k_nhwc_bwd_fused_k3s1(Geom g, const T *__restrict__ x, const T *__restrict__ dy,
                                                              const T *__restrict__ w, T *__restrict__ dx,
                                                              float *__restrict__ ws, int CT, int nctiles, int nowtiles,
@@ -36,7 +39,8 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_fused_k3s1(Geom g, const T *__
 
     const int OWT = 256 / CT;
     const int tx = threadIdx.x % CT, ty = threadIdx.x / CT;
-    const int Q = g.C / V;
+    constexpr int VX = V / M;      // input channels behind the lane's V output channels
+    const int Q = g.O / V;
     const int cq = ctile * CT + tx, ow = owtile * OWT + ty;
     const bool active = cq < Q && ow < g.W;
 
@@ -56,43 +60,46 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_fused_k3s1(Geom g, const T *__
 #pragma unroll
         for (int j = 0; j < K; ++j) {
             const int iw = ow - 1 + j;
-            coloff[j] = (iw >= 0 && iw < g.W) ? (uint32_t)(iw * g.C + cq * V) * (uint32_t)sizeof(T) : BufView::OUTSIDE;
+            coloff[j] = (iw >= 0 && iw < g.W) ? (uint32_t)(iw * g.O + cq * V) * (uint32_t)sizeof(T) : BufView::OUTSIDE;
 #pragma unroll
-            for (int kh = 0; kh < K; ++kh) Vec<T, V>::load(w + (kh * K + (2 - j)) * g.C + cq * V, wd[kh][j]);
+            for (int kh = 0; kh < K; ++kh) Vec<T, V>::load(w + (kh * K + (2 - j)) * g.O + cq * V, wd[kh][j]);
         }
-        const int rowlen = g.W * g.C;
+        const uint32_t xcol = (uint32_t)(ow * g.C + cq * VX) * (uint32_t)sizeof(T);     // the lane's x / dx column
+        const int rowlen = g.W * g.O, xrowlen = g.W * g.C;
         const uint32_t rowbytes = (uint32_t)rowlen * (uint32_t)sizeof(T), imgbytes = (uint32_t)g.H * rowbytes;   // at most 2 GiB
+        const uint32_t xrowbytes = (uint32_t)xrowlen * (uint32_t)sizeof(T), ximgbytes = (uint32_t)g.H * xrowbytes;
         const int oh0 = strip * TH, oh1 = min(g.H, oh0 + TH);
         const int n0 = ngroup * NI, n1 = min(g.N, n0 + NI);
         for (int n = n0; n < n1; ++n) {
-            const BufView xin(x + (size_t)n * g.H * rowlen, imgbytes), dyin(dy + (size_t)n * g.H * rowlen, imgbytes);
-            const BufView dxout(dx + (size_t)n * g.H * rowlen, imgbytes);
+            const BufView xin(x + (size_t)n * g.H * xrowlen, ximgbytes), dyin(dy + (size_t)n * g.H * rowlen, imgbytes);
+            const BufView dxout(dx + (size_t)n * g.H * xrowlen, ximgbytes);
 
             // step t brings dy row t (three columns) and x row t+1 (the lane's own column)
-            RawVec<T, V> dr[R][K], xr[R];
-            auto load_rows = [&](int t, RawVec<T, V> (&dd)[K], RawVec<T, V> &xd) {
+            RawVec<T, V> dr[R][K];
+            RawVec<T, VX> xr[R];
+            auto load_rows = [&](int t, RawVec<T, V> (&dd)[K], RawVec<T, VX> &xd) {
                 const uint32_t dro = (uint32_t)min(max(t, 0), g.H - 1) * rowbytes;
 #pragma unroll
                 for (int j = 0; j < K; ++j) dd[j].load_buf(dyin, coloff[j], dro);
-                xd.load_buf(xin, coloff[1], (uint32_t)min(max(t + 1, 0), g.H - 1) * rowbytes);
+                xd.load_buf(xin, xcol, (uint32_t)min(max(t + 1, 0), g.H - 1) * xrowbytes);
             };
 
             // xw[kh] = x row t-1+kh at the lane's column (zero outside the image); A0, A1: the two unfinished dx rows
-            float A0[V], A1[V], xw[K][V];
+            float A0[VX], A1[VX], xw[K][VX];
 #pragma unroll
-            for (int v = 0; v < V; ++v) { A0[v] = 0.f; A1[v] = 0.f; }
+            for (int v = 0; v < VX; ++v) { A0[v] = 0.f; A1[v] = 0.f; }
             const int t0 = oh0 - 1, nsteps = (oh1 - oh0) + 2;       // t = oh0-1 .. oh1: the dy rows a strip's dx needs
             {
                 // x row t0 enters the window ahead of the first step (it becomes row t-1 of the strip's first dy row)
-                RawVec<T, V> first;
-                first.load_buf(xin, coloff[1], (uint32_t)max(t0, 0) * rowbytes);
-                float f[V];
+                RawVec<T, VX> first;
+                first.load_buf(xin, xcol, (uint32_t)max(t0, 0) * xrowbytes);
+                float f[VX];
                 first.get(f);
 #pragma unroll
-                for (int v = 0; v < V; ++v) { xw[0][v] = 0.f; xw[1][v] = 0.f; xw[2][v] = t0 >= 0 ? f[v] : 0.f; }
+                for (int v = 0; v < VX; ++v) { xw[0][v] = 0.f; xw[1][v] = 0.f; xw[2][v] = t0 >= 0 ? f[v] : 0.f; }
             }
 
-            auto consume = [&](int t, const RawVec<T, V> (&dd)[K], const RawVec<T, V> &xd) {
+            auto consume = [&](int t, const RawVec<T, V> (&dd)[K], const RawVec<T, VX> &xd) {
                 const bool dyok = t >= 0 && t < g.H;                 // dy row t exists
                 const bool mine = t >= oh0 && t < oh1;               // ... and belongs to this block's strip
                 float d[K][V];
@@ -103,27 +110,31 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_fused_k3s1(Geom g, const T *__
                     for (int v = 0; v < V; ++v) d[j][v] = dyok ? d[j][v] : 0.f;
                 }
                 // input gradient: dy row t is tap row 0 of dx row t-1, tap row 1 of dx row t, tap row 2 of dx row t+1
-                float out[V];
+                float out[VX];
 #pragma unroll
-                for (int v = 0; v < V; ++v) {
-                    float s0 = A0[v], s1 = A1[v], s2 = 0.f;
+                for (int c = 0; c < VX; ++c) {
+                    float s0 = A0[c], s1 = A1[c], s2 = 0.f;
 #pragma unroll
-                    for (int j = 0; j < K; ++j) {
-                        s0 = fmaf(wd[0][j][v], d[j][v], s0);
-                        s1 = fmaf(wd[1][j][v], d[j][v], s1);
-                        s2 = fmaf(wd[2][j][v], d[j][v], s2);
+                    for (int mm = 0; mm < M; ++mm) {
+                        const int v = c * M + mm;
+#pragma unroll
+                        for (int j = 0; j < K; ++j) {
+                            s0 = fmaf(wd[0][j][v], d[j][v], s0);
+                            s1 = fmaf(wd[1][j][v], d[j][v], s1);
+                            s2 = fmaf(wd[2][j][v], d[j][v], s2);
+                        }
                     }
-                    out[v] = s0; A0[v] = s1; A1[v] = s2;
+                    out[c] = s0; A0[c] = s1; A1[c] = s2;
                 }
-                if (t - 1 >= oh0 && t - 1 < oh1) store_buf<T, V>(dxout, coloff[1], (uint32_t)(t - 1) * rowbytes, out, nt != 0);
+                if (t - 1 >= oh0 && t - 1 < oh1) store_buf<T, VX>(dxout, xcol, (uint32_t)(t - 1) * xrowbytes, out, nt != 0);
                 // filter gradient, summed per x column: the lane's x column c meets dy[t][c+1-kw] at tap column kw, and x
                 // rows t-1, t, t+1 at tap rows 0, 1, 2 (the sum over all columns is the same as per dy column)
                 {
-                    float xv[V];
+                    float xv[VX];
                     xd.get(xv);
                     const bool xok = t + 1 < g.H;                    // t + 1 >= 0 always (t >= -1)
 #pragma unroll
-                    for (int v = 0; v < V; ++v) { xw[0][v] = xw[1][v]; xw[1][v] = xw[2][v]; xw[2][v] = xok ? xv[v] : 0.f; }
+                    for (int v = 0; v < VX; ++v) { xw[0][v] = xw[1][v]; xw[1][v] = xw[2][v]; xw[2][v] = xok ? xv[v] : 0.f; }
                 }
                 if (mine) {
 #pragma unroll
@@ -132,7 +143,7 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_fused_k3s1(Geom g, const T *__
                         for (int v = 0; v < V; ++v) {
                             const float dd1 = d[2 - kw][v];
 #pragma unroll
-                            for (int kh = 0; kh < K; ++kh) acc[kh][kw][v] = fmaf(dd1, xw[kh][v], acc[kh][kw][v]);
+                            for (int kh = 0; kh < K; ++kh) acc[kh][kw][v] = fmaf(dd1, xw[kh][v / M], acc[kh][kw][v]);
                         }
                 }
             };
@@ -156,9 +167,9 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_fused_k3s1(Geom g, const T *__
 
     // ---- fixed-order block reduction (as in the filter-gradient kernel) ----
     const int part = (ngroup * nstrips + strip) * nowtiles + owtile;
-    float *wsp = ws + (size_t)part * (K * K * g.C);
+    float *wsp = ws + (size_t)part * (K * K * g.O);
     block_reduce_taps<K, V>(acc, CT, red, [&](int kh, int kw, int v, float total) {
-        if (cq < Q) wsp[(kh * K + kw) * g.C + cq * V + v] = total;
+        if (cq < Q) wsp[(kh * K + kw) * g.O + cq * V + v] = total;
     });
 }
 
@@ -305,7 +316,7 @@ __global__ __launch_bounds__(256) void k_nhwc_bwd_fused_k3s2(Geom g, const T *__
 
 bool nhwc_bwd_fused_supported(const Geom &g, int dtype, int V)
 {
-    if (!(g.K == 3 && g.p == 1 && g.m == 1)) return false;
+    if (!(g.K == 3 && g.p == 1 && (g.m == 1 || (g.m == 2 && g.s == 1)))) return false;
     // stride 2 (even maps): 12 % faster than the two passes on 112x112 maps, equal within 2 % on smaller ones
     if (g.s == 2) {
         const char *e = tune_env("DWCONV_TUNE_FUSE_S2H");        // tuning: smallest map height that takes the fused kernel
@@ -329,15 +340,20 @@ hipError_t nhwc_bwd_fused(const Geom &g, int dtype, int V, const void *x, const 
 #define GO(T, VV, PP) hipLaunchKernelGGL((k_nhwc_bwd_fused_k3s1<T, VV, PP>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, \
                                      (const T *)dy, (const T *)w, (T *)dx, ws, CT, nctiles, nowtiles, TH, nstrips, NI, \
                                      nblocks, nt)
+#define GOM2(T) hipLaunchKernelGGL((k_nhwc_bwd_fused_k3s1<T, 4, 2, 2>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, \
+                                   (const T *)dy, (const T *)w, (T *)dx, ws, CT, nctiles, nowtiles, TH, nstrips, NI, \
+                                   nblocks, nt)
 #define GO2(T, VV) hipLaunchKernelGGL((k_nhwc_bwd_fused_k3s2<T, VV>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, \
                                       (const T *)dy, (const T *)w, (T *)dx, ws, CT, nctiles, nowtiles, TH, nstrips, NI, \
                                       nblocks, nt)
     const char *fpf = tune_env("DWCONV_TUNE_FPF");
     const int pf = fpf ? atoi(fpf) : 2;       // two rows ahead: 2 % faster than one although it leaves two wavefronts per SIMD in fp32
-    if (g.s == 2) { if (dtype == DT_F32) GO2(float, 4); else GO2(bf16_t, 4); }
+    if (g.m == 2) { if (dtype == DT_F32) GOM2(float); else GOM2(bf16_t); }
+    else if (g.s == 2) { if (dtype == DT_F32) GO2(float, 4); else GO2(bf16_t, 4); }
     else if (dtype == DT_F32) { if (pf == 2) GO(float, 4, 2); else GO(float, 4, 1); }
     else { if (pf == 2) GO(bf16_t, 4, 2); else GO(bf16_t, 4, 1); }
 #undef GO
+#undef GOM2
 #undef GO2
     return hipGetLastError();
 }

@@ -299,7 +299,7 @@ Plan plan_bwd(const Geom &g, int layout, int dtype)
             if (pf.variant == V_NHWC_BWD_FILTER && pf.a == V) {
                 pl = pf;
                 pl.variant = V_NHWC_BWD_FUSED;
-                pl.name = g.s == 1 ? "nhwc_bwd_fused_k3s1" : "nhwc_bwd_fused_k3s2";
+                pl.name = g.m == 2 ? "nhwc_bwd_fused_k3s1_m2" : (g.s == 1 ? "nhwc_bwd_fused_k3s1" : "nhwc_bwd_fused_k3s2");
             }
         }
     }

@@ -53,7 +53,9 @@ VARIANT_KERNELS = {
     "bwd_data:nchw_smallplane_k5s1_flip": [r"k_nchws_fwd<[\w ]+, 5, 1, \d+, true, \w+>"],
     "bwd_filter:nchw_smallplane_bwd_filter_k5s1": [r"k_nchws_bwd_filter<[\w ]+, 5, 1, \d+>"],
     # whole backward pass in one kernel (dwconv_bwd)
-    "bwd:nhwc_bwd_fused_k3s1": [r"k_nhwc_bwd_fused_k3s1<"],
+    # k_nhwc_bwd_fused_k3s1<T, V, PF, M>
+    "bwd:nhwc_bwd_fused_k3s1": [r"k_nhwc_bwd_fused_k3s1<[\w ]+, \d+, \d+, 1>"],
+    "bwd:nhwc_bwd_fused_k3s1_m2": [r"k_nhwc_bwd_fused_k3s1<[\w ]+, \d+, \d+, 2>"],
     "bwd:nhwc_bwd_fused_k3s2": [r"k_nhwc_bwd_fused_k3s2<"],
     "bwd:nchw_bwd_fused_k3s1": [r"k_nchwd_bwd_fused_k3s1<"],
     "bwd:nchw_bwd_fused_k3s2": [r"k_nchwd_bwd_fused_k3s2<"],

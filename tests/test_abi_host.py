@@ -170,6 +170,11 @@ def test_whole_backward_variant_names():
     assert dw.variant_name(dw.desc(128, 32, 112, 112, 3, 1, 1, 1, dw.NCHW, dw.BF16), 3) == "nchw_bwd_fused_k3s1"
     assert dw.variant_name(dw.desc(128, 32, 112, 112, 5, 1, 2, 1, dw.NCHW, dw.BF16), 3) == "separate"                    # 5x5
     assert dw.variant_name(dw.desc(2, 6, 9, 9, 3, 1, 1, 1, dw.NHWC, dw.F32), 3) == "separate"
+    # channel multiplier 2 (stride 1): the stride-1 kernel with two outputs per input channel
+    assert dw.variant_name(dw.desc(32, 256, 56, 56, 3, 1, 1, 2, dw.NHWC, dw.F32), 3) == "nhwc_bwd_fused_k3s1_m2"
+    assert dw.variant_name(dw.desc(32, 6, 12, 12, 3, 1, 1, 2, dw.NHWC, dw.BF16), 3) == "nhwc_bwd_fused_k3s1_m2"
+    assert dw.variant_name(dw.desc(32, 256, 56, 56, 3, 2, 1, 2, dw.NHWC, dw.F32), 3) == "separate"
+    assert dw.variant_name(dw.desc(32, 256, 56, 56, 3, 1, 1, 2, dw.NCHW, dw.F32), 3) == "separate"
     # bf16 NHWC: the fused kernels with four channels per lane
     assert dw.variant_name(dw.desc(256, 512, 14, 14, 3, 1, 1, 1, dw.NHWC, dw.BF16), 3) == "nhwc_bwd_fused_k3s1"
     assert dw.variant_name(dw.desc(256, 512, 14, 14, 3, 2, 1, 1, dw.NHWC, dw.BF16), 3) == "nhwc_bwd_fused_k3s2"
