@@ -213,7 +213,9 @@ static GPlan gplan(const GGeom &g, int layout, int dtype, int pass)
         if (pass == 2) pl.parts = gconv_nchw_bwd_filter_parts(g);
     } else if (layout == LAYOUT_NHWC && gconv_nhwc_supported(g)) {
         pl.variant = GV_NHWC_K3S1;
-        pl.name = pass == 0 ? "group_nhwc_rowwalk_k3s1" : pass == 1 ? "group_nhwc_rowwalk_k3s1_flip" : "group_nhwc_bwd_filter_k3s1";
+        const bool mm = pass < 2 && gconv_nhwc_mfma_supported(g, dtype);      // forward and backward-data on the matrix cores
+        pl.name = pass == 0 ? (mm ? "group_nhwc_mfma_k3s1" : "group_nhwc_rowwalk_k3s1")
+                : pass == 1 ? (mm ? "group_nhwc_mfma_k3s1_flip" : "group_nhwc_rowwalk_k3s1_flip") : "group_nhwc_bwd_filter_k3s1";
         if (pass == 2) pl.parts = gconv_nhwc_bwd_filter_parts(g, dtype);
     }
     // a tuned filter gradient whose partial sums would not fit in 64 MiB (very wide rows): the generic kernels

@@ -52,4 +52,9 @@ hipError_t gconv_nhwc_xchg_s1(const GGeom &g, int dtype, const void *in, const v
 hipError_t gconv_nhwc_xchg_bwd_filter(const GGeom &g, int dtype, const void *x, const void *dy, float *ws, int CT, int nctiles,
                                       int nowtiles, int TH, int nstrips, int NI, unsigned nblocks, int J, hipStream_t st);
 
+// ---- NHWC on the matrix cores: 4 or 8 channels per group on both sides, channels a multiple of 64 (bf16: 128)
+// (gconv_nhwc_mfma.hip); gconv_nhwc_s1 forwards to it where it applies
+bool gconv_nhwc_mfma_supported(const GGeom &g, int dtype);
+hipError_t gconv_nhwc_mfma_s1(const GGeom &g, int dtype, const void *in, const void *w, void *out, bool flip, hipStream_t st);
+
 }  // namespace dwc

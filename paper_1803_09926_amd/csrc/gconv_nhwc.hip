@@ -343,6 +343,7 @@ static hipError_t launch_gs1(const GGeom &g, const void *in, const void *w, void
 hipError_t gconv_nhwc_s1(const GGeom &g, int dtype, const void *in, const void *w, void *out, bool flip, hipStream_t st)
 {
     if (!gconv_nhwc_supported(g)) return hipErrorInvalidValue;
+    if (gconv_nhwc_mfma_supported(g, dtype)) return gconv_nhwc_mfma_s1(g, dtype, in, w, out, flip, st);
     if (gconv_nhwc_xchg_supported(g)) return gconv_nhwc_xchg_s1(g, dtype, in, w, out, flip, st);
     const int CG = flip ? g.Og : g.Cg, CGW = flip ? g.Cg : g.Og;
     const int OB = nhwc_ob(CG, CGW);

@@ -68,6 +68,9 @@ VARIANT_KERNELS = {
     # k_gconv_nhwc_xchg<T, CG, V, PF, FLIP>: the lane-exchange walk (groups of 4 or 8 channels)
     "fwd:group_nhwc_rowwalk_k3s1": [r"k_gconv_nhwc_s1<[\w ]+, \d+, \d+, \d+, \d+, false>", r"k_gconv_nhwc_xchg<[\w ]+, \d+, \d+, \d+, false>"],
     "bwd_data:group_nhwc_rowwalk_k3s1_flip": [r"k_gconv_nhwc_s1<[\w ]+, \d+, \d+, \d+, \d+, true>", r"k_gconv_nhwc_xchg<[\w ]+, \d+, \d+, \d+, true>"],
+    # k_gconv_nhwc_mfma<T, CG, FLIP, PF>
+    "fwd:group_nhwc_mfma_k3s1": [r"k_gconv_nhwc_mfma<[\w ]+, \d+, false, \d+>"],
+    "bwd_data:group_nhwc_mfma_k3s1_flip": [r"k_gconv_nhwc_mfma<[\w ]+, \d+, true, \d+>"],
     "bwd_filter:group_nhwc_bwd_filter_k3s1": [r"k_gconv_nhwc_bwd_filter<", r"k_gconv_nhwc_xchg_bwd_filter<"],
 }
 

@@ -49,6 +49,14 @@ CASES = [
     ("cg2_c6_tall", 7, 6, 6, 3, 61, 10, 3, 1, 1),
     ("cg4_h1", 2, 8, 8, 2, 1, 16, 3, 1, 1),
     ("cg4_w2", 2, 8, 8, 2, 9, 2, 3, 1, 1),
+    # channel counts that are multiples of 64 with 4 or 8 channels per group: NHWC forward and backward-data run on
+    # the matrix cores (last column quad partly outside the row, one strip and several, one row, one column)
+    ("mm_cg4_c64_w14", 3, 64, 64, 16, 17, 14, 3, 1, 1),
+    ("mm_cg4_c128_h40", 2, 128, 128, 32, 40, 9, 3, 1, 1),
+    ("mm_cg8_c64_w13", 3, 64, 64, 8, 15, 13, 3, 1, 1),
+    ("mm_cg8_c128_h33", 2, 128, 128, 16, 33, 6, 3, 1, 1),
+    ("mm_cg4_h1", 2, 64, 64, 16, 1, 5, 3, 1, 1),
+    ("mm_cg8_w1", 2, 64, 64, 8, 30, 1, 3, 1, 1),
 ]
 
 
@@ -194,3 +202,26 @@ def test_group_conv_writes_nothing_outside_its_outputs():
                 for buf, v in [(ybuf, yv), (dxbuf, dxv), (dwbuf, dwv)]:
                     n = v.numel()
                     assert (buf[:G_] == 12345.0).all() and (buf[G_ + n:] == 12345.0).all(), (name, layout, dtype)
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+def test_group_nhwc_matrix_core_kernels_forced_tilings(dtype):
+    """The matrix-core NHWC kernels walk several images per wavefront only on large batches; the tiling overrides force
+    that path (ragged last image group) and short strips (ragged last strip) at sizes the oracle checks element by
+    element."""
+    cases = [("mmx_cg4", 5, 128, 128, 32, 13, 10, 3, 1, 1), ("mmx_cg8", 7, 128, 128, 16, 11, 7, 3, 1, 1)]
+    knobs = [{"DWCONV_TUNE_GMNI": "2", "DWCONV_TUNE_GMTH": "5"}, {"DWCONV_TUNE_GMNI": "3"}, {"DWCONV_TUNE_GMTH": "3"}]
+    for case in cases:
+        name, N, C, O, G, H, W, K, s, p = case
+        assert dw.gconv_variant_name(dw.group_desc(N, C, H, W, K, s, p, G, O, wl.NHWC, dtype), 0) == "group_nhwc_mfma_k3s1"
+        x, w, dy = wl.make_group_inputs(N, C, O, G, H, W, K, s, p, wl.NHWC, dtype, seed=97)
+        kw = dict(K=K, stride=s, pad=p, groups=G, O=O, layout=wl.NHWC, nthreads=8)
+        want = (og.fwd(x, w, **kw), og.bwd_data(dy, w, x_shape=x.shape, **kw))
+        tol = gu.TOL_F32 if dtype == wl.F32 else gu.TOL_BF16
+        for kn in knobs:
+            with dw.tuning_overrides(kn):
+                print("case", name, "knobs", kn, flush=True)
+                y, dx, _ = run_gpu(case, wl.NHWC, dtype, x, w, dy)
+            tag = "%s %s dtype=%d" % (name, kn, dtype)
+            gu.assert_close(gu.to_host(y), want[0], tol, "gconv fwd " + tag)
+            gu.assert_close(gu.to_host(dx), want[1], tol, "gconv bwd_data " + tag)
