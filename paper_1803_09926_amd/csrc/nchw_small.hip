@@ -402,8 +402,10 @@ __global__ __launch_bounds__(256) void k_nchws_bwd_filter(Geom g, const T *__res
 // the lane accumulates its 9 partial sums from the x rows around its dy row, and it computes row
 // `oh` of dx from the dy rows around it with the rotated filter; the dx planes go to a third
 // LDS area and leave as one flat range with aligned 16-byte streaming stores.
+// INPLACE (28-wide rows, where three areas would leave a block four channels): the dx rows wait in
+// registers until every lane has read its x rows and then take x's place in LDS.
 // ---------------------------------------------------------------------------------------------
-template <typename T, int W>
+template <typename T, int W, bool INPLACE>
 __global__ __launch_bounds__(256) void k_nchws_bwd_fused(Geom g, const T *__restrict__ x, const T *__restrict__ dy,
                                                          const T *__restrict__ w, T *__restrict__ dx,
                                                          float *__restrict__ ws, int U, int NI, int ncblocks,
@@ -420,7 +422,7 @@ __global__ __launch_bounds__(256) void k_nchws_bwd_fused(Geom g, const T *__rest
     const int area = (U * HW + 2 * VE + 3) & ~3;
     float *lx = reinterpret_cast<float *>(smem4);
     float *ld = lx + area;
-    float *lo = ld + area;
+    float *lo = INPLACE ? lx : ld + area;
 
     const int p = threadIdx.x / g.H, oh = threadIdx.x - p * g.H;
     const bool own = p < nc;
@@ -461,6 +463,7 @@ __global__ __launch_bounds__(256) void k_nchws_bwd_fused(Geom g, const T *__rest
             flat_issue<T>(x, g.N * g.C * HW, h0, h0 + nc * HW, rx);
             flat_issue<T>(dy, g.N * g.C * HW, h0, h0 + nc * HW, rd);
         }
+        float out[W];
         if (own) {
             const int off = (g0 & (VE - 1)) + p * HW;
             const float *xp = lx + off, *dpl = ld + off;
@@ -486,7 +489,6 @@ __global__ __launch_bounds__(256) void k_nchws_bwd_fused(Geom g, const T *__rest
                 }
             }
             // input gradient: row oh of dx = rotated filter over dy rows oh-1, oh, oh+1
-            float out[W];
 #pragma unroll
             for (int j = 0; j < W; ++j) out[j] = 0.f;
 #pragma unroll
@@ -503,9 +505,19 @@ __global__ __launch_bounds__(256) void k_nchws_bwd_fused(Geom g, const T *__rest
                         if (iw >= 0 && iw < W) out[j] = fmaf(wr[kh][kw], row[iw], out[j]);
                     }
             }
-            float *op = lo + off + oh * W;
+            if constexpr (!INPLACE) {
+                float *op = lo + off + oh * W;
 #pragma unroll
-            for (int j = 0; j < W; ++j) op[j] = out[j];
+                for (int j = 0; j < W; ++j) op[j] = out[j];
+            }
+        }
+        if constexpr (INPLACE) {
+            __syncthreads();                      // every lane has read its x rows
+            if (own) {
+                float *op = lo + (g0 & (VE - 1)) + p * HW + oh * W;
+#pragma unroll
+                for (int j = 0; j < W; ++j) op[j] = out[j];
+            }
         }
         __syncthreads();
         flat_store<T>(dx, g0, g0 + nc * HW, lo, nt != 0);
@@ -803,14 +815,14 @@ hipError_t nchws_bwd_filter(const Geom &g, int dtype, const void *x, const void 
 bool nchws_bwd_fused_supported(const Geom &g)
 {
     if (!(nchws_supported(g, 2) && g.K == 3 && g.p == 1 && g.m == 1)) return false;
-    if (g.s == 1) return g.W != 28;
+    if (g.s == 1) return true;                      // 28-wide rows with the dx planes in x's LDS area
     return g.W == 28 || g.W == 14 || g.W == 8;      // stride 2 (even H and W by nchws_supported)
 }
 
-static size_t lds_bytes_fused(int U, int plane, int ve)
+static size_t lds_bytes_fused(int U, int plane, int ve, int areas = 3)
 {
     const size_t area = (size_t)((U * plane + 2 * ve + 3) & ~3);
-    size_t b = (3 * area + 4) * sizeof(float);
+    size_t b = ((size_t)areas * area + 4) * sizeof(float);
     return b < 256 * 9 * sizeof(float) ? 256 * 9 * sizeof(float) : b;
 }
 // stride 2: the x area (which the dx planes reuse) and the dy area
@@ -825,7 +837,7 @@ void nchws_bwd_fused_tiling(const Geom &g, int dtype, int *U, int *NI, int *part
     nchws_bwd_filter_tiling(g, dtype, U, NI, parts);       // U within the LDS and register staging of x and dy
     const int ve = dtype == DT_F32 ? 4 : 8;
     if (g.s == 1)
-        while (*U > 1 && lds_bytes_fused(*U, g.H * g.W, ve) > 60 * 1024) --*U;
+        while (*U > 1 && lds_bytes_fused(*U, g.H * g.W, ve, g.W == 28 ? 2 : 3) > 60 * 1024) --*U;
     const int ncb = cdiv(g.C, *U);
     int ni = (int)(((long long)g.N * ncb) / 2048);
     if (ni < 1) ni = 1;
@@ -839,7 +851,8 @@ static hipError_t go_bwd_fused(const Geom &g, const void *x, const void *dy, con
                                int NI, hipStream_t st)
 {
     constexpr int VE = ElemsS<T>::VE;
-    const size_t lds = g.s == 1 ? lds_bytes_fused(U, g.H * g.W, VE) : lds_bytes_fused_s2(U, g.H * g.W, g.Ho * g.Wo, VE);
+    const size_t lds = g.s == 1 ? lds_bytes_fused(U, g.H * g.W, VE, g.W == 28 ? 2 : 3)
+                                : lds_bytes_fused_s2(U, g.H * g.W, g.Ho * g.Wo, VE);
     const int ncb = cdiv(g.C, U);
     const unsigned nblocks = (unsigned)ncb * cdiv(g.N, NI);
     const int nt = stream_stores("NCHW_SMALL_BWD", (long long)g.N * g.C * g.H * g.W * sizeof(T), 0);
@@ -854,12 +867,13 @@ static hipError_t go_bwd_fused(const Geom &g, const void *x, const void *dy, con
 #undef GO2
         return hipGetLastError();
     }
-#define GO(WW) hipLaunchKernelGGL((k_nchws_bwd_fused<T, WW>), dim3(nblocks), dim3(256), lds, st, g, (const T *)x, \
-                                  (const T *)dy, (const T *)w, (T *)dx, ws, U, NI, ncb, nblocks, nt)
-    if (g.W == 14) GO(14);
-    else if (g.W == 7) GO(7);
-    else if (g.W == 8) GO(8);
-    else if (g.W == 4) GO(4);
+#define GO(WW, IP) hipLaunchKernelGGL((k_nchws_bwd_fused<T, WW, IP>), dim3(nblocks), dim3(256), lds, st, g, (const T *)x, \
+                                      (const T *)dy, (const T *)w, (T *)dx, ws, U, NI, ncb, nblocks, nt)
+    if (g.W == 14) GO(14, false);
+    else if (g.W == 7) GO(7, false);
+    else if (g.W == 8) GO(8, false);
+    else if (g.W == 4) GO(4, false);
+    else if (g.W == 28) { if (U * g.H > 256 || lds > 64 * 1024) return hipErrorInvalidValue; GO(28, true); }
     else return hipErrorInvalidValue;
 #undef GO
     return hipGetLastError();

@@ -306,7 +306,9 @@ Plan plan_bwd(const Geom &g, int layout, int dtype)
     if (layout == LAYOUT_NCHW && !tune_env("DWCONV_TUNE_NOFUSE")) {
         // a fused kernel of either family, whichever the separate filter gradient would run on
         Plan pf = pl;
-        if (use_small(g, dtype, 2) && nchws_bwd_fused_supported(g) && plan_bwd_filter_nchws(g, dtype, pf)) {
+        // (28-wide fp32 rows at stride 1 are whole 16-byte vectors: they stay with the row-walk fused kernel below)
+        const bool rowwalk28 = g.s == 1 && g.W == 28 && dtype == DT_F32;
+        if (use_small(g, dtype, 2) && !rowwalk28 && nchws_bwd_fused_supported(g) && plan_bwd_filter_nchws(g, dtype, pf)) {
             int U, NI, parts;
             nchws_bwd_fused_tiling(g, dtype, &U, &NI, &parts);
             if ((long long)parts * g.O * g.K * g.K * 4 <= (64ll << 20)) {

@@ -165,6 +165,9 @@ def test_whole_backward_variant_names():
     assert dw.variant_name(dw.desc(128, 256, 28, 28, 3, 2, 1, 1, dw.NCHW, dw.F32), 3) == "nchw_smallplane_bwd_fused_k3s2"
     assert dw.variant_name(dw.desc(256, 256, 28, 28, 3, 2, 1, 1, dw.NCHW, dw.BF16), 3) == "nchw_smallplane_bwd_fused_k3s2"
     assert dw.variant_name(dw.desc(8, 40, 7, 7, 3, 2, 1, 1, dw.NCHW, dw.F32), 3) == "separate"           # odd planes at stride 2
+    # 28-wide rows at stride 1: fp32 rows are whole 16-byte vectors (row walk), bf16 rows take the small-plane kernel
+    assert dw.variant_name(dw.desc(128, 256, 28, 28, 3, 1, 1, 1, dw.NCHW, dw.F32), 3) == "nchw_bwd_fused_k3s1"
+    assert dw.variant_name(dw.desc(256, 256, 28, 28, 3, 1, 1, 1, dw.NCHW, dw.BF16), 3) == "nchw_smallplane_bwd_fused_k3s1"
     assert dw.variant_name(dw.desc(128, 64, 112, 112, 3, 2, 1, 1, dw.NCHW, dw.F32), 3) == "nchw_bwd_fused_k3s2"
     assert dw.variant_name(dw.desc(128, 64, 112, 112, 3, 2, 1, 1, dw.NCHW, dw.BF16), 3) == "separate"
     assert dw.variant_name(dw.desc(128, 32, 112, 112, 3, 1, 1, 1, dw.NCHW, dw.BF16), 3) == "nchw_bwd_fused_k3s1"
