@@ -131,9 +131,10 @@ int dwconv_bwd_filter_noalloc(const dwconv_desc *desc, const void *x, const void
  * (Section III-A, backward propagation: both gradients come from the same dy; the paper's
  * Table III reports them as one "Backward" time).  Where a fused kernel exists (3x3, pad 1,
  * multiplier 1, and multiplier 2 in NHWC at stride 1.  Stride 1: NHWC; NCHW with rows of whole
- * 16-byte vectors; NCHW planes with rows of 4, 7, 8, 14 or 28.  Stride 2: NHWC on even maps; NCHW
- * fp32 on even maps with rows of 56 and more; NCHW planes with rows of 8, 14 or 28 and an even
- * height) dy and x are read once and the pass moves 2|x| + |y| elements instead of
+ * 16-byte vectors; NCHW planes with rows of 4, 7, 8, 14 or 28.  Stride 2: NHWC on even maps;
+ * NCHW on even maps with rows of 56 and more in fp32, 112 and more in bf16; NCHW planes with
+ * rows of 8, 14 or 28 and an even height) dy and x are read once and the pass moves
+ * 2|x| + |y| elements instead of
  * 2(|x| + |y|); every other shape runs the two passes one after the other on `stream`, with
  * results identical to the separate calls.  dwconv_variant_name(desc, 3) tells which.
  * x, dy, w: device, read.  dx: device, every element written.  dw: device, fp32, written in full.

@@ -1494,9 +1494,13 @@ int nchwd_bwd_fused_rs(const Geom &g, int dtype, int V)
 {
     if (!(g.K == 3 && g.p == 1 && g.m == 1)) return 0;
     if (g.s == 2) {
-        // stride 2: fp32, two dy columns (four dx columns = one 16-byte vector) per lane
-        if (!(dtype == DT_F32 && V == 2 && g.H % 2 == 0 && g.W % 2 == 0 && g.Wo % 2 == 0)) return 0;
-        const int rs = row_group(g.W, 4);
+        // stride 2: two dy columns per lane in fp32, four in bf16 (the dx columns under them are one 16-byte vector).
+        // bf16 on rows of 112 and more only (the 112x112 layer at batch 256: 183 us against 219 for the two passes and
+        // their stage 2; the 56x56 layer 108 against 101)
+        const bool f = dtype == DT_F32 && V == 2;
+        const bool b = dtype == DT_BF16 && V == 4 && g.W >= 112 && !tune_env("DWCONV_TUNE_NOFUSE_NCHW_BF16");
+        if (!((f || b) && g.H % 2 == 0 && g.W % 2 == 0 && g.Wo % V == 0)) return 0;
+        const int rs = row_group(g.W, f ? 4 : 2);
         return (rs && g.H % rs == 0 && g.Wo / V <= 256) ? rs : 0;
     }
     if (g.s != 1) return 0;
@@ -1518,9 +1522,10 @@ hipError_t nchwd_bwd_fused(const Geom &g, int dtype, int V, const void *x, const
     dim3 grid(parts, g.C);
 #define GO(T, VV, RSV) hipLaunchKernelGGL((k_nchwd_bwd_fused_k3s1<T, VV, RSV>), grid, dim3(256), 0, st, g, (const T *)x, \
                                           (const T *)dy, (const T *)w, (T *)dx, ws, TH, nstrips, lg, rounds)
-#define GO2(RSV) hipLaunchKernelGGL((k_nchwd_bwd_fused_k3s2<float, 2, RSV>), grid, dim3(256), 0, st, g, (const float *)x, \
-                                    (const float *)dy, (const float *)w, (float *)dx, ws, TH, nstrips, lg, rounds)
-    if (g.s == 2) { if (rs == 2) GO2(2); else GO2(4); }
+#define GO2(T, VV, RSV) hipLaunchKernelGGL((k_nchwd_bwd_fused_k3s2<T, VV, RSV>), grid, dim3(256), 0, st, g, (const T *)x, \
+                                           (const T *)dy, (const T *)w, (T *)dx, ws, TH, nstrips, lg, rounds)
+    if (g.s == 2 && dtype == DT_F32) { if (rs == 2) GO2(float, 2, 2); else GO2(float, 2, 4); }
+    else if (g.s == 2) { if (rs == 2) GO2(bf16_t, 4, 2); else GO2(bf16_t, 4, 4); }
     else if (dtype == DT_F32) { if (rs == 2) GO(float, 4, 2); else GO(float, 4, 4); }
     else { if (rs == 2) GO(bf16_t, 8, 2); else GO(bf16_t, 8, 4); }
 #undef GO

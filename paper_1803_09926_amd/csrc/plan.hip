@@ -322,7 +322,7 @@ Plan plan_bwd(const Geom &g, int layout, int dtype)
         if (g.s == 2 && !use_small(g, dtype, 2) && !tune_env("DWCONV_TUNE_NOFUSE_NCHW_S2") && plan_bwd_filter_nchwd(g, dtype, pf)) {
             // stride 2 on row-walk shapes: two dy columns per lane, strips of the filter gradient's height made even
             // where a write-out group is four dx rows
-            const int V2 = 2, rs = nchwd_bwd_fused_rs(g, dtype, V2);
+            const int V2 = dtype == DT_F32 ? 2 : 4, rs = nchwd_bwd_fused_rs(g, dtype, V2);
             if (rs) {
                 const int TH = (2 * pf.b) % rs == 0 ? pf.b : pf.b + 1;
                 int lg, nst, rounds, parts;

@@ -169,7 +169,8 @@ def test_whole_backward_variant_names():
     assert dw.variant_name(dw.desc(128, 256, 28, 28, 3, 1, 1, 1, dw.NCHW, dw.F32), 3) == "nchw_bwd_fused_k3s1"
     assert dw.variant_name(dw.desc(256, 256, 28, 28, 3, 1, 1, 1, dw.NCHW, dw.BF16), 3) == "nchw_smallplane_bwd_fused_k3s1"
     assert dw.variant_name(dw.desc(128, 64, 112, 112, 3, 2, 1, 1, dw.NCHW, dw.F32), 3) == "nchw_bwd_fused_k3s2"
-    assert dw.variant_name(dw.desc(128, 64, 112, 112, 3, 2, 1, 1, dw.NCHW, dw.BF16), 3) == "separate"
+    assert dw.variant_name(dw.desc(128, 64, 112, 112, 3, 2, 1, 1, dw.NCHW, dw.BF16), 3) == "nchw_bwd_fused_k3s2"
+    assert dw.variant_name(dw.desc(128, 128, 56, 56, 3, 2, 1, 1, dw.NCHW, dw.BF16), 3) == "separate"      # bf16 rows under 112
     assert dw.variant_name(dw.desc(128, 32, 112, 112, 3, 1, 1, 1, dw.NCHW, dw.BF16), 3) == "nchw_bwd_fused_k3s1"
     assert dw.variant_name(dw.desc(128, 32, 112, 112, 5, 1, 2, 1, dw.NCHW, dw.BF16), 3) == "separate"                    # 5x5
     assert dw.variant_name(dw.desc(2, 6, 9, 9, 3, 1, 1, 1, dw.NHWC, dw.F32), 3) == "separate"
