@@ -20,6 +20,7 @@ import time
 PEAK_HBM_GBS = 8000.0
 # fp32 vector peak: 256 compute units x 128 fp32 multiply-add lanes per clock x 2 flops x 2.4 GHz
 PEAK_ALU_TFLOPS = 157.3
+PEAK_MFMA_TFLOPS = {0: 157.3, 1: 2500.0}      # dense matrix-core peak by storage type: fp32, bf16
 METRIC = "ms and HBM GB/s (% of peak) per fwd+bwd of MobileNet-v1 dw stack, batch 128"
 PASS_NAMES = ("fwd", "bwd_data", "bwd_filter", "bwd")
 
@@ -416,12 +417,15 @@ def main():
         alu_in_step = dom["flops"] / ms_in_step / 1e9                    # TFLOP/s
         ai = dom["flops"] / dom["bytes"]
         # which roofline binds: the one whose peak gives the longer minimum time for this kernel's bytes and flops
-        alu_binds = dom["flops"] / (PEAK_ALU_TFLOPS * 1e12) > dom["bytes"] / (PEAK_HBM_GBS * 1e9)
+        # (a kernel that runs its contraction on the matrix cores is priced against their dense peak for its type)
+        on_mfma = "mfma" in dom_key
+        peak_flops = (PEAK_MFMA_TFLOPS[cfg["dtype"]] if on_mfma else PEAK_ALU_TFLOPS)
+        alu_binds = dom["flops"] / (peak_flops * 1e12) > dom["bytes"] / (PEAK_HBM_GBS * 1e9)
         prof = stored_profile(cfg["name"], dom_key)
-        roof = {"bound": "alu" if alu_binds else "hbm", "kernel": dom_key,
+        roof = {"bound": ("mfma" if on_mfma else "alu") if alu_binds else "hbm", "kernel": dom_key,
                 "achieved": round(alu_in_step if alu_binds else hbm_in_step, 1),
-                "peak": PEAK_ALU_TFLOPS if alu_binds else PEAK_HBM_GBS, "unit": "TFLOP/s" if alu_binds else "GB/s",
-                "frac": round(alu_in_step / PEAK_ALU_TFLOPS if alu_binds else hbm_in_step / PEAK_HBM_GBS, 4),
+                "peak": peak_flops if alu_binds else PEAK_HBM_GBS, "unit": "TFLOP/s" if alu_binds else "GB/s",
+                "frac": round(alu_in_step / peak_flops if alu_binds else hbm_in_step / PEAK_HBM_GBS, 4),
                 "frac_is": "in-step: event-bracketed launch time x (step wall time / sum of bracketed times)",
                 "frac_bracketed": round(hbm_bracketed / PEAK_HBM_GBS, 4),
                 "in_step_stretch": round(stretch, 4),
@@ -439,12 +443,14 @@ def main():
         if ai > 10.0:
             # near the ridge (157.3 TFLOP/s / 8 TB/s = 19.7 flop/B): both fractions
             roof["frac_hbm"] = round(hbm_in_step / PEAK_HBM_GBS, 4)
-            roof["frac_alu"] = round(alu_in_step / PEAK_ALU_TFLOPS, 4)
+            roof["frac_mfma" if on_mfma else "frac_alu"] = round(alu_in_step / peak_flops, 4)
         out["roofline"] = roof
         # every kernel family of the step, against both rooflines (in-step durations)
         out["per_kernel"] = {k: {"launches": v["launches"], "in_step_ms": round(v["ms"] * stretch, 4),
                                  "frac_hbm": round(v["bytes"] / (v["ms"] * stretch) / 1e6 / PEAK_HBM_GBS, 4),
-                                 "frac_alu": round(v["flops"] / (v["ms"] * stretch) / 1e9 / PEAK_ALU_TFLOPS, 4),
+                                 ("frac_mfma" if "mfma" in k else "frac_alu"):
+                                     round(v["flops"] / (v["ms"] * stretch) / 1e9 /
+                                           (PEAK_MFMA_TFLOPS[cfg["dtype"]] if "mfma" in k else PEAK_ALU_TFLOPS), 4),
                                  "flop_per_byte": round(v["flops"] / v["bytes"], 2)}
                              for k, v in sorted(by_variant.items(), key=lambda kv: -kv[1]["ms"])}
         if args.report:
