@@ -213,7 +213,14 @@ __device__ __forceinline__ void fma_quad_acc(float (&a)[4][3], float v, const fl
 // (own channel, three columns) and dy row r+1 (own channel, own column); x row r meets dy rows r+1, r, r-1 at tap
 // rows 0, 1, 2.  The lane accumulates dw[kh][kw][ci][own o] for the CG input channels ci of its group, whose x
 // values it reads from the other lanes of the group.  ws[part][kh][kw][ci][o].
-template <typename T, int CG, int PF>
+// MM: the sums on the matrix cores.  The four lanes of a quad are four channels of one group at one pixel, so a
+// 4x4x1 matrix instruction with A = the lanes' x values and B = their dy values adds the outer product
+// x[ci] * dy[o] of the quad in one instruction (D: register i of lane j = input channel i of the quad against the lane's
+// own output channel): one instruction per tap instead of four multiply-adds with cross-lane operands.  Groups of 8
+// add the mirrored x value (the group's other quad) the same way.  The matrix instructions run on every lane whatever
+// the execution mask, so lanes outside the tensor walk along on clamped addresses with their dy forced to zero.
+typedef float v4fx_t __attribute__((ext_vector_type(4)));
+template <typename T, int CG, int PF, bool MM>
 __global__ __launch_bounds__(256) void k_gconv_nhwc_xchg_bwd_filter(GGeom g, const T *__restrict__ x, const T *__restrict__ dy,
                                                                     float *__restrict__ ws, int CT, int nctiles, int nowtiles,
                                                                     int TH, int nstrips, int NI, unsigned nblocks, int J)
@@ -233,16 +240,22 @@ __global__ __launch_bounds__(256) void k_gconv_nhwc_xchg_bwd_filter(GGeom g, con
     const int sub = c % CG;
 
     float acc[3][NH][4][3];                        // [kw][own / mirrored register][quad permute][kh]
+    v4fx_t accm[3][NH][3];                         // MM: [kw][own / mirrored register][kh], element i = lane i of the quad
 #pragma unroll
     for (int kw = 0; kw < 3; ++kw)
 #pragma unroll
-        for (int h = 0; h < NH; ++h)
+        for (int h = 0; h < NH; ++h) {
 #pragma unroll
             for (int q = 0; q < 4; ++q)
 #pragma unroll
                 for (int kh = 0; kh < 3; ++kh) acc[kw][h][q][kh] = 0.f;
+#pragma unroll
+            for (int kh = 0; kh < 3; ++kh) accm[kw][h][kh] = v4fx_t{0.f, 0.f, 0.f, 0.f};
+        }
 
-    if (active) {
+    if (active || MM) {
+        // MM: lanes outside the tensor take the addresses of the last channel / column and contribute zeros
+        const int c = min(ctile * CT + tx, g.C - 1), ow = min(owtile * OWT + ty, g.W - 1);
         bool colok[3];
         int coloff[3];
 #pragma unroll
@@ -268,7 +281,7 @@ __global__ __launch_bounds__(256) void k_gconv_nhwc_xchg_bwd_filter(GGeom g, con
             };
             auto consume = [&](int r, const RawVec<T, 1> (&xd)[3], const RawVec<T, 1> &dd) {
                 const bool xok = r >= 0 && r < g.H;
-                const bool dok = r + 1 >= oh0 && r + 1 < oh1;       // only dy rows of this block's strip count
+                const bool dok = r + 1 >= oh0 && r + 1 < oh1 && active;       // only dy rows of this block's strip count
                 float d[1];
                 dd.get(d);
                 dyw[2] = dyw[1]; dyw[1] = dyw[0]; dyw[0] = dok ? d[0] : 0.f;
@@ -277,10 +290,22 @@ __global__ __launch_bounds__(256) void k_gconv_nhwc_xchg_bwd_filter(GGeom g, con
                     float xv[1];
                     xd[kw].get(xv);
                     const float xx = xok ? xv[0] : 0.f;
-                    fma_quad_acc(acc[kw][0], xx, dyw);
-                    if constexpr (NH == 2) {
-                        const float m = half_mirror(xx);
-                        fma_quad_acc(acc[kw][1], m, dyw);
+                    if constexpr (MM) {
+#pragma unroll
+                        for (int kh = 0; kh < 3; ++kh)
+                            accm[kw][0][kh] = __builtin_amdgcn_mfma_f32_4x4x1f32(xx, dyw[kh], accm[kw][0][kh], 0, 0, 0);
+                        if constexpr (NH == 2) {
+                            const float m = half_mirror(xx);
+#pragma unroll
+                            for (int kh = 0; kh < 3; ++kh)
+                                accm[kw][1][kh] = __builtin_amdgcn_mfma_f32_4x4x1f32(m, dyw[kh], accm[kw][1][kh], 0, 0, 0);
+                        }
+                    } else {
+                        fma_quad_acc(acc[kw][0], xx, dyw);
+                        if constexpr (NH == 2) {
+                            const float m = half_mirror(xx);
+                            fma_quad_acc(acc[kw][1], m, dyw);
+                        }
                     }
                 }
             };
@@ -310,7 +335,7 @@ __global__ __launch_bounds__(256) void k_gconv_nhwc_xchg_bwd_filter(GGeom g, con
 #pragma unroll
                     for (int q = 0; q < 4; ++q)
 #pragma unroll
-                        for (int kh = 0; kh < 3; ++kh) acc[kw][h][q][kh] = 0.f;
+                        for (int kh = 0; kh < 3; ++kh) { acc[kw][h][q][kh] = 0.f; accm[kw][h][kh][q] = 0.f; }
             }
     }
 
@@ -325,14 +350,15 @@ __global__ __launch_bounds__(256) void k_gconv_nhwc_xchg_bwd_filter(GGeom g, con
 #pragma unroll
             for (int h = 0; h < NH; ++h)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) red[wv][h * 4 + q][lane] = wave_sum_strided(acc[kw][h][q][kh], CT);
+                for (int q = 0; q < 4; ++q) red[wv][h * 4 + q][lane] = wave_sum_strided(MM ? accm[kw][h][kh][q] : acc[kw][h][q][kh], CT);
             __syncthreads();
             if (wv == 0 && lane < CT && c < g.C) {
 #pragma unroll
                 for (int h = 0; h < NH; ++h)
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
-                        const int e = h * 4 + q, ci = sub ^ (h ? 7 - q : q);       // the partner's channel in the group
+                        // the partner's channel in the group (MM: q is the partner's lane number in the quad; mirrored: of lane^7's quad)
+                        const int e = h * 4 + q, ci = MM ? (((sub & ~3) + q) ^ (h ? 7 : 0)) : (sub ^ (h ? 7 - q : q));
                         wsp[((kh * 3 + kw) * g.Cg + ci) * g.O + c] =
                             (red[0][e][lane] + red[1][e][lane]) + (red[2][e][lane] + red[3][e][lane]);
                     }
@@ -409,13 +435,16 @@ hipError_t gconv_nhwc_xchg_bwd_filter(const GGeom &g, int dtype, const void *x, 
                                       int nowtiles, int TH, int nstrips, int NI, unsigned nblocks, int J, hipStream_t st)
 {
     if (!gconv_nhwc_xchg_supported(g) || CT < g.Cg || CT % g.Cg != 0 || 256 % CT != 0) return hipErrorInvalidValue;
-#define TRY(T, CGG) if (g.Cg == CGG) { hipLaunchKernelGGL((k_gconv_nhwc_xchg_bwd_filter<T, CGG, 3>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, (const T *)dy, ws, CT, nctiles, nowtiles, TH, nstrips, NI, nblocks, J); return hipGetLastError(); }
+    const bool mm = xtune("DWCONV_TUNE_GXMM", 1) != 0;
+#define GOF(T, CGG, MMM) hipLaunchKernelGGL((k_gconv_nhwc_xchg_bwd_filter<T, CGG, 3, MMM>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, (const T *)dy, ws, CT, nctiles, nowtiles, TH, nstrips, NI, nblocks, J)
+#define TRY(T, CGG) if (g.Cg == CGG) { if (mm) GOF(T, CGG, true); else GOF(T, CGG, false); return hipGetLastError(); }
     if (dtype == DT_F32) {
         TRY(float, 4); TRY(float, 8);
     } else {
         TRY(bf16_t, 4); TRY(bf16_t, 8);
     }
 #undef TRY
+#undef GOF
     return hipErrorInvalidValue;
 }
 
