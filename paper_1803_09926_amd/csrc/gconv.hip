@@ -203,11 +203,30 @@ hipError_t gconv_generic_bwd_filter(const GGeom &g, int layout, int dtype, const
 
 // ---- variant selection -------------------------------------------------------------------------------
 
+// the same tensor shapes as a depthwise geometry (for the kernels shared with the depthwise layer; C == O)
+static Geom as_geom(const GGeom &g)
+{
+    Geom q;
+    q.N = g.N; q.C = g.C; q.H = g.H; q.W = g.W; q.K = g.K; q.s = g.s; q.p = g.p; q.m = 1; q.O = g.O; q.Ho = g.Ho; q.Wo = g.Wo;
+    return q;
+}
+
 static GPlan gplan(const GGeom &g, int layout, int dtype, int pass)
 {
     GPlan pl = {GV_GENERIC, pass == 2 ? gconv_generic_bwd_filter_parts(g) : 0, 0, 0, 0, "group_generic"};
     if (tune_env("DWCONV_TUNE_GROUP_GENERIC")) return pl;
-    if (layout == LAYOUT_NCHW && gconv_nchw_supported(g)) {
+    // The filter gradient takes the small-plane form for groups of up to 4 on rows of up to 14, and on 28-wide rows in
+    // bf16 (fp32 batch 128: 14x14 groups of 4 37 against 55 us, 28x28 groups of 4 83 against 85, groups of 8 122 against
+    // 103; bf16 batch 256: 48 against 95, 83 against 107, 166 against 160)
+    const bool small_ok = pass < 2 || (g.Cg <= 4 && (g.W <= 14 || dtype == DT_BF16));
+    if (layout == LAYOUT_NCHW && g.Cg == g.Og && small_ok && nchws_group_supported(as_geom(g), g.Cg) &&
+        !tune_env("DWCONV_TUNE_GNOSMALL")) {
+        // small planes (rows of 7, 14 or 28): whole groups staged in LDS through flat 16-byte accesses
+        pl.variant = GV_NCHWS_K3S1;
+        pl.name = pass == 0 ? "group_nchw_smallplane_k3s1" : pass == 1 ? "group_nchw_smallplane_k3s1_flip"
+                                                                        : "group_nchw_smallplane_bwd_filter_k3s1";
+        if (pass == 2) nchws_bwd_filter_tiling(as_geom(g), dtype, &pl.a, &pl.c, &pl.parts, g.Cg);
+    } else if (layout == LAYOUT_NCHW && gconv_nchw_supported(g)) {
         pl.variant = GV_NCHW_K3S1;
         pl.name = pass == 0 ? "group_nchw_rowwalk_k3s1" : pass == 1 ? "group_nchw_rowwalk_k3s1_flip" : "group_nchw_bwd_filter_k3s1";
         if (pass == 2) pl.parts = gconv_nchw_bwd_filter_parts(g);
@@ -303,7 +322,8 @@ int gconv_fwd(const dwconv_group_desc *desc, const void *x, const void *w, void 
     if (gmisaligned(x) || gmisaligned(w) || gmisaligned(y)) return DWCONV_ERR_ALIGN;
     const GPlan pl = gplan(g, desc->layout, desc->dtype, 0);
     hipError_t e;
-    if (pl.variant == GV_NCHW_K3S1) e = gconv_nchw_s1(g, desc->dtype, x, w, y, false, (hipStream_t)stream);
+    if (pl.variant == GV_NCHWS_K3S1) e = nchws_group_fwd(as_geom(g), g.Cg, desc->dtype, x, w, y, false, (hipStream_t)stream);
+    else if (pl.variant == GV_NCHW_K3S1) e = gconv_nchw_s1(g, desc->dtype, x, w, y, false, (hipStream_t)stream);
     else if (pl.variant == GV_NHWC_K3S1) e = gconv_nhwc_s1(g, desc->dtype, x, w, y, false, (hipStream_t)stream);
     else e = gconv_generic_fwd(g, desc->layout, desc->dtype, x, w, y, (hipStream_t)stream);
     return e == hipSuccess ? DWCONV_OK : DWCONV_ERR_LAUNCH;
@@ -322,7 +342,8 @@ int gconv_bwd_data(const dwconv_group_desc *desc, const void *dy, const void *w,
     if (gmisaligned(dy) || gmisaligned(w) || gmisaligned(dx)) return DWCONV_ERR_ALIGN;
     const GPlan pl = gplan(g, desc->layout, desc->dtype, 1);
     hipError_t e;
-    if (pl.variant == GV_NCHW_K3S1) e = gconv_nchw_s1(g, desc->dtype, dy, w, dx, true, (hipStream_t)stream);
+    if (pl.variant == GV_NCHWS_K3S1) e = nchws_group_fwd(as_geom(g), g.Cg, desc->dtype, dy, w, dx, true, (hipStream_t)stream);
+    else if (pl.variant == GV_NCHW_K3S1) e = gconv_nchw_s1(g, desc->dtype, dy, w, dx, true, (hipStream_t)stream);
     else if (pl.variant == GV_NHWC_K3S1) e = gconv_nhwc_s1(g, desc->dtype, dy, w, dx, true, (hipStream_t)stream);
     else e = gconv_generic_bwd_data(g, desc->layout, desc->dtype, dy, w, dx, (hipStream_t)stream);
     return e == hipSuccess ? DWCONV_OK : DWCONV_ERR_LAUNCH;
@@ -346,7 +367,8 @@ int gconv_bwd_filter(const dwconv_group_desc *desc, const void *x, const void *d
     if (!workspace || workspace_bytes < need) return DWCONV_ERR_WORKSPACE;
     if (gmisaligned(workspace)) return DWCONV_ERR_ALIGN;
     hipError_t e;
-    if (pl.variant == GV_NCHW_K3S1) e = gconv_nchw_bwd_filter(g, desc->dtype, x, dy, (float *)workspace, pl.parts, (hipStream_t)stream);
+    if (pl.variant == GV_NCHWS_K3S1) e = nchws_group_bwd_filter(as_geom(g), g.Cg, desc->dtype, x, dy, (float *)workspace, pl.a, pl.c, (hipStream_t)stream);
+    else if (pl.variant == GV_NCHW_K3S1) e = gconv_nchw_bwd_filter(g, desc->dtype, x, dy, (float *)workspace, pl.parts, (hipStream_t)stream);
     else if (pl.variant == GV_NHWC_K3S1) e = gconv_nhwc_bwd_filter(g, desc->dtype, x, dy, (float *)workspace, pl.parts, (hipStream_t)stream);
     else e = gconv_generic_bwd_filter(g, desc->layout, desc->dtype, x, dy, (float *)workspace, pl.parts, (hipStream_t)stream);
     if (e != hipSuccess) return DWCONV_ERR_LAUNCH;

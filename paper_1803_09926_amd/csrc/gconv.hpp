@@ -12,7 +12,7 @@ struct GGeom {
     int Ho, Wo;
 };
 
-enum GVariant { GV_GENERIC = 0, GV_NCHW_K3S1, GV_NHWC_K3S1 };
+enum GVariant { GV_GENERIC = 0, GV_NCHW_K3S1, GV_NHWC_K3S1, GV_NCHWS_K3S1 };
 
 struct GPlan {
     int variant;

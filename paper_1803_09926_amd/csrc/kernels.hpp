@@ -89,7 +89,12 @@ hipError_t nchwd_bwd_filter(const Geom &g, int dtype, int V, const void *x, cons
 bool nchws_supported(const Geom &g, int pass);
 hipError_t nchws_fwd(const Geom &g, int dtype, const void *x, const void *w, void *y, bool flip, hipStream_t st);
 hipError_t nchws_bwd_data_s2(const Geom &g, int dtype, const void *dy, const void *w, void *dx, hipStream_t st);
-void nchws_bwd_filter_tiling(const Geom &g, int dtype, int *U, int *NI, int *parts);
+// group convolution with cg channels per group on both sides through the same forward kernel (filter [O][cg][3][3])
+bool nchws_group_supported(const Geom &g, int cg);
+hipError_t nchws_group_fwd(const Geom &g, int cg, int dtype, const void *x, const void *w, void *y, bool flip, hipStream_t st);
+void nchws_bwd_filter_tiling(const Geom &g, int dtype, int *U, int *NI, int *parts, int cg = 1);
+hipError_t nchws_group_bwd_filter(const Geom &g, int cg, int dtype, const void *x, const void *dy, float *ws, int U, int NI,
+                                  hipStream_t st);
 // fused backward on small planes (3x3 stride 1): x and dy staged in LDS once for both gradients
 bool nchws_bwd_fused_supported(const Geom &g);
 void nchws_bwd_fused_tiling(const Geom &g, int dtype, int *U, int *NI, int *parts);

@@ -158,10 +158,14 @@ __device__ __forceinline__ void flat_store(T *__restrict__ dst, int g0, int g1, 
 // registers while the current tile is computed from LDS and written out, so a block's memory latency is paid once.
 // INPLACE: the outputs (a lane's whole row, held in registers) go back into the LDS area of the inputs once every
 // lane has read its rows, which halves the block's LDS and doubles the blocks per CU on 28-wide planes.
-template <typename T, int K, int S, int W, bool FLIP, bool INPLACE>
+// CG > 1 (3x3 stride 1): a group convolution with CG channels per group on both sides (Section V-B).  The planes of a group
+// are neighbours in memory and a tile holds whole groups (U a multiple of CG), so the lane of output plane o adds up the CG
+// input planes of its group from the same staged tile; filter [O][CG][3][3].
+template <typename T, int K, int S, int W, bool FLIP, bool INPLACE, int CG = 1>
 __global__ __launch_bounds__(256) void k_nchws_fwd(Geom g, const T *__restrict__ x, const T *__restrict__ w,
                                                    T *__restrict__ y, int U, int nplanes, unsigned nblocks, int nt, int TPB)
 {
+    static_assert(CG == 1 || (K == 3 && S == 1), "group form: 3x3 stride 1");
     extern __shared__ float4 smem4[];
     constexpr int VE = ElemsS<T>::VE;
     constexpr int P = (K - 1) / 2;
@@ -197,6 +201,10 @@ __global__ __launch_bounds__(256) void k_nchws_fwd(Geom g, const T *__restrict__
     float out[WO];
     if (p < np) {
         const int c = (p0 + p) % g.C;
+#pragma unroll
+        for (int j = 0; j < WO; ++j) out[j] = 0.f;
+#pragma unroll
+        for (int ci = 0; ci < CG; ++ci) {
         float wr[K][K];
         // taps on rows outside the image are dropped by zeroing their weights (the row address is clamped)
 #pragma unroll
@@ -205,13 +213,17 @@ __global__ __launch_bounds__(256) void k_nchws_fwd(Geom g, const T *__restrict__
             const bool ok = ih >= 0 && ih < g.H;
 #pragma unroll
             for (int kw = 0; kw < K; ++kw) {
-                const float t = ldf(w + (c * K + (FLIP ? K - 1 - kh : kh)) * K + (FLIP ? K - 1 - kw : kw));
+                const int tap = (FLIP ? K - 1 - kh : kh) * K + (FLIP ? K - 1 - kw : kw);
+                int widx;
+                if constexpr (CG == 1) widx = c * K * K + tap;
+                else if constexpr (!FLIP) widx = (c * CG + ci) * K * K + tap;               // w[o = c][ci]
+                else widx = ((c - c % CG + ci) * CG + c % CG) * K * K + tap;                 // w[o = the group's ci-th][the lane's channel]
+                const float t = ldf(w + widx);
                 wr[kh][kw] = ok ? t : 0.f;
             }
         }
-        const float *pl = lin + (gi0 & (VE - 1)) + p * HW;
-#pragma unroll
-        for (int j = 0; j < WO; ++j) out[j] = 0.f;
+        // the plane read: the lane's own (depthwise), or plane ci of the lane's group (p0 is a multiple of CG)
+        const float *pl = lin + (gi0 & (VE - 1)) + (CG == 1 ? p : p - p % CG + ci) * HW;
 #pragma unroll
         for (int kh = 0; kh < K; ++kh) {
             const int ih = min(max(oh * S - P + kh, 0), g.H - 1);
@@ -226,6 +238,7 @@ __global__ __launch_bounds__(256) void k_nchws_fwd(Geom g, const T *__restrict__
                     const int iw = j * S - P + kw;
                     if (iw >= 0 && iw < W) out[j] = fmaf(wr[kh][kw], row[iw], out[j]);
                 }
+        }
         }
         if constexpr (!INPLACE) {
             float *op = lout + (go0 & (VE - 1)) + p * HoWo + oh * WO;
@@ -303,11 +316,15 @@ __global__ __launch_bounds__(256) void k_nchws_bwd_data_s2(Geom g, const T *__re
 // partial sums in registers across the images.  At the end the rows of a channel are added in
 // row order through LDS and one partial per block is written at ws[part][c][kh][kw].
 // ---------------------------------------------------------------------------------------------
-template <typename T, int K, int S, int W>
+// CG > 1 (3x3 stride 1): group convolution with CG channels per group on both sides; the lane of output plane o keeps
+// 9 sums for each of the CG input planes of its group (all in the block's tile: U is a multiple of CG); partial sums
+// at ws[part][o][ci][kh][kw].
+template <typename T, int K, int S, int W, int CG = 1>
 __global__ __launch_bounds__(256) void k_nchws_bwd_filter(Geom g, const T *__restrict__ x, const T *__restrict__ dy,
                                                           float *__restrict__ ws, int U, int NI, int ncblocks,
                                                           unsigned nblocks)
 {
+    static_assert(CG == 1 || (K == 3 && S == 1), "group form: 3x3 stride 1");
     extern __shared__ float4 smem4[];
     constexpr int VE = ElemsS<T>::VE;
     constexpr int P = (K - 1) / 2;
@@ -321,11 +338,13 @@ __global__ __launch_bounds__(256) void k_nchws_bwd_filter(Geom g, const T *__res
     float *ld = lx + ((U * HW + 2 * VE + 3) & ~3);
 
     const int p = threadIdx.x / g.Ho, oh = threadIdx.x - p * g.Ho;
-    float acc[K][K];
+    float acc[CG][K][K];
 #pragma unroll
-    for (int kh = 0; kh < K; ++kh)
+    for (int ci = 0; ci < CG; ++ci)
 #pragma unroll
-        for (int kw = 0; kw < K; ++kw) acc[kh][kw] = 0.f;
+        for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+            for (int kw = 0; kw < K; ++kw) acc[ci][kh][kw] = 0.f;
     bool rowok[K];
     int rowi[K];
 #pragma unroll
@@ -354,44 +373,51 @@ __global__ __launch_bounds__(256) void k_nchws_bwd_filter(Geom g, const T *__res
             flat_issue<T>(dy, g.N * g.O * HoWo, hd0, hd0 + nc * HoWo, rd);
         }
         if (p < nc) {
-            const float *xp = lx + (gx0 & (VE - 1)) + p * HW;
             const float *dp = ld + (gd0 & (VE - 1)) + p * HoWo + oh * WO;
             float d[WO];
 #pragma unroll
             for (int j = 0; j < WO; ++j) d[j] = dp[j];
 #pragma unroll
-            for (int kh = 0; kh < K; ++kh) {
-                const float *rp = xp + rowi[kh] * W;
-                float row[W];
+            for (int ci = 0; ci < CG; ++ci) {
+                // the x plane: the lane's own (depthwise), or plane ci of the lane's group (c0 is a multiple of CG)
+                const float *xp = lx + (gx0 & (VE - 1)) + (CG == 1 ? p : p - p % CG + ci) * HW;
 #pragma unroll
-                for (int i = 0; i < W; ++i) { const float t = rp[i]; row[i] = rowok[kh] ? t : 0.f; }
+                for (int kh = 0; kh < K; ++kh) {
+                    const float *rp = xp + rowi[kh] * W;
+                    float row[W];
 #pragma unroll
-                for (int kw = 0; kw < K; ++kw) {
-                    float s = acc[kh][kw];
+                    for (int i = 0; i < W; ++i) { const float t = rp[i]; row[i] = rowok[kh] ? t : 0.f; }
 #pragma unroll
-                    for (int j = 0; j < WO; ++j) {
-                        const int iw = j * S - P + kw;
-                        if (iw >= 0 && iw < W) s = fmaf(d[j], row[iw], s);
+                    for (int kw = 0; kw < K; ++kw) {
+                        float s = acc[ci][kh][kw];
+#pragma unroll
+                        for (int j = 0; j < WO; ++j) {
+                            const int iw = j * S - P + kw;
+                            if (iw >= 0 && iw < W) s = fmaf(d[j], row[iw], s);
+                        }
+                        acc[ci][kh][kw] = s;
                     }
-                    acc[kh][kw] = s;
                 }
             }
         }
     }
 
-    // rows of a channel are added in row order (fixed), through LDS
-    __syncthreads();
+    // rows of a channel are added in row order (fixed), through LDS; one input channel of the group at a time
     float *red = lx;     // 256 * K*K floats, reusing the staging areas (the host sizes the LDS for it)
 #pragma unroll
-    for (int kh = 0; kh < K; ++kh)
+    for (int ci = 0; ci < CG; ++ci) {
+        __syncthreads();
 #pragma unroll
-        for (int kw = 0; kw < K; ++kw) red[threadIdx.x * (K * K) + kh * K + kw] = (p < nc) ? acc[kh][kw] : 0.f;
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < nc * K * K; idx += 256) {
-        const int pc = idx / (K * K), t = idx - pc * (K * K);
-        float s = 0.f;
-        for (int r = 0; r < g.Ho; ++r) s += red[(pc * g.Ho + r) * (K * K) + t];
-        ws[((size_t)part * g.O + c0 + pc) * (K * K) + t] = s;
+        for (int kh = 0; kh < K; ++kh)
+#pragma unroll
+            for (int kw = 0; kw < K; ++kw) red[threadIdx.x * (K * K) + kh * K + kw] = (p < nc) ? acc[ci][kh][kw] : 0.f;
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < nc * K * K; idx += 256) {
+            const int pc = idx / (K * K), t = idx - pc * (K * K);
+            float s = 0.f;
+            for (int r = 0; r < g.Ho; ++r) s += red[(pc * g.Ho + r) * (K * K) + t];
+            ws[(((size_t)part * g.O + c0 + pc) * CG + ci) * (K * K) + t] = s;
+        }
     }
 }
 
@@ -684,16 +710,18 @@ static size_t lds_bytes_for(int U, int in_plane, int out_plane, int ve)
 }
 
 template <typename T>
-static hipError_t go_fwd(const Geom &g, const void *x, const void *w, void *y, bool flip, hipStream_t st)
+static hipError_t go_fwd(const Geom &g, const void *x, const void *w, void *y, bool flip, hipStream_t st, int cg = 1)
 {
     constexpr int VE = ElemsS<T>::VE;
     int U = planes_per_block(g);
+    if (cg > 1 && !(g.K == 3 && g.s == 1 && (g.W == 7 || g.W == 14 || g.W == 28) && g.C % cg == 0)) return hipErrorInvalidValue;
     const int HW = g.H * g.W, HoWo = g.Ho * g.Wo;
     while (U > 1 && lds_bytes_for(U, HW, HoWo, VE) > 60 * 1024) --U;
     // a tile's planes must fit the register staging that lets the next tile load while this one is computed (8192
     // elements): the 28-wide stride-2 forward takes 10 planes per tile instead of 15 and is 13 % faster for it
     while (U > 1 && U * HW + VE > 8192) --U;
     if (const char *e = tune_env("DWCONV_TUNE_SU")) { if (atoi(e) >= 1 && atoi(e) < U) U = atoi(e); }
+    if (cg > 1) { U -= U % cg; if (U < cg) return hipErrorInvalidValue; }       // whole groups per tile
     // outputs back into the input area when two areas would leave room for at most three blocks per CU
     bool inplace = g.W == 28 && lds_bytes_for(U, HW, HoWo, VE) > 40 * 1024;
     if (const char *e = tune_env("DWCONV_TUNE_SINPLACE")) inplace = g.W == 28 && atoi(e) != 0;
@@ -714,6 +742,17 @@ static hipError_t go_fwd(const Geom &g, const void *x, const void *w, void *y, b
                                                   (const T *)x, (const T *)w, (T *)y, U, nplanes, nblocks, nt, tpb)
 #define PICK(KK, SS, WW) if (g.K == KK && g.s == SS && g.W == WW && !inplace) { if (flip) GO(KK, SS, WW, true, false); else GO(KK, SS, WW, false, false); return hipGetLastError(); }
 #define PICKIP(KK, SS, WW) if (g.K == KK && g.s == SS && g.W == WW && inplace) { if (flip) GO(KK, SS, WW, true, true); else GO(KK, SS, WW, false, true); return hipGetLastError(); }
+#define GOG(WW, FL, IP, CGG) hipLaunchKernelGGL((k_nchws_fwd<T, 3, 1, WW, FL, IP, CGG>), dim3(nblocks), dim3(256), lds, st, g, \
+                                                (const T *)x, (const T *)w, (T *)y, U, nplanes, nblocks, nt, tpb)
+#define PICKG(WW, IP, CGG) if (cg == CGG && g.W == WW && inplace == IP) { if (flip) GOG(WW, true, IP, CGG); else GOG(WW, false, IP, CGG); return hipGetLastError(); }
+#define PICKGW(CGG) PICKG(7, false, CGG) PICKG(14, false, CGG) PICKG(28, false, CGG) PICKG(28, true, CGG)
+    if (cg > 1) {
+        PICKGW(2) PICKGW(4) PICKGW(8)
+        return hipErrorInvalidValue;
+    }
+#undef PICKGW
+#undef PICKG
+#undef GOG
     PICK(3, 1, 7) PICK(3, 1, 14) PICK(3, 1, 28) PICK(3, 2, 14) PICK(3, 2, 28) PICK(5, 1, 7) PICK(5, 1, 14) PICK(5, 1, 28)
     PICK(3, 1, 4) PICK(3, 1, 8) PICK(3, 2, 8)
     PICKIP(3, 1, 28) PICKIP(3, 2, 28) PICKIP(5, 1, 28)
@@ -726,6 +765,18 @@ static hipError_t go_fwd(const Geom &g, const void *x, const void *w, void *y, b
 hipError_t nchws_fwd(const Geom &g, int dtype, const void *x, const void *w, void *y, bool flip, hipStream_t st)
 {
     return dtype == DT_F32 ? go_fwd<float>(g, x, w, y, flip, st) : go_fwd<bf16_t>(g, x, w, y, flip, st);
+}
+
+// Group convolution on small planes: 3x3 stride 1 pad 1, cg = 2, 4 or 8 channels per group on both sides, rows of 7, 14 or 28.
+bool nchws_group_supported(const Geom &g, int cg)
+{
+    return g.K == 3 && g.s == 1 && g.p == 1 && g.m == 1 && (cg == 2 || cg == 4 || cg == 8) && g.C % cg == 0 &&
+           (g.W == 7 || g.W == 14 || g.W == 28) && g.H <= 32 && 256 / g.H >= cg;
+}
+hipError_t nchws_group_fwd(const Geom &g, int cg, int dtype, const void *x, const void *w, void *y, bool flip, hipStream_t st)
+{
+    if (!nchws_group_supported(g, cg)) return hipErrorInvalidValue;
+    return dtype == DT_F32 ? go_fwd<float>(g, x, w, y, flip, st, cg) : go_fwd<bf16_t>(g, x, w, y, flip, st, cg);
 }
 
 template <typename T>
@@ -755,7 +806,7 @@ hipError_t nchws_bwd_data_s2(const Geom &g, int dtype, const void *dy, const voi
 }
 
 // planes (channels) per block and images per block for the filter gradient
-void nchws_bwd_filter_tiling(const Geom &g, int dtype, int *U, int *NI, int *parts)
+void nchws_bwd_filter_tiling(const Geom &g, int dtype, int *U, int *NI, int *parts, int cg)
 {
     const int ve = dtype == DT_F32 ? 4 : 8;
     int u = planes_per_block(g);
@@ -764,6 +815,7 @@ void nchws_bwd_filter_tiling(const Geom &g, int dtype, int *U, int *NI, int *par
     while (u > 1 && lds_bytes_for(u, HW, HoWo, ve) > 60 * 1024) --u;
     // a block's planes of one image must fit the register staging of the loader (8192 elements per tensor)
     while (u > 1 && (u * HW + ve > 8192 || u * HoWo + ve > 8192)) --u;
+    if (cg > 1 && u >= cg) u -= u % cg;            // group convolution: whole groups per block
     *U = u;
     // Images per block.  Planes of 14x14 and smaller: about 1000 blocks in the launch but at most four images per
     // block (a block that walks four images instead of one writes a quarter of the partial sums and pays the block
@@ -779,7 +831,8 @@ void nchws_bwd_filter_tiling(const Geom &g, int dtype, int *U, int *NI, int *par
 }
 
 template <typename T>
-static hipError_t go_bwd_filter(const Geom &g, const void *x, const void *dy, float *ws, int U, int NI, hipStream_t st)
+static hipError_t go_bwd_filter(const Geom &g, const void *x, const void *dy, float *ws, int U, int NI, hipStream_t st,
+                                int cg = 1)
 {
     constexpr int VE = ElemsS<T>::VE;
     const int HW = g.H * g.W, HoWo = g.Ho * g.Wo;
@@ -789,6 +842,17 @@ static hipError_t go_bwd_filter(const Geom &g, const void *x, const void *dy, fl
     const unsigned nblocks = (unsigned)ncb * cdiv(g.N, NI);
 #define GO(KK, SS, WW) hipLaunchKernelGGL((k_nchws_bwd_filter<T, KK, SS, WW>), dim3(nblocks), dim3(256), lds, st, g, \
                                           (const T *)x, (const T *)dy, ws, U, NI, ncb, nblocks)
+#define GOG(WW, CGG) hipLaunchKernelGGL((k_nchws_bwd_filter<T, 3, 1, WW, CGG>), dim3(nblocks), dim3(256), lds, st, g, \
+                                        (const T *)x, (const T *)dy, ws, U, NI, ncb, nblocks)
+#define PICKG(CGG) if (cg == CGG) { if (g.W == 7) GOG(7, CGG); else if (g.W == 14) GOG(14, CGG); else if (g.W == 28) GOG(28, CGG); \
+                                    else return hipErrorInvalidValue; return hipGetLastError(); }
+    if (cg > 1) {
+        if (!(g.K == 3 && g.s == 1) || U % cg != 0) return hipErrorInvalidValue;
+        PICKG(2) PICKG(4)          // groups of 8 measured slower than the row-walk filter gradient and are not routed here
+        return hipErrorInvalidValue;
+    }
+#undef PICKG
+#undef GOG
     if (g.K == 3 && g.s == 1 && g.W == 7) GO(3, 1, 7);
     else if (g.K == 3 && g.s == 1 && g.W == 14) GO(3, 1, 14);
     else if (g.K == 3 && g.s == 1 && g.W == 28) GO(3, 1, 28);
@@ -809,6 +873,13 @@ hipError_t nchws_bwd_filter(const Geom &g, int dtype, const void *x, const void 
                             hipStream_t st)
 {
     return dtype == DT_F32 ? go_bwd_filter<float>(g, x, dy, ws, U, NI, st) : go_bwd_filter<bf16_t>(g, x, dy, ws, U, NI, st);
+}
+
+hipError_t nchws_group_bwd_filter(const Geom &g, int cg, int dtype, const void *x, const void *dy, float *ws, int U, int NI,
+                                  hipStream_t st)
+{
+    if (!nchws_group_supported(g, cg)) return hipErrorInvalidValue;
+    return dtype == DT_F32 ? go_bwd_filter<float>(g, x, dy, ws, U, NI, st, cg) : go_bwd_filter<bf16_t>(g, x, dy, ws, U, NI, st, cg);
 }
 
 // Fused backward on small planes: tiling of the filter gradient, with U bounded by the three LDS areas.

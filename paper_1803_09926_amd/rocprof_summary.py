@@ -42,16 +42,16 @@ VARIANT_KERNELS = {
     "bwd_filter:nchw_rowwalk_bwd_filter_k3s1": [r"k_nchwd_bwd_filter_k3<[\w ]+, \d+, 1>", r"k_nchwd_bwd_filter_s1_bf16<\d+, 3>"],
     "bwd_filter:nchw_rowwalk_bwd_filter_k3s2": [r"k_nchwd_bwd_filter_k3<[\w ]+, \d+, 2>"],
     "bwd_filter:nchw_rowwalk_bwd_filter_k5s1": [r"k_nchwd_bwd_filter_s1<[\w ]+, \d+, 5>", r"k_nchwd_bwd_filter_s1_bf16<\d+, 5>"],
-    # k_nchws_fwd<T, K, S, W, FLIP, INPLACE>, k_nchws_bwd_filter<T, K, S, W>
-    "fwd:nchw_smallplane_k3s1": [r"k_nchws_fwd<[\w ]+, 3, 1, \d+, false, \w+>"],
-    "bwd_data:nchw_smallplane_k3s1_flip": [r"k_nchws_fwd<[\w ]+, 3, 1, \d+, true, \w+>"],
-    "fwd:nchw_smallplane_fwd_k3s2": [r"k_nchws_fwd<[\w ]+, 3, 2, \d+, false, \w+>"],
+    # k_nchws_fwd<T, K, S, W, FLIP, INPLACE, CG>, k_nchws_bwd_filter<T, K, S, W, CG> (CG = 1: depthwise)
+    "fwd:nchw_smallplane_k3s1": [r"k_nchws_fwd<[\w ]+, 3, 1, \d+, false, \w+, 1>"],
+    "bwd_data:nchw_smallplane_k3s1_flip": [r"k_nchws_fwd<[\w ]+, 3, 1, \d+, true, \w+, 1>"],
+    "fwd:nchw_smallplane_fwd_k3s2": [r"k_nchws_fwd<[\w ]+, 3, 2, \d+, false, \w+, 1>"],
     "bwd_data:nchw_smallplane_bwd_data_k3s2": [r"k_nchws_bwd_data_s2<"],
-    "bwd_filter:nchw_smallplane_bwd_filter_k3s1": [r"k_nchws_bwd_filter<[\w ]+, 3, 1, \d+>"],
-    "bwd_filter:nchw_smallplane_bwd_filter_k3s2": [r"k_nchws_bwd_filter<[\w ]+, 3, 2, \d+>"],
-    "fwd:nchw_smallplane_k5s1": [r"k_nchws_fwd<[\w ]+, 5, 1, \d+, false, \w+>"],
-    "bwd_data:nchw_smallplane_k5s1_flip": [r"k_nchws_fwd<[\w ]+, 5, 1, \d+, true, \w+>"],
-    "bwd_filter:nchw_smallplane_bwd_filter_k5s1": [r"k_nchws_bwd_filter<[\w ]+, 5, 1, \d+>"],
+    "bwd_filter:nchw_smallplane_bwd_filter_k3s1": [r"k_nchws_bwd_filter<[\w ]+, 3, 1, \d+, 1>"],
+    "bwd_filter:nchw_smallplane_bwd_filter_k3s2": [r"k_nchws_bwd_filter<[\w ]+, 3, 2, \d+, 1>"],
+    "fwd:nchw_smallplane_k5s1": [r"k_nchws_fwd<[\w ]+, 5, 1, \d+, false, \w+, 1>"],
+    "bwd_data:nchw_smallplane_k5s1_flip": [r"k_nchws_fwd<[\w ]+, 5, 1, \d+, true, \w+, 1>"],
+    "bwd_filter:nchw_smallplane_bwd_filter_k5s1": [r"k_nchws_bwd_filter<[\w ]+, 5, 1, \d+, 1>"],
     # whole backward pass in one kernel (dwconv_bwd)
     # k_nhwc_bwd_fused_k3s1<T, V, PF, M>
     "bwd:nhwc_bwd_fused_k3s1": [r"k_nhwc_bwd_fused_k3s1<[\w ]+, \d+, \d+, 1>"],
@@ -65,6 +65,9 @@ VARIANT_KERNELS = {
     "fwd:group_nchw_rowwalk_k3s1": [r"k_gconv_nchw_s1<[\w ]+, \d+, \d+, \d+, false[,>]"],
     "bwd_data:group_nchw_rowwalk_k3s1_flip": [r"k_gconv_nchw_s1<[\w ]+, \d+, \d+, \d+, true[,>]"],
     "bwd_filter:group_nchw_bwd_filter_k3s1": [r"k_gconv_nchw_bwd_filter<"],
+    "fwd:group_nchw_smallplane_k3s1": [r"k_nchws_fwd<[\w ]+, 3, 1, \d+, false, \w+, [248]>"],
+    "bwd_data:group_nchw_smallplane_k3s1_flip": [r"k_nchws_fwd<[\w ]+, 3, 1, \d+, true, \w+, [248]>"],
+    "bwd_filter:group_nchw_smallplane_bwd_filter_k3s1": [r"k_nchws_bwd_filter<[\w ]+, 3, 1, \d+, [248]>"],
     # k_gconv_nhwc_xchg<T, CG, V, PF, FLIP>: the lane-exchange walk (groups of 4 or 8 channels)
     "fwd:group_nhwc_rowwalk_k3s1": [r"k_gconv_nhwc_s1<[\w ]+, \d+, \d+, \d+, \d+, false>", r"k_gconv_nhwc_xchg<[\w ]+, \d+, \d+, \d+, false>"],
     "bwd_data:group_nhwc_rowwalk_k3s1_flip": [r"k_gconv_nhwc_s1<[\w ]+, \d+, \d+, \d+, \d+, true>", r"k_gconv_nhwc_xchg<[\w ]+, \d+, \d+, \d+, true>"],

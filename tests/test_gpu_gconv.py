@@ -57,6 +57,14 @@ CASES = [
     ("mm_cg8_c128_h33", 2, 128, 128, 16, 33, 6, 3, 1, 1),
     ("mm_cg4_h1", 2, 64, 64, 16, 1, 5, 3, 1, 1),
     ("mm_cg8_w1", 2, 64, 64, 8, 30, 1, 3, 1, 1),
+    # NCHW rows of 7, 14 or 28 with 2, 4 or 8 channels per group: forward and backward-data stage whole groups in LDS
+    # (last tile partly filled, planes that are not square, tiles of one group)
+    ("sp_cg8_28", 3, 24, 24, 3, 28, 28, 3, 1, 1),
+    ("sp_cg8_14_h9", 4, 16, 16, 2, 9, 14, 3, 1, 1),
+    ("sp_cg2_14", 5, 12, 12, 6, 14, 14, 3, 1, 1),
+    ("sp_cg4_h20_w28", 2, 20, 20, 5, 20, 28, 3, 1, 1),
+    ("sp_cg8_7", 9, 16, 16, 2, 7, 7, 3, 1, 1),
+    ("sp_cg8_h32_w7", 2, 8, 8, 1, 32, 7, 3, 1, 1),
 ]
 
 
