@@ -58,6 +58,10 @@ hipError_t nhwc_bwd_fused(const Geom &g, int dtype, int V, const void *x, const 
                           float *ws, int TH, int NI, hipStream_t st);
 hipError_t nhwc_bwd_filter(const Geom &g, int dtype, int V, const void *x, const void *dy, float *ws, int TH, int NI,
                            hipStream_t st);
+// bf16 stage 1 with packed two-row dot products (nhwc_dot2.hip); mapping and tiling of nhwc_bwd_filter
+bool nhwc_bwd_filter_dot2_supported(const Geom &g, int V);
+hipError_t nhwc_bwd_filter_dot2(const Geom &g, int V, const void *x, const void *dy, float *ws, int CT, int nctiles,
+                                int nowtiles, int TH, int nstrips, int NI, unsigned nblocks, hipStream_t st);
 
 // ---- NCHW LDS-tile kernels (nchw.hip) ----------------------------------------------------------
 // TR = rows per unit.  K in {3,5}, stride in {1,2}, any pad, any multiplier for forward and the

@@ -27,9 +27,9 @@ VARIANT_KERNELS = {
     "fwd:nhwc_rowwalk_fwd_k3s2": [r"k_nhwc_fwd_k3s2<"],
     "bwd_data:nhwc_rowwalk_bwd_data_k3s2": [r"k_nhwc_bwd_data_k3s2<"],
     # k_nhwc_bwd_filter<T, V, K, S, PF, M, FLAT>
-    "bwd_filter:nhwc_bwd_filter_k3s1": [r"k_nhwc_bwd_filter<[\w ]+, \d+, 3, 1, \d+, 1, \w+>"],
+    "bwd_filter:nhwc_bwd_filter_k3s1": [r"k_nhwc_bwd_filter<[\w ]+, \d+, 3, 1, \d+, 1, \w+>", r"k_nhwc_bwd_filter_dot2<\d+, 3>"],
     "bwd_filter:nhwc_bwd_filter_k3s2": [r"k_nhwc_bwd_filter<[\w ]+, \d+, 3, 2, \d+, 1, \w+>"],
-    "bwd_filter:nhwc_bwd_filter_k5s1": [r"k_nhwc_bwd_filter<[\w ]+, \d+, 5, 1, \d+, 1, \w+>"],
+    "bwd_filter:nhwc_bwd_filter_k5s1": [r"k_nhwc_bwd_filter<[\w ]+, \d+, 5, 1, \d+, 1, \w+>", r"k_nhwc_bwd_filter_dot2<\d+, 5>"],
     "bwd_filter:nhwc_bwd_filter_k3s1_m2": [r"k_nhwc_bwd_filter<[\w ]+, \d+, 3, 1, \d+, 2, \w+>"],
     # k_nchwd_s1<T, V, K, PF, FLIP, RS> (RS > 0: whole-line write-out)
     # bf16: k_nchwd_s1_bf16x8<V, K, PF, FLIP, RS> (packed pairs)

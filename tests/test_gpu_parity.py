@@ -289,3 +289,24 @@ def test_hip_graph_replay_matches_eager(gpu_lib):
                 torch.cuda.synchronize()
                 for got, want in ((y, ref[0]), (dx, ref[1]), (dwt, ref[2]), (dx2, ref_b[0]), (dw2, ref_b[1])):
                     assert torch.equal(got, want), (layer.name, layout, rep)
+
+
+def test_bf16_nhwc_filter_gradient_dot_product_form_forced_tilings(gpu_lib):
+    """The bf16 NHWC filter gradient with packed two-row dot products (5x5, and 3x3 with four channels per lane) walks
+    its strip two rows at a time: strips of one, two, three and five rows (odd row counts, strips that start inside
+    the filter's reach of the image top, a last strip cut short) and several images per block, against the oracle."""
+    cases = [Layer("d2_k5", 6, 11, 9, 5, 1, 2), Layer("d2_k3_c12", 12, 9, 13, 3, 1, 1)]
+    N = 5
+    for layer in cases:
+        x, w, dy = wl.make_inputs_device(layer, N, wl.NHWC, wl.BF16, 4242)
+        kw = dict(K=layer.K, stride=layer.stride, pad=layer.pad, mult=layer.mult, layout=wl.NHWC, nthreads=8)
+        want = oracle.bwd_filter(gu.to_host(x), gu.to_host(dy), **kw)
+        d = gu.desc_for(layer, N, wl.NHWC, wl.BF16)
+        for th, ni in ((1, 1), (2, 2), (3, 1), (5, 3), (11, 5)):
+            with dw.tuning_overrides({"DWCONV_TUNE_THW": th, "DWCONV_TUNE_NI": ni}):
+                print("case", layer.name, "TH", th, "NI", ni, flush=True)
+                dwt = torch.full(want.shape, float("nan"), device="cuda", dtype=torch.float32)
+                ws = torch.empty(max(dw.bwd_filter_workspace_bytes(d), 16), device="cuda", dtype=torch.uint8)
+                dw.bwd_filter(d, x, dy, dwt, ws)
+                torch.cuda.synchronize()
+            gu.assert_close(gu.to_host(dwt), want, gu.TOL_F32_FILTER, "dot2 bwd_filter %s TH=%d NI=%d" % (layer.name, th, ni))
