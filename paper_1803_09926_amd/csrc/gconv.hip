@@ -218,7 +218,8 @@ static GPlan gplan(const GGeom &g, int layout, int dtype, int pass)
     // The filter gradient takes the small-plane form for groups of up to 4 on rows of up to 14, and on 28-wide rows in
     // bf16 (fp32 batch 128: 14x14 groups of 4 37 against 55 us, 28x28 groups of 4 83 against 85, groups of 8 122 against
     // 103; bf16 batch 256: 48 against 95, 83 against 107, 166 against 160)
-    const bool small_ok = pass < 2 || (g.Cg <= 4 && (g.W <= 14 || dtype == DT_BF16));
+    // Rows the row-walk kernels cannot take (7 elements) always go to the small-plane form instead of the generic one.
+    const bool small_ok = pass < 2 || (g.Cg <= 4 && (g.W <= 14 || dtype == DT_BF16)) || !gconv_nchw_supported(g);
     if (layout == LAYOUT_NCHW && g.Cg == g.Og && small_ok && nchws_group_supported(as_geom(g), g.Cg) &&
         !tune_env("DWCONV_TUNE_GNOSMALL")) {
         // small planes (rows of 7, 14 or 28): whole groups staged in LDS through flat 16-byte accesses

@@ -848,7 +848,7 @@ static hipError_t go_bwd_filter(const Geom &g, const void *x, const void *dy, fl
                                     else return hipErrorInvalidValue; return hipGetLastError(); }
     if (cg > 1) {
         if (!(g.K == 3 && g.s == 1) || U % cg != 0) return hipErrorInvalidValue;
-        PICKG(2) PICKG(4)          // groups of 8 measured slower than the row-walk filter gradient and are not routed here
+        PICKG(2) PICKG(4) PICKG(8) // groups of 8 only where the row-walk filter gradient cannot run (7-wide rows): it measured faster
         return hipErrorInvalidValue;
     }
 #undef PICKG
