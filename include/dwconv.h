@@ -166,7 +166,8 @@ int dwconv_tuning_reload(void);
  * groups equals its number of channels; with fewer groups the 0/1 mask of Eq. 2 keeps, for an output
  * channel, the K x K blocks of every input channel of its own group.  As for the depthwise layer,
  * the dense masked product is not what runs: the passes are direct stencils over the Cg = C/groups
- * input channels of a group, still bound by memory for small Cg.
+ * input channels of a group, still bound by memory for small Cg; with 4 or 8 channels per group the
+ * sum over a group's channels is a small dense contraction and, in NHWC, runs on the matrix cores.
  *
  * The C input and O output channels are split into `groups` runs of Cg = C/groups and Og = O/groups
  * consecutive channels; output channel o reads input channels (o/Og)*Cg .. (o/Og)*Cg + Cg - 1.
