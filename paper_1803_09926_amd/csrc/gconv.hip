@@ -231,6 +231,9 @@ static GPlan gplan(const GGeom &g, int layout, int dtype, int pass)
         pl.variant = GV_NCHW_K3S1;
         pl.name = pass == 0 ? "group_nchw_rowwalk_k3s1" : pass == 1 ? "group_nchw_rowwalk_k3s1_flip" : "group_nchw_bwd_filter_k3s1";
         if (pass == 2) pl.parts = gconv_nchw_bwd_filter_parts(g);
+    } else if (layout == LAYOUT_NHWC && pass < 2 && gconv_nhwc_mfma_s2_supported(g, dtype, pass)) {
+        pl.variant = GV_NHWC_MFMA_S2;
+        pl.name = pass == 0 ? "group_nhwc_mfma_fwd_k3s2" : "group_nhwc_mfma_bwd_data_k3s2";
     } else if (layout == LAYOUT_NHWC && gconv_nhwc_supported(g)) {
         pl.variant = GV_NHWC_K3S1;
         const bool mm = pass < 2 && gconv_nhwc_mfma_supported(g, dtype);      // forward and backward-data on the matrix cores
@@ -326,6 +329,7 @@ int gconv_fwd(const dwconv_group_desc *desc, const void *x, const void *w, void 
     if (pl.variant == GV_NCHWS_K3S1) e = nchws_group_fwd(as_geom(g), g.Cg, desc->dtype, x, w, y, false, (hipStream_t)stream);
     else if (pl.variant == GV_NCHW_K3S1) e = gconv_nchw_s1(g, desc->dtype, x, w, y, false, (hipStream_t)stream);
     else if (pl.variant == GV_NHWC_K3S1) e = gconv_nhwc_s1(g, desc->dtype, x, w, y, false, (hipStream_t)stream);
+    else if (pl.variant == GV_NHWC_MFMA_S2) e = gconv_nhwc_mfma_s2(g, desc->dtype, x, w, y, false, (hipStream_t)stream);
     else e = gconv_generic_fwd(g, desc->layout, desc->dtype, x, w, y, (hipStream_t)stream);
     return e == hipSuccess ? DWCONV_OK : DWCONV_ERR_LAUNCH;
 }
@@ -346,6 +350,7 @@ int gconv_bwd_data(const dwconv_group_desc *desc, const void *dy, const void *w,
     if (pl.variant == GV_NCHWS_K3S1) e = nchws_group_fwd(as_geom(g), g.Cg, desc->dtype, dy, w, dx, true, (hipStream_t)stream);
     else if (pl.variant == GV_NCHW_K3S1) e = gconv_nchw_s1(g, desc->dtype, dy, w, dx, true, (hipStream_t)stream);
     else if (pl.variant == GV_NHWC_K3S1) e = gconv_nhwc_s1(g, desc->dtype, dy, w, dx, true, (hipStream_t)stream);
+    else if (pl.variant == GV_NHWC_MFMA_S2) e = gconv_nhwc_mfma_s2(g, desc->dtype, dy, w, dx, true, (hipStream_t)stream);
     else e = gconv_generic_bwd_data(g, desc->layout, desc->dtype, dy, w, dx, (hipStream_t)stream);
     return e == hipSuccess ? DWCONV_OK : DWCONV_ERR_LAUNCH;
 }

@@ -12,7 +12,7 @@ struct GGeom {
     int Ho, Wo;
 };
 
-enum GVariant { GV_GENERIC = 0, GV_NCHW_K3S1, GV_NHWC_K3S1, GV_NCHWS_K3S1 };
+enum GVariant { GV_GENERIC = 0, GV_NCHW_K3S1, GV_NHWC_K3S1, GV_NCHWS_K3S1, GV_NHWC_MFMA_S2 };
 
 struct GPlan {
     int variant;
@@ -56,5 +56,10 @@ hipError_t gconv_nhwc_xchg_bwd_filter(const GGeom &g, int dtype, const void *x, 
 // (gconv_nhwc_mfma.hip); gconv_nhwc_s1 forwards to it where it applies
 bool gconv_nhwc_mfma_supported(const GGeom &g, int dtype);
 hipError_t gconv_nhwc_mfma_s1(const GGeom &g, int dtype, const void *in, const void *w, void *out, bool flip, hipStream_t st);
+
+// ---- NHWC 3x3 stride 2 pad 1 on the matrix cores, same group sizes and channel counts: forward (pass 0) and
+// backward-data (pass 1, even H and W) (gconv_nhwc_mfma_s2.hip)
+bool gconv_nhwc_mfma_s2_supported(const GGeom &g, int dtype, int pass);
+hipError_t gconv_nhwc_mfma_s2(const GGeom &g, int dtype, const void *in, const void *w, void *out, bool bwd, hipStream_t st);
 
 }  // namespace dwc

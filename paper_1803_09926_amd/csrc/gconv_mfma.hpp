@@ -1,0 +1,124 @@
+// Pieces the matrix-core group-convolution kernels share (gconv_nhwc_mfma.hip, gconv_nhwc_mfma_s2.hip): the lane's input
+// vector as loaded, its filter entries as the A operand, and the 4x4 matrix instructions of the two storage types.
+// Lane layout of both instructions (16 independent blocks of 4 lanes): A[i][k] comes from lane i of the block, B[k][j]
+// from lane j, and D[i][j] is register i of lane j.
+#pragma once
+#include "gconv.hpp"
+
+namespace dwc {
+
+typedef float v4f_t __attribute__((ext_vector_type(4)));
+typedef short v4s_t __attribute__((ext_vector_type(4)));
+
+// The lane's input channels of one pixel, as loaded: LQ quads (fp32: one quad = 16 bytes; bf16: two quads = 16 bytes).
+template <typename T> struct LaneIn;
+template <> struct LaneIn<float> {
+    static constexpr int LQ = 1;
+    float c[4];
+    __device__ __forceinline__ void load(const BufView &b, uint32_t voff, uint32_t soff)
+    {
+        const u4raw_t q = b.b128(voff, soff);
+        c[0] = __uint_as_float(q.x); c[1] = __uint_as_float(q.y); c[2] = __uint_as_float(q.z); c[3] = __uint_as_float(q.w);
+    }
+    __device__ __forceinline__ LaneIn sibling() const      // the same registers of the lane four lanes away (the group's other quad)
+    {
+        LaneIn r;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) r.c[k] = __shfl_xor(c[k], 4, 64);
+        return r;
+    }
+};
+template <> struct LaneIn<bf16_t> {
+    static constexpr int LQ = 2;
+    uint32_t w[4];
+    __device__ __forceinline__ void load(const BufView &b, uint32_t voff, uint32_t soff)
+    {
+        const u4raw_t q = b.b128(voff, soff);
+        w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
+    }
+    __device__ __forceinline__ LaneIn sibling() const { return *this; }     // never needed: a group of 8 is inside the lane
+};
+
+// The lane's filter entries for one (tap, output quad, input quad): A[i][k], i = the lane's output channel, k = 0..3.
+template <typename T> struct QuadW;
+template <> struct QuadW<float> {
+    float a[4];
+    __device__ __forceinline__ void set(int k, float v) { a[k] = v; }
+    __device__ __forceinline__ void finish() {}
+};
+template <> struct QuadW<bf16_t> {
+    uint32_t w[2];
+    __device__ __forceinline__ void set(int k, float v)
+    {
+        // the filter is stored in bf16, so the upper half of its widened value is the stored value
+        const uint32_t h = __float_as_uint(v) >> 16;
+        if (k == 0) w[0] = h; else if (k == 1) w[0] |= h << 16; else if (k == 2) w[1] = h; else w[1] |= h << 16;
+    }
+    __device__ __forceinline__ void finish() {}
+};
+
+typedef uint32_t u2w_t __attribute__((ext_vector_type(2)));
+// d0 += A2 * B, d1 += A1 * B, d2 += A0 * B for input quad `q` of the lane's vector: one input quad against the filter
+// entries of the three tap rows it serves; consecutive instructions go to different accumulators
+__device__ __forceinline__ void quad_mma3(v4f_t &d0, v4f_t &d1, v4f_t &d2, const QuadW<float> &a2, const QuadW<float> &a1,
+                                          const QuadW<float> &a0, const LaneIn<float> &b, int)
+{
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        d0 = __builtin_amdgcn_mfma_f32_4x4x1f32(a2.a[k], b.c[k], d0, 0, 0, 0);
+        d1 = __builtin_amdgcn_mfma_f32_4x4x1f32(a1.a[k], b.c[k], d1, 0, 0, 0);
+        d2 = __builtin_amdgcn_mfma_f32_4x4x1f32(a0.a[k], b.c[k], d2, 0, 0, 0);
+    }
+}
+__device__ __forceinline__ void quad_mma3(v4f_t &d0, v4f_t &d1, v4f_t &d2, const QuadW<bf16_t> &a2, const QuadW<bf16_t> &a1,
+                                          const QuadW<bf16_t> &a0, const LaneIn<bf16_t> &b, int q)
+{
+    const v4s_t bv = __builtin_bit_cast(v4s_t, u2w_t{b.w[2 * q], b.w[2 * q + 1]});
+    d0 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(v4s_t, u2w_t{a2.w[0], a2.w[1]}), bv, d0, 0, 0, 0);
+    d1 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(v4s_t, u2w_t{a1.w[0], a1.w[1]}), bv, d1, 0, 0, 0);
+    d2 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(v4s_t, u2w_t{a0.w[0], a0.w[1]}), bv, d2, 0, 0, 0);
+}
+
+// d += A * B for input quad `q` of the lane's vector
+__device__ __forceinline__ void quad_mma1(v4f_t &d, const QuadW<float> &a, const LaneIn<float> &b, int)
+{
+#pragma unroll
+    for (int k = 0; k < 4; ++k) d = __builtin_amdgcn_mfma_f32_4x4x1f32(a.a[k], b.c[k], d, 0, 0, 0);
+}
+__device__ __forceinline__ void quad_mma1(v4f_t &d, const QuadW<bf16_t> &a, const LaneIn<bf16_t> &b, int q)
+{
+    d = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(v4s_t, u2w_t{a.w[0], a.w[1]}),
+                                               __builtin_bit_cast(v4s_t, u2w_t{b.w[2 * q], b.w[2 * q + 1]}), d, 0, 0, 0);
+}
+
+// The lane's filter entries, wq[oq][tap][iq]: output quad oq of the lane against input quad iq of that quad's group (when
+// the group's other quad lives in the neighbouring block, fp32 groups of 8: iq 0 = the lane's own quad, 1 = the
+// neighbour's).  MODE 0: forward, A[i][k] = w[tap][ci = k][o = i]; MODE 1: backward-data at stride 1, the filter
+// transposed inside the group and rotated, A[i][k] = w[8 - tap][ci = i][o = k]; MODE 2: transposed only.
+template <typename T, int CG, int MODE>
+__device__ __forceinline__ void load_group_filter(const T *__restrict__ w, int C, int cbase, int j,
+                                                  QuadW<T> (&wq)[LaneIn<T>::LQ][9][CG / 4])
+{
+    constexpr int LQ = LaneIn<T>::LQ, NQ = CG / 4;
+    constexpr bool SIB = NQ == 2 && LQ == 1;
+#pragma unroll
+    for (int oq = 0; oq < LQ; ++oq) {
+        const int c4 = cbase + 4 * oq, grp0 = c4 / CG * CG, qpos = (c4 - grp0) / 4;
+#pragma unroll
+        for (int tap = 0; tap < 9; ++tap)
+#pragma unroll
+            for (int iq = 0; iq < NQ; ++iq) {
+                const int rq = NQ == 1 ? 0 : (SIB ? (qpos ^ iq) : iq);         // that input quad's place in the group
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    size_t idx;
+                    if (MODE == 0) idx = (size_t)(tap * CG + rq * 4 + k) * C + c4 + j;
+                    else idx = (size_t)((MODE == 1 ? 8 - tap : tap) * CG + qpos * 4 + j) * C + grp0 + rq * 4 + k;
+                    wq[oq][tap][iq].set(k, ldf(w + idx));
+                }
+                wq[oq][tap][iq].finish();
+            }
+    }
+}
+
+}  // namespace dwc

@@ -65,6 +65,14 @@ CASES = [
     ("sp_cg4_h20_w28", 2, 20, 20, 5, 20, 28, 3, 1, 1),
     ("sp_cg8_7", 9, 16, 16, 2, 7, 7, 3, 1, 1),
     ("sp_cg8_h32_w7", 2, 8, 8, 1, 32, 7, 3, 1, 1),
+    # NHWC stride 2 on the matrix cores (forward any size, backward-data on even maps): odd and even maps, a last column
+    # quad partly outside the row, several strips, the smallest map
+    ("mm_s2_cg4_c64_odd", 2, 64, 64, 16, 15, 16, 3, 2, 1),
+    ("mm_s2_cg4_c128_even", 3, 128, 128, 32, 16, 12, 3, 2, 1),
+    ("mm_s2_cg8_c128", 2, 128, 128, 16, 18, 10, 3, 2, 1),
+    ("mm_s2_cg8_c64_odd", 2, 64, 64, 8, 9, 7, 3, 2, 1),
+    ("mm_s2_tiny", 1, 64, 64, 16, 2, 2, 3, 2, 1),
+    ("mm_s2_tall", 1, 128, 128, 32, 60, 4, 3, 2, 1),
 ]
 
 
