@@ -234,6 +234,10 @@ static GPlan gplan(const GGeom &g, int layout, int dtype, int pass)
     } else if (layout == LAYOUT_NHWC && pass < 2 && gconv_nhwc_mfma_s2_supported(g, dtype, pass)) {
         pl.variant = GV_NHWC_MFMA_S2;
         pl.name = pass == 0 ? "group_nhwc_mfma_fwd_k3s2" : "group_nhwc_mfma_bwd_data_k3s2";
+    } else if (layout == LAYOUT_NHWC && pass == 2 && gconv_nhwc_bwd_filter_s2_supported(g)) {
+        pl.variant = GV_NHWC_BWD_FILTER_S2;
+        pl.name = "group_nhwc_bwd_filter_k3s2";
+        pl.parts = gconv_nhwc_bwd_filter_s2_parts(g);
     } else if (layout == LAYOUT_NHWC && gconv_nhwc_supported(g)) {
         pl.variant = GV_NHWC_K3S1;
         const bool mm = pass < 2 && gconv_nhwc_mfma_supported(g, dtype);      // forward and backward-data on the matrix cores
@@ -374,6 +378,7 @@ int gconv_bwd_filter(const dwconv_group_desc *desc, const void *x, const void *d
     if (gmisaligned(workspace)) return DWCONV_ERR_ALIGN;
     hipError_t e;
     if (pl.variant == GV_NCHWS_K3S1) e = nchws_group_bwd_filter(as_geom(g), g.Cg, desc->dtype, x, dy, (float *)workspace, pl.a, pl.c, (hipStream_t)stream);
+    else if (pl.variant == GV_NHWC_BWD_FILTER_S2) e = gconv_nhwc_bwd_filter_s2(g, desc->dtype, x, dy, (float *)workspace, pl.parts, (hipStream_t)stream);
     else if (pl.variant == GV_NCHW_K3S1) e = gconv_nchw_bwd_filter(g, desc->dtype, x, dy, (float *)workspace, pl.parts, (hipStream_t)stream);
     else if (pl.variant == GV_NHWC_K3S1) e = gconv_nhwc_bwd_filter(g, desc->dtype, x, dy, (float *)workspace, pl.parts, (hipStream_t)stream);
     else e = gconv_generic_bwd_filter(g, desc->layout, desc->dtype, x, dy, (float *)workspace, pl.parts, (hipStream_t)stream);

@@ -12,7 +12,7 @@ struct GGeom {
     int Ho, Wo;
 };
 
-enum GVariant { GV_GENERIC = 0, GV_NCHW_K3S1, GV_NHWC_K3S1, GV_NCHWS_K3S1, GV_NHWC_MFMA_S2 };
+enum GVariant { GV_GENERIC = 0, GV_NCHW_K3S1, GV_NHWC_K3S1, GV_NCHWS_K3S1, GV_NHWC_MFMA_S2, GV_NHWC_BWD_FILTER_S2 };
 
 struct GPlan {
     int variant;
@@ -59,6 +59,10 @@ hipError_t gconv_nhwc_mfma_s1(const GGeom &g, int dtype, const void *in, const v
 
 // ---- NHWC 3x3 stride 2 pad 1 on the matrix cores, same group sizes and channel counts: forward (pass 0) and
 // backward-data (pass 1, even H and W) (gconv_nhwc_mfma_s2.hip)
+// filter gradient at stride 2, groups of 4 or 8 on both sides, any channel count (gconv_nhwc_xchg.hip)
+bool gconv_nhwc_bwd_filter_s2_supported(const GGeom &g);
+int gconv_nhwc_bwd_filter_s2_parts(const GGeom &g);
+hipError_t gconv_nhwc_bwd_filter_s2(const GGeom &g, int dtype, const void *x, const void *dy, float *ws, int parts, hipStream_t st);
 bool gconv_nhwc_mfma_s2_supported(const GGeom &g, int dtype, int pass);
 hipError_t gconv_nhwc_mfma_s2(const GGeom &g, int dtype, const void *in, const void *w, void *out, bool bwd, hipStream_t st);
 

@@ -367,6 +367,143 @@ __global__ __launch_bounds__(256) void k_gconv_nhwc_xchg_bwd_filter(GGeom g, con
         }
 }
 
+// Filter gradient, stage 1, 3x3 stride 2 pad 1, on the matrix cores: lane and block mapping of the kernel above with the
+// lane's column counted in dy (a lane owns one channel at dy column ow); dy row oh meets x rows 2oh-1, 2oh, 2oh+1 at
+// columns 2ow-1, 2ow, 2ow+1, and row 2oh+1 is kept as the top row of the next step.  Per step and tap one 4x4x1
+// matrix instruction adds the quad's outer product x[ci] * dy[o].  Lanes outside the tensor walk along on clamped
+// addresses with their dy forced to zero (the matrix instructions run on every lane).
+template <typename T, int CG>
+__global__ __launch_bounds__(256) void k_gconv_nhwc_xchg_bwd_filter_s2(GGeom g, const T *__restrict__ x, const T *__restrict__ dy,
+                                                                       float *__restrict__ ws, int CT, int nctiles, int nowtiles,
+                                                                       int TH, int nstrips, int NI, unsigned nblocks, int J)
+{
+    constexpr int NH = CG == 8 ? 2 : 1;
+    static_assert(CG == 4 || CG == 8, "groups of 4 or 8 lanes");
+    __shared__ float red[4][CG][64];
+    unsigned lb = xcd_remap(blockIdx.x, nblocks);
+    const int strip = lb % nstrips; lb /= nstrips;
+    const int owtile = lb % nowtiles; lb /= nowtiles;
+    const int ctile = lb % nctiles; const int ngroup = lb / nctiles;
+
+    const int OWT = 256 / CT;
+    const int tx = threadIdx.x % CT, ty = threadIdx.x / CT;
+    const int c = ctile * CT + tx, ow = owtile * OWT + ty;
+    const bool active = c < g.C && ow < g.Wo;
+    const int sub = c % CG;
+
+    v4fx_t accm[3][NH][3];                         // [kw][own / mirrored register][kh], element i = lane i of the quad
+#pragma unroll
+    for (int kw = 0; kw < 3; ++kw)
+#pragma unroll
+        for (int h = 0; h < NH; ++h)
+#pragma unroll
+            for (int kh = 0; kh < 3; ++kh) accm[kw][h][kh] = v4fx_t{0.f, 0.f, 0.f, 0.f};
+
+    bool colok[3];
+    {
+        const int cc = min(c, g.C - 1), oc = min(ow, g.Wo - 1);
+        int coloff[3];
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) {
+            const int iw = 2 * oc - 1 + kw;
+            colok[kw] = iw >= 0 && iw < g.W;
+            coloff[kw] = (colok[kw] ? iw : 2 * oc) * g.C;
+        }
+        const int xrow = g.W * g.C, drow = g.Wo * g.C;
+        const int oh0 = strip * TH, oh1 = min(g.Ho, oh0 + TH);
+        const int n0 = ngroup * NI, n1 = min(g.N, n0 + NI);
+        struct Step { RawVec<T, 1> e[3], o[3], d; };            // x rows 2oh and 2oh+1 at the three columns, dy row oh
+#pragma unroll 1
+        for (int n = n0; n < n1; ++n) {
+            const T *xin = x + (size_t)n * g.H * xrow + cc;
+            const T *dyin = dy + (size_t)n * g.Ho * drow + (size_t)oc * g.C + cc;
+            auto load_x = [&](int r, RawVec<T, 1> (&dst)[3]) {
+                const T *xp = xin + (size_t)min(max(r, 0), g.H - 1) * xrow;
+#pragma unroll
+                for (int kw = 0; kw < 3; ++kw) dst[kw].load(xp + coloff[kw]);
+            };
+            auto load_step = [&](int oh, Step &s) {
+                load_x(2 * oh, s.e); load_x(2 * oh + 1, s.o);
+                s.d.load(dyin + (size_t)min(oh, g.Ho - 1) * drow);
+            };
+            auto tap_row = [&](int kh, const RawVec<T, 1> (&xr)[3], bool rowok, float dv) {
+#pragma unroll
+                for (int kw = 0; kw < 3; ++kw) {
+                    float xv[1];
+                    xr[kw].get(xv);
+                    const float xx = rowok ? xv[0] : 0.f;
+                    accm[kw][0][kh] = __builtin_amdgcn_mfma_f32_4x4x1f32(xx, dv, accm[kw][0][kh], 0, 0, 0);
+                    if constexpr (NH == 2) {
+                        const float m = half_mirror(xx);
+                        accm[kw][1][kh] = __builtin_amdgcn_mfma_f32_4x4x1f32(m, dv, accm[kw][1][kh], 0, 0, 0);
+                    }
+                }
+            };
+            RawVec<T, 1> top[3];
+            load_x(2 * oh0 - 1, top);
+            bool topok = 2 * oh0 - 1 >= 0;
+            auto consume = [&](int oh, const Step &s) {
+                float d[1];
+                s.d.get(d);
+                const float dv = active ? d[0] : 0.f;
+                tap_row(0, top, topok, dv);
+                tap_row(1, s.e, true, dv);                       // 2oh <= H - 1 always
+                const bool ook = 2 * oh + 1 < g.H;
+                tap_row(2, s.o, ook, dv);
+#pragma unroll
+                for (int kw = 0; kw < 3; ++kw) top[kw] = s.o[kw];
+                topok = ook;
+            };
+            Step sa, sb;
+            load_step(oh0, sa);
+            int oh = oh0;
+#pragma unroll 1
+            for (; oh + 2 <= oh1; oh += 2) {
+                load_step(oh + 1, sb);
+                consume(oh, sa);
+                load_step(oh + 2, sa);
+                consume(oh + 1, sb);
+            }
+            if (oh < oh1) consume(oh, sa);
+        }
+        // taps on columns outside the image accumulated clamped data: drop them
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw)
+            if (!colok[kw]) {
+#pragma unroll
+                for (int h = 0; h < NH; ++h)
+#pragma unroll
+                    for (int kh = 0; kh < 3; ++kh) accm[kw][h][kh] = v4fx_t{0.f, 0.f, 0.f, 0.f};
+            }
+    }
+
+    // fixed-order block reduction, one tap at a time: over the columns of a wavefront, then over the wavefronts
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int part = (ngroup * nstrips + strip) * nowtiles + owtile;
+    float *wsp = ws + (size_t)part * J;
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) {
+#pragma unroll
+            for (int h = 0; h < NH; ++h)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) red[wv][h * 4 + q][lane] = wave_sum_strided(accm[kw][h][kh][q], CT);
+            __syncthreads();
+            if (wv == 0 && lane < CT && c < g.C) {
+#pragma unroll
+                for (int h = 0; h < NH; ++h)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int e = h * 4 + q, ci = ((sub & ~3) + q) ^ (h ? 7 : 0);     // q = the partner's lane in the quad; mirrored: lane^7's quad
+                        wsp[((kh * 3 + kw) * g.Cg + ci) * g.O + c] =
+                            (red[0][e][lane] + red[1][e][lane]) + (red[2][e][lane] + red[3][e][lane]);
+                    }
+            }
+            __syncthreads();
+        }
+}
+
 // ---- host side ---------------------------------------------------------------------------------------------
 
 static inline int cdivx(int a, int b) { return (a + b - 1) / b; }
@@ -446,6 +583,61 @@ hipError_t gconv_nhwc_xchg_bwd_filter(const GGeom &g, int dtype, const void *x, 
 #undef TRY
 #undef GOF
     return hipErrorInvalidValue;
+}
+
+// ---- 3x3 stride 2: filter-gradient tiling (shared by the workspace query and the launch) and launch -----------------
+bool gconv_nhwc_bwd_filter_s2_supported(const GGeom &g)
+{
+    if (tune_env("DWCONV_TUNE_GNOXCHG")) return false;
+    return g.K == 3 && g.s == 2 && g.p == 1 && g.Cg == g.Og && (g.Cg == 4 || g.Cg == 8);
+}
+
+static void bwd_filter_s2_tiling(const GGeom &g, int *CT, int *nct, int *nowt, int *TH, int *nst, int *NI, int *ngr)
+{
+    int ct = g.Cg;
+    while (ct < 64 && ct < g.C) ct *= 2;
+    const int nc = cdivx(g.C, ct), now = cdivx(g.Wo, 256 / ct);
+    // whole columns of dy unless the launch would have too few blocks; several images per block when there are plenty
+    int th = g.Ho;
+    const long long per_strip = (long long)nc * now * g.N;
+    while (th > 4 && per_strip * cdivx(g.Ho, th) < 384) th = (th + 1) / 2;
+    int ni = 1;
+    while (ni < g.N && per_strip * cdivx(g.Ho, th) / (ni * 2) >= 384) ni *= 2;
+    th = xtune("DWCONV_TUNE_GHWTH", th); ni = xtune("DWCONV_TUNE_GHWNI", ni);
+    if (th < 1) th = 1;
+    if (th > g.Ho) th = g.Ho;
+    if (ni < 1) ni = 1;
+    if (ni > g.N) ni = g.N;
+    const long long J = (long long)g.O * g.Cg * 9;
+    while ((long long)now * cdivx(g.Ho, th) * cdivx(g.N, ni) * J * 4 > (64ll << 20)) {
+        if (ni < g.N) ni = ni * 2 < g.N ? ni * 2 : g.N; else if (th < g.Ho) th = th * 2 < g.Ho ? th * 2 : g.Ho; else break;
+    }
+    *CT = ct; *nct = nc; *nowt = now; *TH = th; *nst = cdivx(g.Ho, th); *NI = ni; *ngr = cdivx(g.N, ni);
+}
+
+int gconv_nhwc_bwd_filter_s2_parts(const GGeom &g)
+{
+    int CT, nct, nowt, TH, nst, NI, ngr;
+    bwd_filter_s2_tiling(g, &CT, &nct, &nowt, &TH, &nst, &NI, &ngr);
+    return nowt * nst * ngr;
+}
+
+hipError_t gconv_nhwc_bwd_filter_s2(const GGeom &g, int dtype, const void *x, const void *dy, float *ws, int parts, hipStream_t st)
+{
+    if (!gconv_nhwc_bwd_filter_s2_supported(g)) return hipErrorInvalidValue;
+    int CT, nct, nowt, TH, nst, NI, ngr;
+    bwd_filter_s2_tiling(g, &CT, &nct, &nowt, &TH, &nst, &NI, &ngr);
+    if (parts != nowt * nst * ngr || CT % g.Cg != 0 || 256 % CT != 0) return hipErrorInvalidValue;
+    const long long nb = (long long)nct * nowt * nst * ngr;
+    if (nb >= (1ll << 31)) return hipErrorInvalidValue;
+    const unsigned nblocks = (unsigned)nb;
+    const int J = g.O * g.Cg * 9;
+#define GOS(T, CGG) hipLaunchKernelGGL((k_gconv_nhwc_xchg_bwd_filter_s2<T, CGG>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, \
+                                       (const T *)dy, ws, CT, nct, nowt, TH, nst, NI, nblocks, J)
+    if (dtype == DT_F32) { if (g.Cg == 4) GOS(float, 4); else GOS(float, 8); }
+    else { if (g.Cg == 4) GOS(bf16_t, 4); else GOS(bf16_t, 8); }
+#undef GOS
+    return hipGetLastError();
 }
 
 }  // namespace dwc

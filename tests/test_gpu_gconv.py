@@ -241,3 +241,23 @@ def test_group_nhwc_matrix_core_kernels_forced_tilings(dtype):
             tag = "%s %s dtype=%d" % (name, kn, dtype)
             gu.assert_close(gu.to_host(y), want[0], tol, "gconv fwd " + tag)
             gu.assert_close(gu.to_host(dx), want[1], tol, "gconv bwd_data " + tag)
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+def test_group_nhwc_stride2_filter_gradient_forced_tilings(dtype):
+    """The stride-2 NHWC filter gradient splits the dy rows into strips and walks several images per block only on large
+    tensors; the tiling overrides force strips of 1, 3 and 4 rows (the row above a strip's first dy row comes from the
+    neighbouring strip's range) and ragged image groups, on odd and even maps, against the oracle."""
+    cases = [("s2w_cg4", 5, 24, 24, 6, 13, 10, 3, 2, 1), ("s2w_cg8", 3, 16, 16, 2, 12, 9, 3, 2, 1)]
+    knobs = [{"DWCONV_TUNE_GHWTH": "1"}, {"DWCONV_TUNE_GHWTH": "3", "DWCONV_TUNE_GHWNI": "2"}, {"DWCONV_TUNE_GHWTH": "4", "DWCONV_TUNE_GHWNI": "8"}]
+    for case in cases:
+        name, N, C, O, G, H, W, K, s, p = case
+        assert dw.gconv_variant_name(dw.group_desc(N, C, H, W, K, s, p, G, O, wl.NHWC, dtype), 2) == "group_nhwc_bwd_filter_k3s2"
+        x, w, dy = wl.make_group_inputs(N, C, O, G, H, W, K, s, p, wl.NHWC, dtype, seed=96)
+        kw = dict(K=K, stride=s, pad=p, groups=G, O=O, layout=wl.NHWC, nthreads=8)
+        want = og.bwd_filter(x, dy, **kw)
+        for kn in knobs:
+            with dw.tuning_overrides(kn):
+                print("case", name, "knobs", kn, flush=True)
+                _, _, dwt = run_gpu(case, wl.NHWC, dtype, x, w, dy)
+            gu.assert_close(gu.to_host(dwt), want, gu.TOL_F32_FILTER, "gconv bwd_filter %s %s dtype=%d" % (name, kn, dtype))
