@@ -219,13 +219,17 @@ static GPlan gplan(const GGeom &g, int layout, int dtype, int pass)
     // bf16 (fp32 batch 128: 14x14 groups of 4 37 against 55 us, 28x28 groups of 4 83 against 85, groups of 8 122 against
     // 103; bf16 batch 256: 48 against 95, 83 against 107, 166 against 160)
     // Rows the row-walk kernels cannot take (7 elements) always go to the small-plane form instead of the generic one.
-    const bool small_ok = pass < 2 || (g.Cg <= 4 && (g.W <= 14 || dtype == DT_BF16)) || !gconv_nchw_supported(g);
+    const bool small_ok = pass < 2 || (g.Cg <= 4 && (g.W <= 14 || dtype == DT_BF16)) || !gconv_nchw_supported(g);      // (stride 2: always)
     if (layout == LAYOUT_NCHW && g.Cg == g.Og && small_ok && nchws_group_supported(as_geom(g), g.Cg) &&
         !tune_env("DWCONV_TUNE_GNOSMALL")) {
         // small planes (rows of 7, 14 or 28): whole groups staged in LDS through flat 16-byte accesses
         pl.variant = GV_NCHWS_K3S1;
-        pl.name = pass == 0 ? "group_nchw_smallplane_k3s1" : pass == 1 ? "group_nchw_smallplane_k3s1_flip"
-                                                                        : "group_nchw_smallplane_bwd_filter_k3s1";
+        if (g.s == 1)
+            pl.name = pass == 0 ? "group_nchw_smallplane_k3s1" : pass == 1 ? "group_nchw_smallplane_k3s1_flip"
+                                                                            : "group_nchw_smallplane_bwd_filter_k3s1";
+        else
+            pl.name = pass == 0 ? "group_nchw_smallplane_fwd_k3s2" : pass == 1 ? "group_nchw_smallplane_bwd_data_k3s2"
+                                                                               : "group_nchw_smallplane_bwd_filter_k3s2";
         if (pass == 2) nchws_bwd_filter_tiling(as_geom(g), dtype, &pl.a, &pl.c, &pl.parts, g.Cg);
     } else if (layout == LAYOUT_NCHW && gconv_nchw_supported(g)) {
         pl.variant = GV_NCHW_K3S1;
@@ -351,7 +355,8 @@ int gconv_bwd_data(const dwconv_group_desc *desc, const void *dy, const void *w,
     if (gmisaligned(dy) || gmisaligned(w) || gmisaligned(dx)) return DWCONV_ERR_ALIGN;
     const GPlan pl = gplan(g, desc->layout, desc->dtype, 1);
     hipError_t e;
-    if (pl.variant == GV_NCHWS_K3S1) e = nchws_group_fwd(as_geom(g), g.Cg, desc->dtype, dy, w, dx, true, (hipStream_t)stream);
+    if (pl.variant == GV_NCHWS_K3S1 && g.s == 2) e = nchws_group_bwd_data_s2(as_geom(g), g.Cg, desc->dtype, dy, w, dx, (hipStream_t)stream);
+    else if (pl.variant == GV_NCHWS_K3S1) e = nchws_group_fwd(as_geom(g), g.Cg, desc->dtype, dy, w, dx, true, (hipStream_t)stream);
     else if (pl.variant == GV_NCHW_K3S1) e = gconv_nchw_s1(g, desc->dtype, dy, w, dx, true, (hipStream_t)stream);
     else if (pl.variant == GV_NHWC_K3S1) e = gconv_nhwc_s1(g, desc->dtype, dy, w, dx, true, (hipStream_t)stream);
     else if (pl.variant == GV_NHWC_MFMA_S2) e = gconv_nhwc_mfma_s2(g, desc->dtype, dy, w, dx, true, (hipStream_t)stream);

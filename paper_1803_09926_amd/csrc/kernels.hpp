@@ -96,6 +96,7 @@ hipError_t nchws_bwd_data_s2(const Geom &g, int dtype, const void *dy, const voi
 // group convolution with cg channels per group on both sides through the same forward kernel (filter [O][cg][3][3])
 bool nchws_group_supported(const Geom &g, int cg);
 hipError_t nchws_group_fwd(const Geom &g, int cg, int dtype, const void *x, const void *w, void *y, bool flip, hipStream_t st);
+hipError_t nchws_group_bwd_data_s2(const Geom &g, int cg, int dtype, const void *dy, const void *w, void *dx, hipStream_t st);
 void nchws_bwd_filter_tiling(const Geom &g, int dtype, int *U, int *NI, int *parts, int cg = 1);
 hipError_t nchws_group_bwd_filter(const Geom &g, int cg, int dtype, const void *x, const void *dy, float *ws, int U, int NI,
                                   hipStream_t st);

@@ -165,7 +165,7 @@ template <typename T, int K, int S, int W, bool FLIP, bool INPLACE, int CG = 1>
 __global__ __launch_bounds__(256) void k_nchws_fwd(Geom g, const T *__restrict__ x, const T *__restrict__ w,
                                                    T *__restrict__ y, int U, int nplanes, unsigned nblocks, int nt, int TPB)
 {
-    static_assert(CG == 1 || (K == 3 && S == 1), "group form: 3x3 stride 1");
+    static_assert(CG == 1 || (K == 3 && (S == 1 || (S == 2 && !FLIP))), "group form: 3x3, stride 1 or the stride-2 forward");
     extern __shared__ float4 smem4[];
     constexpr int VE = ElemsS<T>::VE;
     constexpr int P = (K - 1) / 2;
@@ -264,7 +264,9 @@ __global__ __launch_bounds__(256) void k_nchws_fwd(Geom g, const T *__restrict__
 // Backward-data 3x3, stride 2, pad 1, dx row width W (template, even), dy row width W/2.
 // One lane per (plane, dy row a): writes dx rows 2a and 2a+1.
 // ---------------------------------------------------------------------------------------------
-template <typename T, int W>
+// CG > 1: group convolution with CG channels per group on both sides; the lane of input plane c adds up the CG dy planes of
+// its group (a tile holds whole groups), filter [O][CG][3][3].
+template <typename T, int W, int CG = 1>
 __global__ __launch_bounds__(256) void k_nchws_bwd_data_s2(Geom g, const T *__restrict__ dy, const T *__restrict__ w,
                                                            T *__restrict__ dx, int U, int nplanes, unsigned nblocks, int nt)
 {
@@ -284,26 +286,38 @@ __global__ __launch_bounds__(256) void k_nchws_bwd_data_s2(Geom g, const T *__re
     const int p = threadIdx.x / g.Ho, a = threadIdx.x - p * g.Ho;
     if (p < np) {
         const int c = (p0 + p) % g.C;
-        float wr[3][3];
-#pragma unroll
-        for (int kh = 0; kh < 3; ++kh)
-#pragma unroll
-            for (int kw = 0; kw < 3; ++kw) wr[kh][kw] = ldf(w + (c * 3 + kh) * 3 + kw);
-        const float *pl = lin + (gi0 & (VE - 1)) + p * HoWo;
         const bool has_b = a + 1 < g.Ho;
-        const float *ra = pl + a * WO, *rb = pl + (has_b ? a + 1 : a) * WO;
-        float A[WO + 1], B[WO + 1];
+        float ev[W], od[W];                       // dx rows 2a and 2a+1
 #pragma unroll
-        for (int i = 0; i < WO; ++i) { A[i] = ra[i]; const float t = rb[i]; B[i] = has_b ? t : 0.f; }
-        A[WO] = 0.f; B[WO] = 0.f;
+        for (int i = 0; i < W; ++i) { ev[i] = 0.f; od[i] = 0.f; }
+#pragma unroll
+        for (int o = 0; o < CG; ++o) {
+            float wr[3][3];
+#pragma unroll
+            for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+                for (int kw = 0; kw < 3; ++kw) {
+                    // depthwise: the lane's own filter; groups: output channel o of the lane's group against the lane's input channel
+                    const int widx = CG == 1 ? (c * 3 + kh) * 3 + kw : (((c - c % CG + o) * CG + c % CG) * 3 + kh) * 3 + kw;
+                    wr[kh][kw] = ldf(w + widx);
+                }
+            const float *pl = lin + (gi0 & (VE - 1)) + (CG == 1 ? p : p - p % CG + o) * HoWo;
+            const float *ra = pl + a * WO, *rb = pl + (has_b ? a + 1 : a) * WO;
+            float A[WO + 1], B[WO + 1];
+#pragma unroll
+            for (int i = 0; i < WO; ++i) { A[i] = ra[i]; const float t = rb[i]; B[i] = has_b ? t : 0.f; }
+            A[WO] = 0.f; B[WO] = 0.f;
+#pragma unroll
+            for (int b = 0; b < WO; ++b) {
+                ev[2 * b] = fmaf(wr[1][1], A[b], ev[2 * b]);
+                ev[2 * b + 1] = fmaf(wr[1][0], A[b + 1], fmaf(wr[1][2], A[b], ev[2 * b + 1]));
+                od[2 * b] = fmaf(wr[0][1], B[b], fmaf(wr[2][1], A[b], od[2 * b]));
+                od[2 * b + 1] = fmaf(wr[0][0], B[b + 1], fmaf(wr[0][2], B[b], fmaf(wr[2][0], A[b + 1], fmaf(wr[2][2], A[b], od[2 * b + 1]))));
+            }
+        }
         float *op = lout + (go0 & (VE - 1)) + p * HW + (2 * a) * W;
 #pragma unroll
-        for (int b = 0; b < WO; ++b) {
-            op[2 * b] = wr[1][1] * A[b];
-            op[2 * b + 1] = fmaf(wr[1][0], A[b + 1], wr[1][2] * A[b]);
-            op[W + 2 * b] = fmaf(wr[0][1], B[b], wr[2][1] * A[b]);
-            op[W + 2 * b + 1] = fmaf(wr[0][0], B[b + 1], fmaf(wr[0][2], B[b], fmaf(wr[2][0], A[b + 1], wr[2][2] * A[b])));
-        }
+        for (int i = 0; i < W; ++i) { op[i] = ev[i]; op[W + i] = od[i]; }
     }
     __syncthreads();
 
@@ -324,7 +338,7 @@ __global__ __launch_bounds__(256) void k_nchws_bwd_filter(Geom g, const T *__res
                                                           float *__restrict__ ws, int U, int NI, int ncblocks,
                                                           unsigned nblocks)
 {
-    static_assert(CG == 1 || (K == 3 && S == 1), "group form: 3x3 stride 1");
+    static_assert(CG == 1 || K == 3, "group form: 3x3");
     extern __shared__ float4 smem4[];
     constexpr int VE = ElemsS<T>::VE;
     constexpr int P = (K - 1) / 2;
@@ -714,7 +728,9 @@ static hipError_t go_fwd(const Geom &g, const void *x, const void *w, void *y, b
 {
     constexpr int VE = ElemsS<T>::VE;
     int U = planes_per_block(g);
-    if (cg > 1 && !(g.K == 3 && g.s == 1 && (g.W == 7 || g.W == 14 || g.W == 28) && g.C % cg == 0)) return hipErrorInvalidValue;
+    if (cg > 1 && !(g.K == 3 && (g.s == 1 || (g.s == 2 && !flip && (g.W == 14 || g.W == 28))) &&
+                    (g.W == 7 || g.W == 14 || g.W == 28) && g.C % cg == 0))
+        return hipErrorInvalidValue;
     const int HW = g.H * g.W, HoWo = g.Ho * g.Wo;
     while (U > 1 && lds_bytes_for(U, HW, HoWo, VE) > 60 * 1024) --U;
     // a tile's planes must fit the register staging that lets the next tile load while this one is computed (8192
@@ -746,10 +762,21 @@ static hipError_t go_fwd(const Geom &g, const void *x, const void *w, void *y, b
                                                 (const T *)x, (const T *)w, (T *)y, U, nplanes, nblocks, nt, tpb)
 #define PICKG(WW, IP, CGG) if (cg == CGG && g.W == WW && inplace == IP) { if (flip) GOG(WW, true, IP, CGG); else GOG(WW, false, IP, CGG); return hipGetLastError(); }
 #define PICKGW(CGG) PICKG(7, false, CGG) PICKG(14, false, CGG) PICKG(28, false, CGG) PICKG(28, true, CGG)
+#define GOG2(WW, IP, CGG) hipLaunchKernelGGL((k_nchws_fwd<T, 3, 2, WW, false, IP, CGG>), dim3(nblocks), dim3(256), lds, st, g, \
+                                             (const T *)x, (const T *)w, (T *)y, U, nplanes, nblocks, nt, tpb)
+#define PICKG2(WW, IP, CGG) if (cg == CGG && g.W == WW && inplace == IP) { GOG2(WW, IP, CGG); return hipGetLastError(); }
+#define PICKGW2(CGG) PICKG2(14, false, CGG) PICKG2(28, false, CGG) PICKG2(28, true, CGG)
+    if (cg > 1 && g.s == 2) {
+        PICKGW2(2) PICKGW2(4) PICKGW2(8)
+        return hipErrorInvalidValue;
+    }
     if (cg > 1) {
         PICKGW(2) PICKGW(4) PICKGW(8)
         return hipErrorInvalidValue;
     }
+#undef PICKGW2
+#undef PICKG2
+#undef GOG2
 #undef PICKGW
 #undef PICKG
 #undef GOG
@@ -770,9 +797,12 @@ hipError_t nchws_fwd(const Geom &g, int dtype, const void *x, const void *w, voi
 // Group convolution on small planes: 3x3 stride 1 pad 1, cg = 2, 4 or 8 channels per group on both sides, rows of 7, 14 or 28.
 bool nchws_group_supported(const Geom &g, int cg)
 {
-    return g.K == 3 && g.s == 1 && g.p == 1 && g.m == 1 && (cg == 2 || cg == 4 || cg == 8) && g.C % cg == 0 &&
-           (g.W == 7 || g.W == 14 || g.W == 28) && g.H <= 32 && 256 / g.H >= cg;
+    if (!(g.K == 3 && g.p == 1 && g.m == 1 && (cg == 2 || cg == 4 || cg == 8) && g.C % cg == 0 && g.H <= 32)) return false;
+    if (g.s == 1) return (g.W == 7 || g.W == 14 || g.W == 28) && 256 / g.H >= cg;
+    // stride 2: even maps with rows of 14 or 28; a block has one lane per (plane, dy row)
+    return g.s == 2 && (g.W == 14 || g.W == 28) && g.H % 2 == 0 && 256 / g.Ho >= cg;
 }
+
 hipError_t nchws_group_fwd(const Geom &g, int cg, int dtype, const void *x, const void *w, void *y, bool flip, hipStream_t st)
 {
     if (!nchws_group_supported(g, cg)) return hipErrorInvalidValue;
@@ -780,18 +810,29 @@ hipError_t nchws_group_fwd(const Geom &g, int cg, int dtype, const void *x, cons
 }
 
 template <typename T>
-static hipError_t go_bwd_data_s2(const Geom &g, const void *dy, const void *w, void *dx, hipStream_t st)
+static hipError_t go_bwd_data_s2(const Geom &g, const void *dy, const void *w, void *dx, hipStream_t st, int cg = 1)
 {
     constexpr int VE = ElemsS<T>::VE;
     int U = planes_per_block(g);
     const int HW = g.H * g.W, HoWo = g.Ho * g.Wo;
     while (U > 1 && lds_bytes_for(U, HoWo, HW, VE) > 60 * 1024) --U;
+    if (cg > 1) { U -= U % cg; if (U < cg) return hipErrorInvalidValue; }       // whole groups per tile
     const size_t lds = lds_bytes_for(U, HoWo, HW, VE);
     const int nplanes = g.N * g.C;
     const unsigned nblocks = (unsigned)cdiv(nplanes, U);
     const int nt = stream_stores("NCHW_SMALL_BWD", (long long)nplanes * HW * sizeof(T), 0);
 #define GO(WW) hipLaunchKernelGGL((k_nchws_bwd_data_s2<T, WW>), dim3(nblocks), dim3(256), lds, st, g, (const T *)dy, \
                                   (const T *)w, (T *)dx, U, nplanes, nblocks, nt)
+#define GOG(WW, CGG) hipLaunchKernelGGL((k_nchws_bwd_data_s2<T, WW, CGG>), dim3(nblocks), dim3(256), lds, st, g, (const T *)dy, \
+                                        (const T *)w, (T *)dx, U, nplanes, nblocks, nt)
+#define PICKG(CGG) if (cg == CGG) { if (g.W == 14) GOG(14, CGG); else if (g.W == 28) GOG(28, CGG); else return hipErrorInvalidValue; \
+                                    return hipGetLastError(); }
+    if (cg > 1) {
+        PICKG(2) PICKG(4) PICKG(8)
+        return hipErrorInvalidValue;
+    }
+#undef PICKG
+#undef GOG
     if (g.W == 14) GO(14);
     else if (g.W == 28) GO(28);
     else if (g.W == 8) GO(8);
@@ -803,6 +844,12 @@ static hipError_t go_bwd_data_s2(const Geom &g, const void *dy, const void *w, v
 hipError_t nchws_bwd_data_s2(const Geom &g, int dtype, const void *dy, const void *w, void *dx, hipStream_t st)
 {
     return dtype == DT_F32 ? go_bwd_data_s2<float>(g, dy, w, dx, st) : go_bwd_data_s2<bf16_t>(g, dy, w, dx, st);
+}
+
+hipError_t nchws_group_bwd_data_s2(const Geom &g, int cg, int dtype, const void *dy, const void *w, void *dx, hipStream_t st)
+{
+    if (!nchws_group_supported(g, cg) || g.s != 2) return hipErrorInvalidValue;
+    return dtype == DT_F32 ? go_bwd_data_s2<float>(g, dy, w, dx, st, cg) : go_bwd_data_s2<bf16_t>(g, dy, w, dx, st, cg);
 }
 
 // planes (channels) per block and images per block for the filter gradient
@@ -844,14 +891,18 @@ static hipError_t go_bwd_filter(const Geom &g, const void *x, const void *dy, fl
                                           (const T *)x, (const T *)dy, ws, U, NI, ncb, nblocks)
 #define GOG(WW, CGG) hipLaunchKernelGGL((k_nchws_bwd_filter<T, 3, 1, WW, CGG>), dim3(nblocks), dim3(256), lds, st, g, \
                                         (const T *)x, (const T *)dy, ws, U, NI, ncb, nblocks)
-#define PICKG(CGG) if (cg == CGG) { if (g.W == 7) GOG(7, CGG); else if (g.W == 14) GOG(14, CGG); else if (g.W == 28) GOG(28, CGG); \
+#define GOG2(WW, CGG) hipLaunchKernelGGL((k_nchws_bwd_filter<T, 3, 2, WW, CGG>), dim3(nblocks), dim3(256), lds, st, g, \
+                                         (const T *)x, (const T *)dy, ws, U, NI, ncb, nblocks)
+#define PICKG(CGG) if (cg == CGG) { if (g.s == 2) { if (g.W == 14) GOG2(14, CGG); else if (g.W == 28) GOG2(28, CGG); else return hipErrorInvalidValue; } \
+                                    else if (g.W == 7) GOG(7, CGG); else if (g.W == 14) GOG(14, CGG); else if (g.W == 28) GOG(28, CGG); \
                                     else return hipErrorInvalidValue; return hipGetLastError(); }
     if (cg > 1) {
-        if (!(g.K == 3 && g.s == 1) || U % cg != 0) return hipErrorInvalidValue;
+        if (!(g.K == 3 && (g.s == 1 || g.s == 2)) || U % cg != 0) return hipErrorInvalidValue;
         PICKG(2) PICKG(4) PICKG(8) // groups of 8 only where the row-walk filter gradient cannot run (7-wide rows): it measured faster
         return hipErrorInvalidValue;
     }
 #undef PICKG
+#undef GOG2
 #undef GOG
     if (g.K == 3 && g.s == 1 && g.W == 7) GO(3, 1, 7);
     else if (g.K == 3 && g.s == 1 && g.W == 14) GO(3, 1, 14);

@@ -73,6 +73,12 @@ CASES = [
     ("mm_s2_cg8_c64_odd", 2, 64, 64, 8, 9, 7, 3, 2, 1),
     ("mm_s2_tiny", 1, 64, 64, 16, 2, 2, 3, 2, 1),
     ("mm_s2_tall", 1, 128, 128, 32, 60, 4, 3, 2, 1),
+    # NCHW stride 2 on small planes (even maps with rows of 14 or 28): all three passes stage whole groups in LDS
+    ("sp_s2_cg4_28", 3, 24, 24, 6, 28, 28, 3, 2, 1),
+    ("sp_s2_cg8_14", 4, 16, 16, 2, 14, 14, 3, 2, 1),
+    ("sp_s2_cg2_h20_w14", 2, 12, 12, 6, 20, 14, 3, 2, 1),
+    ("sp_s2_cg4_h6_w28", 5, 20, 20, 5, 6, 28, 3, 2, 1),
+    ("sp_s2_cg8_h32_w28", 1, 8, 8, 1, 32, 28, 3, 2, 1),
 ]
 
 
