@@ -3,6 +3,7 @@
 Usage:
   python -m paper_1803_09926_amd.rocprof_summary stats   <dir with *_kernel_stats.csv> [workload index of bench.py --config [fused]]
   python -m paper_1803_09926_amd.rocprof_summary traffic <FETCH_SIZE dir> <WRITE_SIZE dir> [workload index]
+  python -m paper_1803_09926_amd.rocprof_summary pmc     <dir of a --pmc run> [substring of the kernel names to keep]
 
 `traffic` expects both runs to contain bench.py's --calibrate-copy dispatches (a plain device copy
 of 2^30 bytes): each counter is scaled so that the copy reads (writes) exactly 2^30 bytes.
@@ -223,9 +224,37 @@ def traffic(dfetch, dwrite, config=None):
             print("ratio %-42s %14.0f %14.0f %7.3f" % (key, measured[key], alg, measured[key] / alg))
 
 
+def pmc(d, pattern=""):
+    """Mean value per dispatch of every counter of a `rocprofv3 --pmc` run, per kernel of the library whose name contains
+    `pattern`; with SQ_VALU_MFMA_BUSY_CYCLES and GRBM_GUI_ACTIVE in the run also the share of time the matrix cores are
+    busy (busy cycles summed over the 1024 SIMDs against the active cycles summed over the 8 XCDs)."""
+    files = glob.glob(os.path.join(d, "**", "*counter_collection.csv"), recursive=True)
+    if not files:
+        sys.exit("no *counter_collection.csv under %s" % d)
+    per = {}
+    for r in csv.DictReader(open(files[0])):
+        n = r["Kernel_Name"]
+        if "dwc::" not in n or pattern not in n:
+            continue
+        n = re.sub(r"\(.*$", "", n).replace("void dwc::", "")
+        per.setdefault(n, {}).setdefault(r["Counter_Name"], []).append(float(r["Counter_Value"]))
+    ctrs = sorted({c for v in per.values() for c in v})
+    print("# mean per dispatch; counters: " + " ".join(ctrs))
+    print("%-58s %5s " % ("kernel", "n") + " ".join("%18s" % c[-18:] for c in ctrs) + "  mfma_busy")
+    for k in sorted(per):
+        v = per[k]
+        mean = {c: sum(v[c]) / len(v[c]) for c in v}
+        busy = ""
+        if "SQ_VALU_MFMA_BUSY_CYCLES" in mean and mean.get("GRBM_GUI_ACTIVE"):
+            busy = "%8.1f %%" % (100.0 * mean["SQ_VALU_MFMA_BUSY_CYCLES"] / (mean["GRBM_GUI_ACTIVE"] / 8.0 * 1024.0))
+        print("%-58s %5d " % (k[:58], len(v[ctrs[0]])) + " ".join("%18.0f" % mean.get(c, 0.0) for c in ctrs) + "  " + busy)
+
+
 if __name__ == "__main__":
     if len(sys.argv) >= 3 and sys.argv[1] == "stats":
         stats(sys.argv[2], int(sys.argv[3]) if len(sys.argv) >= 4 else None, fused=len(sys.argv) >= 5 and sys.argv[4] == "fused")
+    elif len(sys.argv) >= 3 and sys.argv[1] == "pmc":
+        pmc(sys.argv[2], sys.argv[3] if len(sys.argv) >= 4 else "")
     elif len(sys.argv) >= 4 and sys.argv[1] == "traffic":
         traffic(sys.argv[2], sys.argv[3], int(sys.argv[4]) if len(sys.argv) >= 5 else None)
     else:
