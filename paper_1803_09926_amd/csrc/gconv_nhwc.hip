@@ -289,6 +289,176 @@ __global__ __launch_bounds__(256) void k_gconv_nhwc_bwd_filter(GGeom g, const T 
         }
 }
 
+// The same filter gradient in bf16 with packed dot products (see nhwc_dot2.hip): the sum runs over output positions, so two
+// consecutive ROWS of one channel form the two elements of v_dot2c_f32_bf16 after one byte permute per loaded word;
+// the walk takes the strip's x rows two at a time against a window of three dy row pairs, and every (tap, input
+// channel, output channel) sum costs one instruction per row pair with nothing widened.  Mapping, tiling, workspace
+// layout and block reduction of k_gconv_nhwc_bwd_filter; loads go through buffer views (a column outside the image
+// reads as zero).
+__device__ __forceinline__ uint32_t gpair_even(uint32_t lo, uint32_t hi) { return __builtin_amdgcn_perm(hi, lo, 0x05040100u); }
+__device__ __forceinline__ uint32_t gpair_odd(uint32_t lo, uint32_t hi) { return __builtin_amdgcn_perm(hi, lo, 0x07060302u); }
+
+template <int CG, int OB>
+__global__ __launch_bounds__(256) void k_gconv_nhwc_bwd_filter_dot2(GGeom g, const bf16_t *__restrict__ x,
+                                                                    const bf16_t *__restrict__ dy, float *__restrict__ ws, int CT,
+                                                                    int nctiles, int nowtiles, int TH, int nstrips, int NI,
+                                                                    unsigned nblocks, int J)
+{
+    static_assert(CG % 2 == 0 && OB % 2 == 0, "whole 32-bit words of channels");
+    constexpr int XD = CG / 2, DD = OB / 2;
+    __shared__ float red[4][CG * OB][64];
+    unsigned lb = xcd_remap(blockIdx.x, nblocks);
+    const int strip = lb % nstrips; lb /= nstrips;
+    const int owtile = lb % nowtiles; lb /= nowtiles;
+    const int ctile = lb % nctiles; const int ngroup = lb / nctiles;
+
+    const int OWT = 256 / CT;
+    const int tx = threadIdx.x % CT, ty = threadIdx.x / CT;
+    const int Q = g.O / OB;
+    const int cq = ctile * CT + tx, ow = owtile * OWT + ty;
+    const bool active = cq < Q && ow < g.W;
+    const int o0 = cq * OB, grp = o0 / g.Og;
+
+    float acc[3][3][CG][OB];
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw)
+#pragma unroll
+            for (int b = 0; b < CG; ++b)
+#pragma unroll
+                for (int a = 0; a < OB; ++a) acc[kh][kw][b][a] = 0.f;
+
+    if (active) {
+        uint32_t xoff[3];
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) {
+            const int iw = ow - 1 + kw;
+            xoff[kw] = (iw >= 0 && iw < g.W) ? (uint32_t)(iw * g.C + grp * CG) * 2u : BufView::OUTSIDE;
+        }
+        const uint32_t doff = (uint32_t)(ow * g.O + o0) * 2u;
+        const uint32_t xrow = (uint32_t)g.W * (uint32_t)g.C * 2u, drow = (uint32_t)g.W * (uint32_t)g.O * 2u;
+        const uint32_t ximg = (uint32_t)g.H * xrow, dimg = (uint32_t)g.H * drow;             // at most 2 GiB each
+        const int oh0 = strip * TH, oh1 = min(g.H, oh0 + TH);
+        const int n0 = ngroup * NI, n1 = min(g.N, n0 + NI);
+        const int ra = max(oh0 - 1, 0), rb = min(oh1 + 1, g.H);       // the x rows this strip's sums need
+        const int nsteps = (rb - ra + 1) / 2;
+
+        struct Step { uint32_t x[2][3][XD], d[2][DD]; };              // x rows r, r+1 (three columns), dy rows r+1, r+2
+        for (int n = n0; n < n1; ++n) {
+            const BufView xin(x + (size_t)n * g.H * g.W * g.C, ximg), dyin(dy + (size_t)n * g.H * g.W * g.O, dimg);
+            auto load_x = [&](uint32_t voff, int row, uint32_t (&dst)[XD]) {
+                const uint32_t so = (uint32_t)min(max(row, 0), g.H - 1) * xrow;
+                if constexpr (XD == 1) dst[0] = xin.b32(voff, so);
+                else if constexpr (XD == 2) { const u2raw_t q = xin.b64(voff, so); dst[0] = q.x; dst[1] = q.y; }
+                else { static_assert(XD == 4, "2, 4 or 8 channels per group"); const u4raw_t q = xin.b128(voff, so); dst[0] = q.x; dst[1] = q.y; dst[2] = q.z; dst[3] = q.w; }
+            };
+            auto load_d = [&](int row, uint32_t (&dst)[DD]) {
+                const uint32_t so = (uint32_t)min(max(row, 0), g.H - 1) * drow;
+                if constexpr (DD == 1) dst[0] = dyin.b32(doff, so);
+                else { static_assert(DD == 2, "2 or 4 output channels per lane"); const u2raw_t q = dyin.b64(doff, so); dst[0] = q.x; dst[1] = q.y; }
+            };
+            auto load_step = [&](int r, Step &s) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+#pragma unroll
+                    for (int kw = 0; kw < 3; ++kw) load_x(xoff[kw], r + h, s.x[h][kw]);
+                    load_d(r + 1 + h, s.d[h]);
+                }
+            };
+            // dp[kh][a]: dy rows (r+1-kh, r+2-kh) of output channel a; last = the words of dy row r
+            uint32_t dp[3][OB], last[DD];
+#pragma unroll
+            for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+                for (int a = 0; a < OB; ++a) dp[kh][a] = 0u;
+#pragma unroll
+            for (int j = 0; j < DD; ++j) last[j] = 0u;
+
+            auto consume = [&](int r, const Step &s) {
+                // the window moves by two rows: pairs (r, r+1) and (r+1, r+2) enter
+                const bool ok0 = r + 1 >= oh0 && r + 1 < oh1, ok1 = r + 2 >= oh0 && r + 2 < oh1;
+#pragma unroll
+                for (int a = 0; a < OB; ++a) dp[2][a] = dp[0][a];
+#pragma unroll
+                for (int j = 0; j < DD; ++j) {
+                    const uint32_t d0 = ok0 ? s.d[0][j] : 0u, d1 = ok1 ? s.d[1][j] : 0u;
+                    dp[1][2 * j] = gpair_even(last[j], d0); dp[1][2 * j + 1] = gpair_odd(last[j], d0);
+                    dp[0][2 * j] = gpair_even(d0, d1);      dp[0][2 * j + 1] = gpair_odd(d0, d1);
+                    last[j] = d1;
+                }
+                const bool xok0 = r >= 0 && r < g.H, xok1 = r + 1 < g.H;
+#pragma unroll
+                for (int kw = 0; kw < 3; ++kw)
+#pragma unroll
+                    for (int j = 0; j < XD; ++j) {
+                        const uint32_t x0 = xok0 ? s.x[0][kw][j] : 0u, x1 = xok1 ? s.x[1][kw][j] : 0u;
+                        const uint32_t xe = gpair_even(x0, x1), xo = gpair_odd(x0, x1);
+#pragma unroll
+                        for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+                            for (int a = 0; a < OB; ++a) {
+                                acc[kh][kw][2 * j][a] = dot2_bf16(dp[kh][a], xe, acc[kh][kw][2 * j][a]);
+                                acc[kh][kw][2 * j + 1][a] = dot2_bf16(dp[kh][a], xo, acc[kh][kw][2 * j + 1][a]);
+                            }
+                    }
+            };
+
+            Step sa, sb;
+            load_step(ra, sa);
+            if (oh0 < 1) {
+                // the first strip of an image (ra = 0): dy row 0 belongs to the strip but lies above the rows the first step
+                // brings (1, 2); it enters the window as the pair (row -1 = zero, row 0)
+                uint32_t top[DD];
+                load_d(0, top);
+#pragma unroll
+                for (int a = 0; a < OB; ++a) { dp[2][a] = dp[1][a]; dp[1][a] = dp[0][a]; }
+#pragma unroll
+                for (int j = 0; j < DD; ++j) {
+                    const uint32_t cur = oh1 > 0 ? top[j] : 0u;
+                    dp[0][2 * j] = gpair_even(last[j], cur); dp[0][2 * j + 1] = gpair_odd(last[j], cur);
+                    last[j] = cur;
+                }
+            }
+            int i = 0;
+#pragma unroll 1
+            for (; i + 2 <= nsteps; i += 2) {
+                load_step(ra + 2 * i + 2, sb);
+                consume(ra + 2 * i, sa);
+                load_step(ra + 2 * i + 4, sa);
+                consume(ra + 2 * i + 2, sb);
+            }
+            if (i < nsteps) consume(ra + 2 * i, sa);
+        }
+    }
+
+    // fixed-order block reduction, one tap at a time
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int part = (ngroup * nstrips + strip) * nowtiles + owtile;
+    float *wsp = ws + (size_t)part * J;
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) {
+#pragma unroll
+            for (int b = 0; b < CG; ++b)
+#pragma unroll
+                for (int a = 0; a < OB; ++a) red[wv][b * OB + a][lane] = wave_sum_strided(acc[kh][kw][b][a], CT);
+            __syncthreads();
+            if (wv == 0 && lane < CT && cq < Q) {
+#pragma unroll
+                for (int b = 0; b < CG; ++b)
+#pragma unroll
+                    for (int a = 0; a < OB; ++a) {
+                        const int e = b * OB + a;
+                        wsp[((kh * 3 + kw) * g.Cg + b) * g.O + o0 + a] =
+                            (red[0][e][lane] + red[1][e][lane]) + (red[2][e][lane] + red[3][e][lane]);
+                    }
+            }
+            __syncthreads();
+        }
+}
+
 // ---- host side ---------------------------------------------------------------------------------------------
 
 static inline int cdiv(int a, int b) { return (a + b - 1) / b; }
@@ -414,6 +584,12 @@ hipError_t gconv_nhwc_bwd_filter(const GGeom &g, int dtype, const void *x, const
     const int J = g.O * g.Cg * 9;
     if (nhwc_bwd_filter_xchg(g, dtype))
         return gconv_nhwc_xchg_bwd_filter(g, dtype, x, dy, ws, CT, nct, nowt, TH, nst, NI, nblocks, J, st);
+    // bf16 with an even number of channels on both sides of the lane: the dot-product form (image sizes within a buffer view)
+    const bool d2 = dtype == DT_BF16 && !tune_env("DWCONV_TUNE_GNODOT2") && (long long)g.H * g.W * g.C * 2 <= (1ll << 31) &&
+                    (long long)g.H * g.W * g.O * 2 <= (1ll << 31);
+#define TRYD(CGG, OBB) if (d2 && g.Cg == CGG && OB == OBB) { hipLaunchKernelGGL((k_gconv_nhwc_bwd_filter_dot2<CGG, OBB>), dim3(nblocks), dim3(256), 0, st, g, (const bf16_t *)x, (const bf16_t *)dy, ws, CT, nct, nowt, TH, nst, NI, nblocks, J); return hipGetLastError(); }
+    TRYD(2, 4); TRYD(2, 2); TRYD(4, 2);
+#undef TRYD
 #define TRY(T, CGG, OBB) if (g.Cg == CGG && OB == OBB) { hipLaunchKernelGGL((k_gconv_nhwc_bwd_filter<T, CGG, OBB>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, (const T *)dy, ws, CT, nct, nowt, TH, nst, NI, nblocks, J); return hipGetLastError(); }
     if (dtype == DT_F32) {
         TRY(float, 2, 4); TRY(float, 2, 2); TRY(float, 4, 2); TRY(float, 4, 1); TRY(float, 8, 1);

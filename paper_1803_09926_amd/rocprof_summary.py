@@ -75,7 +75,7 @@ VARIANT_KERNELS = {
     # k_gconv_nhwc_mfma<T, CG, FLIP, PF>
     "fwd:group_nhwc_mfma_k3s1": [r"k_gconv_nhwc_mfma<[\w ]+, \d+, false, \d+>"],
     "bwd_data:group_nhwc_mfma_k3s1_flip": [r"k_gconv_nhwc_mfma<[\w ]+, \d+, true, \d+>"],
-    "bwd_filter:group_nhwc_bwd_filter_k3s1": [r"k_gconv_nhwc_bwd_filter<", r"k_gconv_nhwc_xchg_bwd_filter<"],
+    "bwd_filter:group_nhwc_bwd_filter_k3s1": [r"k_gconv_nhwc_bwd_filter<", r"k_gconv_nhwc_bwd_filter_dot2<", r"k_gconv_nhwc_xchg_bwd_filter<"],
 }
 
 

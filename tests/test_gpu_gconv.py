@@ -153,6 +153,30 @@ def test_group_nhwc_exchange_kernels_forced_tilings(dtype):
     gu.assert_close(gu.to_host(dx), og.bwd_data(dy, w, x_shape=x.shape, **kw), tol, "gconv bwd_data two channels per lane")
 
 
+def test_group_nhwc_bf16_filter_gradient_dot_product_form_forced_tilings():
+    """bf16 NHWC filter gradient with 2 or 4 channels per group: the row-pair dot-product kernels.  Strips of one, an odd
+    and an even number of rows, ragged last strips and image groups, odd and even heights, a lane with 2 and with 4
+    output channels."""
+    cases = [("d2_cg2", 5, 12, 12, 6, 13, 10, 3, 1, 1), ("d2_cg2_og4", 3, 8, 16, 4, 8, 9, 3, 1, 1),
+             ("d2_cg4", 4, 16, 16, 4, 7, 12, 3, 1, 1), ("d2_h1", 2, 8, 8, 4, 1, 5, 3, 1, 1), ("d2_h2", 2, 8, 8, 2, 2, 3, 3, 1, 1)]
+    knobs = [{}, {"DWCONV_TUNE_GHWTH": "1"}, {"DWCONV_TUNE_GHWTH": "2", "DWCONV_TUNE_GHWNI": "2"},
+             {"DWCONV_TUNE_GHWTH": "3", "DWCONV_TUNE_GHWNI": "3"}, {"DWCONV_TUNE_GHWTH": "4", "DWCONV_TUNE_GHWNI": "8"},
+             {"DWCONV_TUNE_GHWTH": "64"}]
+    for case in cases:
+        name, N, C, O, G, H, W, K, s, p = case
+        x, w, dy = wl.make_group_inputs(N, C, O, G, H, W, K, s, p, wl.NHWC, wl.BF16, seed=77)
+        kw = dict(K=K, stride=s, pad=p, groups=G, O=O, layout=wl.NHWC, nthreads=8)
+        want = og.bwd_filter(x, dy, **kw)
+        for kn in knobs:
+            with dw.tuning_overrides(kn):
+                print("case", name, "knobs", kn, flush=True)
+                _, _, dwt = run_gpu(case, wl.NHWC, wl.BF16, x, w, dy)
+            gu.assert_close(gu.to_host(dwt), want, gu.TOL_F32_FILTER, "gconv bwd_filter %s %s" % (name, kn))
+        with dw.tuning_overrides({"DWCONV_TUNE_GNODOT2": "1"}):
+            _, _, dwt = run_gpu(case, wl.NHWC, wl.BF16, x, w, dy)
+        gu.assert_close(gu.to_host(dwt), want, gu.TOL_F32_FILTER, "gconv bwd_filter multiply-add form " + name)
+
+
 def test_group_bwd_filter_is_deterministic():
     case = ("det", 4, 32, 32, 8, 28, 28, 3, 1, 1)
     for layout in LAYOUTS:
