@@ -220,7 +220,11 @@ static GPlan gplan(const GGeom &g, int layout, int dtype, int pass)
     // 103; bf16 batch 256: 48 against 95, 83 against 107, 166 against 160)
     // Rows the row-walk kernels cannot take (7 elements) always go to the small-plane form instead of the generic one.
     const bool small_ok = pass < 2 || (g.Cg <= 4 && (g.W <= 14 || dtype == DT_BF16)) || !gconv_nchw_supported(g);      // (stride 2: always)
-    if (layout == LAYOUT_NCHW && g.Cg == g.Og && small_ok && nchws_group_supported(as_geom(g), g.Cg) &&
+    if (layout == LAYOUT_NCHW && pass == 2 && gconv_nchws_mfma_bwd_filter_supported(g)) {
+        pl.variant = GV_NCHWS_MFMA_BWD_FILTER;
+        pl.name = "group_nchw_smallplane_mfma_bwd_filter_k3s1";
+        pl.parts = gconv_nchws_mfma_bwd_filter_parts(g);
+    } else if (layout == LAYOUT_NCHW && g.Cg == g.Og && small_ok && nchws_group_supported(as_geom(g), g.Cg) &&
         !tune_env("DWCONV_TUNE_GNOSMALL")) {
         // small planes (rows of 7, 14 or 28): whole groups staged in LDS through flat 16-byte accesses
         pl.variant = GV_NCHWS_K3S1;
@@ -383,6 +387,7 @@ int gconv_bwd_filter(const dwconv_group_desc *desc, const void *x, const void *d
     if (gmisaligned(workspace)) return DWCONV_ERR_ALIGN;
     hipError_t e;
     if (pl.variant == GV_NCHWS_K3S1) e = nchws_group_bwd_filter(as_geom(g), g.Cg, desc->dtype, x, dy, (float *)workspace, pl.a, pl.c, (hipStream_t)stream);
+    else if (pl.variant == GV_NCHWS_MFMA_BWD_FILTER) e = gconv_nchws_mfma_bwd_filter(g, desc->dtype, x, dy, (float *)workspace, pl.parts, (hipStream_t)stream);
     else if (pl.variant == GV_NHWC_BWD_FILTER_S2) e = gconv_nhwc_bwd_filter_s2(g, desc->dtype, x, dy, (float *)workspace, pl.parts, (hipStream_t)stream);
     else if (pl.variant == GV_NCHW_K3S1) e = gconv_nchw_bwd_filter(g, desc->dtype, x, dy, (float *)workspace, pl.parts, (hipStream_t)stream);
     else if (pl.variant == GV_NHWC_K3S1) e = gconv_nhwc_bwd_filter(g, desc->dtype, x, dy, (float *)workspace, pl.parts, (hipStream_t)stream);

@@ -177,6 +177,26 @@ def test_group_nhwc_bf16_filter_gradient_dot_product_form_forced_tilings():
         gu.assert_close(gu.to_host(dwt), want, gu.TOL_F32_FILTER, "gconv bwd_filter multiply-add form " + name)
 
 
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+def test_group_nchw_matrix_core_filter_gradient_forced_tilings(dtype):
+    """NCHW filter gradient of 28x28 planes with 4 or 8 channels per group (matrix cores, planes staged in LDS): blocks
+    that take one image, several, and a ragged share of the batch; one channel octet and several."""
+    cases = [("mf_cg8", 5, 16, 16, 2, 28, 28, 3, 1, 1), ("mf_cg4", 7, 24, 24, 6, 28, 28, 3, 1, 1), ("mf_cg8_n1", 1, 8, 8, 1, 28, 28, 3, 1, 1)]
+    knobs = [{}, {"DWCONV_TUNE_GSMBLOCKS": "1"}, {"DWCONV_TUNE_GSMBLOCKS": "4"}, {"DWCONV_TUNE_GSMBLOCKS": "9"}]
+    for case in cases:
+        name, N, C, O, G, H, W, K, s, p = case
+        x, w, dy = wl.make_group_inputs(N, C, O, G, H, W, K, s, p, wl.NCHW, dtype, seed=55)
+        kw = dict(K=K, stride=s, pad=p, groups=G, O=O, layout=wl.NCHW, nthreads=8)
+        want = og.bwd_filter(x, dy, **kw)
+        d = dw.group_desc(N, C, H, W, K, s, p, G, O, wl.NCHW, dtype)
+        assert dw.gconv_variant_name(d, 2) == "group_nchw_smallplane_mfma_bwd_filter_k3s1"
+        for kn in knobs:
+            with dw.tuning_overrides(kn):
+                print("case", name, "knobs", kn, flush=True)
+                _, _, dwt = run_gpu(case, wl.NCHW, dtype, x, w, dy)
+            gu.assert_close(gu.to_host(dwt), want, gu.TOL_F32_FILTER, "gconv bwd_filter %s %s" % (name, kn))
+
+
 def test_group_bwd_filter_is_deterministic():
     case = ("det", 4, 32, 32, 8, 28, 28, 3, 1, 1)
     for layout in LAYOUTS:
