@@ -1,5 +1,5 @@
 // Group convolution, NCHW, 3x3 stride 1 pad 1: filter gradient (Eq. 4 with the sum over a group's channel pairs) on the
-// matrix cores, for 4 or 8 channels per group on both sides and 28x28 planes.
+// matrix cores, for 4 or 8 channels per group on both sides and 28x28 or 56x56 planes.
 //
 // Per pixel a group of 8 needs 8*8*9 multiply-adds for 16 loaded values: on the vector ALU this pass is bound by
 // arithmetic (about a third of the memory rate).  The sum over pixels is a matrix product dW[o][b][tap] =
@@ -9,12 +9,13 @@
 // its plane).  A = the dy values of the lane's output channel, B = the x values of the lane's input channel at the
 // tap's offset, D[i][j] (register i of lane j) = the sum for (output channel i, input channel j) of the quad pair.
 //
-// A thread block works on eight consecutive channels (one group of 8, or two groups of 4) of one image at a time:
-// the eight x planes and eight dy planes (contiguous in NCHW) come in as flat 16-byte loads, two images ahead in
-// registers, and are laid out in LDS with a four-element zero gap after every row and a zero row between planes,
-// so every tap's operand is an unconditional LDS read at a constant offset from the position (the padding supplies
-// the zeros of Eq. 4's border).  A wavefront's 16 positions are two streams of eight: the seven 4-pixel vectors of a
-// row and the gap after it (dy is zero there).  A stream walks down its rows and keeps the three x rows of the taps
+// A thread block works on eight consecutive channels (one group of 8, or two groups of 4) of one image at a time
+// (56x56: of one 14-row strip of an image): the eight x planes and eight dy planes come in as 16-byte loads (28x28:
+// one flat range, the planes being contiguous in NCHW), two fills ahead in registers, and are laid out in LDS with a
+// gap of zeros after every row and the rows above and below in place (zeros at the plane's edge), so every tap's
+// operand is an unconditional LDS read at a constant offset from the position (the padding supplies the zeros of
+// Eq. 4's border).  A wavefront's 16 positions are two streams of eight: the seven 4-pixel vectors of a
+// row and the gap after it (dy is zero there); 56x56: one stream of 16, a row's 14 vectors and the gap.  A stream walks down its rows and keeps the three x rows of the taps
 // in registers: a step reads one new x row and one dy row from LDS; the one pixel left and right of a position's
 // four is the neighbour lane's vector, fetched by a lane permute instead of a second LDS read (single-word reads at
 // a stride of four words use a quarter of the banks).  Groups of 8: the four wavefronts take the four (input quad,
@@ -26,89 +27,126 @@
 
 namespace dwc {
 
-template <int W, int H> struct SmallPlaneLds {
-    static constexpr int WP = W + 4;                // row pitch: the row, then four zeros
-    static constexpr int PADP = 16;                 // planes staggered over the LDS banks
-    static constexpr int PP = (H + 1) * WP + PADP;  // plane pitch: the rows, one zero row, the stagger (zeros)
-    static constexpr int LEAD = WP + 4;             // zeros before the first plane (the row above it)
-    static constexpr int AREA = LEAD + 8 * PP;      // elements of one tensor's eight planes
-    static constexpr int V4 = H * W / 4;            // four-pixel vectors of a plane
-    // element offset of four-pixel vector v of the eight planes (v = plane * V4 + index in the plane)
-    static __device__ __forceinline__ int offset(int v)
-    {
-        const int plane = v / V4, rem = v % V4, r = rem / (W / 4), cv = rem % (W / 4);
-        return LEAD + plane * PP + r * WP + cv * 4;
-    }
+// What a block holds in LDS at a time ("fill"): RS rows of eight dy planes and the RS + 2 rows of the eight x planes
+// their taps reach.  28x28: the whole plane (the rows above and below it are zeros that are written once).  56x56:
+// strips of 14 rows (the rows above and below a strip are loaded, or zeroed at the plane's edge).  A row is followed
+// by a gap of zeros up to the pitch WP = 16 positions / streams: two rows of 8 positions or one row of 16.
+template <int W, int H> struct PlaneFill {
+    static_assert((W == 28 && H == 28) || (W == 56 && H == 56), "28x28 planes whole, 56x56 planes in strips");
+    static constexpr bool STRIP = W == 56;
+    static constexpr int RS = STRIP ? 14 : H;           // dy rows of a fill
+    static constexpr int NSTRIP = H / RS;
+    static constexpr int WP = STRIP ? 64 : 32;          // row pitch in elements
+    static constexpr int SPW = 64 / WP;                 // streams (rows walked side by side) of a wavefront
+    static constexpr int VPR = W / 4;                   // four-pixel vectors of a row
+    static constexpr int PADP = 16;                     // planes staggered over the LDS banks
+    static constexpr int PPX = (RS + 2) * WP + PADP;    // x plane pitch: row r0 - 1 first
+    static constexpr int PPD = RS * WP + PADP;
+    static constexpr int XROWS = STRIP ? RS + 2 : RS;   // x rows of a plane that are loaded
+    static constexpr int AREA_X = 8 * PPX, AREA_D = 8 * PPD;
 };
 
 template <typename T, int CG, int W, int H>
 __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_bwd_filter(GGeom g, const T *__restrict__ x, const T *__restrict__ dy,
-                                                                     float *__restrict__ ws, int parts, unsigned nblocks, int J)
+                                                                     float *__restrict__ ws, int parts, int nfills, unsigned nblocks,
+                                                                     int J)
 {
-    using L = SmallPlaneLds<W, H>;
-    static_assert(L::WP == 32 && H % 2 == 0 && (CG == 4 || CG == 8), "rows of seven vectors and a gap: eight positions; groups of 4 or 8");
+    using L = PlaneFill<W, H>;
+    static_assert(CG == 4 || CG == 8, "groups of 4 or 8");
     constexpr bool F32 = sizeof(T) == 4;
-    constexpr int EPC = 16 / (int)sizeof(T);        // elements of a 16-byte chunk
-    constexpr int NCH = 8 * H * W / EPC;            // chunks of one tensor's eight planes
-    constexpr int NPASS = (NCH + 255) / 256;
-    __shared__ __align__(16) T lds[2 * L::AREA];    // x planes, then dy planes
+    constexpr int CPV = F32 ? 1 : 2;                // four-pixel vectors of a 16-byte chunk
+    constexpr int XCH = 8 * L::XROWS * L::VPR / CPV, DCH = 8 * L::RS * L::VPR / CPV;     // chunks of a fill
+    constexpr int XPASS = (XCH + 255) / 256, DPASS = (DCH + 255) / 256;
+    __shared__ __align__(16) T lds[L::AREA_X + L::AREA_D];    // x planes, then dy planes
+    // fills ahead in registers; fp32 strips: one (two would leave registers for one wavefront per SIMD only)
+    constexpr int DEPTH = (F32 && L::STRIP) ? 1 : 2;
 
     unsigned lb = xcd_remap(blockIdx.x, nblocks);
     const int part = lb % parts, cb = lb / parts;   // cb: the block's channel octet
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-    for (int i = tid; i < 2 * L::AREA * (int)sizeof(T) / 16; i += 256) reinterpret_cast<u4raw_t *>(lds)[i] = u4raw_t{0u, 0u, 0u, 0u};
+    for (int i = tid; i < (L::AREA_X + L::AREA_D) * (int)sizeof(T) / 16; i += 256) reinterpret_cast<u4raw_t *>(lds)[i] = u4raw_t{0u, 0u, 0u, 0u};
 
-    // Two images ahead in registers.  Every load is issued unconditionally (lanes past the end of the last pass and
-    // blocks past their last image repeat a valid address and drop the result): the number of loads in flight is then
-    // the same on every path, and the wait before an image's LDS writes covers that image's loads only.
-    struct Stage { u4raw_t x[NPASS], d[NPASS]; };
-    auto gload = [&](Stage &s, int n) {
-        const int nn = n < g.N ? n : part;
-        const T *xs = x + ((size_t)nn * g.C + (size_t)cb * 8) * (H * W);
-        const T *ds = dy + ((size_t)nn * g.O + (size_t)cb * 8) * (H * W);
+    // where four-pixel vector v of a fill's x (dy) rows lives: plane, row within the loaded rows, vector within the row
+    struct Where { int plane, row, cv; };
+    auto where = [](int v, int rows) { Where q; q.plane = v / (rows * L::VPR); const int rem = v % (rows * L::VPR); q.row = rem / L::VPR; q.cv = rem % L::VPR; return q; };
+
+    // DEPTH fills ahead in registers.  Every load is issued unconditionally (lanes past the end of the last pass and
+    // blocks past their last fill repeat a valid address and drop the result; a row outside the plane reads the
+    // nearest row inside and is zeroed on its way to LDS): the number of loads in flight is then the same on every
+    // path, and the wait before a fill's LDS writes covers that fill's loads only.
+    struct Stage { u4raw_t x[XPASS], d[DPASS]; uint32_t xok; };
+    auto gload = [&](Stage &s, int f) {
+        const int ff = f < nfills ? f : part;
+        const int n = ff / L::NSTRIP, r0 = (ff % L::NSTRIP) * L::RS;
+        const T *xs = x + ((size_t)n * g.C + (size_t)cb * 8) * (H * W);
+        const T *ds = dy + ((size_t)n * g.O + (size_t)cb * 8) * (H * W);
+        s.xok = 0xffffffffu;
 #pragma unroll
-        for (int p = 0; p < NPASS; ++p) {
-            const int q = min(p * 256 + tid, NCH - 1);
-            s.x[p] = *reinterpret_cast<const u4raw_t *>(xs + (size_t)q * EPC);
-            s.d[p] = *reinterpret_cast<const u4raw_t *>(ds + (size_t)q * EPC);
+        for (int p = 0; p < XPASS; ++p) {
+            const int q = min(p * 256 + tid, XCH - 1);
+            if constexpr (L::STRIP) {
+                const Where wq = where(q * CPV, L::XROWS);
+                const int rg = r0 - 1 + wq.row;
+                if (rg < 0 || rg >= H) s.xok &= ~(1u << p);
+                s.x[p] = *reinterpret_cast<const u4raw_t *>(xs + (size_t)wq.plane * (H * W) + min(max(rg, 0), H - 1) * W + wq.cv * 4);
+            } else {
+                s.x[p] = *reinterpret_cast<const u4raw_t *>(xs + (size_t)q * (4 * CPV));      // the planes whole: one flat range
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < DPASS; ++p) {
+            const int q = min(p * 256 + tid, DCH - 1);
+            if constexpr (L::STRIP) {
+                const Where wq = where(q * CPV, L::RS);
+                s.d[p] = *reinterpret_cast<const u4raw_t *>(ds + (size_t)wq.plane * (H * W) + (r0 + wq.row) * W + wq.cv * 4);
+            } else {
+                s.d[p] = *reinterpret_cast<const u4raw_t *>(ds + (size_t)q * (4 * CPV));
+            }
+        }
+    };
+    auto put = [&](T *area, int pitch, int rowshift, int rows, int q, u4raw_t v) {
+        if constexpr (F32) {
+            const Where wq = where(q, rows);
+            *reinterpret_cast<u4raw_t *>(area + wq.plane * pitch + (wq.row + rowshift) * L::WP + wq.cv * 4) = v;
+        } else {
+            const Where w0 = where(2 * q, rows), w1 = where(2 * q + 1, rows);
+            *reinterpret_cast<u2raw_t *>(area + w0.plane * pitch + (w0.row + rowshift) * L::WP + w0.cv * 4) = u2raw_t{v.x, v.y};
+            *reinterpret_cast<u2raw_t *>(area + w1.plane * pitch + (w1.row + rowshift) * L::WP + w1.cv * 4) = u2raw_t{v.z, v.w};
         }
     };
     auto lstore = [&](const Stage &s) {
 #pragma unroll
-        for (int p = 0; p < NPASS; ++p) {
+        for (int p = 0; p < XPASS; ++p) {
             const int q = p * 256 + tid;
-            if ((p + 1) * 256 <= NCH || q < NCH) {
-                if constexpr (F32) {
-                    const int o = L::offset(q);
-                    *reinterpret_cast<u4raw_t *>(lds + o) = s.x[p];
-                    *reinterpret_cast<u4raw_t *>(lds + L::AREA + o) = s.d[p];
-                } else {
-                    const int o0 = L::offset(2 * q), o1 = L::offset(2 * q + 1);
-                    *reinterpret_cast<u2raw_t *>(lds + o0) = u2raw_t{s.x[p].x, s.x[p].y};
-                    *reinterpret_cast<u2raw_t *>(lds + o1) = u2raw_t{s.x[p].z, s.x[p].w};
-                    *reinterpret_cast<u2raw_t *>(lds + L::AREA + o0) = u2raw_t{s.d[p].x, s.d[p].y};
-                    *reinterpret_cast<u2raw_t *>(lds + L::AREA + o1) = u2raw_t{s.d[p].z, s.d[p].w};
-                }
+            if ((p + 1) * 256 <= XCH || q < XCH) {
+                const bool ok = (s.xok >> p) & 1u;
+                const u4raw_t v = s.x[p];
+                put(lds, L::PPX, L::STRIP ? 0 : 1, L::XROWS, q, u4raw_t{ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u});
             }
+        }
+#pragma unroll
+        for (int p = 0; p < DPASS; ++p) {
+            const int q = p * 256 + tid;
+            if ((p + 1) * 256 <= DCH || q < DCH) put(lds + L::AREA_X, L::PPD, 0, L::RS, q, s.d[p]);
         }
     };
 
-    // The wavefront's task: quads of x and dy planes within the octet, and its rows.  Its 16 positions are two streams of
-    // eight: the seven vectors of a row and the gap after it (dy reads zeros there); a stream walks down RPS rows, one
-    // row per step, and keeps the three x rows of the taps in registers, so a step reads one new x row and one dy row.
-    // Groups of 8: streams of H/2 rows.  Groups of 4: the group's two wavefronts take the upper and the lower half of
-    // the plane, streams of H/4 rows.
-    constexpr int RPS = CG == 8 ? H / 2 : H / 4;
-    static_assert(H % 4 == 0, "whole streams");
+    // The wavefront's task: quads of x and dy planes within the octet, and its rows.  Its 16 positions are SPW streams:
+    // the vectors of a row and the gap after it (dy reads zeros there); a stream walks down RPS rows, one row per step,
+    // and keeps the three x rows of the taps in registers, so a step reads one new x row and one dy row.  Groups of 8:
+    // the wavefront walks all RS rows of the fill.  Groups of 4: the group's two wavefronts take the upper and the
+    // lower half of them.
+    constexpr int RPW = CG == 8 ? L::RS : L::RS / 2, RPS = RPW / L::SPW;
+    static_assert(RPW % L::SPW == 0, "whole streams");
     const int xq = wv & 1, dq = CG == 8 ? wv >> 1 : wv & 1;
     const int half = wv >> 1;
     const int slot = lane >> 2;
-    const int row0 = (CG == 8 ? 0 : half * (H / 2)) + (slot >> 3) * RPS;
-    const T *xpl = lds + (xq * 4 + (lane & 3)) * L::PP + L::LEAD + row0 * L::WP + (slot & 7) * 4;
-    const T *dpl = lds + L::AREA + (dq * 4 + (lane & 3)) * L::PP + L::LEAD + row0 * L::WP + (slot & 7) * 4;
+    const int row0 = (CG == 8 ? 0 : half * RPW) + (slot / (L::WP / 4)) * RPS;
+    const T *xpl = lds + (xq * 4 + (lane & 3)) * L::PPX + (1 + row0) * L::WP + (slot % (L::WP / 4)) * 4;
+    const T *dpl = lds + L::AREA_X + (dq * 4 + (lane & 3)) * L::PPD + row0 * L::WP + (slot % (L::WP / 4)) * 4;
     // the neighbour positions' vectors come from the lanes four below and four above; position 0 has no left neighbour
-    // in the wavefront and starts a row (zero); positions 7 and 15 are gaps, whatever they get meets a zero of dy
+    // in the wavefront and starts a row (zero); the last position of a row is a gap, whatever it gets meets a zero of dy
     const int up = ((lane - 4) & 63) * 4, dn = ((lane + 4) & 63) * 4;
     const uint32_t lmask = lane < 4 ? 0u : 0xffffffffu;
 
@@ -160,10 +198,10 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_bwd_filter(GGeom g, co
             }
         }
     };
-    auto image = [&](Stage &s, int n) {
+    auto fill = [&](Stage &s, int f) {
         lstore(s);
         __syncthreads();
-        gload(s, n + 2 * parts);
+        gload(s, f + DEPTH * parts);
         XRow R[3];
         xrow(-1, R[0]);
         xrow(0, R[1]);
@@ -172,20 +210,24 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_bwd_filter(GGeom g, co
             xrow(t + 1, R[(t + 2) % 3]);
             step(t, R[t % 3], R[(t + 1) % 3], R[(t + 2) % 3]);
         }
-        __syncthreads();                               // every wavefront is done with this image's planes
+        __syncthreads();                               // every wavefront is done with this fill's rows
     };
 
     Stage sa, sb;
-    int n = part;
-    gload(sa, n);                                      // part < parts <= N
-    gload(sb, n + parts);
+    int f = part;
+    gload(sa, f);                                      // part < parts <= nfills
+    if constexpr (DEPTH == 2) gload(sb, f + parts);
     __syncthreads();                                   // the zeros are in place
-    while (n < g.N) {
-        image(sa, n);
-        n += parts;
-        if (n >= g.N) break;
-        image(sb, n);
-        n += parts;
+    if constexpr (DEPTH == 2) {
+        while (f < nfills) {
+            fill(sa, f);
+            f += parts;
+            if (f >= nfills) break;
+            fill(sb, f);
+            f += parts;
+        }
+    } else {
+        for (; f < nfills; f += parts) fill(sa, f);
     }
 
     // the 16 blocks of the wavefront hold 16 partial sums of the same entries: butterfly over the block index
@@ -212,21 +254,24 @@ bool gconv_nchws_mfma_bwd_filter_supported(const GGeom &g)
 {
     if (tune_env("DWCONV_TUNE_GNOSMM")) return false;
     if (!(g.K == 3 && g.s == 1 && g.p == 1 && g.Cg == g.Og && (g.Cg == 4 || g.Cg == 8))) return false;
-    return g.H == 28 && g.W == 28 && g.C % 8 == 0;
+    return ((g.H == 28 && g.W == 28) || (g.H == 56 && g.W == 56)) && g.C % 8 == 0;
 }
 
-// images are dealt to `parts` blocks per channel octet, about 512 blocks in the launch (two per compute unit: all resident at once; 1024 measured 15 % slower, the first loads and the final reduction of a block are not overlapped with anything of its own), every block the same number
-// of images where the batch allows it
+// fills (28x28: images; 56x56: strips of 14 rows of an image) are dealt to `parts` blocks per channel octet, about 512
+// blocks in the launch (two per compute unit, all resident at once; 1024 measured 15 % slower: the first loads and the
+// final reduction of a block are not overlapped with anything of its own), every block the same number of fills where
+// the batch allows it
+static int nchws_mfma_fills(const GGeom &g) { return g.N * (g.W == 56 ? 4 : 1); }
 static int nchws_mfma_blocks_per_octet(const GGeom &g)
 {
     int target = 512;
     if (const char *e = tune_env("DWCONV_TUNE_GSMBLOCKS")) if (atoi(e) > 0) target = atoi(e);
-    const int octets = g.C / 8;
+    const int octets = g.C / 8, nf = nchws_mfma_fills(g);
     int p = (target + octets - 1) / octets;
-    if (p > g.N) p = g.N;
+    if (p > nf) p = nf;
     if (p < 1) p = 1;
-    const int per = (g.N + p - 1) / p;
-    return (g.N + per - 1) / per;
+    const int per = (nf + p - 1) / p;
+    return (nf + per - 1) / per;
 }
 
 int gconv_nchws_mfma_bwd_filter_parts(const GGeom &g) { return nchws_mfma_blocks_per_octet(g) * (g.Cg == 4 ? 2 : 1); }
@@ -237,8 +282,13 @@ hipError_t gconv_nchws_mfma_bwd_filter(const GGeom &g, int dtype, const void *x,
     const int bpo = nchws_mfma_blocks_per_octet(g);
     const unsigned nblocks = (unsigned)(g.C / 8) * (unsigned)bpo;
     const int J = g.O * g.Cg * 9;
-#define GO(T, CGG) hipLaunchKernelGGL((k_gconv_nchws_mfma_bwd_filter<T, CGG, 28, 28>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, \
-                                      (const T *)dy, ws, bpo, nblocks, J)
+#define GO(T, CGG)                                                                                                                \
+    do {                                                                                                                          \
+        if (g.W == 28) hipLaunchKernelGGL((k_gconv_nchws_mfma_bwd_filter<T, CGG, 28, 28>), dim3(nblocks), dim3(256), 0, st, g,    \
+                                          (const T *)x, (const T *)dy, ws, bpo, nchws_mfma_fills(g), nblocks, J);                 \
+        else hipLaunchKernelGGL((k_gconv_nchws_mfma_bwd_filter<T, CGG, 56, 56>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, \
+                                (const T *)dy, ws, bpo, nchws_mfma_fills(g), nblocks, J);                                         \
+    } while (0)
     if (dtype == DT_F32) { if (g.Cg == 8) GO(float, 8); else GO(float, 4); }
     else                 { if (g.Cg == 8) GO(bf16_t, 8); else GO(bf16_t, 4); }
 #undef GO

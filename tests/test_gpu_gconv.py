@@ -179,9 +179,11 @@ def test_group_nhwc_bf16_filter_gradient_dot_product_form_forced_tilings():
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
 def test_group_nchw_matrix_core_filter_gradient_forced_tilings(dtype):
-    """NCHW filter gradient of 28x28 planes with 4 or 8 channels per group (matrix cores, planes staged in LDS): blocks
-    that take one image, several, and a ragged share of the batch; one channel octet and several."""
-    cases = [("mf_cg8", 5, 16, 16, 2, 28, 28, 3, 1, 1), ("mf_cg4", 7, 24, 24, 6, 28, 28, 3, 1, 1), ("mf_cg8_n1", 1, 8, 8, 1, 28, 28, 3, 1, 1)]
+    """NCHW filter gradient of 28x28 and 56x56 planes with 4 or 8 channels per group (matrix cores, planes or 14-row
+    strips staged in LDS): blocks that take one image or strip, several, and a ragged share of them; one channel octet
+    and several."""
+    cases = [("mf_cg8", 5, 16, 16, 2, 28, 28, 3, 1, 1), ("mf_cg4", 7, 24, 24, 6, 28, 28, 3, 1, 1), ("mf_cg8_n1", 1, 8, 8, 1, 28, 28, 3, 1, 1),
+             ("mf56_cg8", 2, 8, 8, 1, 56, 56, 3, 1, 1), ("mf56_cg4", 3, 16, 16, 4, 56, 56, 3, 1, 1)]
     knobs = [{}, {"DWCONV_TUNE_GSMBLOCKS": "1"}, {"DWCONV_TUNE_GSMBLOCKS": "4"}, {"DWCONV_TUNE_GSMBLOCKS": "9"}]
     for case in cases:
         name, N, C, O, G, H, W, K, s, p = case
