@@ -220,7 +220,10 @@ static GPlan gplan(const GGeom &g, int layout, int dtype, int pass)
     // 103; bf16 batch 256: 48 against 95, 83 against 107, 166 against 160)
     // Rows the row-walk kernels cannot take (7 elements) always go to the small-plane form instead of the generic one.
     const bool small_ok = pass < 2 || (g.Cg <= 4 && (g.W <= 14 || dtype == DT_BF16)) || !gconv_nchw_supported(g);      // (stride 2: always)
-    if (layout == LAYOUT_NCHW && pass == 2 && gconv_nchws_mfma_bwd_filter_supported(g)) {
+    if (layout == LAYOUT_NCHW && pass < 2 && gconv_nchws_mfma_fwd_supported(g)) {
+        pl.variant = GV_NCHWS_MFMA_FWD;
+        pl.name = pass == 0 ? "group_nchw_smallplane_mfma_k3s1" : "group_nchw_smallplane_mfma_k3s1_flip";
+    } else if (layout == LAYOUT_NCHW && pass == 2 && gconv_nchws_mfma_bwd_filter_supported(g)) {
         pl.variant = GV_NCHWS_MFMA_BWD_FILTER;
         pl.name = "group_nchw_smallplane_mfma_bwd_filter_k3s1";
         pl.parts = gconv_nchws_mfma_bwd_filter_parts(g);
@@ -338,7 +341,8 @@ int gconv_fwd(const dwconv_group_desc *desc, const void *x, const void *w, void 
     if (gmisaligned(x) || gmisaligned(w) || gmisaligned(y)) return DWCONV_ERR_ALIGN;
     const GPlan pl = gplan(g, desc->layout, desc->dtype, 0);
     hipError_t e;
-    if (pl.variant == GV_NCHWS_K3S1) e = nchws_group_fwd(as_geom(g), g.Cg, desc->dtype, x, w, y, false, (hipStream_t)stream);
+    if (pl.variant == GV_NCHWS_MFMA_FWD) e = gconv_nchws_mfma_fwd(g, desc->dtype, x, w, y, false, (hipStream_t)stream);
+    else if (pl.variant == GV_NCHWS_K3S1) e = nchws_group_fwd(as_geom(g), g.Cg, desc->dtype, x, w, y, false, (hipStream_t)stream);
     else if (pl.variant == GV_NCHW_K3S1) e = gconv_nchw_s1(g, desc->dtype, x, w, y, false, (hipStream_t)stream);
     else if (pl.variant == GV_NHWC_K3S1) e = gconv_nhwc_s1(g, desc->dtype, x, w, y, false, (hipStream_t)stream);
     else if (pl.variant == GV_NHWC_MFMA_S2) e = gconv_nhwc_mfma_s2(g, desc->dtype, x, w, y, false, (hipStream_t)stream);
@@ -359,7 +363,8 @@ int gconv_bwd_data(const dwconv_group_desc *desc, const void *dy, const void *w,
     if (gmisaligned(dy) || gmisaligned(w) || gmisaligned(dx)) return DWCONV_ERR_ALIGN;
     const GPlan pl = gplan(g, desc->layout, desc->dtype, 1);
     hipError_t e;
-    if (pl.variant == GV_NCHWS_K3S1 && g.s == 2) e = nchws_group_bwd_data_s2(as_geom(g), g.Cg, desc->dtype, dy, w, dx, (hipStream_t)stream);
+    if (pl.variant == GV_NCHWS_MFMA_FWD) e = gconv_nchws_mfma_fwd(g, desc->dtype, dy, w, dx, true, (hipStream_t)stream);
+    else if (pl.variant == GV_NCHWS_K3S1 && g.s == 2) e = nchws_group_bwd_data_s2(as_geom(g), g.Cg, desc->dtype, dy, w, dx, (hipStream_t)stream);
     else if (pl.variant == GV_NCHWS_K3S1) e = nchws_group_fwd(as_geom(g), g.Cg, desc->dtype, dy, w, dx, true, (hipStream_t)stream);
     else if (pl.variant == GV_NCHW_K3S1) e = gconv_nchw_s1(g, desc->dtype, dy, w, dx, true, (hipStream_t)stream);
     else if (pl.variant == GV_NHWC_K3S1) e = gconv_nhwc_s1(g, desc->dtype, dy, w, dx, true, (hipStream_t)stream);

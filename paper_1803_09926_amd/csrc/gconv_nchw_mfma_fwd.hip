@@ -1,0 +1,255 @@
+// Group convolution, NCHW, 3x3 stride 1 pad 1: forward (Eq. 2 with the sum over a group's input channels) and
+// backward-data (Eq. 3) on the matrix cores, for 4 or 8 channels per group on both sides and 28x28 or 56x56 planes.
+//
+// y[o][p] = sum over (b, tap) of w[o][b][tap] * x[b][p + tap] is a matrix product with the output channels as rows and
+// the pixels as columns.  In a 4x4 matrix instruction a block of four lanes is four consecutive pixels of a row: the
+// lane's A operand is the filter entry of ITS output channel of the quad (a register that never changes), its B
+// operand the input value at ITS pixel, and D[i][j] (register i of lane j) collects y[output channel i][pixel j].
+// fp32: one (input channel, tap) per instruction (4x4x1).  bf16: the inner dimension of 4x4x4 is four input channels,
+// the lane packs its pixel's four values (read one by one from the channel planes) into two registers.
+//
+// The block stages eight consecutive input channels (one group of 8 or two groups of 4) of one image (56x56: of a
+// 14-row strip and the rows above and below it) in LDS exactly as the filter gradient does (gconv_nchw_mfma.hip:
+// flat 16-byte loads two fills ahead in registers, a gap of zeros after each row, zero rows at the plane's edge), and
+// the eight output planes of the fill in a second LDS area, written back as flat 16-byte stores.  A wavefront owns one
+// output quad and half of the fill's rows; its lanes are the pixels of a row and its gap (28-wide: two rows side by
+// side), and it walks the input rows downwards: an input row adds to three output rows (three accumulators that
+// change roles), the pixel to the left and right comes from the neighbour lanes by a lane permute, and an output row
+// leaves for LDS when its last input row is done.  Backward-data is the same walk over dy with the filter
+// transposed within the group and the taps reversed.
+#include "gconv_mfma.hpp"
+
+namespace dwc {
+
+template <typename T, int CG, int W, int H, bool FLIP>
+__global__ __launch_bounds__(256) void k_gconv_nchws_mfma_fwd(GGeom g, const T *__restrict__ in, const T *__restrict__ w,
+                                                              T *__restrict__ out, int parts, int nfills, unsigned nblocks)
+{
+    using L = PlaneFill<W, H>;
+    static_assert(CG == 4 || CG == 8, "groups of 4 or 8");
+    constexpr bool F32 = sizeof(T) == 4;
+    constexpr int CPV = F32 ? 1 : 2;                // four-pixel vectors of a 16-byte chunk
+    constexpr int XCH = 8 * L::XROWS * L::VPR / CPV, YCH = 8 * L::RS * L::VPR / CPV;     // chunks of a fill
+    constexpr int XPASS = (XCH + 255) / 256, YPASS = (YCH + 255) / 256;
+    constexpr int AREA_Y = 8 * L::RS * W;           // output planes of the fill, rows packed
+    __shared__ __align__(16) T lds[L::AREA_X + AREA_Y];
+    // fills ahead in registers; fp32 strips: one (two would leave registers for one wavefront per SIMD only)
+    constexpr int DEPTH = (F32 && L::STRIP) ? 1 : 2;
+
+    unsigned lb = xcd_remap(blockIdx.x, nblocks);
+    const int part = lb % parts, cb = lb / parts;   // cb: the block's channel octet
+    const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    T *ylds = lds + L::AREA_X;
+
+    for (int i = tid; i < L::AREA_X * (int)sizeof(T) / 16; i += 256) reinterpret_cast<u4raw_t *>(lds)[i] = u4raw_t{0u, 0u, 0u, 0u};
+
+    struct Where { int plane, row, cv; };
+    auto where = [](int v, int rows) { Where q; q.plane = v / (rows * L::VPR); const int rem = v % (rows * L::VPR); q.row = rem / L::VPR; q.cv = rem % L::VPR; return q; };
+
+    // DEPTH fills ahead in registers; every load is issued unconditionally (see the filter gradient)
+    struct Stage { u4raw_t x[XPASS]; uint32_t xok; };
+    auto gload = [&](Stage &s, int f) {
+        const int ff = f < nfills ? f : part;
+        const int n = ff / L::NSTRIP, r0 = (ff % L::NSTRIP) * L::RS;
+        const T *xs = in + ((size_t)n * g.C + (size_t)cb * 8) * (H * W);
+        s.xok = 0xffffffffu;
+#pragma unroll
+        for (int p = 0; p < XPASS; ++p) {
+            const int q = min(p * 256 + tid, XCH - 1);
+            if constexpr (L::STRIP) {
+                const Where wq = where(q * CPV, L::XROWS);
+                const int rg = r0 - 1 + wq.row;
+                if (rg < 0 || rg >= H) s.xok &= ~(1u << p);
+                s.x[p] = *reinterpret_cast<const u4raw_t *>(xs + (size_t)wq.plane * (H * W) + min(max(rg, 0), H - 1) * W + wq.cv * 4);
+            } else {
+                s.x[p] = *reinterpret_cast<const u4raw_t *>(xs + (size_t)q * (4 * CPV));
+            }
+        }
+    };
+    auto lstore = [&](const Stage &s) {
+#pragma unroll
+        for (int p = 0; p < XPASS; ++p) {
+            const int q = p * 256 + tid;
+            if ((p + 1) * 256 <= XCH || q < XCH) {
+                const bool ok = (s.xok >> p) & 1u;
+                const u4raw_t v = {ok ? s.x[p].x : 0u, ok ? s.x[p].y : 0u, ok ? s.x[p].z : 0u, ok ? s.x[p].w : 0u};
+                constexpr int RSH = L::STRIP ? 0 : 1;
+                if constexpr (F32) {
+                    const Where wq = where(q, L::XROWS);
+                    *reinterpret_cast<u4raw_t *>(lds + wq.plane * L::PPX + (wq.row + RSH) * L::WP + wq.cv * 4) = v;
+                } else {
+                    const Where w0 = where(2 * q, L::XROWS), w1 = where(2 * q + 1, L::XROWS);
+                    *reinterpret_cast<u2raw_t *>(lds + w0.plane * L::PPX + (w0.row + RSH) * L::WP + w0.cv * 4) = u2raw_t{v.x, v.y};
+                    *reinterpret_cast<u2raw_t *>(lds + w1.plane * L::PPX + (w1.row + RSH) * L::WP + w1.cv * 4) = u2raw_t{v.z, v.w};
+                }
+            }
+        }
+    };
+    // the fill's output planes: LDS (rows packed, plane after plane) -> global, 16 bytes per lane
+    auto ystore = [&](int f) {
+        const int n = f / L::NSTRIP, r0 = (f % L::NSTRIP) * L::RS;
+        T *ys = out + ((size_t)n * g.C + (size_t)cb * 8) * (H * W);
+#pragma unroll
+        for (int p = 0; p < YPASS; ++p) {
+            const int q = p * 256 + tid;
+            if ((p + 1) * 256 <= YCH || q < YCH) {
+                const u4raw_t v = *reinterpret_cast<const u4raw_t *>(ylds + (size_t)q * (4 * CPV));
+                if constexpr (L::STRIP) {
+                    const Where wq = where(q * CPV, L::RS);
+                    *reinterpret_cast<u4raw_t *>(ys + (size_t)wq.plane * (H * W) + (r0 + wq.row) * W + wq.cv * 4) = v;
+                } else {
+                    *reinterpret_cast<u4raw_t *>(ys + (size_t)q * (4 * CPV)) = v;
+                }
+            }
+        }
+    };
+
+    // The wavefront's task: one output quad of the octet and half of the fill's rows; its lanes are SPW streams, each a
+    // row's pixels and the gap after them.
+    constexpr int LPS = L::WP;                        // lanes of a stream
+    constexpr int RPS = L::RS / 2 / L::SPW;           // output rows of a stream
+    static_assert(L::RS % (2 * L::SPW) == 0, "whole streams");
+    const int oq = wv & 1, half = wv >> 1;            // groups of 8: output quad of the group; groups of 4: the group of the octet
+    const int col = lane % LPS;
+    const int row0 = half * (L::RS / 2) + (lane / LPS) * RPS;         // the stream's first output row within the fill
+    const bool colok = col < W;
+    // neighbour pixels come from the lanes one below and one above; lane 0 has none to its left and starts a row (zero);
+    // every other stream start has the previous stream's gap there (zero), and a row's last pixel has its own gap
+    const int up = ((lane - 1) & 63) * 4, dn = ((lane + 1) & 63) * 4;
+    const uint32_t lmask = lane == 0 ? 0u : 0xffffffffu;
+    // input planes the wavefront reads: the whole group
+    const int cin0 = CG == 8 ? 0 : oq * 4;            // first input plane of the group within the octet
+    const T *xpl = lds + cin0 * L::PPX + (1 + row0) * L::WP + col;
+    T *ypl = ylds + (oq * 4) * (L::RS * W) + row0 * W + col;
+
+    // The lane's filter entries: output channel i = lane & 3 of the quad, every input channel of the group, every tap.
+    // Forward: w[o][b][tap].  Backward-data: the output of this pass is x's channel, the input dy's: w[b][o][8 - tap].
+    const int grp = CG == 8 ? cb : cb * 2 + oq;
+    const int oi = (CG == 8 ? oq * 4 : 0) + (lane & 3);               // the lane's output channel within the group
+    float wf[F32 ? CG * 9 : 1];
+    uint32_t wb[F32 ? 1 : (CG / 4) * 9 * 2];
+#pragma unroll
+    for (int b = 0; b < CG; ++b)
+#pragma unroll
+        for (int tap = 0; tap < 9; ++tap) {
+            const size_t idx = !FLIP ? (((size_t)grp * CG + oi) * CG + b) * 9 + tap : (((size_t)grp * CG + b) * CG + oi) * 9 + (8 - tap);
+            if constexpr (F32) {
+                wf[b * 9 + tap] = w[idx];
+            } else {
+                const uint32_t h = w[idx];
+                uint32_t &dst = wb[((b / 4) * 9 + tap) * 2 + (b % 4) / 2];
+                if (b % 2 == 0) dst = h; else dst |= h << 16;
+            }
+        }
+
+    v4f_t acc[3];
+
+    auto fill = [&](Stage &s, int f) {
+        lstore(s);
+        __syncthreads();
+        gload(s, f + DEPTH * parts);
+        // input row t (relative to the stream's first output row) adds tap row kh to output row t + 1 - kh
+#pragma unroll
+        for (int t = -1; t <= RPS; ++t) {
+            v4f_t &a0 = acc[(t + 4) % 3], &a1 = acc[(t + 3) % 3], &a2 = acc[(t + 2) % 3];     // output rows t+1, t, t-1
+            const bool k0 = t + 1 < RPS, k1 = t >= 0 && t < RPS, k2 = t - 1 >= 0;
+            if (k0) a0 = v4f_t{0.f, 0.f, 0.f, 0.f};                                             // output row t+1 starts here
+            if constexpr (F32) {
+#pragma unroll
+                for (int b = 0; b < CG; ++b) {
+                    const uint32_t c = __float_as_uint(xpl[b * L::PPX + t * L::WP]);
+                    float X[3];
+                    X[0] = __uint_as_float((uint32_t)__builtin_amdgcn_ds_bpermute(up, (int)c) & lmask);
+                    X[1] = __uint_as_float(c);
+                    X[2] = __uint_as_float((uint32_t)__builtin_amdgcn_ds_bpermute(dn, (int)c));
+#pragma unroll
+                    for (int kw = 0; kw < 3; ++kw) {
+                        if (k0) a0 = __builtin_amdgcn_mfma_f32_4x4x1f32(wf[b * 9 + kw], X[kw], a0, 0, 0, 0);
+                        if (k1) a1 = __builtin_amdgcn_mfma_f32_4x4x1f32(wf[b * 9 + 3 + kw], X[kw], a1, 0, 0, 0);
+                        if (k2) a2 = __builtin_amdgcn_mfma_f32_4x4x1f32(wf[b * 9 + 6 + kw], X[kw], a2, 0, 0, 0);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int bq = 0; bq < CG / 4; ++bq) {
+                    const T *px = xpl + (bq * 4) * L::PPX + t * L::WP;
+                    const uint32_t c0 = px[0], c1 = px[L::PPX], c2 = px[2 * L::PPX], c3 = px[3 * L::PPX];
+                    u2w_t X[3];
+                    X[1] = u2w_t{c0 | (c1 << 16), c2 | (c3 << 16)};
+                    X[0] = u2w_t{(uint32_t)__builtin_amdgcn_ds_bpermute(up, (int)X[1].x) & lmask, (uint32_t)__builtin_amdgcn_ds_bpermute(up, (int)X[1].y) & lmask};
+                    X[2] = u2w_t{(uint32_t)__builtin_amdgcn_ds_bpermute(dn, (int)X[1].x), (uint32_t)__builtin_amdgcn_ds_bpermute(dn, (int)X[1].y)};
+#pragma unroll
+                    for (int kw = 0; kw < 3; ++kw) {
+                        const v4s_t bv = __builtin_bit_cast(v4s_t, X[kw]);
+                        auto A = [&](int tap) { return __builtin_bit_cast(v4s_t, u2w_t{wb[(bq * 9 + tap) * 2], wb[(bq * 9 + tap) * 2 + 1]}); };
+                        if (k0) a0 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(A(kw), bv, a0, 0, 0, 0);
+                        if (k1) a1 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(A(3 + kw), bv, a1, 0, 0, 0);
+                        if (k2) a2 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(A(6 + kw), bv, a2, 0, 0, 0);
+                    }
+                }
+            }
+            if (k2 && colok) {                              // output row t-1 is complete
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if constexpr (F32) ypl[i * (L::RS * W) + (t - 1) * W] = a2[i];
+                    else ypl[i * (L::RS * W) + (t - 1) * W] = f32_to_bf16(a2[i]);
+                }
+            }
+        }
+        __syncthreads();                               // the input rows are free, the output planes complete
+        ystore(f);
+    };
+
+    Stage sa, sb;
+    int f = part;
+    gload(sa, f);                                      // part < parts <= nfills
+    if constexpr (DEPTH == 2) gload(sb, f + parts);
+    __syncthreads();                                   // the zeros are in place
+    if constexpr (DEPTH == 2) {
+        while (f < nfills) {
+            fill(sa, f);
+            f += parts;
+            if (f >= nfills) break;
+            fill(sb, f);
+            f += parts;
+        }
+    } else {
+        for (; f < nfills; f += parts) fill(sa, f);
+    }
+}
+
+// ---- host side ---------------------------------------------------------------------------------------------
+
+bool gconv_nchws_mfma_fwd_supported(const GGeom &g)
+{
+    if (tune_env("DWCONV_TUNE_GNOSMMF")) return false;
+    if (!(g.K == 3 && g.s == 1 && g.p == 1 && g.Cg == g.Og && (g.Cg == 4 || g.Cg == 8))) return false;
+    return ((g.H == 28 && g.W == 28) || (g.H == 56 && g.W == 56)) && g.C % 8 == 0;
+}
+
+hipError_t gconv_nchws_mfma_fwd(const GGeom &g, int dtype, const void *in, const void *w, void *out, bool flip, hipStream_t st)
+{
+    if (!gconv_nchws_mfma_fwd_supported(g)) return hipErrorInvalidValue;
+    // fills (images, or 14-row strips of 56x56 images) dealt to about 512 blocks, all resident at once
+    int target = 512;
+    if (const char *e = tune_env("DWCONV_TUNE_GSMFBLOCKS")) if (atoi(e) > 0) target = atoi(e);
+    const int octets = g.C / 8, nf = g.N * (g.W == 56 ? 4 : 1);
+    int p = (target + octets - 1) / octets;
+    if (p > nf) p = nf;
+    if (p < 1) p = 1;
+    const int per = (nf + p - 1) / p;
+    const int bpo = (nf + per - 1) / per;
+    const unsigned nblocks = (unsigned)octets * (unsigned)bpo;
+#define GO3(T, CGG, WW, FL) hipLaunchKernelGGL((k_gconv_nchws_mfma_fwd<T, CGG, WW, WW, FL>), dim3(nblocks), dim3(256), 0, st, g, (const T *)in, \
+                                               (const T *)w, (T *)out, bpo, nf, nblocks)
+#define GO2(T, CGG, WW) do { if (flip) GO3(T, CGG, WW, true); else GO3(T, CGG, WW, false); } while (0)
+#define GO1(T, CGG) do { if (g.W == 28) GO2(T, CGG, 28); else GO2(T, CGG, 56); } while (0)
+    if (dtype == DT_F32) { if (g.Cg == 8) GO1(float, 8); else GO1(float, 4); }
+    else                 { if (g.Cg == 8) GO1(bf16_t, 8); else GO1(bf16_t, 4); }
+#undef GO1
+#undef GO2
+#undef GO3
+    return hipGetLastError();
+}
+
+}  // namespace dwc

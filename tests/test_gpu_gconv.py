@@ -178,25 +178,32 @@ def test_group_nhwc_bf16_filter_gradient_dot_product_form_forced_tilings():
 
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
-def test_group_nchw_matrix_core_filter_gradient_forced_tilings(dtype):
-    """NCHW filter gradient of 28x28 and 56x56 planes with 4 or 8 channels per group (matrix cores, planes or 14-row
+def test_group_nchw_matrix_core_kernels_forced_tilings(dtype):
+    """NCHW forward, backward-data and filter gradient of 28x28 and 56x56 planes with 4 or 8 channels per group (matrix cores, planes or 14-row
     strips staged in LDS): blocks that take one image or strip, several, and a ragged share of them; one channel octet
     and several."""
     cases = [("mf_cg8", 5, 16, 16, 2, 28, 28, 3, 1, 1), ("mf_cg4", 7, 24, 24, 6, 28, 28, 3, 1, 1), ("mf_cg8_n1", 1, 8, 8, 1, 28, 28, 3, 1, 1),
              ("mf56_cg8", 2, 8, 8, 1, 56, 56, 3, 1, 1), ("mf56_cg4", 3, 16, 16, 4, 56, 56, 3, 1, 1)]
-    knobs = [{}, {"DWCONV_TUNE_GSMBLOCKS": "1"}, {"DWCONV_TUNE_GSMBLOCKS": "4"}, {"DWCONV_TUNE_GSMBLOCKS": "9"}]
+    knobs = [{}, {"DWCONV_TUNE_GSMBLOCKS": "1", "DWCONV_TUNE_GSMFBLOCKS": "1"}, {"DWCONV_TUNE_GSMBLOCKS": "4", "DWCONV_TUNE_GSMFBLOCKS": "3"},
+             {"DWCONV_TUNE_GSMBLOCKS": "9", "DWCONV_TUNE_GSMFBLOCKS": "7"}]
+    tol = gu.TOL_F32 if dtype == wl.F32 else gu.TOL_BF16
     for case in cases:
         name, N, C, O, G, H, W, K, s, p = case
         x, w, dy = wl.make_group_inputs(N, C, O, G, H, W, K, s, p, wl.NCHW, dtype, seed=55)
         kw = dict(K=K, stride=s, pad=p, groups=G, O=O, layout=wl.NCHW, nthreads=8)
-        want = og.bwd_filter(x, dy, **kw)
+        want = (og.fwd(x, w, **kw), og.bwd_data(dy, w, x_shape=x.shape, **kw), og.bwd_filter(x, dy, **kw))
         d = dw.group_desc(N, C, H, W, K, s, p, G, O, wl.NCHW, dtype)
+        assert dw.gconv_variant_name(d, 0) == "group_nchw_smallplane_mfma_k3s1"
+        assert dw.gconv_variant_name(d, 1) == "group_nchw_smallplane_mfma_k3s1_flip"
         assert dw.gconv_variant_name(d, 2) == "group_nchw_smallplane_mfma_bwd_filter_k3s1"
         for kn in knobs:
             with dw.tuning_overrides(kn):
                 print("case", name, "knobs", kn, flush=True)
-                _, _, dwt = run_gpu(case, wl.NCHW, dtype, x, w, dy)
-            gu.assert_close(gu.to_host(dwt), want, gu.TOL_F32_FILTER, "gconv bwd_filter %s %s" % (name, kn))
+                y, dx, dwt = run_gpu(case, wl.NCHW, dtype, x, w, dy)
+            tag = "%s %s" % (name, kn)
+            gu.assert_close(gu.to_host(y), want[0], tol, "gconv fwd " + tag)
+            gu.assert_close(gu.to_host(dx), want[1], tol, "gconv bwd_data " + tag)
+            gu.assert_close(gu.to_host(dwt), want[2], gu.TOL_F32_FILTER, "gconv bwd_filter " + tag)
 
 
 def test_group_bwd_filter_is_deterministic():
