@@ -125,15 +125,16 @@ __device__ __forceinline__ void load_group_filter(const T *__restrict__ w, int C
 //
 // What a block holds in LDS at a time ("fill"): RS rows of eight dy planes and the RS + 2 rows of the eight x planes
 // their taps reach.  28x28: the whole plane (the rows above and below it are zeros that are written once).  56x56:
-// strips of 14 rows (the rows above and below a strip are loaded, or zeroed at the plane's edge).  A row is followed
+// strips of 14 rows (the rows above and below a strip are loaded, or zeroed at the plane's edge); 112x112 (forward and
+// backward-data only): strips of 14 rows in bf16, 7 in fp32.  A row is followed
 // by a gap of zeros up to the pitch WP = 16 positions / streams: two rows of 8 positions or one row of 16.
-template <int W, int H> struct PlaneFill {
-    static_assert((W == 28 && H == 28) || (W == 56 && H == 56), "28x28 planes whole, 56x56 planes in strips");
-    static constexpr bool STRIP = W == 56;
-    static constexpr int RS = STRIP ? 14 : H;           // dy rows of a fill
+template <int W, int H, int ESZ = 4> struct PlaneFill {
+    static_assert((W == 28 && H == 28) || (W == 56 && H == 56) || (W == 112 && H == 112), "28x28 planes whole, larger planes in strips");
+    static constexpr bool STRIP = W != 28;
+    static constexpr int RS = W == 28 ? H : (W == 56 || ESZ == 2) ? 14 : 7;      // dy rows of a fill
     static constexpr int NSTRIP = H / RS;
-    static constexpr int WP = STRIP ? 64 : 32;          // row pitch in elements
-    static constexpr int SPW = 64 / WP;                 // streams (rows walked side by side) of a wavefront
+    static constexpr int WP = W == 28 ? 32 : W == 56 ? 64 : 128;     // row pitch in elements
+    static constexpr int SPW = 64 / WP;                 // streams (rows walked side by side) of a wavefront; 0: a row spans two
     static constexpr int VPR = W / 4;                   // four-pixel vectors of a row
     static constexpr int PADP = 16;                     // planes staggered over the LDS banks
     static constexpr int PPX = (RS + 2) * WP + PADP;    // x plane pitch: row r0 - 1 first

@@ -1,5 +1,6 @@
 // Group convolution, NCHW, 3x3 stride 1 pad 1: forward (Eq. 2 with the sum over a group's input channels) and
-// backward-data (Eq. 3) on the matrix cores, for 4 or 8 channels per group on both sides and 28x28 or 56x56 planes.
+// backward-data (Eq. 3) on the matrix cores, for 4 or 8 channels per group on both sides and 28x28 or 56x56 planes, and
+// for 2 channels per group on 112x112 planes.
 //
 // y[o][p] = sum over (b, tap) of w[o][b][tap] * x[b][p + tap] is a matrix product with the output channels as rows and
 // the pixels as columns.  In a 4x4 matrix instruction a block of four lanes is four consecutive pixels of a row: the
@@ -25,14 +26,16 @@ template <typename T, int CG, int W, int H, bool FLIP>
 __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_fwd(GGeom g, const T *__restrict__ in, const T *__restrict__ w,
                                                               T *__restrict__ out, int parts, int nfills, unsigned nblocks)
 {
-    using L = PlaneFill<W, H>;
-    static_assert(CG == 4 || CG == 8, "groups of 4 or 8");
+    using L = PlaneFill<W, H, (int)sizeof(T)>;
+    static_assert(CG == 2 || CG == 4 || CG == 8, "groups of 2, 4 or 8");
     constexpr bool F32 = sizeof(T) == 4;
     constexpr int CPV = F32 ? 1 : 2;                // four-pixel vectors of a 16-byte chunk
     constexpr int XCH = 8 * L::XROWS * L::VPR / CPV, YCH = 8 * L::RS * L::VPR / CPV;     // chunks of a fill
     constexpr int XPASS = (XCH + 255) / 256, YPASS = (YCH + 255) / 256;
     constexpr int AREA_Y = 8 * L::RS * W;           // output planes of the fill, rows packed
-    __shared__ __align__(16) T lds[L::AREA_X + AREA_Y];
+    constexpr int LEAD = 16 / (int)sizeof(T);       // zeros before the first plane: the pixel left of its first one
+    __shared__ __align__(16) T lds_all[LEAD + L::AREA_X + AREA_Y];
+    T *lds = lds_all + LEAD;
     // fills ahead in registers; fp32 strips: one (two would leave registers for one wavefront per SIMD only)
     constexpr int DEPTH = (F32 && L::STRIP) ? 1 : 2;
 
@@ -41,7 +44,7 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_fwd(GGeom g, const T *
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     T *ylds = lds + L::AREA_X;
 
-    for (int i = tid; i < L::AREA_X * (int)sizeof(T) / 16; i += 256) reinterpret_cast<u4raw_t *>(lds)[i] = u4raw_t{0u, 0u, 0u, 0u};
+    for (int i = tid; i < (LEAD + L::AREA_X) * (int)sizeof(T) / 16; i += 256) reinterpret_cast<u4raw_t *>(lds_all)[i] = u4raw_t{0u, 0u, 0u, 0u};
 
     struct Where { int plane, row, cv; };
     auto where = [](int v, int rows) { Where q; q.plane = v / (rows * L::VPR); const int rem = v % (rows * L::VPR); q.row = rem / L::VPR; q.cv = rem % L::VPR; return q; };
@@ -104,41 +107,52 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_fwd(GGeom g, const T *
         }
     };
 
-    // The wavefront's task: one output quad of the octet and half of the fill's rows; its lanes are SPW streams, each a
-    // row's pixels and the gap after them.
-    constexpr int LPS = L::WP;                        // lanes of a stream
-    constexpr int RPS = L::RS / 2 / L::SPW;           // output rows of a stream
-    static_assert(L::RS % (2 * L::SPW) == 0, "whole streams");
-    const int oq = wv & 1, half = wv >> 1;            // groups of 8: output quad of the group; groups of 4: the group of the octet
-    const int col = lane % LPS;
-    const int row0 = half * (L::RS / 2) + (lane / LPS) * RPS;         // the stream's first output row within the fill
+    // The wavefront's task: one output quad of the octet and half of the fill's pixels.  Rows of up to 64 lanes (pixels and
+    // the gap after them): SPW streams side by side, the upper or the lower half of the fill's rows.  Rows of 128 lanes: the
+    // left or the right half of every row.
+    constexpr int LPS = L::WP;                        // lanes of a row
+    constexpr bool WIDE = LPS > 64;
+    constexpr int RPS = WIDE ? L::RS : L::RS / 2 / (WIDE ? 1 : L::SPW);          // output rows of a stream
+    static_assert(WIDE || L::RS % (2 * L::SPW) == 0, "whole streams");
+    const int oq = wv & 1, half = wv >> 1;            // oq: the output quad of the octet
+    const int col = WIDE ? half * 64 + lane : lane % LPS;
+    const int row0 = WIDE ? 0 : half * (L::RS / 2) + (lane / LPS) * RPS;         // the stream's first output row within the fill
     const bool colok = col < W;
-    // neighbour pixels come from the lanes one below and one above; lane 0 has none to its left and starts a row (zero);
-    // every other stream start has the previous stream's gap there (zero), and a row's last pixel has its own gap
+    // Neighbour pixels.  Narrow rows: from the lanes one below and one above by a lane permute; lane 0 has none to its left
+    // and starts a row (zero), every other stream start has the previous stream's gap there (zero), and a row's last pixel
+    // has its own gap.  Wide rows: read from LDS like the pixel itself (the element before a row is the previous row's gap).
     const int up = ((lane - 1) & 63) * 4, dn = ((lane + 1) & 63) * 4;
     const uint32_t lmask = lane == 0 ? 0u : 0xffffffffu;
-    // input planes the wavefront reads: the whole group
-    const int cin0 = CG == 8 ? 0 : oq * 4;            // first input plane of the group within the octet
+    // The quad's input planes.  Groups of 8: the whole octet.  Groups of 4: the quad's own four planes.  Groups of 2: the
+    // quad is two groups, its four planes are their inputs, and a lane's filter entries for the other group's planes are
+    // zero (a block-diagonal 4x4 filter tile).
+    constexpr int CI = CG == 8 ? 8 : 4;
+    const int cin0 = CG == 8 ? 0 : oq * 4;            // first input plane within the octet
     const T *xpl = lds + cin0 * L::PPX + (1 + row0) * L::WP + col;
     T *ypl = ylds + (oq * 4) * (L::RS * W) + row0 * W + col;
 
-    // The lane's filter entries: output channel i = lane & 3 of the quad, every input channel of the group, every tap.
+    // The lane's filter entries: output channel i = lane & 3 of the quad, every input plane of the quad, every tap.
     // Forward: w[o][b][tap].  Backward-data: the output of this pass is x's channel, the input dy's: w[b][o][8 - tap].
-    const int grp = CG == 8 ? cb : cb * 2 + oq;
-    const int oi = (CG == 8 ? oq * 4 : 0) + (lane & 3);               // the lane's output channel within the group
-    float wf[F32 ? CG * 9 : 1];
-    uint32_t wb[F32 ? 1 : (CG / 4) * 9 * 2];
+    const int li = lane & 3;
+    const int grp = CG == 8 ? cb : CG == 4 ? cb * 2 + oq : cb * 4 + oq * 2 + li / 2;
+    const int oi = CG == 8 ? oq * 4 + li : CG == 4 ? li : li % 2;     // the lane's output channel within its group
+    float wf[F32 ? CI * 9 : 1];
+    uint32_t wb[F32 ? 1 : (CI / 4) * 9 * 2];
 #pragma unroll
-    for (int b = 0; b < CG; ++b)
+    for (int b = 0; b < CI; ++b)
 #pragma unroll
         for (int tap = 0; tap < 9; ++tap) {
-            const size_t idx = !FLIP ? (((size_t)grp * CG + oi) * CG + b) * 9 + tap : (((size_t)grp * CG + b) * CG + oi) * 9 + (8 - tap);
+            const int bg = CG == 2 ? b % 2 : b;                       // the plane's channel within the lane's group
+            const bool mine = CG != 2 || b / 2 == li / 2;             // ... if it is one of that group's
+            const size_t idx = !FLIP ? (((size_t)grp * CG + oi) * CG + bg) * 9 + tap : (((size_t)grp * CG + bg) * CG + oi) * 9 + (8 - tap);
             if constexpr (F32) {
-                wf[b * 9 + tap] = w[idx];
+                const float v = w[idx];
+                wf[b * 9 + tap] = mine ? v : 0.f;
             } else {
-                const uint32_t h = w[idx];
+                const uint32_t v = w[idx];
+                const uint32_t hw = mine ? v : 0u;
                 uint32_t &dst = wb[((b / 4) * 9 + tap) * 2 + (b % 4) / 2];
-                if (b % 2 == 0) dst = h; else dst |= h << 16;
+                if (b % 2 == 0) dst = hw; else dst |= hw << 16;
             }
         }
 
@@ -156,12 +170,17 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_fwd(GGeom g, const T *
             if (k0) a0 = v4f_t{0.f, 0.f, 0.f, 0.f};                                             // output row t+1 starts here
             if constexpr (F32) {
 #pragma unroll
-                for (int b = 0; b < CG; ++b) {
-                    const uint32_t c = __float_as_uint(xpl[b * L::PPX + t * L::WP]);
+                for (int b = 0; b < CI; ++b) {
+                    const float *px = xpl + b * L::PPX + t * L::WP;
+                    const uint32_t c = __float_as_uint(px[0]);
                     float X[3];
-                    X[0] = __uint_as_float((uint32_t)__builtin_amdgcn_ds_bpermute(up, (int)c) & lmask);
                     X[1] = __uint_as_float(c);
-                    X[2] = __uint_as_float((uint32_t)__builtin_amdgcn_ds_bpermute(dn, (int)c));
+                    if constexpr (WIDE) {
+                        X[0] = px[-1]; X[2] = px[1];
+                    } else {
+                        X[0] = __uint_as_float((uint32_t)__builtin_amdgcn_ds_bpermute(up, (int)c) & lmask);
+                        X[2] = __uint_as_float((uint32_t)__builtin_amdgcn_ds_bpermute(dn, (int)c));
+                    }
 #pragma unroll
                     for (int kw = 0; kw < 3; ++kw) {
                         if (k0) a0 = __builtin_amdgcn_mfma_f32_4x4x1f32(wf[b * 9 + kw], X[kw], a0, 0, 0, 0);
@@ -171,13 +190,20 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_fwd(GGeom g, const T *
                 }
             } else {
 #pragma unroll
-                for (int bq = 0; bq < CG / 4; ++bq) {
+                for (int bq = 0; bq < CI / 4; ++bq) {
                     const T *px = xpl + (bq * 4) * L::PPX + t * L::WP;
-                    const uint32_t c0 = px[0], c1 = px[L::PPX], c2 = px[2 * L::PPX], c3 = px[3 * L::PPX];
+                    auto four = [&](int d) {          // the quad's four channels at the pixel d columns away
+                        const uint32_t c0 = px[d], c1 = px[L::PPX + d], c2 = px[2 * L::PPX + d], c3 = px[3 * L::PPX + d];
+                        return u2w_t{c0 | (c1 << 16), c2 | (c3 << 16)};
+                    };
                     u2w_t X[3];
-                    X[1] = u2w_t{c0 | (c1 << 16), c2 | (c3 << 16)};
-                    X[0] = u2w_t{(uint32_t)__builtin_amdgcn_ds_bpermute(up, (int)X[1].x) & lmask, (uint32_t)__builtin_amdgcn_ds_bpermute(up, (int)X[1].y) & lmask};
-                    X[2] = u2w_t{(uint32_t)__builtin_amdgcn_ds_bpermute(dn, (int)X[1].x), (uint32_t)__builtin_amdgcn_ds_bpermute(dn, (int)X[1].y)};
+                    X[1] = four(0);
+                    if constexpr (WIDE) {
+                        X[0] = four(-1); X[2] = four(1);
+                    } else {
+                        X[0] = u2w_t{(uint32_t)__builtin_amdgcn_ds_bpermute(up, (int)X[1].x) & lmask, (uint32_t)__builtin_amdgcn_ds_bpermute(up, (int)X[1].y) & lmask};
+                        X[2] = u2w_t{(uint32_t)__builtin_amdgcn_ds_bpermute(dn, (int)X[1].x), (uint32_t)__builtin_amdgcn_ds_bpermute(dn, (int)X[1].y)};
+                    }
 #pragma unroll
                     for (int kw = 0; kw < 3; ++kw) {
                         const v4s_t bv = __builtin_bit_cast(v4s_t, X[kw]);
@@ -223,8 +249,9 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_fwd(GGeom g, const T *
 bool gconv_nchws_mfma_fwd_supported(const GGeom &g)
 {
     if (tune_env("DWCONV_TUNE_GNOSMMF")) return false;
-    if (!(g.K == 3 && g.s == 1 && g.p == 1 && g.Cg == g.Og && (g.Cg == 4 || g.Cg == 8))) return false;
-    return ((g.H == 28 && g.W == 28) || (g.H == 56 && g.W == 56)) && g.C % 8 == 0;
+    if (!(g.K == 3 && g.s == 1 && g.p == 1 && g.Cg == g.Og && g.C % 8 == 0)) return false;
+    if (g.H == 112 && g.W == 112) return g.Cg == 2 && !tune_env("DWCONV_TUNE_GNOSMMF112");
+    return ((g.H == 28 && g.W == 28) || (g.H == 56 && g.W == 56)) && (g.Cg == 4 || g.Cg == 8);
 }
 
 hipError_t gconv_nchws_mfma_fwd(const GGeom &g, int dtype, const void *in, const void *w, void *out, bool flip, hipStream_t st)
@@ -233,7 +260,7 @@ hipError_t gconv_nchws_mfma_fwd(const GGeom &g, int dtype, const void *in, const
     // fills (images, or 14-row strips of 56x56 images) dealt to about 512 blocks, all resident at once
     int target = 512;
     if (const char *e = tune_env("DWCONV_TUNE_GSMFBLOCKS")) if (atoi(e) > 0) target = atoi(e);
-    const int octets = g.C / 8, nf = g.N * (g.W == 56 ? 4 : 1);
+    const int octets = g.C / 8, nf = g.N * (g.W == 56 ? 4 : g.W == 112 ? (dtype == DT_F32 ? 16 : 8) : 1);
     int p = (target + octets - 1) / octets;
     if (p > nf) p = nf;
     if (p < 1) p = 1;
@@ -244,8 +271,9 @@ hipError_t gconv_nchws_mfma_fwd(const GGeom &g, int dtype, const void *in, const
                                                (const T *)w, (T *)out, bpo, nf, nblocks)
 #define GO2(T, CGG, WW) do { if (flip) GO3(T, CGG, WW, true); else GO3(T, CGG, WW, false); } while (0)
 #define GO1(T, CGG) do { if (g.W == 28) GO2(T, CGG, 28); else GO2(T, CGG, 56); } while (0)
-    if (dtype == DT_F32) { if (g.Cg == 8) GO1(float, 8); else GO1(float, 4); }
-    else                 { if (g.Cg == 8) GO1(bf16_t, 8); else GO1(bf16_t, 4); }
+    if (g.W == 112) { if (dtype == DT_F32) GO2(float, 2, 112); else GO2(bf16_t, 2, 112); }
+    else if (dtype == DT_F32) { if (g.Cg == 8) GO1(float, 8); else GO1(float, 4); }
+    else                      { if (g.Cg == 8) GO1(bf16_t, 8); else GO1(bf16_t, 4); }
 #undef GO1
 #undef GO2
 #undef GO3
