@@ -223,10 +223,10 @@ static GPlan gplan(const GGeom &g, int layout, int dtype, int pass)
     if (layout == LAYOUT_NCHW && pass < 2 && gconv_nchws_mfma_fwd_supported(g)) {
         pl.variant = GV_NCHWS_MFMA_FWD;
         pl.name = pass == 0 ? "group_nchw_smallplane_mfma_k3s1" : "group_nchw_smallplane_mfma_k3s1_flip";
-    } else if (layout == LAYOUT_NCHW && pass == 2 && gconv_nchws_mfma_bwd_filter_supported(g)) {
+    } else if (layout == LAYOUT_NCHW && pass == 2 && gconv_nchws_mfma_bwd_filter_supported(g, dtype)) {
         pl.variant = GV_NCHWS_MFMA_BWD_FILTER;
         pl.name = "group_nchw_smallplane_mfma_bwd_filter_k3s1";
-        pl.parts = gconv_nchws_mfma_bwd_filter_parts(g);
+        pl.parts = gconv_nchws_mfma_bwd_filter_parts(g, dtype);
     } else if (layout == LAYOUT_NCHW && g.Cg == g.Og && small_ok && nchws_group_supported(as_geom(g), g.Cg) &&
         !tune_env("DWCONV_TUNE_GNOSMALL")) {
         // small planes (rows of 7, 14 or 28): whole groups staged in LDS through flat 16-byte accesses

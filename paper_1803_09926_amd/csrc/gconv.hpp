@@ -39,8 +39,8 @@ hipError_t gconv_nchw_bwd_filter(const GGeom &g, int dtype, const void *x, const
 
 // ---- NCHW filter gradient on the matrix cores: 3x3 stride 1 pad 1, 4 or 8 channels per group on both sides, 28x28
 // or 56x56 planes (gconv_nchw_mfma.hip)
-bool gconv_nchws_mfma_bwd_filter_supported(const GGeom &g);
-int gconv_nchws_mfma_bwd_filter_parts(const GGeom &g);
+bool gconv_nchws_mfma_bwd_filter_supported(const GGeom &g, int dtype);
+int gconv_nchws_mfma_bwd_filter_parts(const GGeom &g, int dtype);
 hipError_t gconv_nchws_mfma_bwd_filter(const GGeom &g, int dtype, const void *x, const void *dy, float *ws, int parts, hipStream_t st);
 // forward (flip = false) and backward-data (flip = true) of the same shapes (gconv_nchw_mfma_fwd.hip)
 bool gconv_nchws_mfma_fwd_supported(const GGeom &g);

@@ -32,21 +32,26 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_bwd_filter(GGeom g, co
                                                                      float *__restrict__ ws, int parts, int nfills, unsigned nblocks,
                                                                      int J)
 {
-    using L = PlaneFill<W, H>;
-    static_assert(CG == 4 || CG == 8, "groups of 4 or 8");
+    using L = PlaneFill<W, H, (int)sizeof(T)>;
+    static_assert(CG == 2 || CG == 4 || CG == 8, "groups of 2, 4 or 8");
+    constexpr bool WIDE = L::WP > 64;               // a row's 32 positions span two wavefronts
+    // dy rows: with the gap of zeros after each row, or (wide rows, to fit LDS) packed, the gap positions zeroed when read
+    constexpr int DROW = WIDE ? W : L::WP, PPD = WIDE ? L::RS * W : L::PPD, AREA_D = 8 * PPD;
+    constexpr int LEAD = 16 / (int)sizeof(T);       // zeros before the first plane: the pixel left of its first one
+    // fills ahead in registers; fp32 strips and wide rows: one (two would leave registers for one wavefront per SIMD only)
+    constexpr int DEPTH = (L::STRIP && (sizeof(T) == 4 || WIDE)) ? 1 : 2;
     constexpr bool F32 = sizeof(T) == 4;
     constexpr int CPV = F32 ? 1 : 2;                // four-pixel vectors of a 16-byte chunk
     constexpr int XCH = 8 * L::XROWS * L::VPR / CPV, DCH = 8 * L::RS * L::VPR / CPV;     // chunks of a fill
     constexpr int XPASS = (XCH + 255) / 256, DPASS = (DCH + 255) / 256;
-    __shared__ __align__(16) T lds[L::AREA_X + L::AREA_D];    // x planes, then dy planes
-    // fills ahead in registers; fp32 strips: one (two would leave registers for one wavefront per SIMD only)
-    constexpr int DEPTH = (F32 && L::STRIP) ? 1 : 2;
+    __shared__ __align__(16) T lds_all[LEAD + L::AREA_X + AREA_D];    // x planes, then dy planes
+    T *lds = lds_all + LEAD;
 
     unsigned lb = xcd_remap(blockIdx.x, nblocks);
     const int part = lb % parts, cb = lb / parts;   // cb: the block's channel octet
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-    for (int i = tid; i < (L::AREA_X + L::AREA_D) * (int)sizeof(T) / 16; i += 256) reinterpret_cast<u4raw_t *>(lds)[i] = u4raw_t{0u, 0u, 0u, 0u};
+    for (int i = tid; i < (LEAD + L::AREA_X + AREA_D) * (int)sizeof(T) / 16; i += 256) reinterpret_cast<u4raw_t *>(lds_all)[i] = u4raw_t{0u, 0u, 0u, 0u};
 
     // where four-pixel vector v of a fill's x (dy) rows lives: plane, row within the loaded rows, vector within the row
     struct Where { int plane, row, cv; };
@@ -86,14 +91,14 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_bwd_filter(GGeom g, co
             }
         }
     };
-    auto put = [&](T *area, int pitch, int rowshift, int rows, int q, u4raw_t v) {
+    auto put = [&](T *area, int pitch, int rowpitch, int rowshift, int rows, int q, u4raw_t v) {
         if constexpr (F32) {
             const Where wq = where(q, rows);
-            *reinterpret_cast<u4raw_t *>(area + wq.plane * pitch + (wq.row + rowshift) * L::WP + wq.cv * 4) = v;
+            *reinterpret_cast<u4raw_t *>(area + wq.plane * pitch + (wq.row + rowshift) * rowpitch + wq.cv * 4) = v;
         } else {
             const Where w0 = where(2 * q, rows), w1 = where(2 * q + 1, rows);
-            *reinterpret_cast<u2raw_t *>(area + w0.plane * pitch + (w0.row + rowshift) * L::WP + w0.cv * 4) = u2raw_t{v.x, v.y};
-            *reinterpret_cast<u2raw_t *>(area + w1.plane * pitch + (w1.row + rowshift) * L::WP + w1.cv * 4) = u2raw_t{v.z, v.w};
+            *reinterpret_cast<u2raw_t *>(area + w0.plane * pitch + (w0.row + rowshift) * rowpitch + w0.cv * 4) = u2raw_t{v.x, v.y};
+            *reinterpret_cast<u2raw_t *>(area + w1.plane * pitch + (w1.row + rowshift) * rowpitch + w1.cv * 4) = u2raw_t{v.z, v.w};
         }
     };
     auto lstore = [&](const Stage &s) {
@@ -103,13 +108,13 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_bwd_filter(GGeom g, co
             if ((p + 1) * 256 <= XCH || q < XCH) {
                 const bool ok = (s.xok >> p) & 1u;
                 const u4raw_t v = s.x[p];
-                put(lds, L::PPX, L::STRIP ? 0 : 1, L::XROWS, q, u4raw_t{ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u});
+                put(lds, L::PPX, L::WP, L::STRIP ? 0 : 1, L::XROWS, q, u4raw_t{ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u});
             }
         }
 #pragma unroll
         for (int p = 0; p < DPASS; ++p) {
             const int q = p * 256 + tid;
-            if ((p + 1) * 256 <= DCH || q < DCH) put(lds + L::AREA_X, L::PPD, 0, L::RS, q, s.d[p]);
+            if ((p + 1) * 256 <= DCH || q < DCH) put(lds + L::AREA_X, PPD, DROW, 0, L::RS, q, s.d[p]);
         }
     };
 
@@ -118,14 +123,19 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_bwd_filter(GGeom g, co
     // and keeps the three x rows of the taps in registers, so a step reads one new x row and one dy row.  Groups of 8:
     // the wavefront walks all RS rows of the fill.  Groups of 4: the group's two wavefronts take the upper and the
     // lower half of them.
-    constexpr int RPW = CG == 8 ? L::RS : L::RS / 2, RPS = RPW / L::SPW;
-    static_assert(RPW % L::SPW == 0, "whole streams");
+    // Wide rows (two wavefronts per row, groups of 2): the quad is two groups, the wavefront takes the left or the right
+    // 16 positions of every row of the fill, and only the sums of channel pairs of the same group are kept at the end.
+    constexpr int RPW = (CG == 8 || WIDE) ? L::RS : L::RS / 2, RPS = WIDE ? RPW : RPW / (WIDE ? 1 : L::SPW);
+    static_assert(WIDE || RPW % L::SPW == 0, "whole streams");
+    static_assert(WIDE == (CG == 2), "groups of 2 on wide rows only");
     const int xq = wv & 1, dq = CG == 8 ? wv >> 1 : wv & 1;
     const int half = wv >> 1;
     const int slot = lane >> 2;
-    const int row0 = (CG == 8 ? 0 : half * RPW) + (slot / (L::WP / 4)) * RPS;
-    const T *xpl = lds + (xq * 4 + (lane & 3)) * L::PPX + (1 + row0) * L::WP + (slot % (L::WP / 4)) * 4;
-    const T *dpl = lds + L::AREA_X + (dq * 4 + (lane & 3)) * L::PPD + row0 * L::WP + (slot % (L::WP / 4)) * 4;
+    const int pos = WIDE ? half * 16 + slot : slot % (L::WP / 4);                 // the position within its row
+    const int row0 = WIDE ? 0 : (CG == 8 ? 0 : half * RPW) + (slot / (L::WP / 4)) * RPS;
+    const T *xpl = lds + (xq * 4 + (lane & 3)) * L::PPX + (1 + row0) * L::WP + pos * 4;
+    const bool dvalid = !WIDE || pos < L::VPR;         // packed dy rows have no gap: those positions read a real vector and drop it
+    const T *dpl = lds + L::AREA_X + (dq * 4 + (lane & 3)) * PPD + row0 * DROW + (dvalid ? pos : 0) * 4;
     // the neighbour positions' vectors come from the lanes four below and four above; position 0 has no left neighbour
     // in the wavefront and starts a row (zero); the last position of a row is a gap, whatever it gets meets a zero of dy
     const int up = ((lane - 4) & 63) * 4, dn = ((lane + 4) & 63) * 4;
@@ -142,13 +152,23 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_bwd_filter(GGeom g, co
     auto xrow = [&](int t, XRow &X) {
         if constexpr (F32) {
             const u4raw_t v = *reinterpret_cast<const u4raw_t *>(xpl + t * L::WP);
-            X.f[0] = __uint_as_float((uint32_t)__builtin_amdgcn_ds_bpermute(up, (int)v.w) & lmask);
-            X.f[5] = __uint_as_float((uint32_t)__builtin_amdgcn_ds_bpermute(dn, (int)v.x));
+            uint32_t lw = (uint32_t)__builtin_amdgcn_ds_bpermute(up, (int)v.w) & lmask;
+            uint32_t rw = (uint32_t)__builtin_amdgcn_ds_bpermute(dn, (int)v.x);
+            if constexpr (WIDE) {       // the wavefront's first and last position: the neighbour is in the other wavefront (or the gap)
+                if (slot == 0) lw = __float_as_uint(xpl[t * L::WP - 1]);
+                if (slot == 15) rw = __float_as_uint(xpl[t * L::WP + 4]);
+            }
+            X.f[0] = __uint_as_float(lw);
+            X.f[5] = __uint_as_float(rw);
             X.f[1] = __uint_as_float(v.x); X.f[2] = __uint_as_float(v.y); X.f[3] = __uint_as_float(v.z); X.f[4] = __uint_as_float(v.w);
         } else {
             const u2raw_t v = *reinterpret_cast<const u2raw_t *>(xpl + t * L::WP);                  // columns c .. c+3
-            const uint32_t lw = (uint32_t)__builtin_amdgcn_ds_bpermute(up, (int)v.y) & lmask;       // columns c-2, c-1
-            const uint32_t rw = (uint32_t)__builtin_amdgcn_ds_bpermute(dn, (int)v.x);               // columns c+4, c+5
+            uint32_t lw = (uint32_t)__builtin_amdgcn_ds_bpermute(up, (int)v.y) & lmask;             // columns c-2, c-1
+            uint32_t rw = (uint32_t)__builtin_amdgcn_ds_bpermute(dn, (int)v.x);                     // columns c+4, c+5
+            if constexpr (WIDE) {
+                if (slot == 0) lw = *reinterpret_cast<const uint32_t *>(xpl + t * L::WP - 2);
+                if (slot == 15) rw = *reinterpret_cast<const uint32_t *>(xpl + t * L::WP + 4);
+            }
             const uint32_t p0 = __builtin_amdgcn_alignbyte(v.x, lw, 2);             // c-1, c
             const uint32_t p1 = __builtin_amdgcn_alignbyte(v.y, v.x, 2);            // c+1, c+2
             const uint32_t p2 = __builtin_amdgcn_alignbyte(rw, v.y, 2);             // c+3, c+4
@@ -158,7 +178,8 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_bwd_filter(GGeom g, co
     // dy row t against the x rows t-1, t, t+1
     auto step = [&](int t, const XRow &X0, const XRow &X1, const XRow &X2) {
         if constexpr (F32) {
-            const u4raw_t dr = *reinterpret_cast<const u4raw_t *>(dpl + t * L::WP);
+            u4raw_t dr = *reinterpret_cast<const u4raw_t *>(dpl + t * DROW);
+            if (!dvalid) dr = u4raw_t{0u, 0u, 0u, 0u};
             const float d[4] = {__uint_as_float(dr.x), __uint_as_float(dr.y), __uint_as_float(dr.z), __uint_as_float(dr.w)};
 #pragma unroll
             for (int c = 0; c < 4; ++c)
@@ -169,7 +190,8 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_bwd_filter(GGeom g, co
                     acc[2][kw] = __builtin_amdgcn_mfma_f32_4x4x1f32(d[c], X2.f[c + kw], acc[2][kw], 0, 0, 0);
                 }
         } else {
-            const u2raw_t dr = *reinterpret_cast<const u2raw_t *>(dpl + t * L::WP);
+            u2raw_t dr = *reinterpret_cast<const u2raw_t *>(dpl + t * DROW);
+            if (!dvalid) dr = u2raw_t{0u, 0u};
             const v4s_t a = __builtin_bit_cast(v4s_t, dr);
 #pragma unroll
             for (int kw = 0; kw < 3; ++kw) {
@@ -212,7 +234,7 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_bwd_filter(GGeom g, co
     }
 
     // the 16 blocks of the wavefront hold 16 partial sums of the same entries: butterfly over the block index
-    const int pidx = CG == 8 ? part : part * 2 + half;
+    const int pidx = CG == 8 ? part : part * 2 + half;      // groups of 4 and 2: the two wavefronts of a quad write a partial each
     float *wsp = ws + (size_t)pidx * J;
 #pragma unroll
     for (int kh = 0; kh < 3; ++kh)
@@ -222,8 +244,8 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_bwd_filter(GGeom g, co
             for (int i = 0; i < 4; ++i) {
                 float s = acc[kh][kw][i];
                 s += __shfl_xor(s, 4, 64); s += __shfl_xor(s, 8, 64); s += __shfl_xor(s, 16, 64); s += __shfl_xor(s, 32, 64);
-                if (lane < 4) {
-                    const int o = cb * 8 + dq * 4 + i, b = (CG == 8 ? xq * 4 : 0) + lane;
+                if (lane < 4 && (CG != 2 || (lane >> 1) == (i >> 1))) {        // groups of 2: pairs of the same group only
+                    const int o = cb * 8 + dq * 4 + i, b = CG == 8 ? xq * 4 + lane : CG == 4 ? lane : lane & 1;
                     wsp[((size_t)o * CG + b) * 9 + kh * 3 + kw] = s;
                 }
             }
@@ -231,23 +253,26 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_bwd_filter(GGeom g, co
 
 // ---- host side ---------------------------------------------------------------------------------------------
 
-bool gconv_nchws_mfma_bwd_filter_supported(const GGeom &g)
+bool gconv_nchws_mfma_bwd_filter_supported(const GGeom &g, int dtype)
 {
     if (tune_env("DWCONV_TUNE_GNOSMM")) return false;
-    if (!(g.K == 3 && g.s == 1 && g.p == 1 && g.Cg == g.Og && (g.Cg == 4 || g.Cg == 8))) return false;
-    return ((g.H == 28 && g.W == 28) || (g.H == 56 && g.W == 56)) && g.C % 8 == 0;
+    if (!(g.K == 3 && g.s == 1 && g.p == 1 && g.Cg == g.Og && g.C % 8 == 0)) return false;
+    // 112x112 with groups of 2: bf16 only (254 -> 182 us at batch 256); in fp32 the 7-row strips that fit LDS tie with the
+    // row walk (192 us at batch 128), which stays
+    if (g.H == 112 && g.W == 112) return g.Cg == 2 && (dtype == DT_BF16 || tune_env("DWCONV_TUNE_GSMM112F32")) && !tune_env("DWCONV_TUNE_GNOSMM112");
+    return ((g.H == 28 && g.W == 28) || (g.H == 56 && g.W == 56)) && (g.Cg == 4 || g.Cg == 8);
 }
 
 // fills (28x28: images; 56x56: strips of 14 rows of an image) are dealt to `parts` blocks per channel octet, about 512
 // blocks in the launch (two per compute unit, all resident at once; 1024 measured 15 % slower: the first loads and the
 // final reduction of a block are not overlapped with anything of its own), every block the same number of fills where
 // the batch allows it
-static int nchws_mfma_fills(const GGeom &g) { return g.N * (g.W == 56 ? 4 : 1); }
-static int nchws_mfma_blocks_per_octet(const GGeom &g)
+static int nchws_mfma_fills(const GGeom &g, int dtype) { return g.N * (g.W == 56 ? 4 : g.W == 112 ? (dtype == DT_F32 ? 16 : 8) : 1); }
+static int nchws_mfma_blocks_per_octet(const GGeom &g, int dtype)
 {
     int target = 512;
     if (const char *e = tune_env("DWCONV_TUNE_GSMBLOCKS")) if (atoi(e) > 0) target = atoi(e);
-    const int octets = g.C / 8, nf = nchws_mfma_fills(g);
+    const int octets = g.C / 8, nf = nchws_mfma_fills(g, dtype);
     int p = (target + octets - 1) / octets;
     if (p > nf) p = nf;
     if (p < 1) p = 1;
@@ -255,23 +280,21 @@ static int nchws_mfma_blocks_per_octet(const GGeom &g)
     return (nf + per - 1) / per;
 }
 
-int gconv_nchws_mfma_bwd_filter_parts(const GGeom &g) { return nchws_mfma_blocks_per_octet(g) * (g.Cg == 4 ? 2 : 1); }
+int gconv_nchws_mfma_bwd_filter_parts(const GGeom &g, int dtype) { return nchws_mfma_blocks_per_octet(g, dtype) * (g.Cg == 8 ? 1 : 2); }
 
 hipError_t gconv_nchws_mfma_bwd_filter(const GGeom &g, int dtype, const void *x, const void *dy, float *ws, int parts, hipStream_t st)
 {
-    if (!gconv_nchws_mfma_bwd_filter_supported(g) || parts != gconv_nchws_mfma_bwd_filter_parts(g)) return hipErrorInvalidValue;
-    const int bpo = nchws_mfma_blocks_per_octet(g);
+    if (!gconv_nchws_mfma_bwd_filter_supported(g, dtype) || parts != gconv_nchws_mfma_bwd_filter_parts(g, dtype)) return hipErrorInvalidValue;
+    const int bpo = nchws_mfma_blocks_per_octet(g, dtype);
     const unsigned nblocks = (unsigned)(g.C / 8) * (unsigned)bpo;
     const int J = g.O * g.Cg * 9;
-#define GO(T, CGG)                                                                                                                \
-    do {                                                                                                                          \
-        if (g.W == 28) hipLaunchKernelGGL((k_gconv_nchws_mfma_bwd_filter<T, CGG, 28, 28>), dim3(nblocks), dim3(256), 0, st, g,    \
-                                          (const T *)x, (const T *)dy, ws, bpo, nchws_mfma_fills(g), nblocks, J);                 \
-        else hipLaunchKernelGGL((k_gconv_nchws_mfma_bwd_filter<T, CGG, 56, 56>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, \
-                                (const T *)dy, ws, bpo, nchws_mfma_fills(g), nblocks, J);                                         \
-    } while (0)
-    if (dtype == DT_F32) { if (g.Cg == 8) GO(float, 8); else GO(float, 4); }
-    else                 { if (g.Cg == 8) GO(bf16_t, 8); else GO(bf16_t, 4); }
+#define GOW(T, CGG, WW) hipLaunchKernelGGL((k_gconv_nchws_mfma_bwd_filter<T, CGG, WW, WW>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, \
+                                           (const T *)dy, ws, bpo, nchws_mfma_fills(g, dtype), nblocks, J)
+#define GO(T, CGG) do { if (g.W == 28) GOW(T, CGG, 28); else GOW(T, CGG, 56); } while (0)
+    if (g.W == 112) { if (dtype == DT_F32) GOW(float, 2, 112); else GOW(bf16_t, 2, 112); }
+    else if (dtype == DT_F32) { if (g.Cg == 8) GO(float, 8); else GO(float, 4); }
+    else                      { if (g.Cg == 8) GO(bf16_t, 8); else GO(bf16_t, 4); }
+#undef GOW
 #undef GO
     return hipGetLastError();
 }

@@ -278,18 +278,21 @@ def test_group_nchw_matrix_core_filter_gradient_selection_and_workspace():
     """28x28 and 56x56 NCHW planes with 4 or 8 channels per group on both sides take the matrix-core filter gradient; its
     partial sums (one per block and, for groups of 4, per plane half) stay within the workspace the query reports."""
     for N in (1, 3, 128, 1000):
-        for cg, C in ((4, 256), (8, 256), (8, 8), (4, 24)):
+        for cg, C in ((4, 256), (8, 256), (8, 8), (4, 24), (2, 64), (2, 8)):
             for dt in (dw.F32, dw.BF16):
-                for hw, fills in ((28, N), (56, 4 * N)):
+                for hw, fills in (((112, (16 if dt == dw.F32 else 8) * N),) if cg == 2 else ((28, N), (56, 4 * N))):
                     if N * C * hw * hw >= 2 ** 31:
                         continue
                     d = dw.group_desc(N, C, hw, hw, 3, 1, 1, groups=C // cg, O=C, layout=dw.NCHW, dtype=dt)
+                    if hw == 112 and dt == dw.F32:          # stays with the row walk
+                        assert dw.gconv_variant_name(d, 2) == "group_nchw_bwd_filter_k3s1"
+                        continue
                     assert dw.gconv_variant_name(d, 2) == "group_nchw_smallplane_mfma_bwd_filter_k3s1"
                     nbytes = dw.gconv_bwd_filter_workspace_bytes(d)
                     J = C * cg * 9 * 4
                     assert nbytes % J == 0
                     parts = nbytes // J
-                    per_octet = parts // (2 if cg == 4 else 1)
+                    per_octet = parts // (1 if cg == 8 else 2)
                     assert 1 <= per_octet <= fills and per_octet * (C // 8) <= max(512 + C // 8, C // 8)
     # other shapes keep the earlier kernels
     assert dw.gconv_variant_name(dw.group_desc(4, 16, 28, 28, 3, 1, 1, groups=8, O=16), 2) != "group_nchw_smallplane_mfma_bwd_filter_k3s1"

@@ -179,8 +179,8 @@ def test_group_nhwc_bf16_filter_gradient_dot_product_form_forced_tilings():
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
 def test_group_nchw_matrix_core_kernels_forced_tilings(dtype):
-    """NCHW forward, backward-data and filter gradient of 28x28 and 56x56 planes with 4 or 8 channels per group, forward and
-    backward-data of 112x112 planes with 2 (matrix cores, planes or 14-row
+    """NCHW forward, backward-data and filter gradient of 28x28 and 56x56 planes with 4 or 8 channels per group and of
+    112x112 planes with 2 (matrix cores, planes or 14-row
     strips staged in LDS): blocks that take one image or strip, several, and a ragged share of them; one channel octet
     and several."""
     cases = [("mf_cg8", 5, 16, 16, 2, 28, 28, 3, 1, 1), ("mf_cg4", 7, 24, 24, 6, 28, 28, 3, 1, 1), ("mf_cg8_n1", 1, 8, 8, 1, 28, 28, 3, 1, 1),
@@ -197,11 +197,13 @@ def test_group_nchw_matrix_core_kernels_forced_tilings(dtype):
         d = dw.group_desc(N, C, H, W, K, s, p, G, O, wl.NCHW, dtype)
         assert dw.gconv_variant_name(d, 0) == "group_nchw_smallplane_mfma_k3s1"
         assert dw.gconv_variant_name(d, 1) == "group_nchw_smallplane_mfma_k3s1_flip"
-        if W < 112:         # 112-wide rows (groups of 2): forward and backward-data only
+        if W < 112 or dtype == wl.BF16:         # 112-wide fp32 filter gradient: the row walk, unless asked for
             assert dw.gconv_variant_name(d, 2) == "group_nchw_smallplane_mfma_bwd_filter_k3s1"
         for kn in knobs:
+            kn = dict(kn, DWCONV_TUNE_GSMM112F32="1")
             with dw.tuning_overrides(kn):
                 print("case", name, "knobs", kn, flush=True)
+                assert dw.gconv_variant_name(d, 2) == "group_nchw_smallplane_mfma_bwd_filter_k3s1"
                 y, dx, dwt = run_gpu(case, wl.NCHW, dtype, x, w, dy)
             tag = "%s %s" % (name, kn)
             gu.assert_close(gu.to_host(y), want[0], tol, "gconv fwd " + tag)
