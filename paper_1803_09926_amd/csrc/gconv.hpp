@@ -12,7 +12,7 @@ struct GGeom {
     int Ho, Wo;
 };
 
-enum GVariant { GV_GENERIC = 0, GV_NCHW_K3S1, GV_NHWC_K3S1, GV_NCHWS_K3S1, GV_NHWC_MFMA_S2, GV_NHWC_BWD_FILTER_S2, GV_NCHWS_MFMA_BWD_FILTER, GV_NCHWS_MFMA_FWD };
+enum GVariant { GV_GENERIC = 0, GV_NCHW_K3S1, GV_NHWC_K3S1, GV_NCHWS_K3S1, GV_NHWC_MFMA_S2, GV_NHWC_BWD_FILTER_S2, GV_NCHWS_MFMA_BWD_FILTER, GV_NCHWS_MFMA_FWD, GV_NHWC_LDS_MFMA_BWD_FILTER };
 
 struct GPlan {
     int variant;
@@ -38,10 +38,12 @@ hipError_t gconv_nchw_bwd_filter(const GGeom &g, int dtype, const void *x, const
                                  hipStream_t st);
 
 // ---- NCHW filter gradient on the matrix cores: 3x3 stride 1 pad 1, 4 or 8 channels per group on both sides, 28x28
-// or 56x56 planes (gconv_nchw_mfma.hip)
-bool gconv_nchws_mfma_bwd_filter_supported(const GGeom &g, int dtype);
+// or 56x56 planes (gconv_nchw_mfma.hip); nhwc: the same kernel fed from NHWC tensors (28x28 and 56x56), the channels
+// scattered to planes on their way into LDS
+bool gconv_nchws_mfma_bwd_filter_supported(const GGeom &g, int dtype, bool nhwc);
 int gconv_nchws_mfma_bwd_filter_parts(const GGeom &g, int dtype);
-hipError_t gconv_nchws_mfma_bwd_filter(const GGeom &g, int dtype, const void *x, const void *dy, float *ws, int parts, hipStream_t st);
+hipError_t gconv_nchws_mfma_bwd_filter(const GGeom &g, int dtype, bool nhwc, const void *x, const void *dy, float *ws, int parts,
+                                       hipStream_t st);
 // forward (flip = false) and backward-data (flip = true) of the same shapes (gconv_nchw_mfma_fwd.hip)
 bool gconv_nchws_mfma_fwd_supported(const GGeom &g);
 hipError_t gconv_nchws_mfma_fwd(const GGeom &g, int dtype, const void *in, const void *w, void *out, bool flip, hipStream_t st);

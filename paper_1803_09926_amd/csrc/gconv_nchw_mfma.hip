@@ -27,7 +27,7 @@
 
 namespace dwc {
 
-template <typename T, int CG, int W, int H>
+template <typename T, int CG, int W, int H, bool NHWC>
 __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_bwd_filter(GGeom g, const T *__restrict__ x, const T *__restrict__ dy,
                                                                      float *__restrict__ ws, int parts, int nfills, unsigned nblocks,
                                                                      int J)
@@ -42,13 +42,15 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_bwd_filter(GGeom g, co
     constexpr int DEPTH = (L::STRIP && (sizeof(T) == 4 || WIDE)) ? 1 : 2;
     constexpr bool F32 = sizeof(T) == 4;
     constexpr int CPV = F32 ? 1 : 2;                // four-pixel vectors of a 16-byte chunk
+    constexpr int HPP = F32 ? 2 : 1;                // NHWC: 16-byte chunks of a pixel's eight channels
     constexpr int XCH = 8 * L::XROWS * L::VPR / CPV, DCH = 8 * L::RS * L::VPR / CPV;     // chunks of a fill
     constexpr int XPASS = (XCH + 255) / 256, DPASS = (DCH + 255) / 256;
     __shared__ __align__(16) T lds_all[LEAD + L::AREA_X + AREA_D];    // x planes, then dy planes
     T *lds = lds_all + LEAD;
 
     unsigned lb = xcd_remap(blockIdx.x, nblocks);
-    const int part = lb % parts, cb = lb / parts;   // cb: the block's channel octet
+    // cb: the block's channel octet.  NHWC: the octets of one image run side by side (they share its cache lines)
+    const int part = NHWC ? lb / (g.C / 8) : lb % parts, cb = NHWC ? lb % (g.C / 8) : lb / parts;
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
 
     for (int i = tid; i < (LEAD + L::AREA_X + AREA_D) * (int)sizeof(T) / 16; i += 256) reinterpret_cast<u4raw_t *>(lds_all)[i] = u4raw_t{0u, 0u, 0u, 0u};
@@ -68,6 +70,22 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_bwd_filter(GGeom g, co
         const T *xs = x + ((size_t)n * g.C + (size_t)cb * 8) * (H * W);
         const T *ds = dy + ((size_t)n * g.O + (size_t)cb * 8) * (H * W);
         s.xok = 0xffffffffu;
+        if constexpr (NHWC) {
+            // a chunk is one pixel's eight channels (fp32: four of them): 16 bytes every C elements
+#pragma unroll
+            for (int p = 0; p < XPASS; ++p) {
+                const int q = min(p * 256 + tid, XCH - 1), pq = q / HPP, hs = q % HPP;
+                const int rg = (L::STRIP ? r0 - 1 : 0) + pq / W;
+                if (rg < 0 || rg >= H) s.xok &= ~(1u << p);
+                s.x[p] = *reinterpret_cast<const u4raw_t *>(x + (((size_t)n * H + min(max(rg, 0), H - 1)) * W + pq % W) * g.C + cb * 8 + hs * 4);
+            }
+#pragma unroll
+            for (int p = 0; p < DPASS; ++p) {
+                const int q = min(p * 256 + tid, DCH - 1), pq = q / HPP, hs = q % HPP;
+                s.d[p] = *reinterpret_cast<const u4raw_t *>(dy + (((size_t)n * H + r0 + pq / W) * W + pq % W) * g.O + cb * 8 + hs * 4);
+            }
+            return;
+        }
 #pragma unroll
         for (int p = 0; p < XPASS; ++p) {
             const int q = min(p * 256 + tid, XCH - 1);
@@ -101,7 +119,35 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_bwd_filter(GGeom g, co
             *reinterpret_cast<u2raw_t *>(area + w1.plane * pitch + (w1.row + rowshift) * rowpitch + w1.cv * 4) = u2raw_t{v.z, v.w};
         }
     };
+    // NHWC: the chunk's channels go to their planes one element each (consecutive lanes are consecutive pixels of a row)
+    auto scatter = [&](T *area, int pitch, int rowpitch, int rowshift, int q, u4raw_t v) {
+        const int pq = q / HPP, hs = q % HPP;
+        T *dst = area + (hs * 4) * pitch + (pq / W + rowshift) * rowpitch + pq % W;
+        if constexpr (F32) {
+            dst[0] = __uint_as_float(v.x); dst[pitch] = __uint_as_float(v.y); dst[2 * pitch] = __uint_as_float(v.z); dst[3 * pitch] = __uint_as_float(v.w);
+        } else {
+            dst[0] = (T)v.x; dst[pitch] = (T)(v.x >> 16); dst[2 * pitch] = (T)v.y; dst[3 * pitch] = (T)(v.y >> 16);
+            dst[4 * pitch] = (T)v.z; dst[5 * pitch] = (T)(v.z >> 16); dst[6 * pitch] = (T)v.w; dst[7 * pitch] = (T)(v.w >> 16);
+        }
+    };
     auto lstore = [&](const Stage &s) {
+        if constexpr (NHWC) {
+#pragma unroll
+            for (int p = 0; p < XPASS; ++p) {
+                const int q = p * 256 + tid;
+                if ((p + 1) * 256 <= XCH || q < XCH) {
+                    const bool ok = (s.xok >> p) & 1u;
+                    const u4raw_t v = s.x[p];
+                    scatter(lds, L::PPX, L::WP, L::STRIP ? 0 : 1, q, u4raw_t{ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u});
+                }
+            }
+#pragma unroll
+            for (int p = 0; p < DPASS; ++p) {
+                const int q = p * 256 + tid;
+                if ((p + 1) * 256 <= DCH || q < DCH) scatter(lds + L::AREA_X, PPD, DROW, 0, q, s.d[p]);
+            }
+            return;
+        }
 #pragma unroll
         for (int p = 0; p < XPASS; ++p) {
             const int q = p * 256 + tid;
@@ -246,20 +292,25 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_bwd_filter(GGeom g, co
                 s += __shfl_xor(s, 4, 64); s += __shfl_xor(s, 8, 64); s += __shfl_xor(s, 16, 64); s += __shfl_xor(s, 32, 64);
                 if (lane < 4 && (CG != 2 || (lane >> 1) == (i >> 1))) {        // groups of 2: pairs of the same group only
                     const int o = cb * 8 + dq * 4 + i, b = CG == 8 ? xq * 4 + lane : CG == 4 ? lane : lane & 1;
-                    wsp[((size_t)o * CG + b) * 9 + kh * 3 + kw] = s;
+                    if constexpr (NHWC) wsp[((size_t)(kh * 3 + kw) * CG + b) * g.O + o] = s;     // the filter's layout: [tap][input channel][O]
+                    else wsp[((size_t)o * CG + b) * 9 + kh * 3 + kw] = s;
                 }
             }
 }
 
 // ---- host side ---------------------------------------------------------------------------------------------
 
-bool gconv_nchws_mfma_bwd_filter_supported(const GGeom &g, int dtype)
+bool gconv_nchws_mfma_bwd_filter_supported(const GGeom &g, int dtype, bool nhwc)
 {
     if (tune_env("DWCONV_TUNE_GNOSMM")) return false;
     if (!(g.K == 3 && g.s == 1 && g.p == 1 && g.Cg == g.Og && g.C % 8 == 0)) return false;
     // 112x112 with groups of 2: bf16 only (254 -> 182 us at batch 256); in fp32 the 7-row strips that fit LDS tie with the
     // row walk (192 us at batch 128), which stays
-    if (g.H == 112 && g.W == 112) return g.Cg == 2 && (dtype == DT_BF16 || tune_env("DWCONV_TUNE_GSMM112F32")) && !tune_env("DWCONV_TUNE_GNOSMM112");
+    // NHWC: 16 bytes per pixel and octet are fetched, a strided pattern that runs at half the speed of the NCHW form's flat
+    // ranges; it pays where the lane-exchange kernel is bound by arithmetic: bf16 groups of 8 (28x28 at batch 256:
+    // 159 -> 102 us; groups of 4 and fp32 measured 15 to 40 % slower than the earlier kernels and stay there)
+    if (nhwc && (tune_env("DWCONV_TUNE_GNOSMMNHWC") || !((dtype == DT_BF16 && g.Cg == 8) || tune_env("DWCONV_TUNE_GSMMNHWCALL")))) return false;
+    if (g.H == 112 && g.W == 112) return !nhwc && g.Cg == 2 && (dtype == DT_BF16 || tune_env("DWCONV_TUNE_GSMM112F32")) && !tune_env("DWCONV_TUNE_GNOSMM112");
     return ((g.H == 28 && g.W == 28) || (g.H == 56 && g.W == 56)) && (g.Cg == 4 || g.Cg == 8);
 }
 
@@ -282,19 +333,22 @@ static int nchws_mfma_blocks_per_octet(const GGeom &g, int dtype)
 
 int gconv_nchws_mfma_bwd_filter_parts(const GGeom &g, int dtype) { return nchws_mfma_blocks_per_octet(g, dtype) * (g.Cg == 8 ? 1 : 2); }
 
-hipError_t gconv_nchws_mfma_bwd_filter(const GGeom &g, int dtype, const void *x, const void *dy, float *ws, int parts, hipStream_t st)
+hipError_t gconv_nchws_mfma_bwd_filter(const GGeom &g, int dtype, bool nhwc, const void *x, const void *dy, float *ws, int parts,
+                                       hipStream_t st)
 {
-    if (!gconv_nchws_mfma_bwd_filter_supported(g, dtype) || parts != gconv_nchws_mfma_bwd_filter_parts(g, dtype)) return hipErrorInvalidValue;
+    if (!gconv_nchws_mfma_bwd_filter_supported(g, dtype, nhwc) || parts != gconv_nchws_mfma_bwd_filter_parts(g, dtype)) return hipErrorInvalidValue;
     const int bpo = nchws_mfma_blocks_per_octet(g, dtype);
     const unsigned nblocks = (unsigned)(g.C / 8) * (unsigned)bpo;
     const int J = g.O * g.Cg * 9;
-#define GOW(T, CGG, WW) hipLaunchKernelGGL((k_gconv_nchws_mfma_bwd_filter<T, CGG, WW, WW>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, \
-                                           (const T *)dy, ws, bpo, nchws_mfma_fills(g, dtype), nblocks, J)
+#define GOL(T, CGG, WW, NH) hipLaunchKernelGGL((k_gconv_nchws_mfma_bwd_filter<T, CGG, WW, WW, NH>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, \
+                                               (const T *)dy, ws, bpo, nchws_mfma_fills(g, dtype), nblocks, J)
+#define GOW(T, CGG, WW) do { if (nhwc) GOL(T, CGG, WW, true); else GOL(T, CGG, WW, false); } while (0)
 #define GO(T, CGG) do { if (g.W == 28) GOW(T, CGG, 28); else GOW(T, CGG, 56); } while (0)
-    if (g.W == 112) { if (dtype == DT_F32) GOW(float, 2, 112); else GOW(bf16_t, 2, 112); }
+    if (g.W == 112) { if (dtype == DT_F32) GOL(float, 2, 112, false); else GOL(bf16_t, 2, 112, false); }
     else if (dtype == DT_F32) { if (g.Cg == 8) GO(float, 8); else GO(float, 4); }
     else                      { if (g.Cg == 8) GO(bf16_t, 8); else GO(bf16_t, 4); }
 #undef GOW
+#undef GOL
 #undef GO
     return hipGetLastError();
 }

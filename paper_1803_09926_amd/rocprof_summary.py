@@ -70,7 +70,8 @@ VARIANT_KERNELS = {
     "bwd_data:group_nchw_smallplane_k3s1_flip": [r"k_nchws_fwd<[\w ]+, 3, 1, \d+, true, \w+, [248]>"],
     "fwd:group_nchw_smallplane_mfma_k3s1": [r"k_gconv_nchws_mfma_fwd<[\w ]+, \d+, \d+, \d+, false>"],
     "bwd_data:group_nchw_smallplane_mfma_k3s1_flip": [r"k_gconv_nchws_mfma_fwd<[\w ]+, \d+, \d+, \d+, true>"],
-    "bwd_filter:group_nchw_smallplane_mfma_bwd_filter_k3s1": [r"k_gconv_nchws_mfma_bwd_filter<"],
+    "bwd_filter:group_nchw_smallplane_mfma_bwd_filter_k3s1": [r"k_gconv_nchws_mfma_bwd_filter<[\w ]+, \d+, \d+, \d+, false>"],
+    "bwd_filter:group_nhwc_lds_mfma_bwd_filter_k3s1": [r"k_gconv_nchws_mfma_bwd_filter<[\w ]+, \d+, \d+, \d+, true>"],
     "bwd_filter:group_nchw_smallplane_bwd_filter_k3s1": [r"k_nchws_bwd_filter<[\w ]+, 3, 1, \d+, [248]>"],
     # k_gconv_nhwc_xchg<T, CG, V, PF, FLIP>: the lane-exchange walk (groups of 4 or 8 channels)
     "fwd:group_nhwc_rowwalk_k3s1": [r"k_gconv_nhwc_s1<[\w ]+, \d+, \d+, \d+, \d+, false>", r"k_gconv_nhwc_xchg<[\w ]+, \d+, \d+, \d+, false>"],

@@ -211,6 +211,35 @@ def test_group_nchw_matrix_core_kernels_forced_tilings(dtype):
             gu.assert_close(gu.to_host(dwt), want[2], gu.TOL_F32_FILTER, "gconv bwd_filter " + tag)
 
 
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+def test_group_nhwc_lds_matrix_core_filter_gradient_forced_tilings(dtype):
+    """NHWC filter gradient of 28x28 and 56x56 maps with 4 or 8 channels per group: the channels of an octet are scattered to
+    planes in LDS and the sums run on the matrix cores.  Blocks with one fill, several and a ragged share; one octet and
+    several; against the lane-exchange kernels as well."""
+    cases = [("nl_cg8", 5, 16, 16, 2, 28, 28, 3, 1, 1), ("nl_cg4", 7, 24, 24, 6, 28, 28, 3, 1, 1), ("nl_cg8_n1", 1, 8, 8, 1, 28, 28, 3, 1, 1),
+             ("nl56_cg8", 2, 8, 8, 1, 56, 56, 3, 1, 1), ("nl56_cg4", 3, 16, 16, 4, 56, 56, 3, 1, 1)]
+    knobs = [{}, {"DWCONV_TUNE_GSMBLOCKS": "1"}, {"DWCONV_TUNE_GSMBLOCKS": "4"}, {"DWCONV_TUNE_GSMBLOCKS": "9"}]
+    for case in cases:
+        name, N, C, O, G, H, W, K, s, p = case
+        x, w, dy = wl.make_group_inputs(N, C, O, G, H, W, K, s, p, wl.NHWC, dtype, seed=56)
+        kw = dict(K=K, stride=s, pad=p, groups=G, O=O, layout=wl.NHWC, nthreads=8)
+        want = og.bwd_filter(x, dy, **kw)
+        d = dw.group_desc(N, C, H, W, K, s, p, G, O, wl.NHWC, dtype)
+        # chosen by default for bf16 groups of 8 only; the switch asks for it everywhere
+        assert (dw.gconv_variant_name(d, 2) == "group_nhwc_lds_mfma_bwd_filter_k3s1") == (dtype == wl.BF16 and C // G == 8)
+        for kn in knobs:
+            kn = dict(kn, DWCONV_TUNE_GSMMNHWCALL="1")
+            with dw.tuning_overrides(kn):
+                print("case", name, "knobs", kn, flush=True)
+                assert dw.gconv_variant_name(d, 2) == "group_nhwc_lds_mfma_bwd_filter_k3s1"
+                _, _, dwt = run_gpu(case, wl.NHWC, dtype, x, w, dy)
+            gu.assert_close(gu.to_host(dwt), want, gu.TOL_F32_FILTER, "gconv bwd_filter %s %s" % (name, kn))
+        with dw.tuning_overrides({"DWCONV_TUNE_GNOSMMNHWC": "1"}):
+            assert dw.gconv_variant_name(d, 2) == "group_nhwc_bwd_filter_k3s1"
+            _, _, dwt = run_gpu(case, wl.NHWC, dtype, x, w, dy)
+        gu.assert_close(gu.to_host(dwt), want, gu.TOL_F32_FILTER, "gconv bwd_filter earlier kernels " + name)
+
+
 def test_group_bwd_filter_is_deterministic():
     case = ("det", 4, 32, 32, 8, 28, 28, 3, 1, 1)
     for layout in LAYOUTS:
