@@ -167,7 +167,9 @@ int dwconv_tuning_reload(void);
  * channel, the K x K blocks of every input channel of its own group.  As for the depthwise layer,
  * the dense masked product is not what runs: the passes are direct stencils over the Cg = C/groups
  * input channels of a group, still bound by memory for small Cg; with 4 or 8 channels per group the
- * sum over a group's channels is a small dense contraction and, in NHWC, runs on the matrix cores.
+ * sum over a group's channels is a small dense contraction and runs on the matrix cores (NHWC: forward
+ * and backward-data; NCHW with 28x28 or 56x56 planes, and with 2 channels per group on 112x112 planes:
+ * all three passes).
  *
  * The C input and O output channels are split into `groups` runs of Cg = C/groups and Og = O/groups
  * consecutive channels; output channel o reads input channels (o/Og)*Cg .. (o/Og)*Cg + Cg - 1.
