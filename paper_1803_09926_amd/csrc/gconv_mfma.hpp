@@ -94,12 +94,13 @@ __device__ __forceinline__ void quad_mma1(v4f_t &d, const QuadW<bf16_t> &a, cons
 // The lane's filter entries, wq[oq][tap][iq]: output quad oq of the lane against input quad iq of that quad's group (when
 // the group's other quad lives in the neighbouring block, fp32 groups of 8: iq 0 = the lane's own quad, 1 = the
 // neighbour's).  MODE 0: forward, A[i][k] = w[tap][ci = k][o = i]; MODE 1: backward-data at stride 1, the filter
-// transposed inside the group and rotated, A[i][k] = w[8 - tap][ci = i][o = k]; MODE 2: transposed only.
+// transposed inside the group and rotated, A[i][k] = w[8 - tap][ci = i][o = k]; MODE 2: transposed only.  CG = 2: the
+// quad holds two groups.
 template <typename T, int CG, int MODE>
 __device__ __forceinline__ void load_group_filter(const T *__restrict__ w, int C, int cbase, int j,
-                                                  QuadW<T> (&wq)[LaneIn<T>::LQ][9][CG / 4])
+                                                  QuadW<T> (&wq)[LaneIn<T>::LQ][9][CG <= 4 ? 1 : CG / 4])
 {
-    constexpr int LQ = LaneIn<T>::LQ, NQ = CG / 4;
+    constexpr int LQ = LaneIn<T>::LQ, NQ = CG <= 4 ? 1 : CG / 4;
     constexpr bool SIB = NQ == 2 && LQ == 1;
 #pragma unroll
     for (int oq = 0; oq < LQ; ++oq) {
@@ -112,6 +113,15 @@ __device__ __forceinline__ void load_group_filter(const T *__restrict__ w, int C
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     size_t idx;
+                    if constexpr (CG == 2) {
+                        // a quad is two groups of 2: the entries that pair channels of different groups are zero (a
+                        // block-diagonal 4x4 tile)
+                        if (MODE == 0) idx = (size_t)(tap * 2 + k % 2) * C + c4 + j;
+                        else idx = (size_t)((MODE == 1 ? 8 - tap : tap) * 2 + j % 2) * C + c4 + k;
+                        const float v = ldf(w + idx);
+                        wq[oq][tap][iq].set(k, k / 2 == j / 2 ? v : 0.f);
+                        continue;
+                    }
                     if (MODE == 0) idx = (size_t)(tap * CG + rq * 4 + k) * C + c4 + j;
                     else idx = (size_t)((MODE == 1 ? 8 - tap : tap) * CG + qpos * 4 + j) * C + grp0 + rq * 4 + k;
                     wq[oq][tap][iq].set(k, ldf(w + idx));

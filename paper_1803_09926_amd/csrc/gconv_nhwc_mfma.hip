@@ -29,9 +29,9 @@ namespace dwc {
 template <typename T, int CG, bool FLIP, int PF>
 __global__ __launch_bounds__(256) void k_gconv_nhwc_mfma(GGeom g, const T *__restrict__ in, const T *__restrict__ w,
                                                          T *__restrict__ out, int TH, int nstrips, int ncq, int ncs, int NI,
-                                                         unsigned nwaves, unsigned nblocks, int nt)
+                                                         unsigned nwaves, unsigned nblocks, int nt, int CB)
 {
-    constexpr int LQ = LaneIn<T>::LQ, NQ = CG / 4, R = PF + 1;
+    constexpr int LQ = LaneIn<T>::LQ, NQ = CG <= 4 ? 1 : CG / 4, R = PF + 1;
     constexpr bool SIB = NQ == 2 && LQ == 1;                // the group's other quad lives in the neighbouring block
     const unsigned lb = xcd_remap(blockIdx.x, nblocks);
     // the wavefront's index, as a scalar: everything derived from it (strip, rows, images) then sits in scalar registers
@@ -42,9 +42,11 @@ __global__ __launch_bounds__(256) void k_gconv_nhwc_mfma(GGeom g, const T *__res
     const int cq = gw % ncq; gw /= ncq;
     const int strip = gw % nstrips; const int ngroup = gw / nstrips;
 
+    // CB: blocks that hold one pixel's channels.  16 when the tensor has at least a wavefront's worth of channels; with
+    // fewer, the remaining blocks take the next four pixel columns (the wavefront's accesses stay one contiguous range)
     const int lane = threadIdx.x & 63, blk = lane >> 2, j = lane & 3;
-    const int cbase = (cs * 16 + blk) * 4 * LQ;             // the lane's channels (read and written): LQ quads from here
-    const int col = cq * 4 + j;
+    const int cbase = (cs * 16 + blk % CB) * 4 * LQ;        // the lane's channels (read and written): LQ quads from here
+    const int col = (cq * (16 / CB) + blk / CB) * 4 + j;
     const int C = g.C;                                      // = g.O
 
     QuadW<T> wq[LQ][9][NQ];
@@ -127,9 +129,14 @@ __global__ __launch_bounds__(256) void k_gconv_nhwc_mfma(GGeom g, const T *__res
 bool gconv_nhwc_mfma_supported(const GGeom &g, int dtype)
 {
     if (const char *e = tune_env("DWCONV_TUNE_GMFMA")) { if (atoi(e) == 0) return false; }
-    if (!(g.K == 3 && g.s == 1 && g.p == 1 && g.Cg == g.Og && (g.Cg == 4 || g.Cg == 8))) return false;
-    // a wavefront takes 16 lanes' worth of channels at every pixel: 64 channels in fp32, 128 in bf16
-    if (g.C % (dtype == DT_F32 ? 64 : 128) != 0) return false;
+    if (!(g.K == 3 && g.s == 1 && g.p == 1 && g.Cg == g.Og && (g.Cg == 2 || g.Cg == 4 || g.Cg == 8))) return false;
+    // groups of 2 (a quad = two groups, block-diagonal filter tiles): bf16 only, where the row walk is bound by its
+    // arithmetic (112x112, batch 256: 230 us); in fp32 the row walk is the faster one
+    if (g.Cg == 2 && !(dtype == DT_BF16 || tune_env("DWCONV_TUNE_GMFMA2F32"))) return false;
+    // a wavefront takes 16 lanes' worth of channels at every pixel, 64 channels in fp32 and 128 in bf16, or, of a
+    // tensor with fewer channels (a power-of-two fraction of that), several groups of four pixel columns
+    const int wc = dtype == DT_F32 ? 64 : 128;
+    if (g.C % wc != 0 && !(wc % g.C == 0 && g.C % (wc / 16) == 0)) return false;
     return (long long)g.H * g.W * g.C * 4 <= (1ll << 31);              // an image through a buffer view: at most 2 GiB
 }
 
@@ -144,7 +151,9 @@ static hipError_t launch_m(const GGeom &g, const void *in, const void *w, void *
     if (nstrips < 1) nstrips = 1;
     const int TH = cdivm(g.H, nstrips);
     nstrips = cdivm(g.H, TH);
-    const int ncq = cdivm(g.W, 4), ncs = g.C / (64 * LaneIn<T>::LQ);
+    const int wc = 64 * LaneIn<T>::LQ;                      // channels of a full wavefront
+    const int CB = g.C >= wc ? 16 : g.C / (4 * LaneIn<T>::LQ);
+    const int ncq = cdivm(g.W, 4 * (16 / CB)), ncs = g.C >= wc ? g.C / wc : 1;
     // images per wavefront: the filter entries (9*CG registers) are loaded once per wavefront, so as few wavefronts as
     // still fill the chip about twice
     const long long per_image = (long long)nstrips * ncq * ncs;
@@ -157,7 +166,7 @@ static hipError_t launch_m(const GGeom &g, const void *in, const void *w, void *
     const unsigned nwaves = (unsigned)nw, nblocks = (unsigned)((nw + 3) / 4);
     const int nt = stream_stores("GROUP_NHWC_MFMA", (long long)g.N * g.H * g.W * g.C * sizeof(T), 0);
 #define GO(FL, PP) hipLaunchKernelGGL((k_gconv_nhwc_mfma<T, CG, FL, PP>), dim3(nblocks), dim3(256), 0, st, g, (const T *)in, \
-                                      (const T *)w, (T *)out, TH, nstrips, ncq, ncs, NI, nwaves, nblocks, nt)
+                                      (const T *)w, (T *)out, TH, nstrips, ncq, ncs, NI, nwaves, nblocks, nt, CB)
     int pf = 2;
     if (const char *e = tune_env("DWCONV_TUNE_GMPF")) pf = atoi(e);
     if (pf == 3) { if (flip) GO(true, 3); else GO(false, 3); }
@@ -170,8 +179,11 @@ static hipError_t launch_m(const GGeom &g, const void *in, const void *w, void *
 hipError_t gconv_nhwc_mfma_s1(const GGeom &g, int dtype, const void *in, const void *w, void *out, bool flip, hipStream_t st)
 {
     if (!gconv_nhwc_mfma_supported(g, dtype)) return hipErrorInvalidValue;
-    if (dtype == DT_F32) return g.Cg == 4 ? launch_m<float, 4>(g, in, w, out, flip, st) : launch_m<float, 8>(g, in, w, out, flip, st);
-    return g.Cg == 4 ? launch_m<bf16_t, 4>(g, in, w, out, flip, st) : launch_m<bf16_t, 8>(g, in, w, out, flip, st);
+    if (dtype == DT_F32)
+        return g.Cg == 2 ? launch_m<float, 2>(g, in, w, out, flip, st)
+                         : g.Cg == 4 ? launch_m<float, 4>(g, in, w, out, flip, st) : launch_m<float, 8>(g, in, w, out, flip, st);
+    return g.Cg == 2 ? launch_m<bf16_t, 2>(g, in, w, out, flip, st)
+                     : g.Cg == 4 ? launch_m<bf16_t, 4>(g, in, w, out, flip, st) : launch_m<bf16_t, 8>(g, in, w, out, flip, st);
 }
 
 }  // namespace dwc

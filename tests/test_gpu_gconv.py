@@ -56,6 +56,12 @@ CASES = [
     ("mm_cg8_c64_w13", 3, 64, 64, 8, 15, 13, 3, 1, 1),
     ("mm_cg8_c128_h33", 2, 128, 128, 16, 33, 6, 3, 1, 1),
     ("mm_cg4_h1", 2, 64, 64, 16, 1, 5, 3, 1, 1),
+    # fewer channels than a wavefront's worth (several groups of four columns per wavefront), and groups of 2 (bf16)
+    ("mm_cg4_c32_w37", 2, 32, 32, 8, 9, 37, 3, 1, 1),
+    ("mm_cg8_c8_w70", 1, 8, 8, 1, 5, 70, 3, 1, 1),
+    ("mm_cg2_c64_w30", 2, 64, 64, 32, 11, 30, 3, 1, 1),
+    ("mm_cg2_c128", 1, 128, 128, 64, 7, 9, 3, 1, 1),
+    ("mm_cg2_c16_w41", 3, 16, 16, 8, 6, 41, 3, 1, 1),
     ("mm_cg8_w1", 2, 64, 64, 8, 30, 1, 3, 1, 1),
     # NCHW rows of 7, 14 or 28 with 2, 4 or 8 channels per group: forward and backward-data stage whole groups in LDS
     # (last tile partly filled, planes that are not square, tiles of one group)
@@ -134,6 +140,7 @@ def test_group_nhwc_exchange_kernels_forced_tilings(dtype):
         for kn in knobs:
             if name == "x_cg8" and kn.get("DWCONV_TUNE_GXV") == "2":
                 continue
+            kn = dict(kn, DWCONV_TUNE_GMFMA="0")        # channel counts the matrix-core walk would take otherwise
             with dw.tuning_overrides(kn):
                 print("case", name, "knobs", kn, flush=True)
                 y, dx, dwt = run_gpu(case, wl.NHWC, dtype, x, w, dy)
@@ -146,7 +153,7 @@ def test_group_nhwc_exchange_kernels_forced_tilings(dtype):
     name, N, C, O, G, H, W, K, s, p = case
     x, w, dy = wl.make_group_inputs(N, C, O, G, H, W, K, s, p, wl.NHWC, dtype, seed=98)
     kw = dict(K=K, stride=s, pad=p, groups=G, O=O, layout=wl.NHWC, nthreads=8)
-    with dw.tuning_overrides({"DWCONV_TUNE_GXV": "2"}):
+    with dw.tuning_overrides({"DWCONV_TUNE_GXV": "2", "DWCONV_TUNE_GMFMA": "0"}):
         y, dx, dwt = run_gpu(case, wl.NHWC, dtype, x, w, dy)
     tol = gu.TOL_F32 if dtype == wl.F32 else gu.TOL_BF16
     gu.assert_close(gu.to_host(y), og.fwd(x, w, **kw), tol, "gconv fwd two channels per lane")
@@ -318,11 +325,14 @@ def test_group_nhwc_matrix_core_kernels_forced_tilings(dtype):
     """The matrix-core NHWC kernels walk several images per wavefront only on large batches; the tiling overrides force
     that path (ragged last image group) and short strips (ragged last strip) at sizes the oracle checks element by
     element."""
-    cases = [("mmx_cg4", 5, 128, 128, 32, 13, 10, 3, 1, 1), ("mmx_cg8", 7, 128, 128, 16, 11, 7, 3, 1, 1)]
+    cases = [("mmx_cg4", 5, 128, 128, 32, 13, 10, 3, 1, 1), ("mmx_cg8", 7, 128, 128, 16, 11, 7, 3, 1, 1),
+             ("mmx_cg2_c64", 5, 64, 64, 32, 13, 21, 3, 1, 1), ("mmx_cg4_c16", 7, 16, 16, 4, 11, 35, 3, 1, 1)]
     knobs = [{"DWCONV_TUNE_GMNI": "2", "DWCONV_TUNE_GMTH": "5"}, {"DWCONV_TUNE_GMNI": "3"}, {"DWCONV_TUNE_GMTH": "3"}]
+    knobs = [dict(kn, DWCONV_TUNE_GMFMA2F32="1") for kn in knobs]       # groups of 2 in fp32 too (bf16 by default)
     for case in cases:
         name, N, C, O, G, H, W, K, s, p = case
-        assert dw.gconv_variant_name(dw.group_desc(N, C, H, W, K, s, p, G, O, wl.NHWC, dtype), 0) == "group_nhwc_mfma_k3s1"
+        if C // G > 2 or dtype == wl.BF16:
+            assert dw.gconv_variant_name(dw.group_desc(N, C, H, W, K, s, p, G, O, wl.NHWC, dtype), 0) == "group_nhwc_mfma_k3s1"
         x, w, dy = wl.make_group_inputs(N, C, O, G, H, W, K, s, p, wl.NHWC, dtype, seed=97)
         kw = dict(K=K, stride=s, pad=p, groups=G, O=O, layout=wl.NHWC, nthreads=8)
         want = (og.fwd(x, w, **kw), og.bwd_data(dy, w, x_shape=x.shape, **kw))
