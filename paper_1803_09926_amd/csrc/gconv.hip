@@ -246,6 +246,10 @@ static GPlan gplan(const GGeom &g, int layout, int dtype, int pass)
         pl.variant = GV_NHWC_LDS_MFMA_BWD_FILTER;
         pl.name = "group_nhwc_lds_mfma_bwd_filter_k3s1";
         pl.parts = gconv_nchws_mfma_bwd_filter_parts(g, dtype);
+    } else if (layout == LAYOUT_NHWC && pass == 2 && gconv_nhwc_tr_bwd_filter_supported(g, dtype)) {
+        pl.variant = GV_NHWC_TR_BWD_FILTER;
+        pl.name = "group_nhwc_mfma_bwd_filter_k3s1";
+        pl.parts = gconv_nhwc_tr_bwd_filter_parts(g, dtype);
     } else if (layout == LAYOUT_NHWC && pass < 2 && gconv_nhwc_mfma_s2_supported(g, dtype, pass)) {
         pl.variant = GV_NHWC_MFMA_S2;
         pl.name = pass == 0 ? "group_nhwc_mfma_fwd_k3s2" : "group_nhwc_mfma_bwd_data_k3s2";
@@ -397,6 +401,7 @@ int gconv_bwd_filter(const dwconv_group_desc *desc, const void *x, const void *d
     hipError_t e;
     if (pl.variant == GV_NCHWS_K3S1) e = nchws_group_bwd_filter(as_geom(g), g.Cg, desc->dtype, x, dy, (float *)workspace, pl.a, pl.c, (hipStream_t)stream);
     else if (pl.variant == GV_NCHWS_MFMA_BWD_FILTER) e = gconv_nchws_mfma_bwd_filter(g, desc->dtype, false, x, dy, (float *)workspace, pl.parts, (hipStream_t)stream);
+    else if (pl.variant == GV_NHWC_TR_BWD_FILTER) e = gconv_nhwc_tr_bwd_filter(g, desc->dtype, x, dy, (float *)workspace, pl.parts, (hipStream_t)stream);
     else if (pl.variant == GV_NHWC_LDS_MFMA_BWD_FILTER) e = gconv_nchws_mfma_bwd_filter(g, desc->dtype, true, x, dy, (float *)workspace, pl.parts, (hipStream_t)stream);
     else if (pl.variant == GV_NHWC_BWD_FILTER_S2) e = gconv_nhwc_bwd_filter_s2(g, desc->dtype, x, dy, (float *)workspace, pl.parts, (hipStream_t)stream);
     else if (pl.variant == GV_NCHW_K3S1) e = gconv_nchw_bwd_filter(g, desc->dtype, x, dy, (float *)workspace, pl.parts, (hipStream_t)stream);

@@ -12,7 +12,7 @@ struct GGeom {
     int Ho, Wo;
 };
 
-enum GVariant { GV_GENERIC = 0, GV_NCHW_K3S1, GV_NHWC_K3S1, GV_NCHWS_K3S1, GV_NHWC_MFMA_S2, GV_NHWC_BWD_FILTER_S2, GV_NCHWS_MFMA_BWD_FILTER, GV_NCHWS_MFMA_FWD, GV_NHWC_LDS_MFMA_BWD_FILTER };
+enum GVariant { GV_GENERIC = 0, GV_NCHW_K3S1, GV_NHWC_K3S1, GV_NCHWS_K3S1, GV_NHWC_MFMA_S2, GV_NHWC_BWD_FILTER_S2, GV_NCHWS_MFMA_BWD_FILTER, GV_NCHWS_MFMA_FWD, GV_NHWC_LDS_MFMA_BWD_FILTER, GV_NHWC_TR_BWD_FILTER };
 
 struct GPlan {
     int variant;
@@ -67,6 +67,12 @@ hipError_t gconv_nhwc_xchg_bwd_filter(const GGeom &g, int dtype, const void *x, 
 // (gconv_nhwc_mfma.hip); gconv_nhwc_s1 forwards to it where it applies
 bool gconv_nhwc_mfma_supported(const GGeom &g, int dtype);
 hipError_t gconv_nhwc_mfma_s1(const GGeom &g, int dtype, const void *in, const void *w, void *out, bool flip, hipStream_t st);
+
+// ---- NHWC filter gradient on the matrix cores, 4x4 tiles transposed in registers: 3x3 stride 1 pad 1, groups of 4 or 8
+// on both sides, channels a multiple of 64 (bf16: 128) (gconv_nhwc_tr.hip)
+bool gconv_nhwc_tr_bwd_filter_supported(const GGeom &g, int dtype);
+int gconv_nhwc_tr_bwd_filter_parts(const GGeom &g, int dtype);
+hipError_t gconv_nhwc_tr_bwd_filter(const GGeom &g, int dtype, const void *x, const void *dy, float *ws, int parts, hipStream_t st);
 
 // ---- NHWC 3x3 stride 2 pad 1 on the matrix cores, same group sizes and channel counts: forward (pass 0) and
 // backward-data (pass 1, even H and W) (gconv_nhwc_mfma_s2.hip)

@@ -71,6 +71,7 @@ VARIANT_KERNELS = {
     "fwd:group_nchw_smallplane_mfma_k3s1": [r"k_gconv_nchws_mfma_fwd<[\w ]+, \d+, \d+, \d+, false>"],
     "bwd_data:group_nchw_smallplane_mfma_k3s1_flip": [r"k_gconv_nchws_mfma_fwd<[\w ]+, \d+, \d+, \d+, true>"],
     "bwd_filter:group_nchw_smallplane_mfma_bwd_filter_k3s1": [r"k_gconv_nchws_mfma_bwd_filter<[\w ]+, \d+, \d+, \d+, false>"],
+    "bwd_filter:group_nhwc_mfma_bwd_filter_k3s1": [r"k_gconv_nhwc_tr_bwd_filter<"],
     "bwd_filter:group_nhwc_lds_mfma_bwd_filter_k3s1": [r"k_gconv_nchws_mfma_bwd_filter<[\w ]+, \d+, \d+, \d+, true>"],
     "bwd_filter:group_nchw_smallplane_bwd_filter_k3s1": [r"k_nchws_bwd_filter<[\w ]+, 3, 1, \d+, [248]>"],
     # k_gconv_nhwc_xchg<T, CG, V, PF, FLIP>: the lane-exchange walk (groups of 4 or 8 channels)

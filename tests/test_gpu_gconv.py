@@ -247,6 +247,29 @@ def test_group_nhwc_lds_matrix_core_filter_gradient_forced_tilings(dtype):
         gu.assert_close(gu.to_host(dwt), want, gu.TOL_F32_FILTER, "gconv bwd_filter earlier kernels " + name)
 
 
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+def test_group_nhwc_transposing_matrix_core_filter_gradient_forced_tilings(dtype):
+    """NHWC filter gradient with 4 or 8 channels per group and whole wavefronts of channels: 4x4 tiles transposed in
+    registers, sums on the matrix cores.  One image per wavefront and several, a ragged last image group, maps narrower
+    than a block's 16 columns and wider, a single row, a single column."""
+    cases = [("tr_cg4", 5, 128, 128, 32, 13, 21, 3, 1, 1), ("tr_cg8", 7, 128, 128, 16, 11, 7, 3, 1, 1), ("tr_cg8_c256", 3, 256, 256, 32, 6, 35, 3, 1, 1),
+             ("tr_cg4_h1", 2, 128, 128, 32, 1, 9, 3, 1, 1), ("tr_cg8_w1", 2, 128, 128, 16, 9, 1, 3, 1, 1)]
+    knobs = [{}, {"DWCONV_TUNE_GTRNI": "2"}, {"DWCONV_TUNE_GTRNI": "3", "DWCONV_TUNE_GTRBLOCKS": "7"}, {"DWCONV_TUNE_GTRBLOCKS": "100000"}]
+    for case in cases:
+        name, N, C, O, G, H, W, K, s, p = case
+        x, w, dy = wl.make_group_inputs(N, C, O, G, H, W, K, s, p, wl.NHWC, dtype, seed=57)
+        kw = dict(K=K, stride=s, pad=p, groups=G, O=O, layout=wl.NHWC, nthreads=8)
+        want = og.bwd_filter(x, dy, **kw)
+        d = dw.group_desc(N, C, H, W, K, s, p, G, O, wl.NHWC, dtype)
+        for kn in knobs:
+            kn = dict(kn, DWCONV_TUNE_GTRALL="1")
+            with dw.tuning_overrides(kn):
+                print("case", name, "knobs", kn, flush=True)
+                assert dw.gconv_variant_name(d, 2) == "group_nhwc_mfma_bwd_filter_k3s1"
+                _, _, dwt = run_gpu(case, wl.NHWC, dtype, x, w, dy)
+            gu.assert_close(gu.to_host(dwt), want, gu.TOL_F32_FILTER, "gconv bwd_filter %s %s" % (name, kn))
+
+
 def test_group_bwd_filter_is_deterministic():
     case = ("det", 4, 32, 32, 8, 28, 28, 3, 1, 1)
     for layout in LAYOUTS:
