@@ -1,5 +1,6 @@
 // Group convolution, NCHW, 3x3 stride 1 pad 1: filter gradient (Eq. 4 with the sum over a group's channel pairs) on the
-// matrix cores, for 4 or 8 channels per group on both sides and 28x28 or 56x56 planes.
+// matrix cores, for 4 or 8 channels per group on both sides and 28x28 or 56x56 planes, and for 2 channels per group
+// on 112x112 planes; the same kernel can be fed from NHWC tensors (template switch).
 //
 // Per pixel a group of 8 needs 8*8*9 multiply-adds for 16 loaded values: on the vector ALU this pass is bound by
 // arithmetic (about a third of the memory rate).  The sum over pixels is a matrix product dW[o][b][tap] =
@@ -9,20 +10,29 @@
 // its plane).  A = the dy values of the lane's output channel, B = the x values of the lane's input channel at the
 // tap's offset, D[i][j] (register i of lane j) = the sum for (output channel i, input channel j) of the quad pair.
 //
-// A thread block works on eight consecutive channels (one group of 8, or two groups of 4) of one image at a time
-// (56x56: of one 14-row strip of an image): the eight x planes and eight dy planes come in as 16-byte loads (28x28:
-// one flat range, the planes being contiguous in NCHW), two fills ahead in registers, and are laid out in LDS with a
-// gap of zeros after every row and the rows above and below in place (zeros at the plane's edge), so every tap's
-// operand is an unconditional LDS read at a constant offset from the position (the padding supplies the zeros of
-// Eq. 4's border).  A wavefront's 16 positions are two streams of eight: the seven 4-pixel vectors of a
-// row and the gap after it (dy is zero there); 56x56: one stream of 16, a row's 14 vectors and the gap.  A stream walks down its rows and keeps the three x rows of the taps
-// in registers: a step reads one new x row and one dy row from LDS; the one pixel left and right of a position's
-// four is the neighbour lane's vector, fetched by a lane permute instead of a second LDS read (single-word reads at
-// a stride of four words use a quarter of the banks).  Groups of 8: the four wavefronts take the four (input quad,
-// output quad) pairs and the whole plane (streams of 14 rows), 9 accumulators each.  Groups of 4: two wavefronts
-// per group, the upper and the lower half of the plane (two partial sums per block).  At the end a
-// wavefront adds its 16 blocks with a shuffle butterfly and writes its entries of the block's partial; the shared
-// second stage adds the partials in a fixed order.
+// A thread block works on eight consecutive channels (one group of 8, two groups of 4, four groups of 2) of one
+// "fill" at a time: an image (28x28) or a strip of rows of an image (56x56: 14 rows; 112x112: 14 rows in bf16, 7 in
+// fp32).  The eight x planes and eight dy planes come in as 16-byte loads (28x28: one flat range, the planes being
+// contiguous in NCHW), one or two fills ahead in registers, and are laid out in LDS with a gap of zeros after every
+// row and the rows above and below in place (zeros at the plane's edge), so every tap's operand is an unconditional
+// LDS read at a constant offset from the position (the padding supplies the zeros of Eq. 4's border).
+//
+// A wavefront's 16 positions (4 pixels each) are streams of rows: 28-wide, two streams of eight (the seven vectors of
+// a row and the gap after it, where dy is zero); 56-wide, one stream of 16; 112-wide, half a row (the row's two halves
+// go to two wavefronts).  A stream walks down its rows and keeps the three x rows of the taps in registers: a step
+// reads one new x row and one dy row from LDS; the one pixel left and right of a position's four is the neighbour
+// lane's vector, fetched by a lane permute instead of a second LDS read (single-word reads at a stride of four words
+// use a quarter of the banks); on 112-wide rows the wavefront's first and last position read theirs from LDS.
+// Groups of 8: the four wavefronts take the four (input quad, output quad) pairs and all rows of the fill, 9
+// accumulators each.  Groups of 4: two wavefronts per group, the upper and the lower half of the rows (two partial
+// sums per block).  Groups of 2: a quad is two groups, two wavefronts per quad (left and right half of the rows), and
+// only the sums of channel pairs of the same group are written.  At the end a wavefront adds its 16 blocks with a
+// shuffle butterfly and writes its entries of the block's partial; the shared second stage adds the partials in a
+// fixed order.
+//
+// NHWC feed: the block's eight channels of a pixel are 16 contiguous bytes (fp32: 32); they are loaded as such and
+// scattered to their planes in LDS one element each; everything after that is unchanged, and the partial sums are
+// written in the NHWC filter's layout.
 #include "gconv_mfma.hpp"
 
 namespace dwc {
