@@ -139,15 +139,21 @@ __device__ __forceinline__ void load_group_filter(const T *__restrict__ w, int C
 // backward-data only): strips of 14 rows in bf16, 7 in fp32.  A row is followed
 // by a gap of zeros up to the pitch WP = 16 positions / streams: two rows of 8 positions or one row of 16.
 template <int W, int H, int ESZ = 4> struct PlaneFill {
-    static_assert((W == 28 && H == 28) || (W == 56 && H == 56) || (W == 112 && H == 112), "28x28 planes whole, larger planes in strips");
-    static constexpr bool STRIP = W != 28;
-    static constexpr int RS = W == 28 ? H : (W == 56 || ESZ == 2) ? 14 : 7;      // dy rows of a fill
-    static constexpr int NSTRIP = H / RS;
-    static constexpr int WP = W == 28 ? 32 : W == 56 ? 64 : 128;     // row pitch in elements
+    static_assert((W == 14 && H == 14) || (W == 28 && H == 28) || (W == 56 && H == 56) || (W == 112 && H == 112),
+                  "14x14 planes four at a time, 28x28 planes whole, larger planes in strips");
+    // 14x14: a fill is four images laid out as a 2 x 2 mosaic of the 28-wide geometry, each row [14 | 2 zeros | 14 | 2
+    // zeros] and each column of sub-planes [zero row | 14 rows | zero row] twice: 28 "virtual" rows
+    static constexpr bool MOSAIC = W == 14;
+    static constexpr bool STRIP = W > 28;
+    static constexpr int RS = W <= 28 ? 28 : (W == 56 || ESZ == 2) ? 14 : 7;     // dy rows of a fill
+    static constexpr int NSTRIP = MOSAIC ? 1 : H / RS;
+    static constexpr int WP = W <= 28 ? 32 : W == 56 ? 64 : 128;     // row pitch in elements
     static constexpr int SPW = 64 / WP;                 // streams (rows walked side by side) of a wavefront; 0: a row spans two
-    static constexpr int VPR = W / 4;                   // four-pixel vectors of a row
+    static constexpr int VPR = MOSAIC ? 7 : W / 4;      // four-pixel vectors of a row (mosaic: of a virtual row's 28 pixels)
     static constexpr int PADP = 16;                     // planes staggered over the LDS banks
-    static constexpr int PPX = (RS + 2) * WP + PADP;    // x plane pitch: row r0 - 1 first
+    static constexpr int PPX = (RS + (MOSAIC ? 4 : 2)) * WP + PADP;    // x plane pitch: row r0 - 1 first
+    // LDS row of virtual row vr of the x planes
+    static constexpr __host__ __device__ int xrow(int vr) { return MOSAIC ? (vr / 14) * 16 + 1 + vr % 14 : vr + 1; }
     static constexpr int PPD = RS * WP + PADP;
     static constexpr int XROWS = STRIP ? RS + 2 : RS;   // x rows of a plane that are loaded
     static constexpr int AREA_X = 8 * PPX, AREA_D = 8 * PPD;

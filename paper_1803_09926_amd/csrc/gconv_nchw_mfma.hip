@@ -49,10 +49,11 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_bwd_filter(GGeom g, co
     constexpr int DROW = WIDE ? W : L::WP, PPD = WIDE ? L::RS * W : L::PPD, AREA_D = 8 * PPD;
     constexpr int LEAD = 16 / (int)sizeof(T);       // zeros before the first plane: the pixel left of its first one
     // fills ahead in registers; fp32 strips and wide rows: one (two would leave registers for one wavefront per SIMD only)
-    constexpr int DEPTH = (L::STRIP && (sizeof(T) == 4 || WIDE)) ? 1 : 2;
+    constexpr int DEPTH = ((L::STRIP && (sizeof(T) == 4 || WIDE)) || (L::MOSAIC && sizeof(T) == 4)) ? 1 : 2;
     constexpr bool F32 = sizeof(T) == 4;
     constexpr int CPV = F32 ? 1 : 2;                // four-pixel vectors of a 16-byte chunk
     constexpr int HPP = F32 ? 2 : 1;                // NHWC: 16-byte chunks of a pixel's eight channels
+    constexpr int EPC = 4 * CPV;                    // elements of a chunk
     constexpr int XCH = 8 * L::XROWS * L::VPR / CPV, DCH = 8 * L::RS * L::VPR / CPV;     // chunks of a fill
     constexpr int XPASS = (XCH + 255) / 256, DPASS = (DCH + 255) / 256;
     __shared__ __align__(16) T lds_all[LEAD + L::AREA_X + AREA_D];    // x planes, then dy planes
@@ -73,13 +74,28 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_bwd_filter(GGeom g, co
     // blocks past their last fill repeat a valid address and drop the result; a row outside the plane reads the
     // nearest row inside and is zeroed on its way to LDS): the number of loads in flight is then the same on every
     // path, and the wait before a fill's LDS writes covers that fill's loads only.
-    struct Stage { u4raw_t x[XPASS], d[DPASS]; uint32_t xok; };
+    struct Stage { u4raw_t x[XPASS], d[DPASS]; uint32_t xok; };      // xok: per pass, the x chunk is inside the plane (mosaic: the dy chunk's image exists)
     auto gload = [&](Stage &s, int f) {
         const int ff = f < nfills ? f : part;
         const int n = ff / L::NSTRIP, r0 = (ff % L::NSTRIP) * L::RS;
         const T *xs = x + ((size_t)n * g.C + (size_t)cb * 8) * (H * W);
         const T *ds = dy + ((size_t)n * g.O + (size_t)cb * 8) * (H * W);
         s.xok = 0xffffffffu;
+        if constexpr (L::MOSAIC) {
+            // four images per fill, each image's eight planes one flat range; past the end of the batch the last image is
+            // read again and its dy dropped
+            static_assert(!NHWC && XCH == DCH, "mosaic fills are NCHW, x and dy of one shape");
+            constexpr int CPI = XCH / 4;
+#pragma unroll
+            for (int p = 0; p < XPASS; ++p) {
+                const int q = min(p * 256 + tid, XCH - 1), ni = ff * 4 + q / CPI;
+                if (ni >= g.N) s.xok &= ~(1u << p);
+                const size_t off = ((size_t)min(ni, g.N - 1) * g.C + (size_t)cb * 8) * (H * W) + (size_t)(q % CPI) * EPC;
+                s.x[p] = *reinterpret_cast<const u4raw_t *>(x + off);
+                s.d[p] = *reinterpret_cast<const u4raw_t *>(dy + off);
+            }
+            return;
+        }
         if constexpr (NHWC) {
             // a chunk is one pixel's eight channels (fp32: four of them): 16 bytes every C elements
 #pragma unroll
@@ -140,7 +156,34 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_bwd_filter(GGeom g, co
             dst[4 * pitch] = (T)v.z; dst[5 * pitch] = (T)(v.z >> 16); dst[6 * pitch] = (T)v.w; dst[7 * pitch] = (T)(v.w >> 16);
         }
     };
+    // mosaic: rows of 14 are not whole chunks, so element by element: plane, row and column within its image, the image's
+    // place in the mosaic (x: one zero row above and below each sub-plane; dy: the 28 virtual rows)
+    auto mosaic_put = [&](int q, u4raw_t vx, u4raw_t vd) {
+        constexpr int CPI = XCH / 4;
+        const int a4 = q / CPI, e0 = (q % CPI) * EPC;
+        const uint32_t wx[4] = {vx.x, vx.y, vx.z, vx.w}, wd[4] = {vd.x, vd.y, vd.z, vd.w};
+#pragma unroll
+        for (int k = 0; k < EPC; ++k) {
+            const int e = e0 + k, plane = e / (H * W), rem = e % (H * W), r = rem / W, c = (a4 & 1) * 16 + rem % W;
+            T *dx_ = lds + plane * L::PPX + ((a4 >> 1) * 16 + 1 + r) * L::WP + c;
+            T *dd_ = lds + L::AREA_X + plane * PPD + ((a4 >> 1) * 14 + r) * DROW + c;
+            if constexpr (F32) { *dx_ = __uint_as_float(wx[k]); *dd_ = __uint_as_float(wd[k]); }
+            else { *dx_ = (T)(wx[k >> 1] >> ((k & 1) * 16)); *dd_ = (T)(wd[k >> 1] >> ((k & 1) * 16)); }
+        }
+    };
     auto lstore = [&](const Stage &s) {
+        if constexpr (L::MOSAIC) {
+#pragma unroll
+            for (int p = 0; p < XPASS; ++p) {
+                const int q = p * 256 + tid;
+                if ((p + 1) * 256 <= XCH || q < XCH) {
+                    const bool ok = (s.xok >> p) & 1u;
+                    const u4raw_t d = s.d[p];
+                    mosaic_put(q, s.x[p], u4raw_t{ok ? d.x : 0u, ok ? d.y : 0u, ok ? d.z : 0u, ok ? d.w : 0u});
+                }
+            }
+            return;
+        }
         if constexpr (NHWC) {
 #pragma unroll
             for (int p = 0; p < XPASS; ++p) {
@@ -189,7 +232,7 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_bwd_filter(GGeom g, co
     const int slot = lane >> 2;
     const int pos = WIDE ? half * 16 + slot : slot % (L::WP / 4);                 // the position within its row
     const int row0 = WIDE ? 0 : (CG == 8 ? 0 : half * RPW) + (slot / (L::WP / 4)) * RPS;
-    const T *xpl = lds + (xq * 4 + (lane & 3)) * L::PPX + (1 + row0) * L::WP + pos * 4;
+    const T *xpl = lds + (xq * 4 + (lane & 3)) * L::PPX + L::xrow(row0) * L::WP + pos * 4;
     const bool dvalid = !WIDE || pos < L::VPR;         // packed dy rows have no gap: those positions read a real vector and drop it
     const T *dpl = lds + L::AREA_X + (dq * 4 + (lane & 3)) * PPD + row0 * DROW + (dvalid ? pos : 0) * 4;
     // the neighbour positions' vectors come from the lanes four below and four above; position 0 has no left neighbour
@@ -321,6 +364,7 @@ bool gconv_nchws_mfma_bwd_filter_supported(const GGeom &g, int dtype, bool nhwc)
     // 159 -> 102 us; groups of 4 and fp32 measured 15 to 40 % slower than the earlier kernels and stay there)
     if (nhwc && (tune_env("DWCONV_TUNE_GNOSMMNHWC") || !((dtype == DT_BF16 && g.Cg == 8) || tune_env("DWCONV_TUNE_GSMMNHWCALL")))) return false;
     if (g.H == 112 && g.W == 112) return !nhwc && g.Cg == 2 && (dtype == DT_BF16 || tune_env("DWCONV_TUNE_GSMM112F32")) && !tune_env("DWCONV_TUNE_GNOSMM112");
+    if (g.H == 14 && g.W == 14) return !nhwc && (g.Cg == 4 || g.Cg == 8);
     return ((g.H == 28 && g.W == 28) || (g.H == 56 && g.W == 56)) && (g.Cg == 4 || g.Cg == 8);
 }
 
@@ -328,7 +372,7 @@ bool gconv_nchws_mfma_bwd_filter_supported(const GGeom &g, int dtype, bool nhwc)
 // blocks in the launch (two per compute unit, all resident at once; 1024 measured 15 % slower: the first loads and the
 // final reduction of a block are not overlapped with anything of its own), every block the same number of fills where
 // the batch allows it
-static int nchws_mfma_fills(const GGeom &g, int dtype) { return g.N * (g.W == 56 ? 4 : g.W == 112 ? (dtype == DT_F32 ? 16 : 8) : 1); }
+static int nchws_mfma_fills(const GGeom &g, int dtype) { return g.W == 14 ? (g.N + 3) / 4 : g.N * (g.W == 56 ? 4 : g.W == 112 ? (dtype == DT_F32 ? 16 : 8) : 1); }
 static int nchws_mfma_blocks_per_octet(const GGeom &g, int dtype)
 {
     int target = 512;
@@ -353,7 +397,7 @@ hipError_t gconv_nchws_mfma_bwd_filter(const GGeom &g, int dtype, bool nhwc, con
 #define GOL(T, CGG, WW, NH) hipLaunchKernelGGL((k_gconv_nchws_mfma_bwd_filter<T, CGG, WW, WW, NH>), dim3(nblocks), dim3(256), 0, st, g, (const T *)x, \
                                                (const T *)dy, ws, bpo, nchws_mfma_fills(g, dtype), nblocks, J)
 #define GOW(T, CGG, WW) do { if (nhwc) GOL(T, CGG, WW, true); else GOL(T, CGG, WW, false); } while (0)
-#define GO(T, CGG) do { if (g.W == 28) GOW(T, CGG, 28); else GOW(T, CGG, 56); } while (0)
+#define GO(T, CGG) do { if (g.W == 14) GOL(T, CGG, 14, false); else if (g.W == 28) GOW(T, CGG, 28); else GOW(T, CGG, 56); } while (0)
     if (g.W == 112) { if (dtype == DT_F32) GOL(float, 2, 112, false); else GOL(bf16_t, 2, 112, false); }
     else if (dtype == DT_F32) { if (g.Cg == 8) GO(float, 8); else GO(float, 4); }
     else                      { if (g.Cg == 8) GO(bf16_t, 8); else GO(bf16_t, 4); }

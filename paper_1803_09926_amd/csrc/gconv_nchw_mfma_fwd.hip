@@ -1,5 +1,5 @@
 // Group convolution, NCHW, 3x3 stride 1 pad 1: forward (Eq. 2 with the sum over a group's input channels) and
-// backward-data (Eq. 3) on the matrix cores, for 4 or 8 channels per group on both sides and 28x28 or 56x56 planes, and
+// backward-data (Eq. 3) on the matrix cores, for 4 or 8 channels per group on both sides and 14x14, 28x28 or 56x56 planes, and
 // for 2 channels per group on 112x112 planes.
 //
 // y[o][p] = sum over (b, tap) of w[o][b][tap] * x[b][p + tap] is a matrix product with the output channels as rows and
@@ -32,7 +32,8 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_fwd(GGeom g, const T *
     constexpr int CPV = F32 ? 1 : 2;                // four-pixel vectors of a 16-byte chunk
     constexpr int XCH = 8 * L::XROWS * L::VPR / CPV, YCH = 8 * L::RS * L::VPR / CPV;     // chunks of a fill
     constexpr int XPASS = (XCH + 255) / 256, YPASS = (YCH + 255) / 256;
-    constexpr int AREA_Y = 8 * L::RS * W;           // output planes of the fill, rows packed
+    constexpr int AREA_Y = L::MOSAIC ? 4 * 8 * H * W : 8 * L::RS * W;       // output planes of the fill, rows packed (mosaic: image after image)
+    constexpr int EPC = 4 * CPV, CPI = XCH / 4;    // elements of a chunk; mosaic: chunks of one image's eight planes
     constexpr int LEAD = 16 / (int)sizeof(T);       // zeros before the first plane: the pixel left of its first one
     __shared__ __align__(16) T lds_all[LEAD + L::AREA_X + AREA_Y];
     T *lds = lds_all + LEAD;
@@ -59,7 +60,12 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_fwd(GGeom g, const T *
 #pragma unroll
         for (int p = 0; p < XPASS; ++p) {
             const int q = min(p * 256 + tid, XCH - 1);
-            if constexpr (L::STRIP) {
+            if constexpr (L::MOSAIC) {
+                // four images per fill, each image's eight planes one flat range (a batch that is not a multiple of four
+                // repeats its last image; those outputs are not stored)
+                const int ni = min(ff * 4 + q / CPI, g.N - 1);
+                s.x[p] = *reinterpret_cast<const u4raw_t *>(in + ((size_t)ni * g.C + (size_t)cb * 8) * (H * W) + (size_t)(q % CPI) * EPC);
+            } else if constexpr (L::STRIP) {
                 const Where wq = where(q * CPV, L::XROWS);
                 const int rg = r0 - 1 + wq.row;
                 if (rg < 0 || rg >= H) s.xok &= ~(1u << p);
@@ -77,7 +83,19 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_fwd(GGeom g, const T *
                 const bool ok = (s.xok >> p) & 1u;
                 const u4raw_t v = {ok ? s.x[p].x : 0u, ok ? s.x[p].y : 0u, ok ? s.x[p].z : 0u, ok ? s.x[p].w : 0u};
                 constexpr int RSH = L::STRIP ? 0 : 1;
-                if constexpr (F32) {
+                if constexpr (L::MOSAIC) {
+                    // rows of 14 are not whole chunks: element by element (plane, row, column of its image; the image's
+                    // place in the mosaic)
+                    const int a4 = q / CPI, e0 = (q % CPI) * EPC;
+                    const uint32_t wd[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int k = 0; k < EPC; ++k) {
+                        const int e = e0 + k, plane = e / (H * W), rem = e % (H * W);
+                        T *dst = lds + plane * L::PPX + ((a4 >> 1) * 16 + 1 + rem / W) * L::WP + (a4 & 1) * 16 + rem % W;
+                        if constexpr (F32) *dst = __uint_as_float(wd[k]);
+                        else *dst = (T)(wd[k >> 1] >> ((k & 1) * 16));
+                    }
+                } else if constexpr (F32) {
                     const Where wq = where(q, L::XROWS);
                     *reinterpret_cast<u4raw_t *>(lds + wq.plane * L::PPX + (wq.row + RSH) * L::WP + wq.cv * 4) = v;
                 } else {
@@ -97,7 +115,10 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_fwd(GGeom g, const T *
             const int q = p * 256 + tid;
             if ((p + 1) * 256 <= YCH || q < YCH) {
                 const u4raw_t v = *reinterpret_cast<const u4raw_t *>(ylds + (size_t)q * (4 * CPV));
-                if constexpr (L::STRIP) {
+                if constexpr (L::MOSAIC) {
+                    const int ni = f * 4 + q / CPI;
+                    if (ni < g.N) *reinterpret_cast<u4raw_t *>(out + ((size_t)ni * g.C + (size_t)cb * 8) * (H * W) + (size_t)(q % CPI) * EPC) = v;
+                } else if constexpr (L::STRIP) {
                     const Where wq = where(q * CPV, L::RS);
                     *reinterpret_cast<u4raw_t *>(ys + (size_t)wq.plane * (H * W) + (r0 + wq.row) * W + wq.cv * 4) = v;
                 } else {
@@ -117,7 +138,7 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_fwd(GGeom g, const T *
     const int oq = wv & 1, half = wv >> 1;            // oq: the output quad of the octet
     const int col = WIDE ? half * 64 + lane : lane % LPS;
     const int row0 = WIDE ? 0 : half * (L::RS / 2) + (lane / LPS) * RPS;         // the stream's first output row within the fill
-    const bool colok = col < W;
+    const bool colok = L::MOSAIC ? (col & 15) < W : col < W;
     // Neighbour pixels.  Narrow rows: from the lanes one below and one above by a lane permute; lane 0 has none to its left
     // and starts a row (zero), every other stream start has the previous stream's gap there (zero), and a row's last pixel
     // has its own gap.  Wide rows: read from LDS like the pixel itself (the element before a row is the previous row's gap).
@@ -128,8 +149,11 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_fwd(GGeom g, const T *
     // zero (a block-diagonal 4x4 filter tile).
     constexpr int CI = CG == 8 ? 8 : 4;
     const int cin0 = CG == 8 ? 0 : oq * 4;            // first input plane within the octet
-    const T *xpl = lds + cin0 * L::PPX + (1 + row0) * L::WP + col;
-    T *ypl = ylds + (oq * 4) * (L::RS * W) + row0 * W + col;
+    const T *xpl = lds + cin0 * L::PPX + L::xrow(row0) * L::WP + col;
+    // output planes in LDS: plane pitch YPP, row pitch W (mosaic: the lane's image first)
+    constexpr int YPP = L::MOSAIC ? H * W : L::RS * W;
+    T *ypl = L::MOSAIC ? ylds + ((row0 / 14) * 2 + (col >> 4)) * (8 * H * W) + (oq * 4) * YPP + (row0 % 14) * W + (col & 15)
+                       : ylds + (oq * 4) * YPP + row0 * W + col;
 
     // The lane's filter entries: output channel i = lane & 3 of the quad, every input plane of the quad, every tap.
     // Forward: w[o][b][tap].  Backward-data: the output of this pass is x's channel, the input dy's: w[b][o][8 - tap].
@@ -217,8 +241,8 @@ __global__ __launch_bounds__(256) void k_gconv_nchws_mfma_fwd(GGeom g, const T *
             if (k2 && colok) {                              // output row t-1 is complete
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    if constexpr (F32) ypl[i * (L::RS * W) + (t - 1) * W] = a2[i];
-                    else ypl[i * (L::RS * W) + (t - 1) * W] = f32_to_bf16(a2[i]);
+                    if constexpr (F32) ypl[i * YPP + (t - 1) * W] = a2[i];
+                    else ypl[i * YPP + (t - 1) * W] = f32_to_bf16(a2[i]);
                 }
             }
         }
@@ -251,7 +275,7 @@ bool gconv_nchws_mfma_fwd_supported(const GGeom &g)
     if (tune_env("DWCONV_TUNE_GNOSMMF")) return false;
     if (!(g.K == 3 && g.s == 1 && g.p == 1 && g.Cg == g.Og && g.C % 8 == 0)) return false;
     if (g.H == 112 && g.W == 112) return g.Cg == 2 && !tune_env("DWCONV_TUNE_GNOSMMF112");
-    return ((g.H == 28 && g.W == 28) || (g.H == 56 && g.W == 56)) && (g.Cg == 4 || g.Cg == 8);
+    return ((g.H == 14 && g.W == 14) || (g.H == 28 && g.W == 28) || (g.H == 56 && g.W == 56)) && (g.Cg == 4 || g.Cg == 8);
 }
 
 hipError_t gconv_nchws_mfma_fwd(const GGeom &g, int dtype, const void *in, const void *w, void *out, bool flip, hipStream_t st)
@@ -260,7 +284,7 @@ hipError_t gconv_nchws_mfma_fwd(const GGeom &g, int dtype, const void *in, const
     // fills (images, or 14-row strips of 56x56 images) dealt to about 512 blocks, all resident at once
     int target = 512;
     if (const char *e = tune_env("DWCONV_TUNE_GSMFBLOCKS")) if (atoi(e) > 0) target = atoi(e);
-    const int octets = g.C / 8, nf = g.N * (g.W == 56 ? 4 : g.W == 112 ? (dtype == DT_F32 ? 16 : 8) : 1);
+    const int octets = g.C / 8, nf = g.W == 14 ? (g.N + 3) / 4 : g.N * (g.W == 56 ? 4 : g.W == 112 ? (dtype == DT_F32 ? 16 : 8) : 1);
     int p = (target + octets - 1) / octets;
     if (p > nf) p = nf;
     if (p < 1) p = 1;
@@ -270,7 +294,7 @@ hipError_t gconv_nchws_mfma_fwd(const GGeom &g, int dtype, const void *in, const
 #define GO3(T, CGG, WW, FL) hipLaunchKernelGGL((k_gconv_nchws_mfma_fwd<T, CGG, WW, WW, FL>), dim3(nblocks), dim3(256), 0, st, g, (const T *)in, \
                                                (const T *)w, (T *)out, bpo, nf, nblocks)
 #define GO2(T, CGG, WW) do { if (flip) GO3(T, CGG, WW, true); else GO3(T, CGG, WW, false); } while (0)
-#define GO1(T, CGG) do { if (g.W == 28) GO2(T, CGG, 28); else GO2(T, CGG, 56); } while (0)
+#define GO1(T, CGG) do { if (g.W == 14) GO2(T, CGG, 14); else if (g.W == 28) GO2(T, CGG, 28); else GO2(T, CGG, 56); } while (0)
     if (g.W == 112) { if (dtype == DT_F32) GO2(float, 2, 112); else GO2(bf16_t, 2, 112); }
     else if (dtype == DT_F32) { if (g.Cg == 8) GO1(float, 8); else GO1(float, 4); }
     else                      { if (g.Cg == 8) GO1(bf16_t, 8); else GO1(bf16_t, 4); }

@@ -280,7 +280,7 @@ def test_group_nchw_matrix_core_filter_gradient_selection_and_workspace():
     for N in (1, 3, 128, 1000):
         for cg, C in ((4, 256), (8, 256), (8, 8), (4, 24), (2, 64), (2, 8)):
             for dt in (dw.F32, dw.BF16):
-                for hw, fills in (((112, (16 if dt == dw.F32 else 8) * N),) if cg == 2 else ((28, N), (56, 4 * N))):
+                for hw, fills in (((112, (16 if dt == dw.F32 else 8) * N),) if cg == 2 else ((14, (N + 3) // 4), (28, N), (56, 4 * N))):
                     if N * C * hw * hw >= 2 ** 31:
                         continue
                     d = dw.group_desc(N, C, hw, hw, 3, 1, 1, groups=C // cg, O=C, layout=dw.NCHW, dtype=dt)
@@ -297,7 +297,7 @@ def test_group_nchw_matrix_core_filter_gradient_selection_and_workspace():
     # other shapes keep the earlier kernels
     assert dw.gconv_variant_name(dw.group_desc(4, 16, 28, 28, 3, 1, 1, groups=8, O=16), 2) != "group_nchw_smallplane_mfma_bwd_filter_k3s1"
     assert dw.gconv_variant_name(dw.group_desc(4, 12, 28, 28, 3, 1, 1, groups=3, O=12), 2) != "group_nchw_smallplane_mfma_bwd_filter_k3s1"
-    assert dw.gconv_variant_name(dw.group_desc(4, 16, 14, 14, 3, 1, 1, groups=4, O=16), 2) != "group_nchw_smallplane_mfma_bwd_filter_k3s1"
+    assert dw.gconv_variant_name(dw.group_desc(4, 16, 14, 28, 3, 1, 1, groups=4, O=16), 2) != "group_nchw_smallplane_mfma_bwd_filter_k3s1"
     assert dw.gconv_variant_name(dw.group_desc(4, 16, 28, 28, 3, 1, 1, groups=4, O=32), 2) != "group_nchw_smallplane_mfma_bwd_filter_k3s1"
 
 

@@ -186,13 +186,15 @@ def test_group_nhwc_bf16_filter_gradient_dot_product_form_forced_tilings():
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
 def test_group_nchw_matrix_core_kernels_forced_tilings(dtype):
-    """NCHW forward, backward-data and filter gradient of 28x28 and 56x56 planes with 4 or 8 channels per group and of
+    """NCHW forward, backward-data and filter gradient of 14x14 (four images per fill, batches that are not multiples of
+    four), 28x28 and 56x56 planes with 4 or 8 channels per group and of
     112x112 planes with 2 (matrix cores, planes or 14-row
     strips staged in LDS): blocks that take one image or strip, several, and a ragged share of them; one channel octet
     and several."""
     cases = [("mf_cg8", 5, 16, 16, 2, 28, 28, 3, 1, 1), ("mf_cg4", 7, 24, 24, 6, 28, 28, 3, 1, 1), ("mf_cg8_n1", 1, 8, 8, 1, 28, 28, 3, 1, 1),
              ("mf56_cg8", 2, 8, 8, 1, 56, 56, 3, 1, 1), ("mf56_cg4", 3, 16, 16, 4, 56, 56, 3, 1, 1),
-             ("mf112_cg2", 2, 16, 16, 8, 112, 112, 3, 1, 1)]
+             ("mf112_cg2", 2, 16, 16, 8, 112, 112, 3, 1, 1),
+             ("mf14_cg8", 6, 16, 16, 2, 14, 14, 3, 1, 1), ("mf14_cg4", 9, 24, 24, 6, 14, 14, 3, 1, 1), ("mf14_n1", 1, 8, 8, 2, 14, 14, 3, 1, 1)]
     knobs = [{}, {"DWCONV_TUNE_GSMBLOCKS": "1", "DWCONV_TUNE_GSMFBLOCKS": "1"}, {"DWCONV_TUNE_GSMBLOCKS": "4", "DWCONV_TUNE_GSMFBLOCKS": "3"},
              {"DWCONV_TUNE_GSMBLOCKS": "9", "DWCONV_TUNE_GSMFBLOCKS": "7"}]
     tol = gu.TOL_F32 if dtype == wl.F32 else gu.TOL_BF16
