@@ -9,15 +9,18 @@
 // fp32: one (input channel, tap) per instruction (4x4x1).  bf16: the inner dimension of 4x4x4 is four input channels,
 // the lane packs its pixel's four values (read one by one from the channel planes) into two registers.
 //
-// The block stages eight consecutive input channels (one group of 8 or two groups of 4) of one image (56x56: of a
-// 14-row strip and the rows above and below it) in LDS exactly as the filter gradient does (gconv_nchw_mfma.hip:
-// flat 16-byte loads two fills ahead in registers, a gap of zeros after each row, zero rows at the plane's edge), and
-// the eight output planes of the fill in a second LDS area, written back as flat 16-byte stores.  A wavefront owns one
-// output quad and half of the fill's rows; its lanes are the pixels of a row and its gap (28-wide: two rows side by
-// side), and it walks the input rows downwards: an input row adds to three output rows (three accumulators that
-// change roles), the pixel to the left and right comes from the neighbour lanes by a lane permute, and an output row
-// leaves for LDS when its last input row is done.  Backward-data is the same walk over dy with the filter
-// transposed within the group and the taps reversed.
+// The block stages eight consecutive input channels (one group of 8, two groups of 4, four groups of 2) of one "fill"
+// in LDS exactly as the filter gradient does (gconv_nchw_mfma.hip: flat 16-byte loads one or two fills ahead in
+// registers, a gap of zeros after each row, zero rows at the plane's edge), and the eight output planes of the fill in
+// a second LDS area, written back as flat 16-byte stores.  A fill is an image (28x28), four images as a 2 x 2 mosaic of
+// that geometry (14x14), or a strip of rows with the rows above and below it (56x56: 14 rows; 112x112: 14 rows in
+// bf16, 7 in fp32).  A wavefront owns one output quad and half of the fill's pixels; its lanes are the pixels of a
+// row and its gap (28-wide: two rows side by side; 112-wide: half a row, the neighbour pixels then come from LDS), and
+// it walks the input rows downwards: an input row adds to three output rows (three accumulators that change roles),
+// the pixel to the left and right comes from the neighbour lanes by a lane permute, and an output row leaves for LDS
+// when its last input row is done.  With two channels per group a quad is two groups and the lane's filter entries
+// for the other group's planes are zero (a block-diagonal 4x4 tile).  Backward-data is the same walk over dy with the
+// filter transposed within the group and the taps reversed.
 #include "gconv_mfma.hpp"
 
 namespace dwc {
